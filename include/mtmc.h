@@ -1,0 +1,137 @@
+/*
+ * mtmc.h -- C boundary of the MI355X policy rollout / scoring library (libmtmc.so).
+ *
+ * The Macro Thinking policy of the paper is a lightweight decoder-only language model that
+ * emits an action as a token sequence a_k = {w_k^1 .. w_k^N} (Method, "Training Methodology").
+ * Two operations on that model are exported:
+ *
+ *   mtmc_score    teacher-forced per-token log-probabilities log P(w^i | s, w^1..w^{i-1}),
+ *                 i.e. the logarithms of the factors of Eq. 2;
+ *   mtmc_rollout  sampling such token sequences autoregressively, several continuations per
+ *                 prompt (Inference Pipeline, "Macro Thinking"), returning the sampled ids and
+ *                 the log-probability each was drawn with.
+ *
+ * Model: pre-norm residual blocks (RMSNorm, rotary embedding with pairs (i, i + head_dim/2),
+ * grouped-query causal attention, SwiGLU feed-forward), final RMSNorm, untied LM head, no
+ * biases.  Matrices are row-major [out, in], y = W x.
+ *
+ * General rules
+ *  - All pointers marked "device" must be device memory of the current HIP device; "host"
+ *    pointers are ordinary host memory.  The library never takes ownership of caller memory.
+ *  - Apart from mtmc_weights_create (which allocates the library-owned, re-tiled copy of the
+ *    weights) no call allocates or frees device memory: scratch comes from the caller's
+ *    `workspace`, sized by the matching *_workspace_bytes query.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  mtmc_rollout and
+ *    mtmc_score only enqueue work on it and return without synchronising; outputs are valid
+ *    once the caller has synchronised the stream.  Calls that share a workspace must be
+ *    ordered on one stream.
+ *  - Every int-returning call gives MTMC_OK (0) or a negative code; mtmc_last_error() then
+ *    holds a message for the calling thread.
+ */
+#ifndef MTMC_H
+#define MTMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MTMC_OK       0
+#define MTMC_EINVAL  (-1)  /* null pointer, bad shape, unsupported configuration        */
+#define MTMC_ENOMEM  (-2)  /* workspace too small, or device allocation failed           */
+#define MTMC_EHIP    (-3)  /* a HIP runtime call failed; message holds hipGetErrorString */
+#define MTMC_EDATA   (-4)  /* a token id outside [0, vocab) was seen on the device       */
+
+#define MTMC_F32  0        /* matrices fp32, all arithmetic fp32                          */
+#define MTMC_BF16 1        /* matrices and KV cache bf16, fp32 accumulation and residual  */
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float   rms_eps;        /* added to the mean square inside the square root              */
+  float   rope_base;      /* theta_i = rope_base^(-2i/head_dim)                           */
+  int32_t dtype;          /* MTMC_F32 or MTMC_BF16                                        */
+  int32_t page_tokens;    /* tokens per KV-cache page; must be 16                         */
+  int32_t max_positions;  /* rows of the rotary table: >= prompt_len + max_new, >= seq_len */
+} mtmc_config;
+
+typedef struct mtmc_weights mtmc_weights; /* opaque, library-owned */
+
+/*
+ * Copies the canonical weight blob into library-owned device memory, re-tiled for the
+ * kernels, and builds the rotary cos/sin table (angles in double, rounded to fp32).
+ *
+ * blob: tensors in this order, each starting at the next multiple of 256 bytes:
+ *   embed[V,d]; per layer: attn_norm[d] Wq[Hq*hd,d] Wk[Hkv*hd,d] Wv[Hkv*hd,d] Wo[d,Hq*hd]
+ *   ffn_norm[d] Wgate[F,d] Wup[F,d] Wdown[d,F]; final_norm[d]; lm_head[V,d].
+ *   Norm gains are fp32; matrices are fp32 (MTMC_F32) or bf16 (MTMC_BF16).
+ * blob_on_device: 0 = host pointer, 1 = device pointer.  The caller keeps and frees blob;
+ * it is no longer referenced when the call returns (the call synchronises `stream`).
+ * Constraints: head_dim 64 or 128 (MTMC_BF16: 128 or 64), n_q_heads % n_kv_heads == 0,
+ * d_model, d_ffn, n_q_heads*head_dim multiples of 16, vocab multiple of 16.
+ */
+int mtmc_weights_create(const mtmc_config* cfg, const void* blob, size_t blob_bytes,
+                        int blob_on_device, void* stream, mtmc_weights** out);
+void mtmc_weights_destroy(mtmc_weights* w);
+
+/* Bytes of the canonical blob for a configuration (0 if cfg is invalid). */
+size_t mtmc_blob_bytes(const mtmc_config* cfg);
+
+/*
+ * mtmc_rollout: for every prompt p < n_prompts and sample s < n_samples, sequence
+ * b = p*n_samples + s continues prompt p by max_new tokens.  At step i, with z the logits at
+ * the last position of (prompt + tokens sampled so far):
+ *     y_v = z_v/T + g_v,  token = argmax_v y_v (lowest index on ties),
+ *     logprob = z_token/T - logsumexp_v(z_v/T),
+ * g_v = -ln(-ln u_v), u_v = ((r_v >> 9) + 0.5) * 2^-23, r_v = word (v % 4) of
+ * Philox4x32-10(counter = (v/4, i, seq_offset + b, 0), key = (seed low, seed high)).
+ * temperature == 0 selects greedy decoding (g = 0, T = 1).  No early stop: every sequence
+ * runs max_new steps.  The returned log-probability is the factor of Eq. 2 under the
+ * sampling distribution (equal to mtmc_score's term when T == 1).
+ *
+ * prompts      device int32 [n_prompts, prompt_len], ids in [0, vocab)
+ * out_ids      device int32 [n_prompts*n_samples, max_new]
+ * out_logprobs device float [n_prompts*n_samples, max_new]
+ * workspace    device, >= mtmc_rollout_workspace_bytes(...) bytes, 256-byte aligned
+ * Out-of-range ids are clamped on the device and reported by the next mtmc_poll_errors.
+ */
+size_t mtmc_rollout_workspace_bytes(const mtmc_weights* w, int32_t n_prompts, int32_t prompt_len,
+                                    int32_t n_samples, int32_t max_new);
+int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompts,
+                 int32_t prompt_len, int32_t n_samples, int32_t max_new, float temperature,
+                 uint64_t seed, uint32_t seq_offset, int32_t* out_ids, float* out_logprobs,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * mtmc_score: teacher-forced pass over seqs [n_seqs, seq_len].  For i in [0, seq_len-1):
+ *     out_logprobs[n, i] = z_i[seqs[n, i+1]] - logsumexp_v z_i[v]     if i + 1 >= prompt_len
+ *                        = 0                                           otherwise
+ * where z_i are the logits at position i: the log of the i-th factor of Eq. 2 for the
+ * action that starts at position prompt_len.  The LM head is not evaluated on unscored
+ * positions.  Optional outputs (may be NULL), same shape, 0 where not scored:
+ *     out_top1[n, i]   = argmax_v z_i[v] (lowest index on ties)
+ *     out_margin[n, i] = largest - second largest logit
+ *
+ * seqs         device int32 [n_seqs, seq_len]; seq_len >= 2; 1 <= prompt_len <= seq_len
+ * out_*        device [n_seqs, seq_len - 1]
+ * workspace    device, >= mtmc_score_workspace_bytes(...) bytes, 256-byte aligned
+ */
+size_t mtmc_score_workspace_bytes(const mtmc_weights* w, int32_t n_seqs, int32_t seq_len);
+int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_seqs, int32_t seq_len,
+               int32_t prompt_len, float* out_logprobs, int32_t* out_top1, float* out_margin,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll saw a token
+ * id outside [0, vocab) (the flag is cleared), MTMC_EHIP on a runtime error, else MTMC_OK.
+ */
+int mtmc_poll_errors(const mtmc_weights* w, void* stream);
+
+/* Message of the last failing call on this thread; valid until the next library call. */
+const char* mtmc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTMC_H */

@@ -1,0 +1,219 @@
+// C boundary, argument checks, weight store, workspace carving and the step schedulers.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "engine.h"
+#include "kernels.h"
+
+namespace mtmc {
+
+static thread_local std::string g_last_error;
+void set_error(const std::string& msg) { g_last_error = msg; }
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int check_config(const mtmc_config* c) {
+  MTMC_REQUIRE(c != nullptr, "cfg is NULL");
+  MTMC_REQUIRE(c->n_layers > 0 && c->d_model > 0 && c->n_q_heads > 0 && c->n_kv_heads > 0 &&
+                   c->head_dim > 0 && c->d_ffn > 0 && c->vocab > 0,
+               "all model dimensions must be positive");
+  MTMC_REQUIRE(c->dtype == MTMC_F32 || c->dtype == MTMC_BF16, "dtype must be MTMC_F32 or MTMC_BF16");
+  MTMC_REQUIRE(c->head_dim == 64 || c->head_dim == 128, "head_dim must be 64 or 128");
+  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->head_dim == 128, "MTMC_BF16 kernels need head_dim 128");
+  MTMC_REQUIRE(c->n_q_heads % c->n_kv_heads == 0, "n_q_heads must be a multiple of n_kv_heads");
+  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->n_q_heads / c->n_kv_heads <= 16,
+               "MTMC_BF16 kernels need at most 16 query heads per kv head");
+  MTMC_REQUIRE(c->d_model % 16 == 0 && c->d_ffn % 16 == 0 && c->vocab % 16 == 0,
+               "d_model, d_ffn and vocab must be multiples of 16");
+  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->d_model % 32 == 0, "MTMC_BF16 kernels need d_model % 32 == 0");
+  MTMC_REQUIRE(c->page_tokens == kPageTokens, "page_tokens must be 16");
+  MTMC_REQUIRE(c->max_positions > 0, "max_positions must be positive");
+  MTMC_REQUIRE(c->rms_eps >= 0.f && c->rope_base > 0.f, "rms_eps >= 0 and rope_base > 0 required");
+  return MTMC_OK;
+}
+
+BlobLayout blob_layout(const mtmc_config& c) {
+  BlobLayout b;
+  const size_t eb = c.dtype == MTMC_BF16 ? 2 : 4;
+  const size_t d = c.d_model, q = (size_t)c.n_q_heads * c.head_dim, kv = (size_t)c.n_kv_heads * c.head_dim;
+  const size_t F = c.d_ffn, V = c.vocab;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    off = align_up(off, 256);
+    const size_t at = off;
+    off += bytes;
+    return at;
+  };
+  b.embed = take(V * d * eb);
+  b.layers.resize(c.n_layers);
+  for (auto& l : b.layers) {
+    l.attn_norm = take(d * 4);
+    l.wq = take(q * d * eb);
+    l.wk = take(kv * d * eb);
+    l.wv = take(kv * d * eb);
+    l.wo = take(d * q * eb);
+    l.ffn_norm = take(d * 4);
+    l.wgate = take(F * d * eb);
+    l.wup = take(F * d * eb);
+    l.wdown = take(d * F * eb);
+  }
+  b.final_norm = take(d * 4);
+  b.lm_head = take(V * d * eb);
+  b.total = off;
+  return b;
+}
+
+}  // namespace mtmc
+
+using namespace mtmc;
+
+extern "C" const char* mtmc_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" size_t mtmc_blob_bytes(const mtmc_config* cfg) {
+  if (check_config(cfg) != MTMC_OK) return 0;
+  return blob_layout(*cfg).total;
+}
+
+extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, size_t blob_bytes,
+                                   int blob_on_device, void* stream, mtmc_weights** out) {
+  if (int rc = check_config(cfg)) return rc;
+  MTMC_REQUIRE(blob != nullptr && out != nullptr, "blob and out must not be NULL");
+  const BlobLayout lay = blob_layout(*cfg);
+  MTMC_REQUIRE(blob_bytes >= lay.total, "blob is smaller than the canonical layout of this configuration");
+  hipStream_t st = (hipStream_t)stream;
+  mtmc_weights* w = new (std::nothrow) mtmc_weights();
+  if (!w) { set_error("out of host memory"); return MTMC_ENOMEM; }
+  w->cfg = *cfg;
+  w->storage = nullptr;
+  w->aux = nullptr;
+  int rc = hipGetDevice(&w->device) == hipSuccess ? MTMC_OK : MTMC_EHIP;
+  if (rc == MTMC_OK) rc = build_aux(w, st);
+  if (rc == MTMC_OK)
+    rc = cfg->dtype == MTMC_F32 ? f32_store_weights(w, lay, blob, blob_on_device != 0, st)
+                                : bf16_store_weights(w, lay, blob, blob_on_device != 0, st);
+  if (rc == MTMC_OK && hipStreamSynchronize(st) != hipSuccess) {
+    set_error("hipStreamSynchronize failed after the weight upload");
+    rc = MTMC_EHIP;
+  }
+  if (rc != MTMC_OK) {
+    mtmc_weights_destroy(w);
+    return rc;
+  }
+  *out = w;
+  return MTMC_OK;
+}
+
+extern "C" void mtmc_weights_destroy(mtmc_weights* w) {
+  if (!w) return;
+  if (w->storage) (void)hipFree(w->storage);
+  if (w->aux) (void)hipFree(w->aux);
+  delete w;
+}
+
+extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
+  MTMC_REQUIRE(w != nullptr, "weights is NULL");
+  MTMC_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+  int flag = 0;
+  MTMC_HIP_CHECK(hipMemcpy(&flag, w->err_flag, sizeof(int), hipMemcpyDeviceToHost));
+  if (flag) {
+    MTMC_HIP_CHECK(hipMemset(w->err_flag, 0, sizeof(int)));
+    set_error("a token id outside [0, vocab) was seen (and clamped) on the device");
+    return MTMC_EDATA;
+  }
+  return MTMC_OK;
+}
+
+// --------------------------------------------------------------------------------------
+// rollout
+// --------------------------------------------------------------------------------------
+static int check_rollout_shape(const mtmc_weights* w, int32_t n_prompts, int32_t prompt_len,
+                               int32_t n_samples, int32_t max_new) {
+  MTMC_REQUIRE(w != nullptr, "weights is NULL");
+  MTMC_REQUIRE(n_prompts > 0 && prompt_len > 0 && n_samples > 0 && max_new > 0,
+               "n_prompts, prompt_len, n_samples and max_new must be positive");
+  MTMC_REQUIRE((int64_t)prompt_len + max_new <= w->cfg.max_positions,
+               "prompt_len + max_new exceeds max_positions");
+  MTMC_REQUIRE((int64_t)n_prompts * n_samples <= (1 << 20), "too many sequences");
+  return MTMC_OK;
+}
+
+extern "C" size_t mtmc_rollout_workspace_bytes(const mtmc_weights* w, int32_t n_prompts,
+                                               int32_t prompt_len, int32_t n_samples,
+                                               int32_t max_new) {
+  if (check_rollout_shape(w, n_prompts, prompt_len, n_samples, max_new) != MTMC_OK) return 0;
+  RolloutPlan p = plan_rollout(w, n_prompts, prompt_len, n_samples, max_new, nullptr);
+  return p.total_bytes;
+}
+
+extern "C" int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompts,
+                            int32_t prompt_len, int32_t n_samples, int32_t max_new,
+                            float temperature, uint64_t seed, uint32_t seq_offset, int32_t* out_ids,
+                            float* out_logprobs, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (int rc = check_rollout_shape(w, n_prompts, prompt_len, n_samples, max_new)) return rc;
+  MTMC_REQUIRE(prompts && out_ids && out_logprobs && workspace, "NULL pointer argument");
+  MTMC_REQUIRE(temperature >= 0.f && std::isfinite(temperature), "temperature must be finite and >= 0");
+  MTMC_REQUIRE(((uintptr_t)workspace & 255) == 0, "workspace must be 256-byte aligned");
+  RolloutPlan p = plan_rollout(w, n_prompts, prompt_len, n_samples, max_new, (char*)workspace);
+  if (workspace_bytes < p.total_bytes) {
+    set_error("workspace too small for mtmc_rollout: need " + std::to_string(p.total_bytes) + " bytes");
+    return MTMC_ENOMEM;
+  }
+  SampleArgs sa;
+  sa.greedy = temperature == 0.f ? 1 : 0;
+  sa.inv_temp = sa.greedy ? 1.0f : (float)(1.0 / (double)temperature);
+  sa.seed = seed;
+  sa.seq_offset = seq_offset;
+  sa.max_new = max_new;
+  sa.out_ids = out_ids;
+  sa.out_logprobs = out_logprobs;
+  hipStream_t st = (hipStream_t)stream;
+  int rc = w->cfg.dtype == MTMC_F32 ? f32_rollout(w, p, prompts, sa, st)
+                                    : bf16_rollout(w, p, prompts, sa, st);
+  if (rc != MTMC_OK) return rc;
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}
+
+// --------------------------------------------------------------------------------------
+// scoring
+// --------------------------------------------------------------------------------------
+static int check_score_shape(const mtmc_weights* w, int32_t n_seqs, int32_t seq_len) {
+  MTMC_REQUIRE(w != nullptr, "weights is NULL");
+  MTMC_REQUIRE(n_seqs > 0 && seq_len >= 2, "n_seqs must be positive and seq_len >= 2");
+  MTMC_REQUIRE(seq_len <= w->cfg.max_positions, "seq_len exceeds max_positions");
+  return MTMC_OK;
+}
+
+extern "C" size_t mtmc_score_workspace_bytes(const mtmc_weights* w, int32_t n_seqs, int32_t seq_len) {
+  if (check_score_shape(w, n_seqs, seq_len) != MTMC_OK) return 0;
+  return plan_score(w, n_seqs, seq_len, nullptr).total_bytes;
+}
+
+extern "C" int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_seqs, int32_t seq_len,
+                          int32_t prompt_len, float* out_logprobs, int32_t* out_top1,
+                          float* out_margin, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_score_shape(w, n_seqs, seq_len)) return rc;
+  MTMC_REQUIRE(seqs && out_logprobs && workspace, "NULL pointer argument");
+  MTMC_REQUIRE(prompt_len >= 1 && prompt_len <= seq_len, "prompt_len must lie in [1, seq_len]");
+  MTMC_REQUIRE(((uintptr_t)workspace & 255) == 0, "workspace must be 256-byte aligned");
+  ScorePlan p = plan_score(w, n_seqs, seq_len, (char*)workspace);
+  if (workspace_bytes < p.total_bytes) {
+    set_error("workspace too small for mtmc_score: need " + std::to_string(p.total_bytes) + " bytes");
+    return MTMC_ENOMEM;
+  }
+  ScoreArgs a;
+  a.seqs = seqs;
+  a.n_seqs = n_seqs;
+  a.S = seq_len;
+  a.first = prompt_len - 1;
+  a.out_logprobs = out_logprobs;
+  a.out_top1 = out_top1;
+  a.out_margin = out_margin;
+  hipStream_t st = (hipStream_t)stream;
+  int rc = w->cfg.dtype == MTMC_F32 ? f32_score(w, p, a, st) : bf16_score(w, p, a, st);
+  if (rc != MTMC_OK) return rc;
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}

@@ -1,0 +1,82 @@
+// Internal declarations shared by the library's translation units (not part of the C boundary).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "mtmc.h"
+
+namespace mtmc {
+
+constexpr int kPageTokens = 16;
+
+void set_error(const std::string& msg);
+
+#define MTMC_HIP_CHECK(expr)                                                              \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) {                                                               \
+      ::mtmc::set_error(std::string(#expr) + ": " + hipGetErrorString(e_));              \
+      return MTMC_EHIP;                                                                   \
+    }                                                                                     \
+  } while (0)
+
+#define MTMC_REQUIRE(cond, msg)                                                           \
+  do {                                                                                    \
+    if (!(cond)) {                                                                        \
+      ::mtmc::set_error(std::string("invalid argument: ") + (msg));                       \
+      return MTMC_EINVAL;                                                                 \
+    }                                                                                     \
+  } while (0)
+
+// How the tokens of a launch map to sequences and positions.  Token t belongs to sequence
+// t / S, sits at position pos_base + (*d_step if d_step) + t % S, and uses row
+// (t / S) * row_stride of the page table.
+struct TokMap {
+  int S;
+  int row_stride;
+  int pos_base;
+  const int* d_step;
+};
+
+// Where the KV pages live.  Page `pg` of (layer l, which in {0 = K, 1 = V}, kv head g) starts at
+// element (((l * 2 + which) * n_pages + pg) * n_kv_heads + g) * 16 * head_dim.
+struct KvPool {
+  void* base;
+  int n_pages;
+  int n_kv_heads;
+  int head_dim;
+  const int* page_table;  // [rows, max_pages]
+  int max_pages;
+};
+
+struct LayerWeights {
+  const float* attn_norm;
+  const float* ffn_norm;
+  const void* wqkv;    // [(Hq + 2 Hkv) hd, d]
+  const void* wo;      // [d, Hq hd]
+  const void* wgu;     // fp32: [2F, d] (gate rows, then up rows); bf16: 16-row blocks gate/up interleaved
+  const void* wdown;   // [d, F]
+};
+
+}  // namespace mtmc
+
+struct mtmc_weights {
+  mtmc_config cfg;
+  int device;
+  void* storage;        // single device allocation behind every weight pointer below
+  void* aux;            // device allocation holding the rotary tables and the error flag
+  size_t storage_bytes;
+  const void* embed;    // [V, d] row-major in the storage type
+  const float* final_norm;
+  const void* lm_head;  // [V, d]
+  std::vector<mtmc::LayerWeights> layers;
+  const float* rope_cos;  // [max_positions, hd/2]
+  const float* rope_sin;
+  int* err_flag;        // device int, non-zero once a bad token id was seen
+  int d_ffn_pad;        // F rounded up to the K-tile of the bf16 kernels (== F for fp32)
+};

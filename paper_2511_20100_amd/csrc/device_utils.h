@@ -1,0 +1,128 @@
+// Device-side helpers: wavefront/block reductions, the counter-based generator, Gumbel noise.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.h"
+
+namespace mtmc {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Sum over a block of up to 1024 threads; every thread gets the result.  `red` holds >= 16 floats.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if (lane == 0) red[wid] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if (lane == 0) red[wid] = v;
+  __syncthreads();
+  float t = red[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, red[i]);
+  return t;
+}
+
+// ---- Philox4x32-10 (Salmon et al., SC'11): ten rounds, key bumped by the Weyl constants ----
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c.x), lo0 = M0 * c.x;
+    const uint32_t hi1 = __umulhi(M1, c.z), lo1 = M1 * c.z;
+    c = make_uint4(hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0);
+    k0 += W0;
+    k1 += W1;
+  }
+  return c;
+}
+
+// u = ((r >> 9) + 1/2) 2^-23 lies strictly inside (0, 1) and is exact in fp32; g = -ln(-ln u).
+__device__ __forceinline__ float gumbel_from_bits(uint32_t r) {
+  const float u = ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f;
+  return -logf(-logf(u));
+}
+
+// Online log-sum-exp state (m = running max, s = sum of exp(x - m)).
+struct Lse {
+  float m, s;
+};
+__device__ __forceinline__ Lse lse_empty() { return {-INFINITY, 0.f}; }
+__device__ __forceinline__ void lse_push(Lse& a, float x) {
+  if (x > a.m) {
+    a.s = a.s * expf(a.m - x) + 1.f;
+    a.m = x;
+  } else {
+    a.s += expf(x - a.m);
+  }
+}
+__device__ __forceinline__ Lse lse_merge(Lse a, Lse b) {
+  if (b.s == 0.f) return a;
+  if (a.s == 0.f) return b;
+  const float m = fmaxf(a.m, b.m);
+  return {m, a.s * expf(a.m - m) + b.s * expf(b.m - m)};
+}
+
+// Arg-max with "lowest index wins ties".
+struct Best {
+  float y;
+  int idx;
+};
+__device__ __forceinline__ Best best_empty() { return {-INFINITY, 0x7fffffff}; }
+__device__ __forceinline__ Best best_merge(Best a, Best b) {
+  return (b.y > a.y || (b.y == a.y && b.idx < a.idx)) ? b : a;
+}
+
+// Largest and second largest value (with the index of the largest; lowest index on ties).
+struct Top2 {
+  float v1;
+  int i1;
+  float v2;
+};
+__device__ __forceinline__ Top2 top2_empty() { return {-INFINITY, 0x7fffffff, -INFINITY}; }
+__device__ __forceinline__ void top2_push(Top2& t, float v, int i) {
+  if (v > t.v1 || (v == t.v1 && i < t.i1)) {
+    t.v2 = t.v1;
+    t.v1 = v;
+    t.i1 = i;
+  } else if (v > t.v2) {
+    t.v2 = v;
+  }
+}
+__device__ __forceinline__ Top2 top2_merge(Top2 a, Top2 b) {
+  const bool b_wins = (b.v1 > a.v1 || (b.v1 == a.v1 && b.i1 < a.i1));
+  Top2 r;
+  if (b_wins) {
+    r.v1 = b.v1; r.i1 = b.i1; r.v2 = fmaxf(a.v1, fmaxf(a.v2, b.v2));
+  } else {
+    r.v1 = a.v1; r.i1 = a.i1; r.v2 = fmaxf(b.v1, fmaxf(a.v2, b.v2));
+  }
+  return r;
+}
+
+__device__ __forceinline__ int tok_seq(const TokMap& m, int t) { return t / m.S; }
+__device__ __forceinline__ int tok_pos(const TokMap& m, int t) {
+  return m.pos_base + (m.d_step ? *m.d_step : 0) + t % m.S;
+}
+
+}  // namespace mtmc

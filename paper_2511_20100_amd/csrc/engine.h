@@ -1,0 +1,119 @@
+// Host-side engine: blob layout, workspace plans and the per-dtype schedulers.
+#pragma once
+
+#include "common.h"
+
+namespace mtmc {
+
+struct BlobLayerOffsets {
+  size_t attn_norm, wq, wk, wv, wo, ffn_norm, wgate, wup, wdown;
+};
+struct BlobLayout {
+  size_t embed, final_norm, lm_head, total;
+  std::vector<BlobLayerOffsets> layers;
+};
+BlobLayout blob_layout(const mtmc_config& c);
+
+// Bump allocator over the caller's workspace (base may be NULL to only measure).
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(char* b) : base(b) {}
+  template <class T>
+  T* take(size_t n) {
+    off = (off + 255) / 256 * 256;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+struct RolloutPlan {
+  int n_prompts, prompt_len, n_samples, max_new, B;
+  int n_full;        // pages per prompt that are completely filled by the prompt (shared)
+  int max_pages;     // page-table row length
+  int shared_total;  // n_prompts * n_full
+  int n_pages;       // pages in the pool
+  int chunk_prompts, Tmax;
+  // control
+  int* page_table;
+  int* d_step;
+  int* cur_ids;
+  void* kv;
+  // activations (Tmax rows unless noted)
+  float* h;
+  void* x;
+  float* qkv;
+  void* o;
+  float* gu;
+  void* a;
+  float* hB;      // [B, d]
+  void* xB;       // [B, d]
+  float* logits;  // fp32 path: [B, V]
+  // bf16 path scratch
+  float* part;        // split-K partial sums
+  float* attn_part;   // decode-attention partial (m, l, o) per context split
+  float* lm_part;     // LM-head per-tile partial reductions
+  size_t total_bytes;
+};
+
+struct ScorePlan {
+  int n_seqs, S, chunk_seqs, pages_per_seq, n_pages, T;
+  int rows_max;      // scored rows per chunk at most (chunk_seqs * (S - 1))
+  int logit_rows;    // rows of the logits buffer (fp32 path)
+  int* page_table;
+  void* kv;
+  float* h;
+  void* x;
+  float* qkv;
+  void* o;
+  float* gu;
+  void* a;
+  float* hs;   // [rows_max, d] gathered scored rows
+  void* xs;    // [rows_max, d]
+  float* logits;
+  float* part;
+  float* lm_part;
+  size_t total_bytes;
+};
+
+struct SampleArgs {
+  int greedy;
+  float inv_temp;
+  uint64_t seed;
+  uint32_t seq_offset;
+  int max_new;
+  int* out_ids;
+  float* out_logprobs;
+};
+
+struct ScoreArgs {
+  const int* seqs;
+  int n_seqs, S, first;
+  float* out_logprobs;
+  int* out_top1;
+  float* out_margin;
+};
+
+RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, int n_samples,
+                         int max_new, char* base);
+ScorePlan plan_score(const mtmc_weights* w, int n_seqs, int S, char* base);
+
+// Rotary table (angles in double) and the device error flag.
+int build_aux(mtmc_weights* w, hipStream_t st);
+
+int f32_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob, bool on_device,
+                      hipStream_t st);
+int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts, const SampleArgs& sa,
+                hipStream_t st);
+int f32_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hipStream_t st);
+
+int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob, bool on_device,
+                       hipStream_t st);
+int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
+                 const SampleArgs& sa, hipStream_t st);
+int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hipStream_t st);
+void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& c);
+void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& c);
+
+}  // namespace mtmc

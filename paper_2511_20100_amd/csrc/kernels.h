@@ -1,0 +1,52 @@
+// Host-side launchers of the HIP kernels.  Every launcher only enqueues on `st`.
+#pragma once
+
+#include "common.h"
+
+namespace mtmc {
+
+// ---------------------------------------------------------------- shared (layout / control)
+// Page table of a rollout: row b, entry j -> shared page (b / n_samples) * n_full + j for
+// j < n_full, else private page shared_total + b * (max_pages - n_full) + (j - n_full).
+void launch_build_page_table(int* table, int rows, int max_pages, int n_samples, int n_full,
+                             int shared_total, hipStream_t st);
+void launch_set_int(int* p, int v, hipStream_t st);
+void launch_add_int(int* p, int v, hipStream_t st);
+void launch_fill_u32(uint32_t* p, uint32_t v, size_t n, hipStream_t st);
+// dst[r, :] = src[(r / n_rep) * src_stride + src_offset + (r % n_rep) * rep_stride, :]
+void launch_gather_rows(float* dst, const float* src, int rows, int d, int n_rep, int src_stride,
+                        int src_offset, int rep_stride, hipStream_t st);
+// For every row b with b % n_samples != 0: page table[b][page_idx] := copy of page
+// table[b - b % n_samples][page_idx], in every (layer, K/V).  elem_bytes is the KV element size.
+void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, int page_idx,
+                            int elem_bytes, hipStream_t st);
+
+// ---------------------------------------------------------------- fp32 path
+namespace f32 {
+void embed(float* h, const int* ids, int T, const float* E, int d, int vocab, int* err_flag,
+           hipStream_t st);
+void rmsnorm(float* x, const float* h, const float* gain, float eps, int T, int d, hipStream_t st);
+// C[M, N] (ldc) = or += A[M, K] (lda) * W[N, K]^T      (K % 16 == 0)
+void gemm(float* C, int ldc, const float* A, int lda, const float* W, int M, int N, int K,
+          bool accumulate, hipStream_t st);
+// qkv [T, (Hq + 2 Hkv) hd]: rotates q in place, writes rotated k and v into the pages.
+void rope_kv_write(float* qkv, int T, int Hq, int Hkv, int hd, const float* cos, const float* sin,
+                   TokMap map, KvPool pool, int layer, hipStream_t st);
+// o [T, Hq hd] = causal grouped-query attention of the (rotated) q in qkv over the pages.
+void attention(float* o, const float* qkv, int T, int Hq, int Hkv, int hd, TokMap map, KvPool pool,
+               int layer, hipStream_t st);
+void swiglu(float* a, const float* gu, int T, int F, hipStream_t st);  // gu [T, 2F] -> a [T, F]
+// Gumbel-max sampling from materialised logits [B, V] at step *d_step; writes out_ids[b, step],
+// out_logprobs[b, step] and cur_ids[b].
+void sample(const float* logits, int B, int V, float inv_temp, int greedy, uint64_t seed,
+            uint32_t seq_offset, const int* d_step, int max_new, int* cur_ids, int* out_ids,
+            float* out_logprobs, hipStream_t st);
+// Teacher-forced scoring from materialised logits [R, V].  Row r is position
+// i = first + (row0 + r) % n_scored of sequence n = seq0 + (row0 + r) / n_scored; its target is
+// seqs[n, i + 1] and its output slot [n, i] of the [*, S - 1] outputs.
+void score_rows(const float* logits, int R, int V, const int* seqs, int S, int first, int n_scored,
+                int seq0, int row0, float* out_logprobs, int* out_top1, float* out_margin,
+                int* err_flag, hipStream_t st);
+}  // namespace f32
+
+}  // namespace mtmc

@@ -1,0 +1,166 @@
+"""ctypes binding of libmtmc.so: argument marshalling only.
+
+Every function has the name and the meaning of the C entry point it wraps (include/mtmc.h).
+PyTorch is used for device memory (tensors own the buffers that are passed as raw pointers)
+and for the current HIP stream; no step of the computation runs in Python or in PyTorch.
+There is no fallback: if the library is missing or fails to load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from .inputs import ModelConfig
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtmc.so")
+
+MTMC_OK, MTMC_EINVAL, MTMC_ENOMEM, MTMC_EHIP, MTMC_EDATA = 0, -1, -2, -3, -4
+MTMC_F32, MTMC_BF16 = 0, 1
+
+
+class MtmcError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libmtmc error {code}: {msg}")
+        self.code = code
+
+
+class mtmc_config(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32),
+                ("vocab", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("rope_base", ctypes.c_float),
+                ("dtype", ctypes.c_int32), ("page_tokens", ctypes.c_int32), ("max_positions", ctypes.c_int32)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2511_20100_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, u32, u64, f32, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint64,
+                                  ctypes.c_float, ctypes.c_size_t)
+    cfgp = ctypes.POINTER(mtmc_config)
+    lib.mtmc_weights_create.argtypes = [cfgp, vp, sz, ctypes.c_int, vp, ctypes.POINTER(vp)]
+    lib.mtmc_weights_create.restype = ctypes.c_int
+    lib.mtmc_weights_destroy.argtypes = [vp]
+    lib.mtmc_weights_destroy.restype = None
+    lib.mtmc_blob_bytes.argtypes = [cfgp]
+    lib.mtmc_blob_bytes.restype = sz
+    lib.mtmc_rollout_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.mtmc_rollout_workspace_bytes.restype = sz
+    lib.mtmc_rollout.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, u32, vp, vp, vp, sz, vp]
+    lib.mtmc_rollout.restype = ctypes.c_int
+    lib.mtmc_score_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.mtmc_score_workspace_bytes.restype = sz
+    lib.mtmc_score.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.mtmc_score.restype = ctypes.c_int
+    lib.mtmc_poll_errors.argtypes = [vp, vp]
+    lib.mtmc_poll_errors.restype = ctypes.c_int
+    lib.mtmc_last_error.argtypes = []
+    lib.mtmc_last_error.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mtmc_rollout_workspace_bytes",
+           "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error")
+
+
+def mtmc_last_error() -> str:
+    return (_lib.mtmc_last_error() or b"").decode()
+
+
+def _check(rc: int) -> None:
+    if rc != MTMC_OK:
+        raise MtmcError(rc, mtmc_last_error())
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def make_config(cfg: ModelConfig, max_positions: int) -> mtmc_config:
+    return mtmc_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
+                       cfg.vocab, cfg.rms_eps, cfg.rope_base, MTMC_BF16 if cfg.dtype == "bf16" else MTMC_F32,
+                       16, max_positions)
+
+
+def mtmc_blob_bytes(cfg: mtmc_config) -> int:
+    return int(_lib.mtmc_blob_bytes(ctypes.byref(cfg)))
+
+
+def mtmc_weights_create(cfg: mtmc_config, blob, stream: Optional[torch.cuda.Stream] = None) -> int:
+    """blob: a uint8 torch tensor (CPU or CUDA) or a numpy uint8 array holding the canonical blob.
+    Returns the opaque handle (an integer address)."""
+    if not isinstance(blob, torch.Tensor):
+        blob = torch.from_numpy(blob)
+    assert blob.dtype == torch.uint8 and blob.is_contiguous()
+    handle = ctypes.c_void_p()
+    _check(_lib.mtmc_weights_create(ctypes.byref(cfg), blob.data_ptr(), blob.numel(),
+                                    1 if blob.is_cuda else 0, _stream_ptr(stream), ctypes.byref(handle)))
+    return handle.value
+
+
+def mtmc_weights_destroy(handle: int) -> None:
+    _lib.mtmc_weights_destroy(handle)
+
+
+def mtmc_rollout_workspace_bytes(handle: int, n_prompts: int, prompt_len: int, n_samples: int, max_new: int) -> int:
+    n = int(_lib.mtmc_rollout_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new))
+    if n == 0:
+        raise MtmcError(MTMC_EINVAL, mtmc_last_error())
+    return n
+
+
+def mtmc_rollout(handle: int, prompts: torch.Tensor, n_samples: int, max_new: int, temperature: float, seed: int,
+                 *, seq_offset: int = 0, workspace: Optional[torch.Tensor] = None,
+                 out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                 stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """prompts: int32 CUDA tensor [n_prompts, prompt_len].  Returns (ids, logprobs), both
+    [n_prompts*n_samples, max_new] CUDA tensors, valid after the stream is synchronised."""
+    assert prompts.is_cuda and prompts.dtype == torch.int32 and prompts.is_contiguous() and prompts.dim() == 2
+    n_prompts, prompt_len = prompts.shape
+    if workspace is None:
+        workspace = torch.empty(mtmc_rollout_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new),
+                                dtype=torch.uint8, device=prompts.device)
+    B = n_prompts * n_samples
+    if out_ids is None:
+        out_ids = torch.empty((B, max_new), dtype=torch.int32, device=prompts.device)
+    if out_logprobs is None:
+        out_logprobs = torch.empty((B, max_new), dtype=torch.float32, device=prompts.device)
+    _check(_lib.mtmc_rollout(handle, prompts.data_ptr(), n_prompts, prompt_len, n_samples, max_new,
+                             float(temperature), int(seed), int(seq_offset), out_ids.data_ptr(),
+                             out_logprobs.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out_ids, out_logprobs
+
+
+def mtmc_score_workspace_bytes(handle: int, n_seqs: int, seq_len: int) -> int:
+    n = int(_lib.mtmc_score_workspace_bytes(handle, n_seqs, seq_len))
+    if n == 0:
+        raise MtmcError(MTMC_EINVAL, mtmc_last_error())
+    return n
+
+
+def mtmc_score(handle: int, seqs: torch.Tensor, prompt_len: int = 1, *, want_top1: bool = False,
+               workspace: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+               stream: Optional[torch.cuda.Stream] = None):
+    """seqs: int32 CUDA tensor [n_seqs, seq_len].  Returns logprobs [n_seqs, seq_len-1], or
+    (logprobs, top1, margin) when want_top1."""
+    assert seqs.is_cuda and seqs.dtype == torch.int32 and seqs.is_contiguous() and seqs.dim() == 2
+    n_seqs, S = seqs.shape
+    if workspace is None:
+        workspace = torch.empty(mtmc_score_workspace_bytes(handle, n_seqs, S), dtype=torch.uint8, device=seqs.device)
+    if out_logprobs is None:
+        out_logprobs = torch.empty((n_seqs, S - 1), dtype=torch.float32, device=seqs.device)
+    top1 = torch.empty((n_seqs, S - 1), dtype=torch.int32, device=seqs.device) if want_top1 else None
+    margin = torch.empty((n_seqs, S - 1), dtype=torch.float32, device=seqs.device) if want_top1 else None
+    _check(_lib.mtmc_score(handle, seqs.data_ptr(), n_seqs, S, prompt_len, out_logprobs.data_ptr(),
+                           top1.data_ptr() if want_top1 else None, margin.data_ptr() if want_top1 else None,
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return (out_logprobs, top1, margin) if want_top1 else out_logprobs
+
+
+def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+    _check(_lib.mtmc_poll_errors(handle, _stream_ptr(stream)))

@@ -1,0 +1,112 @@
+"""GPU parity, small all-fp32 workload: 4 prompts x 2 samples, 32-token prompts, 32 new tokens at
+T = 1 (seed 1), then scoring of all 64-token sequences.  Every sampled id must equal the
+oracle's free-running rollout; log-probs within 1e-4."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import mtmc_oracle as oracle
+from helpers import oracle_model
+from paper_2511_20100_amd import inputs
+
+LOGP_TOL_F32 = 1e-4  # fp32 on both sides; only the summation order differs
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w = inputs.make_weights(inputs.TINY, seed=0)
+    handle = mtmc.mtmc_weights_create(mtmc.make_config(inputs.TINY, 128), w.blob())
+    yield w, handle
+    mtmc.mtmc_weights_destroy(handle)
+
+
+def test_rollout_ids_exact_and_logprobs(tiny):
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w, handle = tiny
+    prompts = inputs.make_prompts(4, 32, inputs.TINY.vocab, seed=2)
+    ids, lp = mtmc.mtmc_rollout(handle, torch.from_numpy(prompts).cuda(), 2, 32, 1.0, 1)
+    mtmc.mtmc_poll_errors(handle)
+    ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
+    ref_ids, ref_lp, margins = oracle.rollout(oracle_model(w, 128), prompts, 2, 32, 1.0, seed=1)
+    print("min sampling margin of the oracle:", margins.min())
+    assert np.array_equal(ids, ref_ids)
+    assert np.abs(lp - ref_lp).max() <= LOGP_TOL_F32
+
+
+def test_score_matches_oracle_and_rollout(tiny):
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w, handle = tiny
+    prompts = inputs.make_prompts(4, 32, inputs.TINY.vocab, seed=2)
+    ids, lp = mtmc.mtmc_rollout(handle, torch.from_numpy(prompts).cuda(), 2, 32, 1.0, 1)
+    seqs = torch.cat([torch.from_numpy(prompts).cuda().repeat_interleave(2, dim=0), ids], dim=1).contiguous()
+    s, top1, margin = mtmc.mtmc_score(handle, seqs, 32, want_top1=True)
+    mtmc.mtmc_poll_errors(handle)
+    s, top1, margin = s.cpu().numpy(), top1.cpu().numpy(), margin.cpu().numpy()
+    ref_s, ref_top1, ref_margin = oracle.score(oracle_model(w, 128), seqs.cpu().numpy(), prompt_len=32)
+    assert np.abs(s - ref_s).max() <= LOGP_TOL_F32
+    assert np.all(s[:, :31] == 0.0)
+    gate = ref_margin > 1e-4
+    assert np.array_equal(top1[gate], ref_top1[gate])
+    assert np.abs(margin - ref_margin).max() <= 1e-4
+    # decode and scoring agree: the sampled token's log-prob at T = 1 is its Eq. 2 factor
+    assert np.abs(s[:, 31:] - lp.cpu().numpy()).max() <= LOGP_TOL_F32
+
+
+def test_determinism_and_seed(tiny):
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w, handle = tiny
+    prompts = torch.from_numpy(inputs.make_prompts(3, 20, inputs.TINY.vocab, seed=5)).cuda()
+    a = mtmc.mtmc_rollout(handle, prompts, 3, 12, 1.0, 7)
+    b = mtmc.mtmc_rollout(handle, prompts, 3, 12, 1.0, 7)
+    c = mtmc.mtmc_rollout(handle, prompts, 3, 12, 1.0, 8)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert not torch.equal(a[0], c[0])
+    # one prompt on its own, with its global sequence offset, reproduces its rows of the batch
+    solo = mtmc.mtmc_rollout(handle, prompts[1:2].contiguous(), 3, 12, 1.0, 7, seq_offset=3)
+    torch.cuda.synchronize()
+    assert torch.equal(solo[0], a[0][3:6])
+    assert (solo[1] - a[1][3:6]).abs().max().item() <= 1e-5
+
+
+def test_ragged_shapes_and_greedy(tiny):
+    """Prompt lengths that do not fill a page, more than one prefill chunk, greedy decoding."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w, handle = tiny
+    model = oracle_model(w, 128)
+    for (n_prompts, plen, n_samples, max_new, temp) in [(1, 1, 1, 3, 1.0), (2, 17, 3, 20, 0.7), (3, 16, 2, 5, 0.0)]:
+        prompts = inputs.make_prompts(n_prompts, plen, inputs.TINY.vocab, seed=plen)
+        ids, lp = mtmc.mtmc_rollout(handle, torch.from_numpy(prompts).cuda(), n_samples, max_new, temp, 3)
+        mtmc.mtmc_poll_errors(handle)
+        ref_ids, ref_lp, margins = oracle.rollout(model, prompts, n_samples, max_new, temp, seed=3)
+        ok = np.cumprod(margins > 1e-4, axis=1).astype(bool)  # compare up to the first near-tie
+        assert np.array_equal(ids.cpu().numpy()[ok], ref_ids[ok])
+        assert np.abs(lp.cpu().numpy() - ref_lp)[ok].max() <= LOGP_TOL_F32
+
+
+def test_bad_arguments(tiny):
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w, handle = tiny
+    prompts = torch.from_numpy(inputs.make_prompts(2, 8, inputs.TINY.vocab, seed=5)).cuda()
+    with pytest.raises(mtmc.MtmcError) as e:
+        mtmc.mtmc_rollout(handle, prompts, 2, 500, 1.0, 1)       # exceeds max_positions
+    assert e.value.code == mtmc.MTMC_EINVAL
+    with pytest.raises(mtmc.MtmcError) as e:
+        mtmc.mtmc_rollout(handle, prompts, 2, 4, 1.0, 1, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == mtmc.MTMC_ENOMEM
+    with pytest.raises(mtmc.MtmcError):
+        mtmc.mtmc_rollout(handle, prompts, 2, 4, -1.0, 1)
+    bad = prompts.clone(); bad[0, 0] = inputs.TINY.vocab + 5
+    mtmc.mtmc_rollout(handle, bad, 1, 2, 1.0, 1)
+    with pytest.raises(mtmc.MtmcError) as e:
+        mtmc.mtmc_poll_errors(handle)
+    assert e.value.code == mtmc.MTMC_EDATA
+    mtmc.mtmc_poll_errors(handle)  # flag was cleared
