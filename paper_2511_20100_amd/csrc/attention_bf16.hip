@@ -1,0 +1,303 @@
+// Grouped-query attention over the paged bf16 KV cache (head_dim 128), on MFMA.
+//
+// Page layouts (16 tokens x 128 dims = 4 KiB per (layer, K or V, kv head, page)):
+//   K page: [dim / 8][token][dim % 8]   -> the four 16x32 "A" operands of S^T = K Q^T are the
+//                                          four consecutive 1 KiB quarters of the page;
+//   V page: [dim][token]                -> a lane's "A" operand of O^T = V^T P^T is 4 consecutive
+//                                          tokens of one dim from each of two pages (2 x 8 bytes).
+// Scores are produced transposed (S^T[token][query]), so a lane owns one query column: the
+// softmax reductions run over its 8 registers plus two cross-lane steps, and exp(S^T) is
+// already in the "B" operand layout of the second product -- no transpose through LDS.
+// The k index of that product maps (lane / 16, e) to token 4 (lane / 16) + e % 4 of page e / 4,
+// the same permutation on both operands.
+#include "bf16_kernels.h"
+#include "device_utils.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+constexpr int HD = 128;
+constexpr int PAGE_ELEMS = kPageTokens * HD;
+
+__device__ __forceinline__ const h16_t* kv_page(const KvPool& pool, int layer, int which, int page, int g) {
+  return (const h16_t*)pool.base +
+         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)PAGE_ELEMS;
+}
+
+template <int NQB>
+struct AttnState {
+  float m[NQB];      // running maximum of the column (same in the 4 lanes that share a column)
+  float l[NQB];      // this lane's share of the running sum
+  v4f o[NQB][8];     // O^T[dim = 16 cb + 4 (lane / 16) + r][column]
+};
+
+template <int NQB>
+__device__ __forceinline__ void attn_init(AttnState<NQB>& st) {
+#pragma unroll
+  for (int i = 0; i < NQB; ++i) {
+    st.m[i] = -INFINITY;
+    st.l[i] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) st.o[i][cb] = v4f{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
+// One step over two pages (32 tokens starting at tok0) for up to NQB blocks of 16 query columns.
+// qpos[i] is the position of this lane's column in block i (-1: padding column, fully masked).
+template <int NQB>
+__device__ __forceinline__ void attn_pair(const h16_t* __restrict__ K0, const h16_t* __restrict__ K1,
+                                          const h16_t* __restrict__ V0, const h16_t* __restrict__ V1,
+                                          int tok0, const v8bf (&qf)[NQB][4], const int (&qpos)[NQB],
+                                          int nqb, float scale, AttnState<NQB>& st, int lane) {
+  const int lg = lane >> 4;
+  v8bf kf[2][4];
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    kf[0][kb] = load_frag(K0 + kb * 512, lane);
+    kf[1][kb] = load_frag(K1 + kb * 512, lane);
+  }
+  v8bf pf[NQB];
+#pragma unroll
+  for (int i = 0; i < NQB; ++i) {
+    if (i >= nqb) continue;
+    v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      s0 = mfma16(kf[0][kb], qf[i][kb], s0);
+      s1 = mfma16(kf[1][kb], qf[i][kb], s1);
+    }
+    float sv[8];
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int t0 = tok0 + 4 * lg + r, t1 = t0 + 16;
+      sv[r] = (t0 <= qpos[i]) ? s0[r] * scale : -INFINITY;
+      sv[4 + r] = (t1 <= qpos[i]) ? s1[r] * scale : -INFINITY;
+      tmax = fmaxf(tmax, fmaxf(sv[r], sv[4 + r]));
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(st.m[i], tmax);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float corr = expf(st.m[i] - m_safe);
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = expf(sv[e] - m_safe);
+      psum += p[e];
+    }
+    st.l[i] = st.l[i] * corr + psum;
+    st.m[i] = m_new;
+    v4u pk;
+    pk[0] = pack_h16x2(p[0], p[1]);
+    pk[1] = pack_h16x2(p[2], p[3]);
+    pk[2] = pack_h16x2(p[4], p[5]);
+    pk[3] = pack_h16x2(p[6], p[7]);
+    pf[i] = __builtin_bit_cast(v8bf, pk);
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) st.o[i][cb] = st.o[i][cb] * corr;
+  }
+  const int voff = (lane & 15) * kPageTokens + 4 * lg;
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb) {
+    const uint2 a = *reinterpret_cast<const uint2*>(V0 + cb * 256 + voff);
+    const uint2 b = *reinterpret_cast<const uint2*>(V1 + cb * 256 + voff);
+    const v4u raw = {a.x, a.y, b.x, b.y};
+    const v8bf vf = __builtin_bit_cast(v8bf, raw);
+#pragma unroll
+    for (int i = 0; i < NQB; ++i) {
+      if (i >= nqb) continue;
+      st.o[i][cb] = mfma16(vf, pf[i], st.o[i][cb]);
+    }
+  }
+}
+
+// ======================================================================================
+// decode: one workgroup per (sequence, kv head, context chunk); the G query heads of the kv
+// head are the (padded to 16) columns; four wavefronts share the chunk's page pairs.
+// ======================================================================================
+size_t attn_part_floats(int B, int Hkv, int G, int n_chunks) {
+  return (size_t)B * Hkv * n_chunks * G * (HD + 2);
+}
+
+__global__ __launch_bounds__(256) void k_attn_decode(float* part, const h16_t* q, int Hq, int Hkv,
+                                                     TokMap map, KvPool pool, int layer,
+                                                     int chunk_pages, int n_chunks) {
+  __shared__ float s_o[4][16][HD + 1];
+  __shared__ float s_m[4][16], s_l[4][16];
+  const int b = blockIdx.x, g = blockIdx.y, chunk = blockIdx.z;
+  const int G = Hq / Hkv;
+  const int pos = tok_pos(map, b);
+  const int n_ctx_pages = pos / kPageTokens + 1;
+  const int p_lo = chunk * chunk_pages, p_hi = min(n_ctx_pages, p_lo + chunk_pages);
+  if (p_lo >= p_hi) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, lg = lane >> 4;
+  const int* table = pool.page_table + (size_t)tok_seq(map, b) * map.row_stride * pool.max_pages;
+
+  v8bf qf[1][4];
+  int qpos[1];
+  qpos[0] = (col < G) ? pos : -1;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    v4u raw = {0u, 0u, 0u, 0u};
+    if (col < G)
+      raw = *reinterpret_cast<const v4u*>(q + (size_t)b * Hq * HD + (size_t)(g * G + col) * HD + kb * 32 + 8 * lg);
+    qf[0][kb] = __builtin_bit_cast(v8bf, raw);
+  }
+  AttnState<1> st;
+  attn_init(st);
+  const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  for (int pg = p_lo + 2 * wave; pg < p_hi; pg += 8) {
+    const int id0 = table[pg], id1 = table[min(pg + 1, n_ctx_pages - 1)];
+    attn_pair<1>(kv_page(pool, layer, 0, id0, g), kv_page(pool, layer, 0, id1, g),
+                 kv_page(pool, layer, 1, id0, g), kv_page(pool, layer, 1, id1, g), pg * kPageTokens, qf,
+                 qpos, 1, scale, st, lane);
+  }
+  float l = st.l[0];
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s_o[wave][col][cb * 16 + 4 * lg + r] = st.o[0][cb][r];
+  if (lg == 0) {
+    s_m[wave][col] = st.m[0];
+    s_l[wave][col] = l;
+  }
+  __syncthreads();
+  float* out = part + (((size_t)b * Hkv + g) * n_chunks + chunk) * (size_t)(G * (HD + 2));
+  for (int idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
+    const int c = idx / HD, d = idx % HD;
+    const float mm = fmaxf(fmaxf(s_m[0][c], s_m[1][c]), fmaxf(s_m[2][c], s_m[3][c]));
+    float acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) acc += expf(s_m[w][c] - mm) * s_o[w][c][d];
+    out[idx] = acc;
+  }
+  if (threadIdx.x < G) {
+    const int c = threadIdx.x;
+    const float mm = fmaxf(fmaxf(s_m[0][c], s_m[1][c]), fmaxf(s_m[2][c], s_m[3][c]));
+    float acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) acc += expf(s_m[w][c] - mm) * s_l[w][c];
+    out[G * HD + c] = mm;
+    out[G * HD + G + c] = acc;
+  }
+}
+
+void attention_decode(float* part, const h16_t* q, int B, int Hq, int Hkv, TokMap map, KvPool pool,
+                      int layer, int chunk_pages, int n_chunks, hipStream_t st) {
+  k_attn_decode<<<dim3(B, Hkv, n_chunks), 256, 0, st>>>(part, q, Hq, Hkv, map, pool, layer, chunk_pages,
+                                                       n_chunks);
+}
+
+// Merge of the chunk partials -> o (bf16, tiled activation layout with k = head * 128 + dim).
+__global__ __launch_bounds__(256) void k_attn_decode_merge(h16_t* o, const float* part, int Mpad, int Hq,
+                                                           int Hkv, TokMap map, int chunk_pages,
+                                                           int n_chunks) {
+  const int b = blockIdx.x, g = blockIdx.y;
+  const int G = Hq / Hkv;
+  const int pos = tok_pos(map, b);
+  const int n_act = (pos / kPageTokens + 1 + chunk_pages - 1) / chunk_pages;
+  const int t = threadIdx.x;  // one thread per (column, 8 consecutive dims)
+  if (t >= G * (HD / 8)) return;
+  const int c = t / (HD / 8), d0 = (t % (HD / 8)) * 8;
+  const size_t stride = (size_t)G * (HD + 2);
+  const float* base = part + ((size_t)b * Hkv + g) * n_chunks * stride;
+  float mm = -INFINITY;
+  for (int k = 0; k < n_act; ++k) mm = fmaxf(mm, base[k * stride + G * HD + c]);
+  float l = 0.f, acc[8] = {};
+  for (int k = 0; k < n_act; ++k) {
+    const float w = expf(base[k * stride + G * HD + c] - mm);
+    l += w * base[k * stride + G * HD + G + c];
+    const float* src = base + k * stride + (size_t)c * HD + d0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += w * src[e];
+  }
+  const float inv = 1.0f / l;
+  v4u pk;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) pk[e] = pack_h16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
+  *reinterpret_cast<v4u*>(o + act_off(b, (g * G + c) * HD + d0, Mpad)) = pk;
+}
+
+void attention_decode_merge(h16_t* o, const float* part, int B, int m_tiles, int Hq, int Hkv,
+                            TokMap map, int chunk_pages, int n_chunks, hipStream_t st) {
+  k_attn_decode_merge<<<dim3(B, Hkv), 256, 0, st>>>(o, part, m_tiles * 16, Hq, Hkv, map, chunk_pages,
+                                                   n_chunks);
+}
+
+// ======================================================================================
+// prefill / scoring: one workgroup per (32 query positions, kv head, sequence).  Its 2 G
+// column blocks (16 positions x one query head each) are dealt to the four wavefronts; every
+// wavefront walks the page pairs 0 .. diagonal.
+// ======================================================================================
+constexpr int NQB = 4;
+
+__global__ __launch_bounds__(256) void k_attn_prefill(h16_t* o, const h16_t* q, int S, int Mpad, int Hq,
+                                                      int Hkv, int row_stride, KvPool pool, int layer) {
+  const int qb0 = blockIdx.x * 32, g = blockIdx.y, seq = blockIdx.z;
+  const int G = Hq / Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, lg = lane >> 4;
+  const int n_blocks = 2 * G;
+  const int nqb = (n_blocks - wave + 3) / 4;  // blocks wave, wave + 4, ...
+  if (nqb <= 0) return;
+  const int* table = pool.page_table + (size_t)seq * row_stride * pool.max_pages;
+  const int seq_pages = (S + kPageTokens - 1) / kPageTokens;
+
+  v8bf qf[NQB][4];
+  int qpos[NQB], tok[NQB], head[NQB];
+#pragma unroll
+  for (int i = 0; i < NQB; ++i) {
+    const int blk = wave + 4 * i;
+    head[i] = g * G + (blk >> 1);
+    const int pos = qb0 + (blk & 1) * 16 + col;
+    const bool valid = (i < nqb) && pos < S;
+    qpos[i] = valid ? pos : -1;
+    tok[i] = seq * S + pos;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      v4u raw = {0u, 0u, 0u, 0u};
+      if (valid)
+        raw = *reinterpret_cast<const v4u*>(q + (size_t)tok[i] * Hq * HD + (size_t)head[i] * HD + kb * 32 + 8 * lg);
+      qf[i][kb] = __builtin_bit_cast(v8bf, raw);
+    }
+  }
+  AttnState<NQB> st;
+  attn_init(st);
+  const float scale = 0.08838834764831845f;
+  for (int pp = 0; pp <= (int)blockIdx.x; ++pp) {
+    const int id0 = table[min(2 * pp, seq_pages - 1)], id1 = table[min(2 * pp + 1, seq_pages - 1)];
+    attn_pair<NQB>(kv_page(pool, layer, 0, id0, g), kv_page(pool, layer, 0, id1, g),
+                   kv_page(pool, layer, 1, id0, g), kv_page(pool, layer, 1, id1, g), pp * 32, qf, qpos, nqb,
+                   scale, st, lane);
+  }
+#pragma unroll
+  for (int i = 0; i < NQB; ++i) {
+    if (i >= nqb) continue;
+    float l = st.l[i];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (qpos[i] < 0) continue;
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+      uint2 pk;
+      pk.x = pack_h16x2(st.o[i][cb][0] * inv, st.o[i][cb][1] * inv);
+      pk.y = pack_h16x2(st.o[i][cb][2] * inv, st.o[i][cb][3] * inv);
+      *reinterpret_cast<uint2*>(o + act_off(tok[i], head[i] * HD + cb * 16 + 4 * lg, Mpad)) = pk;
+    }
+  }
+}
+
+void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
+                       TokMap map, KvPool pool, int layer, hipStream_t st) {
+  k_attn_prefill<<<dim3((S + 31) / 32, Hkv, n_seqs), 256, 0, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
+                                                                  map.row_stride, pool, layer);
+}
+
+}  // namespace bf16
+}  // namespace mtmc

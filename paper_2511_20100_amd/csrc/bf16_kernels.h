@@ -1,0 +1,105 @@
+// Launchers of the bf16-path kernels (weights / KV cache in bf16, fp32 accumulation).
+#pragma once
+
+#include "common.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+// Per-call sampling parameters, kept in device memory so that captured launches stay valid.
+struct SampleCtl {
+  int greedy;
+  float inv_temp;
+  uint32_t key0, key1, seq_offset;
+  int max_new;
+  int* out_ids;
+  float* out_logprobs;
+};
+
+struct SkinnyArgs {
+  const h16_t* Wt;   // tiled weights [n_tiles][k_tiles][512]
+  const h16_t* Xt;   // tiled activations [k_tiles][m_tiles][512]
+  int n_tiles, k_tiles, m_tiles, M;
+  float* out_f32;     // partial sums [split][m_tiles*16][ld_out], or sampler partials
+  int ld_out;
+  h16_t* out_bf16;   // tiled activation output (SwiGLU)
+  const SampleCtl* ctl;
+  const int* d_step;
+};
+
+struct LargeArgs {
+  const h16_t* Wt;
+  const h16_t* Xt;
+  int n_tiles, k_tiles, m_tiles, M, N;
+  float* out_f32;
+  int ld_out;
+  h16_t* out_bf16;
+};
+
+struct ScoreHeadArgs {
+  const h16_t* Wt;
+  const h16_t* Xt;
+  int n_tiles, k_tiles, m_tiles, M;
+  const int* targets;
+  float* part;
+  int n_groups, groups_per_block;
+};
+
+// ---- weight re-tiling (once, at load) ------------------------------------------------------
+// dst (tiled fp16, n_tiles x k_tiles blocks) <- src row-major [N, K] bf16; rows/cols past N/K are
+// zero.  Sets bit 1 of *err_flag if a weight does not fit fp16 (magnitude above 65504, or not finite).
+void retile_weight(h16_t* dst, const bf16_t* src, int N, int K, int n_tiles, int k_tiles, int* err_flag,
+                   hipStream_t st);
+// Gate and up interleaved by 16-row tiles: tile 2j <- gate rows 16j.., tile 2j+1 <- up rows 16j..
+void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int K, int f_tiles,
+                    int k_tiles, int* err_flag, hipStream_t st);
+
+// ---- GEMMs ---------------------------------------------------------------------------------
+int skinny_nb(int m_tiles);
+void gemm_skinny_partial(float* P, int ldp, const h16_t* Wt, int n_tiles, int k_tiles,
+                         const h16_t* Xt, int M, int m_tiles, int ksplit, hipStream_t st);
+void gemm_skinny_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
+                        int M, int m_tiles, hipStream_t st);
+int sample_groups(int n_tiles, int m_tiles);
+void gemm_skinny_sample(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
+                        int M, int m_tiles, const SampleCtl* ctl, const int* d_step, hipStream_t st);
+void sample_reduce(const float* part, int n_groups, int M, const SampleCtl* ctl, const int* d_step,
+                   int* cur_ids, hipStream_t st);
+void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
+                    int k_tiles, const h16_t* Xt, int M, int m_tiles, hipStream_t st);
+void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
+                       int M, int m_tiles, hipStream_t st);
+int score_head_blocks(int n_tiles, int* groups_per_block);
+void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
+                  int m_tiles, const int* targets, hipStream_t st);
+void score_targets(int* targets, const int* seqs, int R, int S, int first, int n_scored, int seq0,
+                   int row0, int vocab, int* err_flag, hipStream_t st);
+void score_reduce(const float* part, int n_parts, int R, int S, int first, int n_scored, int seq0,
+                  int row0, float* out_logprobs, int* out_top1, float* out_margin, hipStream_t st);
+
+// ---- elementwise / row kernels -------------------------------------------------------------
+void set_sample_ctl(SampleCtl* dst, const SampleCtl& v, hipStream_t st);
+void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, int* err_flag,
+           hipStream_t st);
+// h[m, :] += sum_s P[s][m][:] (n_split may be 0); x = bf16(RMSNorm(h; gain)) in tiled layout.
+void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
+              h16_t* x, int M, int m_tiles, int d, hipStream_t st);
+// qkv = sum_s P[s][m][:]: rotates q (-> bf16 row-major [T, Hq*hd]) and k, writes k, v into pages.
+void rope_kv_write(h16_t* q, const float* P, int n_split, int ldp, int Mpad_p, int T, int Hq, int Hkv,
+                   const float* cos, const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st);
+
+// ---- attention -----------------------------------------------------------------------------
+// Decode: one query position per sequence (position pos_base + *d_step), context split into
+// chunks of `chunk_pages` pages; partial results in `part`, merged by attention_decode_merge.
+size_t attn_part_floats(int B, int Hkv, int G, int n_chunks);
+void attention_decode(float* part, const h16_t* q, int B, int Hq, int Hkv, TokMap map, KvPool pool,
+                      int layer, int chunk_pages, int n_chunks, hipStream_t st);
+void attention_decode_merge(h16_t* o, const float* part, int B, int m_tiles, int Hq, int Hkv,
+                            TokMap map, int chunk_pages, int n_chunks, hipStream_t st);
+// Prefill / scoring: causal attention of every token of T = n_seqs * S over its own sequence.
+void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
+                       TokMap map, KvPool pool, int layer, hipStream_t st);
+
+}  // namespace bf16
+}  // namespace mtmc

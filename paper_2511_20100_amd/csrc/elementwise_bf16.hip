@@ -1,0 +1,166 @@
+// Row-wise and layout kernels of the bf16 path: weight re-tiling, embedding, residual-add +
+// RMSNorm (-> tiled bf16 GEMM operand), split-K sum + rotary embedding + KV page write.
+#include "bf16_kernels.h"
+#include "device_utils.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+// ---------------------------------------------------------------- weight re-tiling
+__global__ void k_retile(h16_t* dst, const bf16_t* src0, const bf16_t* src1, int N, int K, int n_tiles,
+                         int k_tiles, int interleave, int* err_flag) {
+  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 8-element chunk
+  const size_t total = (size_t)n_tiles * k_tiles * 64;
+  if (chunk >= total) return;
+  const int lane = (int)(chunk & 63);
+  const size_t tile = chunk >> 6;
+  const int kt = (int)(tile % k_tiles), nt = (int)(tile / k_tiles);
+  const int k = kt * 32 + (lane >> 4) * 8;
+  const bf16_t* src = src0;
+  int n;
+  if (interleave) {
+    src = (nt & 1) ? src1 : src0;
+    n = (nt >> 1) * 16 + (lane & 15);
+  } else {
+    n = nt * 16 + (lane & 15);
+  }
+  v4u v = {0u, 0u, 0u, 0u};
+  if (n < N && k < K) {
+    const v4u raw = *reinterpret_cast<const v4u*>(src + (size_t)n * K + k);
+    bool overflow = false;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = __uint_as_float(raw[e] << 16), hi = __uint_as_float(raw[e] & 0xffff0000u);
+      overflow |= !(fabsf(lo) <= 65504.f) || !(fabsf(hi) <= 65504.f);
+      v[e] = pack_h16x2(lo, hi);
+    }
+    if (overflow) atomicOr(err_flag, 2);
+  }
+  *reinterpret_cast<v4u*>(dst + chunk * 8) = v;
+}
+void retile_weight(h16_t* dst, const bf16_t* src, int N, int K, int n_tiles, int k_tiles, int* err_flag,
+                   hipStream_t st) {
+  const size_t total = (size_t)n_tiles * k_tiles * 64;
+  k_retile<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(dst, src, nullptr, N, K, n_tiles, k_tiles, 0, err_flag);
+}
+void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int K, int f_tiles,
+                    int k_tiles, int* err_flag, hipStream_t st) {
+  const size_t total = (size_t)2 * f_tiles * k_tiles * 64;
+  k_retile<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(dst, gate, up, F, K, 2 * f_tiles, k_tiles, 1, err_flag);
+}
+
+// ---------------------------------------------------------------- control
+__global__ void k_set_ctl(SampleCtl* dst, SampleCtl v) { *dst = v; }
+void set_sample_ctl(SampleCtl* dst, const SampleCtl& v, hipStream_t st) { k_set_ctl<<<1, 1, 0, st>>>(dst, v); }
+
+// ---------------------------------------------------------------- embedding
+__global__ void k_embed(float* h, const int* ids, const bf16_t* E, int d, int vocab, int* err_flag) {
+  const int t = blockIdx.x;
+  int id = ids[t];
+  if (id < 0 || id >= vocab) {
+    if (threadIdx.x == 0) atomicOr(err_flag, 1);
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  for (int c = threadIdx.x; c < d; c += blockDim.x) h[(size_t)t * d + c] = bf16_to_f32(E[(size_t)id * d + c]);
+}
+void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, int* err_flag, hipStream_t st) {
+  k_embed<<<T, 256, 0, st>>>(h, ids, E, d, vocab, err_flag);
+}
+
+// ---------------------------------------------------------------- residual add + RMSNorm
+// One workgroup per row; a thread owns 8 consecutive features (one 16-byte chunk of the tiled
+// operand).  Pass 1 folds the split-K partial sums into the fp32 residual and accumulates the
+// sum of squares; pass 2 writes bf16(h * rsqrt(mean + eps) * gain).
+__global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p,
+                                                  const float* gain, float eps, h16_t* x, int Mpad, int d) {
+  __shared__ float red[16];
+  const int m = blockIdx.x;
+  float* hr = h + (size_t)m * d;
+  float ss = 0.f;
+  for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
+    v4f a = *reinterpret_cast<const v4f*>(hr + k), b = *reinterpret_cast<const v4f*>(hr + k + 4);
+    for (int s = 0; s < n_split; ++s) {
+      const float* pr = P + ((size_t)s * Mpad_p + m) * ldp + k;
+      a = a + *reinterpret_cast<const v4f*>(pr);
+      b = b + *reinterpret_cast<const v4f*>(pr + 4);
+    }
+    if (n_split > 0) {
+      *reinterpret_cast<v4f*>(hr + k) = a;
+      *reinterpret_cast<v4f*>(hr + k + 4) = b;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
+  }
+  ss = block_sum(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
+    const v4f a = *reinterpret_cast<const v4f*>(hr + k), b = *reinterpret_cast<const v4f*>(hr + k + 4);
+    const v4f ga = *reinterpret_cast<const v4f*>(gain + k), gb = *reinterpret_cast<const v4f*>(gain + k + 4);
+    v4u pk;
+    pk[0] = pack_h16x2(a[0] * r * ga[0], a[1] * r * ga[1]);
+    pk[1] = pack_h16x2(a[2] * r * ga[2], a[3] * r * ga[3]);
+    pk[2] = pack_h16x2(b[0] * r * gb[0], b[1] * r * gb[1]);
+    pk[3] = pack_h16x2(b[2] * r * gb[2], b[3] * r * gb[3]);
+    *reinterpret_cast<v4u*>(x + act_off(m, k, Mpad)) = pk;
+  }
+}
+void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
+              h16_t* x, int M, int m_tiles, int d, hipStream_t st) {
+  if (M == 0) return;
+  k_add_norm<<<M, 256, 0, st>>>(h, P, n_split, ldp, Mpad_p, gain, eps, x, m_tiles * 16, d);
+}
+
+// ---------------------------------------------------------------- rotary embedding + KV write
+// qkv[m, :] = sum_s P[s][m][:] (fp32).  q heads are rotated and stored bf16 row-major; k heads
+// are rotated and scattered into the K page ([dim/8][token][dim%8]); v into the V page
+// ([dim][token]).  Pairs are (i, i + 64) of the 128-dim head.
+__global__ __launch_bounds__(256) void k_rope_kv_write(h16_t* q, const float* P, int n_split, int ldp,
+                                                       int Mpad_p, int Hq, int Hkv, const float* cos,
+                                                       const float* sin, TokMap map, KvPool pool, int layer) {
+  constexpr int HD = 128, HALF = 64;
+  const int t = blockIdx.x;
+  const int pos = tok_pos(map, t);
+  const int row = tok_seq(map, t) * map.row_stride;
+  const int page = pool.page_table[(size_t)row * pool.max_pages + pos / kPageTokens];
+  const int slot = pos % kPageTokens;
+  h16_t* kv = (h16_t*)pool.base;
+  const size_t page_elems = (size_t)kPageTokens * HD;
+  for (int e = threadIdx.x; e < (Hq + Hkv) * HALF; e += blockDim.x) {
+    const int head = e / HALF, i = e % HALF;
+    float a = 0.f, b = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+      const float* pr = P + ((size_t)s * Mpad_p + t) * ldp + (size_t)head * HD;
+      a += pr[i];
+      b += pr[i + HALF];
+    }
+    const float c = cos[(size_t)pos * HALF + i], sn = sin[(size_t)pos * HALF + i];
+    const float ra = a * c - b * sn, rb = b * c + a * sn;
+    if (head < Hq) {
+      h16_t* qr = q + (size_t)t * Hq * HD + (size_t)head * HD;
+      qr[i] = f32_to_h16(ra);
+      qr[i + HALF] = f32_to_h16(rb);
+    } else {
+      const int g = head - Hq;
+      h16_t* kp = kv + ((((size_t)layer * 2 + 0) * pool.n_pages + page) * pool.n_kv_heads + g) * page_elems;
+      const int c0 = i, c1 = i + HALF;
+      kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(ra);
+      kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(rb);
+    }
+  }
+  for (int e = threadIdx.x; e < Hkv * HD; e += blockDim.x) {
+    const int g = e / HD, c = e % HD;
+    float v = 0.f;
+    for (int s = 0; s < n_split; ++s) v += P[((size_t)s * Mpad_p + t) * ldp + (size_t)(Hq + Hkv) * HD + e];
+    h16_t* vp = kv + ((((size_t)layer * 2 + 1) * pool.n_pages + page) * pool.n_kv_heads + g) * page_elems;
+    vp[c * kPageTokens + slot] = f32_to_h16(v);
+  }
+}
+void rope_kv_write(h16_t* q, const float* P, int n_split, int ldp, int Mpad_p, int T, int Hq, int Hkv,
+                   const float* cos, const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st) {
+  if (T == 0) return;
+  k_rope_kv_write<<<T, 256, 0, st>>>(q, P, n_split, ldp, Mpad_p, Hq, Hkv, cos, sin, map, pool, layer);
+}
+
+}  // namespace bf16
+}  // namespace mtmc

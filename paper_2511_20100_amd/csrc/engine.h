@@ -29,6 +29,9 @@ struct Carver {
 };
 
 struct RolloutPlan {
+  // A call is run as consecutive groups of `n_prompts` prompts (B = n_prompts * n_samples
+  // sequences each); all sizes below are per group.
+  int total_prompts;
   int n_prompts, prompt_len, n_samples, max_new, B;
   int n_full;        // pages per prompt that are completely filled by the prompt (shared)
   int max_pages;     // page-table row length
@@ -54,6 +57,11 @@ struct RolloutPlan {
   float* part;        // split-K partial sums
   float* attn_part;   // decode-attention partial (m, l, o) per context split
   float* lm_part;     // LM-head per-tile partial reductions
+  void* qb;           // rotated queries, bf16 row-major [Tmax, Hq*hd]
+  void* ctl;          // per-call sampling parameters (device copy)
+  int chunk_pages, n_chunks;       // decode-attention context split
+  int ks_qkv, ks_o, ks_down;       // split-K factors of the decode GEMMs
+  int bt;                          // 16-row tiles covering B
   size_t total_bytes;
 };
 
@@ -74,6 +82,8 @@ struct ScorePlan {
   float* logits;
   float* part;
   float* lm_part;
+  void* qb;
+  int* targets;
   size_t total_bytes;
 };
 

@@ -8,6 +8,7 @@ namespace mtmc {
 
 // Tokens per prefill / scoring chunk: bounds activation memory, keeps every launch large.
 static constexpr int kChunkTokens = 8192;
+static constexpr int kMaxBf16Batch = 128;  // rows the skinny decode GEMMs take
 static constexpr size_t kLogitBytes = (size_t)256 << 20;
 
 int build_aux(mtmc_weights* w, hipStream_t st) {
@@ -44,14 +45,17 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
   const mtmc_config& c = w->cfg;
   const bool bf = c.dtype == MTMC_BF16;
   RolloutPlan p{};
+  p.total_prompts = n_prompts;
+  if (bf) n_prompts = std::min(n_prompts, std::max(1, kMaxBf16Batch / n_samples));
   p.n_prompts = n_prompts; p.prompt_len = prompt_len; p.n_samples = n_samples; p.max_new = max_new;
   p.B = n_prompts * n_samples;
+  p.bt = (p.B + 15) / 16;
   p.n_full = prompt_len / kPageTokens;
   p.max_pages = (prompt_len + max_new + kPageTokens - 1) / kPageTokens;
   p.shared_total = n_prompts * p.n_full;
   p.n_pages = p.shared_total + p.B * (p.max_pages - p.n_full);
   p.chunk_prompts = std::max(1, std::min(n_prompts, kChunkTokens / prompt_len));
-  p.Tmax = std::max(p.chunk_prompts * prompt_len, p.B);
+  p.Tmax = (std::max(p.chunk_prompts * prompt_len, p.B) + 127) / 128 * 128;
   const size_t act = bf ? 2 : 4;
   const size_t d = c.d_model, nq = (size_t)c.n_q_heads * c.head_dim;
   const size_t nqkv = nq + 2 * (size_t)c.n_kv_heads * c.head_dim;
@@ -67,7 +71,7 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
   p.o = cv.take<char>((size_t)p.Tmax * nq * act);
   p.a = cv.take<char>((size_t)p.Tmax * F * act);
   p.hB = cv.take<float>((size_t)p.B * d);
-  p.xB = cv.take<char>((size_t)p.B * d * act);
+  p.xB = cv.take<char>((size_t)p.bt * 16 * d * act);
   if (!bf) {
     p.gu = cv.take<float>((size_t)p.Tmax * 2 * F);
     p.logits = cv.take<float>((size_t)p.B * c.vocab);
@@ -86,8 +90,8 @@ ScorePlan plan_score(const mtmc_weights* w, int n_seqs, int S, char* base) {
   p.chunk_seqs = std::max(1, std::min(n_seqs, kChunkTokens / S));
   p.pages_per_seq = (S + kPageTokens - 1) / kPageTokens;
   p.n_pages = p.chunk_seqs * p.pages_per_seq;
-  p.T = p.chunk_seqs * S;
-  p.rows_max = p.chunk_seqs * (S - 1);
+  p.T = (p.chunk_seqs * S + 127) / 128 * 128;
+  p.rows_max = (p.chunk_seqs * (S - 1) + 127) / 128 * 128;
   const size_t act = bf ? 2 : 4;
   const size_t d = c.d_model, nq = (size_t)c.n_q_heads * c.head_dim;
   const size_t nqkv = nq + 2 * (size_t)c.n_kv_heads * c.head_dim;
@@ -182,6 +186,7 @@ void f32_layers(const mtmc_weights* w, const F32Acts& A, int T, TokMap map, KvPo
 
 int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts, const SampleArgs& sa,
                 hipStream_t st) {
+  // the fp32 path runs the whole call as one group (plan_rollout keeps n_prompts == total_prompts)
   const mtmc_config& c = w->cfg;
   const int d = c.d_model, V = c.vocab;
   F32Acts A{p.h, (float*)p.x, p.qkv, (float*)p.o, p.gu, (float*)p.a};

@@ -1,23 +1,332 @@
-// bf16 path schedulers (weights and KV cache in bf16, fp32 residual stream and accumulators).
+// bf16 path: weight store (re-tiled for the MFMA kernels), workspace extras and the schedulers.
+// Weights and KV cache are bf16; the residual stream, norms, softmax and all accumulators fp32.
+#include <algorithm>
+#include <array>
+
+#include "bf16_kernels.h"
 #include "engine.h"
 #include "kernels.h"
 
 namespace mtmc {
 
-void bf16_plan_rollout_extra(const mtmc_weights*, RolloutPlan&, Carver&) {}
-void bf16_plan_score_extra(const mtmc_weights*, ScorePlan&, Carver&) {}
 
-int bf16_store_weights(mtmc_weights*, const BlobLayout&, const void*, bool, hipStream_t) {
-  set_error("MTMC_BF16 is not available in this build");
-  return MTMC_EINVAL;
+
+namespace {
+inline int tiles16(int n) { return (n + 15) / 16; }
+inline int tiles32(int n) { return (n + 31) / 32; }
+
+// Split-K factor of a decode GEMM: enough workgroups to cover the chip, while every wavefront
+// (4 per workgroup) still walks at least two k tiles.
+int choose_ksplit(int n_tiles, int k_tiles, int m_tiles) {
+  const int groups = (n_tiles + bf16::skinny_nb(m_tiles) - 1) / bf16::skinny_nb(m_tiles);
+  const int want = (320 + groups - 1) / groups;
+  return std::max(1, std::min(want, k_tiles / 8));
 }
-int bf16_rollout(const mtmc_weights*, const RolloutPlan&, const int*, const SampleArgs&, hipStream_t) {
-  set_error("MTMC_BF16 is not available in this build");
-  return MTMC_EINVAL;
+
+struct Dims {
+  int d, Hq, Hkv, nq, nqkv, F, V;
+  int kt_d, kt_nq, kt_F;          // k tiles (32) of the three reduction widths
+  int nt_qkv, nt_d, nt_gu, nt_V;  // n tiles (16) of the weight matrices
+};
+Dims dims_of(const mtmc_weights* w) {
+  const mtmc_config& c = w->cfg;
+  Dims D;
+  D.d = c.d_model; D.Hq = c.n_q_heads; D.Hkv = c.n_kv_heads; D.nq = D.Hq * c.head_dim;
+  D.nqkv = (D.Hq + 2 * D.Hkv) * c.head_dim; D.F = w->d_ffn_pad; D.V = c.vocab;
+  D.kt_d = tiles32(D.d); D.kt_nq = tiles32(D.nq); D.kt_F = D.F / 32;
+  D.nt_qkv = tiles16(D.nqkv); D.nt_d = tiles16(D.d); D.nt_gu = 2 * (D.F / 16); D.nt_V = tiles16(D.V);
+  return D;
 }
-int bf16_score(const mtmc_weights*, const ScorePlan&, const ScoreArgs&, hipStream_t) {
-  set_error("MTMC_BF16 is not available in this build");
-  return MTMC_EINVAL;
+}  // namespace
+
+// ======================================================================================
+// weights
+// ======================================================================================
+int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob, bool on_device,
+                       hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  w->d_ffn_pad = (c.d_ffn + 31) / 32 * 32;
+  const Dims D = dims_of(w);
+  for (const BlobLayerOffsets& o : lay.layers) {
+    if (o.wk != o.wq + (size_t)D.nq * D.d * 2 || o.wv != o.wk + (size_t)D.Hkv * c.head_dim * D.d * 2) {
+      set_error("Wq/Wk/Wv must be contiguous in the blob");
+      return MTMC_EINVAL;
+    }
+  }
+  void* dev_blob = nullptr;
+  const char* src = (const char*)blob;
+  if (!on_device) {
+    if (hipMalloc(&dev_blob, lay.total) != hipSuccess) {
+      set_error("hipMalloc failed for the staging copy of the blob");
+      return MTMC_ENOMEM;
+    }
+    if (hipMemcpyAsync(dev_blob, blob, lay.total, hipMemcpyHostToDevice, st) != hipSuccess) {
+      (void)hipFree(dev_blob);
+      set_error("upload of the weight blob failed");
+      return MTMC_EHIP;
+    }
+    src = (const char*)dev_blob;
+  }
+  // ---- carve the library-owned storage
+  Carver cv(nullptr);
+  auto plan = [&](Carver& k) {
+    struct Out { bf16_t* embed; h16_t* lm; float* fnorm; std::vector<std::array<void*, 6>> L; } o;
+    o.embed = k.take<bf16_t>((size_t)D.V * D.d);
+    o.lm = k.take<h16_t>((size_t)D.nt_V * D.kt_d * 512);
+    o.fnorm = k.take<float>(D.d);
+    o.L.resize(c.n_layers);
+    for (auto& l : o.L) {
+      l[0] = k.take<float>(D.d);
+      l[1] = k.take<float>(D.d);
+      l[2] = k.take<h16_t>((size_t)D.nt_qkv * D.kt_d * 512);
+      l[3] = k.take<h16_t>((size_t)D.nt_d * D.kt_nq * 512);
+      l[4] = k.take<h16_t>((size_t)D.nt_gu * D.kt_d * 512);
+      l[5] = k.take<h16_t>((size_t)D.nt_d * D.kt_F * 512);
+    }
+    return o;
+  };
+  plan(cv);
+  const size_t total = cv.off + 256;
+  if (hipMalloc(&w->storage, total) != hipSuccess) {
+    if (dev_blob) (void)hipFree(dev_blob);
+    set_error("hipMalloc failed for the weights (" + std::to_string(total) + " bytes)");
+    return MTMC_ENOMEM;
+  }
+  w->storage_bytes = total;
+  Carver real((char*)w->storage);
+  auto o = plan(real);
+  int rc = MTMC_OK;
+  auto copy = [&](void* dst, size_t off, size_t bytes) {
+    if (rc == MTMC_OK && hipMemcpyAsync(dst, src + off, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+      set_error("device copy of a weight tensor failed");
+      rc = MTMC_EHIP;
+    }
+  };
+  copy(o.embed, lay.embed, (size_t)D.V * D.d * 2);
+  copy(o.fnorm, lay.final_norm, (size_t)D.d * 4);
+  bf16::retile_weight(o.lm, (const bf16_t*)(src + lay.lm_head), D.V, D.d, D.nt_V, D.kt_d, w->err_flag, st);
+  w->embed = o.embed;
+  w->lm_head = o.lm;
+  w->final_norm = o.fnorm;
+  w->layers.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const BlobLayerOffsets& b = lay.layers[l];
+    copy(o.L[l][0], b.attn_norm, (size_t)D.d * 4);
+    copy(o.L[l][1], b.ffn_norm, (size_t)D.d * 4);
+    bf16::retile_weight((h16_t*)o.L[l][2], (const bf16_t*)(src + b.wq), D.nqkv, D.d, D.nt_qkv, D.kt_d, w->err_flag, st);
+    bf16::retile_weight((h16_t*)o.L[l][3], (const bf16_t*)(src + b.wo), D.d, D.nq, D.nt_d, D.kt_nq, w->err_flag, st);
+    bf16::retile_gate_up((h16_t*)o.L[l][4], (const bf16_t*)(src + b.wgate), (const bf16_t*)(src + b.wup),
+                         c.d_ffn, D.d, D.F / 16, D.kt_d, w->err_flag, st);
+    bf16::retile_weight((h16_t*)o.L[l][5], (const bf16_t*)(src + b.wdown), D.d, c.d_ffn, D.nt_d, D.kt_F, w->err_flag, st);
+    LayerWeights& L = w->layers[l];
+    L.attn_norm = (const float*)o.L[l][0];
+    L.ffn_norm = (const float*)o.L[l][1];
+    L.wqkv = o.L[l][2];
+    L.wo = o.L[l][3];
+    L.wgu = o.L[l][4];
+    L.wdown = o.L[l][5];
+  }
+  if (rc == MTMC_OK && hipGetLastError() != hipSuccess) {
+    set_error("a weight re-tiling kernel failed to launch");
+    rc = MTMC_EHIP;
+  }
+  if (hipStreamSynchronize(st) != hipSuccess && rc == MTMC_OK) {
+    set_error("hipStreamSynchronize failed while re-tiling the weights");
+    rc = MTMC_EHIP;
+  }
+  if (dev_blob) (void)hipFree(dev_blob);
+  if (rc == MTMC_OK) {
+    int flag = 0;
+    MTMC_HIP_CHECK(hipMemcpy(&flag, w->err_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag & 2) {
+      (void)hipMemset(w->err_flag, 0, sizeof(int));
+      set_error("invalid argument: a weight is not finite or exceeds 65504 in magnitude (the matrix "
+                "cores run on fp16 copies of the bf16 weights)");
+      return MTMC_EINVAL;
+    }
+  }
+  return rc;
+}
+
+// ======================================================================================
+// workspace extras
+// ======================================================================================
+void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) {
+  const Dims D = dims_of(w);
+  const int G = D.Hq / D.Hkv;
+  p.ks_qkv = choose_ksplit(D.nt_qkv, D.kt_d, p.bt);
+  p.ks_o = choose_ksplit(D.nt_d, D.kt_nq, p.bt);
+  p.ks_down = choose_ksplit(D.nt_d, D.kt_F, p.bt);
+  // context split of the decode attention: about 512 workgroups at full context, >= 8 pages each
+  const int want = std::max(1, 512 / std::max(1, p.B * D.Hkv));
+  p.n_chunks = std::max(1, std::min(want, (p.max_pages + 7) / 8));
+  p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;
+  p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
+  const size_t Mpad = (size_t)p.bt * 16;
+  const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;
+  p.part = cv.take<float>(part);
+  p.attn_part = cv.take<float>(bf16::attn_part_floats(p.B, D.Hkv, G, p.n_chunks));
+  p.lm_part = cv.take<float>((size_t)bf16::sample_groups(D.nt_V, p.bt) * p.B * 8);
+  p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
+  p.ctl = cv.take<bf16::SampleCtl>(1);
+}
+
+void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
+  const Dims D = dims_of(w);
+  int gpb = 0;
+  const int blocks = bf16::score_head_blocks(D.nt_V, &gpb);
+  p.lm_part = cv.take<float>((size_t)blocks * 2 * p.rows_max * 8);
+  p.qb = cv.take<h16_t>((size_t)p.T * D.nq);
+  p.targets = cv.take<int>(p.rows_max);
+}
+
+// ======================================================================================
+// schedulers
+// ======================================================================================
+namespace {
+
+// All residual blocks over T >= 1 tokens in the large-batch (prefill / scoring) form.
+// In: h (fp32 [T, d]) and x = bf16 RMSNorm(h; attn_norm of layer 0) in tiled layout.
+// Out: h after the last block (x is not refreshed after the last block).
+void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, float* qkv, h16_t* qb,
+                    h16_t* o, h16_t* a, int n_seqs, int S, TokMap map, KvPool pool, int layer_stride,
+                    hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  const int T = n_seqs * S, mt = tiles16(T);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerWeights& L = w->layers[l];
+    const int kvl = l * layer_stride;
+    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, st);
+    bf16::rope_kv_write(qb, qkv, 1, D.nqkv, 0, T, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, st);
+    bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, st);
+    bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, st);
+    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, st);
+    if (l + 1 < c.n_layers)
+      bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, st);
+  }
+}
+
+// One decode step over the B sequences of a group: embeds cur_ids, runs the blocks against the
+// paged cache at position prompt_len - 1 + *d_step, leaves x = bf16 RMSNorm(h; final_norm).
+void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, KvPool pool, TokMap dmap,
+                   hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  const int B = p.B, bt = p.bt, Mpad = bt * 16;
+  float* h = p.hB;
+  h16_t* x = (h16_t*)p.xB;
+  h16_t* o = (h16_t*)p.o;
+  h16_t* a = (h16_t*)p.a;
+  h16_t* qb = (h16_t*)p.qb;
+  bf16::embed(h, p.cur_ids, B, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+  bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, x, B, bt, D.d, st);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerWeights& L = w->layers[l];
+    bf16::gemm_skinny_partial(p.part, D.nqkv, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, B, bt, p.ks_qkv, st);
+    bf16::rope_kv_write(qb, p.part, p.ks_qkv, D.nqkv, Mpad, B, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, dmap,
+                        pool, l, st);
+    bf16::attention_decode(p.attn_part, qb, B, D.Hq, D.Hkv, dmap, pool, l, p.chunk_pages, p.n_chunks, st);
+    bf16::attention_decode_merge(o, p.attn_part, B, bt, D.Hq, D.Hkv, dmap, p.chunk_pages, p.n_chunks, st);
+    bf16::gemm_skinny_partial(p.part, D.d, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, B, bt, p.ks_o, st);
+    bf16::add_norm(h, p.part, p.ks_o, D.d, Mpad, L.ffn_norm, c.rms_eps, x, B, bt, D.d, st);
+    bf16::gemm_skinny_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, B, bt, st);
+    bf16::gemm_skinny_partial(p.part, D.d, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, B, bt, p.ks_down, st);
+    const float* next = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
+    bf16::add_norm(h, p.part, p.ks_down, D.d, Mpad, next, c.rms_eps, x, B, bt, D.d, st);
+  }
+}
+
+}  // namespace
+
+int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts, const SampleArgs& sa,
+                 hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  if (p.n_samples > 128) {
+    set_error("invalid argument: MTMC_BF16 rollout takes at most 128 samples per prompt");
+    return MTMC_EINVAL;
+  }
+  const Dims D = dims_of(w);
+  KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};
+  const size_t kv_words = (size_t)c.n_layers * 2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim / 2;
+  for (int g0 = 0; g0 < p.total_prompts; g0 += p.n_prompts) {
+    const int np_group = std::min(p.n_prompts, p.total_prompts - g0);
+    RolloutPlan gp = p;  // this group's shape (the last group may be smaller)
+    gp.n_prompts = np_group;
+    gp.B = np_group * p.n_samples;
+    gp.bt = tiles16(gp.B);
+    gp.shared_total = np_group * p.n_full;
+    const int* gprompts = prompts + (size_t)g0 * p.prompt_len;
+    const size_t out_off = (size_t)g0 * p.n_samples * p.max_new;
+    bf16::SampleCtl ctl{sa.greedy, sa.inv_temp, (uint32_t)(sa.seed & 0xffffffffu), (uint32_t)(sa.seed >> 32),
+                        sa.seq_offset + (uint32_t)(g0 * p.n_samples), sa.max_new, sa.out_ids + out_off,
+                        sa.out_logprobs + out_off};
+    bf16::set_sample_ctl((bf16::SampleCtl*)p.ctl, ctl, st);
+    launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
+    launch_set_int(p.d_step, 0, st);
+    // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
+    launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
+    // ---- prefill, whole prompts per chunk; a prompt's pages are those of its first sample
+    for (int p0 = 0; p0 < np_group; p0 += p.chunk_prompts) {
+      const int np = std::min(p.chunk_prompts, np_group - p0);
+      const int T = np * p.prompt_len, mt = tiles16(T);
+      KvPool chunk_pool = pool;
+      chunk_pool.page_table = p.page_table + (size_t)p0 * p.n_samples * p.max_pages;
+      TokMap map{p.prompt_len, p.n_samples, 0, nullptr};
+      bf16::embed(p.h, gprompts + (size_t)p0 * p.prompt_len, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+      bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+      prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, p.prompt_len,
+                     map, chunk_pool, 1, st);
+      launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, np * p.n_samples, D.d, p.n_samples,
+                         p.prompt_len, p.prompt_len - 1, 0, st);
+    }
+    if (p.prompt_len % kPageTokens != 0)
+      launch_fork_tail_pages(pool, c.n_layers, gp.B, p.n_samples, p.n_full, 2, st);
+    // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i - 1
+    TokMap dmap{1, 1, p.prompt_len - 1, p.d_step};
+    bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, st);
+    for (int i = 0; i < p.max_new; ++i) {
+      if (i > 0) decode_layers(w, D, gp, pool, dmap, st);
+      bf16::gemm_skinny_sample(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xB, gp.B,
+                               gp.bt, (const bf16::SampleCtl*)p.ctl, p.d_step, st);
+      bf16::sample_reduce(p.lm_part, bf16::sample_groups(D.nt_V, gp.bt), gp.B, (const bf16::SampleCtl*)p.ctl,
+                          p.d_step, p.cur_ids, st);
+      launch_add_int(p.d_step, 1, st);
+    }
+  }
+  return MTMC_OK;
+}
+
+int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  const Dims D = dims_of(w);
+  const int S = a.S, n_scored = S - 1 - a.first;
+  const size_t n_out = (size_t)a.n_seqs * (S - 1);
+  launch_fill_u32((uint32_t*)a.out_logprobs, 0u, n_out, st);
+  if (a.out_top1) launch_fill_u32((uint32_t*)a.out_top1, 0u, n_out, st);
+  if (a.out_margin) launch_fill_u32((uint32_t*)a.out_margin, 0u, n_out, st);
+  KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.pages_per_seq};
+  launch_build_page_table(p.page_table, p.chunk_seqs, p.pages_per_seq, 1, 0, 0, st);
+  launch_fill_u32((uint32_t*)p.kv, 0u, (size_t)2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim / 2, st);
+  TokMap map{S, 1, 0, nullptr};
+  int gpb = 0;
+  const int n_parts = bf16::score_head_blocks(D.nt_V, &gpb) * 2;
+  for (int s0 = 0; s0 < a.n_seqs; s0 += p.chunk_seqs) {
+    const int ns = std::min(p.chunk_seqs, a.n_seqs - s0);
+    const int T = ns * S, mt = tiles16(T);
+    bf16::embed(p.h, a.seqs + (size_t)s0 * S, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, S, map, pool, 0, st);
+    const int R = ns * n_scored;
+    if (R == 0) continue;
+    const int rt = tiles16(R);
+    launch_gather_rows(p.hs, p.h, R, D.d, n_scored, S, a.first, 1, st);
+    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
+    bf16::score_targets(p.targets, a.seqs, R, S, a.first, n_scored, s0, 0, D.V, w->err_flag, st);
+    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets, st);
+    bf16::score_reduce(p.lm_part, n_parts, R, S, a.first, n_scored, s0, 0, a.out_logprobs, a.out_top1, a.out_margin, st);
+  }
+  return MTMC_OK;
 }
 
 }  // namespace mtmc

@@ -1,0 +1,484 @@
+// bf16 MFMA GEMMs of the bf16 path.  Both operands are read in the fragment-tiled layouts of
+// frag.h straight into MFMA operand registers: weights stream from HBM as contiguous 1 KiB
+// blocks, activations (small, cache resident) come from L2 in the same block format.
+//
+// Orientation: the weight tile is the MFMA "A" operand (rows = output features n) and the
+// activation tile the "B" operand (columns = tokens m), so a lane ends up holding 4 consecutive
+// output features of one token: D[n = 4 (lane / 16) + r][m = lane % 16].
+#include <algorithm>
+
+#include "bf16_kernels.h"
+#include "device_utils.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+// acc[nb][mb] += W[n tiles nt0 + nb] . X[m tiles mt0 + mb] over k tiles [k0, k1).
+// Tile indices past the end are clamped (their results are never stored).
+template <int NB, int MB>
+__device__ __forceinline__ void wave_gemm(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles,
+                                          int nt0, const h16_t* __restrict__ Xt, int m_tiles,
+                                          int mt0, int k0, int k1, int lane, v4f (&acc)[NB][MB]) {
+  if (k0 >= k1) return;
+  const h16_t* wp[NB];
+  const h16_t* xp[MB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mt0 + mb, m_tiles - 1) * 512;
+  const size_t xstep = (size_t)m_tiles * 512;
+  v8bf wc[NB], xc[MB], wn[NB], xn[MB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) wc[nb] = load_frag(wp[nb] + (size_t)k0 * 512, lane);
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) xc[mb] = load_frag(xp[mb] + (size_t)k0 * xstep, lane);
+  for (int ks = k0; ks < k1; ++ks) {
+    const int kn = min(ks + 1, k1 - 1);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) wn[nb] = load_frag(wp[nb] + (size_t)kn * 512, lane);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) xn[mb] = load_frag(xp[mb] + (size_t)kn * xstep, lane);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wc[nb], xc[mb], acc[nb][mb]);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) wc[nb] = wn[nb];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) xc[mb] = xn[mb];
+  }
+}
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + expf(-g)); }
+
+// ======================================================================================
+// Skinny GEMM (M <= 128 tokens): one workgroup = NB weight row tiles x one K split; its four
+// wavefronts take a quarter of the K range each and are summed through LDS in fixed order.
+// ======================================================================================
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_SAMPLE = 2 };
+
+struct SamplePartial {  // one per (row, weight-tile group)
+  float m, s;           // log-sum-exp state of z / T over the group's vocabulary slice
+  float y;              // best perturbed logit, its vocabulary index, and its z / T
+  int idx;
+  float zt;
+  float pad[3];
+};
+
+template <int NB, int MB, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_skinny(SkinnyArgs a) {
+  __shared__ float red[3][NB * MB * 4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nt0 = blockIdx.x * NB;
+  const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
+  const int ks_lo = blockIdx.y * per_split, ks_hi = min(a.k_tiles, ks_lo + per_split);
+  const int span = max(ks_hi - ks_lo, 0);
+  const int per_wave = (span + 3) / 4;
+  const int k0 = ks_lo + wave * per_wave, k1 = min(ks_hi, k0 + per_wave);
+  v4f acc[NB][MB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
+  wave_gemm<NB, MB>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, 0, k0, k1, lane, acc);
+  if (wave > 0) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave - 1][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[w][(nb * MB + mb) * 4 + r][lane];
+
+  const int col = lane & 15, rq = (lane >> 4) * 4;
+  const int Mpad = a.m_tiles * 16;
+  if (EPI == EPI_PARTIAL) {
+    float* P = a.out_f32 + (size_t)blockIdx.y * Mpad * a.ld_out;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      if (nt0 + nb >= a.n_tiles) continue;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        if (mb >= a.m_tiles) continue;
+        const int m = mb * 16 + col;
+        *reinterpret_cast<v4f*>(P + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = acc[nb][mb];
+      }
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    // weight row tiles alternate gate / up: tile 2j holds gate rows 16j.., tile 2j+1 the up rows
+#pragma unroll
+    for (int nb = 0; nb < NB; nb += 2) {
+      if (nt0 + nb >= a.n_tiles) continue;
+      const int f = ((nt0 + nb) >> 1) * 16 + rq;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        if (mb >= a.m_tiles) continue;
+        const int m = mb * 16 + col;
+        const v4f g = acc[nb][mb], u = acc[nb + 1][mb];
+        uint2 pk;
+        pk.x = pack_h16x2(silu_f(g[0]) * u[0], silu_f(g[1]) * u[1]);
+        pk.y = pack_h16x2(silu_f(g[2]) * u[2], silu_f(g[3]) * u[3]);
+        *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
+      }
+    }
+  } else {  // EPI_SAMPLE: fused log-sum-exp + Gumbel-max over this group's vocabulary slice
+    const SampleCtl ctl = *a.ctl;
+    const int step = *a.d_step;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = mb * 16 + col;
+      Lse lse = lse_empty();
+      float by = -INFINITY, bz = 0.f;
+      int bi = 0x7fffffff;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        if (nt0 + nb >= a.n_tiles) continue;
+        const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
+        uint4 rb = make_uint4(0, 0, 0, 0);
+        if (!ctl.greedy)
+          rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u),
+                             ctl.key0, ctl.key1);
+        const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float zt = ctl.greedy ? acc[nb][mb][r] : acc[nb][mb][r] * ctl.inv_temp;
+          lse_push(lse, zt);
+          const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
+          if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: first maximum wins
+        }
+      }
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+        const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        lse = lse_merge(lse, ol);
+        if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
+      }
+      if (lane < 16 && m < a.M) {
+        SamplePartial* p = reinterpret_cast<SamplePartial*>(a.out_f32) + (size_t)blockIdx.x * a.M + m;
+        p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
+      }
+    }
+  }
+}
+
+template <int NB, int MB>
+static void launch_skinny_t(const SkinnyArgs& a, int epi, int ksplit, hipStream_t st) {
+  const dim3 grid((a.n_tiles + NB - 1) / NB, ksplit);
+  if (epi == EPI_PARTIAL) k_gemm_skinny<NB, MB, EPI_PARTIAL><<<grid, 256, 0, st>>>(a);
+  else if (epi == EPI_SWIGLU) k_gemm_skinny<NB, MB, EPI_SWIGLU><<<grid, 256, 0, st>>>(a);
+  else k_gemm_skinny<NB, MB, EPI_SAMPLE><<<grid, 256, 0, st>>>(a);
+}
+
+int skinny_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
+
+static void launch_skinny(const SkinnyArgs& a, int epi, int ksplit, hipStream_t st) {
+  switch (a.m_tiles) {
+    case 1: launch_skinny_t<4, 1>(a, epi, ksplit, st); break;
+    case 2: launch_skinny_t<4, 2>(a, epi, ksplit, st); break;
+    case 3: case 4: launch_skinny_t<4, 4>(a, epi, ksplit, st); break;
+    default: launch_skinny_t<2, 8>(a, epi, ksplit, st); break;
+  }
+}
+
+void gemm_skinny_partial(float* P, int ldp, const h16_t* Wt, int n_tiles, int k_tiles,
+                         const h16_t* Xt, int M, int m_tiles, int ksplit, hipStream_t st) {
+  SkinnyArgs a{};
+  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
+  a.out_f32 = P; a.ld_out = ldp;
+  launch_skinny(a, EPI_PARTIAL, ksplit, st);
+}
+void gemm_skinny_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
+                        int M, int m_tiles, hipStream_t st) {
+  SkinnyArgs a{};
+  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
+  a.out_bf16 = act;
+  launch_skinny(a, EPI_SWIGLU, 1, st);
+}
+int sample_groups(int n_tiles, int m_tiles) {
+  const int nb = skinny_nb(m_tiles);
+  return (n_tiles + nb - 1) / nb;
+}
+void gemm_skinny_sample(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
+                        int M, int m_tiles, const SampleCtl* ctl, const int* d_step, hipStream_t st) {
+  SkinnyArgs a{};
+  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
+  a.out_f32 = part; a.ctl = ctl; a.d_step = d_step;
+  launch_skinny(a, EPI_SAMPLE, 1, st);
+}
+
+// Merges the per-group partials of one row: token, its log-probability; feeds the next step.
+__global__ __launch_bounds__(256) void k_sample_reduce(const SamplePartial* part, int n_groups, int M,
+                                                       const SampleCtl* ctlp, const int* d_step,
+                                                       int* cur_ids) {
+  __shared__ Lse s_lse[4];
+  __shared__ float s_y[4], s_z[4];
+  __shared__ int s_i[4];
+  const int b = blockIdx.x;
+  Lse lse = lse_empty();
+  float by = -INFINITY, bz = 0.f;
+  int bi = 0x7fffffff;
+  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
+    const SamplePartial p = part[(size_t)g * M + b];
+    lse = lse_merge(lse, Lse{p.m, p.s});
+    if (p.y > by || (p.y == by && p.idx < bi)) { by = p.y; bi = p.idx; bz = p.zt; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+    const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    lse = lse_merge(lse, ol);
+    if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
+  }
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  if (lane == 0) { s_lse[wid] = lse; s_y[wid] = by; s_z[wid] = bz; s_i[wid] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) {
+      lse = lse_merge(lse, s_lse[w]);
+      if (s_y[w] > by || (s_y[w] == by && s_i[w] < bi)) { by = s_y[w]; bi = s_i[w]; bz = s_z[w]; }
+    }
+    const SampleCtl ctl = *ctlp;
+    const int step = *d_step;
+    cur_ids[b] = bi;
+    ctl.out_ids[(size_t)b * ctl.max_new + step] = bi;
+    ctl.out_logprobs[(size_t)b * ctl.max_new + step] = bz - (lse.m + logf(lse.s));
+  }
+}
+void sample_reduce(const float* part, int n_groups, int M, const SampleCtl* ctl, const int* d_step,
+                   int* cur_ids, hipStream_t st) {
+  k_sample_reduce<<<M, 256, 0, st>>>(reinterpret_cast<const SamplePartial*>(part), n_groups, M, ctl,
+                                     d_step, cur_ids);
+}
+
+// ======================================================================================
+// Large GEMM (prefill / scoring): workgroup tile 128 features x 128 tokens, four wavefronts
+// in a 2 x 2 arrangement of 64 x 64 sub-tiles, full K per workgroup.
+// ======================================================================================
+enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_large(LargeArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nt0 = blockIdx.x * 8 + (wave & 1) * 4;
+  const int mt0 = blockIdx.y * 8 + (wave >> 1) * 4;
+  if (nt0 >= a.n_tiles || mt0 >= a.m_tiles) return;
+  v4f acc[4][4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
+  wave_gemm<4, 4>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, 0, a.k_tiles, lane, acc);
+  const int col = lane & 15, rq = (lane >> 4) * 4;
+  const int Mpad = a.m_tiles * 16;
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    if (nt0 + nb >= a.n_tiles) continue;
+    if (EPI == LEPI_SWIGLU && (nb & 1)) continue;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      const int m = (mt0 + mb) * 16 + col;
+      if (m >= a.M) continue;
+      if (EPI == LEPI_SWIGLU) {
+        const int f = ((nt0 + nb) >> 1) * 16 + rq;
+        const v4f g = acc[nb][mb], u = acc[nb + 1][mb];
+        uint2 pk;
+        pk.x = pack_h16x2(silu_f(g[0]) * u[0], silu_f(g[1]) * u[1]);
+        pk.y = pack_h16x2(silu_f(g[2]) * u[2], silu_f(g[3]) * u[3]);
+        *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
+      } else {
+        const int n = (nt0 + nb) * 16 + rq;
+        if (n >= a.N) continue;
+        v4f* c = reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + n);
+        if (EPI == LEPI_ADD) *c = *c + acc[nb][mb];
+        else *c = acc[nb][mb];
+      }
+    }
+  }
+}
+
+static void launch_large(const LargeArgs& a, int epi, hipStream_t st) {
+  const dim3 grid((a.n_tiles + 7) / 8, (a.m_tiles + 7) / 8);
+  if (epi == LEPI_STORE) k_gemm_large<LEPI_STORE><<<grid, 256, 0, st>>>(a);
+  else if (epi == LEPI_ADD) k_gemm_large<LEPI_ADD><<<grid, 256, 0, st>>>(a);
+  else k_gemm_large<LEPI_SWIGLU><<<grid, 256, 0, st>>>(a);
+}
+
+void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
+                    int k_tiles, const h16_t* Xt, int M, int m_tiles, hipStream_t st) {
+  LargeArgs a{};
+  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M; a.N = N;
+  a.out_f32 = C; a.ld_out = ldc;
+  launch_large(a, accumulate ? LEPI_ADD : LEPI_STORE, st);
+}
+void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
+                       int M, int m_tiles, hipStream_t st) {
+  LargeArgs a{};
+  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
+  a.out_bf16 = act;
+  launch_large(a, LEPI_SWIGLU, st);
+}
+
+// ======================================================================================
+// Scoring LM head: logits are never stored.  A workgroup owns 128 rows and a range of
+// vocabulary tiles; every lane keeps running (log-sum-exp, top-2, target logit) for its rows.
+// ======================================================================================
+struct ScorePartial {
+  float m, s, v1;
+  int i1;
+  float v2, zt;
+  float pad[2];
+};
+
+__global__ __launch_bounds__(256) void k_lmhead_score(ScoreHeadArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave & 1;
+  const int mt0 = blockIdx.y * 8 + (wave >> 1) * 4;
+  if (mt0 >= a.m_tiles) return;
+  const int col = lane & 15, rq = (lane >> 4) * 4;
+  Lse lse[4];
+  Top2 top[4];
+  float zt[4];
+  int target[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb) {
+    lse[mb] = lse_empty();
+    top[mb] = top2_empty();
+    zt[mb] = -INFINITY;
+    const int m = (mt0 + mb) * 16 + col;
+    target[mb] = (m < a.M) ? a.targets[m] : -1;
+  }
+  const int g_lo = blockIdx.x * a.groups_per_block, g_hi = min(a.n_groups, g_lo + a.groups_per_block);
+  for (int g = g_lo; g < g_hi; ++g) {
+    const int nt0 = g * 8 + wn * 4;
+    if (nt0 >= a.n_tiles) break;
+    v4f acc[4][4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
+    wave_gemm<4, 4>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, 0, a.k_tiles, lane, acc);
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      if (nt0 + nb >= a.n_tiles) continue;
+      const int v0 = (nt0 + nb) * 16 + rq;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float z = acc[nb][mb][r];
+          lse_push(lse[mb], z);
+          top2_push(top[mb], z, v0 + r);
+          if (v0 + r == target[mb]) zt[mb] = z;
+        }
+    }
+  }
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const Lse ol = {__shfl_xor(lse[mb].m, o, 64), __shfl_xor(lse[mb].s, o, 64)};
+      const Top2 ot = {__shfl_xor(top[mb].v1, o, 64), __shfl_xor(top[mb].i1, o, 64),
+                       __shfl_xor(top[mb].v2, o, 64)};
+      lse[mb] = lse_merge(lse[mb], ol);
+      top[mb] = top2_merge(top[mb], ot);
+      zt[mb] = fmaxf(zt[mb], __shfl_xor(zt[mb], o, 64));
+    }
+    const int m = (mt0 + mb) * 16 + col;
+    if (lane < 16 && m < a.M) {
+      ScorePartial* p = reinterpret_cast<ScorePartial*>(a.part) + ((size_t)(blockIdx.x * 2 + wn)) * a.M + m;
+      p->m = lse[mb].m; p->s = lse[mb].s; p->v1 = top[mb].v1; p->i1 = top[mb].i1; p->v2 = top[mb].v2;
+      p->zt = zt[mb];
+    }
+  }
+}
+
+int score_head_blocks(int n_tiles, int* groups_per_block) {
+  const int n_groups = (n_tiles + 7) / 8;           // 128 vocabulary entries per group
+  const int gpb = std::max(1, std::min(n_groups, 16));
+  *groups_per_block = gpb;
+  return (n_groups + gpb - 1) / gpb;
+}
+
+void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
+                  int m_tiles, const int* targets, hipStream_t st) {
+  ScoreHeadArgs a{};
+  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
+  a.targets = targets; a.part = part;
+  a.n_groups = (n_tiles + 7) / 8;
+  const int blocks = score_head_blocks(n_tiles, &a.groups_per_block);
+  k_lmhead_score<<<dim3(blocks, (m_tiles + 7) / 8), 256, 0, st>>>(a);
+}
+
+// Row r of the chunk is position i = first + (row0 + r) % n_scored of sequence
+// n = seq0 + (row0 + r) / n_scored; targets[r] = seqs[n, i + 1] (clamped, flagging bad ids).
+__global__ void k_score_targets(int* targets, const int* seqs, int R, int S, int first, int n_scored,
+                                int seq0, int row0, int vocab, int* err_flag) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= R) return;
+  const int n = seq0 + (row0 + r) / n_scored, i = first + (row0 + r) % n_scored;
+  int t = seqs[(size_t)n * S + i + 1];
+  if (t < 0 || t >= vocab) {
+    atomicOr(err_flag, 1);
+    t = t < 0 ? 0 : vocab - 1;
+  }
+  targets[r] = t;
+}
+void score_targets(int* targets, const int* seqs, int R, int S, int first, int n_scored, int seq0,
+                   int row0, int vocab, int* err_flag, hipStream_t st) {
+  k_score_targets<<<(R + 255) / 256, 256, 0, st>>>(targets, seqs, R, S, first, n_scored, seq0, row0,
+                                                  vocab, err_flag);
+}
+
+__global__ __launch_bounds__(64) void k_score_reduce(const ScorePartial* part, int n_parts, int R, int S,
+                                                     int first, int n_scored, int seq0, int row0,
+                                                     float* out_logprobs, int* out_top1,
+                                                     float* out_margin) {
+  const int r = blockIdx.x;
+  const int lane = threadIdx.x;
+  Lse lse = lse_empty();
+  Top2 top = top2_empty();
+  float zt = -INFINITY;
+  for (int g = lane; g < n_parts; g += 64) {
+    const ScorePartial p = part[(size_t)g * R + r];
+    lse = lse_merge(lse, Lse{p.m, p.s});
+    top = top2_merge(top, Top2{p.v1, p.i1, p.v2});
+    zt = fmaxf(zt, p.zt);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+    const Top2 ot = {__shfl_xor(top.v1, o, 64), __shfl_xor(top.i1, o, 64), __shfl_xor(top.v2, o, 64)};
+    lse = lse_merge(lse, ol);
+    top = top2_merge(top, ot);
+    zt = fmaxf(zt, __shfl_xor(zt, o, 64));
+  }
+  if (lane == 0) {
+    const int n = seq0 + (row0 + r) / n_scored, i = first + (row0 + r) % n_scored;
+    const size_t slot = (size_t)n * (S - 1) + i;
+    out_logprobs[slot] = zt - (lse.m + logf(lse.s));
+    if (out_top1) out_top1[slot] = top.i1;
+    if (out_margin) out_margin[slot] = top.v1 - top.v2;
+  }
+}
+void score_reduce(const float* part, int n_parts, int R, int S, int first, int n_scored, int seq0,
+                  int row0, float* out_logprobs, int* out_top1, float* out_margin, hipStream_t st) {
+  k_score_reduce<<<R, 64, 0, st>>>(reinterpret_cast<const ScorePartial*>(part), n_parts, R, S, first,
+                                   n_scored, seq0, row0, out_logprobs, out_top1, out_margin);
+}
+
+}  // namespace bf16
+}  // namespace mtmc

@@ -1,0 +1,57 @@
+"""Shared parity checks (GPU library vs CPU oracle) used by the gpu-marked tests."""
+import numpy as np
+
+import mtmc_oracle as oracle
+from helpers import oracle_model
+from paper_2511_20100_amd import inputs
+
+LOGP_TOL_BF16 = 1e-2   # per-token log-prob, bf16 GPU path vs fp32 oracle
+MARGIN_GATE = 0.05     # ids are compared where the oracle's decision margin exceeds this
+
+
+def check_rollout_by_replay(handle, w, prompts, n_samples, max_new, temperature, seed, *, max_positions,
+                            seq_offset=0, rows=None, tol=LOGP_TOL_BF16, label=""):
+    """Runs mtmc_rollout, then has the oracle teacher-force the GPU's own sequences and redo every
+    sampling decision with the same noise.  Ids must agree wherever the oracle's perturbed margin
+    exceeds MARGIN_GATE, log-probs everywhere within tol.  Returns a small report dict."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    ids, lp = mtmc.mtmc_rollout(handle, torch.from_numpy(prompts).cuda(), n_samples, max_new, temperature, seed,
+                                seq_offset=seq_offset)
+    mtmc.mtmc_poll_errors(handle)
+    ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
+    assert ids.min() >= 0 and ids.max() < w.cfg.vocab
+    model = oracle_model(w, max_positions)
+    B = prompts.shape[0] * n_samples
+    rows = range(B) if rows is None else rows
+    gated = total = 0
+    worst = 0.0
+    for b in rows:
+        tok, ref_lp, margin = oracle.replay(model, prompts[b // n_samples], ids[b], temperature, seed, seq_offset + b)
+        gate = margin > MARGIN_GATE
+        bad = np.nonzero(gate & (tok != ids[b]))[0]
+        assert bad.size == 0, f"{label} row {b}: sampled id differs from the oracle at steps {bad[:8]} " \
+                              f"(margins {margin[bad[:8]]})"
+        err = np.abs(ref_lp - lp[b]).max()
+        worst = max(worst, float(err))
+        assert err <= tol, f"{label} row {b}: log-prob error {err}"
+        gated += int(gate.sum()); total += gate.size
+    return {"ids": ids, "logprobs": lp, "compared": gated, "steps": total, "max_logp_err": worst}
+
+
+def check_score(handle, w, seqs, prompt_len, *, max_positions, rows=None, tol=LOGP_TOL_BF16, label=""):
+    import torch
+    from paper_2511_20100_amd import mtmc
+    s, top1, margin = mtmc.mtmc_score(handle, torch.from_numpy(seqs).cuda(), prompt_len, want_top1=True)
+    mtmc.mtmc_poll_errors(handle)
+    s, top1, margin = s.cpu().numpy(), top1.cpu().numpy(), margin.cpu().numpy()
+    model = oracle_model(w, max_positions)
+    rows = list(range(seqs.shape[0])) if rows is None else list(rows)
+    ref_s, ref_top1, ref_margin = oracle.score(model, seqs[rows], prompt_len)
+    err = np.abs(s[rows] - ref_s).max()
+    assert err <= tol, f"{label}: score log-prob error {err}"
+    assert np.all(s[:, :prompt_len - 1] == 0.0) and np.all(top1[:, :prompt_len - 1] == 0)
+    gate = ref_margin > MARGIN_GATE
+    assert np.array_equal(top1[rows][gate], ref_top1[gate]), f"{label}: top-1 ids differ above the margin gate"
+    assert np.abs(margin[rows] - ref_margin).max() <= 2 * tol
+    return {"logprobs": s, "max_logp_err": float(err), "compared": int(gate.sum()), "positions": int(gate.size)}

@@ -1,0 +1,85 @@
+"""GPU parity of the bf16 path on small models (head_dim 128): rollout verified by replay on the
+oracle, scoring against the oracle, decode == score consistency, determinism."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from parity import LOGP_TOL_BF16, check_rollout_by_replay, check_score
+from paper_2511_20100_amd import inputs
+
+# (config, std, n_prompts, prompt_len, n_samples, max_new, temperature)
+SMALL = inputs.ModelConfig(2, 256, 4, 2, 128, 688, 4096, dtype="bf16")      # G = 2, ragged FFN width
+GQA6 = inputs.ModelConfig(2, 384, 6, 1, 128, 1024, 2048, dtype="bf16")      # G = 6 like the 1.5 B policy
+GQA7 = inputs.ModelConfig(1, 512, 7, 1, 128, 1536, 2064, dtype="bf16")      # G = 7 like the 7 B policy
+CASES = [
+    ("small-b8", SMALL, 0.02, 4, 32, 2, 32, 1.0),
+    ("small-ragged", SMALL, 0.05, 3, 37, 3, 21, 0.8),
+    ("gqa6-b24", GQA6, 0.05, 3, 50, 8, 40, 1.0),
+    ("gqa7-b64", GQA7, 0.05, 8, 20, 8, 20, 1.0),
+    ("gqa6-b128", GQA6, 0.04, 16, 16, 8, 12, 1.0),
+    ("gqa6-two-groups", GQA6, 0.04, 18, 9, 8, 6, 1.0),
+    ("small-greedy", SMALL, 0.05, 2, 16, 1, 10, 0.0),
+    ("small-one-token", SMALL, 0.05, 1, 1, 2, 4, 1.0),
+]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2511_20100_amd import mtmc
+    return mtmc
+
+
+@pytest.mark.parametrize("name,cfg,std,n_prompts,plen,n_samples,max_new,temp", CASES, ids=[c[0] for c in CASES])
+def test_rollout_and_score(lib, name, cfg, std, n_prompts, plen, n_samples, max_new, temp):
+    w = inputs.make_weights(cfg, seed=0, std=std)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
+    try:
+        prompts = inputs.make_prompts(n_prompts, plen, cfg.vocab, seed=2)
+        rep = check_rollout_by_replay(handle, w, prompts, n_samples, max_new, temp, 1, max_positions=256, label=name)
+        print(name, "rollout: compared", rep["compared"], "of", rep["steps"], "max log-prob err", rep["max_logp_err"])
+        assert rep["compared"] > 0.5 * rep["steps"]
+        seqs = np.concatenate([np.repeat(prompts, n_samples, axis=0), rep["ids"]], axis=1)
+        sc = check_score(handle, w, seqs, plen, max_positions=256, label=name)
+        print(name, "score: max log-prob err", sc["max_logp_err"], "top-1 compared", sc["compared"], "of", sc["positions"])
+        if temp == 1.0:  # the sampled token's log-prob is its Eq. 2 factor
+            assert np.abs(sc["logprobs"][:, plen - 1:] - rep["logprobs"]).max() <= LOGP_TOL_BF16
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_determinism_and_offsets(lib):
+    import torch
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
+    try:
+        prompts = torch.from_numpy(inputs.make_prompts(3, 20, cfg.vocab, seed=5)).cuda()
+        a = lib.mtmc_rollout(handle, prompts, 4, 12, 1.0, 7)
+        b = lib.mtmc_rollout(handle, prompts, 4, 12, 1.0, 7)
+        c = lib.mtmc_rollout(handle, prompts, 4, 12, 1.0, 8)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        assert not torch.equal(a[0], c[0])
+        s1 = lib.mtmc_score(handle, torch.cat([prompts.repeat_interleave(4, 0), a[0]], 1).contiguous(), 20)
+        s2 = lib.mtmc_score(handle, torch.cat([prompts.repeat_interleave(4, 0), a[0]], 1).contiguous(), 20)
+        torch.cuda.synchronize()
+        assert torch.equal(s1, s2)
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_score_long_sequences_and_chunks(lib):
+    """Sequences longer than one attention block, several sequences per chunk and several chunks."""
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=3, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 4096), w.blob())
+    try:
+        seqs = inputs.make_sequences(40, 333, cfg.vocab, seed=9)     # 40 x 333 tokens: 2 chunks of 24 + 16
+        sc = check_score(handle, w, seqs, 100, max_positions=4096, rows=[0, 23, 24, 39], label="long")
+        print("long score: max log-prob err", sc["max_logp_err"])
+        seqs = inputs.make_sequences(2, 1500, cfg.vocab, seed=10)
+        sc = check_score(handle, w, seqs, 1400, max_positions=4096, rows=[1], label="very-long")
+        print("very long score: max log-prob err", sc["max_logp_err"])
+    finally:
+        lib.mtmc_weights_destroy(handle)
