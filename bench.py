@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Throughput of the policy rollout + scoring path on one MI355X.
+
+One step = one pass of the whole path over one batch: mtmc_rollout (prefill of the prompts, then
+max_new Gumbel-max decode steps for every sequence) followed by mtmc_score of the sequences it
+produced.  The headline value is generated tokens per second over the whole step; inputs
+(weights, prompts) are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|tiny|7b] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2511_20100_amd import inputs  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
+
+WORKLOADS = {
+    # name: (config, n_prompts, prompt_len, n_samples, max_new)
+    "tiny": (inputs.TINY, 4, 32, 2, 32),
+    "1p5b": (inputs.POLICY_1P5B, 8, 512, 8, 1024),
+    "7b": (inputs.POLICY_7B, 16, 1024, 8, 2048),
+}
+
+
+def decode_bytes_per_step(cfg, n_prompts, prompt_len, n_samples, max_new):
+    """Algorithmic HBM bytes of one average decode step: every weight matrix once (2 bytes per
+    parameter, embedding table excluded) plus the KV cache of the context, with the pages of a
+    prompt read once for all its samples."""
+    hd = cfg.head_dim
+    q, kv = cfg.n_q_heads * hd, cfg.n_kv_heads * hd
+    layer = cfg.d_model * (q + 2 * kv) + q * cfg.d_model + 3 * cfg.d_model * cfg.d_ffn
+    weights = 2 * (cfg.n_layers * layer + cfg.vocab * cfg.d_model)
+    kv_per_token = cfg.n_layers * 2 * kv * 2
+    B = n_prompts * n_samples
+    avg_new = (max_new - 1) / 2.0
+    kv_bytes = (n_prompts * prompt_len + B * avg_new) * kv_per_token
+    return weights + kv_bytes, weights, kv_bytes
+
+
+def forward_flops(cfg, n_seqs, seq_len, scored_per_seq):
+    hd = cfg.head_dim
+    q, kv = cfg.n_q_heads * hd, cfg.n_kv_heads * hd
+    layer = cfg.d_model * (q + 2 * kv) + q * cfg.d_model + 3 * cfg.d_model * cfg.d_ffn
+    gemm = 2.0 * cfg.n_layers * layer * n_seqs * seq_len
+    attn = 2.0 * seq_len * seq_len * q * cfg.n_layers * n_seqs      # causal: half of 4 S^2 q
+    head = 2.0 * cfg.d_model * cfg.vocab * n_seqs * scored_per_seq
+    return gemm + attn + head
+
+
+def cpu_baseline(weights, cfg, prompts, max_positions):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import mtmc_oracle as oracle
+    model = oracle.Model(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads,
+                         n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab,
+                         rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, w=weights.f32, max_positions=max_positions)
+    if cfg.n_layers * cfg.d_model > 10000:
+        n_p, n_s, n_new = 1, 2, 8
+    else:
+        n_p, n_s, n_new = prompts.shape[0], 2, 32
+    t0 = time.perf_counter()
+    ids, _, _ = oracle.rollout(model, prompts[:n_p], n_s, n_new, 1.0, seed=1)
+    seqs = np.concatenate([np.repeat(prompts[:n_p], n_s, axis=0), ids], axis=1)[:1]
+    oracle.score(model, seqs, prompt_len=prompts.shape[1])
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": n_p * n_s * n_new / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n_p} prompt(s) of {prompts.shape[1]} tokens x {n_s} samples x {n_new} new tokens "
+                      f"(cached decode), then scoring of 1 resulting sequence; {dt:.1f} s; subset, not extrapolated"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="1p5b", choices=sorted(WORKLOADS))
+    ap.add_argument("--max-new", type=int, default=None, help="override the number of new tokens")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-score", action="store_true", help="time the rollout alone")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by prompt with no collectives; "
+              "run one process per GPU on disjoint prompts). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2511_20100_amd import mtmc
+
+    cfg, n_prompts, prompt_len, n_samples, max_new = WORKLOADS[args.workload]
+    if args.max_new:
+        max_new = args.max_new
+    B = n_prompts * n_samples
+    seq_len = prompt_len + max_new
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.perf_counter()
+    weights = inputs.make_weights(cfg, seed=0)
+    blob = torch.from_numpy(weights.blob())
+    handle = mtmc.mtmc_weights_create(mtmc.make_config(cfg, seq_len), blob)
+    del blob
+    prompts_np = inputs.make_prompts(n_prompts, prompt_len, cfg.vocab, seed=2)
+    prompts = torch.from_numpy(prompts_np).to(dev)
+    ws_r = torch.empty(mtmc.mtmc_rollout_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new),
+                       dtype=torch.uint8, device=dev)
+    ws_s = torch.empty(mtmc.mtmc_score_workspace_bytes(handle, B, seq_len), dtype=torch.uint8, device=dev)
+    out_ids = torch.empty((B, max_new), dtype=torch.int32, device=dev)
+    out_lp = torch.empty((B, max_new), dtype=torch.float32, device=dev)
+    seqs = torch.empty((B, seq_len), dtype=torch.int32, device=dev)
+    seqs[:, :prompt_len] = prompts.repeat_interleave(n_samples, dim=0)
+    score_lp = torch.empty((B, seq_len - 1), dtype=torch.float32, device=dev)
+    setup_s = time.perf_counter() - t0
+    stream = torch.cuda.current_stream()
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def step(seed):
+        ev[0].record(stream)
+        mtmc.mtmc_rollout(handle, prompts, n_samples, max_new, 1.0, seed, workspace=ws_r, out_ids=out_ids,
+                          out_logprobs=out_lp)
+        ev[1].record(stream)
+        if not args.no_score:
+            seqs[:, prompt_len:] = out_ids
+            mtmc.mtmc_score(handle, seqs, prompt_len, workspace=ws_s, out_logprobs=score_lp)
+        ev[2].record(stream)
+
+    for i in range(args.warmup):
+        step(100 + i)
+    torch.cuda.synchronize()
+    rollout_ms, score_ms = [], []
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        step(1 + i)
+        ev[2].synchronize()  # the events are reused by the next step
+        rollout_ms.append(ev[0].elapsed_time(ev[1]))
+        score_ms.append(ev[1].elapsed_time(ev[2]))
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t_begin
+    mtmc.mtmc_poll_errors(handle)
+
+    ms_per_step = 1e3 * total_s / args.steps
+    new_tokens = B * max_new
+    r_ms = float(np.mean(rollout_ms))
+    s_ms = float(np.mean(score_ms))
+    # decode roofline: algorithmic bytes of an average decode step over the measured step time.  The
+    # rollout time is prefill + (max_new - 1) decode steps; prefill is charged to the decode steps.
+    step_bytes, w_bytes, kv_bytes = decode_bytes_per_step(cfg, n_prompts, prompt_len, n_samples, max_new)
+    decode_ms = r_ms / max(1, max_new - 1)
+    achieved_gbs = step_bytes / (decode_ms * 1e-3) / 1e9
+    result = {
+        "metric": "rollout tokens/sec @1.5B-class bs64 bf16; decode HBM GB/s + scoring MFMA % peak",
+        "value": new_tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 weights, f16 MFMA operands and KV cache, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {cfg.n_layers} layers d{cfg.d_model} Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} "
+                               f"F{cfg.d_ffn} V{cfg.vocab}; {n_prompts} prompts x {n_samples} samples = batch {B}, "
+                               f"prompt {prompt_len}, {max_new} new tokens at T=1; then scoring of the {B} x {seq_len} sequences",
+                   "step": "mtmc_rollout + mtmc_score" if not args.no_score else "mtmc_rollout"},
+        "rollout_tokens_per_s": new_tokens / (r_ms * 1e-3), "rollout_ms": r_ms,
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode step (all kernels of one token step; prefill time included)",
+                     "bytes_per_launch": step_bytes, "ms_per_launch": decode_ms},
+        "setup_s": setup_s,
+    }
+    if not args.no_score:
+        flops = forward_flops(cfg, B, seq_len, max_new)
+        result["score_tokens_per_s"] = B * seq_len / (s_ms * 1e-3)
+        result["score_ms"] = s_ms
+        result["score_mfma"] = {"bound": "mfma", "achieved": flops / (s_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": flops / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(weights, cfg, prompts_np, seq_len)
+    mtmc.mtmc_weights_destroy(handle)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

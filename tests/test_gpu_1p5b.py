@@ -1,0 +1,86 @@
+"""GPU parity at the 1.5 B-class workload, in the launch configuration the benchmark times:
+28 layers, d 1536, 12/2 heads, F 8960, V 151936, bf16 weights; 8 prompts x 8 samples, prompt 512,
+1024 new tokens at T = 1.  The oracle cannot run the whole job, so it teacher-forces sampled
+rows of the GPU's output: one sequence over all 1024 steps and a second one over its first
+steps, redoing every sampling decision; the same oracle logits check mtmc_score."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import mtmc_oracle as oracle
+from helpers import oracle_model
+from parity import LOGP_TOL_BF16, MARGIN_GATE
+from paper_2511_20100_amd import inputs
+
+CFG = inputs.POLICY_1P5B
+N_PROMPTS, PROMPT_LEN, N_SAMPLES, MAX_NEW = 8, 512, 8, 1024
+
+
+@pytest.fixture(scope="module")
+def run():
+    import torch
+    from paper_2511_20100_amd import mtmc
+    w = inputs.make_weights(CFG, seed=0)
+    handle = mtmc.mtmc_weights_create(mtmc.make_config(CFG, PROMPT_LEN + MAX_NEW), w.blob())
+    prompts = inputs.make_prompts(N_PROMPTS, PROMPT_LEN, CFG.vocab, seed=2)
+    dprompts = torch.from_numpy(prompts).cuda()
+    ids, lp = mtmc.mtmc_rollout(handle, dprompts, N_SAMPLES, MAX_NEW, 1.0, 1)
+    ids2, lp2 = mtmc.mtmc_rollout(handle, dprompts, N_SAMPLES, MAX_NEW, 1.0, 1)
+    seqs = torch.cat([dprompts.repeat_interleave(N_SAMPLES, 0), ids], 1).contiguous()
+    score, top1, margin = mtmc.mtmc_score(handle, seqs, PROMPT_LEN, want_top1=True)
+    mtmc.mtmc_poll_errors(handle)
+    out = dict(w=w, prompts=prompts, ids=ids.cpu().numpy(), lp=lp.cpu().numpy(), ids2=ids2.cpu().numpy(),
+               lp2=lp2.cpu().numpy(), score=score.cpu().numpy(), top1=top1.cpu().numpy(), margin=margin.cpu().numpy())
+    mtmc.mtmc_weights_destroy(handle)
+    return out
+
+
+def test_run_to_run_determinism(run):
+    assert np.array_equal(run["ids"], run["ids2"]) and np.array_equal(run["lp"], run["lp2"])
+    assert run["ids"].min() >= 0 and run["ids"].max() < CFG.vocab
+    # samples of one prompt are distinct draws
+    assert not np.array_equal(run["ids"][0], run["ids"][1])
+    # near-uniform policy at these weights: log-probs near -ln V
+    assert abs(run["lp"].mean() + np.log(CFG.vocab)) < 0.5
+
+
+def test_decode_equals_score_everywhere(run):
+    """Property that holds at any size: at T = 1 the log-prob returned with a sampled token is the
+    Eq. 2 factor that the scoring pass returns for it (two different kernel paths)."""
+    d = np.abs(run["score"][:, PROMPT_LEN - 1:] - run["lp"])
+    print("decode vs score: max", d.max(), "mean", d.mean())
+    assert d.max() <= LOGP_TOL_BF16
+    assert np.all(run["score"][:, :PROMPT_LEN - 1] == 0.0)
+
+
+@pytest.mark.parametrize("row,steps", [(0, MAX_NEW), (37, 48)])
+def test_rows_against_the_oracle(run, row, steps):
+    model = oracle_model(run["w"], PROMPT_LEN + MAX_NEW)
+    prompt = run["prompts"][row // N_SAMPLES]
+    given = run["ids"][row, :steps]
+    tok, ref_lp, mar = oracle.replay(model, prompt, given, 1.0, 1, row)
+    gate = mar > MARGIN_GATE
+    bad = np.nonzero(gate & (tok != given))[0]
+    err_r = np.abs(ref_lp - run["lp"][row, :steps])
+    err_s = np.abs(ref_lp - run["score"][row, PROMPT_LEN - 1:PROMPT_LEN - 1 + steps])
+    print(f"row {row}: {int(gate.sum())}/{steps} decisions compared, rollout log-prob err max {err_r.max():.2e} "
+          f"rms {np.sqrt((err_r ** 2).mean()):.2e}; score err max {err_s.max():.2e}")
+    assert bad.size == 0, (bad[:8], mar[bad[:8]])
+    assert gate.mean() > 0.8
+    assert err_r.max() <= LOGP_TOL_BF16
+    assert err_s.max() <= LOGP_TOL_BF16
+
+
+def test_score_top1_against_the_oracle(run):
+    """Teacher-forced arg-max ids on a truncated sequence (causality makes the prefix exact)."""
+    model = oracle_model(run["w"], PROMPT_LEN + MAX_NEW)
+    row, n = 21, 560
+    seq = np.concatenate([run["prompts"][row // N_SAMPLES], run["ids"][row]])[:n]
+    ref_s, ref_top1, ref_margin = oracle.score(model, seq[None, :], prompt_len=PROMPT_LEN)
+    sl = slice(PROMPT_LEN - 1, n - 1)
+    gate = ref_margin[0, sl] > MARGIN_GATE
+    print(f"top-1: {int(gate.sum())} of {gate.size} positions above the margin gate")
+    assert np.array_equal(run["top1"][row, sl][gate], ref_top1[0, sl][gate])
+    assert np.abs(run["score"][row, sl] - ref_s[0, sl]).max() <= LOGP_TOL_BF16
+    assert np.abs(run["margin"][row, sl] - ref_margin[0, sl]).max() <= 2 * LOGP_TOL_BF16
