@@ -128,6 +128,16 @@ int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_seqs, int32
  */
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);
 
+/*
+ * Tuning switches.  Results never depend on them (same kernels, same order).
+ *   MTMC_OPT_HIP_GRAPH (default 1): mtmc_rollout captures one decode step into a HIP graph and
+ *   replays it for every token.  Instantiated graphs are cached inside `w`, keyed by workspace
+ *   address and shape; replacing a cached graph synchronises `stream` once.  When `stream` is
+ *   itself being captured the steps are launched directly.
+ */
+#define MTMC_OPT_HIP_GRAPH 1
+int mtmc_set_option(mtmc_weights* w, int option, int value);
+
 /* Message of the last failing call on this thread; valid until the next library call. */
 const char* mtmc_last_error(void);
 

@@ -87,6 +87,8 @@ extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, siz
   w->cfg = *cfg;
   w->storage = nullptr;
   w->aux = nullptr;
+  w->opt_hip_graph = 1;
+  w->graphs = nullptr;
   int rc = hipGetDevice(&w->device) == hipSuccess ? MTMC_OK : MTMC_EHIP;
   if (rc == MTMC_OK) rc = build_aux(w, st);
   if (rc == MTMC_OK)
@@ -106,9 +108,17 @@ extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, siz
 
 extern "C" void mtmc_weights_destroy(mtmc_weights* w) {
   if (!w) return;
+  destroy_graph_cache(w);
   if (w->storage) (void)hipFree(w->storage);
   if (w->aux) (void)hipFree(w->aux);
   delete w;
+}
+
+extern "C" int mtmc_set_option(mtmc_weights* w, int option, int value) {
+  MTMC_REQUIRE(w != nullptr, "weights is NULL");
+  MTMC_REQUIRE(option == MTMC_OPT_HIP_GRAPH, "unknown option");
+  w->opt_hip_graph = value ? 1 : 0;
+  return MTMC_OK;
 }
 
 extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {

@@ -54,6 +54,8 @@ struct KvPool {
   int max_pages;
 };
 
+struct GraphCache;  // engine_bf16.hip
+
 struct LayerWeights {
   const float* attn_norm;
   const float* ffn_norm;
@@ -79,4 +81,6 @@ struct mtmc_weights {
   const float* rope_sin;
   int* err_flag;        // device int, non-zero once a bad token id was seen
   int d_ffn_pad;        // F rounded up to the K-tile of the bf16 kernels (== F for fp32)
+  int opt_hip_graph;    // replay decode steps as a captured HIP graph (default 1)
+  mtmc::GraphCache* graphs;  // instantiated decode-step graphs, keyed by workspace and shape
 };

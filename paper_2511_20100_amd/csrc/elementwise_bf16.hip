@@ -80,6 +80,7 @@ __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int 
   float ss = 0.f;
   for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
     v4f a = *reinterpret_cast<const v4f*>(hr + k), b = *reinterpret_cast<const v4f*>(hr + k + 4);
+#pragma unroll 8
     for (int s = 0; s < n_split; ++s) {
       const float* pr = P + ((size_t)s * Mpad_p + m) * ldp + k;
       a = a + *reinterpret_cast<const v4f*>(pr);
@@ -129,6 +130,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(h16_t* q, const float* P,
   for (int e = threadIdx.x; e < (Hq + Hkv) * HALF; e += blockDim.x) {
     const int head = e / HALF, i = e % HALF;
     float a = 0.f, b = 0.f;
+#pragma unroll 8
     for (int s = 0; s < n_split; ++s) {
       const float* pr = P + ((size_t)s * Mpad_p + t) * ldp + (size_t)head * HD;
       a += pr[i];
@@ -151,6 +153,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(h16_t* q, const float* P,
   for (int e = threadIdx.x; e < Hkv * HD; e += blockDim.x) {
     const int g = e / HD, c = e % HD;
     float v = 0.f;
+#pragma unroll 8
     for (int s = 0; s < n_split; ++s) v += P[((size_t)s * Mpad_p + t) * ldp + (size_t)(Hq + Hkv) * HD + e];
     h16_t* vp = kv + ((((size_t)layer * 2 + 1) * pool.n_pages + page) * pool.n_kv_heads + g) * page_elems;
     vp[c * kPageTokens + slot] = f32_to_h16(v);

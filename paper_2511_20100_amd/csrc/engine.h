@@ -123,6 +123,7 @@ int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob,
 int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
                  const SampleArgs& sa, hipStream_t st);
 int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hipStream_t st);
+void destroy_graph_cache(mtmc_weights* w);
 void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& c);
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& c);
 

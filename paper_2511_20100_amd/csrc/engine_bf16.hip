@@ -2,6 +2,7 @@
 // Weights and KV cache are bf16; the residual stream, norms, softmax and all accumulators fp32.
 #include <algorithm>
 #include <array>
+#include <mutex>
 
 #include "bf16_kernels.h"
 #include "engine.h"
@@ -9,7 +10,27 @@
 
 namespace mtmc {
 
+// Instantiated decode-step graphs.  A graph bakes in the workspace pointers and the group
+// shape; everything that changes between calls (seed, temperature, output pointers, step
+// counter) lives in device memory that the kernels read.
+struct GraphCache {
+  struct Entry {
+    const void* workspace;
+    int B, prompt_len, n_samples, max_new;
+    hipGraphExec_t exec;
+  };
+  std::mutex mu;
+  std::vector<Entry> entries;
+  hipStream_t capture_stream = nullptr;  // never runs work: launches on it are only recorded
+};
 
+void destroy_graph_cache(mtmc_weights* w) {
+  if (!w->graphs) return;
+  for (auto& e : w->graphs->entries) (void)hipGraphExecDestroy(e.exec);
+  if (w->graphs->capture_stream) (void)hipStreamDestroy(w->graphs->capture_stream);
+  delete w->graphs;
+  w->graphs = nullptr;
+}
 
 namespace {
 inline int tiles16(int n) { return (n + 15) / 16; }
@@ -237,6 +258,56 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
   }
 }
 
+// Returns in *out the instantiated graph of one decode step for this workspace and shape, capturing
+// it on a private stream if it is not cached (or nullptr when graphs are off or `st` is already capturing).
+template <class Step>
+int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, Step&& step,
+                 hipGraphExec_t* out) {
+  *out = nullptr;
+  if (!w->opt_hip_graph) return MTMC_OK;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return MTMC_OK;
+  }
+  mtmc_weights* mw = const_cast<mtmc_weights*>(w);
+  if (!mw->graphs) mw->graphs = new GraphCache();
+  GraphCache& gc = *mw->graphs;
+  std::lock_guard<std::mutex> lock(gc.mu);
+  if (!gc.capture_stream) {  // the caller's stream may be the default stream, which cannot capture
+    hipError_t e = hipStreamCreateWithFlags(&gc.capture_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+      set_error(std::string("hipStreamCreateWithFlags: ") + hipGetErrorString(e));
+      return MTMC_EHIP;
+    }
+  }
+  for (auto& e : gc.entries)
+    if (e.workspace == (const void*)gp.page_table && e.B == gp.B && e.prompt_len == gp.prompt_len &&
+        e.n_samples == gp.n_samples && e.max_new == gp.max_new) {
+      *out = e.exec;
+      return MTMC_OK;
+    }
+  if (gc.entries.size() >= 8) {  // evict the oldest; it may still be queued on the stream
+    MTMC_HIP_CHECK(hipStreamSynchronize(st));
+    (void)hipGraphExecDestroy(gc.entries.front().exec);
+    gc.entries.erase(gc.entries.begin());
+  }
+  hipGraph_t graph = nullptr;
+  MTMC_HIP_CHECK(hipStreamBeginCapture(gc.capture_stream, hipStreamCaptureModeThreadLocal));
+  step(gc.capture_stream);
+  MTMC_HIP_CHECK(hipStreamEndCapture(gc.capture_stream, &graph));
+  hipGraphExec_t exec = nullptr;
+  hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) {
+    set_error(std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
+    return MTMC_EHIP;
+  }
+  gc.entries.push_back({(const void*)gp.page_table, gp.B, gp.prompt_len, gp.n_samples, gp.max_new, exec});
+  *out = exec;
+  return MTMC_OK;
+}
+
 }  // namespace
 
 int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts, const SampleArgs& sa,
@@ -285,13 +356,25 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i - 1
     TokMap dmap{1, 1, p.prompt_len - 1, p.d_step};
     bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, st);
-    for (int i = 0; i < p.max_new; ++i) {
-      if (i > 0) decode_layers(w, D, gp, pool, dmap, st);
+    auto sample = [&](hipStream_t s) {
       bf16::gemm_skinny_sample(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xB, gp.B,
-                               gp.bt, (const bf16::SampleCtl*)p.ctl, p.d_step, st);
+                               gp.bt, (const bf16::SampleCtl*)p.ctl, p.d_step, s);
       bf16::sample_reduce(p.lm_part, bf16::sample_groups(D.nt_V, gp.bt), gp.B, (const bf16::SampleCtl*)p.ctl,
-                          p.d_step, p.cur_ids, st);
-      launch_add_int(p.d_step, 1, st);
+                          p.d_step, p.cur_ids, s);
+      launch_add_int(p.d_step, 1, s);
+    };
+    auto decode_step = [&](hipStream_t s) {
+      decode_layers(w, D, gp, pool, dmap, s);
+      sample(s);
+    };
+    sample(st);
+    if (p.max_new > 1) {
+      hipGraphExec_t exec = nullptr;
+      if (int rc = decode_graph(w, gp, st, decode_step, &exec)) return rc;
+      for (int i = 1; i < p.max_new; ++i) {
+        if (exec) MTMC_HIP_CHECK(hipGraphLaunch(exec, st));
+        else decode_step(st);
+      }
     }
   }
   return MTMC_OK;

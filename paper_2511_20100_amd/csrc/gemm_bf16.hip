@@ -15,8 +15,10 @@ namespace mtmc {
 namespace bf16 {
 
 // acc[nb][mb] += W[n tiles nt0 + nb] . X[m tiles mt0 + mb] over k tiles [k0, k1).
-// Tile indices past the end are clamped (their results are never stored).
-template <int NB, int MB>
+// Tile indices past the end are clamped (their results are never stored).  Operands live in a
+// ring of PF k-steps of registers: the loads of step k + PF are issued as soon as step k has
+// been consumed, so PF * (NB + MB) KiB per wavefront are always in flight.
+template <int NB, int MB, int PF>
 __device__ __forceinline__ void wave_gemm(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles,
                                           int nt0, const h16_t* __restrict__ Xt, int m_tiles,
                                           int mt0, int k0, int k1, int lane, v4f (&acc)[NB][MB]) {
@@ -24,29 +26,36 @@ __device__ __forceinline__ void wave_gemm(const h16_t* __restrict__ Wt, int k_ti
   const h16_t* wp[NB];
   const h16_t* xp[MB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512;
+  for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512 + lane * 8;
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mt0 + mb, m_tiles - 1) * 512;
+  for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mt0 + mb, m_tiles - 1) * 512 + lane * 8;
   const size_t xstep = (size_t)m_tiles * 512;
-  v8bf wc[NB], xc[MB], wn[NB], xn[MB];
+  v8bf wr[PF][NB], xr[PF][MB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) wc[nb] = load_frag(wp[nb] + (size_t)k0 * 512, lane);
+  for (int s = 0; s < PF; ++s) {
+    const int kk = min(k0 + s, k1 - 1);
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) xc[mb] = load_frag(xp[mb] + (size_t)k0 * xstep, lane);
-  for (int ks = k0; ks < k1; ++ks) {
-    const int kn = min(ks + 1, k1 - 1);
+    for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kk * 512, 0);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wn[nb] = load_frag(wp[nb] + (size_t)kn * 512, lane);
+    for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kk * xstep, 0);
+  }
+  for (int ks = k0; ks < k1; ks += PF) {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) xn[mb] = load_frag(xp[mb] + (size_t)kn * xstep, lane);
+    for (int s = 0; s < PF; ++s) {
+      if (ks + s < k1) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wc[nb], xc[mb], acc[nb][mb]);
+          for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s][mb], acc[nb][mb]);
+        const int kn = ks + s + PF;
+        if (kn < k1) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wc[nb] = wn[nb];
+          for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kn * 512, 0);
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) xc[mb] = xn[mb];
+          for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kn * xstep, 0);
+        }
+      }
+    }
   }
 }
 
@@ -54,9 +63,10 @@ __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + expf(-g));
 
 // ======================================================================================
 // Skinny GEMM (M <= 128 tokens): one workgroup = NB weight row tiles x one K split; its four
-// wavefronts take a quarter of the K range each and are summed through LDS in fixed order.
+// wavefronts take a quarter of the K range each and are summed through LDS in a fixed tree.
 // ======================================================================================
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_SAMPLE = 2 };
+constexpr int kSkinnyPF = 2;  // k-steps of operands each wavefront keeps in flight
 
 struct SamplePartial {  // one per (row, weight-tile group)
   float m, s;           // log-sum-exp state of z / T over the group's vocabulary slice
@@ -67,8 +77,8 @@ struct SamplePartial {  // one per (row, weight-tile group)
 };
 
 template <int NB, int MB, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_skinny(SkinnyArgs a) {
-  __shared__ float red[3][NB * MB * 4][64];
+__global__ __launch_bounds__(256, (MB > 4 ? 2 : 3)) void k_gemm_skinny(SkinnyArgs a) {
+  __shared__ float red[2][NB * MB * 4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nt0 = blockIdx.x * NB;
   const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
@@ -81,25 +91,41 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(SkinnyArgs a) {
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
-  wave_gemm<NB, MB>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, 0, k0, k1, lane, acc);
-  if (wave > 0) {
+  wave_gemm<NB, MB, kSkinnyPF>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, 0, k0, k1, lane, acc);
+  // fixed-order tree over the four K quarters: (w0 + w2) + (w1 + w3)
+  if (wave >= 2) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave - 1][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
+        for (int r = 0; r < 4; ++r) red[wave - 2][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
+  }
+  __syncthreads();
+  if (wave < 2) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[wave][(nb * MB + mb) * 4 + r][lane];
+  }
+  if (wave == 1) {  // red[1] was read by this wavefront only
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[1][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
   }
   __syncthreads();
   if (wave > 0) return;
 #pragma unroll
-  for (int w = 0; w < 3; ++w)
+  for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[w][(nb * MB + mb) * 4 + r][lane];
+      for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[1][(nb * MB + mb) * 4 + r][lane];
 
   const int col = lane & 15, rq = (lane >> 4) * 4;
   const int Mpad = a.m_tiles * 16;
@@ -281,7 +307,7 @@ __global__ __launch_bounds__(256) void k_gemm_large(LargeArgs a) {
   for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
-  wave_gemm<4, 4>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, 0, a.k_tiles, lane, acc);
+  wave_gemm<4, 4, 2>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, 0, a.k_tiles, lane, acc);
   const int col = lane & 15, rq = (lane >> 4) * 4;
   const int Mpad = a.m_tiles * 16;
 #pragma unroll
@@ -370,7 +396,7 @@ __global__ __launch_bounds__(256) void k_lmhead_score(ScoreHeadArgs a) {
     for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
-    wave_gemm<4, 4>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, 0, a.k_tiles, lane, acc);
+    wave_gemm<4, 4, 2>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, 0, a.k_tiles, lane, acc);
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
       if (nt0 + nb >= a.n_tiles) continue;

@@ -55,6 +55,8 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_score_workspace_bytes.restype = sz
     lib.mtmc_score.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.mtmc_score.restype = ctypes.c_int
+    lib.mtmc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    lib.mtmc_set_option.restype = ctypes.c_int
     lib.mtmc_poll_errors.argtypes = [vp, vp]
     lib.mtmc_poll_errors.restype = ctypes.c_int
     lib.mtmc_last_error.argtypes = []
@@ -64,7 +66,8 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mtmc_rollout_workspace_bytes",
-           "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error")
+           "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
+           "mtmc_set_option")
 
 
 def mtmc_last_error() -> str:
@@ -160,6 +163,13 @@ def mtmc_score(handle: int, seqs: torch.Tensor, prompt_len: int = 1, *, want_top
                            top1.data_ptr() if want_top1 else None, margin.data_ptr() if want_top1 else None,
                            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return (out_logprobs, top1, margin) if want_top1 else out_logprobs
+
+
+MTMC_OPT_HIP_GRAPH = 1
+
+
+def mtmc_set_option(handle: int, option: int, value: int) -> None:
+    _check(_lib.mtmc_set_option(handle, option, value))
 
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:
