@@ -26,7 +26,8 @@ static int check_config(const mtmc_config* c) {
                "MTMC_BF16 kernels need at most 16 query heads per kv head");
   MTMC_REQUIRE(c->d_model % 16 == 0 && c->d_ffn % 16 == 0 && c->vocab % 16 == 0,
                "d_model, d_ffn and vocab must be multiples of 16");
-  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->d_model % 32 == 0, "MTMC_BF16 kernels need d_model % 32 == 0");
+  MTMC_REQUIRE(c->dtype != MTMC_BF16 || (c->d_model % 32 == 0 && c->d_model <= 4096),
+               "MTMC_BF16 kernels need d_model % 32 == 0 and d_model <= 4096");
   MTMC_REQUIRE(c->page_tokens == kPageTokens, "page_tokens must be 16");
   MTMC_REQUIRE(c->max_positions > 0, "max_positions must be positive");
   MTMC_REQUIRE(c->rms_eps >= 0.f && c->rope_base > 0.f, "rms_eps >= 0 and rope_base > 0 required");

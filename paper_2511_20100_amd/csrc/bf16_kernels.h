@@ -46,6 +46,44 @@ struct ScoreHeadArgs {
   int n_groups, groups_per_block;
 };
 
+// ---- decode step (five launches per block; see decode_bf16.hip) ------------------------------
+struct DecGemmArgs {
+  const h16_t* Wt;
+  const h16_t* Xt;
+  int n_tiles, k_tiles, m_tiles, M;
+  const float* ss_cur;   // per-tile sums of squares [ss_tiles][m_tiles*16] of the current residual (NULL: scale 1)
+  const float* ss_old;   // same, of the residual whose norm scaled Xt
+  int ss_tiles;
+  float inv_d, eps;
+  float* out_f32;        // STORE: fp32 [M, ld_out]; RESID: residual h (in/out); SAMPLE: sampler partials
+  int ld_out;
+  h16_t* out_h16;        // SWIGLU / RESID: tiled fp16 operand for the next GEMM
+  float* ss_out;         // RESID: [n_tiles][m_tiles*16]
+  const float* gain;     // RESID: gain of the next norm
+  const SampleCtl* ctl;
+  const int* d_step;
+};
+enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3 };
+void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);
+int dec_wide_nb(int m_tiles);
+void embed_dec(float* h, const int* ids, int B, const bf16_t* E, int d, int vocab, int* err_flag, const float* gain,
+               float eps, h16_t* x, int m_tiles, float* ss_out, hipStream_t st);
+void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,
+                  hipStream_t st);
+struct AttnDecArgs {
+  const float* qkv;      // fp32 [B, (Hq + 2 Hkv) * 128], not yet rotated
+  const float* cos;
+  const float* sin;
+  int Hq, Hkv, layer, pos_base;
+  const int* d_step;
+  KvPool pool;
+  int chunk_pages, n_chunks, m_tiles;
+  float* part;           // [B, Hkv, n_chunks, G * 130]
+  int* counters;         // [B * Hkv], zero between launches
+  h16_t* o;              // tiled fp16 [Hq * 128 (k), m_tiles * 16]
+};
+void attention_dec(const AttnDecArgs& a, int B, hipStream_t st);
+
 // ---- weight re-tiling (once, at load) ------------------------------------------------------
 // dst (tiled fp16, n_tiles x k_tiles blocks) <- src row-major [N, K] bf16; rows/cols past N/K are
 // zero.  Sets bit 1 of *err_flag if a weight does not fit fp16 (magnitude above 65504, or not finite).

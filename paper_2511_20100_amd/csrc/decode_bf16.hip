@@ -1,0 +1,556 @@
+// Decode-step kernels of the bf16 path: five launches per residual block.
+//
+//   qkv   = W_qkv x'                      k_gemm_dec<STORE>
+//   o     = attention(rope(q), cache)     k_attn_dec   (also rotates/writes the new K, V; merges the context chunks)
+//   h    += W_o o;   x' for the FFN       k_gemm_dec<RESID>
+//   a     = silu(W_g x') * (W_u x')       k_gemm_dec<SWIGLU>
+//   h    += W_d a;   x' for the next block k_gemm_dec<RESID>
+//
+// Every GEMM workgroup owns whole output columns (all of K), so results are complete when the
+// workgroup ends: no split-K partials in memory and no separate reduction / norm kernels.
+//
+// Deferred RMSNorm.  A producer (RESID) cannot know the new row norm (other workgroups hold the
+// other columns), so it writes x' = fp16(h_new * gain * r_old), r_old = 1/rms of the row *before*
+// its update (a well-scaled fp16 value), together with the sum of squares of its 16 new columns.
+// The consumer sums those per-tile squares in a fixed order to get r_new and multiplies its
+// fp32 accumulators by r_new / r_old: W (h g r_new) = (W (h g r_old)) r_new / r_old.
+#include "attention_core.h"
+#include "bf16_kernels.h"
+#include "device_utils.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+template <int NB, int MB, int PF>
+__device__ __forceinline__ void wave_gemm_dec(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles, int nt0,
+                                              const h16_t* __restrict__ Xt, int m_tiles, int k0, int k1,
+                                              int lane, v4f (&acc)[NB][MB]) {
+  if (k0 >= k1) return;
+  const h16_t* wp[NB];
+  const h16_t* xp[MB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512 + lane * 8;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mb, m_tiles - 1) * 512 + lane * 8;
+  const size_t xstep = (size_t)m_tiles * 512;
+  v8bf wr[PF][NB], xr[PF][MB];
+#pragma unroll
+  for (int s = 0; s < PF; ++s) {
+    const int kk = min(k0 + s, k1 - 1);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kk * 512, 0);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kk * xstep, 0);
+  }
+  for (int ks = k0; ks < k1; ks += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      if (ks + s < k1) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s][mb], acc[nb][mb]);
+        const int kn = ks + s + PF;
+        if (kn < k1) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kn * 512, 0);
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kn * xstep, 0);
+        }
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ float silu_d(float g) { return g / (1.0f + expf(-g)); }
+
+enum { DEPI_STORE = 0, DEPI_RESID = 1, DEPI_SWIGLU = 2, DEPI_SAMPLE = 3 };
+
+struct DecSamplePartial {
+  float m, s, y;
+  int idx;
+  float zt;
+  float pad[3];
+};
+
+template <int NB, int MB, int WAVES, int PF, int EPI>
+__global__ __launch_bounds__(WAVES * 64, (WAVES == 4 ? (MB > 4 ? 2 : 3) : 1)) void k_gemm_dec(DecGemmArgs a) {
+  __shared__ float red[WAVES / 2][NB * MB * 4][64];
+  __shared__ float s_scale[MB * 16];
+  __shared__ float s_part[2][WAVES * 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nt0 = blockIdx.x * NB;
+  const int Mpad = a.m_tiles * 16;
+  // Row scales (consumers need r_new / r_old, producers r of the state they update).  Thread t sums
+  // tiles part, part + P, ... of row t % Mpad; the P partial sums are then added in index order.
+  {
+    constexpr int NT = WAVES * 64;
+    const int P = NT / Mpad;  // Mpad <= 128 <= NT
+    const int m = tid % Mpad, part = tid / Mpad;
+    const bool two = (EPI != DEPI_RESID) && a.ss_cur && a.ss_old != a.ss_cur;
+    float sa = 0.f, sb = 0.f;
+    if (a.ss_cur && part < P) {
+      for (int t = part; t < a.ss_tiles; t += P) {
+        sa += a.ss_cur[(size_t)t * Mpad + m];
+        if (two) sb += a.ss_old[(size_t)t * Mpad + m];
+      }
+    }
+    if (part < P) {
+      s_part[0][tid] = sa;
+      s_part[1][tid] = sb;
+    }
+    __syncthreads();
+    if (tid < Mpad) {
+      float sc = 1.f;
+      if (a.ss_cur && (EPI == DEPI_RESID || two)) {
+        float ta = 0.f, tb = 0.f;
+        for (int q = 0; q < P; ++q) {
+          ta += s_part[0][q * Mpad + tid];
+          tb += s_part[1][q * Mpad + tid];
+        }
+        sc = 1.0f / sqrtf(ta * a.inv_d + a.eps);
+        if (two) sc *= sqrtf(tb * a.inv_d + a.eps);
+      }
+      s_scale[tid] = sc;
+    }
+  }
+  const int per_wave = (a.k_tiles + WAVES - 1) / WAVES;
+  const int k0 = wave * per_wave, k1 = min(a.k_tiles, k0 + per_wave);
+  v4f acc[NB][MB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
+  wave_gemm_dec<NB, MB, PF>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, k1, lane, acc);
+  // fixed binary tree over the K slices of the wavefronts
+#pragma unroll
+  for (int half = WAVES / 2; half >= 1; half >>= 1) {
+    if (wave >= half && wave < 2 * half) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) red[wave - half][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
+    }
+    __syncthreads();
+    if (wave < half) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[wave][(nb * MB + mb) * 4 + r][lane];
+    }
+    __syncthreads();
+  }
+  if (wave > 0) return;
+
+  const int col = lane & 15, rq = (lane >> 4) * 4;
+  float sc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) sc[mb] = s_scale[min(mb * 16 + col, Mpad - 1)];
+
+  if (EPI == DEPI_STORE) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      if (nt0 + nb >= a.n_tiles) continue;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int m = mb * 16 + col;
+        if (m >= a.M) continue;
+        *reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = acc[nb][mb] * sc[mb];
+      }
+    }
+  } else if (EPI == DEPI_RESID) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      if (nt0 + nb >= a.n_tiles) continue;
+      const int n = (nt0 + nb) * 16 + rq;
+      const v4f g = *reinterpret_cast<const v4f*>(a.gain + n);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int m = mb * 16 + col;
+        const bool live = m < a.M;
+        v4f hv = v4f{0.f, 0.f, 0.f, 0.f};
+        if (live) {
+          float* hp = a.out_f32 + (size_t)m * a.ld_out + n;
+          hv = *reinterpret_cast<const v4f*>(hp) + acc[nb][mb];
+          *reinterpret_cast<v4f*>(hp) = hv;
+          uint2 pk;
+          pk.x = pack_h16x2(hv[0] * g[0] * sc[mb], hv[1] * g[1] * sc[mb]);
+          pk.y = pack_h16x2(hv[2] * g[2] * sc[mb], hv[3] * g[3] * sc[mb]);
+          *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, n, Mpad)) = pk;
+        }
+        float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (lane < 16 && live) a.ss_out[(size_t)(nt0 + nb) * Mpad + m] = ss;
+      }
+    }
+  } else if (EPI == DEPI_SWIGLU) {
+#pragma unroll
+    for (int nb = 0; nb < NB; nb += 2) {
+      if (nt0 + nb >= a.n_tiles) continue;
+      const int f = ((nt0 + nb) >> 1) * 16 + rq;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int m = mb * 16 + col;
+        if (m >= a.M) continue;
+        const v4f g = acc[nb][mb] * sc[mb], u = acc[(nb + 1) % NB][mb] * sc[mb];
+        uint2 pk;
+        pk.x = pack_h16x2(silu_d(g[0]) * u[0], silu_d(g[1]) * u[1]);
+        pk.y = pack_h16x2(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3]);
+        *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, f, Mpad)) = pk;
+      }
+    }
+  } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this workgroup's vocabulary slice
+    const SampleCtl ctl = *a.ctl;
+    const int step = *a.d_step;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = mb * 16 + col;
+      Lse lse = lse_empty();
+      float by = -INFINITY, bz = 0.f;
+      int bi = 0x7fffffff;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        if (nt0 + nb >= a.n_tiles) continue;
+        const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
+        uint4 rb = make_uint4(0, 0, 0, 0);
+        if (!ctl.greedy)
+          rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u), ctl.key0,
+                             ctl.key1);
+        const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float z = acc[nb][mb][r] * sc[mb];
+          const float zt = ctl.greedy ? z : z * ctl.inv_temp;
+          lse_push(lse, zt);
+          const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
+          if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: the first maximum wins
+        }
+      }
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+        const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        lse = lse_merge(lse, ol);
+        if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
+      }
+      if (lane < 16 && m < a.M) {
+        DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)blockIdx.x * a.M + m;
+        p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
+      }
+    }
+  }
+}
+
+template <int NB, int MB, int WAVES, int PF>
+static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
+  const dim3 grid((a.n_tiles + NB - 1) / NB);
+  const dim3 block(WAVES * 64);
+  switch (epi) {
+    case DEPI_STORE: k_gemm_dec<NB, MB, WAVES, PF, DEPI_STORE><<<grid, block, 0, st>>>(a); break;
+    case DEPI_RESID: k_gemm_dec<NB, MB, WAVES, PF, DEPI_RESID><<<grid, block, 0, st>>>(a); break;
+    case DEPI_SWIGLU: k_gemm_dec<NB, MB, WAVES, PF, DEPI_SWIGLU><<<grid, block, 0, st>>>(a); break;
+    default: k_gemm_dec<NB, MB, WAVES, PF, DEPI_SAMPLE><<<grid, block, 0, st>>>(a); break;
+  }
+}
+
+// Narrow shape: one weight row tile per workgroup, K split over 8 or 16 wavefronts (QKV, O, down).
+template <int MB>
+static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
+  if (MB > 4) launch_dec_t<1, MB, 8, 2>(a, epi, st);
+  else if (a.k_tiles >= 128) launch_dec_t<1, MB, 16, 3>(a, epi, st);
+  else launch_dec_t<1, MB, 8, 3>(a, epi, st);
+}
+// Wide shape: many row tiles (gate/up, LM head): NB tiles per workgroup, K split over 4 wavefronts.
+template <int MB>
+static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
+  if (MB > 4) launch_dec_t<2, MB, 4, 2>(a, epi, st);
+  else launch_dec_t<4, MB, 4, 2>(a, epi, st);
+}
+
+int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
+
+void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
+  const bool wide = (epi == DEPI_SWIGLU || epi == DEPI_SAMPLE);
+  const int mb = a.m_tiles <= 1 ? 1 : a.m_tiles <= 2 ? 2 : a.m_tiles <= 4 ? 4 : 8;
+  if (wide) {
+    switch (mb) {
+      case 1: launch_dec_wide<1>(a, epi, st); break;
+      case 2: launch_dec_wide<2>(a, epi, st); break;
+      case 4: launch_dec_wide<4>(a, epi, st); break;
+      default: launch_dec_wide<8>(a, epi, st); break;
+    }
+  } else {
+    switch (mb) {
+      case 1: launch_dec_narrow<1>(a, epi, st); break;
+      case 2: launch_dec_narrow<2>(a, epi, st); break;
+      case 4: launch_dec_narrow<4>(a, epi, st); break;
+      default: launch_dec_narrow<8>(a, epi, st); break;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- embedding of the fed-back token
+// h = E[id]; exact row norm (the workgroup holds the whole row); x' = fp16(h g r); per-tile squares.
+__global__ __launch_bounds__(256) void k_embed_dec(float* h, const int* ids, const bf16_t* E, int d, int vocab,
+                                                   int* err_flag, const float* gain, float eps, h16_t* x,
+                                                   int Mpad, float* ss_out) {
+  __shared__ float red[16];
+  const int m = blockIdx.x;
+  int id = ids[m];
+  if (id < 0 || id >= vocab) {
+    if (threadIdx.x == 0) atomicOr(err_flag, 1);
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  float v[16];
+  float ss = 0.f;
+  const int k = threadIdx.x * 16;
+  const bool live = k < d;
+  if (live) {
+    const v4u r0 = *reinterpret_cast<const v4u*>(E + (size_t)id * d + k);
+    const v4u r1 = *reinterpret_cast<const v4u*>(E + (size_t)id * d + k + 8);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(r0[e] << 16);
+      v[2 * e + 1] = __uint_as_float(r0[e] & 0xffff0000u);
+      v[8 + 2 * e] = __uint_as_float(r1[e] << 16);
+      v[8 + 2 * e + 1] = __uint_as_float(r1[e] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) ss += v[e] * v[e];
+#pragma unroll
+    for (int e = 0; e < 16; e += 4)
+      *reinterpret_cast<v4f*>(h + (size_t)m * d + k + e) = v4f{v[e], v[e + 1], v[e + 2], v[e + 3]};
+    ss_out[(size_t)(k >> 4) * Mpad + m] = ss;
+  }
+  const float tot = block_sum(ss, red);
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+  if (live) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      v4u pk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        pk[e] = pack_h16x2(v[half * 8 + 2 * e] * gain[k + half * 8 + 2 * e] * r,
+                           v[half * 8 + 2 * e + 1] * gain[k + half * 8 + 2 * e + 1] * r);
+      *reinterpret_cast<v4u*>(x + act_off(m, k + half * 8, Mpad)) = pk;
+    }
+  }
+}
+void embed_dec(float* h, const int* ids, int B, const bf16_t* E, int d, int vocab, int* err_flag, const float* gain,
+               float eps, h16_t* x, int m_tiles, float* ss_out, hipStream_t st) {
+  k_embed_dec<<<B, 256, 0, st>>>(h, ids, E, d, vocab, err_flag, gain, eps, x, m_tiles * 16, ss_out);
+}
+
+// ---------------------------------------------------------------- sampler merge (per row)
+__global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* part, int n_groups, int M,
+                                                      const SampleCtl* ctlp, int* d_step, int* cur_ids) {
+  __shared__ Lse s_lse[4];
+  __shared__ float s_y[4], s_z[4];
+  __shared__ int s_i[4];
+  const int b = blockIdx.x;
+  Lse lse = lse_empty();
+  float by = -INFINITY, bz = 0.f;
+  int bi = 0x7fffffff;
+  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
+    const DecSamplePartial p = part[(size_t)g * M + b];
+    lse = lse_merge(lse, Lse{p.m, p.s});
+    if (p.y > by || (p.y == by && p.idx < bi)) { by = p.y; bi = p.idx; bz = p.zt; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+    const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    lse = lse_merge(lse, ol);
+    if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
+  }
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  if (lane == 0) { s_lse[wid] = lse; s_y[wid] = by; s_z[wid] = bz; s_i[wid] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) {
+      lse = lse_merge(lse, s_lse[w]);
+      if (s_y[w] > by || (s_y[w] == by && s_i[w] < bi)) { by = s_y[w]; bi = s_i[w]; bz = s_z[w]; }
+    }
+    const SampleCtl ctl = *ctlp;
+    const int step = *d_step;
+    cur_ids[b] = bi;
+    ctl.out_ids[(size_t)b * ctl.max_new + step] = bi;
+    ctl.out_logprobs[(size_t)b * ctl.max_new + step] = bz - (lse.m + logf(lse.s));
+  }
+}
+void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,
+                  hipStream_t st) {
+  k_sample_merge<<<M, 256, 0, st>>>(reinterpret_cast<const DecSamplePartial*>(part), n_groups, M, ctl, d_step,
+                                    cur_ids);
+}
+
+
+// ---------------------------------------------------------------- decode attention, fused
+// One workgroup per (sequence, kv head, context chunk).  Prologue: rotate the G query heads of the
+// row (fp32 qkv -> fp16, through LDS); the workgroup whose chunk holds the current position also
+// rotates the new key, converts the new value and stores both into their page before attending.
+// Epilogue: the four wavefronts' partial (max, sum, O) are merged through LDS; with several
+// active chunks each workgroup publishes its partial and the last one to arrive (device-scope
+// counter) merges them in chunk order, so the result does not depend on arrival order.
+constexpr int DHD = 128;
+constexpr int DPAGE = kPageTokens * DHD;
+
+__device__ __forceinline__ h16_t* dec_page(const KvPool& pool, int layer, int which, int page, int g) {
+  return (h16_t*)pool.base +
+         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)DPAGE;
+}
+
+__global__ __launch_bounds__(256) void k_attn_dec(AttnDecArgs a) {
+  __shared__ __attribute__((aligned(16))) h16_t q_s[16][DHD];
+  __shared__ float s_o[4][16][DHD + 1];
+  __shared__ float s_m[4][16], s_l[4][16];
+  __shared__ int s_last;
+  const int b = blockIdx.x, g = blockIdx.y, chunk = blockIdx.z;
+  const int Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
+  const int pos = a.pos_base + *a.d_step;
+  const int n_ctx_pages = pos / kPageTokens + 1;
+  const int p_lo = chunk * a.chunk_pages, p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
+  if (p_lo >= p_hi) return;
+  const int n_act = (n_ctx_pages + a.chunk_pages - 1) / a.chunk_pages;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, lg = lane >> 4;
+  const KvPool& pool = a.pool;
+  const int* table = pool.page_table + (size_t)b * pool.max_pages;
+  const float* row = a.qkv + (size_t)b * (Hq + 2 * Hkv) * DHD;
+  const float* cs = a.cos + (size_t)pos * (DHD / 2);
+  const float* sn = a.sin + (size_t)pos * (DHD / 2);
+  // ---- rotate q (G heads x 64 pairs) into LDS
+  for (int e = tid; e < G * 64; e += 256) {
+    const int j = e >> 6, i = e & 63;
+    const float x0 = row[(size_t)(g * G + j) * DHD + i], x1 = row[(size_t)(g * G + j) * DHD + i + 64];
+    const float c = cs[i], s = sn[i];
+    q_s[j][i] = f32_to_h16(x0 * c - x1 * s);
+    q_s[j][i + 64] = f32_to_h16(x1 * c + x0 * s);
+  }
+  // ---- the owner of the current position appends K and V to the cache
+  const int cur_page = pos / kPageTokens;
+  if (cur_page >= p_lo && cur_page < p_hi) {
+    const int page = table[cur_page], slot = pos % kPageTokens;
+    h16_t* kp = dec_page(pool, a.layer, 0, page, g);
+    h16_t* vp = dec_page(pool, a.layer, 1, page, g);
+    if (tid < 64) {
+      const int i = tid;
+      const float x0 = row[(size_t)(Hq + g) * DHD + i], x1 = row[(size_t)(Hq + g) * DHD + i + 64];
+      const float c = cs[i], s = sn[i];
+      const int c0 = i, c1 = i + 64;
+      kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(x0 * c - x1 * s);
+      kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(x1 * c + x0 * s);
+    } else if (tid < 192) {
+      const int c = tid - 64;
+      vp[c * kPageTokens + slot] = f32_to_h16(row[(size_t)(Hq + Hkv + g) * DHD + c]);
+    }
+  }
+  __syncthreads();  // q_s complete; this workgroup's K/V stores are visible to its own loads
+
+  v8bf qf[1][4];
+  int qpos[1];
+  qpos[0] = (col < G) ? pos : -1;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    v4u raw = {0u, 0u, 0u, 0u};
+    if (col < G) raw = *reinterpret_cast<const v4u*>(&q_s[col][kb * 32 + 8 * lg]);
+    qf[0][kb] = __builtin_bit_cast(v8bf, raw);
+  }
+  AttnState<1> st;
+  attn_init(st);
+  const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  for (int pg = p_lo + 2 * wave; pg < p_hi; pg += 8) {
+    const int id0 = table[pg], id1 = table[min(pg + 1, n_ctx_pages - 1)];
+    attn_pair<1>(dec_page(pool, a.layer, 0, id0, g), dec_page(pool, a.layer, 0, id1, g),
+                 dec_page(pool, a.layer, 1, id0, g), dec_page(pool, a.layer, 1, id1, g), pg * kPageTokens, qf, qpos,
+                 1, scale, st, lane);
+  }
+  float l = st.l[0];
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s_o[wave][col][cb * 16 + 4 * lg + r] = st.o[0][cb][r];
+  if (lg == 0) {
+    s_m[wave][col] = st.m[0];
+    s_l[wave][col] = l;
+  }
+  __syncthreads();
+  // ---- merge the four wavefronts: thread t < 16 G owns (column c, 8 consecutive dims)
+  const bool owner = tid < G * (DHD / 8);
+  const int c = tid / (DHD / 8), d0 = (tid % (DHD / 8)) * 8;
+  float mm = -INFINITY, ll = 0.f, acc[8] = {};
+  if (owner) {
+    mm = fmaxf(fmaxf(s_m[0][c], s_m[1][c]), fmaxf(s_m[2][c], s_m[3][c]));
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = expf(s_m[w][c] - mm);
+      ll += f * s_l[w][c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += f * s_o[w][c][d0 + e];
+    }
+  }
+  const int Mpad = a.m_tiles * 16;
+  if (n_act > 1) {
+    const size_t stride = (size_t)G * (DHD + 2);
+    float* base = a.part + ((size_t)b * Hkv + g) * a.n_chunks * stride;
+    if (owner) {
+      float* out = base + chunk * stride;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[(size_t)c * DHD + d0 + e] = acc[e];
+      if (d0 == 0) {
+        out[G * DHD + c] = mm;
+        out[G * DHD + G + c] = ll;
+      }
+    }
+    __syncthreads();  // every wavefront's partial stores have completed (workgroup scope)
+    if (tid == 0) {
+      __threadfence();  // release them at device scope before announcing arrival
+      const int old = atomicAdd(a.counters + b * Hkv + g, 1);
+      s_last = (old == n_act - 1);
+      if (s_last) {
+        __threadfence();  // acquire the other chunks' partials
+        a.counters[b * Hkv + g] = 0;  // ready for the next launch
+      }
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (owner) {
+      mm = -INFINITY;
+      for (int k = 0; k < n_act; ++k) mm = fmaxf(mm, base[k * stride + G * DHD + c]);
+      ll = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+      for (int k = 0; k < n_act; ++k) {
+        const float f = expf(base[k * stride + G * DHD + c] - mm);
+        ll += f * base[k * stride + G * DHD + G + c];
+        const float* src = base + k * stride + (size_t)c * DHD + d0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += f * src[e];
+      }
+    }
+  }
+  if (owner) {
+    const float inv = 1.0f / ll;
+    v4u pk;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pk[e] = pack_h16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
+    *reinterpret_cast<v4u*>(a.o + act_off(b, (g * G + c) * DHD + d0, Mpad)) = pk;
+  }
+}
+
+void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {
+  k_attn_dec<<<dim3(B, a.Hkv, a.n_chunks), 256, 0, st>>>(a);
+}
+
+}  // namespace bf16
+}  // namespace mtmc

@@ -59,6 +59,9 @@ struct RolloutPlan {
   float* lm_part;     // LM-head per-tile partial reductions
   void* qb;           // rotated queries, bf16 row-major [Tmax, Hq*hd]
   void* ctl;          // per-call sampling parameters (device copy)
+  float* ssA;         // per-tile sums of squares of the residual rows (two generations)
+  float* ssB;
+  int* attn_counters; // arrival counters of the decode-attention context chunks
   int chunk_pages, n_chunks;       // decode-attention context split
   int ks_qkv, ks_o, ks_down;       // split-K factors of the decode GEMMs
   int bt;                          // 16-row tiles covering B

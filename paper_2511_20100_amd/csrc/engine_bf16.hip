@@ -190,6 +190,9 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.lm_part = cv.take<float>((size_t)bf16::sample_groups(D.nt_V, p.bt) * p.B * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
   p.ctl = cv.take<bf16::SampleCtl>(1);
+  p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
+  p.ssB = cv.take<float>((size_t)D.nt_d * Mpad);
+  p.attn_counters = cv.take<int>((size_t)p.B * D.Hkv);
 }
 
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
@@ -229,33 +232,52 @@ void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, fl
   }
 }
 
-// One decode step over the B sequences of a group: embeds cur_ids, runs the blocks against the
-// paged cache at position prompt_len - 1 + *d_step, leaves x = bf16 RMSNorm(h; final_norm).
-void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, KvPool pool, TokMap dmap,
-                   hipStream_t st) {
+// One decode step over the B sequences of a group: embeds cur_ids, runs the blocks (five launches
+// each) against the paged cache at position prompt_len - 1 + *d_step and leaves in xB the operand
+// of the LM head together with the row-norm bookkeeping (*ss_cur, *ss_old) its consumer needs.
+void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, KvPool pool, int pos_base,
+                   const float** ss_cur_out, const float** ss_old_out, hipStream_t st) {
   const mtmc_config& c = w->cfg;
-  const int B = p.B, bt = p.bt, Mpad = bt * 16;
+  const int B = p.B, bt = p.bt;
   float* h = p.hB;
   h16_t* x = (h16_t*)p.xB;
   h16_t* o = (h16_t*)p.o;
   h16_t* a = (h16_t*)p.a;
-  h16_t* qb = (h16_t*)p.qb;
-  bf16::embed(h, p.cur_ids, B, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
-  bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, x, B, bt, D.d, st);
+  float* ss[2] = {p.ssA, p.ssB};
+  int cur = 0, old = 0;
+  bf16::embed_dec(h, p.cur_ids, B, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, w->layers[0].attn_norm, c.rms_eps,
+                  x, bt, ss[0], st);
+  bf16::DecGemmArgs g{};
+  g.m_tiles = bt; g.M = B; g.ss_tiles = D.nt_d; g.inv_d = 1.0f / (float)D.d; g.eps = c.rms_eps;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& L = w->layers[l];
-    bf16::gemm_skinny_partial(p.part, D.nqkv, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, B, bt, p.ks_qkv, st);
-    bf16::rope_kv_write(qb, p.part, p.ks_qkv, D.nqkv, Mpad, B, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, dmap,
-                        pool, l, st);
-    bf16::attention_decode(p.attn_part, qb, B, D.Hq, D.Hkv, dmap, pool, l, p.chunk_pages, p.n_chunks, st);
-    bf16::attention_decode_merge(o, p.attn_part, B, bt, D.Hq, D.Hkv, dmap, p.chunk_pages, p.n_chunks, st);
-    bf16::gemm_skinny_partial(p.part, D.d, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, B, bt, p.ks_o, st);
-    bf16::add_norm(h, p.part, p.ks_o, D.d, Mpad, L.ffn_norm, c.rms_eps, x, B, bt, D.d, st);
-    bf16::gemm_skinny_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, B, bt, st);
-    bf16::gemm_skinny_partial(p.part, D.d, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, B, bt, p.ks_down, st);
-    const float* next = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
-    bf16::add_norm(h, p.part, p.ks_down, D.d, Mpad, next, c.rms_eps, x, B, bt, D.d, st);
+    bf16::DecGemmArgs q = g;
+    q.Wt = (const h16_t*)L.wqkv; q.Xt = x; q.n_tiles = D.nt_qkv; q.k_tiles = D.kt_d;
+    q.ss_cur = ss[cur]; q.ss_old = ss[old]; q.out_f32 = p.qkv; q.ld_out = D.nqkv;
+    bf16::gemm_dec(q, bf16::DEC_STORE, st);
+    bf16::AttnDecArgs at{};
+    at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
+    at.pos_base = pos_base; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
+    at.n_chunks = p.n_chunks; at.m_tiles = bt; at.part = p.attn_part; at.counters = p.attn_counters; at.o = o;
+    bf16::attention_dec(at, B, st);
+    bf16::DecGemmArgs r1 = g;
+    r1.Wt = (const h16_t*)L.wo; r1.Xt = o; r1.n_tiles = D.nt_d; r1.k_tiles = D.kt_nq;
+    r1.ss_cur = ss[cur]; r1.out_f32 = h; r1.ld_out = D.d; r1.out_h16 = x; r1.ss_out = ss[cur ^ 1]; r1.gain = L.ffn_norm;
+    bf16::gemm_dec(r1, bf16::DEC_RESID, st);
+    old = cur; cur ^= 1;
+    bf16::DecGemmArgs gu = g;
+    gu.Wt = (const h16_t*)L.wgu; gu.Xt = x; gu.n_tiles = D.nt_gu; gu.k_tiles = D.kt_d;
+    gu.ss_cur = ss[cur]; gu.ss_old = ss[old]; gu.out_h16 = a;
+    bf16::gemm_dec(gu, bf16::DEC_SWIGLU, st);
+    bf16::DecGemmArgs r2 = g;
+    r2.Wt = (const h16_t*)L.wdown; r2.Xt = a; r2.n_tiles = D.nt_d; r2.k_tiles = D.kt_F;
+    r2.ss_cur = ss[cur]; r2.out_f32 = h; r2.ld_out = D.d; r2.out_h16 = x; r2.ss_out = ss[cur ^ 1];
+    r2.gain = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
+    bf16::gemm_dec(r2, bf16::DEC_RESID, st);
+    old = cur; cur ^= 1;
   }
+  *ss_cur_out = ss[cur];
+  *ss_old_out = ss[old];
 }
 
 // Returns in *out the instantiated graph of one decode step for this workspace and shape, capturing
@@ -335,6 +357,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     bf16::set_sample_ctl((bf16::SampleCtl*)p.ctl, ctl, st);
     launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
     launch_set_int(p.d_step, 0, st);
+    launch_fill_u32((uint32_t*)p.attn_counters, 0u, (size_t)p.B * D.Hkv, st);
     // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
     launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
     // ---- prefill, whole prompts per chunk; a prompt's pages are those of its first sample
@@ -354,20 +377,24 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     if (p.prompt_len % kPageTokens != 0)
       launch_fork_tail_pages(pool, c.n_layers, gp.B, p.n_samples, p.n_full, 2, st);
     // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i - 1
-    TokMap dmap{1, 1, p.prompt_len - 1, p.d_step};
     bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, st);
-    auto sample = [&](hipStream_t s) {
-      bf16::gemm_skinny_sample(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xB, gp.B,
-                               gp.bt, (const bf16::SampleCtl*)p.ctl, p.d_step, s);
-      bf16::sample_reduce(p.lm_part, bf16::sample_groups(D.nt_V, gp.bt), gp.B, (const bf16::SampleCtl*)p.ctl,
-                          p.d_step, p.cur_ids, s);
+    auto sample = [&](hipStream_t s, const float* ss_cur, const float* ss_old) {
+      bf16::DecGemmArgs lm{};
+      lm.Wt = (const h16_t*)w->lm_head; lm.Xt = (const h16_t*)p.xB; lm.n_tiles = D.nt_V; lm.k_tiles = D.kt_d;
+      lm.m_tiles = gp.bt; lm.M = gp.B; lm.ss_cur = ss_cur; lm.ss_old = ss_old; lm.ss_tiles = D.nt_d;
+      lm.inv_d = 1.0f / (float)D.d; lm.eps = c.rms_eps; lm.out_f32 = p.lm_part;
+      lm.ctl = (const bf16::SampleCtl*)p.ctl; lm.d_step = p.d_step;
+      bf16::gemm_dec(lm, bf16::DEC_SAMPLE, s);
+      const int groups = (D.nt_V + bf16::dec_wide_nb(gp.bt) - 1) / bf16::dec_wide_nb(gp.bt);
+      bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, s);
       launch_add_int(p.d_step, 1, s);
     };
     auto decode_step = [&](hipStream_t s) {
-      decode_layers(w, D, gp, pool, dmap, s);
-      sample(s);
+      const float *ss_cur = nullptr, *ss_old = nullptr;
+      decode_layers(w, D, gp, pool, p.prompt_len - 1, &ss_cur, &ss_old, s);
+      sample(s, ss_cur, ss_old);
     };
-    sample(st);
+    sample(st, nullptr, nullptr);  // xB holds the exactly normalised last prompt position
     if (p.max_new > 1) {
       hipGraphExec_t exec = nullptr;
       if (int rc = decode_graph(w, gp, st, decode_step, &exec)) return rc;
