@@ -22,8 +22,8 @@ static int check_config(const mtmc_config* c) {
   MTMC_REQUIRE(c->head_dim == 64 || c->head_dim == 128, "head_dim must be 64 or 128");
   MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->head_dim == 128, "MTMC_BF16 kernels need head_dim 128");
   MTMC_REQUIRE(c->n_q_heads % c->n_kv_heads == 0, "n_q_heads must be a multiple of n_kv_heads");
-  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->n_q_heads / c->n_kv_heads <= 16,
-               "MTMC_BF16 kernels need at most 16 query heads per kv head");
+  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->n_q_heads / c->n_kv_heads <= 8,
+               "MTMC_BF16 kernels need at most 8 query heads per kv head");
   MTMC_REQUIRE(c->d_model % 16 == 0 && c->d_ffn % 16 == 0 && c->vocab % 16 == 0,
                "d_model, d_ffn and vocab must be multiples of 16");
   MTMC_REQUIRE(c->dtype != MTMC_BF16 || (c->d_model % 32 == 0 && c->d_model <= 4096),

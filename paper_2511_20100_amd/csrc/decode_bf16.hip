@@ -22,10 +22,13 @@
 namespace mtmc {
 namespace bf16 {
 
-template <int NB, int MB, int PF>
+// acc[nb][mb] += W[n tile nt0 + nb] . X[m tile mb] over k tiles [k0, k1).  Weight fragments (HBM,
+// long latency) are kept PFW k-steps ahead in registers, activation fragments (L2) PFX ahead.
+template <int NB, int MB, int PFW, int PFX>
 __device__ __forceinline__ void wave_gemm_dec(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles, int nt0,
                                               const h16_t* __restrict__ Xt, int m_tiles, int k0, int k1,
                                               int lane, v4f (&acc)[NB][MB]) {
+  static_assert(PFW % PFX == 0, "the weight ring must be a multiple of the activation ring");
   if (k0 >= k1) return;
   const h16_t* wp[NB];
   const h16_t* xp[MB];
@@ -34,29 +37,35 @@ __device__ __forceinline__ void wave_gemm_dec(const h16_t* __restrict__ Wt, int 
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mb, m_tiles - 1) * 512 + lane * 8;
   const size_t xstep = (size_t)m_tiles * 512;
-  v8bf wr[PF][NB], xr[PF][MB];
+  v8bf wr[PFW][NB], xr[PFX][MB];
 #pragma unroll
-  for (int s = 0; s < PF; ++s) {
+  for (int s = 0; s < PFW; ++s) {
     const int kk = min(k0 + s, k1 - 1);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kk * 512, 0);
+  }
+#pragma unroll
+  for (int s = 0; s < PFX; ++s) {
+    const int kk = min(k0 + s, k1 - 1);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kk * xstep, 0);
   }
-  for (int ks = k0; ks < k1; ks += PF) {
+  for (int ks = k0; ks < k1; ks += PFW) {
 #pragma unroll
-    for (int s = 0; s < PF; ++s) {
+    for (int s = 0; s < PFW; ++s) {
       if (ks + s < k1) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-          for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s][mb], acc[nb][mb]);
-        const int kn = ks + s + PF;
-        if (kn < k1) {
+          for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s % PFX][mb], acc[nb][mb]);
+        const int kw = ks + s + PFW, kx = ks + s + PFX;
+        if (kw < k1) {
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kn * 512, 0);
+          for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kw * 512, 0);
+        }
+        if (kx < k1) {
 #pragma unroll
-          for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kn * xstep, 0);
+          for (int mb = 0; mb < MB; ++mb) xr[s % PFX][mb] = load_frag(xp[mb] + (size_t)kx * xstep, 0);
         }
       }
     }
@@ -74,9 +83,9 @@ struct DecSamplePartial {
   float pad[3];
 };
 
-template <int NB, int MB, int WAVES, int PF, int EPI>
-__global__ __launch_bounds__(WAVES * 64, (WAVES == 4 ? (MB > 4 ? 2 : 3) : 1)) void k_gemm_dec(DecGemmArgs a) {
-  __shared__ float red[WAVES / 2][NB * MB * 4][64];
+template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int EPI>
+__global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
+  __shared__ float red[WAVES][NB * MB * 4][64];
   __shared__ float s_scale[MB * 16];
   __shared__ float s_part[2][WAVES * 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -91,9 +100,20 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 4 ? (MB > 4 ? 2 : 3) : 1)) vo
     const bool two = (EPI != DEPI_RESID) && a.ss_cur && a.ss_old != a.ss_cur;
     float sa = 0.f, sb = 0.f;
     if (a.ss_cur && part < P) {
-      for (int t = part; t < a.ss_tiles; t += P) {
-        sa += a.ss_cur[(size_t)t * Mpad + m];
-        if (two) sb += a.ss_old[(size_t)t * Mpad + m];
+      // batches of 8 independent loads, then the adds in index order
+      for (int t0 = part; t0 < a.ss_tiles; t0 += 8 * P) {
+        float va[8], vb[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u * P;
+          va[u] = (t < a.ss_tiles) ? a.ss_cur[(size_t)t * Mpad + m] : 0.f;
+          vb[u] = (two && t < a.ss_tiles) ? a.ss_old[(size_t)t * Mpad + m] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          sa += va[u];
+          sb += vb[u];
+        }
       }
     }
     if (part < P) {
@@ -122,46 +142,35 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 4 ? (MB > 4 ? 2 : 3) : 1)) vo
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
-  wave_gemm_dec<NB, MB, PF>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, k1, lane, acc);
-  // fixed binary tree over the K slices of the wavefronts
+  wave_gemm_dec<NB, MB, PFW, PFX>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, k1, lane, acc);
+  // Sum over the K slices: every wavefront publishes its accumulators; wavefront w then adds the WAVES
+  // slices of token tiles w, w + WAVES, ... in index order and runs the epilogue for those tokens.
 #pragma unroll
-  for (int half = WAVES / 2; half >= 1; half >>= 1) {
-    if (wave >= half && wave < 2 * half) {
+  for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+      for (int r = 0; r < 4; ++r) red[wave][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
+  __syncthreads();
+  for (int mb = wave; mb < MB && mb < a.m_tiles; mb += WAVES) {
+  v4f sum[NB];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) red[wave - half][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
-    }
-    __syncthreads();
-    if (wave < half) {
+  for (int nb = 0; nb < NB; ++nb) {
+    sum[nb] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+    for (int w = 0; w < WAVES; ++w)
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[wave][(nb * MB + mb) * 4 + r][lane];
-    }
-    __syncthreads();
+      for (int r = 0; r < 4; ++r) sum[nb][r] += red[w][(nb * MB + mb) * 4 + r][lane];
   }
-  if (wave > 0) return;
-
   const int col = lane & 15, rq = (lane >> 4) * 4;
-  float sc[MB];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) sc[mb] = s_scale[min(mb * 16 + col, Mpad - 1)];
+  const int m = mb * 16 + col;
+  const float sc = s_scale[m];
 
   if (EPI == DEPI_STORE) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      if (nt0 + nb >= a.n_tiles) continue;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const int m = mb * 16 + col;
-        if (m >= a.M) continue;
-        *reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = acc[nb][mb] * sc[mb];
-      }
+      if (nt0 + nb >= a.n_tiles || m >= a.M) continue;
+      *reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = sum[nb] * sc;
     }
   } else if (EPI == DEPI_RESID) {
 #pragma unroll
@@ -169,109 +178,101 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 4 ? (MB > 4 ? 2 : 3) : 1)) vo
       if (nt0 + nb >= a.n_tiles) continue;
       const int n = (nt0 + nb) * 16 + rq;
       const v4f g = *reinterpret_cast<const v4f*>(a.gain + n);
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const int m = mb * 16 + col;
-        const bool live = m < a.M;
-        v4f hv = v4f{0.f, 0.f, 0.f, 0.f};
-        if (live) {
-          float* hp = a.out_f32 + (size_t)m * a.ld_out + n;
-          hv = *reinterpret_cast<const v4f*>(hp) + acc[nb][mb];
-          *reinterpret_cast<v4f*>(hp) = hv;
-          uint2 pk;
-          pk.x = pack_h16x2(hv[0] * g[0] * sc[mb], hv[1] * g[1] * sc[mb]);
-          pk.y = pack_h16x2(hv[2] * g[2] * sc[mb], hv[3] * g[3] * sc[mb]);
-          *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, n, Mpad)) = pk;
-        }
-        float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
-        ss += __shfl_xor(ss, 16, 64);
-        ss += __shfl_xor(ss, 32, 64);
-        if (lane < 16 && live) a.ss_out[(size_t)(nt0 + nb) * Mpad + m] = ss;
+      const bool live = m < a.M;
+      v4f hv = v4f{0.f, 0.f, 0.f, 0.f};
+      if (live) {
+        float* hp = a.out_f32 + (size_t)m * a.ld_out + n;
+        hv = *reinterpret_cast<const v4f*>(hp) + sum[nb];
+        *reinterpret_cast<v4f*>(hp) = hv;
+        uint2 pk;
+        pk.x = pack_h16x2(hv[0] * g[0] * sc, hv[1] * g[1] * sc);
+        pk.y = pack_h16x2(hv[2] * g[2] * sc, hv[3] * g[3] * sc);
+        *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, n, Mpad)) = pk;
       }
+      float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
+      ss += __shfl_xor(ss, 16, 64);
+      ss += __shfl_xor(ss, 32, 64);
+      if (lane < 16 && live) a.ss_out[(size_t)(nt0 + nb) * Mpad + m] = ss;
     }
   } else if (EPI == DEPI_SWIGLU) {
+    // weight row tiles alternate gate / up: tile 2j holds gate rows 16j.., tile 2j+1 the up rows
 #pragma unroll
     for (int nb = 0; nb < NB; nb += 2) {
-      if (nt0 + nb >= a.n_tiles) continue;
+      if (nt0 + nb >= a.n_tiles || m >= a.M) continue;
       const int f = ((nt0 + nb) >> 1) * 16 + rq;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const int m = mb * 16 + col;
-        if (m >= a.M) continue;
-        const v4f g = acc[nb][mb] * sc[mb], u = acc[(nb + 1) % NB][mb] * sc[mb];
-        uint2 pk;
-        pk.x = pack_h16x2(silu_d(g[0]) * u[0], silu_d(g[1]) * u[1]);
-        pk.y = pack_h16x2(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3]);
-        *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, f, Mpad)) = pk;
-      }
+      const v4f g = sum[nb] * sc, u = sum[(nb + 1) % NB] * sc;
+      uint2 pk;
+      pk.x = pack_h16x2(silu_d(g[0]) * u[0], silu_d(g[1]) * u[1]);
+      pk.y = pack_h16x2(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3]);
+      *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, f, Mpad)) = pk;
     }
   } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this workgroup's vocabulary slice
     const SampleCtl ctl = *a.ctl;
     const int step = *a.d_step;
+    Lse lse = lse_empty();
+    float by = -INFINITY, bz = 0.f;
+    int bi = 0x7fffffff;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      const int m = mb * 16 + col;
-      Lse lse = lse_empty();
-      float by = -INFINITY, bz = 0.f;
-      int bi = 0x7fffffff;
+    for (int nb = 0; nb < NB; ++nb) {
+      if (nt0 + nb >= a.n_tiles) continue;
+      const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
+      uint4 rb = make_uint4(0, 0, 0, 0);
+      if (!ctl.greedy)
+        rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u), ctl.key0,
+                           ctl.key1);
+      const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        if (nt0 + nb >= a.n_tiles) continue;
-        const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
-        uint4 rb = make_uint4(0, 0, 0, 0);
-        if (!ctl.greedy)
-          rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u), ctl.key0,
-                             ctl.key1);
-        const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float z = acc[nb][mb][r] * sc[mb];
-          const float zt = ctl.greedy ? z : z * ctl.inv_temp;
-          lse_push(lse, zt);
-          const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
-          if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: the first maximum wins
-        }
-      }
-#pragma unroll
-      for (int o = 16; o <= 32; o <<= 1) {
-        const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
-        const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
-        const int oi = __shfl_xor(bi, o, 64);
-        lse = lse_merge(lse, ol);
-        if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
-      }
-      if (lane < 16 && m < a.M) {
-        DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)blockIdx.x * a.M + m;
-        p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
+      for (int r = 0; r < 4; ++r) {
+        const float z = sum[nb][r] * sc;
+        const float zt = ctl.greedy ? z : z * ctl.inv_temp;
+        lse_push(lse, zt);
+        const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
+        if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: the first maximum wins
       }
     }
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+      const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
+      const int oi = __shfl_xor(bi, o, 64);
+      lse = lse_merge(lse, ol);
+      if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
+    }
+    if (lane < 16 && m < a.M) {
+      DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)blockIdx.x * a.M + m;
+      p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
+    }
   }
+  }  // token tiles of this wavefront
 }
 
-template <int NB, int MB, int WAVES, int PF>
+template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW>
 static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
   const dim3 grid((a.n_tiles + NB - 1) / NB);
   const dim3 block(WAVES * 64);
   switch (epi) {
-    case DEPI_STORE: k_gemm_dec<NB, MB, WAVES, PF, DEPI_STORE><<<grid, block, 0, st>>>(a); break;
-    case DEPI_RESID: k_gemm_dec<NB, MB, WAVES, PF, DEPI_RESID><<<grid, block, 0, st>>>(a); break;
-    case DEPI_SWIGLU: k_gemm_dec<NB, MB, WAVES, PF, DEPI_SWIGLU><<<grid, block, 0, st>>>(a); break;
-    default: k_gemm_dec<NB, MB, WAVES, PF, DEPI_SAMPLE><<<grid, block, 0, st>>>(a); break;
+    case DEPI_STORE: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_STORE><<<grid, block, 0, st>>>(a); break;
+    case DEPI_RESID: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_RESID><<<grid, block, 0, st>>>(a); break;
+    case DEPI_SWIGLU: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU><<<grid, block, 0, st>>>(a); break;
+    default: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SAMPLE><<<grid, block, 0, st>>>(a); break;
   }
 }
 
 // Narrow shape: one weight row tile per workgroup, K split over 8 or 16 wavefronts (QKV, O, down).
 template <int MB>
 static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
-  if (MB > 4) launch_dec_t<1, MB, 8, 2>(a, epi, st);
-  else if (a.k_tiles >= 128) launch_dec_t<1, MB, 16, 3>(a, epi, st);
-  else launch_dec_t<1, MB, 8, 3>(a, epi, st);
+  if constexpr (MB > 4) {
+    launch_dec_t<1, MB, 8, 2, 2, 1>(a, epi, st);
+  } else {
+    if (a.k_tiles >= 128) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st);
+    else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st);
+  }
 }
 // Wide shape: many row tiles (gate/up, LM head): NB tiles per workgroup, K split over 4 wavefronts.
 template <int MB>
 static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
-  if (MB > 4) launch_dec_t<2, MB, 4, 2>(a, epi, st);
-  else launch_dec_t<4, MB, 4, 2>(a, epi, st);
+  if constexpr (MB > 4) launch_dec_t<2, MB, 4, 2, 2, 2>(a, epi, st);
+  else launch_dec_t<4, MB, 4, 2, 2, 2>(a, epi, st);
 }
 
 int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
@@ -408,91 +409,190 @@ __device__ __forceinline__ h16_t* dec_page(const KvPool& pool, int layer, int wh
          ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)DPAGE;
 }
 
-__global__ __launch_bounds__(256) void k_attn_dec(AttnDecArgs a) {
+constexpr int AW = 8;        // wavefronts per workgroup
+constexpr int AGMAX = 8;     // query heads per kv head at most
+constexpr int ATAB = 512;    // page-table entries of one chunk kept in LDS
+
+struct KvFrags {
+  v8bf k[2][4];
+  v4u v[8];
+};
+__device__ __forceinline__ KvFrags load_kv(const h16_t* K0, const h16_t* K1, const h16_t* V0, const h16_t* V1,
+                                           int lane) {
+  KvFrags f;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    f.k[0][kb] = load_frag(K0 + kb * 512, lane);
+    f.k[1][kb] = load_frag(K1 + kb * 512, lane);
+  }
+  const int voff = (lane & 15) * kPageTokens + 4 * (lane >> 4);
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb) {
+    const uint2 x = *reinterpret_cast<const uint2*>(V0 + cb * 256 + voff);
+    const uint2 y = *reinterpret_cast<const uint2*>(V1 + cb * 256 + voff);
+    f.v[cb] = v4u{x.x, x.y, y.x, y.y};
+  }
+  return f;
+}
+
+// One step (two pages, 32 tokens from tok0) of a single block of query columns on loaded fragments.
+__device__ __forceinline__ void attn_step1(const KvFrags& f, int tok0, const v8bf (&qf)[4], int qpos, float scale,
+                                           AttnState<1>& st, int lane) {
+  const int lg = lane >> 4;
+  v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    s0 = mfma16(f.k[0][kb], qf[kb], s0);
+    s1 = mfma16(f.k[1][kb], qf[kb], s1);
+  }
+  float sv[8];
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int t0 = tok0 + 4 * lg + r, t1 = t0 + 16;
+    sv[r] = (t0 <= qpos) ? s0[r] * scale : -INFINITY;
+    sv[4 + r] = (t1 <= qpos) ? s1[r] * scale : -INFINITY;
+    tmax = fmaxf(tmax, fmaxf(sv[r], sv[4 + r]));
+  }
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  const float m_new = fmaxf(st.m[0], tmax);
+  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+  const float corr = expf(st.m[0] - m_safe);
+  float p[8], psum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    p[e] = expf(sv[e] - m_safe);
+    psum += p[e];
+  }
+  st.l[0] = st.l[0] * corr + psum;
+  st.m[0] = m_new;
+  v4u pk;
+  pk[0] = pack_h16x2(p[0], p[1]);
+  pk[1] = pack_h16x2(p[2], p[3]);
+  pk[2] = pack_h16x2(p[4], p[5]);
+  pk[3] = pack_h16x2(p[6], p[7]);
+  const v8bf pf = __builtin_bit_cast(v8bf, pk);
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+    st.o[0][cb] = mfma16(__builtin_bit_cast(v8bf, f.v[cb]), pf, st.o[0][cb] * corr);
+}
+
+__global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   __shared__ __attribute__((aligned(16))) h16_t q_s[16][DHD];
-  __shared__ float s_o[4][16][DHD + 1];
-  __shared__ float s_m[4][16], s_l[4][16];
+  __shared__ float s_o[AW][AGMAX][DHD + 1];
+  __shared__ float s_m[AW][16], s_l[AW][16];
+  __shared__ int s_table[ATAB];
   __shared__ int s_last;
   const int b = blockIdx.x, g = blockIdx.y, chunk = blockIdx.z;
   const int Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
-  const int pos = a.pos_base + *a.d_step;
-  const int n_ctx_pages = pos / kPageTokens + 1;
-  const int p_lo = chunk * a.chunk_pages, p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
-  if (p_lo >= p_hi) return;
-  const int n_act = (n_ctx_pages + a.chunk_pages - 1) / a.chunk_pages;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, lg = lane >> 4;
   const KvPool& pool = a.pool;
   const int* table = pool.page_table + (size_t)b * pool.max_pages;
+  const int p_lo = chunk * a.chunk_pages;
+  // ---- loads that do not depend on the position: step counter, this chunk's page ids, the raw
+  // q/k/v row, and (speculatively) the first pair of pages of this wavefront
+  const int step = *a.d_step;
+  for (int i = tid; i < a.chunk_pages; i += AW * 64) s_table[i] = table[min(p_lo + i, pool.max_pages - 1)];
   const float* row = a.qkv + (size_t)b * (Hq + 2 * Hkv) * DHD;
+  float qraw[2] = {0.f, 0.f};
+  const int qj = tid >> 6, qi = tid & 63;  // wavefront j rotates head j (AW >= G)
+  if (qj < G) {
+    qraw[0] = row[(size_t)(g * G + qj) * DHD + qi];
+    qraw[1] = row[(size_t)(g * G + qj) * DHD + qi + 64];
+  }
+  const int pg0 = p_lo + 2 * wave;
+  KvFrags cur;
+  {
+    const int i0 = table[min(pg0, pool.max_pages - 1)], i1 = table[min(pg0 + 1, pool.max_pages - 1)];
+    cur = load_kv(dec_page(pool, a.layer, 0, i0, g), dec_page(pool, a.layer, 0, i1, g),
+                  dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
+  }
+  // ---- position-dependent part
+  const int pos = a.pos_base + step;
+  const int n_ctx_pages = pos / kPageTokens + 1;
+  const int p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
+  if (p_lo >= p_hi) return;
+  const int n_act = (n_ctx_pages + a.chunk_pages - 1) / a.chunk_pages;
   const float* cs = a.cos + (size_t)pos * (DHD / 2);
   const float* sn = a.sin + (size_t)pos * (DHD / 2);
-  // ---- rotate q (G heads x 64 pairs) into LDS
-  for (int e = tid; e < G * 64; e += 256) {
-    const int j = e >> 6, i = e & 63;
-    const float x0 = row[(size_t)(g * G + j) * DHD + i], x1 = row[(size_t)(g * G + j) * DHD + i + 64];
-    const float c = cs[i], s = sn[i];
-    q_s[j][i] = f32_to_h16(x0 * c - x1 * s);
-    q_s[j][i + 64] = f32_to_h16(x1 * c + x0 * s);
+  if (qj < G) {
+    const float c = cs[qi], s = sn[qi];
+    q_s[qj][qi] = f32_to_h16(qraw[0] * c - qraw[1] * s);
+    q_s[qj][qi + 64] = f32_to_h16(qraw[1] * c + qraw[0] * s);
   }
-  // ---- the owner of the current position appends K and V to the cache
+  // the owner of the current position appends K and V to the cache (last wavefront: it is idle above when G < AW)
   const int cur_page = pos / kPageTokens;
-  if (cur_page >= p_lo && cur_page < p_hi) {
+  const bool owner_wg = cur_page >= p_lo && cur_page < p_hi;
+  if (owner_wg && wave == AW - 1) {
     const int page = table[cur_page], slot = pos % kPageTokens;
     h16_t* kp = dec_page(pool, a.layer, 0, page, g);
     h16_t* vp = dec_page(pool, a.layer, 1, page, g);
-    if (tid < 64) {
-      const int i = tid;
-      const float x0 = row[(size_t)(Hq + g) * DHD + i], x1 = row[(size_t)(Hq + g) * DHD + i + 64];
-      const float c = cs[i], s = sn[i];
-      const int c0 = i, c1 = i + 64;
-      kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(x0 * c - x1 * s);
-      kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(x1 * c + x0 * s);
-    } else if (tid < 192) {
-      const int c = tid - 64;
-      vp[c * kPageTokens + slot] = f32_to_h16(row[(size_t)(Hq + Hkv + g) * DHD + c]);
-    }
+    const int i = lane;
+    const float x0 = row[(size_t)(Hq + g) * DHD + i], x1 = row[(size_t)(Hq + g) * DHD + i + 64];
+    const float v0 = row[(size_t)(Hq + Hkv + g) * DHD + i], v1 = row[(size_t)(Hq + Hkv + g) * DHD + i + 64];
+    const float c = cs[i], s = sn[i];
+    const int c0 = i, c1 = i + 64;
+    kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(x0 * c - x1 * s);
+    kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(x1 * c + x0 * s);
+    vp[c0 * kPageTokens + slot] = f32_to_h16(v0);
+    vp[c1 * kPageTokens + slot] = f32_to_h16(v1);
   }
-  __syncthreads();  // q_s complete; this workgroup's K/V stores are visible to its own loads
+  __syncthreads();  // q_s, s_table complete; this workgroup's K/V stores are visible to its own loads
 
-  v8bf qf[1][4];
-  int qpos[1];
-  qpos[0] = (col < G) ? pos : -1;
+  v8bf qf[4];
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
     v4u raw = {0u, 0u, 0u, 0u};
     if (col < G) raw = *reinterpret_cast<const v4u*>(&q_s[col][kb * 32 + 8 * lg]);
-    qf[0][kb] = __builtin_bit_cast(v8bf, raw);
+    qf[kb] = __builtin_bit_cast(v8bf, raw);
   }
+  const int qpos = (col < G) ? pos : -1;
   AttnState<1> st;
   attn_init(st);
   const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
-  for (int pg = p_lo + 2 * wave; pg < p_hi; pg += 8) {
-    const int id0 = table[pg], id1 = table[min(pg + 1, n_ctx_pages - 1)];
-    attn_pair<1>(dec_page(pool, a.layer, 0, id0, g), dec_page(pool, a.layer, 0, id1, g),
-                 dec_page(pool, a.layer, 1, id0, g), dec_page(pool, a.layer, 1, id1, g), pg * kPageTokens, qf, qpos,
-                 1, scale, st, lane);
+  auto page_id = [&](int pg) { return s_table[min(pg, n_ctx_pages - 1) - p_lo]; };
+  // the speculative load may have raced with the append above: redo it if it covers the current page
+  if (owner_wg && (cur_page == pg0 || cur_page == pg0 + 1) && pg0 < p_hi) {
+    const int i0 = page_id(pg0), i1 = page_id(pg0 + 1);
+    cur = load_kv(dec_page(pool, a.layer, 0, i0, g), dec_page(pool, a.layer, 0, i1, g),
+                  dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
+  }
+  for (int pg = pg0; pg < p_hi; pg += 2 * AW) {
+    const int pn = pg + 2 * AW;
+    KvFrags nxt = cur;
+    if (pn < p_hi) {
+      const int i0 = page_id(pn), i1 = page_id(pn + 1);
+      nxt = load_kv(dec_page(pool, a.layer, 0, i0, g), dec_page(pool, a.layer, 0, i1, g),
+                    dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
+    }
+    attn_step1(cur, pg * kPageTokens, qf, qpos, scale, st, lane);
+    cur = nxt;
   }
   float l = st.l[0];
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
+  if (col < AGMAX) {
 #pragma unroll
-  for (int cb = 0; cb < 8; ++cb)
+    for (int cb = 0; cb < 8; ++cb)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) s_o[wave][col][cb * 16 + 4 * lg + r] = st.o[0][cb][r];
+      for (int r = 0; r < 4; ++r) s_o[wave][col][cb * 16 + 4 * lg + r] = st.o[0][cb][r];
+  }
   if (lg == 0) {
     s_m[wave][col] = st.m[0];
     s_l[wave][col] = l;
   }
   __syncthreads();
-  // ---- merge the four wavefronts: thread t < 16 G owns (column c, 8 consecutive dims)
+  // ---- merge the wavefronts: thread t < 16 G owns (column c, 8 consecutive dims)
   const bool owner = tid < G * (DHD / 8);
   const int c = tid / (DHD / 8), d0 = (tid % (DHD / 8)) * 8;
   float mm = -INFINITY, ll = 0.f, acc[8] = {};
   if (owner) {
-    mm = fmaxf(fmaxf(s_m[0][c], s_m[1][c]), fmaxf(s_m[2][c], s_m[3][c]));
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < AW; ++w) mm = fmaxf(mm, s_m[w][c]);
+#pragma unroll
+    for (int w = 0; w < AW; ++w) {
       const float f = expf(s_m[w][c] - mm);
       ll += f * s_l[w][c];
 #pragma unroll
@@ -549,7 +649,7 @@ __global__ __launch_bounds__(256) void k_attn_dec(AttnDecArgs a) {
 }
 
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {
-  k_attn_dec<<<dim3(B, a.Hkv, a.n_chunks), 256, 0, st>>>(a);
+  k_attn_dec<<<dim3(B, a.Hkv, a.n_chunks), AW * 64, 0, st>>>(a);
 }
 
 }  // namespace bf16

@@ -178,16 +178,18 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.ks_qkv = choose_ksplit(D.nt_qkv, D.kt_d, p.bt);
   p.ks_o = choose_ksplit(D.nt_d, D.kt_nq, p.bt);
   p.ks_down = choose_ksplit(D.nt_d, D.kt_F, p.bt);
-  // context split of the decode attention: about 512 workgroups at full context, >= 8 pages each
-  const int want = std::max(1, 512 / std::max(1, p.B * D.Hkv));
+  // context split of the decode attention, only for small batches: the cross-workgroup merge costs
+  // more than it gains once there are about 128 (sequence, kv head) workgroups of 8 wavefronts
+  const int want = std::max(1, 128 / std::max(1, p.B * D.Hkv));
   p.n_chunks = std::max(1, std::min(want, (p.max_pages + 7) / 8));
   p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;
+  p.chunk_pages = std::min(p.chunk_pages, 512);  // page ids of a chunk are staged in LDS
   p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
   const size_t Mpad = (size_t)p.bt * 16;
   const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;
   p.part = cv.take<float>(part);
   p.attn_part = cv.take<float>(bf16::attn_part_floats(p.B, D.Hkv, G, p.n_chunks));
-  p.lm_part = cv.take<float>((size_t)bf16::sample_groups(D.nt_V, p.bt) * p.B * 8);
+  p.lm_part = cv.take<float>((size_t)((D.nt_V + 1) / 2) * p.B * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
   p.ctl = cv.take<bf16::SampleCtl>(1);
   p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
