@@ -62,8 +62,12 @@ struct DecGemmArgs {
   const float* gain;     // RESID: gain of the next norm
   const SampleCtl* ctl;
   const int* d_step;
+  int ksplit;            // PARTIAL: K splits (grid.y); out_f32 = partial sums [ksplit][m_tiles*16][ld_out]
+  float* rs_out;         // PARTIAL: 1/rms of every row of the state described by ss_cur
 };
-enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3 };
+enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3, DEC_PARTIAL = 4 };
+void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
+                  h16_t* x, float* ss_out, int M, hipStream_t st);
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);
 int dec_wide_nb(int m_tiles);
 void embed_dec(float* h, const int* ids, int B, const bf16_t* E, int d, int vocab, int* err_flag, const float* gain,

@@ -74,7 +74,7 @@ __device__ __forceinline__ void wave_gemm_dec(const h16_t* __restrict__ Wt, int 
 
 __device__ __forceinline__ float silu_d(float g) { return g / (1.0f + expf(-g)); }
 
-enum { DEPI_STORE = 0, DEPI_RESID = 1, DEPI_SWIGLU = 2, DEPI_SAMPLE = 3 };
+enum { DEPI_STORE = 0, DEPI_RESID = 1, DEPI_SWIGLU = 2, DEPI_SAMPLE = 3, DEPI_PARTIAL = 4 };
 
 struct DecSamplePartial {
   float m, s, y;
@@ -93,11 +93,14 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   const int Mpad = a.m_tiles * 16;
   // Row scales (consumers need r_new / r_old, producers r of the state they update).  Thread t sums
   // tiles part, part + P, ... of row t % Mpad; the P partial sums are then added in index order.
-  {
+  // A split-K launch only needs them in the kernel that finishes the sum: its first workgroup
+  // computes them on the side and leaves them in rs_out.
+  constexpr bool kProducer = (EPI == DEPI_RESID || EPI == DEPI_PARTIAL);
+  if (EPI != DEPI_PARTIAL || (blockIdx.x == 0 && blockIdx.y == 0)) {
     constexpr int NT = WAVES * 64;
     const int P = NT / Mpad;  // Mpad <= 128 <= NT
     const int m = tid % Mpad, part = tid / Mpad;
-    const bool two = (EPI != DEPI_RESID) && a.ss_cur && a.ss_old != a.ss_cur;
+    const bool two = !kProducer && a.ss_cur && a.ss_old != a.ss_cur;
     float sa = 0.f, sb = 0.f;
     if (a.ss_cur && part < P) {
       // batches of 8 independent loads, then the adds in index order
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
     __syncthreads();
     if (tid < Mpad) {
       float sc = 1.f;
-      if (a.ss_cur && (EPI == DEPI_RESID || two)) {
+      if (a.ss_cur && (kProducer || two)) {
         float ta = 0.f, tb = 0.f;
         for (int q = 0; q < P; ++q) {
           ta += s_part[0][q * Mpad + tid];
@@ -133,10 +136,17 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
         if (two) sc *= sqrtf(tb * a.inv_d + a.eps);
       }
       s_scale[tid] = sc;
+      if (EPI == DEPI_PARTIAL) a.rs_out[tid] = sc;
     }
   }
-  const int per_wave = (a.k_tiles + WAVES - 1) / WAVES;
-  const int k0 = wave * per_wave, k1 = min(a.k_tiles, k0 + per_wave);
+  int kbeg = 0, kend = a.k_tiles;
+  if (EPI == DEPI_PARTIAL) {
+    const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
+    kbeg = blockIdx.y * per_split;
+    kend = min(a.k_tiles, kbeg + per_split);
+  }
+  const int per_wave = (max(kend - kbeg, 0) + WAVES - 1) / WAVES;
+  const int k0 = kbeg + wave * per_wave, k1 = min(kend, k0 + per_wave);
   v4f acc[NB][MB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
@@ -164,9 +174,16 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   }
   const int col = lane & 15, rq = (lane >> 4) * 4;
   const int m = mb * 16 + col;
-  const float sc = s_scale[m];
+  const float sc = (EPI == DEPI_PARTIAL) ? 1.f : s_scale[m];
 
-  if (EPI == DEPI_STORE) {
+  if (EPI == DEPI_PARTIAL) {
+    float* P = a.out_f32 + (size_t)blockIdx.y * Mpad * a.ld_out;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      if (nt0 + nb >= a.n_tiles) continue;
+      *reinterpret_cast<v4f*>(P + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = sum[nb];
+    }
+  } else if (EPI == DEPI_STORE) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       if (nt0 + nb >= a.n_tiles || m >= a.M) continue;
@@ -248,9 +265,10 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW>
 static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
-  const dim3 grid((a.n_tiles + NB - 1) / NB);
+  const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1);
   const dim3 block(WAVES * 64);
   switch (epi) {
+    case DEPI_PARTIAL: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL><<<grid, block, 0, st>>>(a); break;
     case DEPI_STORE: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_STORE><<<grid, block, 0, st>>>(a); break;
     case DEPI_RESID: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_RESID><<<grid, block, 0, st>>>(a); break;
     case DEPI_SWIGLU: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU><<<grid, block, 0, st>>>(a); break;
@@ -278,7 +296,7 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
 int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
 
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
-  const bool wide = (epi == DEPI_SWIGLU || epi == DEPI_SAMPLE);
+  const bool wide = (epi == DEPI_SWIGLU || epi == DEPI_SAMPLE || epi == DEPI_PARTIAL);
   const int mb = a.m_tiles <= 1 ? 1 : a.m_tiles <= 2 ? 2 : a.m_tiles <= 4 ? 4 : 8;
   if (wide) {
     switch (mb) {
@@ -295,6 +313,49 @@ void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
       default: launch_dec_narrow<8>(a, epi, st); break;
     }
   }
+}
+
+// ---------------------------------------------------------------- split-K sum + residual epilogue
+// h += sum_s P[s]; x' = fp16(h g r_old); per-tile sums of squares.  One workgroup per 16 output
+// columns; a thread owns (row, 4 consecutive columns).  The partial sums are added in split order.
+__global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ P, int ksplit, int Mpad, int N,
+                                                      float* h, const float* __restrict__ gain,
+                                                      const float* __restrict__ rs, h16_t* x, float* ss_out, int M) {
+  const int nt = blockIdx.x, cg = threadIdx.x & 3;
+  const int n = nt * 16 + cg * 4;
+  const v4f g = *reinterpret_cast<const v4f*>(gain + n);
+  for (int m = threadIdx.x >> 2; m < Mpad; m += 64) {
+    const bool live = m < M;
+    v4f hv = v4f{0.f, 0.f, 0.f, 0.f};
+    if (live) {
+      v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
+      for (int s0 = 0; s0 < ksplit; s0 += 8) {
+        v4f v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          v[u] = (s0 + u < ksplit) ? *reinterpret_cast<const v4f*>(P + ((size_t)(s0 + u) * Mpad + m) * N + n)
+                                   : v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = acc + v[u];
+      }
+      float* hp = h + (size_t)m * N + n;
+      hv = *reinterpret_cast<const v4f*>(hp) + acc;
+      *reinterpret_cast<v4f*>(hp) = hv;
+      const float sc = rs[m];
+      uint2 pk;
+      pk.x = pack_h16x2(hv[0] * g[0] * sc, hv[1] * g[1] * sc);
+      pk.y = pack_h16x2(hv[2] * g[2] * sc, hv[3] * g[3] * sc);
+      *reinterpret_cast<uint2*>(x + act_off(m, n, Mpad)) = pk;
+    }
+    float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
+    ss += __shfl_xor(ss, 1, 64);
+    ss += __shfl_xor(ss, 2, 64);
+    if (cg == 0 && live) ss_out[(size_t)nt * Mpad + m] = ss;
+  }
+}
+void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
+                  h16_t* x, float* ss_out, int M, hipStream_t st) {
+  k_resid_reduce<<<N / 16, 256, 0, st>>>(P, ksplit, m_tiles * 16, N, h, gain, rs, x, ss_out, M);
 }
 
 // ---------------------------------------------------------------- embedding of the fed-back token

@@ -62,6 +62,7 @@ struct RolloutPlan {
   float* ssA;         // per-tile sums of squares of the residual rows (two generations)
   float* ssB;
   int* attn_counters; // arrival counters of the decode-attention context chunks
+  float* rs_buf;      // 1/rms per row, handed from the split-K down projection to its reduction
   int chunk_pages, n_chunks;       // decode-attention context split
   int ks_qkv, ks_o, ks_down;       // split-K factors of the decode GEMMs
   int bt;                          // 16-row tiles covering B

@@ -195,6 +195,7 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
   p.ssB = cv.take<float>((size_t)D.nt_d * Mpad);
   p.attn_counters = cv.take<int>((size_t)p.B * D.Hkv);
+  p.rs_buf = cv.take<float>(Mpad);
 }
 
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
@@ -271,11 +272,14 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     gu.Wt = (const h16_t*)L.wgu; gu.Xt = x; gu.n_tiles = D.nt_gu; gu.k_tiles = D.kt_d;
     gu.ss_cur = ss[cur]; gu.ss_old = ss[old]; gu.out_h16 = a;
     bf16::gemm_dec(gu, bf16::DEC_SWIGLU, st);
+    // down projection: split-K partial sums (enough workgroups to pull full bandwidth), then one
+    // launch that adds them in split order and does the residual / norm bookkeeping
     bf16::DecGemmArgs r2 = g;
     r2.Wt = (const h16_t*)L.wdown; r2.Xt = a; r2.n_tiles = D.nt_d; r2.k_tiles = D.kt_F;
-    r2.ss_cur = ss[cur]; r2.out_f32 = h; r2.ld_out = D.d; r2.out_h16 = x; r2.ss_out = ss[cur ^ 1];
-    r2.gain = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
-    bf16::gemm_dec(r2, bf16::DEC_RESID, st);
+    r2.ss_cur = ss[cur]; r2.out_f32 = p.part; r2.ld_out = D.d; r2.ksplit = p.ks_down; r2.rs_out = p.rs_buf;
+    bf16::gemm_dec(r2, bf16::DEC_PARTIAL, st);
+    bf16::resid_reduce(p.part, p.ks_down, bt, D.d, h, (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm,
+                       p.rs_buf, x, ss[cur ^ 1], B, st);
     old = cur; cur ^= 1;
   }
   *ss_cur_out = ss[cur];
