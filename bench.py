@@ -144,6 +144,11 @@ def main() -> int:
     for i in range(args.warmup):
         step(100 + i)
     torch.cuda.synchronize()
+    # dominant decode kernel (gate/up projection: half of the layer weight bytes): every 32nd decode
+    # step of the timed region is launched directly with a HIP-event pair around each of its launches
+    timed_kernel = cfg.dtype == "bf16"
+    if timed_kernel:
+        mtmc.mtmc_kernel_timer(handle, mtmc.MTMC_KERNEL_GATE_UP, 32)
     rollout_ms, score_ms = [], []
     t_begin = time.perf_counter()
     for i in range(args.steps):
@@ -154,6 +159,10 @@ def main() -> int:
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_begin
     mtmc.mtmc_poll_errors(handle)
+    k_ms, k_launches = (0.0, 0)
+    if timed_kernel:
+        k_ms, k_launches = mtmc.mtmc_kernel_timer_read(handle)
+        mtmc.mtmc_kernel_timer(handle, 0, 0)
 
     ms_per_step = 1e3 * total_s / args.steps
     new_tokens = B * max_new
@@ -163,7 +172,17 @@ def main() -> int:
     # rollout time is prefill + (max_new - 1) decode steps; prefill is charged to the decode steps.
     step_bytes, w_bytes, kv_bytes = decode_bytes_per_step(cfg, n_prompts, prompt_len, n_samples, max_new)
     decode_ms = r_ms / max(1, max_new - 1)
-    achieved_gbs = step_bytes / (decode_ms * 1e-3) / 1e9
+    step_gbs = step_bytes / (decode_ms * 1e-3) / 1e9
+    gate_up_bytes = 2 * cfg.d_ffn * cfg.d_model * 2   # gate and up matrices, 2 bytes per weight, read once
+    if k_launches > 0:
+        k_us = 1e3 * k_ms / k_launches
+        roofline = {"bound": "hbm", "achieved": gate_up_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gate_up_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                    "kernel": "k_gemm_dec<..., SWIGLU> (gate/up projection, one launch per layer per decode step)",
+                    "bytes_per_launch": gate_up_bytes, "us_per_launch": k_us, "timed_launches": k_launches}
+    else:
+        roofline = {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": step_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "whole decode step"}
     result = {
         "metric": "rollout tokens/sec @1.5B-class bs64 bf16; decode HBM GB/s + scoring MFMA % peak",
         "value": new_tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -175,10 +194,11 @@ def main() -> int:
                                f"prompt {prompt_len}, {max_new} new tokens at T=1; then scoring of the {B} x {seq_len} sequences",
                    "step": "mtmc_rollout + mtmc_score" if not args.no_score else "mtmc_rollout"},
         "rollout_tokens_per_s": new_tokens / (r_ms * 1e-3), "rollout_ms": r_ms,
-        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "decode step (all kernels of one token step; prefill time included)",
-                     "bytes_per_launch": step_bytes, "ms_per_launch": decode_ms},
+        "roofline": roofline,
+        "decode_step": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": step_bytes, "ms_per_step": decode_ms,
+                        "note": "algorithmic bytes of an average decode step (weights once + KV with shared prompt pages) "
+                                "over rollout time / decode steps (prefill time included)"},
         "setup_s": setup_s,
     }
     if not args.no_score:

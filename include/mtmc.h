@@ -138,6 +138,22 @@ int mtmc_poll_errors(const mtmc_weights* w, void* stream);
 #define MTMC_OPT_HIP_GRAPH 1
 int mtmc_set_option(mtmc_weights* w, int option, int value);
 
+/*
+ * Diagnostics for measurement: HIP-event timing of one class of decode kernel inside mtmc_rollout
+ * (MTMC_BF16).  While a class is selected, every `every_n_steps`-th decode step is launched
+ * directly instead of through the captured graph, with an event pair around each launch of
+ * that class (same kernels, same results).  mtmc_kernel_timer_read synchronises `stream` and
+ * returns the summed duration and the number of timed launches since the last read.
+ * kernel_class 0 switches the timer off.
+ */
+#define MTMC_KERNEL_QKV       1  /* QKV projection                              */
+#define MTMC_KERNEL_ATTENTION 2  /* rope + KV append + paged attention          */
+#define MTMC_KERNEL_GATE_UP   3  /* gate/up projection with SwiGLU epilogue     */
+#define MTMC_KERNEL_DOWN      4  /* down projection (split-K partial sums)      */
+#define MTMC_KERNEL_LM_HEAD   5  /* LM head + log-softmax + Gumbel-max + merge  */
+int mtmc_kernel_timer(mtmc_weights* w, int kernel_class, int every_n_steps);
+int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches);
+
 /* Message of the last failing call on this thread; valid until the next library call. */
 const char* mtmc_last_error(void);
 

@@ -122,6 +122,18 @@ extern "C" int mtmc_set_option(mtmc_weights* w, int option, int value) {
   return MTMC_OK;
 }
 
+extern "C" int mtmc_kernel_timer(mtmc_weights* w, int kernel_class, int every_n_steps) {
+  MTMC_REQUIRE(w != nullptr, "weights is NULL");
+  MTMC_REQUIRE(w->cfg.dtype == MTMC_BF16, "the kernel timer covers the MTMC_BF16 decode kernels");
+  MTMC_REQUIRE(kernel_class >= 0 && kernel_class <= MTMC_KERNEL_LM_HEAD && every_n_steps >= 0, "bad kernel class or period");
+  return kernel_timer_set(w, kernel_class, every_n_steps);
+}
+
+extern "C" int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches) {
+  MTMC_REQUIRE(w != nullptr && total_ms != nullptr && launches != nullptr, "NULL pointer argument");
+  return kernel_timer_read(w, (hipStream_t)stream, total_ms, launches);
+}
+
 extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
   MTMC_REQUIRE(w != nullptr, "weights is NULL");
   MTMC_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));

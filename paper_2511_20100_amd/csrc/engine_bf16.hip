@@ -22,14 +22,61 @@ struct GraphCache {
   std::mutex mu;
   std::vector<Entry> entries;
   hipStream_t capture_stream = nullptr;  // never runs work: launches on it are only recorded
+  // kernel timer (diagnostics): event pairs recorded around one class of decode kernel
+  int timer_class = 0, timer_every = 0;
+  std::vector<hipEvent_t> events;  // pool, used pairwise
+  size_t events_used = 0;
+};
+
+// Brackets launches of one kernel class with HIP events while a decode step is launched directly.
+struct KernelTimer {
+  GraphCache* gc;
+  int cls;
+  hipStream_t st;
+  void mark(int k) {
+    if (!gc || k != cls) return;
+    if (gc->events_used == gc->events.size()) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return;
+      gc->events.push_back(e);
+    }
+    (void)hipEventRecord(gc->events[gc->events_used++], st);
+  }
 };
 
 void destroy_graph_cache(mtmc_weights* w) {
   if (!w->graphs) return;
   for (auto& e : w->graphs->entries) (void)hipGraphExecDestroy(e.exec);
   if (w->graphs->capture_stream) (void)hipStreamDestroy(w->graphs->capture_stream);
+  for (hipEvent_t e : w->graphs->events) (void)hipEventDestroy(e);
   delete w->graphs;
   w->graphs = nullptr;
+}
+
+int kernel_timer_set(mtmc_weights* w, int cls, int every) {
+  if (!w->graphs) w->graphs = new GraphCache();
+  std::lock_guard<std::mutex> lock(w->graphs->mu);
+  w->graphs->timer_class = cls;
+  w->graphs->timer_every = every;
+  w->graphs->events_used = 0;
+  return MTMC_OK;
+}
+
+int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t* launches) {
+  *total_ms = 0.0;
+  *launches = 0;
+  if (!w->graphs) return MTMC_OK;
+  MTMC_HIP_CHECK(hipStreamSynchronize(st));
+  std::lock_guard<std::mutex> lock(w->graphs->mu);
+  GraphCache& gc = *w->graphs;
+  for (size_t i = 0; i + 1 < gc.events_used; i += 2) {
+    float ms = 0.f;
+    MTMC_HIP_CHECK(hipEventElapsedTime(&ms, gc.events[i], gc.events[i + 1]));
+    *total_ms += ms;
+    *launches += 1;
+  }
+  gc.events_used = 0;
+  return MTMC_OK;
 }
 
 namespace {
@@ -239,7 +286,8 @@ void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, fl
 // each) against the paged cache at position prompt_len - 1 + *d_step and leaves in xB the operand
 // of the LM head together with the row-norm bookkeeping (*ss_cur, *ss_old) its consumer needs.
 void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, KvPool pool, int pos_base,
-                   const float** ss_cur_out, const float** ss_old_out, hipStream_t st) {
+                   const float** ss_cur_out, const float** ss_old_out, hipStream_t st, KernelTimer* tm = nullptr) {
+  auto mark = [&](int k) { if (tm) tm->mark(k); };
   const mtmc_config& c = w->cfg;
   const int B = p.B, bt = p.bt;
   float* h = p.hB;
@@ -257,12 +305,16 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     bf16::DecGemmArgs q = g;
     q.Wt = (const h16_t*)L.wqkv; q.Xt = x; q.n_tiles = D.nt_qkv; q.k_tiles = D.kt_d;
     q.ss_cur = ss[cur]; q.ss_old = ss[old]; q.out_f32 = p.qkv; q.ld_out = D.nqkv;
+    mark(MTMC_KERNEL_QKV);
     bf16::gemm_dec(q, bf16::DEC_STORE, st);
+    mark(MTMC_KERNEL_QKV);
     bf16::AttnDecArgs at{};
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
     at.pos_base = pos_base; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
     at.n_chunks = p.n_chunks; at.m_tiles = bt; at.part = p.attn_part; at.counters = p.attn_counters; at.o = o;
+    mark(MTMC_KERNEL_ATTENTION);
     bf16::attention_dec(at, B, st);
+    mark(MTMC_KERNEL_ATTENTION);
     bf16::DecGemmArgs r1 = g;
     r1.Wt = (const h16_t*)L.wo; r1.Xt = o; r1.n_tiles = D.nt_d; r1.k_tiles = D.kt_nq;
     r1.ss_cur = ss[cur]; r1.out_f32 = h; r1.ld_out = D.d; r1.out_h16 = x; r1.ss_out = ss[cur ^ 1]; r1.gain = L.ffn_norm;
@@ -271,13 +323,17 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     bf16::DecGemmArgs gu = g;
     gu.Wt = (const h16_t*)L.wgu; gu.Xt = x; gu.n_tiles = D.nt_gu; gu.k_tiles = D.kt_d;
     gu.ss_cur = ss[cur]; gu.ss_old = ss[old]; gu.out_h16 = a;
+    mark(MTMC_KERNEL_GATE_UP);
     bf16::gemm_dec(gu, bf16::DEC_SWIGLU, st);
+    mark(MTMC_KERNEL_GATE_UP);
     // down projection: split-K partial sums (enough workgroups to pull full bandwidth), then one
     // launch that adds them in split order and does the residual / norm bookkeeping
     bf16::DecGemmArgs r2 = g;
     r2.Wt = (const h16_t*)L.wdown; r2.Xt = a; r2.n_tiles = D.nt_d; r2.k_tiles = D.kt_F;
     r2.ss_cur = ss[cur]; r2.out_f32 = p.part; r2.ld_out = D.d; r2.ksplit = p.ks_down; r2.rs_out = p.rs_buf;
+    mark(MTMC_KERNEL_DOWN);
     bf16::gemm_dec(r2, bf16::DEC_PARTIAL, st);
+    mark(MTMC_KERNEL_DOWN);
     bf16::resid_reduce(p.part, p.ks_down, bt, D.d, h, (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm,
                        p.rs_buf, x, ss[cur ^ 1], B, st);
     old = cur; cur ^= 1;
@@ -395,17 +451,24 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, s);
       launch_add_int(p.d_step, 1, s);
     };
-    auto decode_step = [&](hipStream_t s) {
+    auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) {
       const float *ss_cur = nullptr, *ss_old = nullptr;
-      decode_layers(w, D, gp, pool, p.prompt_len - 1, &ss_cur, &ss_old, s);
+      decode_layers(w, D, gp, pool, p.prompt_len - 1, &ss_cur, &ss_old, s, tm);
+      if (tm) tm->mark(MTMC_KERNEL_LM_HEAD);
       sample(s, ss_cur, ss_old);
+      if (tm) tm->mark(MTMC_KERNEL_LM_HEAD);
     };
+    auto decode_step = [&](hipStream_t s) { decode_step_timed(s, nullptr); };
     sample(st, nullptr, nullptr);  // xB holds the exactly normalised last prompt position
     if (p.max_new > 1) {
       hipGraphExec_t exec = nullptr;
       if (int rc = decode_graph(w, gp, st, decode_step, &exec)) return rc;
+      GraphCache* gc = w->graphs;
+      KernelTimer tm{gc, gc ? gc->timer_class : 0, st};
+      const int every = gc ? gc->timer_every : 0;
       for (int i = 1; i < p.max_new; ++i) {
-        if (exec) MTMC_HIP_CHECK(hipGraphLaunch(exec, st));
+        if (tm.cls && every > 0 && i % every == 1 % every) decode_step_timed(st, &tm);  // launched directly, with events
+        else if (exec) MTMC_HIP_CHECK(hipGraphLaunch(exec, st));
         else decode_step(st);
       }
     }

@@ -57,6 +57,10 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_score.restype = ctypes.c_int
     lib.mtmc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.mtmc_set_option.restype = ctypes.c_int
+    lib.mtmc_kernel_timer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    lib.mtmc_kernel_timer.restype = ctypes.c_int
+    lib.mtmc_kernel_timer_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.mtmc_kernel_timer_read.restype = ctypes.c_int
     lib.mtmc_poll_errors.argtypes = [vp, vp]
     lib.mtmc_poll_errors.restype = ctypes.c_int
     lib.mtmc_last_error.argtypes = []
@@ -67,7 +71,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mtmc_rollout_workspace_bytes",
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
-           "mtmc_set_option")
+           "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read")
 
 
 def mtmc_last_error() -> str:
@@ -170,6 +174,20 @@ MTMC_OPT_HIP_GRAPH = 1
 
 def mtmc_set_option(handle: int, option: int, value: int) -> None:
     _check(_lib.mtmc_set_option(handle, option, value))
+
+
+MTMC_KERNEL_QKV, MTMC_KERNEL_ATTENTION, MTMC_KERNEL_GATE_UP, MTMC_KERNEL_DOWN, MTMC_KERNEL_LM_HEAD = 1, 2, 3, 4, 5
+
+
+def mtmc_kernel_timer(handle: int, kernel_class: int, every_n_steps: int) -> None:
+    _check(_lib.mtmc_kernel_timer(handle, kernel_class, every_n_steps))
+
+
+def mtmc_kernel_timer_read(handle: int, stream: Optional[torch.cuda.Stream] = None) -> Tuple[float, int]:
+    """Returns (total milliseconds, number of timed launches) since the last read."""
+    ms, n = ctypes.c_double(), ctypes.c_int64()
+    _check(_lib.mtmc_kernel_timer_read(handle, _stream_ptr(stream), ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
 
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:

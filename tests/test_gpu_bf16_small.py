@@ -108,3 +108,21 @@ def test_graph_replay_matches_direct_launches(lib):
             assert not torch.equal(other[0], ref[0])
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+def test_kernel_timer_does_not_change_results(lib):
+    import torch
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
+    try:
+        prompts = torch.from_numpy(inputs.make_prompts(2, 17, cfg.vocab, seed=5)).cuda()
+        ref = [t.clone() for t in lib.mtmc_rollout(handle, prompts, 4, 20, 1.0, 3)]
+        lib.mtmc_kernel_timer(handle, lib.MTMC_KERNEL_GATE_UP, 4)
+        got = lib.mtmc_rollout(handle, prompts, 4, 20, 1.0, 3)
+        ms, n = lib.mtmc_kernel_timer_read(handle)
+        lib.mtmc_kernel_timer(handle, 0, 0)
+        assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1])
+        assert n == 5 * cfg.n_layers and ms > 0      # steps 1, 5, 9, 13, 17 of 19 decode steps
+    finally:
+        lib.mtmc_weights_destroy(handle)
