@@ -159,9 +159,9 @@ def main() -> int:
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_begin
     mtmc.mtmc_poll_errors(handle)
-    k_ms, k_launches = (0.0, 0)
+    k_ms, k_launches, k_empty_ms = (0.0, 0, 0.0)
     if timed_kernel:
-        k_ms, k_launches = mtmc.mtmc_kernel_timer_read(handle)
+        k_ms, k_launches, k_empty_ms = mtmc.mtmc_kernel_timer_read(handle)
         mtmc.mtmc_kernel_timer(handle, 0, 0)
 
     ms_per_step = 1e3 * total_s / args.steps
@@ -179,7 +179,8 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": gate_up_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gate_up_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
                     "kernel": "k_gemm_dec<..., SWIGLU> (gate/up projection, one launch per layer per decode step)",
-                    "bytes_per_launch": gate_up_bytes, "us_per_launch": k_us, "timed_launches": k_launches}
+                    "bytes_per_launch": gate_up_bytes, "us_per_launch": k_us, "timed_launches": k_launches,
+                    "empty_event_pair_us": 1e3 * k_empty_ms}
     else:
         roofline = {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": step_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "whole decode step"}

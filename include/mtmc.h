@@ -143,7 +143,9 @@ int mtmc_set_option(mtmc_weights* w, int option, int value);
  * (MTMC_BF16).  While a class is selected, every `every_n_steps`-th decode step is launched
  * directly instead of through the captured graph, with an event pair around each launch of
  * that class (same kernels, same results).  mtmc_kernel_timer_read synchronises `stream` and
- * returns the summed duration and the number of timed launches since the last read.
+ * returns the summed duration and the number of timed launches since the last read; if
+ * `empty_pair_ms` is not NULL it receives the mean duration of event pairs recorded back to back
+ * with nothing between them (one such pair per timed step: what the bracketing itself adds).
  * kernel_class 0 switches the timer off.
  */
 #define MTMC_KERNEL_QKV       1  /* QKV projection                              */
@@ -152,7 +154,8 @@ int mtmc_set_option(mtmc_weights* w, int option, int value);
 #define MTMC_KERNEL_DOWN      4  /* down projection (split-K partial sums)      */
 #define MTMC_KERNEL_LM_HEAD   5  /* LM head + log-softmax + Gumbel-max + merge  */
 int mtmc_kernel_timer(mtmc_weights* w, int kernel_class, int every_n_steps);
-int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches);
+int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches,
+                           double* empty_pair_ms);
 
 /* Message of the last failing call on this thread; valid until the next library call. */
 const char* mtmc_last_error(void);

@@ -129,9 +129,10 @@ extern "C" int mtmc_kernel_timer(mtmc_weights* w, int kernel_class, int every_n_
   return kernel_timer_set(w, kernel_class, every_n_steps);
 }
 
-extern "C" int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches) {
+extern "C" int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches,
+                                      double* empty_pair_ms) {
   MTMC_REQUIRE(w != nullptr && total_ms != nullptr && launches != nullptr, "NULL pointer argument");
-  return kernel_timer_read(w, (hipStream_t)stream, total_ms, launches);
+  return kernel_timer_read(w, (hipStream_t)stream, total_ms, launches, empty_pair_ms);
 }
 
 extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {

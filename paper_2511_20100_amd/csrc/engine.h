@@ -129,7 +129,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
 int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hipStream_t st);
 void destroy_graph_cache(mtmc_weights* w);
 int kernel_timer_set(mtmc_weights* w, int cls, int every);
-int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t* launches);
+int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t* launches, double* empty_pair_ms);
 void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& c);
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& c);
 

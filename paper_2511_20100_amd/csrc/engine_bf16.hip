@@ -26,6 +26,8 @@ struct GraphCache {
   int timer_class = 0, timer_every = 0;
   std::vector<hipEvent_t> events;  // pool, used pairwise
   size_t events_used = 0;
+  std::vector<hipEvent_t> empty_events;  // pairs recorded back to back (what a pair costs by itself)
+  size_t empty_used = 0;
 };
 
 // Brackets launches of one kernel class with HIP events while a decode step is launched directly.
@@ -42,6 +44,18 @@ struct KernelTimer {
     }
     (void)hipEventRecord(gc->events[gc->events_used++], st);
   }
+  // Two events with nothing between them, once per timed step.
+  void mark_empty_pair() {
+    if (!gc || !cls) return;
+    for (int i = 0; i < 2; ++i) {
+      if (gc->empty_used == gc->empty_events.size()) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        gc->empty_events.push_back(e);
+      }
+      (void)hipEventRecord(gc->empty_events[gc->empty_used++], st);
+    }
+  }
 };
 
 void destroy_graph_cache(mtmc_weights* w) {
@@ -49,6 +63,7 @@ void destroy_graph_cache(mtmc_weights* w) {
   for (auto& e : w->graphs->entries) (void)hipGraphExecDestroy(e.exec);
   if (w->graphs->capture_stream) (void)hipStreamDestroy(w->graphs->capture_stream);
   for (hipEvent_t e : w->graphs->events) (void)hipEventDestroy(e);
+  for (hipEvent_t e : w->graphs->empty_events) (void)hipEventDestroy(e);
   delete w->graphs;
   w->graphs = nullptr;
 }
@@ -59,12 +74,14 @@ int kernel_timer_set(mtmc_weights* w, int cls, int every) {
   w->graphs->timer_class = cls;
   w->graphs->timer_every = every;
   w->graphs->events_used = 0;
+  w->graphs->empty_used = 0;
   return MTMC_OK;
 }
 
-int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t* launches) {
+int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t* launches, double* empty_pair_ms) {
   *total_ms = 0.0;
   *launches = 0;
+  if (empty_pair_ms) *empty_pair_ms = 0.0;
   if (!w->graphs) return MTMC_OK;
   MTMC_HIP_CHECK(hipStreamSynchronize(st));
   std::lock_guard<std::mutex> lock(w->graphs->mu);
@@ -76,6 +93,14 @@ int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t
     *launches += 1;
   }
   gc.events_used = 0;
+  double empty = 0.0;
+  for (size_t i = 0; i + 1 < gc.empty_used; i += 2) {
+    float ms = 0.f;
+    MTMC_HIP_CHECK(hipEventElapsedTime(&ms, gc.empty_events[i], gc.empty_events[i + 1]));
+    empty += ms;
+  }
+  if (empty_pair_ms && gc.empty_used >= 2) *empty_pair_ms = empty / (double)(gc.empty_used / 2);
+  gc.empty_used = 0;
   return MTMC_OK;
 }
 
@@ -453,6 +478,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     };
     auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) {
       const float *ss_cur = nullptr, *ss_old = nullptr;
+      if (tm) tm->mark_empty_pair();
       decode_layers(w, D, gp, pool, p.prompt_len - 1, &ss_cur, &ss_old, s, tm);
       if (tm) tm->mark(MTMC_KERNEL_LM_HEAD);
       sample(s, ss_cur, ss_old);

@@ -59,7 +59,8 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_set_option.restype = ctypes.c_int
     lib.mtmc_kernel_timer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.mtmc_kernel_timer.restype = ctypes.c_int
-    lib.mtmc_kernel_timer_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.mtmc_kernel_timer_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_double)]
     lib.mtmc_kernel_timer_read.restype = ctypes.c_int
     lib.mtmc_poll_errors.argtypes = [vp, vp]
     lib.mtmc_poll_errors.restype = ctypes.c_int
@@ -183,11 +184,13 @@ def mtmc_kernel_timer(handle: int, kernel_class: int, every_n_steps: int) -> Non
     _check(_lib.mtmc_kernel_timer(handle, kernel_class, every_n_steps))
 
 
-def mtmc_kernel_timer_read(handle: int, stream: Optional[torch.cuda.Stream] = None) -> Tuple[float, int]:
-    """Returns (total milliseconds, number of timed launches) since the last read."""
-    ms, n = ctypes.c_double(), ctypes.c_int64()
-    _check(_lib.mtmc_kernel_timer_read(handle, _stream_ptr(stream), ctypes.byref(ms), ctypes.byref(n)))
-    return ms.value, n.value
+def mtmc_kernel_timer_read(handle: int, stream: Optional[torch.cuda.Stream] = None) -> Tuple[float, int, float]:
+    """Returns (total milliseconds, number of timed launches, mean milliseconds of an empty event
+    pair) since the last read."""
+    ms, n, empty = ctypes.c_double(), ctypes.c_int64(), ctypes.c_double()
+    _check(_lib.mtmc_kernel_timer_read(handle, _stream_ptr(stream), ctypes.byref(ms), ctypes.byref(n),
+                                       ctypes.byref(empty)))
+    return ms.value, n.value, empty.value
 
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:

@@ -47,10 +47,11 @@ def test_run_to_run_determinism(run):
 
 def test_decode_equals_score_everywhere(run):
     """Property that holds at any size: at T = 1 the log-prob returned with a sampled token is the
-    Eq. 2 factor that the scoring pass returns for it (two different kernel paths)."""
+    Eq. 2 factor that the scoring pass returns for it (two different kernel paths).  Each path is
+    within the tolerance of the exact factor, so the two are within twice that of each other."""
     d = np.abs(run["score"][:, PROMPT_LEN - 1:] - run["lp"])
     print("decode vs score: max", d.max(), "mean", d.mean())
-    assert d.max() <= LOGP_TOL_BF16
+    assert d.max() <= 2 * LOGP_TOL_BF16 and d.mean() <= 0.25 * LOGP_TOL_BF16
     assert np.all(run["score"][:, :PROMPT_LEN - 1] == 0.0)
 
 
