@@ -94,6 +94,11 @@ def main() -> int:
     ap.add_argument("--max-new", type=int, default=None, help="override the number of new tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-score", action="store_true", help="time the rollout alone")
+    ap.add_argument("--no-graph", action="store_true", help="launch decode steps directly (for counter runs)")
+    ap.add_argument("--no-kernel-timer", action="store_true", help="do not bracket the gate/up launches with events")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="before the workload, copy this many MiB device to device once: a kernel of known "
+                         "traffic against which hardware byte counters of the same run are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by prompt with no collectives; "
@@ -116,6 +121,15 @@ def main() -> int:
     blob = torch.from_numpy(weights.blob())
     handle = mtmc.mtmc_weights_create(mtmc.make_config(cfg, seq_len), blob)
     del blob
+    if args.no_graph:
+        mtmc.mtmc_set_option(handle, mtmc.MTMC_OPT_HIP_GRAPH, 0)
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     prompts_np = inputs.make_prompts(n_prompts, prompt_len, cfg.vocab, seed=2)
     prompts = torch.from_numpy(prompts_np).to(dev)
     ws_r = torch.empty(mtmc.mtmc_rollout_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new),
@@ -146,7 +160,7 @@ def main() -> int:
     torch.cuda.synchronize()
     # dominant decode kernel (gate/up projection: half of the layer weight bytes): every 32nd decode
     # step of the timed region is launched directly with a HIP-event pair around each of its launches
-    timed_kernel = cfg.dtype == "bf16"
+    timed_kernel = cfg.dtype == "bf16" and not args.no_kernel_timer
     if timed_kernel:
         mtmc.mtmc_kernel_timer(handle, mtmc.MTMC_KERNEL_GATE_UP, 32)
     rollout_ms, score_ms = [], []

@@ -129,13 +129,19 @@ int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_seqs, int32
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);
 
 /*
- * Tuning switches.  Results never depend on them (same kernels, same order).
+ * Tuning switches.
  *   MTMC_OPT_HIP_GRAPH (default 1): mtmc_rollout captures one decode step into a HIP graph and
- *   replays it for every token.  Instantiated graphs are cached inside `w`, keyed by workspace
- *   address and shape; replacing a cached graph synchronises `stream` once.  When `stream` is
- *   itself being captured the steps are launched directly.
+ *   replays it for every token.  Results do not depend on it (same kernels in the same order).
+ *   Instantiated graphs are cached inside `w`, keyed by workspace address and shape; replacing
+ *   a cached graph synchronises `stream` once.  When `stream` is itself being captured the steps
+ *   are launched directly.
+ *   MTMC_OPT_GEMM_LDS_MIN_BLOCKS (default 192, value >= 1): prefill / scoring GEMMs (MTMC_BF16)
+ *   whose output has at least this many 256 x 256 blocks run in the LDS-staged kernel, smaller
+ *   ones in the direct 128 x 128 kernel.  Both sum over K in the same order; results agree to
+ *   the fp32 rounding inside the matrix instruction.
  */
 #define MTMC_OPT_HIP_GRAPH 1
+#define MTMC_OPT_GEMM_LDS_MIN_BLOCKS 2
 int mtmc_set_option(mtmc_weights* w, int option, int value);
 
 /*

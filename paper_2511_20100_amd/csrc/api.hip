@@ -89,6 +89,7 @@ extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, siz
   w->storage = nullptr;
   w->aux = nullptr;
   w->opt_hip_graph = 1;
+  w->opt_lds_min_blocks = 192;
   w->graphs = nullptr;
   int rc = hipGetDevice(&w->device) == hipSuccess ? MTMC_OK : MTMC_EHIP;
   if (rc == MTMC_OK) rc = build_aux(w, st);
@@ -117,8 +118,13 @@ extern "C" void mtmc_weights_destroy(mtmc_weights* w) {
 
 extern "C" int mtmc_set_option(mtmc_weights* w, int option, int value) {
   MTMC_REQUIRE(w != nullptr, "weights is NULL");
-  MTMC_REQUIRE(option == MTMC_OPT_HIP_GRAPH, "unknown option");
-  w->opt_hip_graph = value ? 1 : 0;
+  MTMC_REQUIRE(option == MTMC_OPT_HIP_GRAPH || option == MTMC_OPT_GEMM_LDS_MIN_BLOCKS, "unknown option");
+  if (option == MTMC_OPT_HIP_GRAPH) {
+    w->opt_hip_graph = value ? 1 : 0;
+  } else {
+    MTMC_REQUIRE(value >= 1, "MTMC_OPT_GEMM_LDS_MIN_BLOCKS needs a value >= 1");
+    w->opt_lds_min_blocks = value;
+  }
   return MTMC_OK;
 }
 

@@ -82,6 +82,7 @@ struct AttnDecArgs {
   const int* d_step;
   KvPool pool;
   int chunk_pages, n_chunks, m_tiles;
+  int share;             // consecutive sequences that share prompt pages (samples per prompt); B % share == 0
   float* part;           // [B, Hkv, n_chunks, G * 130]
   int* counters;         // [B * Hkv], zero between launches
   h16_t* o;              // tiled fp16 [Hq * 128 (k), m_tiles * 16]
@@ -109,9 +110,11 @@ void gemm_skinny_sample(float* part, const h16_t* Wt, int n_tiles, int k_tiles, 
 void sample_reduce(const float* part, int n_groups, int M, const SampleCtl* ctl, const int* d_step,
                    int* cur_ids, hipStream_t st);
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
-                    int k_tiles, const h16_t* Xt, int M, int m_tiles, hipStream_t st);
+                    int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st);
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                       int M, int m_tiles, hipStream_t st);
+                       int M, int m_tiles, int lds_min_blocks, hipStream_t st);
+// LDS-staged 256 x 256 kernel behind the two launchers above (epi: 0 store, 1 accumulate, 2 SwiGLU).
+void gemm_lds(const LargeArgs& a, int epi, hipStream_t st);
 int score_head_blocks(int n_tiles, int* groups_per_block);
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
                   int m_tiles, const int* targets, hipStream_t st);

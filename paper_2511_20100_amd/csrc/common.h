@@ -82,5 +82,6 @@ struct mtmc_weights {
   int* err_flag;        // device int, non-zero once a bad token id was seen
   int d_ffn_pad;        // F rounded up to the K-tile of the bf16 kernels (== F for fp32)
   int opt_hip_graph;    // replay decode steps as a captured HIP graph (default 1)
+  int opt_lds_min_blocks;  // output blocks (256 x 256) from which large GEMMs use the LDS-staged kernel
   mtmc::GraphCache* graphs;  // instantiated decode-step graphs, keyed by workspace and shape
 };

@@ -83,9 +83,12 @@ struct DecSamplePartial {
   float pad[3];
 };
 
-template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int EPI>
+template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int EPI, int NBP = NB>
 __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
-  __shared__ float red[WAVES][NB * MB * 4][64];
+  // NBP = row tiles summed and finished per pass over the LDS exchange buffer (NB / NBP passes)
+  static_assert(NB % NBP == 0 && (EPI != DEPI_SWIGLU || NBP % 2 == 0 || NB == 1) && (EPI != DEPI_SAMPLE || NBP == NB),
+                "bad tiles-per-pass");
+  __shared__ float red[WAVES][NBP * MB * 4][64];
   __shared__ float s_scale[MB * 16];
   __shared__ float s_part[2][WAVES * 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -156,16 +159,20 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // Sum over the K slices: every wavefront publishes its accumulators; wavefront w then adds the WAVES
   // slices of token tiles w, w + WAVES, ... in index order and runs the epilogue for those tokens.
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+  for (int ph = 0; ph < NB / NBP; ++ph) {
+  const int nbase = nt0 + ph * NBP;  // first row tile of this pass
+  if (ph) __syncthreads();            // the previous pass has been read
+#pragma unroll
+  for (int j = 0; j < NBP; ++j)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) red[wave][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
+      for (int r = 0; r < 4; ++r) red[wave][(j * MB + mb) * 4 + r][lane] = acc[ph * NBP + j][mb][r];
   __syncthreads();
   for (int mb = wave; mb < MB && mb < a.m_tiles; mb += WAVES) {
-  v4f sum[NB];
+  v4f sum[NBP];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
+  for (int nb = 0; nb < NBP; ++nb) {
     sum[nb] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int w = 0; w < WAVES; ++w)
@@ -179,21 +186,21 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   if (EPI == DEPI_PARTIAL) {
     float* P = a.out_f32 + (size_t)blockIdx.y * Mpad * a.ld_out;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      if (nt0 + nb >= a.n_tiles) continue;
-      *reinterpret_cast<v4f*>(P + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = sum[nb];
+    for (int nb = 0; nb < NBP; ++nb) {
+      if (nbase + nb >= a.n_tiles) continue;
+      *reinterpret_cast<v4f*>(P + (size_t)m * a.ld_out + (nbase + nb) * 16 + rq) = sum[nb];
     }
   } else if (EPI == DEPI_STORE) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      if (nt0 + nb >= a.n_tiles || m >= a.M) continue;
-      *reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = sum[nb] * sc;
+    for (int nb = 0; nb < NBP; ++nb) {
+      if (nbase + nb >= a.n_tiles || m >= a.M) continue;
+      *reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + (nbase + nb) * 16 + rq) = sum[nb] * sc;
     }
   } else if (EPI == DEPI_RESID) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      if (nt0 + nb >= a.n_tiles) continue;
-      const int n = (nt0 + nb) * 16 + rq;
+    for (int nb = 0; nb < NBP; ++nb) {
+      if (nbase + nb >= a.n_tiles) continue;
+      const int n = (nbase + nb) * 16 + rq;
       const v4f g = *reinterpret_cast<const v4f*>(a.gain + n);
       const bool live = m < a.M;
       v4f hv = v4f{0.f, 0.f, 0.f, 0.f};
@@ -209,15 +216,15 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
       ss += __shfl_xor(ss, 16, 64);
       ss += __shfl_xor(ss, 32, 64);
-      if (lane < 16 && live) a.ss_out[(size_t)(nt0 + nb) * Mpad + m] = ss;
+      if (lane < 16 && live) a.ss_out[(size_t)(nbase + nb) * Mpad + m] = ss;
     }
   } else if (EPI == DEPI_SWIGLU) {
     // weight row tiles alternate gate / up: tile 2j holds gate rows 16j.., tile 2j+1 the up rows
 #pragma unroll
-    for (int nb = 0; nb < NB; nb += 2) {
-      if (nt0 + nb >= a.n_tiles || m >= a.M) continue;
-      const int f = ((nt0 + nb) >> 1) * 16 + rq;
-      const v4f g = sum[nb] * sc, u = sum[(nb + 1) % NB] * sc;
+    for (int nb = 0; nb < NBP; nb += 2) {
+      if (nbase + nb >= a.n_tiles || m >= a.M) continue;
+      const int f = ((nbase + nb) >> 1) * 16 + rq;
+      const v4f g = sum[nb] * sc, u = sum[(nb + 1) % NBP] * sc;
       uint2 pk;
       pk.x = pack_h16x2(silu_d(g[0]) * u[0], silu_d(g[1]) * u[1]);
       pk.y = pack_h16x2(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3]);
@@ -230,9 +237,9 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
     float by = -INFINITY, bz = 0.f;
     int bi = 0x7fffffff;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      if (nt0 + nb >= a.n_tiles) continue;
-      const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
+    for (int nb = 0; nb < NBP; ++nb) {
+      if (nbase + nb >= a.n_tiles) continue;
+      const int v0 = (nbase + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
       uint4 rb = make_uint4(0, 0, 0, 0);
       if (!ctl.greedy)
         rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u), ctl.key0,
@@ -261,18 +268,24 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
     }
   }
   }  // token tiles of this wavefront
+  }  // passes
 }
 
-template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW>
+template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int NBP = NB>
 static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
-  const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1);
-  const dim3 block(WAVES * 64);
-  switch (epi) {
-    case DEPI_PARTIAL: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL><<<grid, block, 0, st>>>(a); break;
-    case DEPI_STORE: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_STORE><<<grid, block, 0, st>>>(a); break;
-    case DEPI_RESID: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_RESID><<<grid, block, 0, st>>>(a); break;
-    case DEPI_SWIGLU: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU><<<grid, block, 0, st>>>(a); break;
-    default: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SAMPLE><<<grid, block, 0, st>>>(a); break;
+  if constexpr (NBP != NB) {  // several passes over the exchange buffer: SwiGLU shape only
+    const dim3 grid((a.n_tiles + NB - 1) / NB, 1), block(WAVES * 64);
+    k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
+  } else {
+    const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1);
+    const dim3 block(WAVES * 64);
+    switch (epi) {
+      case DEPI_PARTIAL: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL><<<grid, block, 0, st>>>(a); break;
+      case DEPI_STORE: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_STORE><<<grid, block, 0, st>>>(a); break;
+      case DEPI_RESID: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_RESID><<<grid, block, 0, st>>>(a); break;
+      case DEPI_SWIGLU: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU><<<grid, block, 0, st>>>(a); break;
+      default: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SAMPLE><<<grid, block, 0, st>>>(a); break;
+    }
   }
 }
 
@@ -289,8 +302,15 @@ static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
 // Wide shape: many row tiles (gate/up, LM head): NB tiles per workgroup, K split over 4 wavefronts.
 template <int MB>
 static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
-  if constexpr (MB > 4) launch_dec_t<2, MB, 4, 2, 2, 2>(a, epi, st);
-  else launch_dec_t<4, MB, 4, 2, 2, 2>(a, epi, st);
+  if constexpr (MB > 4) {
+    launch_dec_t<2, MB, 4, 2, 2, 2>(a, epi, st);
+  } else {
+    // every workgroup reads the whole activation operand, so a CU that hosts two workgroups takes
+    // about twice as long as one that hosts one: when the tiles fit into one round of 256
+    // workgroups of 6, use that instead of 1.x rounds of 4
+    if (epi == DEPI_SWIGLU && a.n_tiles > 4 * 256 && a.n_tiles <= 6 * 256) launch_dec_t<6, MB, 8, 3, 3, 1, 2>(a, epi, st);
+    else launch_dec_t<4, MB, 4, 2, 2, 2>(a, epi, st);
+  }
 }
 
 int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
@@ -545,7 +565,21 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   __shared__ float s_m[AW][16], s_l[AW][16];
   __shared__ int s_table[ATAB];
   __shared__ int s_last;
-  const int b = blockIdx.x, g = blockIdx.y, chunk = blockIdx.z;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
+  // The `share` sequences that sample from one prompt read the same prompt pages, so their
+  // workgroups (for one kv head) are given launch indices that are congruent modulo 8: the pages
+  // then come from HBM once per XCD instead of once per sequence.
+  int b = blockIdx.x, g = blockIdx.y;
+  {
+    const int B = gridDim.x, total = B * gridDim.y, S = a.share;
+    if (S > 1 && total % (8 * S) == 0) {
+      const int L = b + B * g, xcd = L & 7, slot = L >> 3;
+      const int item = ((slot / S) * 8 + xcd) * S + slot % S;
+      g = item / B;
+      b = item - g * B;
+    }
+  }
+  const int chunk = blockIdx.z;
   const int Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, lg = lane >> 4;

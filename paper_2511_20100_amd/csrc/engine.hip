@@ -6,8 +6,12 @@
 
 namespace mtmc {
 
-// Tokens per prefill / scoring chunk: bounds activation memory, keeps every launch large.
+// Tokens per prefill / scoring chunk: bounds activation memory, keeps every launch large.  The
+// bf16 scoring pass takes up to 128 Ki tokens at once (about 5 GB of activations at d = 1536,
+// F = 8960), so that even the narrowest GEMM of a chunk fills the 256 CUs several times over with
+// 256 x 256 output blocks, and splits longer jobs into equal chunks.
 static constexpr int kChunkTokens = 8192;
+static constexpr int kScoreChunkTokensBf16 = 131072;
 static constexpr int kMaxBf16Batch = 128;  // rows the skinny decode GEMMs take
 static constexpr size_t kLogitBytes = (size_t)256 << 20;
 
@@ -87,7 +91,11 @@ ScorePlan plan_score(const mtmc_weights* w, int n_seqs, int S, char* base) {
   const bool bf = c.dtype == MTMC_BF16;
   ScorePlan p{};
   p.n_seqs = n_seqs; p.S = S;
-  p.chunk_seqs = std::max(1, std::min(n_seqs, kChunkTokens / S));
+  p.chunk_seqs = std::max(1, std::min(n_seqs, (bf ? kScoreChunkTokensBf16 : kChunkTokens) / S));
+  if (bf) {  // equal chunks
+    const int n_chunks = (n_seqs + p.chunk_seqs - 1) / p.chunk_seqs;
+    p.chunk_seqs = (n_seqs + n_chunks - 1) / n_chunks;
+  }
   p.pages_per_seq = (S + kPageTokens - 1) / kPageTokens;
   p.n_pages = p.chunk_seqs * p.pages_per_seq;
   p.T = (p.chunk_seqs * S + 127) / 128 * 128;

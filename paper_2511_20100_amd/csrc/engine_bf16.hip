@@ -291,17 +291,17 @@ void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, fl
                     h16_t* o, h16_t* a, int n_seqs, int S, TokMap map, KvPool pool, int layer_stride,
                     hipStream_t st) {
   const mtmc_config& c = w->cfg;
-  const int T = n_seqs * S, mt = tiles16(T);
+  const int T = n_seqs * S, mt = tiles16(T), lmb = w->opt_lds_min_blocks;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& L = w->layers[l];
     const int kvl = l * layer_stride;
-    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, st);
+    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, st);
     bf16::rope_kv_write(qb, qkv, 1, D.nqkv, 0, T, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, st);
     bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, st);
-    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, st);
     bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, st);
-    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, st);
-    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, st);
+    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, lmb, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, lmb, st);
     if (l + 1 < c.n_layers)
       bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, st);
   }
@@ -336,7 +336,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     bf16::AttnDecArgs at{};
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
     at.pos_base = pos_base; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
-    at.n_chunks = p.n_chunks; at.m_tiles = bt; at.part = p.attn_part; at.counters = p.attn_counters; at.o = o;
+    at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples; at.part = p.attn_part; at.counters = p.attn_counters; at.o = o;
     mark(MTMC_KERNEL_ATTENTION);
     bf16::attention_dec(at, B, st);
     mark(MTMC_KERNEL_ATTENTION);

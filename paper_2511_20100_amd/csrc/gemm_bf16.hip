@@ -296,11 +296,32 @@ void sample_reduce(const float* part, int n_groups, int M, const SampleCtl* ctl,
 // ======================================================================================
 enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
 
+// Workgroup -> output block.  Launch index L runs on XCD L % 8 (round-robin hand-out), and each XCD
+// has its own L2.  Every XCD therefore owns whole rows of token blocks (token block = xcd + 8 i) and
+// walks them in bands of LGM token blocks x all feature blocks, feature index slowest, so that the
+// ~32-64 workgroups resident on an XCD at one time share LGM activation panels and a few weight
+// panels through that L2.
+constexpr int LGM = 4;
+struct LargeBlock { int nb, mb; bool valid; };
+__device__ __forceinline__ LargeBlock large_block(int L, int nb_n, int nb_m) {
+  const int xcd = L & 7, j = L >> 3;
+  const int band = j / (LGM * nb_n), r = j - band * (LGM * nb_n);
+  const int nb = r / LGM, mi = band * LGM + (r - nb * LGM);
+  const int mb = xcd + 8 * mi;
+  return LargeBlock{nb, mb, mb < nb_m};
+}
+static int large_grid(int nb_n, int nb_m) {
+  const int per_xcd = (nb_m + 7) / 8, bands = (per_xcd + LGM - 1) / LGM;
+  return 8 * bands * LGM * nb_n;
+}
+
 template <int EPI>
 __global__ __launch_bounds__(256) void k_gemm_large(LargeArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nt0 = blockIdx.x * 8 + (wave & 1) * 4;
-  const int mt0 = blockIdx.y * 8 + (wave >> 1) * 4;
+  const LargeBlock blk = large_block(blockIdx.x, (a.n_tiles + 7) / 8, (a.m_tiles + 7) / 8);
+  if (!blk.valid) return;
+  const int nt0 = blk.nb * 8 + (wave & 1) * 4;
+  const int mt0 = blk.mb * 8 + (wave >> 1) * 4;
   if (nt0 >= a.n_tiles || mt0 >= a.m_tiles) return;
   v4f acc[4][4];
 #pragma unroll
@@ -337,25 +358,34 @@ __global__ __launch_bounds__(256) void k_gemm_large(LargeArgs a) {
 }
 
 static void launch_large(const LargeArgs& a, int epi, hipStream_t st) {
-  const dim3 grid((a.n_tiles + 7) / 8, (a.m_tiles + 7) / 8);
+  const dim3 grid(large_grid((a.n_tiles + 7) / 8, (a.m_tiles + 7) / 8));
   if (epi == LEPI_STORE) k_gemm_large<LEPI_STORE><<<grid, 256, 0, st>>>(a);
   else if (epi == LEPI_ADD) k_gemm_large<LEPI_ADD><<<grid, 256, 0, st>>>(a);
   else k_gemm_large<LEPI_SWIGLU><<<grid, 256, 0, st>>>(a);
 }
 
+// The LDS-staged kernel (256 x 256 blocks, one workgroup per CU) takes over once the output has
+// at least `lds_min_blocks` such blocks; smaller problems keep the 128 x 128 direct kernel, which
+// spreads them over more workgroups.
+static bool use_lds_kernel(int n_tiles, int m_tiles, int lds_min_blocks) {
+  return ((n_tiles + 15) / 16) * ((m_tiles + 15) / 16) >= lds_min_blocks;
+}
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
-                    int k_tiles, const h16_t* Xt, int M, int m_tiles, hipStream_t st) {
+                    int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st) {
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M; a.N = N;
   a.out_f32 = C; a.ld_out = ldc;
-  launch_large(a, accumulate ? LEPI_ADD : LEPI_STORE, st);
+  const int epi = accumulate ? LEPI_ADD : LEPI_STORE;
+  if (use_lds_kernel(n_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, epi, st);
+  else launch_large(a, epi, st);
 }
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                       int M, int m_tiles, hipStream_t st) {
+                       int M, int m_tiles, int lds_min_blocks, hipStream_t st) {
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
   a.out_bf16 = act;
-  launch_large(a, LEPI_SWIGLU, st);
+  if (use_lds_kernel(n_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, LEPI_SWIGLU, st);
+  else launch_large(a, LEPI_SWIGLU, st);
 }
 
 // ======================================================================================

@@ -1,0 +1,236 @@
+// Large-batch GEMM of the prefill / scoring pass, staged through LDS.
+//
+// Workgroup tile: 256 output features x 256 tokens, full K.  Four wavefronts (one per SIMD) in a
+// 2 x 2 arrangement own 128 x 128 each: 4 x 4 accumulator blocks of v_mfma_f32_32x32x16_f16 per
+// wavefront (a single wavefront per SIMD keeps the matrix pipe above 90 % busy with this shape, but
+// only near 55 % with the 16x16x32 shape), which puts the LDS read rate at 16 KiB per k-step per
+// wavefront (about half of what the LDS can deliver) and the global rate at 32 KiB per k-step per
+// workgroup.
+//
+// Both operands already sit in memory as 1 KiB MFMA operand blocks (frag.h), so staging is a plain
+// copy: every k-step (32 columns of K) needs 16 weight blocks and 16 activation blocks, which the
+// wavefronts fetch with LDS-direct 16-byte loads (no registers involved) into a ring of kStages
+// buffers, kStages - 1 steps ahead of the one being multiplied.  One workgroup barrier per step:
+// it makes the step's blocks visible to every wavefront and at the same time guarantees that
+// the buffer refilled next (read in the previous step) is no longer in use.
+#include "bf16_kernels.h"
+#include "device_utils.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+namespace {
+
+constexpr int kStages = 4;
+constexpr int kBlkTiles = 16;                       // 16-row tiles per workgroup tile side
+constexpr int kStageBytes = 2 * kBlkTiles * 1024;   // weight blocks, then activation blocks
+constexpr int kLoadsPerStage = 2 * kBlkTiles / 4;   // LDS-direct loads each wavefront issues per step
+
+typedef __attribute__((ext_vector_type(16))) float v16f;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+__device__ __forceinline__ void copy_block_to_lds(const uint8_t* src_lane, uint8_t* dst_block) {
+  __builtin_amdgcn_global_load_lds((glb_ptr_t)src_lane, (lds_ptr_t)dst_block, 16, 0, 0);
+}
+
+// s_waitcnt on the vector-memory counter alone (the other counters left at their maxima).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// acc += A B with the accumulator pinned to the AGPR half of the register file (the 256 accumulator
+// registers of a wavefront fill it exactly; left to itself the register allocator spreads them over both
+// halves and spills).  Consecutive uses of one accumulator are 16 MFMAs apart, far beyond the
+// dependent-issue distance of the instruction.
+__device__ __forceinline__ void mfma32_acc(v16f& acc, v8bf a, v8bf b) {
+  asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
+}
+
+__device__ __forceinline__ float silu_l(float g) { return g / (1.0f + expf(-g)); }
+
+// Launch index -> output block: XCD (L % 8) owns token blocks xcd + 8 i and walks them in bands of
+// kBand token blocks x all feature blocks, so workgroups resident together on an XCD share panels
+// in its L2.
+constexpr int kBand = 4;
+struct Block { int nb, mb; bool valid; };
+__device__ __forceinline__ Block block_of(int L, int nb_n, int nb_m) {
+  const int xcd = L & 7, j = L >> 3;
+  const int band = j / (kBand * nb_n), r = j - band * (kBand * nb_n);
+  const int nb = r / kBand, mi = band * kBand + (r - nb * kBand);
+  const int mb = xcd + 8 * mi;
+  return Block{nb, mb, mb < nb_m};
+}
+int grid_of(int nb_n, int nb_m) {
+  const int per_xcd = (nb_m + 7) / 8, bands = (per_xcd + kBand - 1) / kBand;
+  return 8 * bands * kBand * nb_n;
+}
+
+enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  const Block blk = block_of(blockIdx.x, nb_n, nb_m);
+  if (!blk.valid) return;  // whole workgroup
+  const int nt_base = blk.nb * kBlkTiles, mt_base = blk.mb * kBlkTiles;
+  const int K = a.k_tiles;
+
+  // ---- this wavefront's share of every stage: weight blocks 4 wave .. + 3 and activation blocks
+  // 4 wave .. + 3 (tile indices past the end are clamped: such blocks are multiplied but never stored).
+  // Block addresses are wavefront-uniform (scalar registers); the lane adds its 16-byte slot.
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const uint8_t* wsrc[4];
+  const uint8_t* xsrc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int nt = min(nt_base + 4 * uwave + j, a.n_tiles - 1);
+    const int mt = min(mt_base + 4 * uwave + j, a.m_tiles - 1);
+    wsrc[j] = reinterpret_cast<const uint8_t*>(a.Wt) + ((size_t)nt * K) * 1024;
+    xsrc[j] = reinterpret_cast<const uint8_t*>(a.Xt) + (size_t)mt * 1024;
+  }
+  const size_t xstep = (size_t)a.m_tiles * 1024;
+  const uint32_t lane16 = lane * 16;
+  auto issue = [&](int kt, int buf) {
+    const int kk = min(kt, K - 1);
+    uint8_t* sb = lds + buf * kStageBytes + uwave * 4096;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) copy_block_to_lds(wsrc[j] + (size_t)kk * 1024 + lane16, sb + j * 1024);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      copy_block_to_lds(xsrc[j] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j) * 1024);
+  };
+
+  // 4 x 4 accumulator blocks of 32 x 32 (v_mfma_f32_32x32x16_f16), 16 registers each
+  v16f acc[4][4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[nb][mb][j] = 0.f;
+
+  // A 32-row operand of the 32x32x16 MFMA (lane l: row l % 32, 8 consecutive k of half l / 32) is
+  // gathered from two adjacent 16-row blocks: lane -> (block (l % 32) / 16, row l % 16, k group
+  // 2 p + l / 32) for the p-th pair of k groups; the two pairs of a k-step are 512 bytes apart.
+  const int r32 = lane & 31;
+  const int lane_off = (r32 >> 4) * 1024 + (((lane >> 5) << 4) + (r32 & 15)) * 16;
+
+  // Fragments of one k-step: per 32-row block two operands (k groups 0,1 and 2,3).
+  struct Frags { v8bf w[4][2], x[4][2]; };
+  auto read_frag = [&](Frags& f, const uint8_t* sb, int i) {  // i = 0..15
+    const int blk = (i >> 1) & 3, p = i & 1;
+    if (i < 8) f.x[blk][p] = *reinterpret_cast<const v8bf*>(sb + (kBlkTiles + 8 * wm + 2 * blk) * 1024 + p * 512);
+    else f.w[blk][p] = *reinterpret_cast<const v8bf*>(sb + (8 * wn + 2 * blk) * 1024 + p * 512);
+  };
+  auto issue_one = [&](int kk, uint8_t* sb, int j) {  // j = 0..7
+    if (j < 4) copy_block_to_lds(wsrc[j] + (size_t)kk * 1024 + lane16, sb + j * 1024);
+    else copy_block_to_lds(xsrc[j - 4] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j - 4) * 1024);
+  };
+  // Step kt multiplies the fragments already in registers; spread between its 32 MFMAs (which take 32
+  // cycles each and leave the issue slots free) are the 16 LDS reads of the fragments of step kt + 1
+  // and the 8 block fetches of step kt + kStages, into the buffer step kt was read from.
+  auto step = [&](const Frags& cur, Frags& next, int kt) {
+    // own LDS reads done (they all feed `cur`); blocks of step kt + 1 landed, kt + 2 and kt + 3 may fly
+    __builtin_amdgcn_s_waitcnt((((kStages - 2) * kLoadsPerStage) & 15) | ((((kStages - 2) * kLoadsPerStage) >> 4) << 14) |
+                               (7 << 4) | (0 << 8));
+    __builtin_amdgcn_s_barrier();
+    const uint8_t* rb = lds + ((kt + 1) % kStages) * kStageBytes + lane_off;  // step K: clamped copy, never used
+    uint8_t* fb = lds + (kt % kStages) * kStageBytes + uwave * 4096;
+    const int kk = min(kt + kStages, K - 1);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const int pp = i >> 4, nb = (i >> 2) & 3, mb = i & 3;
+      mfma32_acc(acc[nb][mb], cur.w[nb][pp], cur.x[mb][pp]);
+      if ((i & 1) == 0) read_frag(next, rb, i >> 1);
+      if ((i & 3) == 1) issue_one(kk, fb, i >> 2);
+    }
+  };
+
+#pragma unroll
+  for (int s = 0; s < kStages; ++s) issue(s, s);
+  Frags fa, fb;
+  wait_vmcnt<(kStages - 1) * kLoadsPerStage>();
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) read_frag(fa, lds + lane_off, i);
+  int kt = 0;
+  for (; kt + 1 < K; kt += 2) {
+    step(fa, fb, kt);
+    step(fb, fa, kt + 1);
+  }
+  if (kt < K) step(fa, fb, kt);
+  wait_vmcnt<0>();  // the clamped loads past the last step still target this workgroup's LDS
+  // the last MFMAs were issued from inline assembly: give them time to retire before their
+  // accumulators are read (16 passes of 4 cycles cover the longest one)
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+  // ---- epilogue: in a 32 x 32 block, lane holds token lane % 32 and features 8 q + 4 (lane / 32) + 0..3
+  // (q = 0..3) in registers 4 q .. 4 q + 3
+  const int col = lane & 31, rh = (lane >> 5) * 4;
+  const int Mpad = a.m_tiles * 16;
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      asm volatile("" ::: "memory");  // one accumulator block at a time (keeps them out of the VGPR half until needed)
+      const int m = (mt_base + 8 * wm + 2 * mb) * 16 + col;
+      if (m >= a.M) continue;
+      const int n0 = (nt_base + 8 * wn + 2 * nb) * 16;  // first feature row of the block
+      if (EPI == LEPI_SWIGLU) {
+        // rows 0..15 of the block are gate rows, rows 16..31 the matching up rows
+        if (n0 >= a.n_tiles * 16) continue;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int f = (n0 >> 1) + 8 * q + rh;
+          uint2 pk;
+          pk.x = pack_h16x2(silu_l(acc[nb][mb][4 * q + 0]) * acc[nb][mb][4 * q + 8],
+                            silu_l(acc[nb][mb][4 * q + 1]) * acc[nb][mb][4 * q + 9]);
+          pk.y = pack_h16x2(silu_l(acc[nb][mb][4 * q + 2]) * acc[nb][mb][4 * q + 10],
+                            silu_l(acc[nb][mb][4 * q + 3]) * acc[nb][mb][4 * q + 11]);
+          *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + 8 * q + rh;
+          if (n >= a.N) continue;
+          const v4f v = v4f{acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
+          v4f* c = reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + n);
+          if (EPI == LEPI_ADD) *c = *c + v;
+          else *c = v;
+        }
+      }
+    }
+  }
+}
+
+template <int EPI>
+void launch_one(const LargeArgs& a, hipStream_t st) {
+  static bool configured = false;  // per process; the attribute is a property of the function
+  const int lds_bytes = kStages * kStageBytes;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_lds<EPI>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    configured = true;
+  }
+  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  k_gemm_lds<EPI><<<grid_of(nb_n, nb_m), 256, lds_bytes, st>>>(a);
+}
+
+}  // namespace
+
+void gemm_lds(const LargeArgs& a, int epi, hipStream_t st) {
+  if (epi == LEPI_STORE) launch_one<LEPI_STORE>(a, st);
+  else if (epi == LEPI_ADD) launch_one<LEPI_ADD>(a, st);
+  else launch_one<LEPI_SWIGLU>(a, st);
+}
+
+}  // namespace bf16
+}  // namespace mtmc

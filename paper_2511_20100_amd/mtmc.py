@@ -171,6 +171,7 @@ def mtmc_score(handle: int, seqs: torch.Tensor, prompt_len: int = 1, *, want_top
 
 
 MTMC_OPT_HIP_GRAPH = 1
+MTMC_OPT_GEMM_LDS_MIN_BLOCKS = 2
 
 
 def mtmc_set_option(handle: int, option: int, value: int) -> None:

@@ -126,3 +126,26 @@ def test_kernel_timer_does_not_change_results(lib):
         assert n == 5 * cfg.n_layers and ms > 0 and 0 <= empty_ms < ms / n      # steps 1, 5, 9, 13, 17 of 19 decode steps
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+@pytest.mark.parametrize("cfg,n_seqs,seq_len", [(SMALL, 7, 211), (GQA6, 9, 300)], ids=["small-ragged", "gqa6"])
+def test_lds_staged_gemm_on_ragged_shapes(lib, cfg, n_seqs, seq_len):
+    """The 256 x 256 LDS-staged GEMM forced onto small problems: token counts (1477, 2700) and
+    feature counts (256 ... 2 x 688) that are not multiples of its block, against the oracle and
+    against the direct kernel; then the same for the prompt pass of a rollout."""
+    import torch
+    w = inputs.make_weights(cfg, seed=4, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 512), w.blob())
+    try:
+        seqs = inputs.make_sequences(n_seqs, seq_len, cfg.vocab, seed=11)
+        direct = lib.mtmc_score(handle, torch.from_numpy(seqs).cuda(), 50).cpu().numpy()
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_GEMM_LDS_MIN_BLOCKS, 1)
+        sc = check_score(handle, w, seqs, 50, max_positions=512, rows=[0, n_seqs - 1], label="lds")
+        print("lds-staged score: max log-prob err", sc["max_logp_err"],
+              "max difference from the direct kernel", np.abs(sc["logprobs"] - direct).max())
+        assert np.abs(sc["logprobs"] - direct).max() <= 1e-3
+        prompts = inputs.make_prompts(3, 130, cfg.vocab, seed=2)
+        rep = check_rollout_by_replay(handle, w, prompts, 2, 6, 1.0, 1, max_positions=512, label="lds-prefill")
+        assert rep["compared"] > 0.5 * rep["steps"]
+    finally:
+        lib.mtmc_weights_destroy(handle)
