@@ -149,3 +149,19 @@ def test_lds_staged_gemm_on_ragged_shapes(lib, cfg, n_seqs, seq_len):
         assert rep["compared"] > 0.5 * rep["steps"]
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+def test_long_context_over_several_attention_chunks(lib):
+    """Context beyond 8192 tokens (more than the 512 pages one decode-attention workgroup stages):
+    the context is then split over workgroups whose partial results are merged by the last to
+    finish.  Prompt 8200 + 24 new tokens, small model, both samples replayed on the oracle."""
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=6, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 8256), w.blob())
+    try:
+        prompts = inputs.make_prompts(1, 8200, cfg.vocab, seed=8)
+        rep = check_rollout_by_replay(handle, w, prompts, 2, 24, 1.0, 5, max_positions=8256, label="long-context")
+        print("long context: compared", rep["compared"], "of", rep["steps"], "max log-prob err", rep["max_logp_err"])
+        assert rep["compared"] > 0.5 * rep["steps"]
+    finally:
+        lib.mtmc_weights_destroy(handle)
