@@ -117,7 +117,16 @@ void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, co
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st);
 int score_head_blocks(int n_tiles, int* groups_per_block);
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
-                  int m_tiles, const int* targets, hipStream_t st);
+                  int m_tiles, const int* targets, int lds_min_blocks, hipStream_t st);
+// One partial result of the scoring LM head: a row's state over one vocabulary slice.
+struct ScorePartial {
+  float m, s, v1;   // log-sum-exp state, largest logit
+  int i1;           // its index
+  float v2, zt;     // second largest logit, logit of the target token (-inf if not in the slice)
+  float pad[2];
+};
+// LDS-staged version (256 rows x 256 vocabulary entries per step, `slices` vocabulary slices of 128 row tiles).
+void lmhead_score_lds(const ScoreHeadArgs& a, int slices, hipStream_t st);
 void score_targets(int* targets, const int* seqs, int R, int S, int first, int n_scored, int seq0,
                    int row0, int vocab, int* err_flag, hipStream_t st);
 void score_reduce(const float* part, int n_parts, int R, int S, int first, int n_scored, int seq0,

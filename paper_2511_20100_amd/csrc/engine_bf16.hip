@@ -106,6 +106,7 @@ int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t
 
 namespace {
 inline int tiles16(int n) { return (n + 15) / 16; }
+
 inline int tiles32(int n) { return (n + 31) / 32; }
 
 // Split-K factor of a decode GEMM: enough workgroups to cover the chip, while every wavefront
@@ -528,7 +529,7 @@ int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hi
     launch_gather_rows(p.hs, p.h, R, D.d, n_scored, S, a.first, 1, st);
     bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
     bf16::score_targets(p.targets, a.seqs, R, S, a.first, n_scored, s0, 0, D.V, w->err_flag, st);
-    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets, st);
+    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets, w->opt_lds_min_blocks, st);
     bf16::score_reduce(p.lm_part, n_parts, R, S, a.first, n_scored, s0, 0, a.out_logprobs, a.out_top1, a.out_margin, st);
   }
   return MTMC_OK;

@@ -392,13 +392,6 @@ void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, co
 // Scoring LM head: logits are never stored.  A workgroup owns 128 rows and a range of
 // vocabulary tiles; every lane keeps running (log-sum-exp, top-2, target logit) for its rows.
 // ======================================================================================
-struct ScorePartial {
-  float m, s, v1;
-  int i1;
-  float v2, zt;
-  float pad[2];
-};
-
 __global__ __launch_bounds__(256) void k_lmhead_score(ScoreHeadArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave & 1;
@@ -470,13 +463,15 @@ int score_head_blocks(int n_tiles, int* groups_per_block) {
 }
 
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
-                  int m_tiles, const int* targets, hipStream_t st) {
+                  int m_tiles, const int* targets, int lds_min_blocks, hipStream_t st) {
   ScoreHeadArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
   a.targets = targets; a.part = part;
   a.n_groups = (n_tiles + 7) / 8;
   const int blocks = score_head_blocks(n_tiles, &a.groups_per_block);
-  k_lmhead_score<<<dim3(blocks, (m_tiles + 7) / 8), 256, 0, st>>>(a);
+  // same vocabulary slices (and partial results) in both kernels: 128 row tiles per slice
+  if (use_lds_kernel(n_tiles, m_tiles, lds_min_blocks)) lmhead_score_lds(a, blocks, st);
+  else k_lmhead_score<<<dim3(blocks, (m_tiles + 7) / 8), 256, 0, st>>>(a);
 }
 
 // Row r of the chunk is position i = first + (row0 + r) % n_scored of sequence

@@ -13,6 +13,8 @@
 // buffers, kStages - 1 steps ahead of the one being multiplied.  One workgroup barrier per step:
 // it makes the step's blocks visible to every wavefront and at the same time guarantees that
 // the buffer refilled next (read in the previous step) is no longer in use.
+#include <algorithm>
+
 #include "bf16_kernels.h"
 #include "device_utils.h"
 #include "frag.h"
@@ -71,31 +73,29 @@ int grid_of(int nb_n, int nb_m) {
 
 enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
 
-template <int EPI>
-__global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
-  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wn = wave & 1, wm = wave >> 1;
-  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
-  const Block blk = block_of(blockIdx.x, nb_n, nb_m);
-  if (!blk.valid) return;  // whole workgroup
-  const int nt_base = blk.nb * kBlkTiles, mt_base = blk.mb * kBlkTiles;
-  const int K = a.k_tiles;
-
+// acc (4 x 4 accumulator blocks of 32 x 32, v_mfma_f32_32x32x16_f16, 16 registers each) = the 128 x 128
+// part of this wavefront (wn, wm) of the 256 x 256 output block at (nt_base, mt_base), over all K
+// k-steps.  Called by all four wavefronts of the workgroup together; `lds` is the ring of kStages
+// buffers.  May be called again for another block: it starts with a barrier so that the ring is
+// refilled only after every wavefront has left the previous call.
+__device__ __forceinline__ void lds_gemm_block(v16f (&acc)[4][4], const uint8_t* Wt, const uint8_t* Xt, int n_tiles,
+                                               int m_tiles, int K, int nt_base, int mt_base, uint8_t* lds, int lane,
+                                               int uwave, int wn, int wm) {
+  __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8));  // nothing of an earlier block in flight
+  __builtin_amdgcn_s_barrier();
   // ---- this wavefront's share of every stage: weight blocks 4 wave .. + 3 and activation blocks
   // 4 wave .. + 3 (tile indices past the end are clamped: such blocks are multiplied but never stored).
   // Block addresses are wavefront-uniform (scalar registers); the lane adds its 16-byte slot.
-  const int uwave = __builtin_amdgcn_readfirstlane(wave);
   const uint8_t* wsrc[4];
   const uint8_t* xsrc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int nt = min(nt_base + 4 * uwave + j, a.n_tiles - 1);
-    const int mt = min(mt_base + 4 * uwave + j, a.m_tiles - 1);
-    wsrc[j] = reinterpret_cast<const uint8_t*>(a.Wt) + ((size_t)nt * K) * 1024;
-    xsrc[j] = reinterpret_cast<const uint8_t*>(a.Xt) + (size_t)mt * 1024;
+    const int nt = min(nt_base + 4 * uwave + j, n_tiles - 1);
+    const int mt = min(mt_base + 4 * uwave + j, m_tiles - 1);
+    wsrc[j] = Wt + ((size_t)nt * K) * 1024;
+    xsrc[j] = Xt + (size_t)mt * 1024;
   }
-  const size_t xstep = (size_t)a.m_tiles * 1024;
+  const size_t xstep = (size_t)m_tiles * 1024;
   const uint32_t lane16 = lane * 16;
   auto issue = [&](int kt, int buf) {
     const int kk = min(kt, K - 1);
@@ -107,8 +107,6 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
       copy_block_to_lds(xsrc[j] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j) * 1024);
   };
 
-  // 4 x 4 accumulator blocks of 32 x 32 (v_mfma_f32_32x32x16_f16), 16 registers each
-  v16f acc[4][4];
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
@@ -171,6 +169,21 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   // accumulators are read (16 passes of 4 cycles cover the longest one)
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  const Block blk = block_of(blockIdx.x, nb_n, nb_m);
+  if (!blk.valid) return;  // whole workgroup
+  const int nt_base = blk.nb * kBlkTiles, mt_base = blk.mb * kBlkTiles;
+  v16f acc[4][4];
+  lds_gemm_block(acc, reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles,
+                 a.m_tiles, a.k_tiles, nt_base, mt_base, lds, lane, __builtin_amdgcn_readfirstlane(wave), wn, wm);
+
   // ---- epilogue: in a 32 x 32 block, lane holds token lane % 32 and features 8 q + 4 (lane / 32) + 0..3
   // (q = 0..3) in registers 4 q .. 4 q + 3
   const int col = lane & 31, rh = (lane >> 5) * 4;
@@ -211,6 +224,95 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   }
 }
 
+// Scoring LM head on the same engine: a workgroup owns 256 rows and one vocabulary slice (8 blocks of
+// 256 entries), computes the logits block by block and folds them into running per-row results
+// (log-sum-exp, two largest logits, logit of the target token); logits are never stored.
+__global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slices) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  const Block blk = block_of(blockIdx.x, slices, nb_m);
+  if (!blk.valid) return;  // whole workgroup
+  const int mt_base = blk.mb * kBlkTiles;
+  const int col = lane & 31, rh = (lane >> 5) * 4;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  Lse lse[4];
+  Top2 top[4];
+  float zt[4];
+  int target[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb) {
+    lse[mb] = lse_empty();
+    top[mb] = top2_empty();
+    zt[mb] = -INFINITY;
+    const int m = (mt_base + 8 * wm + 2 * mb) * 16 + col;
+    target[mb] = (m < a.M) ? a.targets[m] : -1;
+  }
+  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles;
+  const int vocab = a.n_tiles * 16;
+  for (int nbk = blk.nb * 8; nbk < min(blk.nb * 8 + 8, nb_n); ++nbk) {
+    v16f acc[4][4];
+    lds_gemm_block(acc, reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles,
+                   a.m_tiles, a.k_tiles, nbk * kBlkTiles, mt_base, lds, lane, uwave, wn, wm);
+    const bool full = (nbk + 1) * kBlkTiles <= a.n_tiles;  // all 256 entries of the block exist (workgroup-uniform)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        asm volatile("" ::: "memory");  // one accumulator block at a time
+        // this lane's 16 entries of the block: n0 + 8 q + r (q, r = 0..3) in register 4 q + r
+        const int n0 = (nbk * kBlkTiles + 8 * wn + 2 * nb) * 16 + rh;
+        v16f z = acc[nb][mb];
+        if (!full) {
+#pragma unroll
+          for (int j = 0; j < 16; ++j)
+            if (n0 + 8 * (j >> 2) + (j & 3) >= vocab) z[j] = -INFINITY;
+        }
+        float bm = z[0];
+#pragma unroll
+        for (int j = 1; j < 16; ++j) bm = fmaxf(bm, z[j]);
+        if (bm > lse[mb].m) {  // -inf never gets here: an empty block leaves the state untouched
+          lse[mb].s *= __expf(lse[mb].m - bm);
+          lse[mb].m = bm;
+        }
+        if (lse[mb].m > -INFINITY) {
+          const float mm = lse[mb].m;
+          float add = 0.f;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) add += __expf(z[j] - mm);  // exp(-inf) = 0 for missing entries
+          lse[mb].s += add;
+        }
+        if (bm > top[mb].v2 || bm == top[mb].v1) {  // only then can the two largest (or a tie) change
+#pragma unroll
+          for (int j = 0; j < 16; ++j) top2_push(top[mb], z[j], n0 + 8 * (j >> 2) + (j & 3));
+        }
+        const int d = target[mb] - n0;
+        if (d >= 0 && d < 32 && (d & 4) == 0) {
+          const int idx = (d >> 3) * 4 + (d & 3);
+#pragma unroll
+          for (int j = 0; j < 16; ++j)
+            if (j == idx) zt[mb] = z[j];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb) {
+    const Lse ol = {__shfl_xor(lse[mb].m, 32, 64), __shfl_xor(lse[mb].s, 32, 64)};
+    const Top2 ot = {__shfl_xor(top[mb].v1, 32, 64), __shfl_xor(top[mb].i1, 32, 64), __shfl_xor(top[mb].v2, 32, 64)};
+    lse[mb] = lse_merge(lse[mb], ol);
+    top[mb] = top2_merge(top[mb], ot);
+    zt[mb] = fmaxf(zt[mb], __shfl_xor(zt[mb], 32, 64));
+    const int m = (mt_base + 8 * wm + 2 * mb) * 16 + col;
+    if (lane < 32 && m < a.M) {
+      ScorePartial* p = reinterpret_cast<ScorePartial*>(a.part) + ((size_t)(blk.nb * 2 + wn)) * a.M + m;
+      p->m = lse[mb].m; p->s = lse[mb].s; p->v1 = top[mb].v1; p->i1 = top[mb].i1; p->v2 = top[mb].v2;
+      p->zt = zt[mb];
+    }
+  }
+}
+
 template <int EPI>
 void launch_one(const LargeArgs& a, hipStream_t st) {
   static bool configured = false;  // per process; the attribute is a property of the function
@@ -225,6 +327,17 @@ void launch_one(const LargeArgs& a, hipStream_t st) {
 }
 
 }  // namespace
+
+void lmhead_score_lds(const ScoreHeadArgs& a, int slices, hipStream_t st) {
+  static bool configured = false;
+  const int lds_bytes = kStages * kStageBytes;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_lds), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              lds_bytes);
+    configured = true;
+  }
+  k_lmhead_lds<<<grid_of(slices, (a.m_tiles + kBlkTiles - 1) / kBlkTiles), 256, lds_bytes, st>>>(a, slices);
+}
 
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st) {
   if (epi == LEPI_STORE) launch_one<LEPI_STORE>(a, st);
