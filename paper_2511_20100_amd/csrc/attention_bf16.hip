@@ -142,75 +142,5 @@ void attention_decode_merge(h16_t* o, const float* part, int B, int m_tiles, int
                                                    n_chunks);
 }
 
-// ======================================================================================
-// prefill / scoring: one workgroup per (32 query positions, kv head, sequence).  Its 2 G
-// column blocks (16 positions x one query head each) are dealt to the four wavefronts; every
-// wavefront walks the page pairs 0 .. diagonal.
-// ======================================================================================
-constexpr int NQB = 4;
-
-__global__ __launch_bounds__(256) void k_attn_prefill(h16_t* o, const h16_t* q, int S, int Mpad, int Hq,
-                                                      int Hkv, int row_stride, KvPool pool, int layer) {
-  const int qb0 = blockIdx.x * 32, g = blockIdx.y, seq = blockIdx.z;
-  const int G = Hq / Hkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col = lane & 15, lg = lane >> 4;
-  const int n_blocks = 2 * G;
-  const int nqb = (n_blocks - wave + 3) / 4;  // blocks wave, wave + 4, ...
-  if (nqb <= 0) return;
-  const int* table = pool.page_table + (size_t)seq * row_stride * pool.max_pages;
-  const int seq_pages = (S + kPageTokens - 1) / kPageTokens;
-
-  v8bf qf[NQB][4];
-  int qpos[NQB], tok[NQB], head[NQB];
-#pragma unroll
-  for (int i = 0; i < NQB; ++i) {
-    const int blk = wave + 4 * i;
-    head[i] = g * G + (blk >> 1);
-    const int pos = qb0 + (blk & 1) * 16 + col;
-    const bool valid = (i < nqb) && pos < S;
-    qpos[i] = valid ? pos : -1;
-    tok[i] = seq * S + pos;
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-      v4u raw = {0u, 0u, 0u, 0u};
-      if (valid)
-        raw = *reinterpret_cast<const v4u*>(q + (size_t)tok[i] * Hq * HD + (size_t)head[i] * HD + kb * 32 + 8 * lg);
-      qf[i][kb] = __builtin_bit_cast(v8bf, raw);
-    }
-  }
-  AttnState<NQB> st;
-  attn_init(st);
-  const float scale = 0.08838834764831845f;
-  for (int pp = 0; pp <= (int)blockIdx.x; ++pp) {
-    const int id0 = table[min(2 * pp, seq_pages - 1)], id1 = table[min(2 * pp + 1, seq_pages - 1)];
-    attn_pair<NQB>(kv_page(pool, layer, 0, id0, g), kv_page(pool, layer, 0, id1, g),
-                   kv_page(pool, layer, 1, id0, g), kv_page(pool, layer, 1, id1, g), pp * 32, qf, qpos, nqb,
-                   scale, st, lane);
-  }
-#pragma unroll
-  for (int i = 0; i < NQB; ++i) {
-    if (i >= nqb) continue;
-    float l = st.l[i];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    if (qpos[i] < 0) continue;
-    const float inv = 1.0f / l;
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-      uint2 pk;
-      pk.x = pack_h16x2(st.o[i][cb][0] * inv, st.o[i][cb][1] * inv);
-      pk.y = pack_h16x2(st.o[i][cb][2] * inv, st.o[i][cb][3] * inv);
-      *reinterpret_cast<uint2*>(o + act_off(tok[i], head[i] * HD + cb * 16 + 4 * lg, Mpad)) = pk;
-    }
-  }
-}
-
-void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
-                       TokMap map, KvPool pool, int layer, hipStream_t st) {
-  k_attn_prefill<<<dim3((S + 31) / 32, Hkv, n_seqs), 256, 0, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
-                                                                  map.row_stride, pool, layer);
-}
-
 }  // namespace bf16
 }  // namespace mtmc

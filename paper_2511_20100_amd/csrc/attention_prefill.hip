@@ -1,0 +1,243 @@
+// Causal grouped-query attention of the prefill / scoring pass (head_dim 128) on the 32x32x16 MFMA.
+//
+// One workgroup per (256 query positions, query head, sequence): eight column blocks of 32 positions.
+// Wavefront w takes blocks w and 7 - w.  Every block takes part in every step up to the workgroup's last
+// key (steps beyond a block's own positions are fully masked and add zeros: branching on that made the
+// register allocator spill, which cost more than the ~12 % of MFMAs saved).  The workgroup walks the keys in steps of
+// 32 tokens (two 16-token pages): the four wavefronts copy the two K pages and two V pages of a step
+// (16 KiB) into a ring of LDS buffers with LDS-direct loads, three steps ahead, and every wavefront reads
+// them from there.
+//
+// Per step and column block:  S^T[token][column] = K Q^T  (8 MFMAs over the 128 dims), online softmax
+// down each column (a column's 32 tokens sit in 16 registers of lanes l and l + 32), then
+// O^T[dim][column] += V^T P^T (4 blocks of 32 dims x 2 MFMAs over 16 tokens).  exp(S^T) is already in
+// the B-operand layout of the second product: slot e of lane (column, half h) in token group jj holds
+// token 16 jj + 8 (e / 4) + 4 h + e % 4, and the V^T operand is gathered with the same map (two
+// 8-byte pieces of a V page row).  Page layouts: see attention_bf16.hip.
+#include "bf16_kernels.h"
+#include "device_utils.h"
+#include "frag.h"
+
+namespace mtmc {
+namespace bf16 {
+
+namespace {
+
+constexpr int PHD = 128;
+constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 KiB
+constexpr int kAStages = 4;
+constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
+
+typedef __attribute__((ext_vector_type(16))) float v16f;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+__device__ __forceinline__ const uint8_t* page_ptr(const KvPool& pool, int layer, int which, int page, int g) {
+  return (const uint8_t*)pool.base +
+         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)kPageBytes;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+constexpr int NCB = 2;    // column blocks per wavefront
+constexpr int QB = 256;   // query positions per workgroup
+
+__global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
+                                                           int row_stride, KvPool pool, int layer) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int qblk = gridDim.x - 1 - blockIdx.x;  // longest columns first
+  const int q0 = qblk * QB, qhead = blockIdx.y, seq = blockIdx.z;
+  const int G = Hq / Hkv, g = qhead / G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const int col = lane & 31, hh = lane >> 5;
+  const int* table = pool.page_table + (size_t)seq * row_stride * pool.max_pages;
+  const int seq_pages = (S + kPageTokens - 1) / kPageTokens;
+  const int n_steps = (min(q0 + QB, S) + 31) / 32;  // key blocks 0 .. n_steps - 1 (causal)
+
+  // ---- page ids of the steps, staged in LDS behind the ring (a global load inside the loop would be a
+  // vector load, and waiting for it would drain the ring of copies in flight)
+  int* s_ids = reinterpret_cast<int*>(lds + kAStages * kAStageBytes);
+  for (int i = threadIdx.x; i < 2 * n_steps; i += 256) s_ids[i] = table[min(i, seq_pages - 1)];
+  __syncthreads();
+  // ---- copies of one step: wavefront w moves KiB w of each of the four pages
+  auto issue = [&](int step, int buf) {
+    const int st = min(step, n_steps - 1);
+    const int id0 = __builtin_amdgcn_readfirstlane(s_ids[2 * st]);
+    const int id1 = __builtin_amdgcn_readfirstlane(s_ids[2 * st + 1]);
+    uint8_t* sb = lds + buf * kAStageBytes + uwave * 1024;
+    const uint32_t off = uwave * 1024 + lane * 16;
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 0, id0, g) + off), (lds_ptr_t)(sb), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 0, id1, g) + off),
+                                     (lds_ptr_t)(sb + kPageBytes), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 1, id0, g) + off),
+                                     (lds_ptr_t)(sb + 2 * kPageBytes), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 1, id1, g) + off),
+                                     (lds_ptr_t)(sb + 3 * kPageBytes), 16, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < kAStages - 1; ++s) issue(s, s);
+
+  // ---- this wavefront's column blocks (positions q0 + 32 b + col, b = wave and 7 - wave).
+  // Q fragments (B operand: column col, dims 16 j + 8 hh + 0..7).
+  v8bf qf[NCB][8];
+  int qpos[NCB];
+#pragma unroll
+  for (int i = 0; i < NCB; ++i) {
+    const int b = (i == 0) ? uwave : 7 - uwave;
+    const int pos = q0 + 32 * b + col;
+    qpos[i] = (pos < S) ? pos : -1;
+    const h16_t* qrow = q + ((size_t)seq * S + max(qpos[i], 0)) * Hq * PHD + (size_t)qhead * PHD + 8 * hh;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      v4u raw = {0u, 0u, 0u, 0u};
+      if (qpos[i] >= 0) raw = *reinterpret_cast<const v4u*>(qrow + 16 * j);
+      qf[i][j] = __builtin_bit_cast(v8bf, raw);
+    }
+  }
+  v16f oacc[NCB][4];
+  float mrun[NCB], lrun[NCB];
+#pragma unroll
+  for (int i = 0; i < NCB; ++i) {
+    mrun[i] = -INFINITY;
+    lrun[i] = 0.f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[i][d][e] = 0.f;
+  }
+  // exp(x / sqrt(128)) = exp2(x c)
+  const float c2 = 0.08838834764831845f * 1.4426950408889634f;
+  // lane offsets inside a stage: K operand (token row col, dim group 2 j + hh) and V operand
+  // (dim row 32 d + col, tokens 4 hh .. and 8 + 4 hh .. of page jj)
+  const int koff = (col >> 4) * kPageBytes + (hh * 16 + (col & 15)) * 16;
+  const int voff = 2 * kPageBytes + col * 32 + hh * 8;
+
+  // One key step for both column blocks.
+  auto step = [&](int t, const uint8_t* sb) {
+    // ---- S^T = K Q^T: K fragments read from LDS once, used by every active block
+    v16f sacc[NCB];
+#pragma unroll
+    for (int i = 0; i < NCB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[i][e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const v8bf kf = *reinterpret_cast<const v8bf*>(sb + koff + j * 512);
+#pragma unroll
+      for (int i = 0; i < NCB; ++i)
+        sacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[i][j], sacc[i], 0, 0, 0);
+    }
+    // ---- online softmax down each column; P^T fragments for the two token groups
+    v8bf pf[NCB][2];
+    const bool diag = 32 * t + 31 > q0;  // some column of the workgroup may not see all 32 tokens
+#pragma unroll
+    for (int i = 0; i < NCB; ++i) {
+      float sv[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sv[e] = sacc[i][e];
+      if (diag || qpos[i] < 0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int tok = 32 * t + 8 * (e >> 2) + 4 * hh + (e & 3);
+          if (tok > qpos[i]) sv[e] = -INFINITY;
+        }
+      }
+      float bm = sv[0];
+#pragma unroll
+      for (int e = 1; e < 16; ++e) bm = fmaxf(bm, sv[e]);
+      bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+      const float m_new = fmaxf(mrun[i], bm);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f((mrun[i] - m_safe) * c2);  // exp2(-inf) = 0 on the first step
+      const float mc = m_safe * c2;
+      float psum = 0.f;
+      float p[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(sv[e] * c2 - mc);
+        psum += p[e];
+      }
+      lrun[i] = lrun[i] * corr + psum;
+      // rescale O only when some column's maximum moved (rare after the first steps)
+      if (__builtin_amdgcn_ballot_w64(m_new > mrun[i]) != 0) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) oacc[i][d] = oacc[i][d] * corr;
+      }
+      mrun[i] = m_new;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        v4u pk;
+        pk[0] = pack_h16x2(p[8 * jj + 0], p[8 * jj + 1]);
+        pk[1] = pack_h16x2(p[8 * jj + 2], p[8 * jj + 3]);
+        pk[2] = pack_h16x2(p[8 * jj + 4], p[8 * jj + 5]);
+        pk[3] = pack_h16x2(p[8 * jj + 6], p[8 * jj + 7]);
+        pf[i][jj] = __builtin_bit_cast(v8bf, pk);
+      }
+    }
+    // ---- O^T += V^T P^T: V fragments read from LDS once, used by every active block
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const uint8_t* vp = sb + voff + jj * kPageBytes + d * 1024;
+        const uint2 va = *reinterpret_cast<const uint2*>(vp);
+        const uint2 vb = *reinterpret_cast<const uint2*>(vp + 16);
+        const v4u raw = {va.x, va.y, vb.x, vb.y};
+        const v8bf vf = __builtin_bit_cast(v8bf, raw);
+#pragma unroll
+        for (int i = 0; i < NCB; ++i)
+          oacc[i][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[i][jj], oacc[i][d], 0, 0, 0);
+      }
+  };
+  for (int t = 0; t < n_steps; ++t) {
+    wait_vm<(kAStages - 2) * 4>();  // step t landed; t + 1, t + 2 may be in flight
+    __builtin_amdgcn_s_barrier();
+    issue(t + kAStages - 1, (t + kAStages - 1) % kAStages);
+    const uint8_t* sb = lds + (t % kAStages) * kAStageBytes;
+    step(t, sb);
+  }
+  wait_vm<0>();  // the clamped copies past the last step still target this workgroup's LDS
+
+  // ---- normalise and store: lane holds dims 32 d + 8 qq + 4 hh + 0..3 of its column in registers 4 qq ..
+#pragma unroll
+  for (int i = 0; i < NCB; ++i) {
+    float l = lrun[i];
+    l += __shfl_xor(l, 32, 64);
+    if (qpos[i] < 0) continue;
+    const float inv = 1.0f / l;
+    const int tok = seq * S + qpos[i];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+      for (int qq = 0; qq < 4; ++qq) {
+        uint2 pk;
+        pk.x = pack_h16x2(oacc[i][d][4 * qq] * inv, oacc[i][d][4 * qq + 1] * inv);
+        pk.y = pack_h16x2(oacc[i][d][4 * qq + 2] * inv, oacc[i][d][4 * qq + 3] * inv);
+        *reinterpret_cast<uint2*>(o + act_off(tok, qhead * PHD + 32 * d + 8 * qq + 4 * hh, Mpad)) = pk;
+      }
+  }
+}
+
+}  // namespace
+
+void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
+                       TokMap map, KvPool pool, int layer, hipStream_t st) {
+  static bool configured = false;
+  // ring of K/V steps + page ids of one sequence (2 per step of 32 tokens)
+  const int lds_bytes = kAStages * kAStageBytes + 2 * ((S + 31) / 32) * (int)sizeof(int);
+  constexpr int kLdsMax = 160 * 1024;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill32), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kLdsMax);
+    configured = true;
+  }
+  k_attn_prefill32<<<dim3((S + QB - 1) / QB, Hq, n_seqs), 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
+                                                                             map.row_stride, pool, layer);
+}
+
+}  // namespace bf16
+}  // namespace mtmc
