@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 from paper_2511_20100_amd import inputs  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+# HBM bytes one launch of the gate/up decode kernel moves at the 1.5B workload, from FETCH_SIZE / WRITE_SIZE
+# counter runs scaled by the library's copy kernel (profiles/decode_kernels_1p5b_hbm_counters.txt).
+# Belongs to k_gemm_dec<6, 4, 4, 2, 2, 1, SWIGLU>: set to None when that kernel or its launch shape changes.
+GATE_UP_TRAFFIC_1P5B = 27934.5 * 1024 * 2.000 + 1120.0 * 1024 * 1.000
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
 
 WORKLOADS = {
@@ -67,7 +71,7 @@ def cpu_baseline(weights, cfg, prompts, max_positions):
                          n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab,
                          rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, w=weights.f32, max_positions=max_positions)
     if cfg.n_layers * cfg.d_model > 10000:
-        n_p, n_s, n_new = 1, 2, 8
+        n_p, n_s, n_new = 1, 2, 48
     else:
         n_p, n_s, n_new = prompts.shape[0], 2, 32
     t0 = time.perf_counter()
@@ -127,7 +131,7 @@ def main() -> int:
         src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst.copy_(src)
+        mtmc.mtmc_copy_probe(dst, src)
         torch.cuda.synchronize()
         del src, dst
     prompts_np = inputs.make_prompts(n_prompts, prompt_len, cfg.vocab, seed=2)
@@ -191,7 +195,8 @@ def main() -> int:
     if k_launches > 0:
         k_us = 1e3 * k_ms / k_launches
         roofline = {"bound": "hbm", "achieved": gate_up_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": gate_up_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                    "frac": gate_up_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                    "traffic": GATE_UP_TRAFFIC_1P5B if args.workload == "1p5b" else None,
                     "kernel": "k_gemm_dec<..., SWIGLU> (gate/up projection, one launch per layer per decode step)",
                     "bytes_per_launch": gate_up_bytes, "us_per_launch": k_us, "timed_launches": k_launches,
                     "empty_event_pair_us": 1e3 * k_empty_ms}

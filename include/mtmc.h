@@ -163,6 +163,14 @@ int mtmc_kernel_timer(mtmc_weights* w, int kernel_class, int every_n_steps);
 int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* total_ms, int64_t* launches,
                            double* empty_pair_ms);
 
+/*
+ * Diagnostics for measurement: copies `bytes` (a multiple of 16; both device pointers 16-byte
+ * aligned, ranges not overlapping) from src to dst with one plain copy kernel.  A kernel that is
+ * known to read and to write exactly `bytes`: hardware byte counters of a profiled run are scaled
+ * by what they report for it.  Stream-ordered, does not synchronise.
+ */
+int mtmc_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Message of the last failing call on this thread; valid until the next library call. */
 const char* mtmc_last_error(void);
 

@@ -141,6 +141,15 @@ extern "C" int mtmc_kernel_timer_read(mtmc_weights* w, void* stream, double* tot
   return kernel_timer_read(w, (hipStream_t)stream, total_ms, launches, empty_pair_ms);
 }
 
+extern "C" int mtmc_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  MTMC_REQUIRE(dst != nullptr && src != nullptr, "NULL pointer argument");
+  MTMC_REQUIRE(bytes % 16 == 0 && ((uintptr_t)dst & 15) == 0 && ((uintptr_t)src & 15) == 0,
+               "bytes and both pointers must be multiples of 16");
+  launch_copy_probe(dst, src, bytes, (hipStream_t)stream);
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}
+
 extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
   MTMC_REQUIRE(w != nullptr, "weights is NULL");
   MTMC_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));

@@ -13,6 +13,7 @@ void launch_build_page_table(int* table, int rows, int max_pages, int n_samples,
 void launch_set_int(int* p, int v, hipStream_t st);
 void launch_add_int(int* p, int v, hipStream_t st);
 void launch_fill_u32(uint32_t* p, uint32_t v, size_t n, hipStream_t st);
+void launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t st);
 // dst[r, :] = src[(r / n_rep) * src_stride + src_offset + (r % n_rep) * rep_stride, :]
 void launch_gather_rows(float* dst, const float* src, int rows, int d, int n_rep, int src_stride,
                         int src_offset, int rep_stride, hipStream_t st);

@@ -39,6 +39,17 @@ void launch_fill_u32(uint32_t* p, uint32_t v, size_t n, hipStream_t st) {
   k_fill_u32<<<blocks, 256, 0, st>>>(p, v, n);
 }
 
+// Plain 16-byte-per-lane copy: a kernel of exactly known traffic for calibrating byte counters.
+__global__ void k_copy_probe(uint4* dst, const uint4* src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+void launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  const size_t n = bytes / 16;
+  if (n == 0) return;
+  k_copy_probe<<<4096, 256, 0, st>>>((uint4*)dst, (const uint4*)src, n);
+}
+
 __global__ void k_gather_rows(float* dst, const float* src, int d, int n_rep, int src_stride,
                               int src_offset, int rep_stride) {
   const int r = blockIdx.x;

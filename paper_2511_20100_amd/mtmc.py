@@ -62,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_kernel_timer_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
                                            ctypes.POINTER(ctypes.c_double)]
     lib.mtmc_kernel_timer_read.restype = ctypes.c_int
+    lib.mtmc_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.mtmc_copy_probe.restype = ctypes.c_int
     lib.mtmc_poll_errors.argtypes = [vp, vp]
     lib.mtmc_poll_errors.restype = ctypes.c_int
     lib.mtmc_last_error.argtypes = []
@@ -72,7 +74,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mtmc_rollout_workspace_bytes",
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
-           "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read")
+           "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe")
 
 
 def mtmc_last_error() -> str:
@@ -192,6 +194,14 @@ def mtmc_kernel_timer_read(handle: int, stream: Optional[torch.cuda.Stream] = No
     _check(_lib.mtmc_kernel_timer_read(handle, _stream_ptr(stream), ctypes.byref(ms), ctypes.byref(n),
                                        ctypes.byref(empty)))
     return ms.value, n.value, empty.value
+
+
+def mtmc_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """dst <- src with the library's plain copy kernel (same byte size, contiguous device tensors)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
+        raise ValueError("mtmc_copy_probe needs two device tensors of the same byte size")
+    _check(_lib.mtmc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)))
 
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:
