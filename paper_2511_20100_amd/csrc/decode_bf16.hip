@@ -24,53 +24,66 @@ namespace bf16 {
 
 // acc[nb][mb] += W[n tile nt0 + nb] . X[m tile mb] over k tiles [k0, k1).  Weight fragments (HBM,
 // long latency) are kept PFW k-steps ahead in registers, activation fragments (L2) PFX ahead.
+// The operand streams of one wavefront: weight tiles nt0 .. nt0 + NB - 1 and all MB token tiles over k tiles
+// [k0, k1), through register rings PFW / PFX k-steps deep.  start() issues the first loads (so that they are
+// in flight while the kernel does other things), run() multiplies.
 template <int NB, int MB, int PFW, int PFX>
-__device__ __forceinline__ void wave_gemm_dec(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles, int nt0,
-                                              const h16_t* __restrict__ Xt, int m_tiles, int k0, int k1,
-                                              int lane, v4f (&acc)[NB][MB]) {
+struct DecStream {
   static_assert(PFW % PFX == 0, "the weight ring must be a multiple of the activation ring");
-  if (k0 >= k1) return;
   const h16_t* wp[NB];
   const h16_t* xp[MB];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512 + lane * 8;
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mb, m_tiles - 1) * 512 + lane * 8;
-  const size_t xstep = (size_t)m_tiles * 512;
+  size_t xstep;
+  int k0, k1;
   v8bf wr[PFW][NB], xr[PFX][MB];
+
+  __device__ __forceinline__ void start(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles, int nt0,
+                                        const h16_t* __restrict__ Xt, int m_tiles, int k0_, int k1_, int lane) {
+    k0 = k0_;
+    k1 = k1_;
+    if (k0 >= k1) return;
 #pragma unroll
-  for (int s = 0; s < PFW; ++s) {
-    const int kk = min(k0 + s, k1 - 1);
+    for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512 + lane * 8;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kk * 512, 0);
-  }
-#pragma unroll
-  for (int s = 0; s < PFX; ++s) {
-    const int kk = min(k0 + s, k1 - 1);
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kk * xstep, 0);
-  }
-  for (int ks = k0; ks < k1; ks += PFW) {
+    for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mb, m_tiles - 1) * 512 + lane * 8;
+    xstep = (size_t)m_tiles * 512;
 #pragma unroll
     for (int s = 0; s < PFW; ++s) {
-      if (ks + s < k1) {
+      const int kk = min(k0 + s, k1 - 1);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+      for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kk * 512, 0);
+    }
 #pragma unroll
-          for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s % PFX][mb], acc[nb][mb]);
-        const int kw = ks + s + PFW, kx = ks + s + PFX;
-        if (kw < k1) {
+    for (int s = 0; s < PFX; ++s) {
+      const int kk = min(k0 + s, k1 - 1);
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kw * 512, 0);
-        }
-        if (kx < k1) {
+      for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kk * xstep, 0);
+    }
+  }
+
+  __device__ __forceinline__ void run(v4f (&acc)[NB][MB]) {
+    if (k0 >= k1) return;
+    for (int ks = k0; ks < k1; ks += PFW) {
 #pragma unroll
-          for (int mb = 0; mb < MB; ++mb) xr[s % PFX][mb] = load_frag(xp[mb] + (size_t)kx * xstep, 0);
+      for (int s = 0; s < PFW; ++s) {
+        if (ks + s < k1) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s % PFX][mb], acc[nb][mb]);
+          const int kw = ks + s + PFW, kx = ks + s + PFX;
+          if (kw < k1) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)kw * 512, 0);
+          }
+          if (kx < k1) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) xr[s % PFX][mb] = load_frag(xp[mb] + (size_t)kx * xstep, 0);
+          }
         }
       }
     }
   }
-}
+};
 
 __device__ __forceinline__ float silu_d(float g) { return g / (1.0f + expf(-g)); }
 
@@ -99,34 +112,62 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // A split-K launch only needs them in the kernel that finishes the sum: its first workgroup
   // computes them on the side and leaves them in rs_out.
   constexpr bool kProducer = (EPI == DEPI_RESID || EPI == DEPI_PARTIAL);
-  if (EPI != DEPI_PARTIAL || (blockIdx.x == 0 && blockIdx.y == 0)) {
-    constexpr int NT = WAVES * 64;
-    const int P = NT / Mpad;  // Mpad <= 128 <= NT
-    const int m = tid % Mpad, part = tid / Mpad;
-    const bool two = !kProducer && a.ss_cur && a.ss_old != a.ss_cur;
-    float sa = 0.f, sb = 0.f;
-    if (a.ss_cur && part < P) {
-      // batches of 8 independent loads, then the adds in index order
-      for (int t0 = part; t0 < a.ss_tiles; t0 += 8 * P) {
-        float va[8], vb[8];
+  const bool do_rs = EPI != DEPI_PARTIAL || (blockIdx.x == 0 && blockIdx.y == 0);  // workgroup-uniform
+  constexpr int NT = WAVES * 64;
+  constexpr int BT = (WAVES >= 8) ? 8 : 24;  // loads per batch (all tiles of d = 1536 in one batch)
+  const int P = NT / Mpad;  // Mpad <= 128 <= NT
+  const int m = tid % Mpad, part = tid / Mpad;
+  const bool two = !kProducer && a.ss_cur && a.ss_old != a.ss_cur;
+  float sa = 0.f, sb = 0.f;
+  float va[BT], vb[BT];  // the last batch stays pending while the operand streams are started
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int t = t0 + u * P;
-          va[u] = (t < a.ss_tiles) ? a.ss_cur[(size_t)t * Mpad + m] : 0.f;
-          vb[u] = (two && t < a.ss_tiles) ? a.ss_old[(size_t)t * Mpad + m] : 0.f;
-        }
+  for (int u = 0; u < BT; ++u) va[u] = vb[u] = 0.f;
+  if (do_rs && a.ss_cur && part < P) {
+    int t0 = part;
+    for (; t0 + BT * P < a.ss_tiles; t0 += BT * P) {  // full batches: independent loads, then adds in index order
+      float fa[BT], fb[BT];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          sa += va[u];
-          sb += vb[u];
-        }
+      for (int u = 0; u < BT; ++u) {
+        fa[u] = a.ss_cur[(size_t)(t0 + u * P) * Mpad + m];
+        fb[u] = two ? a.ss_old[(size_t)(t0 + u * P) * Mpad + m] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < BT; ++u) {
+        sa += fa[u];
+        sb += fb[u];
       }
     }
+#pragma unroll
+    for (int u = 0; u < BT; ++u) {
+      const int t = t0 + u * P;
+      va[u] = (t < a.ss_tiles) ? a.ss_cur[(size_t)t * Mpad + m] : 0.f;
+      vb[u] = (two && t < a.ss_tiles) ? a.ss_old[(size_t)t * Mpad + m] : 0.f;
+    }
+  }
+  // ---- operand streams: issued behind the row-scale loads, in flight while the scales are worked out
+  int kbeg = 0, kend = a.k_tiles;
+  if (EPI == DEPI_PARTIAL) {
+    const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
+    kbeg = blockIdx.y * per_split;
+    kend = min(a.k_tiles, kbeg + per_split);
+  }
+  const int per_wave = (max(kend - kbeg, 0) + WAVES - 1) / WAVES;
+  const int k0 = kbeg + wave * per_wave, k1 = min(kend, k0 + per_wave);
+  DecStream<NB, MB, PFW, PFX> stream;
+  stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, k1, lane);
+#pragma unroll
+  for (int u = 0; u < BT; ++u) {
+    sa += va[u];
+    sb += vb[u];
+  }
+  if (do_rs) {
     if (part < P) {
       s_part[0][tid] = sa;
       s_part[1][tid] = sb;
     }
-    __syncthreads();
+    // workgroup barrier on the LDS writes only (a __syncthreads() would also wait for the operand streams)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
     if (tid < Mpad) {
       float sc = 1.f;
       if (a.ss_cur && (kProducer || two)) {
@@ -142,20 +183,12 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       if (EPI == DEPI_PARTIAL) a.rs_out[tid] = sc;
     }
   }
-  int kbeg = 0, kend = a.k_tiles;
-  if (EPI == DEPI_PARTIAL) {
-    const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
-    kbeg = blockIdx.y * per_split;
-    kend = min(a.k_tiles, kbeg + per_split);
-  }
-  const int per_wave = (max(kend - kbeg, 0) + WAVES - 1) / WAVES;
-  const int k0 = kbeg + wave * per_wave, k1 = min(kend, k0 + per_wave);
   v4f acc[NB][MB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
-  wave_gemm_dec<NB, MB, PFW, PFX>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, k1, lane, acc);
+  stream.run(acc);
   // Sum over the K slices: every wavefront publishes its accumulators; wavefront w then adds the WAVES
   // slices of token tiles w, w + WAVES, ... in index order and runs the epilogue for those tokens.
 #pragma unroll
@@ -295,7 +328,7 @@ static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
   if constexpr (MB > 4) {
     launch_dec_t<1, MB, 8, 2, 2, 1>(a, epi, st);
   } else {
-    if (a.k_tiles >= 128) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st);
+    if (a.k_tiles >= 48) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st);
     else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st);
   }
 }

@@ -109,11 +109,13 @@ inline int tiles16(int n) { return (n + 15) / 16; }
 
 inline int tiles32(int n) { return (n + 31) / 32; }
 
-// Split-K factor of a decode GEMM: enough workgroups to cover the chip, while every wavefront
-// (4 per workgroup) still walks at least two k tiles.
+// Split-K factor of a decode GEMM: as many workgroups as fit into ONE round on the 256 CUs (a CU
+// that hosts two of them takes twice as long), while every wavefront (4 per workgroup) still
+// walks at least two k tiles.
 int choose_ksplit(int n_tiles, int k_tiles, int m_tiles) {
-  const int groups = (n_tiles + bf16::skinny_nb(m_tiles) - 1) / bf16::skinny_nb(m_tiles);
-  const int want = (320 + groups - 1) / groups;
+  const int nb = bf16::dec_wide_nb(m_tiles);
+  const int groups = (n_tiles + nb - 1) / nb;
+  const int want = std::max(1, 256 / groups);
   return std::max(1, std::min(want, k_tiles / 8));
 }
 
