@@ -367,8 +367,9 @@ static void launch_large(const LargeArgs& a, int epi, hipStream_t st) {
 // The LDS-staged kernel (256 x 256 blocks, one workgroup per CU) takes over once the output has
 // at least `lds_min_blocks` such blocks; smaller problems keep the 128 x 128 direct kernel, which
 // spreads them over more workgroups.
-static bool use_lds_kernel(int n_tiles, int m_tiles, int lds_min_blocks) {
-  return ((n_tiles + 15) / 16) * ((m_tiles + 15) / 16) >= lds_min_blocks;
+static bool use_lds_kernel(int n_tiles, int k_tiles, int m_tiles, int lds_min_blocks) {
+  // the LDS pipeline streams k-steps in pairs through a ring of four buffers
+  return k_tiles >= 4 && k_tiles % 2 == 0 && ((n_tiles + 15) / 16) * ((m_tiles + 15) / 16) >= lds_min_blocks;
 }
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
                     int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st) {
@@ -376,7 +377,7 @@ void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, 
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M; a.N = N;
   a.out_f32 = C; a.ld_out = ldc;
   const int epi = accumulate ? LEPI_ADD : LEPI_STORE;
-  if (use_lds_kernel(n_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, epi, st);
+  if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, epi, st);
   else launch_large(a, epi, st);
 }
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
@@ -384,7 +385,7 @@ void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, co
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
   a.out_bf16 = act;
-  if (use_lds_kernel(n_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, LEPI_SWIGLU, st);
+  if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, LEPI_SWIGLU, st);
   else launch_large(a, LEPI_SWIGLU, st);
 }
 
@@ -470,7 +471,7 @@ void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const 
   a.n_groups = (n_tiles + 7) / 8;
   const int blocks = score_head_blocks(n_tiles, &a.groups_per_block);
   // same vocabulary slices (and partial results) in both kernels: 128 row tiles per slice
-  if (use_lds_kernel(n_tiles, m_tiles, lds_min_blocks)) lmhead_score_lds(a, blocks, st);
+  if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) lmhead_score_lds(a, blocks, st);
   else k_lmhead_score<<<dim3(blocks, (m_tiles + 7) / 8), 256, 0, st>>>(a);
 }
 

@@ -25,6 +25,7 @@ namespace bf16 {
 namespace {
 
 constexpr int kStages = 4;
+constexpr int kPersistentGrid = 256;                 // CUs of the device; a multiple of the 8 XCDs
 constexpr int kBlkTiles = 16;                       // 16-row tiles per workgroup tile side
 constexpr int kStageBytes = 2 * kBlkTiles * 1024;   // weight blocks, then activation blocks
 constexpr int kLoadsPerStage = 2 * kBlkTiles / 4;   // LDS-direct loads each wavefront issues per step
@@ -52,7 +53,11 @@ __device__ __forceinline__ void mfma32_acc(v16f& acc, v8bf a, v8bf b) {
   asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
 }
 
-__device__ __forceinline__ float silu_l(float g) { return g / (1.0f + expf(-g)); }
+// silu with the hardware exp2 / reciprocal (about 1e-6 relative error; the result is rounded to fp16 anyway):
+// the 128 evaluations per lane and output block would otherwise take a tenth of the block's time
+__device__ __forceinline__ float silu_l(float g) {
+  return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+}
 
 // Launch index -> output block: XCD (L % 8) owns token blocks xcd + 8 i and walks them in bands of
 // kBand token blocks x all feature blocks, so workgroups resident together on an XCD share panels
@@ -73,53 +78,44 @@ int grid_of(int nb_n, int nb_m) {
 
 enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
 
-// acc (4 x 4 accumulator blocks of 32 x 32, v_mfma_f32_32x32x16_f16, 16 registers each) = the 128 x 128
-// part of this wavefront (wn, wm) of the 256 x 256 output block at (nt_base, mt_base), over all K
-// k-steps.  Called by all four wavefronts of the workgroup together; `lds` is the ring of kStages
-// buffers.  May be called again for another block: it starts with a barrier so that the ring is
-// refilled only after every wavefront has left the previous call.
-__device__ __forceinline__ void lds_gemm_block(v16f (&acc)[4][4], const uint8_t* Wt, const uint8_t* Xt, int n_tiles,
-                                               int m_tiles, int K, int nt_base, int mt_base, uint8_t* lds, int lane,
-                                               int uwave, int wn, int wm) {
-  __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8));  // nothing of an earlier block in flight
-  __builtin_amdgcn_s_barrier();
-  // ---- this wavefront's share of every stage: weight blocks 4 wave .. + 3 and activation blocks
-  // 4 wave .. + 3 (tile indices past the end are clamped: such blocks are multiplied but never stored).
-  // Block addresses are wavefront-uniform (scalar registers); the lane adds its 16-byte slot.
-  const uint8_t* wsrc[4];
-  const uint8_t* xsrc[4];
+// This wavefront's share of the copies of one 256 x 256 output block: weight blocks 4 wave .. + 3 and
+// activation blocks 4 wave .. + 3 of every k-step (tile indices past the end are clamped: such blocks are
+// multiplied but never stored).  Wavefront-uniform addresses of k-step 0; the lane adds its 16-byte slot.
+struct TileSrc {
+  const uint8_t* w[4];
+  const uint8_t* x[4];
+};
+__device__ __forceinline__ TileSrc tile_src(const uint8_t* Wt, const uint8_t* Xt, int n_tiles, int m_tiles, int K,
+                                            int nt_base, int mt_base, int uwave) {
+  TileSrc t;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int nt = min(nt_base + 4 * uwave + j, n_tiles - 1);
-    const int mt = min(mt_base + 4 * uwave + j, m_tiles - 1);
-    wsrc[j] = Wt + ((size_t)nt * K) * 1024;
-    xsrc[j] = Xt + (size_t)mt * 1024;
+    t.w[j] = Wt + ((size_t)min(nt_base + 4 * uwave + j, n_tiles - 1) * K) * 1024;
+    t.x[j] = Xt + (size_t)min(mt_base + 4 * uwave + j, m_tiles - 1) * 1024;
   }
+  return t;
+}
+
+// The matrix pipeline of a workgroup over a SEQUENCE of output blocks.  `tile_at(i, nt_base, mt_base)`
+// names the i-th block (false: no more), `epilogue(acc, nt_base, mt_base)` consumes a finished one:
+// acc = 4 x 4 accumulator blocks of 32 x 32 (v_mfma_f32_32x32x16_f16, 16 registers each) = the 128 x 128
+// part of this wavefront (wn, wm).  The k-steps of consecutive blocks form one stream through the ring of
+// kStages LDS buffers: while the last steps of a block are multiplied the first steps of the next one are
+// already being fetched, and its first fragments are read, so that a new block starts without refilling
+// the pipeline and its copies run under the epilogue of the previous one.  K >= kStages and even.
+template <typename TileAt, typename Epilogue>
+__device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t* Xt, int n_tiles, int m_tiles, int K,
+                                                uint8_t* lds, int lane, int uwave, int wn, int wm, TileAt tile_at,
+                                                Epilogue epilogue) {
+  int nt_base = 0, mt_base = 0;
+  if (!tile_at(0, nt_base, mt_base)) return;  // whole workgroup
   const size_t xstep = (size_t)m_tiles * 1024;
   const uint32_t lane16 = lane * 16;
-  auto issue = [&](int kt, int buf) {
-    const int kk = min(kt, K - 1);
-    uint8_t* sb = lds + buf * kStageBytes + uwave * 4096;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) copy_block_to_lds(wsrc[j] + (size_t)kk * 1024 + lane16, sb + j * 1024);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      copy_block_to_lds(xsrc[j] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j) * 1024);
-  };
-
-#pragma unroll
-  for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) acc[nb][mb][j] = 0.f;
-
   // A 32-row operand of the 32x32x16 MFMA (lane l: row l % 32, 8 consecutive k of half l / 32) is
   // gathered from two adjacent 16-row blocks: lane -> (block (l % 32) / 16, row l % 16, k group
   // 2 p + l / 32) for the p-th pair of k groups; the two pairs of a k-step are 512 bytes apart.
   const int r32 = lane & 31;
   const int lane_off = (r32 >> 4) * 1024 + (((lane >> 5) << 4) + (r32 & 15)) * 16;
-
   // Fragments of one k-step: per 32-row block two operands (k groups 0,1 and 2,3).
   struct Frags { v8bf w[4][2], x[4][2]; };
   auto read_frag = [&](Frags& f, const uint8_t* sb, int i) {  // i = 0..15
@@ -127,48 +123,78 @@ __device__ __forceinline__ void lds_gemm_block(v16f (&acc)[4][4], const uint8_t*
     if (i < 8) f.x[blk][p] = *reinterpret_cast<const v8bf*>(sb + (kBlkTiles + 8 * wm + 2 * blk) * 1024 + p * 512);
     else f.w[blk][p] = *reinterpret_cast<const v8bf*>(sb + (8 * wn + 2 * blk) * 1024 + p * 512);
   };
-  auto issue_one = [&](int kk, uint8_t* sb, int j) {  // j = 0..7
-    if (j < 4) copy_block_to_lds(wsrc[j] + (size_t)kk * 1024 + lane16, sb + j * 1024);
-    else copy_block_to_lds(xsrc[j - 4] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j - 4) * 1024);
-  };
-  // Step kt multiplies the fragments already in registers; spread between its 32 MFMAs (which take 32
-  // cycles each and leave the issue slots free) are the 16 LDS reads of the fragments of step kt + 1
-  // and the 8 block fetches of step kt + kStages, into the buffer step kt was read from.
-  auto step = [&](const Frags& cur, Frags& next, int kt) {
-    // own LDS reads done (they all feed `cur`); blocks of step kt + 1 landed, kt + 2 and kt + 3 may fly
-    __builtin_amdgcn_s_waitcnt((((kStages - 2) * kLoadsPerStage) & 15) | ((((kStages - 2) * kLoadsPerStage) >> 4) << 14) |
-                               (7 << 4) | (0 << 8));
-    __builtin_amdgcn_s_barrier();
-    const uint8_t* rb = lds + ((kt + 1) % kStages) * kStageBytes + lane_off;  // step K: clamped copy, never used
-    uint8_t* fb = lds + (kt % kStages) * kStageBytes + uwave * 4096;
-    const int kk = min(kt + kStages, K - 1);
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const int pp = i >> 4, nb = (i >> 2) & 3, mb = i & 3;
-      mfma32_acc(acc[nb][mb], cur.w[nb][pp], cur.x[mb][pp]);
-      if ((i & 1) == 0) read_frag(next, rb, i >> 1);
-      if ((i & 3) == 1) issue_one(kk, fb, i >> 2);
-    }
+  auto issue_one = [&](const TileSrc& t, int kk, uint8_t* sb, int j) {  // j = 0..7; sb = this wavefront's part of a buffer
+    if (j < 4) copy_block_to_lds(t.w[j] + (size_t)kk * 1024 + lane16, sb + j * 1024);
+    else copy_block_to_lds(t.x[j - 4] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j - 4) * 1024);
   };
 
+  TileSrc cur = tile_src(Wt, Xt, n_tiles, m_tiles, K, nt_base, mt_base, uwave);
+  // ---- fill the ring with the first kStages steps of the first block, read its first fragments
 #pragma unroll
-  for (int s = 0; s < kStages; ++s) issue(s, s);
+  for (int s = 0; s < kStages; ++s)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) issue_one(cur, s, lds + s * kStageBytes + uwave * 4096, j);
   Frags fa, fb;
   wait_vmcnt<(kStages - 1) * kLoadsPerStage>();
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int i = 0; i < 16; ++i) read_frag(fa, lds + lane_off, i);
-  int kt = 0;
-  for (; kt + 1 < K; kt += 2) {
-    step(fa, fb, kt);
-    step(fb, fa, kt + 1);
-  }
-  if (kt < K) step(fa, fb, kt);
-  wait_vmcnt<0>();  // the clamped loads past the last step still target this workgroup's LDS
-  // the last MFMAs were issued from inline assembly: give them time to retire before their
-  // accumulators are read (16 passes of 4 cycles cover the longest one)
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
+  int g0 = 0;  // stream index of step 0 of the current block (step g lives in buffer g % kStages)
+  for (int ti = 0;; ++ti) {
+    int nt_next = 0, mt_next = 0;
+    const bool has_next = tile_at(ti + 1, nt_next, mt_next);
+    const TileSrc nxt = has_next ? tile_src(Wt, Xt, n_tiles, m_tiles, K, nt_next, mt_next, uwave) : cur;
+    v16f acc[4][4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[nb][mb][j] = 0.f;
+    asm volatile("s_nop 7" ::: "memory");  // accumulator writes settle before the first (inline-asm) MFMA reads them
+    // Step kt multiplies the fragments already in registers; spread between its 32 MFMAs (which take 32
+    // cycles each and leave the issue slots free) are the 16 LDS reads of the fragments of stream step
+    // g + 1 and the 8 block fetches of stream step g + kStages, into the buffer step g was read from.
+    auto step = [&](const Frags& fc, Frags& fn, int kt) {
+      // own LDS reads done (they all feed `fc`); blocks of step g + 1 landed, g + 2 and g + 3 may fly
+      __builtin_amdgcn_s_waitcnt((((kStages - 2) * kLoadsPerStage) & 15) | ((((kStages - 2) * kLoadsPerStage) >> 4) << 14) |
+                                 (7 << 4) | (0 << 8));
+      __builtin_amdgcn_s_barrier();
+      const int g = g0 + kt;
+      const uint8_t* rb = lds + ((g + 1) % kStages) * kStageBytes + lane_off;
+      uint8_t* fbuf = lds + (g % kStages) * kStageBytes + uwave * 4096;
+      // step g + kStages: of this block, else of the next one, else (nothing follows) a clamped copy nobody reads
+      const int ka = kt + kStages;
+      const bool own = ka < K;
+      const TileSrc& src = own ? cur : nxt;
+      const int kk = own ? ka : (has_next ? ka - K : K - 1);
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const int pp = i >> 4, nb = (i >> 2) & 3, mb = i & 3;
+        mfma32_acc(acc[nb][mb], fc.w[nb][pp], fc.x[mb][pp]);
+        if ((i & 1) == 0) read_frag(fn, rb, i >> 1);
+        if ((i & 3) == 1) issue_one(src, kk, fbuf, i >> 2);
+      }
+    };
+    for (int kt = 0; kt < K; kt += 2) {
+      step(fa, fb, kt);
+      step(fb, fa, kt + 1);
+    }
+    g0 += K;
+    // the last MFMAs were issued from inline assembly: give them time to retire before their accumulators
+    // are read (16 passes of 4 cycles cover the longest one)
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    epilogue(acc, nt_base, mt_base);
+    if (!has_next) break;
+    // the epilogue's stores (and loads) share the counter with the copies: drain it so that the waits of the
+    // next block count copies only (they have been flying under the epilogue)
+    wait_vmcnt<0>();
+    nt_base = nt_next;
+    mt_base = mt_next;
+    cur = nxt;
+  }
+  wait_vmcnt<0>();  // the clamped copies past the last step still target this workgroup's LDS
 }
 
 template <int EPI>
@@ -177,13 +203,22 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave & 1, wm = wave >> 1;
   const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
-  const Block blk = block_of(blockIdx.x, nb_n, nb_m);
-  if (!blk.valid) return;  // whole workgroup
-  const int nt_base = blk.nb * kBlkTiles, mt_base = blk.mb * kBlkTiles;
-  v16f acc[4][4];
-  lds_gemm_block(acc, reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles,
-                 a.m_tiles, a.k_tiles, nt_base, mt_base, lds, lane, __builtin_amdgcn_readfirstlane(wave), wn, wm);
-
+  // persistent workgroup: launch indices blockIdx.x, + gridDim.x, ... (gridDim.x is a multiple of 8, so all
+  // of them map to the same XCD); indices that name no block are skipped
+  const int total = 8 * ((((nb_m + 7) / 8) + kBand - 1) / kBand) * kBand * nb_n;
+  int L = (int)blockIdx.x - (int)gridDim.x;
+  auto tile_at = [&](int, int& nt_base, int& mt_base) {
+    for (L += gridDim.x; L < total; L += gridDim.x) {
+      const Block blk = block_of(L, nb_n, nb_m);
+      if (blk.valid) {
+        nt_base = blk.nb * kBlkTiles;
+        mt_base = blk.mb * kBlkTiles;
+        return true;
+      }
+    }
+    return false;
+  };
+  auto epilogue = [&](v16f (&acc)[4][4], int nt_base, int mt_base) {
   // ---- epilogue: in a 32 x 32 block, lane holds token lane % 32 and features 8 q + 4 (lane / 32) + 0..3
   // (q = 0..3) in registers 4 q .. 4 q + 3
   const int col = lane & 31, rh = (lane >> 5) * 4;
@@ -222,6 +257,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
       }
     }
   }
+};
+  lds_gemm_stream(reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles, a.m_tiles,
+                  a.k_tiles, lds, lane, __builtin_amdgcn_readfirstlane(wave), wn, wm, tile_at, epilogue);
 }
 
 // Scoring LM head on the same engine: a workgroup owns 256 rows and one vocabulary slice (8 blocks of
@@ -237,25 +275,44 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
   const int mt_base = blk.mb * kBlkTiles;
   const int col = lane & 31, rh = (lane >> 5) * 4;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  Lse lse[4];
-  Top2 top[4];
-  float zt[4];
-  int target[4];
+  // The per-row running results live in LDS behind the ring (28 words per thread, word-interleaved over the
+  // threads) and are loaded only inside the epilogue, so that they take no registers from the matrix loop.
+  float* st_f = reinterpret_cast<float*>(lds + kStages * kStageBytes) + threadIdx.x;
+  int* st_i = reinterpret_cast<int*>(st_f);
+  constexpr int SM = 0, SS = 4, SV1 = 8, SI1 = 12, SV2 = 16, SZT = 20, STG = 24;  // word index + mb, x 256 threads
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb) {
-    lse[mb] = lse_empty();
-    top[mb] = top2_empty();
-    zt[mb] = -INFINITY;
     const int m = (mt_base + 8 * wm + 2 * mb) * 16 + col;
-    target[mb] = (m < a.M) ? a.targets[m] : -1;
+    st_f[(SM + mb) * 256] = -INFINITY;
+    st_f[(SS + mb) * 256] = 0.f;
+    st_f[(SV1 + mb) * 256] = -INFINITY;
+    st_i[(SI1 + mb) * 256] = 0x7fffffff;
+    st_f[(SV2 + mb) * 256] = -INFINITY;
+    st_f[(SZT + mb) * 256] = -INFINITY;
+    st_i[(STG + mb) * 256] = (m < a.M) ? a.targets[m] : -1;
   }
   const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles;
   const int vocab = a.n_tiles * 16;
-  for (int nbk = blk.nb * 8; nbk < min(blk.nb * 8 + 8, nb_n); ++nbk) {
-    v16f acc[4][4];
-    lds_gemm_block(acc, reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles,
-                   a.m_tiles, a.k_tiles, nbk * kBlkTiles, mt_base, lds, lane, uwave, wn, wm);
+  const int nbk0 = blk.nb * 8, nbk1 = min(blk.nb * 8 + 8, nb_n);
+  auto tile_at = [&](int i, int& nt_base, int& mt_b) {
+    nt_base = (nbk0 + i) * kBlkTiles;
+    mt_b = mt_base;
+    return nbk0 + i < nbk1;
+  };
+  auto epilogue = [&](v16f (&acc)[4][4], int nt_base, int) {
+    const int nbk = nt_base / kBlkTiles;
     const bool full = (nbk + 1) * kBlkTiles <= a.n_tiles;  // all 256 entries of the block exist (workgroup-uniform)
+    Lse lse[4];
+    Top2 top[4];
+    float zt[4];
+    int target[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      lse[mb] = Lse{st_f[(SM + mb) * 256], st_f[(SS + mb) * 256]};
+      top[mb] = Top2{st_f[(SV1 + mb) * 256], st_i[(SI1 + mb) * 256], st_f[(SV2 + mb) * 256]};
+      zt[mb] = st_f[(SZT + mb) * 256];
+      target[mb] = st_i[(STG + mb) * 256];
+    }
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
 #pragma unroll
@@ -296,6 +353,26 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
         }
       }
     }
+  #pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      st_f[(SM + mb) * 256] = lse[mb].m;
+      st_f[(SS + mb) * 256] = lse[mb].s;
+      st_f[(SV1 + mb) * 256] = top[mb].v1;
+      st_i[(SI1 + mb) * 256] = top[mb].i1;
+      st_f[(SV2 + mb) * 256] = top[mb].v2;
+      st_f[(SZT + mb) * 256] = zt[mb];
+    }
+  };
+  lds_gemm_stream(reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles, a.m_tiles,
+                  a.k_tiles, lds, lane, uwave, wn, wm, tile_at, epilogue);
+  Lse lse[4];
+  Top2 top[4];
+  float zt[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb) {
+    lse[mb] = Lse{st_f[(SM + mb) * 256], st_f[(SS + mb) * 256]};
+    top[mb] = Top2{st_f[(SV1 + mb) * 256], st_i[(SI1 + mb) * 256], st_f[(SV2 + mb) * 256]};
+    zt[mb] = st_f[(SZT + mb) * 256];
   }
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb) {
@@ -323,14 +400,16 @@ void launch_one(const LargeArgs& a, hipStream_t st) {
     configured = true;
   }
   const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
-  k_gemm_lds<EPI><<<grid_of(nb_n, nb_m), 256, lds_bytes, st>>>(a);
+  // persistent: one workgroup per CU (the kernel fills a CU), each walks launch indices i, i + grid, ...
+  const int grid = std::min(grid_of(nb_n, nb_m), kPersistentGrid);
+  k_gemm_lds<EPI><<<grid, 256, lds_bytes, st>>>(a);
 }
 
 }  // namespace
 
 void lmhead_score_lds(const ScoreHeadArgs& a, int slices, hipStream_t st) {
   static bool configured = false;
-  const int lds_bytes = kStages * kStageBytes;
+  const int lds_bytes = kStages * kStageBytes + 28 * 256 * 4;  // ring + per-thread running results
   if (!configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_lds), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lds_bytes);
