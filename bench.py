@@ -71,7 +71,7 @@ def cpu_baseline(weights, cfg, prompts, max_positions):
                          n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab,
                          rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, w=weights.f32, max_positions=max_positions)
     if cfg.n_layers * cfg.d_model > 10000:
-        n_p, n_s, n_new = 1, 2, 48
+        n_p, n_s, n_new = 1, 2, 128
     else:
         n_p, n_s, n_new = prompts.shape[0], 2, 32
     t0 = time.perf_counter()

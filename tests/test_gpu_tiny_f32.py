@@ -110,3 +110,16 @@ def test_bad_arguments(tiny):
         mtmc.mtmc_poll_errors(handle)
     assert e.value.code == mtmc.MTMC_EDATA
     mtmc.mtmc_poll_errors(handle)  # flag was cleared
+
+
+def test_copy_probe_copies_exactly():
+    """The calibration kernel of the byte counters: dst == src afterwards, bad sizes are rejected."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    mtmc.mtmc_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(Exception):
+        mtmc.mtmc_copy_probe(dst[:7].view(torch.uint8)[:20], src[:7].view(torch.uint8)[:20])
