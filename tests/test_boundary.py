@@ -72,3 +72,27 @@ def test_blob_roundtrip():
     a, b = w.f32("lm_head"), wb.f32("lm_head")
     assert np.abs(a - b).max() <= np.abs(a).max() * 2.0 ** -8
     assert ((wb.tensors["lm_head"].astype(np.uint32) << 16).view(np.float32) == b).all()
+
+
+def test_product_sources_never_touch_the_oracle():
+    """The oracle is test infrastructure: nothing in the package (Python or HIP) or in the C header
+    may import, include or name it, and the two sides share no source file."""
+    import os
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    offenders = []
+    for base in ("paper_2511_20100_amd", "include"):
+        for dirpath, _, files in os.walk(os.path.join(root, base)):
+            for f in files:
+                if not f.endswith((".py", ".h", ".hip", ".cpp", ".c")):
+                    continue
+                text = open(os.path.join(dirpath, f), errors="ignore").read()
+                if f == "inputs.py":  # the seeded input generators serve both sides and import neither
+                    assert not re.search(r"^\s*(import|from)\s+(mtmc_oracle|oracle|\.mtmc|paper_2511_20100_amd\.mtmc)", text, re.M)
+                    continue
+                if re.search(r"\boracle\b", text):
+                    offenders.append(os.path.join(dirpath, f))
+    assert offenders == []
+    oracle_text = "".join(open(os.path.join(root, "oracle", f)).read() for f in os.listdir(os.path.join(root, "oracle"))
+                          if f.endswith(".py"))
+    assert "paper_2511_20100_amd" not in oracle_text and "libmtmc" not in oracle_text

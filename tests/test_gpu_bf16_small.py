@@ -165,3 +165,59 @@ def test_long_context_over_several_attention_chunks(lib):
         assert rep["compared"] > 0.5 * rep["steps"]
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+def test_degenerate_sizes(lib):
+    """Nothing to score (prompt_len == seq_len), the shortest scorable sequence, a single new token, and
+    a call split over two processes' worth of prompts (seq_offset) that must reproduce the whole call."""
+    import torch
+    cfg = SMALL
+    w = inputs.make_weights(cfg, seed=1, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        seqs = torch.from_numpy(inputs.make_sequences(3, 20, cfg.vocab, seed=4)).cuda()
+        s = lib.mtmc_score(handle, seqs, 20)
+        assert s.shape == (3, 19) and torch.all(s == 0)
+        two = inputs.make_sequences(5, 2, cfg.vocab, seed=6)
+        sc = check_score(handle, w, two, 1, max_positions=128, label="two-token")
+        assert sc["logprobs"].shape == (5, 1)
+        prompts = inputs.make_prompts(4, 9, cfg.vocab, seed=3)
+        rep = check_rollout_by_replay(handle, w, prompts, 3, 1, 1.0, 2, max_positions=128, label="one-new-token")
+        assert rep["ids"].shape == (12, 1)
+        dp = torch.from_numpy(prompts).cuda()
+        whole = lib.mtmc_rollout(handle, dp, 3, 7, 1.0, 11)
+        first = lib.mtmc_rollout(handle, dp[:1].contiguous(), 3, 7, 1.0, 11)
+        rest = lib.mtmc_rollout(handle, dp[1:].contiguous(), 3, 7, 1.0, 11, seq_offset=3)
+        assert torch.equal(whole[0], torch.cat([first[0], rest[0]]))
+        assert (whole[1] - torch.cat([first[1], rest[1]])).abs().max() <= 1e-3   # batch size changes the tiling
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_bad_inputs_are_reported(lib):
+    """A token id outside the vocabulary raises the sticky data flag; a weight beyond the fp16 range is refused."""
+    import torch
+    cfg = SMALL
+    w = inputs.make_weights(cfg, seed=1, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        prompts = torch.from_numpy(inputs.make_prompts(2, 8, cfg.vocab, seed=5)).cuda()
+        bad = prompts.clone(); bad[1, 3] = cfg.vocab
+        lib.mtmc_rollout(handle, bad, 2, 3, 1.0, 1)
+        with pytest.raises(lib.MtmcError) as e:
+            lib.mtmc_poll_errors(handle)
+        assert e.value.code == lib.MTMC_EDATA
+        lib.mtmc_poll_errors(handle)
+        seqs = torch.cat([prompts, prompts], 1).contiguous(); seqs[0, 10] = -1
+        lib.mtmc_score(handle, seqs, 4)
+        with pytest.raises(lib.MtmcError):
+            lib.mtmc_poll_errors(handle)
+    finally:
+        lib.mtmc_weights_destroy(handle)
+    blob = w.blob().copy()
+    lay, _ = inputs.blob_layout(cfg)
+    off = lay["layers.1.wq"][0]
+    blob.view(np.uint16)[off // 2 + 5] = 0x7F00   # bf16 1.7e38: not an fp16 value
+    with pytest.raises(lib.MtmcError) as e:
+        lib.mtmc_weights_create(lib.make_config(cfg, 128), blob)
+    assert e.value.code == lib.MTMC_EINVAL
