@@ -1,4 +1,16 @@
-// The MFMA inner step shared by the attention kernels: two KV pages against blocks of 16 query columns.
+// The MFMA inner step of the decode attention kernel: two KV pages against blocks of 16 query columns
+// of grouped-query attention over the paged fp16 KV cache (head_dim 128).
+//
+// Page layouts (16 tokens x 128 dims = 4 KiB per (layer, K or V, kv head, page)):
+//   K page: [dim / 8][token][dim % 8]   -> the four 16x32 "A" operands of S^T = K Q^T are the
+//                                          four consecutive 1 KiB quarters of the page;
+//   V page: [dim][token]                -> a lane's "A" operand of O^T = V^T P^T is 4 consecutive
+//                                          tokens of one dim from each of two pages (2 x 8 bytes).
+// Scores are produced transposed (S^T[token][query]), so a lane owns one query column: the
+// softmax reductions run over its 8 registers plus two cross-lane steps, and exp(S^T) is
+// already in the "B" operand layout of the second product -- no transpose through LDS.
+// The k index of that product maps (lane / 16, e) to token 4 (lane / 16) + e % 4 of page e / 4,
+// the same permutation on both operands.
 #pragma once
 
 #include "common.h"

@@ -13,7 +13,7 @@
 // O^T[dim][column] += V^T P^T (4 blocks of 32 dims x 2 MFMAs over 16 tokens).  exp(S^T) is already in
 // the B-operand layout of the second product: slot e of lane (column, half h) in token group jj holds
 // token 16 jj + 8 (e / 4) + 4 h + e % 4, and the V^T operand is gathered with the same map (two
-// 8-byte pieces of a V page row).  Page layouts: see attention_bf16.hip.
+// 8-byte pieces of a V page row).  Page layouts: see attention_core.h.
 #include "bf16_kernels.h"
 #include "device_utils.h"
 #include "frag.h"

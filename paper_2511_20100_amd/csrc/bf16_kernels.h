@@ -17,17 +17,6 @@ struct SampleCtl {
   float* out_logprobs;
 };
 
-struct SkinnyArgs {
-  const h16_t* Wt;   // tiled weights [n_tiles][k_tiles][512]
-  const h16_t* Xt;   // tiled activations [k_tiles][m_tiles][512]
-  int n_tiles, k_tiles, m_tiles, M;
-  float* out_f32;     // partial sums [split][m_tiles*16][ld_out], or sampler partials
-  int ld_out;
-  h16_t* out_bf16;   // tiled activation output (SwiGLU)
-  const SampleCtl* ctl;
-  const int* d_step;
-};
-
 struct LargeArgs {
   const h16_t* Wt;
   const h16_t* Xt;
@@ -99,16 +88,6 @@ void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int
                     int k_tiles, int* err_flag, hipStream_t st);
 
 // ---- GEMMs ---------------------------------------------------------------------------------
-int skinny_nb(int m_tiles);
-void gemm_skinny_partial(float* P, int ldp, const h16_t* Wt, int n_tiles, int k_tiles,
-                         const h16_t* Xt, int M, int m_tiles, int ksplit, hipStream_t st);
-void gemm_skinny_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                        int M, int m_tiles, hipStream_t st);
-int sample_groups(int n_tiles, int m_tiles);
-void gemm_skinny_sample(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                        int M, int m_tiles, const SampleCtl* ctl, const int* d_step, hipStream_t st);
-void sample_reduce(const float* part, int n_groups, int M, const SampleCtl* ctl, const int* d_step,
-                   int* cur_ids, hipStream_t st);
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
                     int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st);
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
@@ -144,13 +123,8 @@ void rope_kv_write(h16_t* q, const float* P, int n_split, int ldp, int Mpad_p, i
                    const float* cos, const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st);
 
 // ---- attention -----------------------------------------------------------------------------
-// Decode: one query position per sequence (position pos_base + *d_step), context split into
-// chunks of `chunk_pages` pages; partial results in `part`, merged by attention_decode_merge.
+// Floats of the per-chunk partial results of the decode attention kernel.
 size_t attn_part_floats(int B, int Hkv, int G, int n_chunks);
-void attention_decode(float* part, const h16_t* q, int B, int Hq, int Hkv, TokMap map, KvPool pool,
-                      int layer, int chunk_pages, int n_chunks, hipStream_t st);
-void attention_decode_merge(h16_t* o, const float* part, int B, int m_tiles, int Hq, int Hkv,
-                            TokMap map, int chunk_pages, int n_chunks, hipStream_t st);
 // Prefill / scoring: causal attention of every token of T = n_seqs * S over its own sequence.
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
                        TokMap map, KvPool pool, int layer, hipStream_t st);

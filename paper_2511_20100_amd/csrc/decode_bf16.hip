@@ -775,6 +775,10 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   }
 }
 
+size_t attn_part_floats(int B, int Hkv, int G, int n_chunks) {
+  return (size_t)B * Hkv * n_chunks * G * (DHD + 2);
+}
+
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {
   k_attn_dec<<<dim3(B, a.Hkv, a.n_chunks), AW * 64, 0, st>>>(a);
 }

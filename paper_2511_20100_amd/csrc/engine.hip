@@ -12,7 +12,7 @@ namespace mtmc {
 // 256 x 256 output blocks, and splits longer jobs into equal chunks.
 static constexpr int kChunkTokens = 8192;
 static constexpr int kScoreChunkTokensBf16 = 131072;
-static constexpr int kMaxBf16Batch = 128;  // rows the skinny decode GEMMs take
+static constexpr int kMaxBf16Batch = 128;  // rows the decode GEMMs take
 static constexpr size_t kLogitBytes = (size_t)256 << 20;
 
 int build_aux(mtmc_weights* w, hipStream_t st) {

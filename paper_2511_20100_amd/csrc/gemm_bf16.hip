@@ -62,235 +62,6 @@ __device__ __forceinline__ void wave_gemm(const h16_t* __restrict__ Wt, int k_ti
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + expf(-g)); }
 
 // ======================================================================================
-// Skinny GEMM (M <= 128 tokens): one workgroup = NB weight row tiles x one K split; its four
-// wavefronts take a quarter of the K range each and are summed through LDS in a fixed tree.
-// ======================================================================================
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_SAMPLE = 2 };
-constexpr int kSkinnyPF = 2;  // k-steps of operands each wavefront keeps in flight
-
-struct SamplePartial {  // one per (row, weight-tile group)
-  float m, s;           // log-sum-exp state of z / T over the group's vocabulary slice
-  float y;              // best perturbed logit, its vocabulary index, and its z / T
-  int idx;
-  float zt;
-  float pad[3];
-};
-
-template <int NB, int MB, int EPI>
-__global__ __launch_bounds__(256, (MB > 4 ? 2 : 3)) void k_gemm_skinny(SkinnyArgs a) {
-  __shared__ float red[2][NB * MB * 4][64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nt0 = blockIdx.x * NB;
-  const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
-  const int ks_lo = blockIdx.y * per_split, ks_hi = min(a.k_tiles, ks_lo + per_split);
-  const int span = max(ks_hi - ks_lo, 0);
-  const int per_wave = (span + 3) / 4;
-  const int k0 = ks_lo + wave * per_wave, k1 = min(ks_hi, k0 + per_wave);
-  v4f acc[NB][MB];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
-  wave_gemm<NB, MB, kSkinnyPF>(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, 0, k0, k1, lane, acc);
-  // fixed-order tree over the four K quarters: (w0 + w2) + (w1 + w3)
-  if (wave >= 2) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave - 2][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
-  }
-  __syncthreads();
-  if (wave < 2) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[wave][(nb * MB + mb) * 4 + r][lane];
-  }
-  if (wave == 1) {  // red[1] was read by this wavefront only
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[1][(nb * MB + mb) * 4 + r][lane] = acc[nb][mb][r];
-  }
-  __syncthreads();
-  if (wave > 0) return;
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[nb][mb][r] += red[1][(nb * MB + mb) * 4 + r][lane];
-
-  const int col = lane & 15, rq = (lane >> 4) * 4;
-  const int Mpad = a.m_tiles * 16;
-  if (EPI == EPI_PARTIAL) {
-    float* P = a.out_f32 + (size_t)blockIdx.y * Mpad * a.ld_out;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      if (nt0 + nb >= a.n_tiles) continue;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        if (mb >= a.m_tiles) continue;
-        const int m = mb * 16 + col;
-        *reinterpret_cast<v4f*>(P + (size_t)m * a.ld_out + (nt0 + nb) * 16 + rq) = acc[nb][mb];
-      }
-    }
-  } else if (EPI == EPI_SWIGLU) {
-    // weight row tiles alternate gate / up: tile 2j holds gate rows 16j.., tile 2j+1 the up rows
-#pragma unroll
-    for (int nb = 0; nb < NB; nb += 2) {
-      if (nt0 + nb >= a.n_tiles) continue;
-      const int f = ((nt0 + nb) >> 1) * 16 + rq;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        if (mb >= a.m_tiles) continue;
-        const int m = mb * 16 + col;
-        const v4f g = acc[nb][mb], u = acc[nb + 1][mb];
-        uint2 pk;
-        pk.x = pack_h16x2(silu_f(g[0]) * u[0], silu_f(g[1]) * u[1]);
-        pk.y = pack_h16x2(silu_f(g[2]) * u[2], silu_f(g[3]) * u[3]);
-        *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
-      }
-    }
-  } else {  // EPI_SAMPLE: fused log-sum-exp + Gumbel-max over this group's vocabulary slice
-    const SampleCtl ctl = *a.ctl;
-    const int step = *a.d_step;
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      const int m = mb * 16 + col;
-      Lse lse = lse_empty();
-      float by = -INFINITY, bz = 0.f;
-      int bi = 0x7fffffff;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        if (nt0 + nb >= a.n_tiles) continue;
-        const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
-        uint4 rb = make_uint4(0, 0, 0, 0);
-        if (!ctl.greedy)
-          rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u),
-                             ctl.key0, ctl.key1);
-        const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float zt = ctl.greedy ? acc[nb][mb][r] : acc[nb][mb][r] * ctl.inv_temp;
-          lse_push(lse, zt);
-          const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
-          if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: first maximum wins
-        }
-      }
-#pragma unroll
-      for (int o = 16; o <= 32; o <<= 1) {
-        const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
-        const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
-        const int oi = __shfl_xor(bi, o, 64);
-        lse = lse_merge(lse, ol);
-        if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
-      }
-      if (lane < 16 && m < a.M) {
-        SamplePartial* p = reinterpret_cast<SamplePartial*>(a.out_f32) + (size_t)blockIdx.x * a.M + m;
-        p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
-      }
-    }
-  }
-}
-
-template <int NB, int MB>
-static void launch_skinny_t(const SkinnyArgs& a, int epi, int ksplit, hipStream_t st) {
-  const dim3 grid((a.n_tiles + NB - 1) / NB, ksplit);
-  if (epi == EPI_PARTIAL) k_gemm_skinny<NB, MB, EPI_PARTIAL><<<grid, 256, 0, st>>>(a);
-  else if (epi == EPI_SWIGLU) k_gemm_skinny<NB, MB, EPI_SWIGLU><<<grid, 256, 0, st>>>(a);
-  else k_gemm_skinny<NB, MB, EPI_SAMPLE><<<grid, 256, 0, st>>>(a);
-}
-
-int skinny_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
-
-static void launch_skinny(const SkinnyArgs& a, int epi, int ksplit, hipStream_t st) {
-  switch (a.m_tiles) {
-    case 1: launch_skinny_t<4, 1>(a, epi, ksplit, st); break;
-    case 2: launch_skinny_t<4, 2>(a, epi, ksplit, st); break;
-    case 3: case 4: launch_skinny_t<4, 4>(a, epi, ksplit, st); break;
-    default: launch_skinny_t<2, 8>(a, epi, ksplit, st); break;
-  }
-}
-
-void gemm_skinny_partial(float* P, int ldp, const h16_t* Wt, int n_tiles, int k_tiles,
-                         const h16_t* Xt, int M, int m_tiles, int ksplit, hipStream_t st) {
-  SkinnyArgs a{};
-  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
-  a.out_f32 = P; a.ld_out = ldp;
-  launch_skinny(a, EPI_PARTIAL, ksplit, st);
-}
-void gemm_skinny_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                        int M, int m_tiles, hipStream_t st) {
-  SkinnyArgs a{};
-  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
-  a.out_bf16 = act;
-  launch_skinny(a, EPI_SWIGLU, 1, st);
-}
-int sample_groups(int n_tiles, int m_tiles) {
-  const int nb = skinny_nb(m_tiles);
-  return (n_tiles + nb - 1) / nb;
-}
-void gemm_skinny_sample(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                        int M, int m_tiles, const SampleCtl* ctl, const int* d_step, hipStream_t st) {
-  SkinnyArgs a{};
-  a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
-  a.out_f32 = part; a.ctl = ctl; a.d_step = d_step;
-  launch_skinny(a, EPI_SAMPLE, 1, st);
-}
-
-// Merges the per-group partials of one row: token, its log-probability; feeds the next step.
-__global__ __launch_bounds__(256) void k_sample_reduce(const SamplePartial* part, int n_groups, int M,
-                                                       const SampleCtl* ctlp, const int* d_step,
-                                                       int* cur_ids) {
-  __shared__ Lse s_lse[4];
-  __shared__ float s_y[4], s_z[4];
-  __shared__ int s_i[4];
-  const int b = blockIdx.x;
-  Lse lse = lse_empty();
-  float by = -INFINITY, bz = 0.f;
-  int bi = 0x7fffffff;
-  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
-    const SamplePartial p = part[(size_t)g * M + b];
-    lse = lse_merge(lse, Lse{p.m, p.s});
-    if (p.y > by || (p.y == by && p.idx < bi)) { by = p.y; bi = p.idx; bz = p.zt; }
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
-    const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
-    const int oi = __shfl_xor(bi, o, 64);
-    lse = lse_merge(lse, ol);
-    if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
-  }
-  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-  if (lane == 0) { s_lse[wid] = lse; s_y[wid] = by; s_z[wid] = bz; s_i[wid] = bi; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    for (int w = 1; w < 4; ++w) {
-      lse = lse_merge(lse, s_lse[w]);
-      if (s_y[w] > by || (s_y[w] == by && s_i[w] < bi)) { by = s_y[w]; bi = s_i[w]; bz = s_z[w]; }
-    }
-    const SampleCtl ctl = *ctlp;
-    const int step = *d_step;
-    cur_ids[b] = bi;
-    ctl.out_ids[(size_t)b * ctl.max_new + step] = bi;
-    ctl.out_logprobs[(size_t)b * ctl.max_new + step] = bz - (lse.m + logf(lse.s));
-  }
-}
-void sample_reduce(const float* part, int n_groups, int M, const SampleCtl* ctl, const int* d_step,
-                   int* cur_ids, hipStream_t st) {
-  k_sample_reduce<<<M, 256, 0, st>>>(reinterpret_cast<const SamplePartial*>(part), n_groups, M, ctl,
-                                     d_step, cur_ids);
-}
-
-// ======================================================================================
 // Large GEMM (prefill / scoring): workgroup tile 128 features x 128 tokens, four wavefronts
 // in a 2 x 2 arrangement of 64 x 64 sub-tiles, full K per workgroup.
 // ======================================================================================
