@@ -13,6 +13,8 @@ product of the per-token conditionals (Eq. 2).  Two operations follow from that:
 
 * ``score``   -- teacher-forced per-token log-probabilities log P(w^i | s, w^<i): the
                  logarithms of the factors of Eq. 2.
+* ``action_policy`` -- the sums of those terms over each candidate action of a state and
+                 their softmax over the candidate set (the sampling probability of an action).
 * ``rollout`` -- sampling a token sequence from the same conditionals, one token at a
                  time (Inference Pipeline, "Macro Thinking": the policy outputs an action),
                  by the Gumbel-max rule with noise from a counter-based generator.
@@ -31,7 +33,9 @@ Pins (tests/test_oracle_*.py): Philox known-answer vectors; Gumbel-max law (chi-
 brute-force scalar-loop attention and forward pass on tiny shapes; closed forms (2-D
 rotation, uniform attention = running mean, zero-residual model); invariants (rotary
 norm / relative position, RMS, log-softmax rows, chain rule over all continuations,
-causality, cache == recompute, batch-independence of the sampler).
+causality, cache == recompute, batch-independence of the sampler); for the action policy,
+the full candidate set (all V^n actions: the softmax changes nothing), single-token actions
+(policy = softmax of the logits), padding independence and the composition of two actions.
 The full forward pass at real model sizes has no external truth to compare with (no
 trained weights or reference logits exist here): "parity unpinned" beyond those pins.
 """
@@ -285,6 +289,40 @@ def score(model: Model, seqs: np.ndarray, prompt_len: int = 1):
 def action_logprob(token_logp: np.ndarray) -> float:
     """log P_token(a | s): the sum of an action's per-token terms (Eq. 2 in log form)."""
     return float(np.sum(token_logp, dtype=np.float64))
+
+
+def action_policy(model: Model, states: np.ndarray, actions: np.ndarray, action_len: np.ndarray,
+                  normalize: bool = False):
+    """The policy over a state's candidate actions (Method, "Training Methodology": Eq. 2, then
+    the normalisation of the candidates' scores by a softmax).
+
+    states int [Ns, P]; actions int [Ns, K, A] (entries at and beyond an action's length are
+    padding and never looked at); action_len int [Ns, K] with values in [0, A].
+    For state n and candidate k, with a = actions[n, k, :action_len[n, k]]:
+      token_logp[n, k, i] = log P(a_i | state_n, a_<i)          (0 at padding)
+      action_logp[n, k]   = sum_i token_logp[n, k, i]           (Eq. 2 in log form),
+                            divided by the action's length when ``normalize`` (a reading: the
+                            paper does not say whether lengths are normalised; off by default)
+      policy_logp[n, k]   = action_logp[n, k] - logsumexp_j action_logp[n, j].
+    Every candidate is evaluated by itself from the start of its state: nothing is shared.
+    Returns (token_logp float32 [Ns, K, A], action_logp float32 [Ns, K], policy_logp float32 [Ns, K])."""
+    Ns, P = states.shape
+    _, K, A = actions.shape
+    token_logp = np.zeros((Ns, K, A), dtype=np.float32)
+    action_logp = np.zeros((Ns, K), dtype=np.float64)
+    for n in range(Ns):
+        for k in range(K):
+            ln = int(action_len[n, k])
+            if ln == 0:
+                continue
+            a = actions[n, k, :ln]
+            z = model.logits(np.concatenate([states[n], a]))[P - 1:P - 1 + ln]
+            token_logp[n, k, :ln] = log_softmax_at(z, a).astype(np.float32)
+            total = float(np.sum(token_logp[n, k, :ln], dtype=np.float64))
+            action_logp[n, k] = total / ln if normalize else total
+    m = action_logp.max(axis=1, keepdims=True)
+    lse = m + np.log(np.exp(action_logp - m).sum(axis=1, keepdims=True))
+    return token_logp, action_logp.astype(np.float32), (action_logp - lse).astype(np.float32)
 
 
 # --------------------------------------------------------------------------------------

@@ -187,6 +187,87 @@ def test_causality_bitwise(small_model):
     assert not np.array_equal(a[0, 6:], b[0, 6:])
 
 
+# ---------------------------------------------------------------- policy over candidate actions
+def test_policy_over_the_full_candidate_set_is_eq2_itself(small_model):
+    """If the candidates of a state are ALL V^n actions of length n, their Eq. 2 probabilities
+    already sum to one, so the softmax over the set must leave them unchanged."""
+    V, n = 6, 2
+    states = np.array([[1, 4, 4], [0, 5, 2]])
+    cand = np.array(list(itertools.product(range(V), repeat=n)))
+    actions = np.broadcast_to(cand, (2,) + cand.shape).copy()
+    lens = np.full((2, len(cand)), n)
+    tok, act, pol = oracle.action_policy(small_model, states, actions, lens)
+    assert np.allclose(np.exp(act.astype(np.float64)).sum(axis=1), 1.0, atol=1e-5)
+    assert np.allclose(pol, act, atol=1e-5)
+    assert np.allclose(tok.sum(axis=2), act, atol=1e-6)
+
+
+def test_single_token_actions_give_the_softmax_of_the_logits(small_model):
+    state = np.array([[3, 0, 2, 5]])
+    actions = np.arange(6).reshape(1, 6, 1)
+    tok, act, pol = oracle.action_policy(small_model, state, actions, np.ones((1, 6), dtype=int))
+    z = small_model.logits(state[0])[-1]
+    ref = z - math.log(sum(math.exp(x) for x in z))
+    assert np.allclose(pol[0], ref, atol=1e-6) and np.allclose(act[0], ref, atol=1e-6)
+    # a subset of the vocabulary: the policy is the softmax of the logits restricted to the subset
+    sub = [4, 1, 2]
+    _, _, pol = oracle.action_policy(small_model, state, np.array(sub).reshape(1, 3, 1), np.ones((1, 3), dtype=int))
+    zs = np.array([z[v] for v in sub])
+    assert np.allclose(pol[0], zs - math.log(np.exp(zs).sum()), atol=1e-6)
+
+
+def test_policy_rows_are_distributions_and_ignore_padding(small_model):
+    rng = np.random.default_rng(11)
+    states = inputs.make_sequences(3, 5, 6, seed=12)
+    actions = rng.integers(0, 6, (3, 4, 5))
+    lens = np.array([[5, 1, 3, 2], [2, 2, 5, 4], [1, 5, 5, 0]])
+    tok, act, pol = oracle.action_policy(small_model, states, actions, lens)
+    assert np.allclose(np.exp(pol.astype(np.float64)).sum(axis=1), 1.0, atol=1e-6)
+    for n in range(3):
+        for k in range(4):
+            assert np.all(tok[n, k, lens[n, k]:] == 0.0) and np.all(tok[n, k, :lens[n, k]] < 0.0)
+    assert act[2, 3] == 0.0  # the empty action: an empty product
+    other = actions.copy()
+    for n in range(3):
+        for k in range(4):
+            other[n, k, lens[n, k]:] = (other[n, k, lens[n, k]:] + 1) % 6
+    tok2, act2, pol2 = oracle.action_policy(small_model, states, other, lens)
+    assert np.array_equal(tok, tok2) and np.array_equal(act, act2) and np.array_equal(pol, pol2)
+    # one candidate only: probability one
+    _, _, one = oracle.action_policy(small_model, states, actions[:, :1], lens[:, :1])
+    assert np.all(one == 0.0)
+
+
+def test_action_scores_compose_and_match_the_scoring_pass(small_model):
+    """log P(a b | s) = log P(a | s) + log P(b | s a), and each term is what score() gives for the
+    concatenated sequence."""
+    s = np.array([[2, 2, 5]])
+    a, b = [1, 0, 3], [4, 4]
+    _, ab, _ = oracle.action_policy(small_model, s, np.array([[a + b]]), np.array([[5]]))
+    _, pa, _ = oracle.action_policy(small_model, s, np.array([[a]]), np.array([[3]]))
+    _, pb, _ = oracle.action_policy(small_model, np.array([s[0].tolist() + a]), np.array([[b]]), np.array([[2]]))
+    assert abs(ab[0, 0] - (pa[0, 0] + pb[0, 0])) < 1e-5
+    lp, _, _ = oracle.score(small_model, np.array([s[0].tolist() + a + b]), prompt_len=3)
+    tok, _, _ = oracle.action_policy(small_model, s, np.array([[a + b]]), np.array([[5]]))
+    assert np.array_equal(tok[0, 0], lp[0, 2:])
+
+
+def test_length_normalisation_divides_before_the_softmax(small_model):
+    rng = np.random.default_rng(13)
+    states = inputs.make_sequences(2, 4, 6, seed=14)
+    actions = rng.integers(0, 6, (2, 3, 4))
+    lens = np.array([[4, 2, 1], [3, 3, 3]])
+    _, act, _ = oracle.action_policy(small_model, states, actions, lens)
+    _, actn, poln = oracle.action_policy(small_model, states, actions, lens, normalize=True)
+    assert np.allclose(actn, act / lens, atol=1e-6)
+    ref = actn.astype(np.float64)
+    ref = ref - np.log(np.exp(ref).sum(axis=1, keepdims=True))
+    assert np.allclose(poln, ref, atol=1e-6)
+    # equal lengths: normalising rescales the scores by 1 / N, which changes the policy unless N = 1
+    _, _, pol = oracle.action_policy(small_model, states, actions, lens)
+    assert not np.allclose(pol[1], poln[1], atol=1e-4)
+
+
 # ---------------------------------------------------------------- cache, rollout
 @pytest.mark.parametrize("dtype,tol", [(np.float64, 1e-10), (np.float32, 1e-5)])
 def test_cached_decode_equals_full_recompute(dtype, tol):
