@@ -123,8 +123,39 @@ int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_seqs, int32
                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * mtmc_score_actions: the policy over each state's candidate actions (Method, "Training
+ * Methodology": the action probability of Eq. 2, then the softmax over the candidates).
+ * State n has K = n_actions candidates; candidate k is the first action_len[n, k] tokens a_1..a_N
+ * of actions[n, k, :] (the rest of the row is padding and never influences a result).
+ *     out_token_logprobs[n, k, i] = log P(a_{i+1} | state_n, a_1..a_i)    for i < N, else 0
+ *     out_action_logprobs[n, k]   = sum_i out_token_logprobs[n, k, i]     (Eq. 2 in log form);
+ *                                   divided by N when normalize != 0 and N > 0 (the paper does not
+ *                                   say whether lengths are normalised: off unless asked for)
+ *     out_policy_logprobs[n, k]   = out_action_logprobs[n, k] - logsumexp_j out_action_logprobs[n, j]
+ * An empty action (N = 0) has log-probability 0.  The state is evaluated once per state, not once
+ * per candidate: the K candidates of a state read the same cached keys and values of its tokens.
+ *
+ * states       device int32 [n_states, state_len], state_len >= 1
+ * actions      device int32 [n_states, n_actions, max_action_len]; padding entries are ignored
+ * action_len   device int32 [n_states, n_actions], values in [0, max_action_len]; a value outside
+ *              is clamped and reported by mtmc_poll_errors
+ * out_token_logprobs   device fp32 [n_states, n_actions, max_action_len]
+ * out_action_logprobs, out_policy_logprobs   device fp32 [n_states, n_actions]
+ * workspace    device, >= mtmc_score_actions_workspace_bytes(...) bytes, 256-byte aligned
+ * state_len + max_action_len must not exceed max_positions.
+ */
+size_t mtmc_score_actions_workspace_bytes(const mtmc_weights* w, int32_t n_states, int32_t state_len,
+                                          int32_t n_actions, int32_t max_action_len);
+int mtmc_score_actions(const mtmc_weights* w, const int32_t* states, int32_t n_states, int32_t state_len,
+                       const int32_t* actions, const int32_t* action_len, int32_t n_actions,
+                       int32_t max_action_len, int32_t normalize, float* out_token_logprobs,
+                       float* out_action_logprobs, float* out_policy_logprobs, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
  * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll saw a token
- * id outside [0, vocab) (the flag is cleared), MTMC_EHIP on a runtime error, else MTMC_OK.
+ * id outside [0, vocab) or an action length outside its range (the flag is cleared), MTMC_EHIP
+ * on a runtime error, else MTMC_OK.
  */
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);
 

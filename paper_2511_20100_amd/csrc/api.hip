@@ -157,7 +157,9 @@ extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
   MTMC_HIP_CHECK(hipMemcpy(&flag, w->err_flag, sizeof(int), hipMemcpyDeviceToHost));
   if (flag) {
     MTMC_HIP_CHECK(hipMemset(w->err_flag, 0, sizeof(int)));
-    set_error("a token id outside [0, vocab) was seen (and clamped) on the device");
+    set_error(std::string(flag & 1 ? "a token id outside [0, vocab) was seen (and clamped) on the device" : "") +
+              ((flag & 1) && (flag & 4) ? "; " : "") +
+              (flag & 4 ? "an action length outside [0, max_action_len] was seen (and clamped) on the device" : ""));
     return MTMC_EDATA;
   }
   return MTMC_OK;
@@ -252,6 +254,60 @@ extern "C" int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_
   a.out_margin = out_margin;
   hipStream_t st = (hipStream_t)stream;
   int rc = w->cfg.dtype == MTMC_F32 ? f32_score(w, p, a, st) : bf16_score(w, p, a, st);
+  if (rc != MTMC_OK) return rc;
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}
+
+// --------------------------------------------------------------------------------------
+// action-level scoring
+// --------------------------------------------------------------------------------------
+static int check_actions_shape(const mtmc_weights* w, int32_t n_states, int32_t state_len, int32_t n_actions,
+                               int32_t max_action_len) {
+  MTMC_REQUIRE(w != nullptr, "weights is NULL");
+  MTMC_REQUIRE(n_states > 0 && state_len > 0 && n_actions > 0 && max_action_len > 0,
+               "n_states, state_len, n_actions and max_action_len must be positive");
+  MTMC_REQUIRE((int64_t)state_len + max_action_len <= w->cfg.max_positions,
+               "state_len + max_action_len exceeds max_positions");
+  MTMC_REQUIRE((int64_t)n_states * n_actions <= (1 << 20), "too many candidate actions");
+  MTMC_REQUIRE((int64_t)n_states * n_actions * ((int64_t)max_action_len + 1) < (1ll << 31) &&
+                   (int64_t)n_states * state_len < (1ll << 31),
+               "too many tokens");
+  return MTMC_OK;
+}
+
+extern "C" size_t mtmc_score_actions_workspace_bytes(const mtmc_weights* w, int32_t n_states, int32_t state_len,
+                                                     int32_t n_actions, int32_t max_action_len) {
+  if (check_actions_shape(w, n_states, state_len, n_actions, max_action_len) != MTMC_OK) return 0;
+  return plan_actions(w, n_states, state_len, n_actions, max_action_len, nullptr).total_bytes;
+}
+
+extern "C" int mtmc_score_actions(const mtmc_weights* w, const int32_t* states, int32_t n_states,
+                                  int32_t state_len, const int32_t* actions, const int32_t* action_len,
+                                  int32_t n_actions, int32_t max_action_len, int32_t normalize,
+                                  float* out_token_logprobs, float* out_action_logprobs,
+                                  float* out_policy_logprobs, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (int rc = check_actions_shape(w, n_states, state_len, n_actions, max_action_len)) return rc;
+  MTMC_REQUIRE(states && actions && action_len && out_token_logprobs && out_action_logprobs &&
+                   out_policy_logprobs && workspace,
+               "NULL pointer argument");
+  MTMC_REQUIRE(((uintptr_t)workspace & 255) == 0, "workspace must be 256-byte aligned");
+  ActionPlan p = plan_actions(w, n_states, state_len, n_actions, max_action_len, (char*)workspace);
+  if (workspace_bytes < p.total_bytes) {
+    set_error("workspace too small for mtmc_score_actions: need " + std::to_string(p.total_bytes) + " bytes");
+    return MTMC_ENOMEM;
+  }
+  ActionArgs a;
+  a.states = states;
+  a.actions = actions;
+  a.action_len = action_len;
+  a.normalize = normalize != 0;
+  a.out_token = out_token_logprobs;
+  a.out_action = out_action_logprobs;
+  a.out_policy = out_policy_logprobs;
+  hipStream_t st = (hipStream_t)stream;
+  int rc = w->cfg.dtype == MTMC_F32 ? f32_score_actions(w, p, a, st) : bf16_score_actions(w, p, a, st);
   if (rc != MTMC_OK) return rc;
   MTMC_HIP_CHECK(hipGetLastError());
   return MTMC_OK;

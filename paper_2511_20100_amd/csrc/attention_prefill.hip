@@ -46,7 +46,7 @@ constexpr int NCB = 2;    // column blocks per wavefront
 constexpr int QB = 256;   // query positions per workgroup
 
 __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
-                                                           int row_stride, KvPool pool, int layer) {
+                                                           int row_stride, int pos_base, KvPool pool, int layer) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int qblk = gridDim.x - 1 - blockIdx.x;  // longest columns first
   const int q0 = qblk * QB, qhead = blockIdx.y, seq = blockIdx.z;
@@ -55,8 +55,9 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   const int col = lane & 31, hh = lane >> 5;
   const int* table = pool.page_table + (size_t)seq * row_stride * pool.max_pages;
-  const int seq_pages = (S + kPageTokens - 1) / kPageTokens;
-  const int n_steps = (min(q0 + QB, S) + 31) / 32;  // key blocks 0 .. n_steps - 1 (causal)
+  // query j of the sequence sits at position pos_base + j and sees the keys at positions 0 .. pos_base + j
+  const int seq_pages = (pos_base + S + kPageTokens - 1) / kPageTokens;
+  const int n_steps = (pos_base + min(q0 + QB, S) + 31) / 32;  // key blocks 0 .. n_steps - 1 (causal)
 
   // ---- page ids of the steps, staged in LDS behind the ring (a global load inside the loop would be a
   // vector load, and waiting for it would drain the ring of copies in flight)
@@ -84,12 +85,13 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
   // ---- this wavefront's column blocks (positions q0 + 32 b + col, b = wave and 7 - wave).
   // Q fragments (B operand: column col, dims 16 j + 8 hh + 0..7).
   v8bf qf[NCB][8];
-  int qpos[NCB];
+  int qpos[NCB], qabs[NCB];  // index in the sequence / position among the keys (-1: padding column)
 #pragma unroll
   for (int i = 0; i < NCB; ++i) {
     const int b = (i == 0) ? uwave : 7 - uwave;
     const int pos = q0 + 32 * b + col;
     qpos[i] = (pos < S) ? pos : -1;
+    qabs[i] = (pos < S) ? pos_base + pos : -1;
     const h16_t* qrow = q + ((size_t)seq * S + max(qpos[i], 0)) * Hq * PHD + (size_t)qhead * PHD + 8 * hh;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
     }
     // ---- online softmax down each column; P^T fragments for the two token groups
     v8bf pf[NCB][2];
-    const bool diag = 32 * t + 31 > q0;  // some column of the workgroup may not see all 32 tokens
+    const bool diag = 32 * t + 31 > pos_base + q0;  // some column of the workgroup may not see all 32 tokens
 #pragma unroll
     for (int i = 0; i < NCB; ++i) {
       float sv[16];
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int tok = 32 * t + 8 * (e >> 2) + 4 * hh + (e & 3);
-          if (tok > qpos[i]) sv[e] = -INFINITY;
+          if (tok > qabs[i]) sv[e] = -INFINITY;
         }
       }
       float bm = sv[0];
@@ -228,7 +230,7 @@ void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles,
                        TokMap map, KvPool pool, int layer, hipStream_t st) {
   static bool configured = false;
   // ring of K/V steps + page ids of one sequence (2 per step of 32 tokens)
-  const int lds_bytes = kAStages * kAStageBytes + 2 * ((S + 31) / 32) * (int)sizeof(int);
+  const int lds_bytes = kAStages * kAStageBytes + 2 * ((map.pos_base + S + 31) / 32) * (int)sizeof(int);
   constexpr int kLdsMax = 160 * 1024;
   if (!configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill32), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -236,7 +238,7 @@ void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles,
     configured = true;
   }
   k_attn_prefill32<<<dim3((S + QB - 1) / QB, Hq, n_seqs), 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
-                                                                             map.row_stride, pool, layer);
+                                                                             map.row_stride, map.pos_base, pool, layer);
 }
 
 }  // namespace bf16

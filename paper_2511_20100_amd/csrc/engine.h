@@ -91,6 +91,51 @@ struct ScorePlan {
   size_t total_bytes;
 };
 
+// Action-level scoring.  The states (without their last token) are prefilled once into pages that
+// the K candidates of a state share; row b = n K + k then runs the A + 1 tokens
+// [last state token, action tokens, padding] at positions P - 1 .. P - 1 + A on top of them.
+struct ActionPlan {
+  int n_states, P, K, A, B;
+  int Pp;            // prefilled tokens per state (P - 1)
+  int W;             // tokens per candidate row (A + 1)
+  int n_full;        // pages per state completely filled by the prefilled tokens (shared)
+  int max_pages;     // page-table row length
+  int shared_total;  // n_states * n_full
+  int n_pages;
+  int chunk_states;  // states per prefill chunk
+  int chunk_rows;    // candidate rows per chunk of the second pass
+  int Tmax;          // token rows of the activation buffers
+  int rows_max;      // scored rows per chunk at most (chunk_rows * A)
+  int logit_rows;    // fp32 path: rows of the logits buffer
+  int* page_table;   // [B, max_pages]
+  int* vseq;         // [B, W]
+  int* prefix;       // [n_states, Pp]
+  void* kv;
+  float* h;
+  void* x;
+  float* qkv;
+  void* o;
+  float* gu;
+  void* a;
+  float* hs;
+  void* xs;
+  float* logits;
+  float* lm_part;
+  void* qb;
+  int* targets;
+  size_t total_bytes;
+};
+
+struct ActionArgs {
+  const int* states;
+  const int* actions;
+  const int* action_len;
+  int normalize;
+  float* out_token;
+  float* out_action;
+  float* out_policy;
+};
+
 struct SampleArgs {
   int greedy;
   float inv_temp;
@@ -112,6 +157,7 @@ struct ScoreArgs {
 RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, int n_samples,
                          int max_new, char* base);
 ScorePlan plan_score(const mtmc_weights* w, int n_seqs, int S, char* base);
+ActionPlan plan_actions(const mtmc_weights* w, int n_states, int P, int K, int A, char* base);
 
 // Rotary table (angles in double) and the device error flag.
 int build_aux(mtmc_weights* w, hipStream_t st);
@@ -127,10 +173,13 @@ int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob,
 int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
                  const SampleArgs& sa, hipStream_t st);
 int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hipStream_t st);
+int f32_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionArgs& a, hipStream_t st);
+int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionArgs& a, hipStream_t st);
 void destroy_graph_cache(mtmc_weights* w);
 int kernel_timer_set(mtmc_weights* w, int cls, int every);
 int kernel_timer_read(mtmc_weights* w, hipStream_t st, double* total_ms, int64_t* launches, double* empty_pair_ms);
 void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& c);
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& c);
+void bf16_plan_actions_extra(const mtmc_weights* w, ActionPlan& p, Carver& c);
 
 }  // namespace mtmc

@@ -125,6 +125,48 @@ ScorePlan plan_score(const mtmc_weights* w, int n_seqs, int S, char* base) {
   return p;
 }
 
+ActionPlan plan_actions(const mtmc_weights* w, int n_states, int P, int K, int A, char* base) {
+  const mtmc_config& c = w->cfg;
+  const bool bf = c.dtype == MTMC_BF16;
+  ActionPlan p{};
+  p.n_states = n_states; p.P = P; p.K = K; p.A = A; p.B = n_states * K;
+  p.Pp = P - 1; p.W = A + 1;
+  p.n_full = p.Pp / kPageTokens;
+  p.max_pages = (p.Pp + p.W + kPageTokens - 1) / kPageTokens;
+  p.shared_total = n_states * p.n_full;
+  p.n_pages = p.shared_total + p.B * (p.max_pages - p.n_full);
+  const int chunk = bf ? kScoreChunkTokensBf16 : kChunkTokens;
+  p.chunk_states = std::max(1, std::min(n_states, chunk / std::max(1, p.Pp)));
+  p.chunk_rows = std::max(1, std::min(p.B, chunk / p.W));
+  p.Tmax = (std::max(p.chunk_states * p.Pp, p.chunk_rows * p.W) + 127) / 128 * 128;
+  p.rows_max = (p.chunk_rows * A + 127) / 128 * 128;
+  const size_t act = bf ? 2 : 4;
+  const size_t d = c.d_model, nq = (size_t)c.n_q_heads * c.head_dim;
+  const size_t nqkv = nq + 2 * (size_t)c.n_kv_heads * c.head_dim;
+  const size_t F = bf ? w->d_ffn_pad : c.d_ffn;
+  Carver cv(base);
+  p.page_table = cv.take<int>((size_t)p.B * p.max_pages);
+  p.vseq = cv.take<int>((size_t)p.B * p.W);
+  p.prefix = cv.take<int>((size_t)n_states * p.Pp + 1);
+  p.kv = cv.take<char>((size_t)c.n_layers * 2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim * act);
+  p.h = cv.take<float>((size_t)p.Tmax * d);
+  p.x = cv.take<char>((size_t)p.Tmax * d * act);
+  p.qkv = cv.take<float>((size_t)p.Tmax * nqkv);
+  p.o = cv.take<char>((size_t)p.Tmax * nq * act);
+  p.a = cv.take<char>((size_t)p.Tmax * F * act);
+  p.hs = cv.take<float>((size_t)p.rows_max * d);
+  p.xs = cv.take<char>((size_t)p.rows_max * d * act);
+  if (!bf) {
+    p.gu = cv.take<float>((size_t)p.Tmax * 2 * F);
+    p.logit_rows = (int)std::max<size_t>(1, std::min<size_t>(p.rows_max, kLogitBytes / ((size_t)c.vocab * 4)));
+    p.logits = cv.take<float>((size_t)p.logit_rows * c.vocab);
+  } else {
+    bf16_plan_actions_extra(w, p, cv);
+  }
+  p.total_bytes = (cv.off + 255) / 256 * 256;
+  return p;
+}
+
 // ======================================================================================
 // fp32 path
 // ======================================================================================
@@ -261,6 +303,53 @@ int f32_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hip
                       a.out_margin, w->err_flag, st);
     }
   }
+  return MTMC_OK;
+}
+
+int f32_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionArgs& a, hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  const int d = c.d_model, V = c.vocab;
+  F32Acts A{p.h, (float*)p.x, p.qkv, (float*)p.o, p.gu, (float*)p.a};
+  KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};
+  launch_build_page_table(p.page_table, p.B, p.max_pages, p.K, p.n_full, p.shared_total, st);
+  launch_build_action_seqs(p.vseq, p.prefix, a.states, a.actions, a.action_len, p.n_states, p.P, p.K, p.A,
+                           w->err_flag, st);
+  launch_fill_u32((uint32_t*)a.out_token, 0u, (size_t)p.B * p.A, st);
+  // ---- the states without their last token, once per state, into the pages of their first candidate
+  if (p.Pp > 0) {
+    for (int n0 = 0; n0 < p.n_states; n0 += p.chunk_states) {
+      const int ns = std::min(p.chunk_states, p.n_states - n0);
+      const int T = ns * p.Pp;
+      KvPool chunk_pool = pool;
+      chunk_pool.page_table = p.page_table + (size_t)n0 * p.K * p.max_pages;
+      TokMap map{p.Pp, p.K, 0, nullptr};
+      f32::embed(A.h, p.prefix + (size_t)n0 * p.Pp, T, (const float*)w->embed, d, V, w->err_flag, st);
+      f32_layers(w, A, T, map, chunk_pool, 1, st);
+    }
+    if (p.Pp % kPageTokens != 0) launch_fork_tail_pages(pool, c.n_layers, p.B, p.K, p.n_full, 4, st);
+  }
+  // ---- the candidates: W tokens per row on top of the shared pages, every position scored
+  TokMap map{p.W, 1, p.Pp, nullptr};
+  for (int r0 = 0; r0 < p.B; r0 += p.chunk_rows) {
+    const int nr = std::min(p.chunk_rows, p.B - r0);
+    const int T = nr * p.W;
+    KvPool chunk_pool = pool;
+    chunk_pool.page_table = p.page_table + (size_t)r0 * p.max_pages;
+    f32::embed(A.h, p.vseq + (size_t)r0 * p.W, T, (const float*)w->embed, d, V, w->err_flag, st);
+    f32_layers(w, A, T, map, chunk_pool, 1, st);
+    const int R = nr * p.A;
+    launch_gather_rows(p.hs, A.h, R, d, p.A, p.W, 0, 1, st);
+    f32::rmsnorm((float*)p.xs, p.hs, w->final_norm, c.rms_eps, R, d, st);
+    for (int q0 = 0; q0 < R; q0 += p.logit_rows) {
+      const int nq = std::min(p.logit_rows, R - q0);
+      f32::gemm(p.logits, V, (const float*)p.xs + (size_t)q0 * d, d, (const float*)w->lm_head, nq, V, d,
+                false, st);
+      f32::score_rows(p.logits, nq, V, p.vseq, p.W, 0, p.A, r0, q0, a.out_token, nullptr, nullptr, w->err_flag,
+                      st);
+    }
+  }
+  launch_action_reduce(a.out_token, a.action_len, p.n_states, p.K, p.A, a.normalize, a.out_action, a.out_policy,
+                       st);
   return MTMC_OK;
 }
 

@@ -282,6 +282,15 @@ void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
   p.targets = cv.take<int>(p.rows_max);
 }
 
+void bf16_plan_actions_extra(const mtmc_weights* w, ActionPlan& p, Carver& cv) {
+  const Dims D = dims_of(w);
+  int gpb = 0;
+  const int blocks = bf16::score_head_blocks(D.nt_V, &gpb);
+  p.lm_part = cv.take<float>((size_t)blocks * 2 * p.rows_max * 8);
+  p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
+  p.targets = cv.take<int>(p.rows_max);
+}
+
 // ======================================================================================
 // schedulers
 // ======================================================================================
@@ -534,6 +543,58 @@ int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hi
     bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets, w->opt_lds_min_blocks, st);
     bf16::score_reduce(p.lm_part, n_parts, R, S, a.first, n_scored, s0, 0, a.out_logprobs, a.out_top1, a.out_margin, st);
   }
+  return MTMC_OK;
+}
+
+int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionArgs& a, hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  const Dims D = dims_of(w);
+  KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};
+  launch_build_page_table(p.page_table, p.B, p.max_pages, p.K, p.n_full, p.shared_total, st);
+  launch_build_action_seqs(p.vseq, p.prefix, a.states, a.actions, a.action_len, p.n_states, p.P, p.K, p.A,
+                           w->err_flag, st);
+  launch_fill_u32((uint32_t*)a.out_token, 0u, (size_t)p.B * p.A, st);
+  // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
+  launch_fill_u32((uint32_t*)p.kv, 0u,
+                  (size_t)c.n_layers * 2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim / 2, st);
+  // ---- the states without their last token, once per state, into the pages of their first candidate
+  if (p.Pp > 0) {
+    for (int n0 = 0; n0 < p.n_states; n0 += p.chunk_states) {
+      const int ns = std::min(p.chunk_states, p.n_states - n0);
+      const int T = ns * p.Pp, mt = tiles16(T);
+      KvPool chunk_pool = pool;
+      chunk_pool.page_table = p.page_table + (size_t)n0 * p.K * p.max_pages;
+      TokMap map{p.Pp, p.K, 0, nullptr};
+      bf16::embed(p.h, p.prefix + (size_t)n0 * p.Pp, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+      bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+      prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, p.Pp, map,
+                     chunk_pool, 1, st);
+    }
+    if (p.Pp % kPageTokens != 0) launch_fork_tail_pages(pool, c.n_layers, p.B, p.K, p.n_full, 2, st);
+  }
+  // ---- the candidates: W tokens per row on top of the shared pages, every position scored
+  TokMap map{p.W, 1, p.Pp, nullptr};
+  int gpb = 0;
+  const int n_parts = bf16::score_head_blocks(D.nt_V, &gpb) * 2;
+  for (int r0 = 0; r0 < p.B; r0 += p.chunk_rows) {
+    const int nr = std::min(p.chunk_rows, p.B - r0);
+    const int T = nr * p.W, mt = tiles16(T);
+    KvPool chunk_pool = pool;
+    chunk_pool.page_table = p.page_table + (size_t)r0 * p.max_pages;
+    bf16::embed(p.h, p.vseq + (size_t)r0 * p.W, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, nr, p.W, map,
+                   chunk_pool, 1, st);
+    const int R = nr * p.A, rt = tiles16(R);
+    launch_gather_rows(p.hs, p.h, R, D.d, p.A, p.W, 0, 1, st);
+    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
+    bf16::score_targets(p.targets, p.vseq, R, p.W, 0, p.A, r0, 0, D.V, w->err_flag, st);
+    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
+                       w->opt_lds_min_blocks, st);
+    bf16::score_reduce(p.lm_part, n_parts, R, p.W, 0, p.A, r0, 0, a.out_token, nullptr, nullptr, st);
+  }
+  launch_action_reduce(a.out_token, a.action_len, p.n_states, p.K, p.A, a.normalize, a.out_action, a.out_policy,
+                       st);
   return MTMC_OK;
 }
 

@@ -22,6 +22,17 @@ void launch_gather_rows(float* dst, const float* src, int rows, int d, int n_rep
 void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, int page_idx,
                             int elem_bytes, hipStream_t st);
 
+// Action-level scoring.  vseq [n_states K, A + 1]: row n K + k = last token of state n, then the
+// tokens of candidate k, then zeros; prefix [n_states, P - 1]: the states without their last token.
+// An action_len outside [0, A] raises bit 4 of *err_flag and is clamped.
+void launch_build_action_seqs(int* vseq, int* prefix, const int* states, const int* actions,
+                              const int* action_len, int n_states, int P, int K, int A, int* err_flag,
+                              hipStream_t st);
+// token_lp [n_states K, A] in place: padding cleared; out_action = per-candidate sums (divided by the
+// length if normalize); out_policy = their log-softmax over the K candidates of a state.
+void launch_action_reduce(float* token_lp, const int* action_len, int n_states, int K, int A, int normalize,
+                          float* out_action, float* out_policy, hipStream_t st);
+
 // ---------------------------------------------------------------- fp32 path
 namespace f32 {
 void embed(float* h, const int* ids, int T, const float* E, int d, int vocab, int* err_flag,

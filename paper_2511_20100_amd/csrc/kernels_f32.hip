@@ -1,5 +1,7 @@
 // fp32 path: plain HIP kernels for the small all-fp32 configuration, plus the layout/control
 // kernels both paths use.  Correctness vehicle; the bf16 path has its own tuned kernels.
+#include <algorithm>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -76,6 +78,87 @@ void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, 
                             int elem_bytes, hipStream_t st) {
   const int words = pool.n_kv_heads * kPageTokens * pool.head_dim * elem_bytes / 4;
   k_fork_tail_pages<<<dim3(rows, n_layers * 2), 256, 0, st>>>(pool, n_samples, page_idx, words);
+}
+
+// =====================================================================================
+// action-level scoring: inputs of the two passes, and the sums / softmax over the candidates
+// =====================================================================================
+// Row b = n K + k of vseq is [last state token, action tokens ..., 0 padding]; prefix row n is the
+// state without its last token.
+__global__ void k_build_action_seqs(int* vseq, int* prefix, const int* states, const int* actions,
+                                    const int* action_len, int n_states, int P, int K, int A, int* err_flag) {
+  const int W = A + 1;
+  const size_t n_v = (size_t)n_states * K * W, n_p = (size_t)n_states * (P - 1);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_v + n_p;
+       i += (size_t)gridDim.x * blockDim.x) {
+    if (i < n_v) {
+      const int b = (int)(i / W), j = (int)(i % W);
+      int len = action_len[b];
+      if (len < 0 || len > A) {
+        if (j == 0) atomicOr(err_flag, 4);
+        len = len < 0 ? 0 : A;
+      }
+      vseq[i] = (j == 0) ? states[(size_t)(b / K) * P + P - 1] : (j <= len ? actions[(size_t)b * A + j - 1] : 0);
+    } else {
+      const size_t r = i - n_v;
+      prefix[r] = states[(r / (P - 1)) * P + r % (P - 1)];
+    }
+  }
+}
+void launch_build_action_seqs(int* vseq, int* prefix, const int* states, const int* actions,
+                              const int* action_len, int n_states, int P, int K, int A, int* err_flag,
+                              hipStream_t st) {
+  const size_t n = (size_t)n_states * K * (A + 1) + (size_t)n_states * (P - 1);
+  const int blocks = (int)std::min<size_t>((n + 255) / 256, 2048);
+  k_build_action_seqs<<<blocks, 256, 0, st>>>(vseq, prefix, states, actions, action_len, n_states, P, K, A,
+                                              err_flag);
+}
+
+// One workgroup per state.  Candidate k: padding terms of token_lp are cleared, the others summed
+// in position order (double), divided by the length if asked; then the log-softmax over the K
+// sums, with the maximum and the sum of exponentials reduced in a fixed tree order.
+__global__ __launch_bounds__(256) void k_action_reduce(float* token_lp, const int* action_len, int K, int A,
+                                                       int normalize, float* out_action, float* out_policy) {
+  __shared__ double red[256];
+  const int n = blockIdx.x, tid = threadIdx.x;
+  auto total_of = [&](int k) {
+    const int b = n * K + k;
+    const int len = min(max(action_len[b], 0), A);
+    const float* row = token_lp + (size_t)b * A;
+    double s = 0.0;
+    for (int j = 0; j < len; ++j) s += (double)row[j];
+    return (normalize && len > 0) ? s / (double)len : s;
+  };
+  auto block_reduce = [&](double v, bool take_max) {
+    red[tid] = v;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if (tid < w) red[tid] = take_max ? fmax(red[tid], red[tid + w]) : red[tid] + red[tid + w];
+      __syncthreads();
+    }
+    const double r = red[0];
+    __syncthreads();
+    return r;
+  };
+  double mx = -INFINITY;
+  for (int k = tid; k < K; k += 256) {
+    const int b = n * K + k;
+    const int len = min(max(action_len[b], 0), A);
+    for (int j = len; j < A; ++j) token_lp[(size_t)b * A + j] = 0.f;
+    const double t = total_of(k);
+    out_action[b] = (float)t;
+    mx = fmax(mx, t);
+  }
+  mx = block_reduce(mx, true);
+  double se = 0.0;
+  for (int k = tid; k < K; k += 256) se += exp(total_of(k) - mx);
+  se = block_reduce(se, false);
+  const double lse = mx + log(se);
+  for (int k = tid; k < K; k += 256) out_policy[n * K + k] = (float)(total_of(k) - lse);
+}
+void launch_action_reduce(float* token_lp, const int* action_len, int n_states, int K, int A, int normalize,
+                          float* out_action, float* out_policy, hipStream_t st) {
+  k_action_reduce<<<n_states, 256, 0, st>>>(token_lp, action_len, K, A, normalize, out_action, out_policy);
 }
 
 namespace f32 {

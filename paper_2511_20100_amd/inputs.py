@@ -229,3 +229,18 @@ def make_prompts(n_prompts: int, prompt_len: int, vocab: int, seed: int) -> np.n
 
 def make_sequences(n_seqs: int, seq_len: int, vocab: int, seed: int) -> np.ndarray:
     return make_token_ids((n_seqs, seq_len), vocab, seed)
+
+
+def make_actions(n_states: int, n_actions: int, max_action_len: int, vocab: int, seed: int,
+                 min_len: int = 1) -> Tuple[np.ndarray, np.ndarray]:
+    """Candidate actions of every state: uniform random token ids [n_states, n_actions, max_action_len]
+    and lengths uniform in [min_len, max_action_len] (int32 [n_states, n_actions]).  The first candidate
+    of every state has the full length, so the longest row is always exercised; with min_len 0 the last
+    candidate of every state is empty."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0x61637473])))
+    actions = rng.integers(0, vocab, size=(n_states, n_actions, max_action_len), dtype=np.int64).astype(np.int32)
+    lens = rng.integers(min_len, max_action_len + 1, size=(n_states, n_actions), dtype=np.int64).astype(np.int32)
+    if min_len == 0:
+        lens[:, -1] = 0
+    lens[:, 0] = max_action_len
+    return actions, lens

@@ -55,6 +55,10 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_score_workspace_bytes.restype = sz
     lib.mtmc_score.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.mtmc_score.restype = ctypes.c_int
+    lib.mtmc_score_actions_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.mtmc_score_actions_workspace_bytes.restype = sz
+    lib.mtmc_score_actions.argtypes = [vp, vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.mtmc_score_actions.restype = ctypes.c_int
     lib.mtmc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.mtmc_set_option.restype = ctypes.c_int
     lib.mtmc_kernel_timer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -74,7 +78,8 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mtmc_rollout_workspace_bytes",
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
-           "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe")
+           "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
+           "mtmc_score_actions_workspace_bytes", "mtmc_score_actions")
 
 
 def mtmc_last_error() -> str:
@@ -170,6 +175,37 @@ def mtmc_score(handle: int, seqs: torch.Tensor, prompt_len: int = 1, *, want_top
                            top1.data_ptr() if want_top1 else None, margin.data_ptr() if want_top1 else None,
                            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return (out_logprobs, top1, margin) if want_top1 else out_logprobs
+
+
+def mtmc_score_actions_workspace_bytes(handle: int, n_states: int, state_len: int, n_actions: int,
+                                       max_action_len: int) -> int:
+    n = int(_lib.mtmc_score_actions_workspace_bytes(handle, n_states, state_len, n_actions, max_action_len))
+    if n == 0:
+        raise MtmcError(MTMC_EINVAL, mtmc_last_error())
+    return n
+
+
+def mtmc_score_actions(handle: int, states: torch.Tensor, actions: torch.Tensor, action_len: torch.Tensor, *,
+                       normalize: bool = False, workspace: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None):
+    """states int32 [n_states, state_len], actions int32 [n_states, K, A], action_len int32 [n_states, K]
+    (CUDA tensors).  Returns (token_logprobs [n_states, K, A], action_logprobs [n_states, K],
+    policy_logprobs [n_states, K])."""
+    for t in (states, actions, action_len):
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+    n_states, P = states.shape
+    ns2, K, A = actions.shape
+    assert ns2 == n_states and tuple(action_len.shape) == (n_states, K)
+    if workspace is None:
+        workspace = torch.empty(mtmc_score_actions_workspace_bytes(handle, n_states, P, K, A), dtype=torch.uint8,
+                                device=states.device)
+    tok = torch.empty((n_states, K, A), dtype=torch.float32, device=states.device)
+    act = torch.empty((n_states, K), dtype=torch.float32, device=states.device)
+    pol = torch.empty((n_states, K), dtype=torch.float32, device=states.device)
+    _check(_lib.mtmc_score_actions(handle, states.data_ptr(), n_states, P, actions.data_ptr(), action_len.data_ptr(),
+                                   K, A, 1 if normalize else 0, tok.data_ptr(), act.data_ptr(), pol.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return tok, act, pol
 
 
 MTMC_OPT_HIP_GRAPH = 1

@@ -55,3 +55,30 @@ def check_score(handle, w, seqs, prompt_len, *, max_positions, rows=None, tol=LO
     assert np.array_equal(top1[rows][gate], ref_top1[gate]), f"{label}: top-1 ids differ above the margin gate"
     assert np.abs(margin[rows] - ref_margin).max() <= 2 * tol
     return {"logprobs": s, "max_logp_err": float(err), "compared": int(gate.sum()), "positions": int(gate.size)}
+
+
+def check_actions(handle, w, states, actions, lens, *, normalize=False, max_positions, tol, label=""):
+    """Runs mtmc_score_actions and compares all three outputs with the oracle's action_policy.
+    Per-token terms within tol; an action's score is a sum of N terms, so N * tol bounds it (tol when
+    normalised); a policy term is a score minus a weighted mean of scores: twice that bound."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    tok, act, pol = mtmc.mtmc_score_actions(handle, torch.from_numpy(states).cuda(), torch.from_numpy(actions).cuda(),
+                                            torch.from_numpy(lens).cuda(), normalize=normalize)
+    mtmc.mtmc_poll_errors(handle)
+    tok, act, pol = tok.cpu().numpy(), act.cpu().numpy(), pol.cpu().numpy()
+    ref_tok, ref_act, ref_pol = oracle.action_policy(oracle_model(w, max_positions), states, actions, lens,
+                                                     normalize=normalize)
+    A = actions.shape[2]
+    pad = np.arange(A)[None, None, :] >= lens[:, :, None]
+    assert np.all(tok[pad] == 0.0), f"{label}: padding terms must be zero"
+    e_tok = float(np.abs(tok - ref_tok).max())
+    assert e_tok <= tol, f"{label}: token log-prob error {e_tok}"
+    act_tol = tol * (1 if normalize else np.maximum(lens, 1))
+    e_act = np.abs(act - ref_act)
+    assert np.all(e_act <= act_tol), f"{label}: action log-prob error {e_act.max()}"
+    e_pol = np.abs(pol - ref_pol)
+    assert np.all(e_pol <= 2 * np.max(act_tol)), f"{label}: policy log-prob error {e_pol.max()}"
+    assert np.allclose(np.exp(pol.astype(np.float64)).sum(axis=1), 1.0, atol=1e-5)
+    return {"token": tok, "action": act, "policy": pol, "max_token_err": e_tok, "max_action_err": float(e_act.max()),
+            "max_policy_err": float(e_pol.max())}
