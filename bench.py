@@ -98,6 +98,7 @@ def main() -> int:
     ap.add_argument("--max-new", type=int, default=None, help="override the number of new tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-score", action="store_true", help="time the rollout alone")
+    ap.add_argument("--no-actions", action="store_true", help="skip the action-scoring leg (reported beside the step)")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps directly (for counter runs)")
     ap.add_argument("--no-kernel-timer", action="store_true", help="do not bracket the gate/up launches with events")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -227,6 +228,25 @@ def main() -> int:
         result["score_ms"] = s_ms
         result["score_mfma"] = {"bound": "mfma", "achieved": flops / (s_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
                                 "unit": "TFLOP/s", "frac": flops / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+    if not args.no_actions:
+        # beside the step, not part of `value`: the prompts as states, 32 candidate actions of up to 32 tokens each
+        K, A = 32, min(32, max_new)
+        actions_np, lens_np = inputs.make_actions(n_prompts, K, A, cfg.vocab, seed=4)
+        d_actions, d_lens = torch.from_numpy(actions_np).to(dev), torch.from_numpy(lens_np).to(dev)
+        ws_a = torch.empty(mtmc.mtmc_score_actions_workspace_bytes(handle, n_prompts, prompt_len, K, A),
+                           dtype=torch.uint8, device=dev)
+        mtmc.mtmc_score_actions(handle, prompts, d_actions, d_lens, workspace=ws_a)
+        ev[0].record(stream)
+        for _ in range(3):
+            mtmc.mtmc_score_actions(handle, prompts, d_actions, d_lens, workspace=ws_a)
+        ev[1].record(stream)
+        ev[1].synchronize()
+        mtmc.mtmc_poll_errors(handle)
+        a_ms = ev[0].elapsed_time(ev[1]) / 3
+        result["action_scoring"] = {"workload": f"{n_prompts} states x {prompt_len} tokens, {K} candidate actions each, "
+                                                f"1..{A} tokens per action", "ms": a_ms,
+                                    "actions_per_s": n_prompts * K / (a_ms * 1e-3)}
+        del ws_a
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(weights, cfg, prompts_np, seq_len)
     mtmc.mtmc_weights_destroy(handle)

@@ -1,12 +1,15 @@
 // Causal grouped-query attention of the prefill / scoring pass (head_dim 128) on the 32x32x16 MFMA.
 //
-// One workgroup per (256 query positions, query head, sequence): eight column blocks of 32 positions.
-// Wavefront w takes blocks w and 7 - w.  Every block takes part in every step up to the workgroup's last
-// key (steps beyond a block's own positions are fully masked and add zeros: branching on that made the
-// register allocator spill, which cost more than the ~12 % of MFMAs saved).  The workgroup walks the keys in steps of
-// 32 tokens (two 16-token pages): the four wavefronts copy the two K pages and two V pages of a step
-// (16 KiB) into a ring of LDS buffers with LDS-direct loads, three steps ahead, and every wavefront reads
-// them from there.
+// One workgroup per (256 query columns, kv head, sequence).  The columns of a kv head are the
+// (query head of its group, position) pairs, position fastest: with S a multiple of 256 a workgroup holds 256
+// consecutive positions of one query head; with short sequences (the candidate rows of action scoring, small
+// prompts) the G query heads of the group sit side by side in one workgroup and share every K/V step.
+// Eight column blocks of 32; wavefront w takes blocks w and 7 - w.  Every block takes part in every step up to
+// the workgroup's last key (steps beyond a block's own positions are fully masked and add zeros: branching on
+// that made the register allocator spill, which cost more than the ~12 % of MFMAs saved).  The workgroup walks
+// the keys in steps of 32 tokens (two 16-token pages): the four wavefronts copy the two K pages and two V pages
+// of a step (16 KiB) into a ring of LDS buffers with LDS-direct loads, three steps ahead, and every wavefront
+// reads them from there.  Query j of a sequence sits at position pos_base + j and sees keys 0 .. pos_base + j.
 //
 // Per step and column block:  S^T[token][column] = K Q^T  (8 MFMAs over the 128 dims), online softmax
 // down each column (a column's 32 tokens sit in 16 registers of lanes l and l + 32), then
@@ -49,15 +52,19 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
                                                            int row_stride, int pos_base, KvPool pool, int layer) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int qblk = gridDim.x - 1 - blockIdx.x;  // longest columns first
-  const int q0 = qblk * QB, qhead = blockIdx.y, seq = blockIdx.z;
-  const int G = Hq / Hkv, g = qhead / G;
+  const int c0 = qblk * QB, g = blockIdx.y, seq = blockIdx.z;
+  const int G = Hq / Hkv, n_cols = G * S;
+  // positions covered by the workgroup's columns: exact when they belong to one query head, else all
+  const int c_last = min(c0 + QB, n_cols) - 1;
+  const bool one_head = c0 / S == c_last / S;
+  const int min_pos = one_head ? c0 % S : 0, max_pos = one_head ? c_last % S : S - 1;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   const int col = lane & 31, hh = lane >> 5;
   const int* table = pool.page_table + (size_t)seq * row_stride * pool.max_pages;
   // query j of the sequence sits at position pos_base + j and sees the keys at positions 0 .. pos_base + j
   const int seq_pages = (pos_base + S + kPageTokens - 1) / kPageTokens;
-  const int n_steps = (pos_base + min(q0 + QB, S) + 31) / 32;  // key blocks 0 .. n_steps - 1 (causal)
+  const int n_steps = (pos_base + max_pos + 32) / 32;  // key blocks 0 .. n_steps - 1 (causal)
 
   // ---- page ids of the steps, staged in LDS behind the ring (a global load inside the loop would be a
   // vector load, and waiting for it would drain the ring of copies in flight)
@@ -82,17 +89,20 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
 #pragma unroll
   for (int s = 0; s < kAStages - 1; ++s) issue(s, s);
 
-  // ---- this wavefront's column blocks (positions q0 + 32 b + col, b = wave and 7 - wave).
+  // ---- this wavefront's column blocks (columns c0 + 32 b + col, b = wave and 7 - wave).
   // Q fragments (B operand: column col, dims 16 j + 8 hh + 0..7).
   v8bf qf[NCB][8];
-  int qpos[NCB], qabs[NCB];  // index in the sequence / position among the keys (-1: padding column)
+  int qpos[NCB], qabs[NCB], qhd[NCB];  // index in the sequence / position among the keys (-1: padding), head
 #pragma unroll
   for (int i = 0; i < NCB; ++i) {
     const int b = (i == 0) ? uwave : 7 - uwave;
-    const int pos = q0 + 32 * b + col;
-    qpos[i] = (pos < S) ? pos : -1;
-    qabs[i] = (pos < S) ? pos_base + pos : -1;
-    const h16_t* qrow = q + ((size_t)seq * S + max(qpos[i], 0)) * Hq * PHD + (size_t)qhead * PHD + 8 * hh;
+    const int c = c0 + 32 * b + col;
+    const bool live = c < n_cols;
+    const int jh = live ? c / S : 0, pos = c - jh * S;
+    qpos[i] = live ? pos : -1;
+    qabs[i] = live ? pos_base + pos : -1;
+    qhd[i] = g * G + jh;
+    const h16_t* qrow = q + ((size_t)seq * S + max(qpos[i], 0)) * Hq * PHD + (size_t)qhd[i] * PHD + 8 * hh;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       v4u raw = {0u, 0u, 0u, 0u};
@@ -135,7 +145,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
     }
     // ---- online softmax down each column; P^T fragments for the two token groups
     v8bf pf[NCB][2];
-    const bool diag = 32 * t + 31 > pos_base + q0;  // some column of the workgroup may not see all 32 tokens
+    const bool diag = 32 * t + 31 > pos_base + min_pos;  // some column of the workgroup may not see all 32 tokens
 #pragma unroll
     for (int i = 0; i < NCB; ++i) {
       float sv[16];
@@ -219,7 +229,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
         uint2 pk;
         pk.x = pack_h16x2(oacc[i][d][4 * qq] * inv, oacc[i][d][4 * qq + 1] * inv);
         pk.y = pack_h16x2(oacc[i][d][4 * qq + 2] * inv, oacc[i][d][4 * qq + 3] * inv);
-        *reinterpret_cast<uint2*>(o + act_off(tok, qhead * PHD + 32 * d + 8 * qq + 4 * hh, Mpad)) = pk;
+        *reinterpret_cast<uint2*>(o + act_off(tok, qhd[i] * PHD + 32 * d + 8 * qq + 4 * hh, Mpad)) = pk;
       }
   }
 }
@@ -237,7 +247,8 @@ void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles,
                               kLdsMax);
     configured = true;
   }
-  k_attn_prefill32<<<dim3((S + QB - 1) / QB, Hq, n_seqs), 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
+  const int n_cols = Hq / Hkv * S;
+  k_attn_prefill32<<<dim3((n_cols + QB - 1) / QB, Hkv, n_seqs), 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
                                                                              map.row_stride, map.pos_base, pool, layer);
 }
 

@@ -15,6 +15,7 @@ from paper_2511_20100_amd import inputs
 
 CFG = inputs.POLICY_1P5B
 N_PROMPTS, PROMPT_LEN, N_SAMPLES, MAX_NEW = 8, 512, 8, 1024
+N_ACTIONS, MAX_ACTION_LEN = 8, 16
 
 
 @pytest.fixture(scope="module")
@@ -29,8 +30,17 @@ def run():
     ids2, lp2 = mtmc.mtmc_rollout(handle, dprompts, N_SAMPLES, MAX_NEW, 1.0, 1)
     seqs = torch.cat([dprompts.repeat_interleave(N_SAMPLES, 0), ids], 1).contiguous()
     score, top1, margin = mtmc.mtmc_score(handle, seqs, PROMPT_LEN, want_top1=True)
+    # action-level scoring at the same shape: the prompts as states, 8 candidates of up to 16 tokens each
+    actions, lens = inputs.make_actions(N_PROMPTS, N_ACTIONS, MAX_ACTION_LEN, CFG.vocab, seed=4)
+    a_tok, a_act, a_pol = mtmc.mtmc_score_actions(handle, dprompts, torch.from_numpy(actions).cuda(),
+                                                  torch.from_numpy(lens).cuda())
+    a_seqs = torch.cat([dprompts.repeat_interleave(N_ACTIONS, 0),
+                        torch.from_numpy(actions.reshape(-1, MAX_ACTION_LEN)).cuda()], 1).contiguous()
+    a_score = mtmc.mtmc_score(handle, a_seqs, PROMPT_LEN)
     mtmc.mtmc_poll_errors(handle)
-    out = dict(w=w, prompts=prompts, ids=ids.cpu().numpy(), lp=lp.cpu().numpy(), ids2=ids2.cpu().numpy(),
+    acts = dict(actions=actions, lens=lens, tok=a_tok.cpu().numpy(), act=a_act.cpu().numpy(), pol=a_pol.cpu().numpy(),
+                score=a_score.cpu().numpy()[:, PROMPT_LEN - 1:].reshape(N_PROMPTS, N_ACTIONS, MAX_ACTION_LEN))
+    out = dict(w=w, prompts=prompts, acts=acts, ids=ids.cpu().numpy(), lp=lp.cpu().numpy(), ids2=ids2.cpu().numpy(),
                lp2=lp2.cpu().numpy(), score=score.cpu().numpy(), top1=top1.cpu().numpy(), margin=margin.cpu().numpy())
     mtmc.mtmc_weights_destroy(handle)
     return out
@@ -85,3 +95,31 @@ def test_score_top1_against_the_oracle(run):
     assert np.array_equal(run["top1"][row, sl][gate], ref_top1[0, sl][gate])
     assert np.abs(run["score"][row, sl] - ref_s[0, sl]).max() <= LOGP_TOL_BF16
     assert np.abs(run["margin"][row, sl] - ref_margin[0, sl]).max() <= 2 * LOGP_TOL_BF16
+
+
+def test_action_scoring_properties_at_full_size(run):
+    """Properties that hold at any size: padding terms are zero, a state's policy is a distribution, the
+    sums are the sums, and the per-token terms agree with the scoring pass over state + action as one
+    sequence (a different launch shape of the same kernels)."""
+    a = run["acts"]
+    live = np.arange(MAX_ACTION_LEN)[None, None, :] < a["lens"][:, :, None]
+    assert np.all(a["tok"][~live] == 0.0) and np.all(a["tok"][live] < 0.0)
+    assert np.allclose(a["tok"].astype(np.float64).sum(axis=2), a["act"], atol=1e-4)
+    assert np.allclose(np.exp(a["pol"].astype(np.float64)).sum(axis=1), 1.0, atol=1e-5)
+    d = np.abs(np.where(live, a["tok"] - a["score"], 0.0))
+    print("action terms vs scoring pass: max", d.max())
+    assert d.max() <= 2 * LOGP_TOL_BF16
+
+
+def test_sampled_actions_against_the_oracle(run):
+    """The oracle evaluates two candidates of one state from scratch (state and action as one sequence)."""
+    a = run["acts"]
+    model = oracle_model(run["w"], PROMPT_LEN + MAX_NEW)
+    n, ks = 3, [0, 5]
+    ref_tok, ref_act, _ = oracle.action_policy(model, run["prompts"][n:n + 1], a["actions"][n:n + 1, ks],
+                                               a["lens"][n:n + 1, ks])
+    e_tok = np.abs(ref_tok[0] - a["tok"][n, ks]).max()
+    e_act = np.abs(ref_act[0] - a["act"][n, ks])
+    print("1.5 B actions: token err", e_tok, "action err", e_act.max())
+    assert e_tok <= LOGP_TOL_BF16
+    assert np.all(e_act <= LOGP_TOL_BF16 * a["lens"][n, ks])
