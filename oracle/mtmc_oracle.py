@@ -15,6 +15,7 @@ product of the per-token conditionals (Eq. 2).  Two operations follow from that:
                  logarithms of the factors of Eq. 2.
 * ``action_policy`` -- the sums of those terms over each candidate action of a state and
                  their softmax over the candidate set (the sampling probability of an action).
+* ``rollout_ragged`` -- the same for prompts of different lengths, ending at a stop token.
 * ``rollout`` -- sampling a token sequence from the same conditionals, one token at a
                  time (Inference Pipeline, "Macro Thinking": the policy outputs an action),
                  by the Gumbel-max rule with noise from a counter-based generator.
@@ -378,6 +379,40 @@ def rollout(model: Model, prompts: np.ndarray, n_samples: int, max_new: int,
                 if mode == "cache" and i + 1 < max_new:
                     z = extend(model, cache, np.array([tok], dtype=np.int64))
     return ids, logp, margins
+
+
+def rollout_ragged(model: Model, prompts: np.ndarray, prompt_lens: np.ndarray, n_samples: int, max_new: int,
+                   temperature: float, seed: int, stop_id: int = -1, first_seq: int = 0):
+    """Rollout of prompts of different lengths with an optional stop token (Inference Pipeline,
+    "Macro Thinking": generation ends with a terminal action or at the step limit).
+
+    prompts int [P, Lmax], right-padded: prompt p is prompts[p, :prompt_lens[p]] and the padding is
+    never looked at.  Sequence b = first_seq + p * n_samples + s continues prompt p exactly as
+    ``rollout`` would continue it alone.  With stop_id >= 0 a sequence ends with the first sampled
+    stop_id: that token and its log-probability are reported, every later slot holds stop_id with
+    log-probability 0.  Returns (ids [B, max_new] int32, logp float32, lens int32 [B] = tokens
+    generated including the stop token, margins float32 (0 after the end))."""
+    P = prompts.shape[0]
+    B = P * n_samples
+    ids = np.zeros((B, max_new), dtype=np.int32)
+    logp = np.zeros((B, max_new), dtype=np.float32)
+    margins = np.zeros((B, max_new), dtype=np.float32)
+    lens = np.full(B, max_new, dtype=np.int32)
+    for p in range(P):
+        rows = slice(p * n_samples, (p + 1) * n_samples)
+        ids[rows], logp[rows], margins[rows] = rollout(model, prompts[p:p + 1, :int(prompt_lens[p])], n_samples,
+                                                       max_new, temperature, seed,
+                                                       first_seq=first_seq + p * n_samples)
+    if stop_id >= 0:
+        for b in range(B):
+            hits = np.nonzero(ids[b] == stop_id)[0]
+            if hits.size:
+                n = int(hits[0]) + 1
+                lens[b] = n
+                ids[b, n:] = stop_id
+                logp[b, n:] = 0.0
+                margins[b, n:] = 0.0
+    return ids, logp, lens, margins
 
 
 def replay(model: Model, prompt: np.ndarray, new_ids: np.ndarray, temperature: float,

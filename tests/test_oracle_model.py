@@ -317,6 +317,53 @@ def test_sampler_does_not_depend_on_batch_composition():
     assert not np.array_equal(ids[0], ids[1])
 
 
+def test_ragged_rollout_reduces_to_the_uniform_one_and_ignores_padding():
+    cfg = small_cfg()
+    m = oracle_model(inputs.make_weights(cfg, seed=1, std=0.3), max_positions=64)
+    prompts = inputs.make_prompts(3, 7, cfg.vocab, seed=8)
+    # equal lengths, no stop token: exactly the uniform rollout
+    ids, lp, mar = oracle.rollout(m, prompts, 2, 5, 1.0, seed=11)
+    rid, rlp, rlens, rmar = oracle.rollout_ragged(m, prompts, np.array([7, 7, 7]), 2, 5, 1.0, seed=11)
+    assert np.array_equal(ids, rid) and np.array_equal(lp, rlp) and np.all(rlens == 5) and np.array_equal(mar, rmar)
+    # different lengths: each prompt continues as it would alone, whatever the padding holds
+    lens = np.array([7, 3, 5])
+    rid, rlp, _, _ = oracle.rollout_ragged(m, prompts, lens, 2, 5, 1.0, seed=11)
+    junk = prompts.copy()
+    for p in range(3):
+        junk[p, lens[p]:] = (junk[p, lens[p]:] + 1) % cfg.vocab
+    jid, jlp, _, _ = oracle.rollout_ragged(m, junk, lens, 2, 5, 1.0, seed=11)
+    assert np.array_equal(rid, jid) and np.array_equal(rlp, jlp)
+    for p in range(3):
+        alone, alp, _ = oracle.rollout(m, prompts[p:p + 1, :lens[p]], 2, 5, 1.0, seed=11, first_seq=2 * p)
+        assert np.array_equal(rid[2 * p:2 * p + 2], alone) and np.array_equal(rlp[2 * p:2 * p + 2], alp)
+    assert np.array_equal(rid[0:2], ids[0:2]) and not np.array_equal(rid[2:4], ids[2:4])
+
+
+def test_stop_token_ends_a_sequence_and_changes_nothing_before_it():
+    cfg = small_cfg(vocab=6)
+    m = oracle_model(inputs.make_weights(cfg, seed=3, std=0.4), max_positions=64)
+    prompts = inputs.make_prompts(3, 6, cfg.vocab, seed=5)
+    lens = np.array([6, 2, 4])
+    free, flp, flens, _ = oracle.rollout_ragged(m, prompts, lens, 3, 8, 1.0, seed=2)
+    assert np.all(flens == 8)
+    stop = 4
+    ids, lp, n, mar = oracle.rollout_ragged(m, prompts, lens, 3, 8, 1.0, seed=2, stop_id=stop)
+    stopped = 0
+    for b in range(9):
+        hits = [i for i in range(8) if free[b, i] == stop]
+        end = hits[0] + 1 if hits else 8
+        stopped += bool(hits)
+        assert n[b] == end
+        assert np.array_equal(ids[b, :end], free[b, :end]) and np.array_equal(lp[b, :end], flp[b, :end])
+        assert np.all(ids[b, end:] == stop) and np.all(lp[b, end:] == 0.0) and np.all(mar[b, end:] == 0.0)
+        assert stop not in ids[b, :end - 1]
+        # the reported terms are the Eq. 2 factors of the tokens that were generated
+        seq = np.concatenate([prompts[b // 3, :lens[b // 3]], ids[b, :end]])[None, :]
+        s, _, _ = oracle.score(m, seq, prompt_len=int(lens[b // 3]))
+        assert np.allclose(s[0, lens[b // 3] - 1:], lp[b, :end], atol=1e-5)
+    assert 0 < stopped < 9  # the case exercises both outcomes
+
+
 def test_temperature_enters_the_returned_logprob():
     cfg = small_cfg()
     m = oracle_model(inputs.make_weights(cfg, seed=1, std=0.3), max_positions=64)
