@@ -104,6 +104,33 @@ int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompt
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * mtmc_rollout_ragged: mtmc_rollout for prompts of different lengths, with an optional stop token
+ * (Inference Pipeline, "Macro Thinking": the policy's output ends with a terminal action or at the
+ * step limit).  Prompt p is prompts[p, :prompt_lens[p]]; the rest of its row is padding and never
+ * influences a result.  Sequence b = p * n_samples + s continues prompt p exactly as mtmc_rollout
+ * would continue it alone (same counters of the random generator, same results for any batch
+ * composition).  With stop_id >= 0 a sequence ends with the first sampled stop_id: that token and
+ * its log-probability are reported, every later slot of the row holds stop_id with log-probability
+ * 0, and out_lens[b] = number of tokens generated including the stop token (max_new if none).
+ * Finished sequences keep their slot in the batch: the call costs the same as without a stop token.
+ *
+ * prompts      device int32 [n_prompts, max_prompt_len], right-padded
+ * prompt_lens  device int32 [n_prompts], values in [1, max_prompt_len]; a value outside is clamped
+ *              and reported by mtmc_poll_errors
+ * stop_id      a token id, or negative for none
+ * out_lens     device int32 [n_prompts * n_samples]
+ * other arguments, errors and workspace rules as for mtmc_rollout, with
+ * mtmc_rollout_ragged_workspace_bytes(...); max_prompt_len + max_new <= max_positions.
+ */
+size_t mtmc_rollout_ragged_workspace_bytes(const mtmc_weights* w, int32_t n_prompts, int32_t max_prompt_len,
+                                           int32_t n_samples, int32_t max_new);
+int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                        int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples, int32_t max_new,
+                        float temperature, uint64_t seed, uint32_t seq_offset, int32_t stop_id,
+                        int32_t* out_ids, float* out_logprobs, int32_t* out_lens, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
  * mtmc_score: teacher-forced pass over seqs [n_seqs, seq_len].  For i in [0, seq_len-1):
  *     out_logprobs[n, i] = z_i[seqs[n, i+1]] - logsumexp_v z_i[v]     if i + 1 >= prompt_len
  *                        = 0                                           otherwise
@@ -154,7 +181,7 @@ int mtmc_score_actions(const mtmc_weights* w, const int32_t* states, int32_t n_s
 
 /*
  * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll saw a token
- * id outside [0, vocab) or an action length outside its range (the flag is cleared), MTMC_EHIP
+ * id outside [0, vocab) or an action / prompt length outside its range (the flag is cleared), MTMC_EHIP
  * on a runtime error, else MTMC_OK.
  */
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);

@@ -159,7 +159,7 @@ extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
     MTMC_HIP_CHECK(hipMemset(w->err_flag, 0, sizeof(int)));
     set_error(std::string(flag & 1 ? "a token id outside [0, vocab) was seen (and clamped) on the device" : "") +
               ((flag & 1) && (flag & 4) ? "; " : "") +
-              (flag & 4 ? "an action length outside [0, max_action_len] was seen (and clamped) on the device" : ""));
+              (flag & 4 ? "an action or prompt length outside its range was seen (and clamped) on the device" : ""));
     return MTMC_EDATA;
   }
   return MTMC_OK;
@@ -209,6 +209,50 @@ extern "C" int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32
   sa.max_new = max_new;
   sa.out_ids = out_ids;
   sa.out_logprobs = out_logprobs;
+  sa.prompt_lens = nullptr;
+  sa.stop_id = -1;
+  sa.out_lens = nullptr;
+  hipStream_t st = (hipStream_t)stream;
+  int rc = w->cfg.dtype == MTMC_F32 ? f32_rollout(w, p, prompts, sa, st)
+                                    : bf16_rollout(w, p, prompts, sa, st);
+  if (rc != MTMC_OK) return rc;
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}
+
+extern "C" size_t mtmc_rollout_ragged_workspace_bytes(const mtmc_weights* w, int32_t n_prompts,
+                                                      int32_t max_prompt_len, int32_t n_samples,
+                                                      int32_t max_new) {
+  if (check_rollout_shape(w, n_prompts, max_prompt_len, n_samples, max_new) != MTMC_OK) return 0;
+  return plan_rollout(w, n_prompts, max_prompt_len, n_samples, max_new, nullptr, true).total_bytes;
+}
+
+extern "C" int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                                   int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples,
+                                   int32_t max_new, float temperature, uint64_t seed, uint32_t seq_offset,
+                                   int32_t stop_id, int32_t* out_ids, float* out_logprobs, int32_t* out_lens,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_rollout_shape(w, n_prompts, max_prompt_len, n_samples, max_new)) return rc;
+  MTMC_REQUIRE(prompts && prompt_lens && out_ids && out_logprobs && out_lens && workspace, "NULL pointer argument");
+  MTMC_REQUIRE(temperature >= 0.f && std::isfinite(temperature), "temperature must be finite and >= 0");
+  MTMC_REQUIRE(stop_id < w->cfg.vocab, "stop_id must be a token id, or negative for none");
+  MTMC_REQUIRE(((uintptr_t)workspace & 255) == 0, "workspace must be 256-byte aligned");
+  RolloutPlan p = plan_rollout(w, n_prompts, max_prompt_len, n_samples, max_new, (char*)workspace, true);
+  if (workspace_bytes < p.total_bytes) {
+    set_error("workspace too small for mtmc_rollout_ragged: need " + std::to_string(p.total_bytes) + " bytes");
+    return MTMC_ENOMEM;
+  }
+  SampleArgs sa;
+  sa.greedy = temperature == 0.f ? 1 : 0;
+  sa.inv_temp = sa.greedy ? 1.0f : (float)(1.0 / (double)temperature);
+  sa.seed = seed;
+  sa.seq_offset = seq_offset;
+  sa.max_new = max_new;
+  sa.out_ids = out_ids;
+  sa.out_logprobs = out_logprobs;
+  sa.prompt_lens = prompt_lens;
+  sa.stop_id = stop_id < 0 ? -1 : stop_id;
+  sa.out_lens = out_lens;
   hipStream_t st = (hipStream_t)stream;
   int rc = w->cfg.dtype == MTMC_F32 ? f32_rollout(w, p, prompts, sa, st)
                                     : bf16_rollout(w, p, prompts, sa, st);

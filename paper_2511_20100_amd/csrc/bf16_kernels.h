@@ -15,6 +15,11 @@ struct SampleCtl {
   int max_new;
   int* out_ids;
   float* out_logprobs;
+  // stop token (done == NULL: none): a row whose flag is set reports stop_id with log-prob 0; a row that
+  // samples stop_id sets its flag and out_lens[row] = step + 1
+  int stop_id;
+  int* done;
+  int* out_lens;
 };
 
 struct LargeArgs {
@@ -68,6 +73,7 @@ struct AttnDecArgs {
   const float* cos;
   const float* sin;
   int Hq, Hkv, layer, pos_base;
+  const int* row_pos;    // per-sequence position base (sequences of different lengths), or NULL: pos_base
   const int* d_step;
   KvPool pool;
   int chunk_pages, n_chunks, m_tiles;

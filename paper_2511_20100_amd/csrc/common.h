@@ -34,13 +34,15 @@ void set_error(const std::string& msg);
   } while (0)
 
 // How the tokens of a launch map to sequences and positions.  Token t belongs to sequence
-// t / S, sits at position pos_base + (*d_step if d_step) + t % S, and uses row
-// (t / S) * row_stride of the page table.
+// t / S, sits at position base + (*d_step if d_step) + t % S with base = row_pos[t / S] if row_pos
+// is given (sequences of different lengths), else pos_base, and uses row (t / S) * row_stride of
+// the page table.
 struct TokMap {
   int S;
   int row_stride;
   int pos_base;
   const int* d_step;
+  const int* row_pos;
 };
 
 // Where the KV pages live.  Page `pg` of (layer l, which in {0 = K, 1 = V}, kv head g) starts at

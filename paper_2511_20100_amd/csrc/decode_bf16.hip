@@ -495,9 +495,20 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
     }
     const SampleCtl ctl = *ctlp;
     const int step = *d_step;
-    cur_ids[b] = bi;
-    ctl.out_ids[(size_t)b * ctl.max_new + step] = bi;
-    ctl.out_logprobs[(size_t)b * ctl.max_new + step] = bz - (lse.m + logf(lse.s));
+    int tok = bi;
+    float lp = bz - (lse.m + logf(lse.s));
+    if (ctl.done) {
+      if (ctl.done[b]) {
+        tok = ctl.stop_id;
+        lp = 0.f;
+      } else if (tok == ctl.stop_id) {
+        ctl.done[b] = 1;
+        ctl.out_lens[b] = step + 1;
+      }
+    }
+    cur_ids[b] = tok;
+    ctl.out_ids[(size_t)b * ctl.max_new + step] = tok;
+    ctl.out_logprobs[(size_t)b * ctl.max_new + step] = lp;
   }
 }
 void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,
@@ -621,6 +632,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   // ---- loads that do not depend on the position: step counter, this chunk's page ids, the raw
   // q/k/v row, and (speculatively) the first pair of pages of this wavefront
   const int step = *a.d_step;
+  const int base = a.row_pos ? a.row_pos[b] : a.pos_base;
   for (int i = tid; i < a.chunk_pages; i += AW * 64) s_table[i] = table[min(p_lo + i, pool.max_pages - 1)];
   const float* row = a.qkv + (size_t)b * (Hq + 2 * Hkv) * DHD;
   float qraw[2] = {0.f, 0.f};
@@ -637,7 +649,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
                   dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
   }
   // ---- position-dependent part
-  const int pos = a.pos_base + step;
+  const int pos = base + step;
   const int n_ctx_pages = pos / kPageTokens + 1;
   const int p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
   if (p_lo >= p_hi) return;

@@ -122,7 +122,7 @@ __device__ __forceinline__ Top2 top2_merge(Top2 a, Top2 b) {
 
 __device__ __forceinline__ int tok_seq(const TokMap& m, int t) { return t / m.S; }
 __device__ __forceinline__ int tok_pos(const TokMap& m, int t) {
-  return m.pos_base + (m.d_step ? *m.d_step : 0) + t % m.S;
+  return (m.row_pos ? m.row_pos[t / m.S] : m.pos_base) + (m.d_step ? *m.d_step : 0) + t % m.S;
 }
 
 }  // namespace mtmc

@@ -33,6 +33,9 @@ struct RolloutPlan {
   // sequences each); all sizes below are per group.
   int total_prompts;
   int n_prompts, prompt_len, n_samples, max_new, B;
+  int ragged;        // prompts of different lengths: prompt_len is the padded length, n_full is 0 (a row
+                     // has private pages for its whole length) and up to nf_max pages per prompt are shared
+  int nf_max;        // ragged: shared pages reserved per prompt (prompt_len / 16)
   int n_full;        // pages per prompt that are completely filled by the prompt (shared)
   int max_pages;     // page-table row length
   int shared_total;  // n_prompts * n_full
@@ -42,6 +45,9 @@ struct RolloutPlan {
   int* page_table;
   int* d_step;
   int* cur_ids;
+  int* row_pos;      // ragged: [B] position of a row's last prompt token
+  int* done;         // ragged: [B] stop flags
+  int* prompt_ids;   // ragged: [n_prompts, prompt_len] prompts with the padding cleared
   void* kv;
   // activations (Tmax rows unless noted)
   float* h;
@@ -144,6 +150,10 @@ struct SampleArgs {
   int max_new;
   int* out_ids;
   float* out_logprobs;
+  // prompts of different lengths / stop token (mtmc_rollout_ragged); prompt_lens == NULL otherwise
+  const int* prompt_lens;
+  int stop_id;
+  int* out_lens;
 };
 
 struct ScoreArgs {
@@ -155,7 +165,7 @@ struct ScoreArgs {
 };
 
 RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, int n_samples,
-                         int max_new, char* base);
+                         int max_new, char* base, bool ragged = false);
 ScorePlan plan_score(const mtmc_weights* w, int n_seqs, int S, char* base);
 ActionPlan plan_actions(const mtmc_weights* w, int n_states, int P, int K, int A, char* base);
 

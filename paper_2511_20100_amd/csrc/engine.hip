@@ -45,7 +45,7 @@ int build_aux(mtmc_weights* w, hipStream_t st) {
 }
 
 RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, int n_samples,
-                         int max_new, char* base) {
+                         int max_new, char* base, bool ragged) {
   const mtmc_config& c = w->cfg;
   const bool bf = c.dtype == MTMC_BF16;
   RolloutPlan p{};
@@ -54,9 +54,11 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
   p.n_prompts = n_prompts; p.prompt_len = prompt_len; p.n_samples = n_samples; p.max_new = max_new;
   p.B = n_prompts * n_samples;
   p.bt = (p.B + 15) / 16;
-  p.n_full = prompt_len / kPageTokens;
+  p.ragged = ragged ? 1 : 0;
+  p.nf_max = prompt_len / kPageTokens;
+  p.n_full = ragged ? 0 : p.nf_max;
   p.max_pages = (prompt_len + max_new + kPageTokens - 1) / kPageTokens;
-  p.shared_total = n_prompts * p.n_full;
+  p.shared_total = n_prompts * p.nf_max;
   p.n_pages = p.shared_total + p.B * (p.max_pages - p.n_full);
   p.chunk_prompts = std::max(1, std::min(n_prompts, kChunkTokens / prompt_len));
   p.Tmax = (std::max(p.chunk_prompts * prompt_len, p.B) + 127) / 128 * 128;
@@ -68,6 +70,11 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
   p.page_table = cv.take<int>((size_t)p.B * p.max_pages);
   p.d_step = cv.take<int>(64);
   p.cur_ids = cv.take<int>(p.B);
+  if (ragged) {
+    p.row_pos = cv.take<int>(p.B);
+    p.done = cv.take<int>(p.B);
+    p.prompt_ids = cv.take<int>((size_t)n_prompts * prompt_len);
+  }
   p.kv = cv.take<char>((size_t)c.n_layers * 2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim * act);
   p.h = cv.take<float>((size_t)p.Tmax * d);
   p.x = cv.take<char>((size_t)p.Tmax * d * act);
@@ -241,7 +248,15 @@ int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
   const int d = c.d_model, V = c.vocab;
   F32Acts A{p.h, (float*)p.x, p.qkv, (float*)p.o, p.gu, (float*)p.a};
   KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};
-  launch_build_page_table(p.page_table, p.B, p.max_pages, p.n_samples, p.n_full, p.shared_total, st);
+  const bool ragged = sa.prompt_lens != nullptr;
+  if (ragged) {
+    launch_ragged_setup(p.page_table, p.row_pos, p.done, sa.out_lens, p.prompt_ids, prompts, sa.prompt_lens,
+                        p.n_prompts, p.n_samples, p.prompt_len, p.max_pages, p.nf_max, p.shared_total, p.max_new,
+                        w->err_flag, st);
+    prompts = p.prompt_ids;
+  } else {
+    launch_build_page_table(p.page_table, p.B, p.max_pages, p.n_samples, p.n_full, p.shared_total, st);
+  }
   launch_set_int(p.d_step, 0, st);
   // ---- prefill: whole prompts, chunk by chunk; the prompt's pages are those of its first sample
   for (int p0 = 0; p0 < p.n_prompts; p0 += p.chunk_prompts) {
@@ -252,13 +267,20 @@ int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
     TokMap map{p.prompt_len, p.n_samples, 0, nullptr};
     f32::embed(A.h, prompts + (size_t)p0 * p.prompt_len, T, (const float*)w->embed, d, V, w->err_flag, st);
     f32_layers(w, A, T, map, chunk_pool, 1, st);
-    launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * d, A.h, np * p.n_samples, d, p.n_samples,
-                       p.prompt_len, p.prompt_len - 1, 0, st);
+    if (ragged)
+      launch_gather_last_rows(p.hB + (size_t)p0 * p.n_samples * d, A.h, d, np, p.n_samples, p.prompt_len,
+                              sa.prompt_lens + p0, st);
+    else
+      launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * d, A.h, np * p.n_samples, d, p.n_samples,
+                         p.prompt_len, p.prompt_len - 1, 0, st);
   }
-  if (p.prompt_len % kPageTokens != 0)
+  if (ragged)
+    launch_fork_tail_pages_ragged(pool, c.n_layers, p.B, p.n_samples, sa.prompt_lens, p.prompt_len, 4, st);
+  else if (p.prompt_len % kPageTokens != 0)
     launch_fork_tail_pages(pool, c.n_layers, p.B, p.n_samples, p.n_full, 4, st);
   // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i-1
-  TokMap dmap{1, 1, p.prompt_len - 1, p.d_step};
+  TokMap dmap{1, 1, p.prompt_len - 1, p.d_step, ragged ? p.row_pos : nullptr};
+  int* done = (ragged && sa.stop_id >= 0) ? p.done : nullptr;
   for (int i = 0; i < p.max_new; ++i) {
     if (i > 0) {
       f32::embed(p.hB, p.cur_ids, p.B, (const float*)w->embed, d, V, w->err_flag, st);
@@ -268,7 +290,7 @@ int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
     f32::rmsnorm((float*)p.xB, p.hB, w->final_norm, c.rms_eps, p.B, d, st);
     f32::gemm(p.logits, V, (const float*)p.xB, d, (const float*)w->lm_head, p.B, V, d, false, st);
     f32::sample(p.logits, p.B, V, sa.inv_temp, sa.greedy, sa.seed, sa.seq_offset, p.d_step, sa.max_new,
-                p.cur_ids, sa.out_ids, sa.out_logprobs, st);
+                p.cur_ids, sa.out_ids, sa.out_logprobs, sa.stop_id, done, sa.out_lens, st);
     launch_add_int(p.d_step, 1, st);
   }
   return MTMC_OK;

@@ -16,7 +16,7 @@ namespace mtmc {
 struct GraphCache {
   struct Entry {
     const void* workspace;
-    int B, prompt_len, n_samples, max_new;
+    int B, prompt_len, n_samples, max_new, ragged;
     hipGraphExec_t exec;
   };
   std::mutex mu;
@@ -347,7 +347,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     mark(MTMC_KERNEL_QKV);
     bf16::AttnDecArgs at{};
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
-    at.pos_base = pos_base; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
+    at.pos_base = pos_base; at.row_pos = p.ragged ? p.row_pos : nullptr; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
     at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples; at.part = p.attn_part; at.counters = p.attn_counters; at.o = o;
     mark(MTMC_KERNEL_ATTENTION);
     bf16::attention_dec(at, B, st);
@@ -404,7 +404,7 @@ int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, S
   }
   for (auto& e : gc.entries)
     if (e.workspace == (const void*)gp.page_table && e.B == gp.B && e.prompt_len == gp.prompt_len &&
-        e.n_samples == gp.n_samples && e.max_new == gp.max_new) {
+        e.n_samples == gp.n_samples && e.max_new == gp.max_new && e.ragged == gp.ragged) {
       *out = e.exec;
       return MTMC_OK;
     }
@@ -424,7 +424,7 @@ int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, S
     set_error(std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
     return MTMC_EHIP;
   }
-  gc.entries.push_back({(const void*)gp.page_table, gp.B, gp.prompt_len, gp.n_samples, gp.max_new, exec});
+  gc.entries.push_back({(const void*)gp.page_table, gp.B, gp.prompt_len, gp.n_samples, gp.max_new, gp.ragged, exec});
   *out = exec;
   return MTMC_OK;
 }
@@ -447,14 +447,25 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     gp.n_prompts = np_group;
     gp.B = np_group * p.n_samples;
     gp.bt = tiles16(gp.B);
-    gp.shared_total = np_group * p.n_full;
+    gp.shared_total = np_group * p.nf_max;
+    const bool ragged = sa.prompt_lens != nullptr;
+    const int* glens = ragged ? sa.prompt_lens + g0 : nullptr;
+    int* g_out_lens = ragged ? sa.out_lens + (size_t)g0 * p.n_samples : nullptr;
     const int* gprompts = prompts + (size_t)g0 * p.prompt_len;
     const size_t out_off = (size_t)g0 * p.n_samples * p.max_new;
     bf16::SampleCtl ctl{sa.greedy, sa.inv_temp, (uint32_t)(sa.seed & 0xffffffffu), (uint32_t)(sa.seed >> 32),
                         sa.seq_offset + (uint32_t)(g0 * p.n_samples), sa.max_new, sa.out_ids + out_off,
-                        sa.out_logprobs + out_off};
+                        sa.out_logprobs + out_off, sa.stop_id, (ragged && sa.stop_id >= 0) ? p.done : nullptr,
+                        g_out_lens};
     bf16::set_sample_ctl((bf16::SampleCtl*)p.ctl, ctl, st);
-    launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
+    if (ragged) {
+      launch_ragged_setup(p.page_table, p.row_pos, p.done, g_out_lens, p.prompt_ids, gprompts, glens, np_group,
+                          p.n_samples, p.prompt_len, p.max_pages, p.nf_max, gp.shared_total, p.max_new, w->err_flag,
+                          st);
+      gprompts = p.prompt_ids;
+    } else {
+      launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
+    }
     launch_set_int(p.d_step, 0, st);
     launch_fill_u32((uint32_t*)p.attn_counters, 0u, (size_t)p.B * D.Hkv, st);
     // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
@@ -470,10 +481,16 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
       prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, p.prompt_len,
                      map, chunk_pool, 1, st);
-      launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, np * p.n_samples, D.d, p.n_samples,
-                         p.prompt_len, p.prompt_len - 1, 0, st);
+      if (ragged)
+        launch_gather_last_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, D.d, np, p.n_samples, p.prompt_len,
+                                glens + p0, st);
+      else
+        launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, np * p.n_samples, D.d, p.n_samples,
+                           p.prompt_len, p.prompt_len - 1, 0, st);
     }
-    if (p.prompt_len % kPageTokens != 0)
+    if (ragged)
+      launch_fork_tail_pages_ragged(pool, c.n_layers, gp.B, p.n_samples, glens, p.prompt_len, 2, st);
+    else if (p.prompt_len % kPageTokens != 0)
       launch_fork_tail_pages(pool, c.n_layers, gp.B, p.n_samples, p.n_full, 2, st);
     // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i - 1
     bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, st);

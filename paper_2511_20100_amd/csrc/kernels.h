@@ -22,6 +22,21 @@ void launch_gather_rows(float* dst, const float* src, int rows, int d, int n_rep
 void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, int page_idx,
                             int elem_bytes, hipStream_t st);
 
+// Rollout of prompts of different lengths (lens [n_prompts], clamped to [1, Lmax]; a value outside
+// raises bit 4 of *err_flag).  Row b = p n_samples + s: table entry j is shared page p nf_max + j for
+// j < lens[p] / 16, else private page shared_total + b max_pages + j; row_pos[b] = lens[p] - 1;
+// done[b] = 0; out_lens[b] = max_new.  prompt_ids [n_prompts, Lmax] = prompts with the padding set to 0.
+void launch_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, const int* prompts,
+                         const int* lens, int n_prompts, int n_samples, int Lmax, int max_pages, int nf_max,
+                         int shared_total, int max_new, int* err_flag, hipStream_t st);
+// For every row b with b % n_samples != 0 whose prompt length is not a multiple of the page size: the page
+// that holds the prompt's last tokens := copy of that page of row b - b % n_samples, in every (layer, K/V).
+void launch_fork_tail_pages_ragged(KvPool pool, int n_layers, int rows, int n_samples, const int* lens, int Lmax,
+                                   int elem_bytes, hipStream_t st);
+// dst[p n_samples + s, :] = src[p Lmax + lens[p] - 1, :] for p < n_prompts, s < n_samples.
+void launch_gather_last_rows(float* dst, const float* src, int d, int n_prompts, int n_samples, int Lmax,
+                             const int* lens, hipStream_t st);
+
 // Action-level scoring.  vseq [n_states K, A + 1]: row n K + k = last token of state n, then the
 // tokens of candidate k, then zeros; prefix [n_states, P - 1]: the states without their last token.
 // An action_len outside [0, A] raises bit 4 of *err_flag and is clamped.
@@ -50,9 +65,11 @@ void attention(float* o, const float* qkv, int T, int Hq, int Hkv, int hd, TokMa
 void swiglu(float* a, const float* gu, int T, int F, hipStream_t st);  // gu [T, 2F] -> a [T, F]
 // Gumbel-max sampling from materialised logits [B, V] at step *d_step; writes out_ids[b, step],
 // out_logprobs[b, step] and cur_ids[b].
+// With done != NULL (stop token in use): a row whose done flag is set reports stop_id with log-prob 0; a row
+// that samples stop_id sets its flag and out_lens[b] = step + 1.
 void sample(const float* logits, int B, int V, float inv_temp, int greedy, uint64_t seed,
             uint32_t seq_offset, const int* d_step, int max_new, int* cur_ids, int* out_ids,
-            float* out_logprobs, hipStream_t st);
+            float* out_logprobs, int stop_id, int* done, int* out_lens, hipStream_t st);
 // Teacher-forced scoring from materialised logits [R, V].  Row r is position
 // i = first + (row0 + r) % n_scored of sequence n = seq0 + (row0 + r) / n_scored; its target is
 // seqs[n, i + 1] and its output slot [n, i] of the [*, S - 1] outputs.

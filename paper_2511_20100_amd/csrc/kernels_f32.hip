@@ -81,6 +81,67 @@ void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, 
 }
 
 // =====================================================================================
+// rollout of prompts of different lengths
+// =====================================================================================
+__device__ __forceinline__ int clamp_len(int len, int Lmax) { return min(max(len, 1), Lmax); }
+
+__global__ void k_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids,
+                               const int* prompts, const int* lens, int n_samples, int Lmax, int max_pages,
+                               int nf_max, int shared_total, int max_new, int* err_flag) {
+  const int b = blockIdx.x, p = b / n_samples;
+  const int raw = lens[p], len = clamp_len(raw, Lmax);
+  if (threadIdx.x == 0) {
+    if (raw != len) atomicOr(err_flag, 4);
+    row_pos[b] = len - 1;
+    done[b] = 0;
+    out_lens[b] = max_new;
+  }
+  const int n_full = len / kPageTokens;
+  for (int j = threadIdx.x; j < max_pages; j += blockDim.x)
+    table[(size_t)b * max_pages + j] = (j < n_full) ? p * nf_max + j : shared_total + b * max_pages + j;
+  if (b % n_samples == 0)
+    for (int j = threadIdx.x; j < Lmax; j += blockDim.x)
+      prompt_ids[(size_t)p * Lmax + j] = (j < len) ? prompts[(size_t)p * Lmax + j] : 0;
+}
+void launch_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, const int* prompts,
+                         const int* lens, int n_prompts, int n_samples, int Lmax, int max_pages, int nf_max,
+                         int shared_total, int max_new, int* err_flag, hipStream_t st) {
+  k_ragged_setup<<<n_prompts * n_samples, 256, 0, st>>>(table, row_pos, done, out_lens, prompt_ids, prompts, lens,
+                                                        n_samples, Lmax, max_pages, nf_max, shared_total, max_new,
+                                                        err_flag);
+}
+
+__global__ void k_fork_tail_pages_ragged(KvPool pool, int n_samples, const int* lens, int Lmax, int words_per_page) {
+  const int b = blockIdx.x;
+  if (b % n_samples == 0) return;
+  const int len = clamp_len(lens[b / n_samples], Lmax);
+  if (len % kPageTokens == 0) return;
+  const int page_idx = len / kPageTokens;
+  const int lw = blockIdx.y;  // layer * 2 + which
+  const int src = pool.page_table[(size_t)(b - b % n_samples) * pool.max_pages + page_idx];
+  const int dst = pool.page_table[(size_t)b * pool.max_pages + page_idx];
+  const uint32_t* s = (const uint32_t*)pool.base + ((size_t)lw * pool.n_pages + src) * words_per_page;
+  uint32_t* d = (uint32_t*)pool.base + ((size_t)lw * pool.n_pages + dst) * words_per_page;
+  for (int i = threadIdx.x; i < words_per_page; i += blockDim.x) d[i] = s[i];
+}
+void launch_fork_tail_pages_ragged(KvPool pool, int n_layers, int rows, int n_samples, const int* lens, int Lmax,
+                                   int elem_bytes, hipStream_t st) {
+  const int words = pool.n_kv_heads * kPageTokens * pool.head_dim * elem_bytes / 4;
+  k_fork_tail_pages_ragged<<<dim3(rows, n_layers * 2), 256, 0, st>>>(pool, n_samples, lens, Lmax, words);
+}
+
+__global__ void k_gather_last_rows(float* dst, const float* src, int d, int n_samples, int Lmax, const int* lens) {
+  const int r = blockIdx.x, p = r / n_samples;
+  const size_t s = (size_t)p * Lmax + clamp_len(lens[p], Lmax) - 1;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(size_t)r * d + c] = src[s * d + c];
+}
+void launch_gather_last_rows(float* dst, const float* src, int d, int n_prompts, int n_samples, int Lmax,
+                             const int* lens, hipStream_t st) {
+  if (n_prompts == 0) return;
+  k_gather_last_rows<<<n_prompts * n_samples, 256, 0, st>>>(dst, src, d, n_samples, Lmax, lens);
+}
+
+// =====================================================================================
 // action-level scoring: inputs of the two passes, and the sums / softmax over the candidates
 // =====================================================================================
 // Row b = n K + k of vseq is [last state token, action tokens ..., 0 padding]; prefix row n is the
@@ -363,7 +424,8 @@ void attention(float* o, const float* qkv, int T, int Hq, int Hkv, int hd, TokMa
 __global__ __launch_bounds__(256) void k_sample(const float* logits, int V, float inv_temp,
                                                 int greedy, uint32_t key0, uint32_t key1,
                                                 uint32_t seq_offset, const int* d_step, int max_new,
-                                                int* cur_ids, int* out_ids, float* out_logprobs) {
+                                                int* cur_ids, int* out_ids, float* out_logprobs, int stop_id,
+                                                int* done, int* out_lens) {
   __shared__ Lse s_lse[4];
   __shared__ Best s_best[4];
   const int b = blockIdx.x;
@@ -398,17 +460,28 @@ __global__ __launch_bounds__(256) void k_sample(const float* logits, int V, floa
   if (threadIdx.x == 0) {
     for (int i = 1; i < 4; ++i) { lse = lse_merge(lse, s_lse[i]); best = best_merge(best, s_best[i]); }
     const float zt = greedy ? z[best.idx] : z[best.idx] * inv_temp;
-    cur_ids[b] = best.idx;
-    out_ids[(size_t)b * max_new + step] = best.idx;
-    out_logprobs[(size_t)b * max_new + step] = zt - (lse.m + logf(lse.s));
+    int tok = best.idx;
+    float lp = zt - (lse.m + logf(lse.s));
+    if (done) {
+      if (done[b]) {
+        tok = stop_id;
+        lp = 0.f;
+      } else if (tok == stop_id) {
+        done[b] = 1;
+        out_lens[b] = step + 1;
+      }
+    }
+    cur_ids[b] = tok;
+    out_ids[(size_t)b * max_new + step] = tok;
+    out_logprobs[(size_t)b * max_new + step] = lp;
   }
 }
 void sample(const float* logits, int B, int V, float inv_temp, int greedy, uint64_t seed,
             uint32_t seq_offset, const int* d_step, int max_new, int* cur_ids, int* out_ids,
-            float* out_logprobs, hipStream_t st) {
+            float* out_logprobs, int stop_id, int* done, int* out_lens, hipStream_t st) {
   k_sample<<<B, 256, 0, st>>>(logits, V, inv_temp, greedy, (uint32_t)(seed & 0xffffffffu),
                               (uint32_t)(seed >> 32), seq_offset, d_step, max_new, cur_ids, out_ids,
-                              out_logprobs);
+                              out_logprobs, stop_id, done, out_lens);
 }
 
 __global__ __launch_bounds__(256) void k_score_rows(const float* logits, int V, const int* seqs,

@@ -51,6 +51,10 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_rollout_workspace_bytes.restype = sz
     lib.mtmc_rollout.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, u32, vp, vp, vp, sz, vp]
     lib.mtmc_rollout.restype = ctypes.c_int
+    lib.mtmc_rollout_ragged_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.mtmc_rollout_ragged_workspace_bytes.restype = sz
+    lib.mtmc_rollout_ragged.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, u64, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.mtmc_rollout_ragged.restype = ctypes.c_int
     lib.mtmc_score_workspace_bytes.argtypes = [vp, i32, i32]
     lib.mtmc_score_workspace_bytes.restype = sz
     lib.mtmc_score.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -79,7 +83,8 @@ _lib = _load()
 EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mtmc_rollout_workspace_bytes",
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
-           "mtmc_score_actions_workspace_bytes", "mtmc_score_actions")
+           "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
+           "mtmc_rollout_ragged")
 
 
 def mtmc_last_error() -> str:
@@ -149,6 +154,36 @@ def mtmc_rollout(handle: int, prompts: torch.Tensor, n_samples: int, max_new: in
                              float(temperature), int(seed), int(seq_offset), out_ids.data_ptr(),
                              out_logprobs.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out_ids, out_logprobs
+
+
+def mtmc_rollout_ragged_workspace_bytes(handle: int, n_prompts: int, max_prompt_len: int, n_samples: int,
+                                        max_new: int) -> int:
+    n = int(_lib.mtmc_rollout_ragged_workspace_bytes(handle, n_prompts, max_prompt_len, n_samples, max_new))
+    if n == 0:
+        raise MtmcError(MTMC_EINVAL, mtmc_last_error())
+    return n
+
+
+def mtmc_rollout_ragged(handle: int, prompts: torch.Tensor, prompt_lens: torch.Tensor, n_samples: int, max_new: int,
+                        temperature: float, seed: int, *, stop_id: int = -1, seq_offset: int = 0,
+                        workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """prompts int32 CUDA [n_prompts, max_prompt_len] (right-padded), prompt_lens int32 CUDA [n_prompts].
+    Returns (ids [B, max_new] int32, logprobs [B, max_new] float32, lens [B] int32), B = n_prompts * n_samples."""
+    for t in (prompts, prompt_lens):
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+    n_prompts, Lmax = prompts.shape
+    assert tuple(prompt_lens.shape) == (n_prompts,)
+    B = n_prompts * n_samples
+    if workspace is None:
+        workspace = torch.empty(mtmc_rollout_ragged_workspace_bytes(handle, n_prompts, Lmax, n_samples, max_new),
+                                dtype=torch.uint8, device=prompts.device)
+    ids = torch.empty((B, max_new), dtype=torch.int32, device=prompts.device)
+    lp = torch.empty((B, max_new), dtype=torch.float32, device=prompts.device)
+    lens = torch.empty((B,), dtype=torch.int32, device=prompts.device)
+    _check(_lib.mtmc_rollout_ragged(handle, prompts.data_ptr(), prompt_lens.data_ptr(), n_prompts, Lmax, n_samples,
+                                    max_new, temperature, seed, seq_offset, stop_id, ids.data_ptr(), lp.data_ptr(),
+                                    lens.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return ids, lp, lens
 
 
 def mtmc_score_workspace_bytes(handle: int, n_seqs: int, seq_len: int) -> int:

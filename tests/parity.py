@@ -82,3 +82,34 @@ def check_actions(handle, w, states, actions, lens, *, normalize=False, max_posi
     assert np.allclose(np.exp(pol.astype(np.float64)).sum(axis=1), 1.0, atol=1e-5)
     return {"token": tok, "action": act, "policy": pol, "max_token_err": e_tok, "max_action_err": float(e_act.max()),
             "max_policy_err": float(e_pol.max())}
+
+
+def check_ragged_by_replay(handle, w, prompts, lens, n_samples, max_new, temperature, seed, *, stop_id=-1,
+                           max_positions, tol=LOGP_TOL_BF16, label=""):
+    """mtmc_rollout_ragged, verified row by row: the oracle teacher-forces prompt[:len] + the tokens the GPU
+    generated up to the row's end and redoes every sampling decision (ids above the margin gate, log-probs
+    within tol); the row ends at the first stop token, and every slot after it holds stop_id / 0."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    ids, lp, n = mtmc.mtmc_rollout_ragged(handle, torch.from_numpy(prompts).cuda(), torch.from_numpy(lens).cuda(),
+                                          n_samples, max_new, temperature, seed, stop_id=stop_id)
+    mtmc.mtmc_poll_errors(handle)
+    ids, lp, n = ids.cpu().numpy(), lp.cpu().numpy(), n.cpu().numpy()
+    model = oracle_model(w, max_positions)
+    gated = total = 0
+    worst = 0.0
+    for b in range(ids.shape[0]):
+        p = b // n_samples
+        hits = np.nonzero(ids[b] == stop_id)[0] if stop_id >= 0 else np.array([], dtype=int)
+        end = int(hits[0]) + 1 if hits.size else max_new
+        assert n[b] == end, f"{label} row {b}: reported length {n[b]}, first stop token ends it at {end}"
+        assert np.all(ids[b, end:] == stop_id) and np.all(lp[b, end:] == 0.0), f"{label} row {b}: slots after the end"
+        tok, ref_lp, margin = oracle.replay(model, prompts[p, :lens[p]], ids[b, :end], temperature, seed, b)
+        gate = margin > MARGIN_GATE
+        bad = np.nonzero(gate & (tok != ids[b, :end]))[0]
+        assert bad.size == 0, f"{label} row {b}: sampled id differs from the oracle at steps {bad[:8]}"
+        err = float(np.abs(ref_lp - lp[b, :end]).max())
+        worst = max(worst, err)
+        assert err <= tol, f"{label} row {b}: log-prob error {err}"
+        gated += int(gate.sum()); total += gate.size
+    return {"ids": ids, "logprobs": lp, "lens": n, "compared": gated, "steps": total, "max_logp_err": worst}

@@ -16,6 +16,8 @@ from paper_2511_20100_amd import inputs
 CFG = inputs.POLICY_1P5B
 N_PROMPTS, PROMPT_LEN, N_SAMPLES, MAX_NEW = 8, 512, 8, 1024
 N_ACTIONS, MAX_ACTION_LEN = 8, 16
+RAGGED_LENS = np.array([512, 100, 333, 16, 497, 250, 1, 448], dtype=np.int32)
+RAGGED_NEW = 48
 
 
 @pytest.fixture(scope="module")
@@ -40,7 +42,16 @@ def run():
     mtmc.mtmc_poll_errors(handle)
     acts = dict(actions=actions, lens=lens, tok=a_tok.cpu().numpy(), act=a_act.cpu().numpy(), pol=a_pol.cpu().numpy(),
                 score=a_score.cpu().numpy()[:, PROMPT_LEN - 1:].reshape(N_PROMPTS, N_ACTIONS, MAX_ACTION_LEN))
-    out = dict(w=w, prompts=prompts, acts=acts, ids=ids.cpu().numpy(), lp=lp.cpu().numpy(), ids2=ids2.cpu().numpy(),
+    # prompts of different lengths with a stop token, at the same batch shape (48 new tokens)
+    r_lens = RAGGED_LENS.copy()
+    free = mtmc.mtmc_rollout_ragged(handle, dprompts, torch.from_numpy(r_lens).cuda(), N_SAMPLES, RAGGED_NEW, 1.0, 1)
+    stop = int(free[0][13, 9])
+    stopped = mtmc.mtmc_rollout_ragged(handle, dprompts, torch.from_numpy(r_lens).cuda(), N_SAMPLES, RAGGED_NEW, 1.0, 1,
+                                       stop_id=stop)
+    mtmc.mtmc_poll_errors(handle)
+    ragged = dict(lens=r_lens, stop=stop, free=[t.cpu().numpy() for t in free],
+                  stopped=[t.cpu().numpy() for t in stopped])
+    out = dict(w=w, prompts=prompts, acts=acts, ragged=ragged, ids=ids.cpu().numpy(), lp=lp.cpu().numpy(), ids2=ids2.cpu().numpy(),
                lp2=lp2.cpu().numpy(), score=score.cpu().numpy(), top1=top1.cpu().numpy(), margin=margin.cpu().numpy())
     mtmc.mtmc_weights_destroy(handle)
     return out
@@ -123,3 +134,29 @@ def test_sampled_actions_against_the_oracle(run):
     print("1.5 B actions: token err", e_tok, "action err", e_act.max())
     assert e_tok <= LOGP_TOL_BF16
     assert np.all(e_act <= LOGP_TOL_BF16 * a["lens"][n, ks])
+
+
+def test_ragged_rollout_at_full_batch(run):
+    """Prompts of eight different lengths in the benchmark's batch shape.  Properties at any size: a stopped
+    run equals the free run up to each row's first stop token and is stop / 0 after it; one row is replayed
+    on the oracle from its own (short) prompt."""
+    r = run["ragged"]
+    f_ids, f_lp, f_n = r["free"]
+    s_ids, s_lp, s_n = r["stopped"]
+    assert np.all(f_n == RAGGED_NEW) and s_n[13] == 10
+    for b in range(N_PROMPTS * N_SAMPLES):
+        hits = np.nonzero(f_ids[b] == r["stop"])[0]
+        end = int(hits[0]) + 1 if hits.size else RAGGED_NEW
+        assert s_n[b] == end
+        assert np.array_equal(s_ids[b, :end], f_ids[b, :end]) and np.array_equal(s_lp[b, :end], f_lp[b, :end])
+        assert np.all(s_ids[b, end:] == r["stop"]) and np.all(s_lp[b, end:] == 0.0)
+    # the full-length prompt (row 0..7) is the uniform rollout's
+    assert np.array_equal(f_ids[:N_SAMPLES], run["ids"][:N_SAMPLES, :RAGGED_NEW])
+    model = oracle_model(run["w"], PROMPT_LEN + MAX_NEW)
+    b = 13  # second sample of the 100-token prompt
+    p = b // N_SAMPLES
+    tok, ref_lp, margin = oracle.replay(model, run["prompts"][p, :r["lens"][p]], f_ids[b], 1.0, 1, b)
+    gate = margin > MARGIN_GATE
+    err = np.abs(ref_lp - f_lp[b]).max()
+    print(f"ragged row {b}: {int(gate.sum())}/{gate.size} decisions compared, log-prob err max {err:.2e}")
+    assert np.array_equal(tok[gate], f_ids[b][gate]) and err <= LOGP_TOL_BF16
