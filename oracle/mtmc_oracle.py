@@ -15,6 +15,7 @@ product of the per-token conditionals (Eq. 2).  Two operations follow from that:
                  logarithms of the factors of Eq. 2.
 * ``action_policy`` -- the sums of those terms over each candidate action of a state and
                  their softmax over the candidate set (the sampling probability of an action).
+* ``ppo_clip_loss`` -- the clipped surrogate of the PPO update over scored samples (value only).
 * ``rollout_ragged`` -- the same for prompts of different lengths, ending at a stop token.
 * ``rollout`` -- sampling a token sequence from the same conditionals, one token at a
                  time (Inference Pipeline, "Macro Thinking": the policy outputs an action),
@@ -324,6 +325,30 @@ def action_policy(model: Model, states: np.ndarray, actions: np.ndarray, action_
     m = action_logp.max(axis=1, keepdims=True)
     lse = m + np.log(np.exp(action_logp - m).sum(axis=1, keepdims=True))
     return token_logp, action_logp.astype(np.float32), (action_logp - lse).astype(np.float32)
+
+
+def ppo_clip_loss(new_logp: np.ndarray, old_logp: np.ndarray, advantages: np.ndarray, clip_eps: float,
+                  mask: Optional[np.ndarray] = None):
+    """The clipped surrogate of the standard PPO algorithm that the policy is trained with (Method,
+    "Training Methodology"), over the n samples whose mask is non-zero (all when mask is None):
+      r_i  = exp(new_logp_i - old_logp_i)
+      loss = - mean_i min(r_i A_i, clip(r_i, 1 - eps, 1 + eps) A_i)
+    plus two diagnostics: the fraction of samples with |r_i - 1| > eps and the mean of
+    old_logp_i - new_logp_i (a first-order estimate of the KL divergence from the old policy).
+    The paper gives no value of eps (its appendix is not available): it is an argument.
+    Everything in float64.  Returns (loss, clip_fraction, approx_kl, count); zeros when nothing is selected."""
+    new_logp = np.asarray(new_logp, dtype=np.float64).ravel()
+    old_logp = np.asarray(old_logp, dtype=np.float64).ravel()
+    adv = np.asarray(advantages, dtype=np.float64).ravel()
+    keep = np.ones(new_logp.shape, dtype=bool) if mask is None else (np.asarray(mask).ravel() != 0)
+    n = int(keep.sum())
+    if n == 0:
+        return 0.0, 0.0, 0.0, 0
+    r = np.exp(new_logp[keep] - old_logp[keep])
+    a = adv[keep]
+    surrogate = np.minimum(r * a, np.clip(r, 1.0 - clip_eps, 1.0 + clip_eps) * a)
+    return (float(-surrogate.mean()), float((np.abs(r - 1.0) > clip_eps).mean()),
+            float((old_logp[keep] - new_logp[keep]).mean()), n)
 
 
 # --------------------------------------------------------------------------------------

@@ -147,3 +147,43 @@ def test_attention_one_hot_limit_picks_the_matching_key():
     q = np.zeros((1, 1, hd)); q[0, 0, 2] = 1.0  # selects key 2
     out = oracle.causal_gqa_attention(q, k, v)
     assert np.allclose(out[0, 0], v[2, 0], atol=1e-9)
+
+
+# ---------------------------------------------------------------- PPO clipped surrogate
+def test_ppo_surrogate_closed_forms():
+    eps = 0.2
+    one = lambda r, a: oracle.ppo_clip_loss([math.log(r)], [0.0], [a], eps)[0]
+    assert abs(one(1.5, 2.0) + (1 + eps) * 2.0) < 1e-12     # gain capped at 1 + eps
+    assert abs(one(0.5, 2.0) + 0.5 * 2.0) < 1e-12           # a lower ratio is not clipped when A > 0
+    assert abs(one(0.5, -2.0) - (1 - eps) * 2.0) < 1e-12    # penalty capped at 1 - eps
+    assert abs(one(1.5, -2.0) - 1.5 * 2.0) < 1e-12          # a higher ratio is not clipped when A < 0
+    assert abs(one(1.1, 3.0) + 1.1 * 3.0) < 1e-12           # inside the band: plain importance weighting
+    # unchanged policy: minus the mean advantage, no clipping, zero divergence
+    lp = np.linspace(-5, -1, 7)
+    adv = np.array([1.0, -2.0, 0.5, 3.0, -1.0, 0.0, 2.5])
+    loss, frac, kl, n = oracle.ppo_clip_loss(lp, lp, adv, eps)
+    assert abs(loss + adv.mean()) < 1e-12 and frac == 0.0 and kl == 0.0 and n == 7
+
+
+def test_ppo_surrogate_against_a_scalar_loop_and_its_bound():
+    rng = np.random.default_rng(5)
+    n, eps = 200, 0.1
+    new, old, adv = rng.normal(-3, 1, n), rng.normal(-3, 1, n), rng.normal(0, 1, n)
+    mask = rng.integers(0, 2, n)
+    tot = cnt = clipped = 0
+    kl = 0.0
+    for i in range(n):
+        if not mask[i]:
+            continue
+        r = math.exp(new[i] - old[i])
+        rc = min(max(r, 1 - eps), 1 + eps)
+        tot += min(r * adv[i], rc * adv[i]); cnt += 1; clipped += abs(r - 1) > eps; kl += old[i] - new[i]
+    loss, frac, akl, m = oracle.ppo_clip_loss(new, old, adv, eps, mask)
+    assert m == cnt and abs(loss + tot / cnt) < 1e-12 and abs(frac - clipped / cnt) < 1e-12 and abs(akl - kl / cnt) < 1e-12
+    # the clipped objective never exceeds the unclipped one
+    keep = mask != 0
+    assert -loss <= (np.exp(new - old) * adv)[keep].mean() + 1e-12
+    # masked-out samples do not matter; an empty selection gives zeros
+    adv2 = adv.copy(); adv2[~keep] = 1e9
+    assert oracle.ppo_clip_loss(new, old, adv2, eps, mask) == (loss, frac, akl, m)
+    assert oracle.ppo_clip_loss(new, old, adv, eps, np.zeros(n)) == (0.0, 0.0, 0.0, 0)
