@@ -180,6 +180,28 @@ int mtmc_score_actions(const mtmc_weights* w, const int32_t* states, int32_t n_s
                        size_t workspace_bytes, void* stream);
 
 /*
+ * mtmc_ppo_clip_loss: the clipped surrogate of the standard PPO update that the policy is trained with
+ * (Method, "Training Methodology"), over the samples i < n whose mask is non-zero (all if mask is NULL):
+ *     r_i  = exp(new_logprobs[i] - old_logprobs[i])
+ *     loss = - mean_i min(r_i A_i, clip(r_i, 1 - clip_eps, 1 + clip_eps) A_i),   A_i = advantages[i]
+ * The log-probabilities are what mtmc_score / mtmc_score_actions return (per token or per action) under
+ * the current and the behaviour policy.  Value only: no gradient is formed.  clip_eps is the caller's
+ * (the paper does not state it).
+ *     out[0] = loss   out[1] = fraction of samples with |r_i - 1| > clip_eps
+ *     out[2] = mean of old - new log-probability   out[3] = number of samples selected
+ * All zero when no sample is selected.  Sums are formed in double in a fixed order (results do not
+ * depend on scheduling).
+ *
+ * new_logprobs, old_logprobs, advantages   device fp32 [n];  mask   device int32 [n] or NULL
+ * out          device double [4]
+ * workspace    device, >= mtmc_ppo_workspace_bytes() bytes, 256-byte aligned
+ */
+size_t mtmc_ppo_workspace_bytes(void);
+int mtmc_ppo_clip_loss(const float* new_logprobs, const float* old_logprobs, const float* advantages,
+                       const int32_t* mask, int64_t n, float clip_eps, double* out, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
  * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll saw a token
  * id outside [0, vocab) or an action / prompt length outside its range (the flag is cleared), MTMC_EHIP
  * on a runtime error, else MTMC_OK.

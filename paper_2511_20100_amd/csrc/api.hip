@@ -356,3 +356,25 @@ extern "C" int mtmc_score_actions(const mtmc_weights* w, const int32_t* states, 
   MTMC_HIP_CHECK(hipGetLastError());
   return MTMC_OK;
 }
+
+// --------------------------------------------------------------------------------------
+// PPO clipped surrogate
+// --------------------------------------------------------------------------------------
+extern "C" size_t mtmc_ppo_workspace_bytes(void) { return ppo_workspace_bytes(); }
+
+extern "C" int mtmc_ppo_clip_loss(const float* new_logprobs, const float* old_logprobs, const float* advantages,
+                                  const int32_t* mask, int64_t n, float clip_eps, double* out, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  MTMC_REQUIRE(new_logprobs && old_logprobs && advantages && out && workspace, "NULL pointer argument");
+  MTMC_REQUIRE(n > 0, "n must be positive");
+  MTMC_REQUIRE(clip_eps >= 0.f && clip_eps < 1.f && std::isfinite(clip_eps), "clip_eps must lie in [0, 1)");
+  MTMC_REQUIRE(((uintptr_t)workspace & 255) == 0, "workspace must be 256-byte aligned");
+  if (workspace_bytes < ppo_workspace_bytes()) {
+    set_error("workspace too small for mtmc_ppo_clip_loss: need " + std::to_string(ppo_workspace_bytes()) + " bytes");
+    return MTMC_ENOMEM;
+  }
+  launch_ppo_clip_loss(new_logprobs, old_logprobs, advantages, mask, (long long)n, (double)clip_eps, out, workspace,
+                       (hipStream_t)stream);
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}

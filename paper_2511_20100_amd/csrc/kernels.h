@@ -48,6 +48,12 @@ void launch_build_action_seqs(int* vseq, int* prefix, const int* states, const i
 void launch_action_reduce(float* token_lp, const int* action_len, int n_states, int K, int A, int normalize,
                           float* out_action, float* out_policy, hipStream_t st);
 
+// Clipped PPO surrogate over n samples (mask may be NULL); out = {loss, clip fraction, approx KL, count} as
+// doubles; workspace of ppo_workspace_bytes() bytes holds the per-workgroup partial sums.
+size_t ppo_workspace_bytes();
+void launch_ppo_clip_loss(const float* new_logp, const float* old_logp, const float* adv, const int* mask,
+                          long long n, double eps, double* out, void* workspace, hipStream_t st);
+
 // ---------------------------------------------------------------- fp32 path
 namespace f32 {
 void embed(float* h, const int* ids, int T, const float* E, int d, int vocab, int* err_flag,

@@ -244,3 +244,15 @@ def make_actions(n_states: int, n_actions: int, max_action_len: int, vocab: int,
         lens[:, -1] = 0
     lens[:, 0] = max_action_len
     return actions, lens
+
+
+def make_ppo_samples(n: int, seed: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """Stand-ins for the scored samples of a policy update: old log-probs N(-12, 0.5) (the level of the
+    synthetic policies), new = old + N(0, 0.15), advantages N(0, 1), and a mask that keeps ~80 %.
+    Returns (new, old, advantages) as float32 and mask as int32."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0x70706f])))
+    old = rng.normal(-12.0, 0.5, n).astype(np.float32)
+    new = (old + rng.normal(0.0, 0.15, n)).astype(np.float32)
+    adv = rng.normal(0.0, 1.0, n).astype(np.float32)
+    mask = (rng.random(n) < 0.8).astype(np.int32)
+    return new, old, adv, mask

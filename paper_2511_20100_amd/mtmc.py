@@ -63,6 +63,10 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_score_actions_workspace_bytes.restype = sz
     lib.mtmc_score_actions.argtypes = [vp, vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.mtmc_score_actions.restype = ctypes.c_int
+    lib.mtmc_ppo_workspace_bytes.argtypes = []
+    lib.mtmc_ppo_workspace_bytes.restype = sz
+    lib.mtmc_ppo_clip_loss.argtypes = [vp, vp, vp, vp, ctypes.c_int64, f32, vp, vp, sz, vp]
+    lib.mtmc_ppo_clip_loss.restype = ctypes.c_int
     lib.mtmc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.mtmc_set_option.restype = ctypes.c_int
     lib.mtmc_kernel_timer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -84,7 +88,7 @@ EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mt
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
            "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
-           "mtmc_rollout_ragged")
+           "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss")
 
 
 def mtmc_last_error() -> str:
@@ -241,6 +245,23 @@ def mtmc_score_actions(handle: int, states: torch.Tensor, actions: torch.Tensor,
                                    K, A, 1 if normalize else 0, tok.data_ptr(), act.data_ptr(), pol.data_ptr(),
                                    workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return tok, act, pol
+
+
+def mtmc_ppo_clip_loss(new_logprobs: torch.Tensor, old_logprobs: torch.Tensor, advantages: torch.Tensor,
+                       clip_eps: float, mask: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """fp32 CUDA tensors of one size (mask: int32 or None).  Returns a CUDA double tensor
+    [loss, clip fraction, approx KL, count]."""
+    for t in (new_logprobs, old_logprobs, advantages):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == new_logprobs.numel()
+    if mask is not None:
+        assert mask.is_cuda and mask.dtype == torch.int32 and mask.is_contiguous() and mask.numel() == new_logprobs.numel()
+    ws = torch.empty(int(_lib.mtmc_ppo_workspace_bytes()), dtype=torch.uint8, device=new_logprobs.device)
+    out = torch.empty(4, dtype=torch.float64, device=new_logprobs.device)
+    _check(_lib.mtmc_ppo_clip_loss(new_logprobs.data_ptr(), old_logprobs.data_ptr(), advantages.data_ptr(),
+                                   mask.data_ptr() if mask is not None else None, new_logprobs.numel(), clip_eps,
+                                   out.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return out
 
 
 MTMC_OPT_HIP_GRAPH = 1
