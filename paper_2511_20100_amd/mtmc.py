@@ -247,6 +247,10 @@ def mtmc_score_actions(handle: int, states: torch.Tensor, actions: torch.Tensor,
     return tok, act, pol
 
 
+def mtmc_ppo_workspace_bytes() -> int:
+    return int(_lib.mtmc_ppo_workspace_bytes())
+
+
 def mtmc_ppo_clip_loss(new_logprobs: torch.Tensor, old_logprobs: torch.Tensor, advantages: torch.Tensor,
                        clip_eps: float, mask: Optional[torch.Tensor] = None,
                        stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
@@ -256,7 +260,7 @@ def mtmc_ppo_clip_loss(new_logprobs: torch.Tensor, old_logprobs: torch.Tensor, a
         assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == new_logprobs.numel()
     if mask is not None:
         assert mask.is_cuda and mask.dtype == torch.int32 and mask.is_contiguous() and mask.numel() == new_logprobs.numel()
-    ws = torch.empty(int(_lib.mtmc_ppo_workspace_bytes()), dtype=torch.uint8, device=new_logprobs.device)
+    ws = torch.empty(mtmc_ppo_workspace_bytes(), dtype=torch.uint8, device=new_logprobs.device)
     out = torch.empty(4, dtype=torch.float64, device=new_logprobs.device)
     _check(_lib.mtmc_ppo_clip_loss(new_logprobs.data_ptr(), old_logprobs.data_ptr(), advantages.data_ptr(),
                                    mask.data_ptr() if mask is not None else None, new_logprobs.numel(), clip_eps,
