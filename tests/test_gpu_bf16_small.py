@@ -12,7 +12,13 @@ from paper_2511_20100_amd import inputs
 SMALL = inputs.ModelConfig(2, 256, 4, 2, 128, 688, 4096, dtype="bf16")      # G = 2, ragged FFN width
 GQA6 = inputs.ModelConfig(2, 384, 6, 1, 128, 1024, 2048, dtype="bf16")      # G = 6 like the 1.5 B policy
 GQA7 = inputs.ModelConfig(1, 512, 7, 1, 128, 1536, 2064, dtype="bf16")      # G = 7 like the 7 B policy
+MHA = inputs.ModelConfig(2, 256, 2, 2, 128, 512, 2048, dtype="bf16")        # G = 1: every query head has its own kv head
+GQA4 = inputs.ModelConfig(1, 512, 4, 1, 128, 1024, 2048, dtype="bf16")
+GQA8 = inputs.ModelConfig(1, 1024, 8, 1, 128, 1024, 2048, dtype="bf16")     # the widest group the kernels take
 CASES = [
+    ("mha-b12", MHA, 0.05, 4, 37, 3, 24, 1.0),
+    ("gqa4-b16", GQA4, 0.05, 2, 40, 8, 16, 1.0),
+    ("gqa8-b10", GQA8, 0.04, 5, 33, 2, 18, 1.0),
     ("small-b8", SMALL, 0.02, 4, 32, 2, 32, 1.0),
     ("small-ragged", SMALL, 0.05, 3, 37, 3, 21, 0.8),
     ("gqa6-b24", GQA6, 0.05, 3, 50, 8, 40, 1.0),
