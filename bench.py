@@ -35,6 +35,8 @@ WORKLOADS = {
     "tiny": (inputs.TINY, 4, 32, 2, 32),
     "1p5b": (inputs.POLICY_1P5B, 8, 512, 8, 1024),
     "7b": (inputs.POLICY_7B, 16, 1024, 8, 2048),
+    "1p3b-mha": (inputs.POLICY_1P3B_MHA, 8, 512, 8, 1024),
+    "1b-hd64": (inputs.POLICY_1B_HD64, 8, 512, 8, 1024),
 }
 
 

@@ -54,6 +54,7 @@ typedef struct {
   int32_t dtype;          /* MTMC_F32 or MTMC_BF16                                        */
   int32_t page_tokens;    /* tokens per KV-cache page; must be 16                         */
   int32_t max_positions;  /* rows of the rotary table: >= prompt_len + max_new, >= seq_len */
+  int32_t tie_embeddings; /* 1: the LM head is the embedding matrix and the blob has no lm_head  */
 } mtmc_config;
 
 typedef struct mtmc_weights mtmc_weights; /* opaque, library-owned */
@@ -64,11 +65,12 @@ typedef struct mtmc_weights mtmc_weights; /* opaque, library-owned */
  *
  * blob: tensors in this order, each starting at the next multiple of 256 bytes:
  *   embed[V,d]; per layer: attn_norm[d] Wq[Hq*hd,d] Wk[Hkv*hd,d] Wv[Hkv*hd,d] Wo[d,Hq*hd]
- *   ffn_norm[d] Wgate[F,d] Wup[F,d] Wdown[d,F]; final_norm[d]; lm_head[V,d].
+ *   ffn_norm[d] Wgate[F,d] Wup[F,d] Wdown[d,F]; final_norm[d]; lm_head[V,d] (absent when
+ *   tie_embeddings is set: logits are then taken against embed).
  *   Norm gains are fp32; matrices are fp32 (MTMC_F32) or bf16 (MTMC_BF16).
  * blob_on_device: 0 = host pointer, 1 = device pointer.  The caller keeps and frees blob;
  * it is no longer referenced when the call returns (the call synchronises `stream`).
- * Constraints: head_dim 64 or 128 (MTMC_BF16: 128 or 64), n_q_heads % n_kv_heads == 0,
+ * Constraints: head_dim 64 or 128, n_q_heads % n_kv_heads == 0,
  * d_model, d_ffn, n_q_heads*head_dim multiples of 16, vocab multiple of 16.
  */
 int mtmc_weights_create(const mtmc_config* cfg, const void* blob, size_t blob_bytes,

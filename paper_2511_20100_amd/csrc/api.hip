@@ -20,7 +20,6 @@ static int check_config(const mtmc_config* c) {
                "all model dimensions must be positive");
   MTMC_REQUIRE(c->dtype == MTMC_F32 || c->dtype == MTMC_BF16, "dtype must be MTMC_F32 or MTMC_BF16");
   MTMC_REQUIRE(c->head_dim == 64 || c->head_dim == 128, "head_dim must be 64 or 128");
-  MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->head_dim == 128, "MTMC_BF16 kernels need head_dim 128");
   MTMC_REQUIRE(c->n_q_heads % c->n_kv_heads == 0, "n_q_heads must be a multiple of n_kv_heads");
   MTMC_REQUIRE(c->dtype != MTMC_BF16 || c->n_q_heads / c->n_kv_heads <= 8,
                "MTMC_BF16 kernels need at most 8 query heads per kv head");
@@ -31,6 +30,7 @@ static int check_config(const mtmc_config* c) {
   MTMC_REQUIRE(c->page_tokens == kPageTokens, "page_tokens must be 16");
   MTMC_REQUIRE(c->max_positions > 0, "max_positions must be positive");
   MTMC_REQUIRE(c->rms_eps >= 0.f && c->rope_base > 0.f, "rms_eps >= 0 and rope_base > 0 required");
+  MTMC_REQUIRE(c->tie_embeddings == 0 || c->tie_embeddings == 1, "tie_embeddings must be 0 or 1");
   return MTMC_OK;
 }
 
@@ -60,7 +60,7 @@ BlobLayout blob_layout(const mtmc_config& c) {
     l.wdown = take(d * F * eb);
   }
   b.final_norm = take(d * 4);
-  b.lm_head = take(V * d * eb);
+  b.lm_head = c.tie_embeddings ? b.embed : take(V * d * eb);  // tied: the embedding matrix is the LM head
   b.total = off;
   return b;
 }

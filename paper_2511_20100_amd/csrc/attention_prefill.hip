@@ -1,4 +1,4 @@
-// Causal grouped-query attention of the prefill / scoring pass (head_dim 128) on the 32x32x16 MFMA.
+// Causal grouped-query attention of the prefill / scoring pass (head_dim 128 or 64) on the 32x32x16 MFMA.
 //
 // One workgroup per (256 query columns, kv head, sequence).  The columns of a kv head are the
 // (query head of its group, position) pairs, position fastest: with S a multiple of 256 a workgroup holds 256
@@ -8,7 +8,7 @@
 // the workgroup's last key (steps beyond a block's own positions are fully masked and add zeros: branching on
 // that made the register allocator spill, which cost more than the ~12 % of MFMAs saved).  The workgroup walks
 // the keys in steps of 32 tokens (two 16-token pages): the four wavefronts copy the two K pages and two V pages
-// of a step (16 KiB) into a ring of LDS buffers with LDS-direct loads, three steps ahead, and every wavefront
+// of a step (16 KiB at head_dim 128) into a ring of LDS buffers with LDS-direct loads, three steps ahead, and every wavefront
 // reads them from there.  Query j of a sequence sits at position pos_base + j and sees keys 0 .. pos_base + j.
 //
 // Per step and column block:  S^T[token][column] = K Q^T  (8 MFMAs over the 128 dims), online softmax
@@ -26,18 +26,16 @@ namespace bf16 {
 
 namespace {
 
-constexpr int PHD = 128;
-constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 KiB
 constexpr int kAStages = 4;
-constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
 
 typedef __attribute__((ext_vector_type(16))) float v16f;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
-__device__ __forceinline__ const uint8_t* page_ptr(const KvPool& pool, int layer, int which, int page, int g) {
+__device__ __forceinline__ const uint8_t* page_ptr(const KvPool& pool, int layer, int which, int page, int g,
+                                                   int page_bytes) {
   return (const uint8_t*)pool.base +
-         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)kPageBytes;
+         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)page_bytes;
 }
 
 template <int N>
@@ -48,8 +46,13 @@ __device__ __forceinline__ void wait_vm() {
 constexpr int NCB = 2;    // column blocks per wavefront
 constexpr int QB = 256;   // query positions per workgroup
 
+template <int PHD>
 __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
                                                            int row_stride, int pos_base, KvPool pool, int layer) {
+  constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 or 2 KiB
+  constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
+  constexpr int kPageKiB = kPageBytes / 1024;
+  constexpr int kCopies = kAStageBytes / 1024 / 4;   // 1 KiB copies per wavefront and step
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int qblk = gridDim.x - 1 - blockIdx.x;  // longest columns first
   const int c0 = qblk * QB, g = blockIdx.y, seq = blockIdx.z;
@@ -71,27 +74,27 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
   int* s_ids = reinterpret_cast<int*>(lds + kAStages * kAStageBytes);
   for (int i = threadIdx.x; i < 2 * n_steps; i += 256) s_ids[i] = table[min(i, seq_pages - 1)];
   __syncthreads();
-  // ---- copies of one step: wavefront w moves KiB w of each of the four pages
+  // ---- copies of one step: the stage is 4 * kPageKiB pieces of 1 KiB (pages K0, K1, V0, V1 in this order);
+  // wavefront w moves pieces w, w + 4, ... (at head_dim 128: KiB w of each of the four pages)
   auto issue = [&](int step, int buf) {
     const int st = min(step, n_steps - 1);
     const int id0 = __builtin_amdgcn_readfirstlane(s_ids[2 * st]);
     const int id1 = __builtin_amdgcn_readfirstlane(s_ids[2 * st + 1]);
-    uint8_t* sb = lds + buf * kAStageBytes + uwave * 1024;
-    const uint32_t off = uwave * 1024 + lane * 16;
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 0, id0, g) + off), (lds_ptr_t)(sb), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 0, id1, g) + off),
-                                     (lds_ptr_t)(sb + kPageBytes), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 1, id0, g) + off),
-                                     (lds_ptr_t)(sb + 2 * kPageBytes), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(page_ptr(pool, layer, 1, id1, g) + off),
-                                     (lds_ptr_t)(sb + 3 * kPageBytes), 16, 0, 0);
+#pragma unroll
+    for (int c = 0; c < kCopies; ++c) {
+      const int piece = 4 * c + uwave;
+      const int page = piece / kPageKiB, kib = piece % kPageKiB;  // page: 0 = K0, 1 = K1, 2 = V0, 3 = V1
+      const uint8_t* src =
+          page_ptr(pool, layer, page >> 1, (page & 1) ? id1 : id0, g, kPageBytes) + kib * 1024 + lane * 16;
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)(lds + buf * kAStageBytes + piece * 1024), 16, 0, 0);
+    }
   };
 #pragma unroll
   for (int s = 0; s < kAStages - 1; ++s) issue(s, s);
 
   // ---- this wavefront's column blocks (columns c0 + 32 b + col, b = wave and 7 - wave).
   // Q fragments (B operand: column col, dims 16 j + 8 hh + 0..7).
-  v8bf qf[NCB][8];
+  v8bf qf[NCB][PHD / 16];
   int qpos[NCB], qabs[NCB], qhd[NCB];  // index in the sequence / position among the keys (-1: padding), head
 #pragma unroll
   for (int i = 0; i < NCB; ++i) {
@@ -104,25 +107,25 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
     qhd[i] = g * G + jh;
     const h16_t* qrow = q + ((size_t)seq * S + max(qpos[i], 0)) * Hq * PHD + (size_t)qhd[i] * PHD + 8 * hh;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < PHD / 16; ++j) {
       v4u raw = {0u, 0u, 0u, 0u};
       if (qpos[i] >= 0) raw = *reinterpret_cast<const v4u*>(qrow + 16 * j);
       qf[i][j] = __builtin_bit_cast(v8bf, raw);
     }
   }
-  v16f oacc[NCB][4];
+  v16f oacc[NCB][PHD / 32];
   float mrun[NCB], lrun[NCB];
 #pragma unroll
   for (int i = 0; i < NCB; ++i) {
     mrun[i] = -INFINITY;
     lrun[i] = 0.f;
 #pragma unroll
-    for (int d = 0; d < 4; ++d)
+    for (int d = 0; d < PHD / 32; ++d)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[i][d][e] = 0.f;
   }
-  // exp(x / sqrt(128)) = exp2(x c)
-  const float c2 = 0.08838834764831845f * 1.4426950408889634f;
+  // exp(x / sqrt(head_dim)) = exp2(x c)
+  const float c2 = (PHD == 128 ? 0.08838834764831845f : 0.125f) * 1.4426950408889634f;
   // lane offsets inside a stage: K operand (token row col, dim group 2 j + hh) and V operand
   // (dim row 32 d + col, tokens 4 hh .. and 8 + 4 hh .. of page jj)
   const int koff = (col >> 4) * kPageBytes + (hh * 16 + (col & 15)) * 16;
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
 #pragma unroll
       for (int e = 0; e < 16; ++e) sacc[i][e] = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < PHD / 16; ++j) {
       const v8bf kf = *reinterpret_cast<const v8bf*>(sb + koff + j * 512);
 #pragma unroll
       for (int i = 0; i < NCB; ++i)
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
       // rescale O only when some column's maximum moved (rare after the first steps)
       if (__builtin_amdgcn_ballot_w64(m_new > mrun[i]) != 0) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) oacc[i][d] = oacc[i][d] * corr;
+        for (int d = 0; d < PHD / 32; ++d) oacc[i][d] = oacc[i][d] * corr;
       }
       mrun[i] = m_new;
 #pragma unroll
@@ -194,7 +197,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
+      for (int d = 0; d < PHD / 32; ++d) {
         const uint8_t* vp = sb + voff + jj * kPageBytes + d * 1024;
         const uint2 va = *reinterpret_cast<const uint2*>(vp);
         const uint2 vb = *reinterpret_cast<const uint2*>(vp + 16);
@@ -206,7 +209,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
       }
   };
   for (int t = 0; t < n_steps; ++t) {
-    wait_vm<(kAStages - 2) * 4>();  // step t landed; t + 1, t + 2 may be in flight
+    wait_vm<(kAStages - 2) * kCopies>();  // step t landed; t + 1, t + 2 may be in flight
     __builtin_amdgcn_s_barrier();
     issue(t + kAStages - 1, (t + kAStages - 1) % kAStages);
     const uint8_t* sb = lds + (t % kAStages) * kAStageBytes;
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
     const float inv = 1.0f / l;
     const int tok = seq * S + qpos[i];
 #pragma unroll
-    for (int d = 0; d < 4; ++d)
+    for (int d = 0; d < PHD / 32; ++d)
 #pragma unroll
       for (int qq = 0; qq < 4; ++qq) {
         uint2 pk;
@@ -239,17 +242,25 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
                        TokMap map, KvPool pool, int layer, hipStream_t st) {
   static bool configured = false;
-  // ring of K/V steps + page ids of one sequence (2 per step of 32 tokens)
-  const int lds_bytes = kAStages * kAStageBytes + 2 * ((map.pos_base + S + 31) / 32) * (int)sizeof(int);
   constexpr int kLdsMax = 160 * 1024;
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill32), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kLdsMax);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill32<128>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill32<64>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax);
     configured = true;
   }
+  // ring of K/V steps + page ids of one sequence (2 per step of 32 tokens)
+  const int hd = pool.head_dim;
+  const int lds_bytes = kAStages * 4 * kPageTokens * hd * 2 + 2 * ((map.pos_base + S + 31) / 32) * (int)sizeof(int);
   const int n_cols = Hq / Hkv * S;
-  k_attn_prefill32<<<dim3((n_cols + QB - 1) / QB, Hkv, n_seqs), 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv,
-                                                                             map.row_stride, map.pos_base, pool, layer);
+  const dim3 grid((n_cols + QB - 1) / QB, Hkv, n_seqs);
+  if (hd == 64)
+    k_attn_prefill32<64><<<grid, 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv, map.row_stride, map.pos_base, pool,
+                                                       layer);
+  else
+    k_attn_prefill32<128><<<grid, 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv, map.row_stride, map.pos_base,
+                                                        pool, layer);
 }
 
 }  // namespace bf16

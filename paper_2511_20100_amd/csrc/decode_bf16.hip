@@ -525,33 +525,33 @@ void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, 
 // Epilogue: the four wavefronts' partial (max, sum, O) are merged through LDS; with several
 // active chunks each workgroup publishes its partial and the last one to arrive (device-scope
 // counter) merges them in chunk order, so the result does not depend on arrival order.
-constexpr int DHD = 128;
-constexpr int DPAGE = kPageTokens * DHD;
-
+template <int HD>
 __device__ __forceinline__ h16_t* dec_page(const KvPool& pool, int layer, int which, int page, int g) {
   return (h16_t*)pool.base +
-         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)DPAGE;
+         ((((size_t)layer * 2 + which) * pool.n_pages + page) * pool.n_kv_heads + g) * (size_t)(kPageTokens * HD);
 }
 
 constexpr int AW = 8;        // wavefronts per workgroup
 constexpr int AGMAX = 8;     // query heads per kv head at most
 constexpr int ATAB = 512;    // page-table entries of one chunk kept in LDS
 
+template <int HD>
 struct KvFrags {
-  v8bf k[2][4];
-  v4u v[8];
+  v8bf k[2][HD / 32];
+  v4u v[HD / 16];
 };
-__device__ __forceinline__ KvFrags load_kv(const h16_t* K0, const h16_t* K1, const h16_t* V0, const h16_t* V1,
-                                           int lane) {
-  KvFrags f;
+template <int HD>
+__device__ __forceinline__ KvFrags<HD> load_kv(const h16_t* K0, const h16_t* K1, const h16_t* V0, const h16_t* V1,
+                                               int lane) {
+  KvFrags<HD> f;
 #pragma unroll
-  for (int kb = 0; kb < 4; ++kb) {
+  for (int kb = 0; kb < HD / 32; ++kb) {
     f.k[0][kb] = load_frag(K0 + kb * 512, lane);
     f.k[1][kb] = load_frag(K1 + kb * 512, lane);
   }
   const int voff = (lane & 15) * kPageTokens + 4 * (lane >> 4);
 #pragma unroll
-  for (int cb = 0; cb < 8; ++cb) {
+  for (int cb = 0; cb < HD / 16; ++cb) {
     const uint2 x = *reinterpret_cast<const uint2*>(V0 + cb * 256 + voff);
     const uint2 y = *reinterpret_cast<const uint2*>(V1 + cb * 256 + voff);
     f.v[cb] = v4u{x.x, x.y, y.x, y.y};
@@ -560,12 +560,13 @@ __device__ __forceinline__ KvFrags load_kv(const h16_t* K0, const h16_t* K1, con
 }
 
 // One step (two pages, 32 tokens from tok0) of a single block of query columns on loaded fragments.
-__device__ __forceinline__ void attn_step1(const KvFrags& f, int tok0, const v8bf (&qf)[4], int qpos, float scale,
-                                           AttnState<1>& st, int lane) {
+template <int HD>
+__device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const v8bf (&qf)[HD / 32], int qpos,
+                                           float scale, AttnState<HD / 16>& st, int lane) {
   const int lg = lane >> 4;
   v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
-  for (int kb = 0; kb < 4; ++kb) {
+  for (int kb = 0; kb < HD / 32; ++kb) {
     s0 = mfma16(f.k[0][kb], qf[kb], s0);
     s1 = mfma16(f.k[1][kb], qf[kb], s1);
   }
@@ -580,17 +581,17 @@ __device__ __forceinline__ void attn_step1(const KvFrags& f, int tok0, const v8b
   }
   tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-  const float m_new = fmaxf(st.m[0], tmax);
+  const float m_new = fmaxf(st.m, tmax);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  const float corr = expf(st.m[0] - m_safe);
+  const float corr = expf(st.m - m_safe);
   float p[8], psum = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     p[e] = expf(sv[e] - m_safe);
     psum += p[e];
   }
-  st.l[0] = st.l[0] * corr + psum;
-  st.m[0] = m_new;
+  st.l = st.l * corr + psum;
+  st.m = m_new;
   v4u pk;
   pk[0] = pack_h16x2(p[0], p[1]);
   pk[1] = pack_h16x2(p[2], p[3]);
@@ -598,11 +599,13 @@ __device__ __forceinline__ void attn_step1(const KvFrags& f, int tok0, const v8b
   pk[3] = pack_h16x2(p[6], p[7]);
   const v8bf pf = __builtin_bit_cast(v8bf, pk);
 #pragma unroll
-  for (int cb = 0; cb < 8; ++cb)
-    st.o[0][cb] = mfma16(__builtin_bit_cast(v8bf, f.v[cb]), pf, st.o[0][cb] * corr);
+  for (int cb = 0; cb < HD / 16; ++cb)
+    st.o[cb] = mfma16(__builtin_bit_cast(v8bf, f.v[cb]), pf, st.o[cb] * corr);
 }
 
+template <int DHD>
 __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
+  constexpr int HALF = DHD / 2;
   __shared__ __attribute__((aligned(16))) h16_t q_s[16][DHD];
   __shared__ float s_o[AW][AGMAX][DHD + 1];
   __shared__ float s_m[AW][16], s_l[AW][16];
@@ -632,47 +635,47 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   // ---- loads that do not depend on the position: step counter, this chunk's page ids, the raw
   // q/k/v row, and (speculatively) the first pair of pages of this wavefront
   const int step = *a.d_step;
-  const int base = a.row_pos ? a.row_pos[b] : a.pos_base;
+  const int pos0 = a.row_pos ? a.row_pos[b] : a.pos_base;
   for (int i = tid; i < a.chunk_pages; i += AW * 64) s_table[i] = table[min(p_lo + i, pool.max_pages - 1)];
   const float* row = a.qkv + (size_t)b * (Hq + 2 * Hkv) * DHD;
   float qraw[2] = {0.f, 0.f};
   const int qj = tid >> 6, qi = tid & 63;  // wavefront j rotates head j (AW >= G)
-  if (qj < G) {
+  if (qj < G && qi < HALF) {
     qraw[0] = row[(size_t)(g * G + qj) * DHD + qi];
-    qraw[1] = row[(size_t)(g * G + qj) * DHD + qi + 64];
+    qraw[1] = row[(size_t)(g * G + qj) * DHD + qi + HALF];
   }
   const int pg0 = p_lo + 2 * wave;
-  KvFrags cur;
+  KvFrags<DHD> cur;
   {
     const int i0 = table[min(pg0, pool.max_pages - 1)], i1 = table[min(pg0 + 1, pool.max_pages - 1)];
-    cur = load_kv(dec_page(pool, a.layer, 0, i0, g), dec_page(pool, a.layer, 0, i1, g),
-                  dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
+    cur = load_kv<DHD>(dec_page<DHD>(pool, a.layer, 0, i0, g), dec_page<DHD>(pool, a.layer, 0, i1, g),
+                  dec_page<DHD>(pool, a.layer, 1, i0, g), dec_page<DHD>(pool, a.layer, 1, i1, g), lane);
   }
   // ---- position-dependent part
-  const int pos = base + step;
+  const int pos = pos0 + step;
   const int n_ctx_pages = pos / kPageTokens + 1;
   const int p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
   if (p_lo >= p_hi) return;
   const int n_act = (n_ctx_pages + a.chunk_pages - 1) / a.chunk_pages;
   const float* cs = a.cos + (size_t)pos * (DHD / 2);
   const float* sn = a.sin + (size_t)pos * (DHD / 2);
-  if (qj < G) {
+  if (qj < G && qi < HALF) {
     const float c = cs[qi], s = sn[qi];
     q_s[qj][qi] = f32_to_h16(qraw[0] * c - qraw[1] * s);
-    q_s[qj][qi + 64] = f32_to_h16(qraw[1] * c + qraw[0] * s);
+    q_s[qj][qi + HALF] = f32_to_h16(qraw[1] * c + qraw[0] * s);
   }
   // the owner of the current position appends K and V to the cache (last wavefront: it is idle above when G < AW)
   const int cur_page = pos / kPageTokens;
   const bool owner_wg = cur_page >= p_lo && cur_page < p_hi;
-  if (owner_wg && wave == AW - 1) {
+  if (owner_wg && wave == AW - 1 && lane < HALF) {
     const int page = table[cur_page], slot = pos % kPageTokens;
-    h16_t* kp = dec_page(pool, a.layer, 0, page, g);
-    h16_t* vp = dec_page(pool, a.layer, 1, page, g);
+    h16_t* kp = dec_page<DHD>(pool, a.layer, 0, page, g);
+    h16_t* vp = dec_page<DHD>(pool, a.layer, 1, page, g);
     const int i = lane;
-    const float x0 = row[(size_t)(Hq + g) * DHD + i], x1 = row[(size_t)(Hq + g) * DHD + i + 64];
-    const float v0 = row[(size_t)(Hq + Hkv + g) * DHD + i], v1 = row[(size_t)(Hq + Hkv + g) * DHD + i + 64];
+    const float x0 = row[(size_t)(Hq + g) * DHD + i], x1 = row[(size_t)(Hq + g) * DHD + i + HALF];
+    const float v0 = row[(size_t)(Hq + Hkv + g) * DHD + i], v1 = row[(size_t)(Hq + Hkv + g) * DHD + i + HALF];
     const float c = cs[i], s = sn[i];
-    const int c0 = i, c1 = i + 64;
+    const int c0 = i, c1 = i + HALF;
     kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(x0 * c - x1 * s);
     kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(x1 * c + x0 * s);
     vp[c0 * kPageTokens + slot] = f32_to_h16(v0);
@@ -680,46 +683,46 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   }
   __syncthreads();  // q_s, s_table complete; this workgroup's K/V stores are visible to its own loads
 
-  v8bf qf[4];
+  v8bf qf[DHD / 32];
 #pragma unroll
-  for (int kb = 0; kb < 4; ++kb) {
+  for (int kb = 0; kb < DHD / 32; ++kb) {
     v4u raw = {0u, 0u, 0u, 0u};
     if (col < G) raw = *reinterpret_cast<const v4u*>(&q_s[col][kb * 32 + 8 * lg]);
     qf[kb] = __builtin_bit_cast(v8bf, raw);
   }
   const int qpos = (col < G) ? pos : -1;
-  AttnState<1> st;
+  AttnState<DHD / 16> st;
   attn_init(st);
-  const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  const float scale = DHD == 128 ? 0.08838834764831845f : 0.125f;  // 1 / sqrt(head_dim)
   auto page_id = [&](int pg) { return s_table[min(pg, n_ctx_pages - 1) - p_lo]; };
   // the speculative load may have raced with the append above: redo it if it covers the current page
   if (owner_wg && (cur_page == pg0 || cur_page == pg0 + 1) && pg0 < p_hi) {
     const int i0 = page_id(pg0), i1 = page_id(pg0 + 1);
-    cur = load_kv(dec_page(pool, a.layer, 0, i0, g), dec_page(pool, a.layer, 0, i1, g),
-                  dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
+    cur = load_kv<DHD>(dec_page<DHD>(pool, a.layer, 0, i0, g), dec_page<DHD>(pool, a.layer, 0, i1, g),
+                  dec_page<DHD>(pool, a.layer, 1, i0, g), dec_page<DHD>(pool, a.layer, 1, i1, g), lane);
   }
   for (int pg = pg0; pg < p_hi; pg += 2 * AW) {
     const int pn = pg + 2 * AW;
-    KvFrags nxt = cur;
+    KvFrags<DHD> nxt = cur;
     if (pn < p_hi) {
       const int i0 = page_id(pn), i1 = page_id(pn + 1);
-      nxt = load_kv(dec_page(pool, a.layer, 0, i0, g), dec_page(pool, a.layer, 0, i1, g),
-                    dec_page(pool, a.layer, 1, i0, g), dec_page(pool, a.layer, 1, i1, g), lane);
+      nxt = load_kv<DHD>(dec_page<DHD>(pool, a.layer, 0, i0, g), dec_page<DHD>(pool, a.layer, 0, i1, g),
+                    dec_page<DHD>(pool, a.layer, 1, i0, g), dec_page<DHD>(pool, a.layer, 1, i1, g), lane);
     }
-    attn_step1(cur, pg * kPageTokens, qf, qpos, scale, st, lane);
+    attn_step1<DHD>(cur, pg * kPageTokens, qf, qpos, scale, st, lane);
     cur = nxt;
   }
-  float l = st.l[0];
+  float l = st.l;
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
   if (col < AGMAX) {
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
+    for (int cb = 0; cb < DHD / 16; ++cb)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) s_o[wave][col][cb * 16 + 4 * lg + r] = st.o[0][cb][r];
+      for (int r = 0; r < 4; ++r) s_o[wave][col][cb * 16 + 4 * lg + r] = st.o[cb][r];
   }
   if (lg == 0) {
-    s_m[wave][col] = st.m[0];
+    s_m[wave][col] = st.m;
     s_l[wave][col] = l;
   }
   __syncthreads();
@@ -788,11 +791,13 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
 }
 
 size_t attn_part_floats(int B, int Hkv, int G, int n_chunks) {
-  return (size_t)B * Hkv * n_chunks * G * (DHD + 2);
+  return (size_t)B * Hkv * n_chunks * G * (128 + 2);  // sized for the larger head_dim
 }
 
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {
-  k_attn_dec<<<dim3(B, a.Hkv, a.n_chunks), AW * 64, 0, st>>>(a);
+  const dim3 grid(B, a.Hkv, a.n_chunks);
+  if (a.pool.head_dim == 64) k_attn_dec<64><<<grid, AW * 64, 0, st>>>(a);
+  else k_attn_dec<128><<<grid, AW * 64, 0, st>>>(a);
 }
 
 }  // namespace bf16

@@ -162,11 +162,12 @@ void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const 
 // ---------------------------------------------------------------- rotary embedding + KV write
 // qkv[m, :] = sum_s P[s][m][:] (fp32).  q heads are rotated and stored bf16 row-major; k heads
 // are rotated and scattered into the K page ([dim/8][token][dim%8]); v into the V page
-// ([dim][token]).  Pairs are (i, i + 64) of the 128-dim head.
+// ([dim][token]).  Pairs are (i, i + HD / 2) of the head.
+template <int HD>
 __global__ __launch_bounds__(256) void k_rope_kv_write(h16_t* q, const float* P, int n_split, int ldp,
                                                        int Mpad_p, int Hq, int Hkv, const float* cos,
                                                        const float* sin, TokMap map, KvPool pool, int layer) {
-  constexpr int HD = 128, HALF = 64;
+  constexpr int HALF = HD / 2;
   const int t = blockIdx.x;
   const int pos = tok_pos(map, t);
   const int row = tok_seq(map, t) * map.row_stride;
@@ -209,7 +210,10 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(h16_t* q, const float* P,
 void rope_kv_write(h16_t* q, const float* P, int n_split, int ldp, int Mpad_p, int T, int Hq, int Hkv,
                    const float* cos, const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st) {
   if (T == 0) return;
-  k_rope_kv_write<<<T, 256, 0, st>>>(q, P, n_split, ldp, Mpad_p, Hq, Hkv, cos, sin, map, pool, layer);
+  if (pool.head_dim == 64)
+    k_rope_kv_write<64><<<T, 256, 0, st>>>(q, P, n_split, ldp, Mpad_p, Hq, Hkv, cos, sin, map, pool, layer);
+  else
+    k_rope_kv_write<128><<<T, 256, 0, st>>>(q, P, n_split, ldp, Mpad_p, Hq, Hkv, cos, sin, map, pool, layer);
 }
 
 }  // namespace bf16

@@ -51,6 +51,7 @@ class ModelConfig:
     rms_eps: float = 1e-6
     rope_base: float = 10000.0
     dtype: str = "bf16"  # "fp32" or "bf16": storage type of the matrices
+    tie_embeddings: bool = False  # the LM head is the embedding matrix (no lm_head tensor)
 
     @property
     def group(self) -> int:
@@ -64,6 +65,10 @@ class ModelConfig:
 TINY = ModelConfig(2, 256, 4, 2, 64, 688, 4096, dtype="fp32")
 POLICY_1P5B = ModelConfig(28, 1536, 12, 2, 128, 8960, 151936, dtype="bf16")
 POLICY_7B = ModelConfig(28, 3584, 28, 4, 128, 18944, 152064, dtype="bf16")
+# Shapes of the classes of the paper's own policy backbones (Method, "Training Methodology"): a 1.3 B-class
+# model with one kv head per query head, and a 1 B-class model with 64-dim heads and a tied LM head.
+POLICY_1P3B_MHA = ModelConfig(24, 2048, 16, 16, 128, 5504, 32256, dtype="bf16")
+POLICY_1B_HD64 = ModelConfig(16, 2048, 32, 8, 64, 8192, 128256, dtype="bf16", tie_embeddings=True)
 
 
 def tensor_specs(cfg: ModelConfig) -> List[Tuple[str, Tuple[int, ...], bool]]:
@@ -84,7 +89,9 @@ def tensor_specs(cfg: ModelConfig) -> List[Tuple[str, Tuple[int, ...], bool]]:
             (p + "wup", (f, d), True),
             (p + "wdown", (d, f), True),
         ]
-    specs += [("final_norm", (d,), False), ("lm_head", (v, d), True)]
+    specs += [("final_norm", (d,), False)]
+    if not cfg.tie_embeddings:
+        specs += [("lm_head", (v, d), True)]
     return specs
 
 
@@ -163,6 +170,8 @@ class Weights:
         return self.tensors.keys()
 
     def f32(self, name: str, cache: bool = True) -> np.ndarray:
+        if name == "lm_head" and self.cfg.tie_embeddings:
+            name = "embed"
         t = self.tensors[name]
         if t.dtype == np.float32:
             return t

@@ -31,7 +31,8 @@ class mtmc_config(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32),
                 ("vocab", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("rope_base", ctypes.c_float),
-                ("dtype", ctypes.c_int32), ("page_tokens", ctypes.c_int32), ("max_positions", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("page_tokens", ctypes.c_int32), ("max_positions", ctypes.c_int32),
+                ("tie_embeddings", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -108,7 +109,7 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
 def make_config(cfg: ModelConfig, max_positions: int) -> mtmc_config:
     return mtmc_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
                        cfg.vocab, cfg.rms_eps, cfg.rope_base, MTMC_BF16 if cfg.dtype == "bf16" else MTMC_F32,
-                       16, max_positions)
+                       16, max_positions, 1 if cfg.tie_embeddings else 0)
 
 
 def mtmc_blob_bytes(cfg: mtmc_config) -> int:

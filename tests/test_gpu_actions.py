@@ -23,6 +23,8 @@ CASES = [
     ("bf16-long-actions", SMALL, 0.05, LOGP_TOL_BF16, 2, 70, 3, 40, 1, True),      # candidates span several pages
     ("bf16-gqa6-many", GQA6, 0.05, LOGP_TOL_BF16, 4, 48, 16, 6, 1, False),
     ("bf16-one-token-state", GQA6, 0.05, LOGP_TOL_BF16, 1, 1, 2, 4, 1, False),
+    ("bf16-hd64-tied", inputs.ModelConfig(2, 512, 8, 2, 64, 1024, 2048, dtype="bf16", tie_embeddings=True), 0.05,
+     LOGP_TOL_BF16, 2, 45, 6, 9, 1, False),
     ("bf16-long-state", GQA6, 0.04, LOGP_TOL_BF16, 1, 300, 3, 5, 1, False),         # several 256-key blocks of context
 ]
 

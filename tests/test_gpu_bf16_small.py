@@ -15,7 +15,12 @@ GQA7 = inputs.ModelConfig(1, 512, 7, 1, 128, 1536, 2064, dtype="bf16")      # G 
 MHA = inputs.ModelConfig(2, 256, 2, 2, 128, 512, 2048, dtype="bf16")        # G = 1: every query head has its own kv head
 GQA4 = inputs.ModelConfig(1, 512, 4, 1, 128, 1024, 2048, dtype="bf16")
 GQA8 = inputs.ModelConfig(1, 1024, 8, 1, 128, 1024, 2048, dtype="bf16")     # the widest group the kernels take
+HD64 = inputs.ModelConfig(2, 256, 4, 2, 64, 688, 4096, dtype="bf16")        # head_dim 64
+HD64_TIED = inputs.ModelConfig(2, 512, 8, 2, 64, 1024, 2048, dtype="bf16", tie_embeddings=True)  # G = 4, tied LM head
 CASES = [
+    ("hd64-b9", HD64, 0.05, 3, 37, 3, 21, 1.0),
+    ("hd64-tied-b64", HD64_TIED, 0.05, 8, 50, 8, 24, 1.0),
+    ("hd64-long", HD64, 0.05, 1, 200, 2, 40, 1.0),
     ("mha-b12", MHA, 0.05, 4, 37, 3, 24, 1.0),
     ("gqa4-b16", GQA4, 0.05, 2, 40, 8, 16, 1.0),
     ("gqa8-b10", GQA8, 0.04, 5, 33, 2, 18, 1.0),

@@ -123,3 +123,23 @@ def test_copy_probe_copies_exactly():
     assert torch.equal(dst, src)
     with pytest.raises(Exception):
         mtmc.mtmc_copy_probe(dst[:7].view(torch.uint8)[:20], src[:7].view(torch.uint8)[:20])
+
+
+def test_tied_lm_head():
+    """The embedding matrix used as the LM head (no lm_head tensor in the blob): ids exact, log-probs within tolerance."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    cfg = inputs.TINY.with_(tie_embeddings=True)
+    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    assert "lm_head" not in set(w.names())
+    handle = mtmc.mtmc_weights_create(mtmc.make_config(cfg, 64), w.blob())
+    try:
+        prompts = inputs.make_prompts(2, 9, cfg.vocab, seed=2)
+        ids, lp = mtmc.mtmc_rollout(handle, torch.from_numpy(prompts).cuda(), 2, 12, 1.0, 1)
+        mtmc.mtmc_poll_errors(handle)
+        ref_ids, ref_lp, margins = oracle.rollout(oracle_model(w, 64), prompts, 2, 12, 1.0, seed=1)
+        assert margins.min() > 1e-3
+        assert np.array_equal(ids.cpu().numpy(), ref_ids)
+        assert np.abs(lp.cpu().numpy() - ref_lp).max() <= LOGP_TOL_F32
+    finally:
+        mtmc.mtmc_weights_destroy(handle)
