@@ -100,6 +100,8 @@ def main() -> int:
     ap.add_argument("--max-new", type=int, default=None, help="override the number of new tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-score", action="store_true", help="time the rollout alone")
+    ap.add_argument("--no-rollout", action="store_true",
+                    help="time the scoring pass alone, on sequences whose new tokens are random ids (for counter runs)")
     ap.add_argument("--no-actions", action="store_true", help="skip the action-scoring leg (reported beside the step)")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps directly (for counter runs)")
     ap.add_argument("--no-kernel-timer", action="store_true", help="do not bracket the gate/up launches with events")
@@ -152,10 +154,14 @@ def main() -> int:
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
+    if args.no_rollout:
+        out_ids.copy_(torch.from_numpy(inputs.make_token_ids((B, max_new), cfg.vocab, seed=5)).to(dev))
+
     def step(seed):
         ev[0].record(stream)
-        mtmc.mtmc_rollout(handle, prompts, n_samples, max_new, 1.0, seed, workspace=ws_r, out_ids=out_ids,
-                          out_logprobs=out_lp)
+        if not args.no_rollout:
+            mtmc.mtmc_rollout(handle, prompts, n_samples, max_new, 1.0, seed, workspace=ws_r, out_ids=out_ids,
+                              out_logprobs=out_lp)
         ev[1].record(stream)
         if not args.no_score:
             seqs[:, prompt_len:] = out_ids
@@ -167,7 +173,7 @@ def main() -> int:
     torch.cuda.synchronize()
     # dominant decode kernel (gate/up projection: half of the layer weight bytes): every 32nd decode
     # step of the timed region is launched directly with a HIP-event pair around each of its launches
-    timed_kernel = cfg.dtype == "bf16" and not args.no_kernel_timer
+    timed_kernel = cfg.dtype == "bf16" and not args.no_kernel_timer and not args.no_rollout
     if timed_kernel:
         mtmc.mtmc_kernel_timer(handle, mtmc.MTMC_KERNEL_GATE_UP, 32)
     rollout_ms, score_ms = [], []
@@ -215,7 +221,8 @@ def main() -> int:
         "config": {"workload": f"{args.workload}: {cfg.n_layers} layers d{cfg.d_model} Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} "
                                f"F{cfg.d_ffn} V{cfg.vocab}; {n_prompts} prompts x {n_samples} samples = batch {B}, "
                                f"prompt {prompt_len}, {max_new} new tokens at T=1; then scoring of the {B} x {seq_len} sequences",
-                   "step": "mtmc_rollout + mtmc_score" if not args.no_score else "mtmc_rollout"},
+                   "step": "mtmc_score" if args.no_rollout else "mtmc_rollout + mtmc_score" if not args.no_score
+                           else "mtmc_rollout"},
         "rollout_tokens_per_s": new_tokens / (r_ms * 1e-3), "rollout_ms": r_ms,
         "roofline": roofline,
         "decode_step": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -227,7 +227,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   for (int nb = 0; nb < 4; ++nb) {
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) {
-      asm volatile("" ::: "memory");  // one accumulator block at a time (keeps them out of the VGPR half until needed)
+      // one accumulator block at a time: it is taken from its registers here, not earlier (volatile statements
+      // keep their order), which keeps the 256 accumulators out of the VGPR half until they are needed
+      asm volatile("" : "+a"(acc[nb][mb])::"memory");
       const int m = (mt_base + 8 * wm + 2 * mb) * 16 + col;
       if (m >= a.M) continue;
       const int n0 = (nt_base + 8 * wn + 2 * nb) * 16;  // first feature row of the block
@@ -302,22 +304,17 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
   auto epilogue = [&](v16f (&acc)[4][4], int nt_base, int) {
     const int nbk = nt_base / kBlkTiles;
     const bool full = (nbk + 1) * kBlkTiles <= a.n_tiles;  // all 256 entries of the block exist (workgroup-uniform)
-    Lse lse[4];
-    Top2 top[4];
-    float zt[4];
-    int target[4];
+    // one group of 32 rows (mb) at a time, so that only its running results and one accumulator block are live
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) {
-      lse[mb] = Lse{st_f[(SM + mb) * 256], st_f[(SS + mb) * 256]};
-      top[mb] = Top2{st_f[(SV1 + mb) * 256], st_i[(SI1 + mb) * 256], st_f[(SV2 + mb) * 256]};
-      zt[mb] = st_f[(SZT + mb) * 256];
-      target[mb] = st_i[(STG + mb) * 256];
-    }
+      Lse lse = Lse{st_f[(SM + mb) * 256], st_f[(SS + mb) * 256]};
+      Top2 top = Top2{st_f[(SV1 + mb) * 256], st_i[(SI1 + mb) * 256], st_f[(SV2 + mb) * 256]};
+      float zt = st_f[(SZT + mb) * 256];
+      const int target = st_i[(STG + mb) * 256];
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb) {
-        asm volatile("" ::: "memory");  // one accumulator block at a time
+      for (int nb = 0; nb < 4; ++nb) {
+        // the accumulator block is taken from its registers here, not earlier (volatile statements keep their order)
+        asm volatile("" : "+a"(acc[nb][mb])::"memory");
         // this lane's 16 entries of the block: n0 + 8 q + r (q, r = 0..3) in register 4 q + r
         const int n0 = (nbk * kBlkTiles + 8 * wn + 2 * nb) * 16 + rh;
         v16f z = acc[nb][mb];
@@ -329,38 +326,35 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
         float bm = z[0];
 #pragma unroll
         for (int j = 1; j < 16; ++j) bm = fmaxf(bm, z[j]);
-        if (bm > lse[mb].m) {  // -inf never gets here: an empty block leaves the state untouched
-          lse[mb].s *= __expf(lse[mb].m - bm);
-          lse[mb].m = bm;
+        if (bm > lse.m) {  // -inf never gets here: an empty block leaves the state untouched
+          lse.s *= __expf(lse.m - bm);
+          lse.m = bm;
         }
-        if (lse[mb].m > -INFINITY) {
-          const float mm = lse[mb].m;
+        if (lse.m > -INFINITY) {
+          const float mm = lse.m;
           float add = 0.f;
 #pragma unroll
           for (int j = 0; j < 16; ++j) add += __expf(z[j] - mm);  // exp(-inf) = 0 for missing entries
-          lse[mb].s += add;
+          lse.s += add;
         }
-        if (bm > top[mb].v2 || bm == top[mb].v1) {  // only then can the two largest (or a tie) change
+        if (bm > top.v2 || bm == top.v1) {  // only then can the two largest (or a tie) change
 #pragma unroll
-          for (int j = 0; j < 16; ++j) top2_push(top[mb], z[j], n0 + 8 * (j >> 2) + (j & 3));
+          for (int j = 0; j < 16; ++j) top2_push(top, z[j], n0 + 8 * (j >> 2) + (j & 3));
         }
-        const int d = target[mb] - n0;
+        const int d = target - n0;
         if (d >= 0 && d < 32 && (d & 4) == 0) {
           const int idx = (d >> 3) * 4 + (d & 3);
 #pragma unroll
           for (int j = 0; j < 16; ++j)
-            if (j == idx) zt[mb] = z[j];
+            if (j == idx) zt = z[j];
         }
       }
-    }
-  #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
-      st_f[(SM + mb) * 256] = lse[mb].m;
-      st_f[(SS + mb) * 256] = lse[mb].s;
-      st_f[(SV1 + mb) * 256] = top[mb].v1;
-      st_i[(SI1 + mb) * 256] = top[mb].i1;
-      st_f[(SV2 + mb) * 256] = top[mb].v2;
-      st_f[(SZT + mb) * 256] = zt[mb];
+      st_f[(SM + mb) * 256] = lse.m;
+      st_f[(SS + mb) * 256] = lse.s;
+      st_f[(SV1 + mb) * 256] = top.v1;
+      st_i[(SI1 + mb) * 256] = top.i1;
+      st_f[(SV2 + mb) * 256] = top.v2;
+      st_f[(SZT + mb) * 256] = zt;
     }
   };
   lds_gemm_stream(reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles, a.m_tiles,
