@@ -38,6 +38,7 @@ struct ScoreHeadArgs {
   const int* targets;
   float* part;
   int n_groups, groups_per_block;
+  int want_top;   // 0: the two largest logits are not tracked (the caller asked for log-probs only)
 };
 
 // ---- decode step (five launches per block; see decode_bf16.hip) ------------------------------
@@ -102,7 +103,7 @@ void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, co
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st);
 int score_head_blocks(int n_tiles, int* groups_per_block);
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
-                  int m_tiles, const int* targets, int lds_min_blocks, hipStream_t st);
+                  int m_tiles, const int* targets, bool want_top, int lds_min_blocks, hipStream_t st);
 // One partial result of the scoring LM head: a row's state over one vocabulary slice.
 struct ScorePartial {
   float m, s, v1;   // log-sum-exp state, largest logit

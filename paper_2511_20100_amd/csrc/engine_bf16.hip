@@ -557,7 +557,8 @@ int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hi
     launch_gather_rows(p.hs, p.h, R, D.d, n_scored, S, a.first, 1, st);
     bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
     bf16::score_targets(p.targets, a.seqs, R, S, a.first, n_scored, s0, 0, D.V, w->err_flag, st);
-    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets, w->opt_lds_min_blocks, st);
+    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
+                       a.out_top1 != nullptr || a.out_margin != nullptr, w->opt_lds_min_blocks, st);
     bf16::score_reduce(p.lm_part, n_parts, R, S, a.first, n_scored, s0, 0, a.out_logprobs, a.out_top1, a.out_margin, st);
   }
   return MTMC_OK;
@@ -607,7 +608,7 @@ int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionA
     bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
     bf16::score_targets(p.targets, p.vseq, R, p.W, 0, p.A, r0, 0, D.V, w->err_flag, st);
     bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
-                       w->opt_lds_min_blocks, st);
+                       false, w->opt_lds_min_blocks, st);
     bf16::score_reduce(p.lm_part, n_parts, R, p.W, 0, p.A, r0, 0, a.out_token, nullptr, nullptr, st);
   }
   launch_action_reduce(a.out_token, a.action_len, p.n_states, p.K, p.A, a.normalize, a.out_action, a.out_policy,

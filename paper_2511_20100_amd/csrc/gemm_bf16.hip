@@ -235,8 +235,9 @@ int score_head_blocks(int n_tiles, int* groups_per_block) {
 }
 
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
-                  int m_tiles, const int* targets, int lds_min_blocks, hipStream_t st) {
+                  int m_tiles, const int* targets, bool want_top, int lds_min_blocks, hipStream_t st) {
   ScoreHeadArgs a{};
+  a.want_top = want_top ? 1 : 0;
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
   a.targets = targets; a.part = part;
   a.n_groups = (n_tiles + 7) / 8;

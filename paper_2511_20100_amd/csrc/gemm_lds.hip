@@ -337,7 +337,7 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
           for (int j = 0; j < 16; ++j) add += __expf(z[j] - mm);  // exp(-inf) = 0 for missing entries
           lse.s += add;
         }
-        if (bm > top.v2 || bm == top.v1) {  // only then can the two largest (or a tie) change
+        if (a.want_top && (bm > top.v2 || bm == top.v1)) {  // only then can the two largest (or a tie) change
 #pragma unroll
           for (int j = 0; j < 16; ++j) top2_push(top, z[j], n0 + 8 * (j >> 2) + (j & 3));
         }

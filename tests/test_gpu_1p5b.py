@@ -32,6 +32,8 @@ def run():
     ids2, lp2 = mtmc.mtmc_rollout(handle, dprompts, N_SAMPLES, MAX_NEW, 1.0, 1)
     seqs = torch.cat([dprompts.repeat_interleave(N_SAMPLES, 0), ids], 1).contiguous()
     score, top1, margin = mtmc.mtmc_score(handle, seqs, PROMPT_LEN, want_top1=True)
+    score_plain = mtmc.mtmc_score(handle, seqs, PROMPT_LEN)  # log-probs only: the LM head skips the top-2 tracking
+    assert torch.equal(score, score_plain)
     # action-level scoring at the same shape: the prompts as states, 8 candidates of up to 16 tokens each
     actions, lens = inputs.make_actions(N_PROMPTS, N_ACTIONS, MAX_ACTION_LEN, CFG.vocab, seed=4)
     a_tok, a_act, a_pol = mtmc.mtmc_score_actions(handle, dprompts, torch.from_numpy(actions).cuda(),
