@@ -14,9 +14,9 @@
 // Per step and column block:  S^T[token][column] = K Q^T  (8 MFMAs over the 128 dims), online softmax
 // down each column (a column's 32 tokens sit in 16 registers of lanes l and l + 32), then
 // O^T[dim][column] += V^T P^T (4 blocks of 32 dims x 2 MFMAs over 16 tokens).  exp(S^T) is already in
-// the B-operand layout of the second product: slot e of lane (column, half h) in token group jj holds
-// token 16 jj + 8 (e / 4) + 4 h + e % 4, and the V^T operand is gathered with the same map (two
-// 8-byte pieces of a V page row).  Page layouts: see attention_core.h.
+// the B-operand layout of the second product: with the K rows permuted on their way into LDS (see the copy
+// code), slot e of lane (column, half h) in token group jj holds token 16 jj + 8 h + e, and the V^T operand
+// of a lane is one 16-byte piece of a V page row.  Page layouts: see attention_core.h.
 #include "bf16_kernels.h"
 #include "device_utils.h"
 #include "frag.h"
@@ -75,7 +75,18 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
   for (int i = threadIdx.x; i < 2 * n_steps; i += 256) s_ids[i] = table[min(i, seq_pages - 1)];
   __syncthreads();
   // ---- copies of one step: the stage is 4 * kPageKiB pieces of 1 KiB (pages K0, K1, V0, V1 in this order);
-  // wavefront w moves pieces w, w + 4, ... (at head_dim 128: KiB w of each of the four pages)
+  // wavefront w moves pieces w, w + 4, ... (at head_dim 128: KiB w of each of the four pages).  A copy puts
+  // the 16 bytes of lane s at offset 16 s of its piece, and the lane may fetch them from anywhere: the pieces
+  // are permuted on the way in, so that every later LDS read is one 16-byte access at offset 16 * lane.
+  //   K piece (4 dim groups x 16 tokens): slot (dim group, i) <- token i with bits 2 and 3 swapped.  Operand
+  //     row r of the K MFMA operand then stands for token tau(r) = r with bits 2 and 3 swapped, which makes
+  //     the 8 scores a lane holds per token group, and hence its 8 k-slots of the second product, the 8
+  //     CONSECUTIVE tokens 16 jj + 8 hh .. + 7;
+  //   V piece (32 dims x 2 halves of 8 tokens): slot 32 hh + c <- (dim c, tokens 8 hh .. 8 hh + 7), which is
+  //     exactly the V^T operand of lane (c, hh).
+  // (Two 8-byte reads per lane from the unpermuted V page cost four-way bank conflicts: 64 % of the LDS cycles.)
+  const int src_k = ((lane & 0x30) | ((lane & 4) << 1) | ((lane & 8) >> 1) | (lane & 3)) * 16;
+  const int src_v = ((lane & 31) * 2 + (lane >> 5)) * 16;
   auto issue = [&](int step, int buf) {
     const int st = min(step, n_steps - 1);
     const int id0 = __builtin_amdgcn_readfirstlane(s_ids[2 * st]);
@@ -84,8 +95,8 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
     for (int c = 0; c < kCopies; ++c) {
       const int piece = 4 * c + uwave;
       const int page = piece / kPageKiB, kib = piece % kPageKiB;  // page: 0 = K0, 1 = K1, 2 = V0, 3 = V1
-      const uint8_t* src =
-          page_ptr(pool, layer, page >> 1, (page & 1) ? id1 : id0, g, kPageBytes) + kib * 1024 + lane * 16;
+      const uint8_t* src = page_ptr(pool, layer, page >> 1, (page & 1) ? id1 : id0, g, kPageBytes) + kib * 1024 +
+                           ((page >> 1) ? src_v : src_k);
       __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)(lds + buf * kAStageBytes + piece * 1024), 16, 0, 0);
     }
   };
@@ -126,10 +137,10 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
   }
   // exp(x / sqrt(head_dim)) = exp2(x c)
   const float c2 = (PHD == 128 ? 0.08838834764831845f : 0.125f) * 1.4426950408889634f;
-  // lane offsets inside a stage: K operand (token row col, dim group 2 j + hh) and V operand
-  // (dim row 32 d + col, tokens 4 hh .. and 8 + 4 hh .. of page jj)
+  // lane offsets inside a stage: K operand (operand row col, dim group 2 j + hh) and V operand
+  // (dim row 32 d + col, tokens 8 hh .. 8 hh + 7 of page jj)
   const int koff = (col >> 4) * kPageBytes + (hh * 16 + (col & 15)) * 16;
-  const int voff = 2 * kPageBytes + col * 32 + hh * 8;
+  const int voff = 2 * kPageBytes + lane * 16;
 
   // One key step for both column blocks.
   auto step = [&](int t, const uint8_t* sb) {
@@ -157,7 +168,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
       if (diag || qpos[i] < 0) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int tok = 32 * t + 8 * (e >> 2) + 4 * hh + (e & 3);
+          const int tok = 32 * t + 16 * (e >> 3) + 8 * hh + (e & 7);  // operand row 8 (e / 4) + 4 hh + e % 4 -> tau
           if (tok > qabs[i]) sv[e] = -INFINITY;
         }
       }
@@ -178,7 +189,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
       }
       lrun[i] = lrun[i] * corr + psum;
       // rescale O only when some column's maximum moved (rare after the first steps)
-      if (__builtin_amdgcn_ballot_w64(m_new > mrun[i]) != 0) {
+      if (__builtin_expect(__builtin_amdgcn_ballot_w64(m_new > mrun[i]) != 0, 0)) {
 #pragma unroll
         for (int d = 0; d < PHD / 32; ++d) oacc[i][d] = oacc[i][d] * corr;
       }
@@ -186,10 +197,10 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         v4u pk;
-        pk[0] = pack_h16x2(p[8 * jj + 0], p[8 * jj + 1]);
-        pk[1] = pack_h16x2(p[8 * jj + 2], p[8 * jj + 3]);
-        pk[2] = pack_h16x2(p[8 * jj + 4], p[8 * jj + 5]);
-        pk[3] = pack_h16x2(p[8 * jj + 6], p[8 * jj + 7]);
+        pk[0] = pack_h16x2_inrange(p[8 * jj + 0], p[8 * jj + 1]);  // exp(s - max) lies in [0, 1]
+        pk[1] = pack_h16x2_inrange(p[8 * jj + 2], p[8 * jj + 3]);
+        pk[2] = pack_h16x2_inrange(p[8 * jj + 4], p[8 * jj + 5]);
+        pk[3] = pack_h16x2_inrange(p[8 * jj + 6], p[8 * jj + 7]);
         pf[i][jj] = __builtin_bit_cast(v8bf, pk);
       }
     }
@@ -198,11 +209,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int d = 0; d < PHD / 32; ++d) {
-        const uint8_t* vp = sb + voff + jj * kPageBytes + d * 1024;
-        const uint2 va = *reinterpret_cast<const uint2*>(vp);
-        const uint2 vb = *reinterpret_cast<const uint2*>(vp + 16);
-        const v4u raw = {va.x, va.y, vb.x, vb.y};
-        const v8bf vf = __builtin_bit_cast(v8bf, raw);
+        const v8bf vf = *reinterpret_cast<const v8bf*>(sb + voff + jj * kPageBytes + d * 1024);
 #pragma unroll
         for (int i = 0; i < NCB; ++i)
           oacc[i][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[i][jj], oacc[i][d], 0, 0, 0);

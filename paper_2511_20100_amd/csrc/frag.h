@@ -40,6 +40,12 @@ __device__ __forceinline__ uint32_t pack_h16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// For values known to lie inside the fp16 range (probabilities in [0, 1]): no clamp.
+__device__ __forceinline__ uint32_t pack_h16x2_inrange(float lo, float hi) {
+  const v2h v = {(_Float16)lo, (_Float16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
 __host__ __device__ __forceinline__ size_t act_off(int r, int k, int Rpad) {
   return ((size_t)(k >> 5) * (Rpad >> 4) + (r >> 4)) * 512 + ((((k & 31) >> 3) << 4) + (r & 15)) * 8 + (k & 7);
 }
