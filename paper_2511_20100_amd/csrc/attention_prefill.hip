@@ -43,11 +43,11 @@ __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-constexpr int NCB = 2;    // column blocks per wavefront
-constexpr int QB = 256;   // query positions per workgroup
+constexpr int NCB = 1;    // column blocks per wavefront
+constexpr int QB = 128;   // query columns per workgroup
 
 template <int PHD>
-__global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
+__global__ __launch_bounds__(256, 2) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
                                                            int row_stride, int pos_base, KvPool pool, int layer) {
   constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 or 2 KiB
   constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_prefill32(h16_t* o, const h16_t
   int qpos[NCB], qabs[NCB], qhd[NCB];  // index in the sequence / position among the keys (-1: padding), head
 #pragma unroll
   for (int i = 0; i < NCB; ++i) {
-    const int b = (i == 0) ? uwave : 7 - uwave;
+    const int b = (NCB == 1) ? uwave : (i == 0) ? uwave : 7 - uwave;
     const int c = c0 + 32 * b + col;
     const bool live = c < n_cols;
     const int jh = live ? c / S : 0, pos = c - jh * S;
