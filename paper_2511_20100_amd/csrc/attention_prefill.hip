@@ -26,7 +26,7 @@ namespace bf16 {
 
 namespace {
 
-constexpr int kAStages = 4;
+constexpr int kAStages = 3;
 
 typedef __attribute__((ext_vector_type(16))) float v16f;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -47,7 +47,7 @@ constexpr int NCB = 1;    // column blocks per wavefront
 constexpr int QB = 128;   // query columns per workgroup
 
 template <int PHD>
-__global__ __launch_bounds__(256, 2) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
+__global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
                                                            int row_stride, int pos_base, KvPool pool, int layer) {
   constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 or 2 KiB
   constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
