@@ -1,15 +1,17 @@
 // Causal grouped-query attention of the prefill / scoring pass (head_dim 128 or 64) on the 32x32x16 MFMA.
 //
-// One workgroup per (256 query columns, kv head, sequence).  The columns of a kv head are the
-// (query head of its group, position) pairs, position fastest: with S a multiple of 256 a workgroup holds 256
+// One workgroup per (128 query columns, kv head, sequence).  The columns of a kv head are the
+// (query head of its group, position) pairs, position fastest: with S a multiple of 128 a workgroup holds 128
 // consecutive positions of one query head; with short sequences (the candidate rows of action scoring, small
 // prompts) the G query heads of the group sit side by side in one workgroup and share every K/V step.
-// Eight column blocks of 32; wavefront w takes blocks w and 7 - w.  Every block takes part in every step up to
-// the workgroup's last key (steps beyond a block's own positions are fully masked and add zeros: branching on
-// that made the register allocator spill, which cost more than the ~12 % of MFMAs saved).  The workgroup walks
-// the keys in steps of 32 tokens (two 16-token pages): the four wavefronts copy the two K pages and two V pages
-// of a step (16 KiB at head_dim 128) into a ring of LDS buffers with LDS-direct loads, three steps ahead, and every wavefront
-// reads them from there.  Query j of a sequence sits at position pos_base + j and sees keys 0 .. pos_base + j.
+// Four column blocks of 32, one per wavefront, and three workgroups per CU: a wavefront's chain
+// (K Q^T -> softmax -> V^T P^T) is serial, so the matrix products of one wavefront run under the softmax
+// arithmetic of the others on its SIMD (with two blocks per wavefront and one workgroup per CU the kernel took
+// 1.9 times as long).  The workgroup walks the keys in steps of 32 tokens (two 16-token pages): the four
+// wavefronts copy the two K pages and two V pages of a step (16 KiB at head_dim 128) into a ring of three LDS
+// buffers with LDS-direct loads, two steps ahead, and every wavefront reads them from there; a wavefront skips
+// the arithmetic of steps that lie wholly behind its own columns.  Query j of a sequence sits at position
+// pos_base + j and sees keys 0 .. pos_base + j.
 //
 // Per step and column block:  S^T[token][column] = K Q^T  (8 MFMAs over the 128 dims), online softmax
 // down each column (a column's 32 tokens sit in 16 registers of lanes l and l + 32), then
@@ -124,6 +126,13 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
       qf[i][j] = __builtin_bit_cast(v8bf, raw);
     }
   }
+  // last key step that holds a key some column of this wavefront's block may see (-1: the block is all padding)
+  int my_last = -1;
+  {
+    static_assert(NCB == 1, "one column block per wavefront");
+    const int b0 = c0 + 32 * uwave, b1 = min(b0 + 31, n_cols - 1);
+    if (b0 < n_cols) my_last = (pos_base + ((b0 / S == b1 / S) ? b1 % S : S - 1)) / 32;
+  }
   v16f oacc[NCB][PHD / 32];
   float mrun[NCB], lrun[NCB];
 #pragma unroll
@@ -216,11 +225,11 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
       }
   };
   for (int t = 0; t < n_steps; ++t) {
-    wait_vm<(kAStages - 2) * kCopies>();  // step t landed; t + 1, t + 2 may be in flight
+    wait_vm<(kAStages - 2) * kCopies>();  // step t landed; the later ones may be in flight
     __builtin_amdgcn_s_barrier();
     issue(t + kAStages - 1, (t + kAStages - 1) % kAStages);
     const uint8_t* sb = lds + (t % kAStages) * kAStageBytes;
-    step(t, sb);
+    if (t <= my_last) step(t, sb);  // wavefront-uniform: later steps hold only keys behind this block
   }
   wait_vm<0>();  // the clamped copies past the last step still target this workgroup's LDS
 
