@@ -125,9 +125,10 @@ void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, i
 // h[m, :] += sum_s P[s][m][:] (n_split may be 0); x = bf16(RMSNorm(h; gain)) in tiled layout.
 void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
               h16_t* x, int M, int m_tiles, int d, hipStream_t st);
-// qkv = sum_s P[s][m][:]: rotates q (-> bf16 row-major [T, Hq*hd]) and k, writes k, v into pages.
-void rope_kv_write(h16_t* q, const float* P, int n_split, int ldp, int Mpad_p, int T, int Hq, int Hkv,
-                   const float* cos, const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st);
+// qkv fp32 [T, (Hq + 2 Hkv) hd] (row stride ld), T = n_seqs * S tokens at positions map.pos_base + t % S: rotates q
+// (-> fp16 row-major [T, Hq*hd]) and k, writes k and v into the pages.  map.d_step and map.row_pos must be NULL.
+void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int Hkv, const float* cos,
+                   const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st);
 
 // ---- attention -----------------------------------------------------------------------------
 // Floats of the per-chunk partial results of the decode attention kernel.

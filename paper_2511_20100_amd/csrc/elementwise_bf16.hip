@@ -160,60 +160,105 @@ void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const 
 }
 
 // ---------------------------------------------------------------- rotary embedding + KV write
-// qkv[m, :] = sum_s P[s][m][:] (fp32).  q heads are rotated and stored bf16 row-major; k heads
-// are rotated and scattered into the K page ([dim/8][token][dim%8]); v into the V page
-// ([dim][token]).  Pairs are (i, i + HD / 2) of the head.
+// qkv [T, (Hq + 2 Hkv) HD] fp32 (row stride ld).  q heads are rotated and stored fp16 row-major [T, Hq HD];
+// k heads are rotated and written into the K pages ([dim/8][token][dim%8]); v into the V pages ([dim][token]).
+// Rotation pairs are (i, i + HD / 2) of a head.
+//
+// One workgroup per (page, sequence): the up to 16 tokens of the sequence whose positions fall into one page.
+// Thread (token, quad) rotates 4 + 4 values of a head at a time.  The K and V values of a kv head are collected
+// token-major in LDS and leave as the page's 16-byte pieces (one per thread, 4 KiB contiguous at HD = 128); a
+// page that the launch fills only partly is written value by value for its live slots instead.
 template <int HD>
-__global__ __launch_bounds__(256) void k_rope_kv_write(h16_t* q, const float* P, int n_split, int ldp,
-                                                       int Mpad_p, int Hq, int Hkv, const float* cos,
-                                                       const float* sin, TokMap map, KvPool pool, int layer) {
-  constexpr int HALF = HD / 2;
-  const int t = blockIdx.x;
-  const int pos = tok_pos(map, t);
-  const int row = tok_seq(map, t) * map.row_stride;
-  const int page = pool.page_table[(size_t)row * pool.max_pages + pos / kPageTokens];
-  const int slot = pos % kPageTokens;
+__global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv, int ld, int S, int Hq, int Hkv,
+                                                      const float* cos, const float* sin, int row_stride, int pos_base,
+                                                      KvPool pool, int layer) {
+  constexpr int HALF = HD / 2, QUADS = HALF / 4;  // quads of rotation pairs per head
+  constexpr int ROW = HD + 8;                     // LDS row stride in halfs: 16-byte reads down a column stay conflict-free
+  __shared__ __attribute__((aligned(16))) h16_t k_s[kPageTokens][ROW];
+  __shared__ __attribute__((aligned(16))) h16_t v_s[kPageTokens][ROW];
+  const int seq = blockIdx.y;
+  const int pg = pos_base / kPageTokens + blockIdx.x;          // page index of the sequence
+  const int p_lo = max(pg * kPageTokens, pos_base), p_hi = min((pg + 1) * kPageTokens, pos_base + S);
+  const bool whole = p_hi - p_lo == kPageTokens;
+  const int page = pool.page_table[(size_t)seq * row_stride * pool.max_pages + pg];
   h16_t* kv = (h16_t*)pool.base;
   const size_t page_elems = (size_t)kPageTokens * HD;
-  for (int e = threadIdx.x; e < (Hq + Hkv) * HALF; e += blockDim.x) {
-    const int head = e / HALF, i = e % HALF;
-    float a = 0.f, b = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < n_split; ++s) {
-      const float* pr = P + ((size_t)s * Mpad_p + t) * ldp + (size_t)head * HD;
-      a += pr[i];
-      b += pr[i + HALF];
+  const int tid = threadIdx.x;
+  // ---- rotation of the q and k heads: unit = (slot, quad)
+  for (int head = 0; head < Hq + Hkv; ++head) {
+    for (int u = tid; u < kPageTokens * QUADS; u += 256) {
+      const int slot = u / QUADS, i = (u % QUADS) * 4;
+      const int pos = pg * kPageTokens + slot;
+      if (pos < p_lo || pos >= p_hi) continue;
+      const size_t t = (size_t)seq * S + (pos - pos_base);
+      const float* pr = qkv + t * ld + (size_t)head * HD;
+      const v4f a = *reinterpret_cast<const v4f*>(pr + i), b = *reinterpret_cast<const v4f*>(pr + i + HALF);
+      const v4f c = *reinterpret_cast<const v4f*>(cos + (size_t)pos * HALF + i);
+      const v4f sn = *reinterpret_cast<const v4f*>(sin + (size_t)pos * HALF + i);
+      const v4f ra = a * c - b * sn, rb = b * c + a * sn;
+      uint2 lo, hi;
+      lo.x = pack_h16x2(ra[0], ra[1]); lo.y = pack_h16x2(ra[2], ra[3]);
+      hi.x = pack_h16x2(rb[0], rb[1]); hi.y = pack_h16x2(rb[2], rb[3]);
+      if (head < Hq) {
+        h16_t* qr = q + t * Hq * HD + (size_t)head * HD;
+        *reinterpret_cast<uint2*>(qr + i) = lo;
+        *reinterpret_cast<uint2*>(qr + i + HALF) = hi;
+      } else {
+        *reinterpret_cast<uint2*>(&k_s[slot][i]) = lo;
+        *reinterpret_cast<uint2*>(&k_s[slot][i + HALF]) = hi;
+      }
     }
-    const float c = cos[(size_t)pos * HALF + i], sn = sin[(size_t)pos * HALF + i];
-    const float ra = a * c - b * sn, rb = b * c + a * sn;
-    if (head < Hq) {
-      h16_t* qr = q + (size_t)t * Hq * HD + (size_t)head * HD;
-      qr[i] = f32_to_h16(ra);
-      qr[i + HALF] = f32_to_h16(rb);
-    } else {
-      const int g = head - Hq;
-      h16_t* kp = kv + ((((size_t)layer * 2 + 0) * pool.n_pages + page) * pool.n_kv_heads + g) * page_elems;
-      const int c0 = i, c1 = i + HALF;
-      kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(ra);
-      kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(rb);
+    if (head < Hq) continue;
+    // ---- a kv head: its v values next to the rotated k values, then both pages
+    const int g = head - Hq;
+    for (int u = tid; u < kPageTokens * (HD / 4); u += 256) {
+      const int slot = u / (HD / 4), i = (u % (HD / 4)) * 4;
+      const int pos = pg * kPageTokens + slot;
+      if (pos < p_lo || pos >= p_hi) continue;
+      const size_t t = (size_t)seq * S + (pos - pos_base);
+      const v4f v = *reinterpret_cast<const v4f*>(qkv + t * ld + (size_t)(Hq + Hkv + g) * HD + i);
+      uint2 pk;
+      pk.x = pack_h16x2(v[0], v[1]); pk.y = pack_h16x2(v[2], v[3]);
+      *reinterpret_cast<uint2*>(&v_s[slot][i]) = pk;
     }
-  }
-  for (int e = threadIdx.x; e < Hkv * HD; e += blockDim.x) {
-    const int g = e / HD, c = e % HD;
-    float v = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < n_split; ++s) v += P[((size_t)s * Mpad_p + t) * ldp + (size_t)(Hq + Hkv) * HD + e];
+    __syncthreads();
+    h16_t* kp = kv + ((((size_t)layer * 2 + 0) * pool.n_pages + page) * pool.n_kv_heads + g) * page_elems;
     h16_t* vp = kv + ((((size_t)layer * 2 + 1) * pool.n_pages + page) * pool.n_kv_heads + g) * page_elems;
-    vp[c * kPageTokens + slot] = f32_to_h16(v);
+    if (whole) {
+      // K piece (dim group dg, token): 8 dims of one token.  V piece (dim c, token half th): 8 tokens of one dim.
+      for (int u = tid; u < kPageTokens * HD / 8; u += 256) {
+        const int dg = u / kPageTokens, tok = u % kPageTokens;
+        *reinterpret_cast<v4u*>(kp + (size_t)u * 8) = *reinterpret_cast<const v4u*>(&k_s[tok][dg * 8]);
+        const int c = u >> 1, th = u & 1;
+        v4u col;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          col[e] = (uint32_t)v_s[th * 8 + 2 * e][c] | ((uint32_t)v_s[th * 8 + 2 * e + 1][c] << 16);
+        *reinterpret_cast<v4u*>(vp + (size_t)u * 8) = col;
+      }
+    } else {
+      for (int u = tid; u < kPageTokens * HD; u += 256) {
+        const int slot = u / HD, c = u % HD;
+        const int pos = pg * kPageTokens + slot;
+        if (pos < p_lo || pos >= p_hi) continue;
+        kp[(c >> 3) * 128 + slot * 8 + (c & 7)] = k_s[slot][c];
+        vp[c * kPageTokens + slot] = v_s[slot][c];
+      }
+    }
+    __syncthreads();  // the next kv head reuses k_s / v_s
   }
 }
-void rope_kv_write(h16_t* q, const float* P, int n_split, int ldp, int Mpad_p, int T, int Hq, int Hkv,
-                   const float* cos, const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st) {
+void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int Hkv, const float* cos,
+                   const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st) {
   if (T == 0) return;
+  // pages that the positions pos_base .. pos_base + S - 1 of a sequence touch
+  const int n_pg = (map.pos_base + S - 1) / kPageTokens - map.pos_base / kPageTokens + 1;
+  const dim3 grid(n_pg, T / S);
   if (pool.head_dim == 64)
-    k_rope_kv_write<64><<<T, 256, 0, st>>>(q, P, n_split, ldp, Mpad_p, Hq, Hkv, cos, sin, map, pool, layer);
+    k_rope_kv_page<64><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool, layer);
   else
-    k_rope_kv_write<128><<<T, 256, 0, st>>>(q, P, n_split, ldp, Mpad_p, Hq, Hkv, cos, sin, map, pool, layer);
+    k_rope_kv_page<128><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool,
+                                              layer);
 }
 
 }  // namespace bf16

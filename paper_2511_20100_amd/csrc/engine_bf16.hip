@@ -308,7 +308,7 @@ void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, fl
     const LayerWeights& L = w->layers[l];
     const int kvl = l * layer_stride;
     bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, st);
-    bf16::rope_kv_write(qb, qkv, 1, D.nqkv, 0, T, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, st);
+    bf16::rope_kv_write(qb, qkv, D.nqkv, T, S, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, st);
     bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, st);
     bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, st);
     bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, st);
