@@ -59,6 +59,13 @@ struct DecGemmArgs {
   const int* d_step;
   int ksplit;            // PARTIAL: K splits (grid.y); out_f32 = partial sums [ksplit][m_tiles*16][ld_out]
   float* rs_out;         // PARTIAL: 1/rms of every row of the state described by ss_cur
+  // RESID with n_xchunks > 1 (O projection behind a context-split attention): Xt holds n_xchunks operands
+  // x_chunk_stride elements apart, each the attention output over one chunk of the context, normalised by itself;
+  // chunk_ml [M][k_tiles / head_tiles][n_xchunks][2] = (running maximum, sum) of row, head, chunk.  The product is
+  // taken head by head and chunk by chunk and the pieces are added with their softmax weights.
+  int n_xchunks, head_tiles;
+  size_t x_chunk_stride;
+  const float* chunk_ml;
 };
 enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3, DEC_PARTIAL = 4 };
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
@@ -79,9 +86,10 @@ struct AttnDecArgs {
   KvPool pool;
   int chunk_pages, n_chunks, m_tiles;
   int share;             // consecutive sequences that share prompt pages (samples per prompt); B % share == 0
-  float* part;           // [B, Hkv, n_chunks, G * 130]
-  int* counters;         // [B * Hkv], zero between launches
-  h16_t* o;              // tiled fp16 [Hq * 128 (k), m_tiles * 16]
+  h16_t* o;              // tiled fp16 [Hq * hd (k), m_tiles * 16], one per chunk, o_chunk_stride elements apart:
+  size_t o_chunk_stride; //   the output over the chunk's keys alone, normalised by the chunk's own sum
+  float* ml;             // [B, Hq, n_chunks, 2]: running maximum and sum of (sequence, head, chunk); the consumer
+                         //   (O projection) combines the chunks.  Not written when n_chunks == 1.
 };
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st);
 
@@ -132,7 +140,6 @@ void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int
 
 // ---- attention -----------------------------------------------------------------------------
 // Floats of the per-chunk partial results of the decode attention kernel.
-size_t attn_part_floats(int B, int Hkv, int G, int n_chunks);
 // Prefill / scoring: causal attention of every token of T = n_seqs * S over its own sequence.
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
                        TokMap map, KvPool pool, int layer, hipStream_t st);

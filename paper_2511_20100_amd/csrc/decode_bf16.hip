@@ -153,8 +153,11 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   }
   const int per_wave = (max(kend - kbeg, 0) + WAVES - 1) / WAVES;
   const int k0 = kbeg + wave * per_wave, k1 = min(kend, k0 + per_wave);
+  // O projection behind a context-split attention: the operand comes in chunks that are combined below
+  bool chunked = false;
+  if constexpr (EPI == DEPI_RESID && NB == 1 && WAVES == 8 && MB <= 4) chunked = a.n_xchunks > 1;  // workgroup-uniform
   DecStream<NB, MB, PFW, PFX> stream;
-  stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, k1, lane);
+  stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, chunked ? k0 : k1, lane);
 #pragma unroll
   for (int u = 0; u < BT; ++u) {
     sa += va[u];
@@ -189,6 +192,69 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
   stream.run(acc);
+  if constexpr (EPI == DEPI_RESID && NB == 1 && WAVES == 8 && MB <= 4) {
+    if (chunked) {
+      // out[n][row] = sum_head sum_chunk share(row, head, chunk) * (W[n, head] . o_chunk[head, row]), where o_chunk is
+      // the attention output over the chunk's keys normalised by the chunk's own sum l, and
+      // share = l exp(m - max_c m) / sum_c l exp(m - max_c m).  Wavefront w takes heads w, w + WAVES, ...; everything
+      // a head needs (its weight tiles, the operand tiles of every chunk, the chunk statistics) is requested at once.
+      constexpr int NCM = MB >= 4 ? 2 : MB == 2 ? 4 : 8;  // chunks at most (the host keeps MB * chunks <= 8)
+      const int HT = a.head_tiles, n_heads = a.k_tiles / HT, NC = a.n_xchunks;
+      const int col = lane & 15;
+      const h16_t* wp = a.Wt + (size_t)min(nt0, a.n_tiles - 1) * a.k_tiles * 512 + lane * 8;
+      for (int j = wave; j < n_heads; j += WAVES) {
+        v8bf wf[4], xf[NCM][4][MB];
+        float cm[NCM][MB], cl[NCM][MB];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) wf[t] = load_frag(wp + (size_t)(j * HT + min(t, HT - 1)) * 512, 0);
+#pragma unroll
+        for (int c = 0; c < NCM; ++c)
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            const bool live = c < NC && mb * 16 + col < a.M;
+            const float* ml = a.chunk_ml + (((size_t)(mb * 16 + col) * n_heads + j) * NC + c) * 2;
+            cm[c][mb] = live ? ml[0] : -INFINITY;
+            cl[c][mb] = live ? ml[1] : 0.f;
+          }
+#pragma unroll
+        for (int c = 0; c < NCM; ++c) {
+          const h16_t* xp = a.Xt + (size_t)min(c, NC - 1) * a.x_chunk_stride + lane * 8;
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+              xf[c][t][mb] =
+                  load_frag(xp + ((size_t)(j * HT + min(t, HT - 1)) * a.m_tiles + min(mb, a.m_tiles - 1)) * 512, 0);
+        }
+        float mx[MB], den[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          mx[mb] = cm[0][mb];
+#pragma unroll
+          for (int c = 1; c < NCM; ++c) mx[mb] = fmaxf(mx[mb], cm[c][mb]);
+          den[mb] = 0.f;
+#pragma unroll
+          for (int c = 0; c < NCM; ++c) {
+            cl[c][mb] = (cl[c][mb] > 0.f) ? cl[c][mb] * expf(cm[c][mb] - mx[mb]) : 0.f;  // un-normalised share
+            den[mb] += cl[c][mb];
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < NCM; ++c) {
+          if (c >= NC) break;
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            v4f part = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+              if (t < HT) part = mfma16(wf[t], xf[c][t][mb], part);
+            const float share = (den[mb] > 0.f) ? cl[c][mb] / den[mb] : 0.f;
+            acc[0][mb] = acc[0][mb] + part * share;
+          }
+        }
+      }
+    }
+  }
   // Sum over the K slices: every wavefront publishes its accumulators; wavefront w then adds the WAVES
   // slices of token tiles w, w + WAVES, ... in index order and runs the epilogue for those tokens.
 #pragma unroll
@@ -328,7 +394,9 @@ static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
   if constexpr (MB > 4) {
     launch_dec_t<1, MB, 8, 2, 2, 1>(a, epi, st);
   } else {
-    if (a.k_tiles >= 48) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st);
+    // 16 wavefronts split long K ranges; the chunked O projection keeps 8, which leaves a wavefront the registers
+    // to hold a whole head's operands of every chunk at once
+    if (a.k_tiles >= 48 && !(epi == DEPI_RESID && a.n_xchunks > 1)) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st);
     else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st);
   }
 }
@@ -522,9 +590,12 @@ void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, 
 // One workgroup per (sequence, kv head, context chunk).  Prologue: rotate the G query heads of the
 // row (fp32 qkv -> fp16, through LDS); the workgroup whose chunk holds the current position also
 // rotates the new key, converts the new value and stores both into their page before attending.
-// Epilogue: the four wavefronts' partial (max, sum, O) are merged through LDS; with several
-// active chunks each workgroup publishes its partial and the last one to arrive (device-scope
-// counter) merges them in chunk order, so the result does not depend on arrival order.
+// Epilogue: the wavefronts' partial (max, sum, O) are merged through LDS and the workgroup writes
+// the output over ITS chunk of the context, normalised by the chunk's own sum, together with the
+// chunk's (max, sum) per head.  Chunks are combined by the consumer (the O projection weights the
+// per-chunk products by their softmax shares): no cross-workgroup hand-over inside this kernel.
+// (A merge by the last workgroup to arrive needs device-scope fences around an atomic counter,
+// which cost more than the split saved.)
 template <int HD>
 __device__ __forceinline__ h16_t* dec_page(const KvPool& pool, int layer, int which, int page, int g) {
   return (h16_t*)pool.base +
@@ -610,7 +681,6 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   __shared__ float s_o[AW][AGMAX][DHD + 1];
   __shared__ float s_m[AW][16], s_l[AW][16];
   __shared__ int s_table[ATAB];
-  __shared__ int s_last;
   // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
   // The `share` sequences that sample from one prompt read the same prompt pages, so their
   // workgroups (for one kv head) are given launch indices that are congruent modulo 8: the pages
@@ -655,8 +725,21 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   const int pos = pos0 + step;
   const int n_ctx_pages = pos / kPageTokens + 1;
   const int p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
-  if (p_lo >= p_hi) return;
-  const int n_act = (n_ctx_pages + a.chunk_pages - 1) / a.chunk_pages;
+  if (p_lo >= p_hi) {
+    // this chunk lies beyond the context: it contributes nothing, which its consumer learns from a zero sum;
+    // the operand slice is cleared so that stale bits (possibly NaN patterns) never meet a zero weight
+    if (tid < G * (DHD / 8)) {
+      const int c = tid / (DHD / 8), d0 = (tid % (DHD / 8)) * 8;
+      *reinterpret_cast<v4u*>(a.o + chunk * a.o_chunk_stride + act_off(b, (g * G + c) * DHD + d0, a.m_tiles * 16)) =
+          v4u{0u, 0u, 0u, 0u};
+      if (d0 == 0) {
+        float* ml = a.ml + (((size_t)b * Hq + g * G + c) * a.n_chunks + chunk) * 2;
+        ml[0] = -INFINITY;
+        ml[1] = 0.f;
+      }
+    }
+    return;
+  }
   const float* cs = a.cos + (size_t)pos * (DHD / 2);
   const float* sn = a.sin + (size_t)pos * (DHD / 2);
   if (qj < G && qi < HALF) {
@@ -742,56 +825,18 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     }
   }
   const int Mpad = a.m_tiles * 16;
-  if (n_act > 1) {
-    const size_t stride = (size_t)G * (DHD + 2);
-    float* base = a.part + ((size_t)b * Hkv + g) * a.n_chunks * stride;
-    if (owner) {
-      float* out = base + chunk * stride;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) out[(size_t)c * DHD + d0 + e] = acc[e];
-      if (d0 == 0) {
-        out[G * DHD + c] = mm;
-        out[G * DHD + G + c] = ll;
-      }
-    }
-    __syncthreads();  // every wavefront's partial stores have completed (workgroup scope)
-    if (tid == 0) {
-      __threadfence();  // release them at device scope before announcing arrival
-      const int old = atomicAdd(a.counters + b * Hkv + g, 1);
-      s_last = (old == n_act - 1);
-      if (s_last) {
-        __threadfence();  // acquire the other chunks' partials
-        a.counters[b * Hkv + g] = 0;  // ready for the next launch
-      }
-    }
-    __syncthreads();
-    if (!s_last) return;
-    if (owner) {
-      mm = -INFINITY;
-      for (int k = 0; k < n_act; ++k) mm = fmaxf(mm, base[k * stride + G * DHD + c]);
-      ll = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-      for (int k = 0; k < n_act; ++k) {
-        const float f = expf(base[k * stride + G * DHD + c] - mm);
-        ll += f * base[k * stride + G * DHD + G + c];
-        const float* src = base + k * stride + (size_t)c * DHD + d0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += f * src[e];
-      }
-    }
-  }
   if (owner) {
-    const float inv = 1.0f / ll;
+    const float inv = 1.0f / ll;  // every page of an active chunk holds at least one visible key
     v4u pk;
 #pragma unroll
     for (int e = 0; e < 4; ++e) pk[e] = pack_h16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
-    *reinterpret_cast<v4u*>(a.o + act_off(b, (g * G + c) * DHD + d0, Mpad)) = pk;
+    *reinterpret_cast<v4u*>(a.o + chunk * a.o_chunk_stride + act_off(b, (g * G + c) * DHD + d0, Mpad)) = pk;
+    if (a.n_chunks > 1 && d0 == 0) {
+      float* ml = a.ml + (((size_t)b * Hq + g * G + c) * a.n_chunks + chunk) * 2;
+      ml[0] = mm;
+      ml[1] = ll;
+    }
   }
-}
-
-size_t attn_part_floats(int B, int Hkv, int G, int n_chunks) {
-  return (size_t)B * Hkv * n_chunks * G * (128 + 2);  // sized for the larger head_dim
 }
 
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {

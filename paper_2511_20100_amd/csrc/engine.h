@@ -61,13 +61,13 @@ struct RolloutPlan {
   float* logits;  // fp32 path: [B, V]
   // bf16 path scratch
   float* part;        // split-K partial sums
-  float* attn_part;   // decode-attention partial (m, l, o) per context split
+  void* o_chunks;     // decode-attention output per context chunk: n_chunks tiled fp16 operands [Hq*hd, bt*16]
+  float* attn_ml;     // (max, sum) per (sequence, head, chunk) for the O projection to combine the chunks
   float* lm_part;     // LM-head per-tile partial reductions
   void* qb;           // rotated queries, bf16 row-major [Tmax, Hq*hd]
   void* ctl;          // per-call sampling parameters (device copy)
   float* ssA;         // per-tile sums of squares of the residual rows (two generations)
   float* ssB;
-  int* attn_counters; // arrival counters of the decode-attention context chunks
   float* rs_buf;      // 1/rms per row, handed from the split-K down projection to its reduction
   int chunk_pages, n_chunks;       // decode-attention context split
   int ks_qkv, ks_o, ks_down;       // split-K factors of the decode GEMMs

@@ -249,27 +249,28 @@ int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob,
 // ======================================================================================
 void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) {
   const Dims D = dims_of(w);
-  const int G = D.Hq / D.Hkv;
   p.ks_qkv = choose_ksplit(D.nt_qkv, D.kt_d, p.bt);
   p.ks_o = choose_ksplit(D.nt_d, D.kt_nq, p.bt);
   p.ks_down = choose_ksplit(D.nt_d, D.kt_F, p.bt);
-  // context split of the decode attention, only for small batches: the cross-workgroup merge costs
-  // more than it gains once there are about 128 (sequence, kv head) workgroups of 8 wavefronts
+  // context split of the decode attention for small batches, up to about 128 workgroups of 8 wavefronts (beyond
+  // that the attention kernel's fixed part dominates and the split only costs the O projection, which combines
+  // the chunks, a second operand: measured at batch 64 with 2 kv heads)
   const int want = std::max(1, 128 / std::max(1, p.B * D.Hkv));
-  p.n_chunks = std::max(1, std::min(want, (p.max_pages + 7) / 8));
+  const int mb = p.bt <= 1 ? 1 : p.bt <= 2 ? 2 : p.bt <= 4 ? 4 : 8;  // row tiles of the decode GEMM instantiation
+  p.n_chunks = std::max(1, std::min({want, (p.max_pages + 7) / 8, 8 / mb}));  // the O projection holds mb * chunks <= 8
   p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;
   p.chunk_pages = std::min(p.chunk_pages, 512);  // page ids of a chunk are staged in LDS
   p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
   const size_t Mpad = (size_t)p.bt * 16;
   const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;
   p.part = cv.take<float>(part);
-  p.attn_part = cv.take<float>(bf16::attn_part_floats(p.B, D.Hkv, G, p.n_chunks));
+  p.o_chunks = cv.take<h16_t>((size_t)p.n_chunks * D.nq * Mpad);
+  p.attn_ml = cv.take<float>((size_t)p.B * D.Hq * p.n_chunks * 2);
   p.lm_part = cv.take<float>((size_t)((D.nt_V + 1) / 2) * p.B * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
   p.ctl = cv.take<bf16::SampleCtl>(1);
   p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
   p.ssB = cv.take<float>((size_t)D.nt_d * Mpad);
-  p.attn_counters = cv.take<int>((size_t)p.B * D.Hkv);
   p.rs_buf = cv.take<float>(Mpad);
 }
 
@@ -348,12 +349,15 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     bf16::AttnDecArgs at{};
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
     at.pos_base = pos_base; at.row_pos = p.ragged ? p.row_pos : nullptr; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
-    at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples; at.part = p.attn_part; at.counters = p.attn_counters; at.o = o;
+    at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples;
+    at.o = (h16_t*)p.o_chunks; at.o_chunk_stride = (size_t)D.nq * bt * 16; at.ml = p.attn_ml;
     mark(MTMC_KERNEL_ATTENTION);
     bf16::attention_dec(at, B, st);
     mark(MTMC_KERNEL_ATTENTION);
     bf16::DecGemmArgs r1 = g;
-    r1.Wt = (const h16_t*)L.wo; r1.Xt = o; r1.n_tiles = D.nt_d; r1.k_tiles = D.kt_nq;
+    r1.Wt = (const h16_t*)L.wo; r1.Xt = (const h16_t*)p.o_chunks; r1.n_tiles = D.nt_d; r1.k_tiles = D.kt_nq;
+    r1.n_xchunks = p.n_chunks; r1.head_tiles = c.head_dim / 32; r1.x_chunk_stride = at.o_chunk_stride;
+    r1.chunk_ml = p.attn_ml;
     r1.ss_cur = ss[cur]; r1.out_f32 = h; r1.ld_out = D.d; r1.out_h16 = x; r1.ss_out = ss[cur ^ 1]; r1.gain = L.ffn_norm;
     bf16::gemm_dec(r1, bf16::DEC_RESID, st);
     old = cur; cur ^= 1;
@@ -467,7 +471,6 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
     }
     launch_set_int(p.d_step, 0, st);
-    launch_fill_u32((uint32_t*)p.attn_counters, 0u, (size_t)p.B * D.Hkv, st);
     // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
     launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
     // ---- prefill, whole prompts per chunk; a prompt's pages are those of its first sample
