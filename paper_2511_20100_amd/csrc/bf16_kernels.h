@@ -74,6 +74,8 @@ void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);
 int dec_wide_nb(int m_tiles);
 void embed_dec(float* h, const int* ids, int B, const bf16_t* E, int d, int vocab, int* err_flag, const float* gain,
                float eps, h16_t* x, int m_tiles, float* ss_out, hipStream_t st);
+// Merges the sampler partials of a step, writes the outputs of step *d_step and advances *d_step (d_step[1] is the
+// kernel's arrival counter: zero before the first launch, left at zero by every launch).
 void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,
                   hipStream_t st);
 struct AttnDecArgs {

@@ -362,7 +362,8 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
     }
     if (lane < 16 && m < a.M) {
-      DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)blockIdx.x * a.M + m;
+      // row-major per token row, so that the merge reads a row's partials as one contiguous run
+      DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)m * gridDim.x + blockIdx.x;
       p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
     }
   }
@@ -540,10 +541,21 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
   Lse lse = lse_empty();
   float by = -INFINITY, bz = 0.f;
   int bi = 0x7fffffff;
-  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
-    const DecSamplePartial p = part[(size_t)g * M + b];
-    lse = lse_merge(lse, Lse{p.m, p.s});
-    if (p.y > by || (p.y == by && p.idx < bi)) { by = p.y; bi = p.idx; bz = p.zt; }
+  // batches of independent loads (a partial per iteration would serialise one memory round trip each)
+  constexpr int kBatch = 5;
+  for (int g0 = threadIdx.x; g0 < n_groups; g0 += kBatch * blockDim.x) {
+    DecSamplePartial p[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int g = g0 + u * blockDim.x;
+      p[u] = part[(size_t)b * n_groups + min(g, n_groups - 1)];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (g0 + u * (int)blockDim.x >= n_groups) break;
+      lse = lse_merge(lse, Lse{p[u].m, p[u].s});
+      if (p[u].y > by || (p[u].y == by && p[u].idx < bi)) { by = p[u].y; bi = p[u].idx; bz = p[u].zt; }
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -577,6 +589,13 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
     cur_ids[b] = tok;
     ctl.out_ids[(size_t)b * ctl.max_new + step] = tok;
     ctl.out_logprobs[(size_t)b * ctl.max_new + step] = lp;
+    // the last row to get here advances the step counter: by then every row has read it (d_step[1] counts
+    // arrivals and is left at zero for the next launch)
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    if (atomicAdd(d_step + 1, 1) == M - 1) {
+      d_step[1] = 0;
+      d_step[0] = step + 1;
+    }
   }
 }
 void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,

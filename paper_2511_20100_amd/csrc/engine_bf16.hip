@@ -471,6 +471,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
     }
     launch_set_int(p.d_step, 0, st);
+    launch_set_int(p.d_step + 1, 0, st);  // arrival counter of the sampler merge
     // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
     launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
     // ---- prefill, whole prompts per chunk; a prompt's pages are those of its first sample
@@ -505,8 +506,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       lm.ctl = (const bf16::SampleCtl*)p.ctl; lm.d_step = p.d_step;
       bf16::gemm_dec(lm, bf16::DEC_SAMPLE, s);
       const int groups = (D.nt_V + bf16::dec_wide_nb(gp.bt) - 1) / bf16::dec_wide_nb(gp.bt);
-      bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, s);
-      launch_add_int(p.d_step, 1, s);
+      bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, s);  // also ++*d_step
     };
     auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) {
       const float *ss_cur = nullptr, *ss_old = nullptr;
