@@ -19,6 +19,7 @@ CASES = [
     ("f32-page-aligned", inputs.TINY, 0.02, LOGP_TOL_F32, 2, 33, 4, 20, 1, False),  # state fills whole pages
     ("f32-one-token-state", inputs.TINY, 0.02, LOGP_TOL_F32, 2, 1, 3, 5, 1, True),  # nothing to prefill
     ("f32-short-state", inputs.TINY, 0.02, LOGP_TOL_F32, 2, 9, 6, 3, 1, True),      # state shorter than a page
+    ("f32-chunked", inputs.TINY, 0.02, LOGP_TOL_F32, 5, 2000, 10, 170, 1, False),   # states and candidate rows in 2 chunks each
     ("bf16-ragged", SMALL, 0.05, LOGP_TOL_BF16, 3, 37, 5, 7, 0, False),
     ("bf16-long-actions", SMALL, 0.05, LOGP_TOL_BF16, 2, 70, 3, 40, 1, True),      # candidates span several pages
     ("bf16-gqa6-many", GQA6, 0.05, LOGP_TOL_BF16, 4, 48, 16, 6, 1, False),
@@ -38,11 +39,11 @@ def lib():
 @pytest.mark.parametrize("name,cfg,std,tol,n_states,P,K,A,min_len,normalize", CASES, ids=[c[0] for c in CASES])
 def test_actions_match_oracle(lib, name, cfg, std, tol, n_states, P, K, A, min_len, normalize):
     w = inputs.make_weights(cfg, seed=0, std=std)
-    handle = lib.mtmc_weights_create(lib.make_config(cfg, 512), w.blob())
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, max(512, P + A)), w.blob())
     try:
         states = inputs.make_prompts(n_states, P, cfg.vocab, seed=21)
         actions, lens = inputs.make_actions(n_states, K, A, cfg.vocab, seed=22, min_len=min_len)
-        rep = check_actions(handle, w, states, actions, lens, normalize=normalize, max_positions=512, tol=tol,
+        rep = check_actions(handle, w, states, actions, lens, normalize=normalize, max_positions=max(512, P + A), tol=tol,
                             label=name)
         print(name, "token err", rep["max_token_err"], "action err", rep["max_action_err"], "policy err",
               rep["max_policy_err"])
