@@ -107,17 +107,34 @@ __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int 
   }
 }
 // Large-batch form without partial sums: one workgroup per tile of 16 rows, 16 threads per row.  The
-// normalised row tile is assembled in LDS in the fragment layout and leaves as whole 1 KiB blocks
-// (the per-row kernel above writes 16 bytes of every 256: sixteen workgroups share each cache line).
+// normalised row tile is collected in LDS (row-major, rows 16 bytes longer than d values so that both the
+// row-wise writes and the column-wise reads below are free of bank conflicts) and leaves as whole 1 KiB blocks
+// of the fragment layout (the per-row kernel above writes 16 bytes of every 256: sixteen workgroups share
+// each cache line).
 __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h, const float* __restrict__ gain,
                                                      float eps, h16_t* x, int M, int m_tiles, int d) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t xs[];  // d / 32 blocks of 1 KiB
+  extern __shared__ __attribute__((aligned(16))) uint8_t xs[];  // 16 rows of 2 d + 16 bytes
+  const int row_bytes = 2 * d + 16;
   const int mt = blockIdx.x, r = threadIdx.x >> 4, sub = threadIdx.x & 15;
   const int m = mt * 16 + r;
   const bool valid = m < M;
   const float* hr = h + (size_t)min(m, M - 1) * d;
+  // the row is read once: up to kKeep chunks of 8 values per thread stay in registers between the two passes
+  constexpr int kKeep = 12;  // d <= 1536; wider rows read their tail a second time (from cache)
+  v4f ka[kKeep], kb[kKeep];
   float ss = 0.f;
-  for (int k = sub * 8; k < d; k += 128) {
+#pragma unroll
+  for (int it = 0; it < kKeep; ++it) {
+    const int k = sub * 8 + it * 128;
+    ka[it] = kb[it] = v4f{0.f, 0.f, 0.f, 0.f};
+    if (k < d) {
+      ka[it] = *reinterpret_cast<const v4f*>(hr + k);
+      kb[it] = *reinterpret_cast<const v4f*>(hr + k + 4);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ss += ka[it][e] * ka[it][e] + kb[it][e] * kb[it][e];
+  }
+  for (int k = sub * 8 + kKeep * 128; k < d; k += 128) {
     const v4f a = *reinterpret_cast<const v4f*>(hr + k), b = *reinterpret_cast<const v4f*>(hr + k + 4);
 #pragma unroll
     for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
@@ -125,35 +142,42 @@ __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h
 #pragma unroll
   for (int o = 1; o < 16; o <<= 1) ss += __shfl_xor(ss, o, 64);  // the 16 threads of a row are adjacent lanes
   const float rr = valid ? 1.0f / sqrtf(ss / (float)d + eps) : 0.f;  // padding rows become zeros
-  for (int k = sub * 8; k < d; k += 128) {
-    const v4f a = *reinterpret_cast<const v4f*>(hr + k), b = *reinterpret_cast<const v4f*>(hr + k + 4);
+  auto emit = [&](int k, const v4f& a, const v4f& b) {
     const v4f ga = *reinterpret_cast<const v4f*>(gain + k), gb = *reinterpret_cast<const v4f*>(gain + k + 4);
     v4u pk;
     pk[0] = pack_h16x2(a[0] * rr * ga[0], a[1] * rr * ga[1]);
     pk[1] = pack_h16x2(a[2] * rr * ga[2], a[3] * rr * ga[3]);
     pk[2] = pack_h16x2(b[0] * rr * gb[0], b[1] * rr * gb[1]);
     pk[3] = pack_h16x2(b[2] * rr * gb[2], b[3] * rr * gb[3]);
-    *reinterpret_cast<v4u*>(xs + (k >> 5) * 1024 + ((((k & 31) >> 3) << 4) + r) * 16) = pk;
+    *reinterpret_cast<v4u*>(xs + r * row_bytes + k * 2) = pk;
+  };
+#pragma unroll
+  for (int it = 0; it < kKeep; ++it) {
+    const int k = sub * 8 + it * 128;
+    if (k < d) emit(k, ka[it], kb[it]);
   }
+  for (int k = sub * 8 + kKeep * 128; k < d; k += 128)
+    emit(k, *reinterpret_cast<const v4f*>(hr + k), *reinterpret_cast<const v4f*>(hr + k + 4));
   __syncthreads();
+  // block kt of the fragment layout: piece (dim group dg, row) = 8 values of one row, at offset 16 (16 dg + row)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint8_t* dst = reinterpret_cast<uint8_t*>(x);
   for (int kt = wave; kt < d / 32; kt += 4)
     *reinterpret_cast<v4u*>(dst + ((size_t)kt * m_tiles + mt) * 1024 + lane * 16) =
-        *reinterpret_cast<const v4u*>(xs + kt * 1024 + lane * 16);
+        *reinterpret_cast<const v4u*>(xs + (lane & 15) * row_bytes + (kt * 32 + (lane >> 4) * 8) * 2);
 }
 
 void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
               h16_t* x, int M, int m_tiles, int d, hipStream_t st) {
   if (M == 0) return;
-  if (n_split == 0 && M >= 1024 && d % 32 == 0 && d * 32 <= 160 * 1024) {
+  if (n_split == 0 && M >= 1024 && d % 32 == 0 && d * 32 + 256 <= 160 * 1024) {
     static bool configured = false;
     if (!configured) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_norm_tile16), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 160 * 1024);
       configured = true;
     }
-    k_norm_tile16<<<(M + 15) / 16, 256, d * 32, st>>>(h, gain, eps, x, M, m_tiles, d);
+    k_norm_tile16<<<(M + 15) / 16, 256, 16 * (2 * d + 16), st>>>(h, gain, eps, x, M, m_tiles, d);
     return;
   }
   k_add_norm<<<M, 256, 0, st>>>(h, P, n_split, ldp, Mpad_p, gain, eps, x, m_tiles * 16, d);
