@@ -28,6 +28,8 @@ constexpr int kStages = 4;
 constexpr int kPersistentGrid = 256;                 // CUs of the device; a multiple of the 8 XCDs
 constexpr int kBlkTiles = 16;                       // 16-row tiles per workgroup tile side
 constexpr int kStageBytes = 2 * kBlkTiles * 1024;   // weight blocks, then activation blocks
+constexpr int kTrRow = 36;                          // floats per row of the epilogue's 32 x 32 transposition tile
+constexpr int kTrBytes = 4 * 32 * kTrRow * 4;       // one tile per wavefront, behind the ring
 constexpr int kLoadsPerStage = 2 * kBlkTiles / 4;   // LDS-direct loads each wavefront issues per step
 
 typedef __attribute__((ext_vector_type(16))) float v16f;
@@ -231,11 +233,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
       // keep their order), which keeps the 256 accumulators out of the VGPR half until they are needed
       asm volatile("" : "+a"(acc[nb][mb])::"memory");
       const int m = (mt_base + 8 * wm + 2 * mb) * 16 + col;
-      if (m >= a.M) continue;
       const int n0 = (nt_base + 8 * wn + 2 * nb) * 16;  // first feature row of the block
       if (EPI == LEPI_SWIGLU) {
         // rows 0..15 of the block are gate rows, rows 16..31 the matching up rows
-        if (n0 >= a.n_tiles * 16) continue;
+        if (m >= a.M || n0 >= a.n_tiles * 16) continue;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
           const int f = (n0 >> 1) + 8 * q + rh;
@@ -247,15 +248,34 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
           *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
         }
       } else {
+        // fp32 output, row-major [token][feature]: a lane's 4 consecutive features of ONE token would make every
+        // store instruction touch 32 different rows; the 32 x 32 block is turned round in a wavefront-private
+        // LDS tile (behind the ring) so that an instruction covers 8 rows of 128 contiguous bytes
+        float* tb = reinterpret_cast<float*>(lds + kStages * kStageBytes) + wave * (32 * kTrRow);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + 8 * q + rh;
-          if (n >= a.N) continue;
-          const v4f v = v4f{acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
-          v4f* c = reinterpret_cast<v4f*>(a.out_f32 + (size_t)m * a.ld_out + n);
-          if (EPI == LEPI_ADD) *c = *c + v;
-          else *c = v;
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<v4f*>(tb + col * kTrRow + 8 * q + rh) =
+              v4f{acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
+        __builtin_amdgcn_wave_barrier();
+        const int m0 = (mt_base + 8 * wm + 2 * mb) * 16;
+        // all four loads of the accumulate form first: written pass by pass, each load would wait for the store
+        // before it (the compiler cannot tell the rows apart)
+        v4f cur[4];
+        const int f = (lane & 7) * 4, n = n0 + f;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+          const int mm = m0 + pass * 8 + (lane >> 3);
+          cur[pass] = v4f{0.f, 0.f, 0.f, 0.f};
+          if (EPI == LEPI_ADD && mm < a.M && n < a.N)
+            cur[pass] = *reinterpret_cast<const v4f*>(a.out_f32 + (size_t)mm * a.ld_out + n);
         }
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+          const int row = pass * 8 + (lane >> 3), mm = m0 + row;
+          const v4f v = *reinterpret_cast<const v4f*>(tb + row * kTrRow + f);
+          if (mm < a.M && n < a.N) *reinterpret_cast<v4f*>(a.out_f32 + (size_t)mm * a.ld_out + n) = cur[pass] + v;
+        }
+        __builtin_amdgcn_wave_barrier();  // the tile is reused by the next accumulator block
       }
     }
   }
@@ -387,7 +407,7 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
 template <int EPI>
 void launch_one(const LargeArgs& a, hipStream_t st) {
   static bool configured = false;  // per process; the attribute is a property of the function
-  const int lds_bytes = kStages * kStageBytes;
+  const int lds_bytes = kStages * kStageBytes + kTrBytes;
   if (!configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_lds<EPI>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
