@@ -225,8 +225,25 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   // (q = 0..3) in registers 4 q .. 4 q + 3
   const int col = lane & 31, rh = (lane >> 5) * 4;
   const int Mpad = a.m_tiles * 16;
+  // accumulate form: the old values of a group of four blocks (one nb, the four mb) are requested while the
+  // group before it is worked on; pass by pass, each block would wait a whole memory round trip for them
+  v4f old[2][4][4];
+  const int f = (lane & 7) * 4, trow = lane >> 3;
+  auto fetch_old = [&](int nb, v4f (&dst)[4][4]) {
+    const int n = (nt_base + 8 * wn + 2 * nb) * 16 + f;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int pass = 0; pass < 4; ++pass) {
+        const int mm = (mt_base + 8 * wm + 2 * mb) * 16 + pass * 8 + trow;
+        dst[mb][pass] = v4f{0.f, 0.f, 0.f, 0.f};
+        if (mm < a.M && n < a.N) dst[mb][pass] = *reinterpret_cast<const v4f*>(a.out_f32 + (size_t)mm * a.ld_out + n);
+      }
+  };
+  if (EPI == LEPI_ADD) fetch_old(0, old[0]);
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb) {
+    if (EPI == LEPI_ADD && nb + 1 < 4) fetch_old(nb + 1, old[(nb + 1) & 1]);
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) {
       // one accumulator block at a time: it is taken from its registers here, not earlier (volatile statements
@@ -239,13 +256,13 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
         if (m >= a.M || n0 >= a.n_tiles * 16) continue;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-          const int f = (n0 >> 1) + 8 * q + rh;
+          const int fo = (n0 >> 1) + 8 * q + rh;
           uint2 pk;
           pk.x = pack_h16x2(silu_l(acc[nb][mb][4 * q + 0]) * acc[nb][mb][4 * q + 8],
                             silu_l(acc[nb][mb][4 * q + 1]) * acc[nb][mb][4 * q + 9]);
           pk.y = pack_h16x2(silu_l(acc[nb][mb][4 * q + 2]) * acc[nb][mb][4 * q + 10],
                             silu_l(acc[nb][mb][4 * q + 3]) * acc[nb][mb][4 * q + 11]);
-          *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
+          *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, fo, Mpad)) = pk;
         }
       } else {
         // fp32 output, row-major [token][feature]: a lane's 4 consecutive features of ONE token would make every
@@ -257,23 +274,13 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
           *reinterpret_cast<v4f*>(tb + col * kTrRow + 8 * q + rh) =
               v4f{acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
         __builtin_amdgcn_wave_barrier();
-        const int m0 = (mt_base + 8 * wm + 2 * mb) * 16;
-        // all four loads of the accumulate form first: written pass by pass, each load would wait for the store
-        // before it (the compiler cannot tell the rows apart)
-        v4f cur[4];
-        const int f = (lane & 7) * 4, n = n0 + f;
+        const int m0 = (mt_base + 8 * wm + 2 * mb) * 16, n = n0 + f;
 #pragma unroll
         for (int pass = 0; pass < 4; ++pass) {
-          const int mm = m0 + pass * 8 + (lane >> 3);
-          cur[pass] = v4f{0.f, 0.f, 0.f, 0.f};
-          if (EPI == LEPI_ADD && mm < a.M && n < a.N)
-            cur[pass] = *reinterpret_cast<const v4f*>(a.out_f32 + (size_t)mm * a.ld_out + n);
-        }
-#pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-          const int row = pass * 8 + (lane >> 3), mm = m0 + row;
-          const v4f v = *reinterpret_cast<const v4f*>(tb + row * kTrRow + f);
-          if (mm < a.M && n < a.N) *reinterpret_cast<v4f*>(a.out_f32 + (size_t)mm * a.ld_out + n) = cur[pass] + v;
+          const int row = pass * 8 + trow, mm = m0 + row;
+          v4f v = *reinterpret_cast<const v4f*>(tb + row * kTrRow + f);
+          if (EPI == LEPI_ADD) v = v + old[nb & 1][mb][pass];
+          if (mm < a.M && n < a.N) *reinterpret_cast<v4f*>(a.out_f32 + (size_t)mm * a.ld_out + n) = v;
         }
         __builtin_amdgcn_wave_barrier();  // the tile is reused by the next accumulator block
       }
