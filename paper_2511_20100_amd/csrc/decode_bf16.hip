@@ -373,9 +373,10 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int NBP = NB>
 static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
-  if constexpr (NBP != NB) {  // several passes over the exchange buffer: SwiGLU shape only
-    const dim3 grid((a.n_tiles + NB - 1) / NB, 1), block(WAVES * 64);
-    k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
+  if constexpr (NBP != NB) {  // several passes over the exchange buffer: SwiGLU and split-K shapes only
+    const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1), block(WAVES * 64);
+    if (epi == DEPI_PARTIAL) k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL, NBP><<<grid, block, 0, st>>>(a);
+    else k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
   } else {
     const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1);
     const dim3 block(WAVES * 64);
@@ -405,7 +406,10 @@ static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
 template <int MB>
 static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
   if constexpr (MB > 4) {
-    launch_dec_t<2, MB, 4, 2, 2, 2>(a, epi, st);
+    // 128 rows: the activation operand is 8 KiB per k step against 1 KiB per weight row tile, and every
+    // workgroup reads all of it from L2, so four row tiles per workgroup halve the L2 traffic of two
+    if (epi == DEPI_SAMPLE) launch_dec_t<4, MB, 4, 2, 2, 1>(a, epi, st);
+    else launch_dec_t<4, MB, 4, 2, 2, 1, 2>(a, epi, st);
   } else {
     // every workgroup reads the whole activation operand, so a CU that hosts two workgroups takes about
     // twice as long as one that hosts one: one round of workgroups with 6 row tiles beats 1.x rounds with 4
@@ -414,7 +418,7 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
   }
 }
 
-int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? 2 : 4; }
+int dec_wide_nb(int) { return 4; }
 
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
   const bool wide = (epi == DEPI_SWIGLU || epi == DEPI_SAMPLE || epi == DEPI_PARTIAL);
