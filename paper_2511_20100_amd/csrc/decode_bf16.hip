@@ -394,7 +394,9 @@ static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
 template <int MB>
 static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
   if constexpr (MB > 4) {
-    launch_dec_t<1, MB, 8, 2, 2, 1>(a, epi, st);
+    // 128 rows: with one row tile per workgroup the activation operand (8 KiB per k step, from L2) outweighs the
+    // weights 8 to 1 and L2 bandwidth bounds the launch; two row tiles per workgroup halve that
+    launch_dec_t<2, MB, 8, 2, 2, 1>(a, epi, st);
   } else {
     // 16 wavefronts split long K ranges; the chunked O projection keeps 8, which leaves a wavefront the registers
     // to hold a whole head's operands of every chunk at once
