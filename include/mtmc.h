@@ -11,9 +11,13 @@
  *                 prompt (Inference Pipeline, "Macro Thinking"), returning the sampled ids and
  *                 the log-probability each was drawn with.
  *
+ * and, built on the same kernels: mtmc_rollout_ragged (prompts of different lengths, stop token),
+ * mtmc_score_actions (Eq. 2 summed per candidate action and the softmax over a state's candidates)
+ * and mtmc_ppo_clip_loss (value of the clipped surrogate of the PPO update over scored samples).
+ *
  * Model: pre-norm residual blocks (RMSNorm, rotary embedding with pairs (i, i + head_dim/2),
- * grouped-query causal attention, SwiGLU feed-forward), final RMSNorm, untied LM head, no
- * biases.  Matrices are row-major [out, in], y = W x.
+ * grouped-query causal attention, SwiGLU feed-forward), final RMSNorm, LM head (its own matrix,
+ * or the embedding matrix when tie_embeddings is set), no biases.  Matrices are row-major [out, in], y = W x.
  *
  * General rules
  *  - All pointers marked "device" must be device memory of the current HIP device; "host"
