@@ -216,7 +216,8 @@ def main() -> int:
         "metric": "rollout tokens/sec @1.5B-class bs64 bf16; decode HBM GB/s + scoring MFMA % peak",
         "value": new_tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 weights, f16 MFMA operands and KV cache, f32 accumulate",
+        "vs_baseline": None,
+        "dtype": "bf16 weights, f16 MFMA operands and KV cache, f32 accumulate" if cfg.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {cfg.n_layers} layers d{cfg.d_model} Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} "
                                f"F{cfg.d_ffn} V{cfg.vocab}; {n_prompts} prompts x {n_samples} samples = batch {B}, "
