@@ -28,7 +28,8 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  mtmc_rollout and
  *    mtmc_score only enqueue work on it and return without synchronising; outputs are valid
  *    once the caller has synchronised the stream.  Calls that share a workspace must be
- *    ordered on one stream.
+ *    ordered on one stream; calls on one weights handle with distinct workspaces may overlap
+ *    on different streams and give the results they give alone.
  *  - Every int-returning call gives MTMC_OK (0) or a negative code; mtmc_last_error() then
  *    holds a message for the calling thread.
  */

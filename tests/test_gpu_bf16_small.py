@@ -121,6 +121,38 @@ def test_graph_replay_matches_direct_launches(lib):
         lib.mtmc_weights_destroy(handle)
 
 
+def test_calls_overlapping_on_two_streams_match_calls_in_turn(lib):
+    """Two rollouts and a scoring pass on one weights handle, each with its own workspace and
+    stream, give bit for bit what the same calls give one after the other."""
+    import torch
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
+    try:
+        halves = [torch.from_numpy(inputs.make_prompts(3, 21, cfg.vocab, seed=5 + i)).cuda() for i in range(2)]
+        seqs = torch.from_numpy(inputs.make_sequences(6, 60, cfg.vocab, seed=9)).cuda()
+        wss = [torch.empty(lib.mtmc_rollout_workspace_bytes(handle, 3, 21, 4, 40), dtype=torch.uint8, device="cuda")
+               for _ in range(2)]
+        ws_sc = torch.empty(lib.mtmc_score_workspace_bytes(handle, 6, 60), dtype=torch.uint8, device="cuda")
+
+        def run(streams):
+            out = [lib.mtmc_rollout(handle, halves[i], 4, 40, 1.0, 3, seq_offset=12 * i, workspace=wss[i],
+                                    stream=streams[i]) for i in range(2)]
+            sc = lib.mtmc_score(handle, seqs, 20, workspace=ws_sc, stream=streams[2])
+            torch.cuda.synchronize()
+            return [t.clone() for pair in out for t in pair] + [sc.clone()]
+
+        ref = run([None, None, None])
+        streams = [torch.cuda.Stream() for _ in range(3)]
+        torch.cuda.synchronize()
+        for rep in range(3):
+            got = run(streams)
+            for a, b in zip(got, ref):
+                assert torch.equal(a, b), rep
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
 def test_kernel_timer_does_not_change_results(lib):
     import torch
     cfg = GQA6
