@@ -3,10 +3,11 @@
 
 One step = one pass of the whole path over one batch: mtmc_rollout (prefill of the prompts, then
 max_new Gumbel-max decode steps for every sequence) followed by mtmc_score of the sequences it
-produced.  The headline value is generated tokens per second over the whole step; inputs
-(weights, prompts) are resident in HBM before the timed region.  Prints ONE JSON line.
+produced.  The headline value is generated tokens per second over the whole step (scored tokens
+per second when the step is the scoring pass alone); inputs (weights, prompts) are resident in HBM
+before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|tiny|7b] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|tiny|7b|...] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -35,6 +36,8 @@ WORKLOADS = {
     "tiny": (inputs.TINY, 4, 32, 2, 32),
     "1p5b": (inputs.POLICY_1P5B, 8, 512, 8, 1024),
     "7b": (inputs.POLICY_7B, 16, 1024, 8, 2048),
+    "7b-long": (inputs.POLICY_7B, 4, 2048, 8, 8192),       # long generations: context up to 10240 tokens
+    "7b-score": (inputs.POLICY_7B, 32, 1024, 8, 2048),     # scoring alone: 256 sequences of 3072 tokens
     "1p3b-mha": (inputs.POLICY_1P3B_MHA, 8, 512, 8, 1024),
     "1b-hd64": (inputs.POLICY_1B_HD64, 8, 512, 8, 1024),
 }
@@ -104,6 +107,7 @@ def main() -> int:
                     help="time the scoring pass alone, on sequences whose new tokens are random ids (for counter runs)")
     ap.add_argument("--no-actions", action="store_true", help="skip the action-scoring leg (reported beside the step)")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps directly (for counter runs)")
+    ap.add_argument("--progress", action="store_true", help="print a line to stderr as each stage ends")
     ap.add_argument("--no-kernel-timer", action="store_true", help="do not bracket the gate/up launches with events")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the workload, copy this many MiB device to device once: a kernel of known "
@@ -117,7 +121,13 @@ def main() -> int:
     import torch
     from paper_2511_20100_amd import mtmc
 
+    def progress(msg):
+        if args.progress:
+            print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
     cfg, n_prompts, prompt_len, n_samples, max_new = WORKLOADS[args.workload]
+    if args.workload == "7b-score":
+        args.no_rollout = args.no_actions = True
     if args.max_new:
         max_new = args.max_new
     B = n_prompts * n_samples
@@ -141,8 +151,8 @@ def main() -> int:
         del src, dst
     prompts_np = inputs.make_prompts(n_prompts, prompt_len, cfg.vocab, seed=2)
     prompts = torch.from_numpy(prompts_np).to(dev)
-    ws_r = torch.empty(mtmc.mtmc_rollout_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new),
-                       dtype=torch.uint8, device=dev)
+    ws_r = None if args.no_rollout else torch.empty(
+        mtmc.mtmc_rollout_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new), dtype=torch.uint8, device=dev)
     ws_s = torch.empty(mtmc.mtmc_score_workspace_bytes(handle, B, seq_len), dtype=torch.uint8, device=dev)
     out_ids = torch.empty((B, max_new), dtype=torch.int32, device=dev)
     out_lp = torch.empty((B, max_new), dtype=torch.float32, device=dev)
@@ -150,6 +160,7 @@ def main() -> int:
     seqs[:, :prompt_len] = prompts.repeat_interleave(n_samples, dim=0)
     score_lp = torch.empty((B, seq_len - 1), dtype=torch.float32, device=dev)
     setup_s = time.perf_counter() - t0
+    progress(f"weights re-tiled and inputs resident after {setup_s:.1f} s")
     stream = torch.cuda.current_stream()
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -170,7 +181,8 @@ def main() -> int:
 
     for i in range(args.warmup):
         step(100 + i)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        progress(f"warm-up step {i + 1} of {args.warmup} done")
     # dominant decode kernel (gate/up projection: half of the layer weight bytes): every 32nd decode
     # step of the timed region is launched directly with a HIP-event pair around each of its launches
     timed_kernel = cfg.dtype == "bf16" and not args.no_kernel_timer and not args.no_rollout
@@ -183,6 +195,7 @@ def main() -> int:
         ev[2].synchronize()  # the events are reused by the next step
         rollout_ms.append(ev[0].elapsed_time(ev[1]))
         score_ms.append(ev[1].elapsed_time(ev[2]))
+        progress(f"timed step {i + 1} of {args.steps}: rollout {rollout_ms[-1]:.1f} ms, scoring {score_ms[-1]:.1f} ms")
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_begin
     mtmc.mtmc_poll_errors(handle)
@@ -214,7 +227,7 @@ def main() -> int:
                     "frac": step_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "whole decode step"}
     result = {
         "metric": "rollout tokens/sec @1.5B-class bs64 bf16; decode HBM GB/s + scoring MFMA % peak",
-        "value": new_tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "value": (B * seq_len if args.no_rollout else new_tokens) / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16 weights, f16 MFMA operands and KV cache, f32 accumulate" if cfg.dtype == "bf16" else "f32",
@@ -238,6 +251,11 @@ def main() -> int:
         result["score_ms"] = s_ms
         result["score_mfma"] = {"bound": "mfma", "achieved": flops / (s_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
                                 "unit": "TFLOP/s", "frac": flops / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+    if args.no_rollout:  # nothing was decoded: the step is the scoring pass, bound by the matrix cores
+        for key in ("rollout_tokens_per_s", "rollout_ms", "decode_step"):
+            del result[key]
+        result["roofline"] = dict(result["score_mfma"], traffic=None,
+                                  kernel="whole scoring pass (algorithmic flops of the forward pass over its time)")
     if not args.no_actions:
         # beside the step, not part of `value`: the prompts as states, 32 candidate actions of up to 32 tokens each
         K, A = 32, min(32, max_new)

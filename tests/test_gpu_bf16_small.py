@@ -196,8 +196,8 @@ def test_lds_staged_gemm_on_ragged_shapes(lib, cfg, n_seqs, seq_len):
 
 def test_long_context_over_several_attention_chunks(lib):
     """Context beyond 8192 tokens (more than the 512 pages one decode-attention workgroup stages):
-    the context is then split over workgroups whose partial results are merged by the last to
-    finish.  Prompt 8200 + 24 new tokens, small model, both samples replayed on the oracle."""
+    the context is then split over workgroups whose partial results the O projection combines.
+    Prompt 8200 + 24 new tokens, small model, both samples replayed on the oracle."""
     cfg = GQA6
     w = inputs.make_weights(cfg, seed=6, std=0.05)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 8256), w.blob())
