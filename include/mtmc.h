@@ -102,7 +102,10 @@ size_t mtmc_blob_bytes(const mtmc_config* cfg);
  * out_logprobs device float [n_prompts*n_samples, max_new]
  * workspace    device, >= mtmc_rollout_workspace_bytes(...) bytes, 256-byte aligned
  * Out-of-range ids are clamped on the device and reported by the next mtmc_poll_errors.
+ * MTMC_BF16 decodes contexts of at most MTMC_MAX_DECODE_CONTEXT tokens: prompt_len + max_new
+ * beyond that is MTMC_EINVAL.
  */
+#define MTMC_MAX_DECODE_CONTEXT 32768
 size_t mtmc_rollout_workspace_bytes(const mtmc_weights* w, int32_t n_prompts, int32_t prompt_len,
                                     int32_t n_samples, int32_t max_new);
 int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompts,

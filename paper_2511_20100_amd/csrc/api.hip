@@ -176,6 +176,9 @@ static int check_rollout_shape(const mtmc_weights* w, int32_t n_prompts, int32_t
   MTMC_REQUIRE((int64_t)prompt_len + max_new <= w->cfg.max_positions,
                "prompt_len + max_new exceeds max_positions");
   MTMC_REQUIRE((int64_t)n_prompts * n_samples <= (1 << 20), "too many sequences");
+  // the decode attention splits the context into at most 4 chunks of 512 pages (the O projection combines them)
+  MTMC_REQUIRE(w->cfg.dtype != MTMC_BF16 || (int64_t)prompt_len + max_new <= MTMC_MAX_DECODE_CONTEXT,
+               "prompt_len + max_new exceeds MTMC_MAX_DECODE_CONTEXT (32768) of the MTMC_BF16 path");
   return MTMC_OK;
 }
 

@@ -37,14 +37,15 @@ struct DecStream {
   v8bf wr[PFW][NB], xr[PFX][MB];
 
   __device__ __forceinline__ void start(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles, int nt0,
-                                        const h16_t* __restrict__ Xt, int m_tiles, int k0_, int k1_, int lane) {
+                                        const h16_t* __restrict__ Xt, int m_tiles, int mt0, int k0_, int k1_,
+                                        int lane) {
     k0 = k0_;
     k1 = k1_;
     if (k0 >= k1) return;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) wp[nb] = Wt + (size_t)min(nt0 + nb, n_tiles - 1) * k_tiles * 512 + lane * 8;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mb, m_tiles - 1) * 512 + lane * 8;
+    for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mt0 + mb, m_tiles - 1) * 512 + lane * 8;
     xstep = (size_t)m_tiles * 512;
 #pragma unroll
     for (int s = 0; s < PFW; ++s) {
@@ -102,10 +103,12 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   static_assert(NB % NBP == 0 && (EPI != DEPI_SWIGLU || NBP % 2 == 0 || NB == 1) && (EPI != DEPI_SAMPLE || NBP == NB),
                 "bad tiles-per-pass");
   __shared__ float red[WAVES][NBP * MB * 4][64];
-  __shared__ float s_scale[MB * 16];
+  __shared__ float s_scale[128];
   __shared__ float s_part[2][WAVES * 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nt0 = blockIdx.x * NB;
+  // token tiles mt0 .. mt0 + MB - 1 (the launch may split the rows over gridDim.y; split-K uses that index itself)
+  const int mt0 = (EPI == DEPI_PARTIAL) ? 0 : blockIdx.y * MB;
   const int Mpad = a.m_tiles * 16;
   // Row scales (consumers need r_new / r_old, producers r of the state they update).  Thread t sums
   // tiles part, part + P, ... of row t % Mpad; the P partial sums are then added in index order.
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   bool chunked = false;
   if constexpr (EPI == DEPI_RESID && NB == 1 && WAVES == 8 && MB <= 4) chunked = a.n_xchunks > 1;  // workgroup-uniform
   DecStream<NB, MB, PFW, PFX> stream;
-  stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, k0, chunked ? k0 : k1, lane);
+  stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, k0, chunked ? k0 : k1, lane);
 #pragma unroll
   for (int u = 0; u < BT; ++u) {
     sa += va[u];
@@ -211,8 +214,9 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
         for (int c = 0; c < NCM; ++c)
 #pragma unroll
           for (int mb = 0; mb < MB; ++mb) {
-            const bool live = c < NC && mb * 16 + col < a.M;
-            const float* ml = a.chunk_ml + (((size_t)(mb * 16 + col) * n_heads + j) * NC + c) * 2;
+            const int row = (mt0 + mb) * 16 + col;
+            const bool live = c < NC && row < a.M;
+            const float* ml = a.chunk_ml + (((size_t)row * n_heads + j) * NC + c) * 2;
             cm[c][mb] = live ? ml[0] : -INFINITY;
             cl[c][mb] = live ? ml[1] : 0.f;
           }
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
               xf[c][t][mb] =
-                  load_frag(xp + ((size_t)(j * HT + min(t, HT - 1)) * a.m_tiles + min(mb, a.m_tiles - 1)) * 512, 0);
+                  load_frag(xp + ((size_t)(j * HT + min(t, HT - 1)) * a.m_tiles + min(mt0 + mb, a.m_tiles - 1)) * 512, 0);
         }
         float mx[MB], den[MB];
 #pragma unroll
@@ -268,7 +272,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) red[wave][(j * MB + mb) * 4 + r][lane] = acc[ph * NBP + j][mb][r];
   __syncthreads();
-  for (int mb = wave; mb < MB && mb < a.m_tiles; mb += WAVES) {
+  for (int mb = wave; mb < MB && mt0 + mb < a.m_tiles; mb += WAVES) {
   v4f sum[NBP];
 #pragma unroll
   for (int nb = 0; nb < NBP; ++nb) {
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       for (int r = 0; r < 4; ++r) sum[nb][r] += red[w][(nb * MB + mb) * 4 + r][lane];
   }
   const int col = lane & 15, rq = (lane >> 4) * 4;
-  const int m = mb * 16 + col;
+  const int m = (mt0 + mb) * 16 + col;
   const float sc = (EPI == DEPI_PARTIAL) ? 1.f : s_scale[m];
 
   if (EPI == DEPI_PARTIAL) {
@@ -372,13 +376,13 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 }
 
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int NBP = NB>
-static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
+static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st, int msplit = 1) {
   if constexpr (NBP != NB) {  // several passes over the exchange buffer: SwiGLU and split-K shapes only
     const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1), block(WAVES * 64);
     if (epi == DEPI_PARTIAL) k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL, NBP><<<grid, block, 0, st>>>(a);
     else k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
   } else {
-    const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1);
+    const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : msplit);
     const dim3 block(WAVES * 64);
     switch (epi) {
       case DEPI_PARTIAL: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL><<<grid, block, 0, st>>>(a); break;
@@ -392,17 +396,11 @@ static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st) {
 
 // Narrow shape: one weight row tile per workgroup, K split over 8 or 16 wavefronts (QKV, O, down).
 template <int MB>
-static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st) {
-  if constexpr (MB > 4) {
-    // 128 rows: with one row tile per workgroup the activation operand (8 KiB per k step, from L2) outweighs the
-    // weights 8 to 1 and L2 bandwidth bounds the launch; two row tiles per workgroup halve that
-    launch_dec_t<2, MB, 8, 2, 2, 1>(a, epi, st);
-  } else {
-    // 16 wavefronts split long K ranges; the chunked O projection keeps 8, which leaves a wavefront the registers
-    // to hold a whole head's operands of every chunk at once
-    if (a.k_tiles >= 48 && !(epi == DEPI_RESID && a.n_xchunks > 1)) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st);
-    else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st);
-  }
+static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st, int msplit = 1) {
+  // 16 wavefronts split long K ranges; the chunked O projection keeps 8, which leaves a wavefront the registers
+  // to hold a whole head's operands of every chunk at once
+  if (a.k_tiles >= 48 && !(epi == DEPI_RESID && a.n_xchunks > 1)) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st, msplit);
+  else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st, msplit);
 }
 // Wide shape: many row tiles (gate/up, LM head): NB tiles per workgroup, K split over 4 wavefronts.
 template <int MB>
@@ -435,9 +433,17 @@ void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
   } else {
     switch (mb) {
       case 1: launch_dec_narrow<1>(a, epi, st); break;
-      case 2: launch_dec_narrow<2>(a, epi, st); break;
-      case 4: launch_dec_narrow<4>(a, epi, st); break;
-      default: launch_dec_narrow<8>(a, epi, st); break;
+      case 2: launch_dec_narrow<1>(a, epi, st, 2); break;
+      // 33..64 rows: every workgroup reads the whole activation operand of its rows from L2, four times the bytes
+      // of its weight tile, and with one workgroup per weight row tile only 100-odd CUs work: two workgroups per
+      // row tile, 32 rows each (placed on the same XCD by the launch order, so the tile's second read hits L2)
+      case 4: launch_dec_narrow<2>(a, epi, st, 2); break;
+      // 65..128 rows: two weight row tiles per workgroup (the activation operand outweighs the weights) and two
+      // workgroups of 64 rows per pair of tiles; behind a context-split attention the form that combines chunks
+      default:
+        if (epi == DEPI_RESID && a.n_xchunks > 1) launch_dec_narrow<2>(a, epi, st, (a.m_tiles + 1) / 2);
+        else launch_dec_t<2, 4, 8, 2, 2, 1>(a, epi, st, 2);
+        break;
     }
   }
 }

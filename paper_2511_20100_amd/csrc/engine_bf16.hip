@@ -256,10 +256,13 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   // that the attention kernel's fixed part dominates and the split only costs the O projection, which combines
   // the chunks, a second operand: measured at batch 64 with 2 kv heads)
   const int want = std::max(1, 128 / std::max(1, p.B * D.Hkv));
-  const int mb = p.bt <= 1 ? 1 : p.bt <= 2 ? 2 : p.bt <= 4 ? 4 : 8;  // row tiles of the decode GEMM instantiation
-  p.n_chunks = std::max(1, std::min({want, (p.max_pages + 7) / 8, 8 / mb}));  // the O projection holds mb * chunks <= 8
+  // the O projection that combines the chunks holds (row tiles per workgroup) * chunks <= 8 operand sets: its
+  // workgroups take one row tile up to 32 rows and two beyond
+  const int max_chunks = p.bt <= 2 ? 8 : 4;
+  p.n_chunks = std::max(1, std::min({want, (p.max_pages + 7) / 8, max_chunks}));
   p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;
-  p.chunk_pages = std::min(p.chunk_pages, 512);  // page ids of a chunk are staged in LDS
+  // page ids of a chunk are staged in LDS; kMaxDecodeContext keeps the chunk count within max_chunks
+  p.chunk_pages = std::min(p.chunk_pages, 512);
   p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
   const size_t Mpad = (size_t)p.bt * 16;
   const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;

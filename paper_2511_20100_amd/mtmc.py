@@ -269,6 +269,7 @@ def mtmc_ppo_clip_loss(new_logprobs: torch.Tensor, old_logprobs: torch.Tensor, a
     return out
 
 
+MTMC_MAX_DECODE_CONTEXT = 32768   # prompt_len + max_new of a MTMC_BF16 rollout
 MTMC_OPT_HIP_GRAPH = 1
 MTMC_OPT_GEMM_LDS_MIN_BLOCKS = 2
 

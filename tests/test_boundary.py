@@ -40,6 +40,15 @@ def test_binding_lists_the_same_entry_points():
         assert hasattr(mtmc, n) or n == "mtmc_last_error"
 
 
+def test_binding_constants_match_the_header():
+    from paper_2511_20100_amd import mtmc
+    text = open(os.path.join(ROOT, "include", "mtmc.h")).read()
+    defines = {k: v.strip("()") for k, v in re.findall(r"^#define\s+(MTMC_[A-Z0-9_]+)\s+(\(?-?\d+\)?)", text, flags=re.M)}
+    assert {"MTMC_OK", "MTMC_EINVAL", "MTMC_BF16", "MTMC_MAX_DECODE_CONTEXT", "MTMC_OPT_HIP_GRAPH"} <= set(defines)
+    for name, value in defines.items():
+        assert getattr(mtmc, name) == int(value), name
+
+
 @pytest.mark.parametrize("cfg", [inputs.TINY, inputs.POLICY_1P5B, inputs.POLICY_7B,
                                  inputs.TINY.with_(dtype="bf16", head_dim=128, n_q_heads=2, n_kv_heads=1)])
 def test_blob_size_agrees_with_the_input_generator(cfg):

@@ -210,6 +210,37 @@ def test_long_context_over_several_attention_chunks(lib):
         lib.mtmc_weights_destroy(handle)
 
 
+def test_long_context_at_more_than_64_rows(lib):
+    """72 sequences (five row tiles: the 128-row form of the decode GEMMs) with a context beyond 8192
+    tokens, so that the O projection of that form has to combine two context chunks.  One prompt
+    of 8200 tokens with 72 samples; three of them are replayed on the oracle."""
+    cfg = GQA4
+    w = inputs.make_weights(cfg, seed=6, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 8256), w.blob())
+    try:
+        prompts = inputs.make_prompts(1, 8200, cfg.vocab, seed=8)
+        rep = check_rollout_by_replay(handle, w, prompts, 72, 20, 1.0, 5, max_positions=8256, rows=[0, 37, 71],
+                                      label="long-context-72")
+        print("long context, 72 rows: compared", rep["compared"], "of", rep["steps"], "max log-prob err", rep["max_logp_err"])
+        assert rep["compared"] > 0.5 * rep["steps"]
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_context_limit_is_enforced(lib):
+    import torch
+    cfg = GQA4
+    w = inputs.make_weights(cfg, seed=6, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 40000), w.blob())
+    try:
+        with pytest.raises(lib.MtmcError) as e:
+            lib.mtmc_rollout_workspace_bytes(handle, 1, lib.MTMC_MAX_DECODE_CONTEXT - 7, 2, 8)
+        assert e.value.code == lib.MTMC_EINVAL and "MTMC_MAX_DECODE_CONTEXT" in str(e.value)
+        assert lib.mtmc_rollout_workspace_bytes(handle, 1, lib.MTMC_MAX_DECODE_CONTEXT - 8, 2, 8) > 0
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
 def test_degenerate_sizes(lib):
     """Nothing to score (prompt_len == seq_len), the shortest scorable sequence, a single new token, and
     a call split over two processes' worth of prompts (seq_offset) that must reproduce the whole call."""
