@@ -66,6 +66,9 @@ struct DecGemmArgs {
   int n_xchunks, head_tiles;
   size_t x_chunk_stride;
   const float* chunk_ml;
+  // set by the launcher: the rows are split over pairs of workgroups that follow each other by 8 in launch order
+  // (same XCD, dispatched together, so the second read of a weight tile hits L2); 0 = rows split over grid.y, if at all
+  int row_pairs;
 };
 enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3, DEC_PARTIAL = 4 };
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,

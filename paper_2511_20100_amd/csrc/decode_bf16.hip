@@ -106,16 +106,24 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   __shared__ float s_scale[128];
   __shared__ float s_part[2][WAVES * 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nt0 = blockIdx.x * NB;
-  // token tiles mt0 .. mt0 + MB - 1 (the launch may split the rows over gridDim.y; split-K uses that index itself)
-  const int mt0 = (EPI == DEPI_PARTIAL) ? 0 : blockIdx.y * MB;
+  // weight row tiles nt0 .. nt0 + NB - 1 (group grp of n_groups), token tiles mt0 .. mt0 + MB - 1: the launch may
+  // split the rows over gridDim.y (split-K uses that index itself) or over pairs of workgroups along x
+  int grp = blockIdx.x, n_groups = gridDim.x, mpart = (EPI == DEPI_PARTIAL) ? 0 : blockIdx.y;
+  if (a.row_pairs) {
+    grp = (blockIdx.x >> 4) * 8 + (blockIdx.x & 7);
+    mpart = (blockIdx.x >> 3) & 1;
+    n_groups = (a.n_tiles + NB - 1) / NB;
+    if (grp >= n_groups) return;  // the grid is rounded up to whole sets of 8 pairs
+  }
+  const int nt0 = grp * NB;
+  const int mt0 = mpart * MB;
   const int Mpad = a.m_tiles * 16;
   // Row scales (consumers need r_new / r_old, producers r of the state they update).  Thread t sums
   // tiles part, part + P, ... of row t % Mpad; the P partial sums are then added in index order.
   // A split-K launch only needs them in the kernel that finishes the sum: its first workgroup
   // computes them on the side and leaves them in rs_out.
   constexpr bool kProducer = (EPI == DEPI_RESID || EPI == DEPI_PARTIAL);
-  const bool do_rs = EPI != DEPI_PARTIAL || (blockIdx.x == 0 && blockIdx.y == 0);  // workgroup-uniform
+  const bool do_rs = EPI != DEPI_PARTIAL || (blockIdx.x == 0 && blockIdx.y == 0);  // workgroup-uniform (x 0: group 0, rows 0..)
   constexpr int NT = WAVES * 64;
   constexpr int BT = (WAVES >= 8) ? 8 : 24;  // loads per batch (all tiles of d = 1536 in one batch)
   const int P = NT / Mpad;  // Mpad <= 128 <= NT
@@ -367,7 +375,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
     }
     if (lane < 16 && m < a.M) {
       // row-major per token row, so that the merge reads a row's partials as one contiguous run
-      DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)m * gridDim.x + blockIdx.x;
+      DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)m * n_groups + grp;
       p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
     }
   }
@@ -376,13 +384,17 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 }
 
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int NBP = NB>
-static void launch_dec_t(const DecGemmArgs& a, int epi, hipStream_t st, int msplit = 1) {
+static void launch_dec_t(const DecGemmArgs& a0, int epi, hipStream_t st, int msplit = 1, bool row_pairs = false) {
+  DecGemmArgs a = a0;
+  a.row_pairs = row_pairs ? 1 : 0;
+  const int groups = (a.n_tiles + NB - 1) / NB;
+  const int gx = row_pairs ? (groups + 7) / 8 * 16 : groups;
   if constexpr (NBP != NB) {  // several passes over the exchange buffer: SwiGLU and split-K shapes only
-    const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : 1), block(WAVES * 64);
+    const dim3 grid(gx, epi == DEPI_PARTIAL ? a.ksplit : 1), block(WAVES * 64);
     if (epi == DEPI_PARTIAL) k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL, NBP><<<grid, block, 0, st>>>(a);
     else k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
   } else {
-    const dim3 grid((a.n_tiles + NB - 1) / NB, epi == DEPI_PARTIAL ? a.ksplit : msplit);
+    const dim3 grid(gx, epi == DEPI_PARTIAL ? a.ksplit : msplit);
     const dim3 block(WAVES * 64);
     switch (epi) {
       case DEPI_PARTIAL: k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL><<<grid, block, 0, st>>>(a); break;
@@ -408,8 +420,7 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
   if constexpr (MB > 4) {
     // 128 rows: the activation operand is 8 KiB per k step against 1 KiB per weight row tile, and every
     // workgroup reads all of it from L2, so four row tiles per workgroup halve the L2 traffic of two
-    if (epi == DEPI_SAMPLE) launch_dec_t<4, MB, 4, 2, 2, 1>(a, epi, st);
-    else launch_dec_t<4, MB, 4, 2, 2, 1, 2>(a, epi, st);
+    launch_dec_t<4, 4, 4, 2, 2, 2>(a, epi, st, 1, true);
   } else {
     // every workgroup reads the whole activation operand, so a CU that hosts two workgroups takes about
     // twice as long as one that hosts one: one round of workgroups with 6 row tiles beats 1.x rounds with 4
