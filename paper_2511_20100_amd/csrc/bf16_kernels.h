@@ -41,7 +41,7 @@ struct ScoreHeadArgs {
   int want_top;   // 0: the two largest logits are not tracked (the caller asked for log-probs only)
 };
 
-// ---- decode step (five launches per block; see decode_bf16.hip) ------------------------------
+// ---- decode step (six launches per block; see decode_bf16.hip) ------------------------------
 struct DecGemmArgs {
   const h16_t* Wt;
   const h16_t* Xt;

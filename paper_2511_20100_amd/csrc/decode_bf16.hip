@@ -1,13 +1,14 @@
-// Decode-step kernels of the bf16 path: five launches per residual block.
+// Decode-step kernels of the bf16 path: six launches per residual block.
 //
 //   qkv   = W_qkv x'                      k_gemm_dec<STORE>
-//   o     = attention(rope(q), cache)     k_attn_dec   (also rotates/writes the new K, V; merges the context chunks)
-//   h    += W_o o;   x' for the FFN       k_gemm_dec<RESID>
+//   o     = attention(rope(q), cache)     k_attn_dec   (also rotates/writes the new K, V; output per context chunk)
+//   h    += W_o o;   x' for the FFN       k_gemm_dec<RESID>   (combines the context chunks)
 //   a     = silu(W_g x') * (W_u x')       k_gemm_dec<SWIGLU>
-//   h    += W_d a;   x' for the next block k_gemm_dec<RESID>
+//   P_s   = W_d[:, k range s] a           k_gemm_dec<PARTIAL> (split-K: the matrix has too few rows to fill the chip)
+//   h    += sum_s P_s; x' for the next block   k_resid_reduce
 //
-// Every GEMM workgroup owns whole output columns (all of K), so results are complete when the
-// workgroup ends: no split-K partials in memory and no separate reduction / norm kernels.
+// Apart from the down projection every GEMM workgroup owns whole output columns (all of K), so its results are
+// complete when the workgroup ends.  Nothing is accumulated with atomics: every sum has a fixed order.
 //
 // Deferred RMSNorm.  A producer (RESID) cannot know the new row norm (other workgroups hold the
 // other columns), so it writes x' = fp16(h_new * gain * r_old), r_old = 1/rms of the row *before*
