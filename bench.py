@@ -27,8 +27,8 @@ from paper_2511_20100_amd import inputs  # noqa: E402
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 # HBM bytes one launch of the gate/up decode kernel moves at the 1.5B workload, from FETCH_SIZE / WRITE_SIZE
 # counter runs scaled by the library's copy kernel (profiles/decode_kernels_1p5b_hbm_counters.txt).
-# Belongs to k_gemm_dec<6, 4, 4, 2, 2, 1, SWIGLU>: set to None when that kernel or its launch shape changes.
-GATE_UP_TRAFFIC_1P5B = 27954.5 * 1024 * 2.000 + 1120.0 * 1024 * 1.000
+# Belongs to k_gemm_dec<6, 4, 8, 2, 2, 1, SWIGLU, 2>: set to None when that kernel or its launch shape changes.
+GATE_UP_TRAFFIC_1P5B = 27932.0 * 1024 * 2.000 + 1120.0 * 1024 * 1.000
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
 
 WORKLOADS = {
