@@ -426,6 +426,7 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
     // every workgroup reads the whole activation operand, so a CU that hosts two workgroups takes about
     // twice as long as one that hosts one: one round of workgroups with 6 row tiles beats 1.x rounds with 4
     if (epi == DEPI_SWIGLU && a.n_tiles > 4 * 256 && a.n_tiles <= 6 * 256) launch_dec_t<6, MB, 8, 2, 2, 1, 2>(a, epi, st);
+    else if (epi == DEPI_PARTIAL && a.partial_nb == 2) launch_dec_t<2, MB, 8, 2, 2, 1>(a, epi, st);
     else launch_dec_t<4, MB, 4, 2, 2, 2>(a, epi, st);
   }
 }

@@ -71,6 +71,7 @@ struct RolloutPlan {
   float* rs_buf;      // 1/rms per row, handed from the split-K down projection to its reduction
   int chunk_pages, n_chunks;       // decode-attention context split
   int ks_qkv, ks_o, ks_down;       // split-K factors of the decode GEMMs
+  int down_nb;                     // weight row tiles per workgroup of the down projection (2 or 4)
   int bt;                          // 16-row tiles covering B
   size_t total_bytes;
 };

@@ -252,6 +252,14 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.ks_qkv = choose_ksplit(D.nt_qkv, D.kt_d, p.bt);
   p.ks_o = choose_ksplit(D.nt_d, D.kt_nq, p.bt);
   p.ks_down = choose_ksplit(D.nt_d, D.kt_F, p.bt);
+  // A small down projection (each workgroup's share of the weights under 256 KB) is bound by fixed costs and by
+  // what few wavefronts pull per CU: two row tiles and 8 wavefronts per workgroup, half the K splits (1.3-1.7 %
+  // of the step at d 1536 / F 8960; at d 3584 / F 18944 the doubled activation reads cost 1.3 % instead).
+  p.down_nb = 4;
+  if (p.bt <= 4 && 4 * (D.kt_F / p.ks_down) < 256) {
+    p.down_nb = 2;
+    p.ks_down = std::max(1, std::min(256 / ((D.nt_d + 1) / 2), D.kt_F / 16));
+  }
   // context split of the decode attention for small batches, up to about 128 workgroups of 8 wavefronts (beyond
   // that the attention kernel's fixed part dominates and the split only costs the O projection, which combines
   // the chunks, a second operand: measured at batch 64 with 2 kv heads)
@@ -374,7 +382,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     // launch that adds them in split order and does the residual / norm bookkeeping
     bf16::DecGemmArgs r2 = g;
     r2.Wt = (const h16_t*)L.wdown; r2.Xt = a; r2.n_tiles = D.nt_d; r2.k_tiles = D.kt_F;
-    r2.ss_cur = ss[cur]; r2.out_f32 = p.part; r2.ld_out = D.d; r2.ksplit = p.ks_down; r2.rs_out = p.rs_buf;
+    r2.ss_cur = ss[cur]; r2.out_f32 = p.part; r2.ld_out = D.d; r2.ksplit = p.ks_down; r2.rs_out = p.rs_buf; r2.partial_nb = p.down_nb;
     mark(MTMC_KERNEL_DOWN);
     bf16::gemm_dec(r2, bf16::DEC_PARTIAL, st);
     mark(MTMC_KERNEL_DOWN);
