@@ -101,7 +101,7 @@ struct DecSamplePartial {
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int EPI, int NBP = NB>
 __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // NBP = row tiles summed and finished per pass over the LDS exchange buffer (NB / NBP passes)
-  static_assert(NB % NBP == 0 && (EPI != DEPI_SWIGLU || NBP % 2 == 0 || NB == 1) && (EPI != DEPI_SAMPLE || NBP == NB),
+  static_assert(NB % NBP == 0 && (EPI != DEPI_SWIGLU || NBP % 2 == 0 || NB == 1) && (EPI != DEPI_SAMPLE || MB <= WAVES),
                 "bad tiles-per-pass");
   __shared__ float red[WAVES][NBP * MB * 4][64];
   __shared__ float s_scale[128];
@@ -270,6 +270,10 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   }
   // Sum over the K slices: every wavefront publishes its accumulators; wavefront w then adds the WAVES
   // slices of token tiles w, w + WAVES, ... in index order and runs the epilogue for those tokens.
+  // SAMPLE: a wavefront has at most one token tile (MB <= WAVES); its sampler state lives across the passes.
+  Lse smp_lse = lse_empty();
+  float smp_y = -INFINITY, smp_z = 0.f;
+  int smp_i = 0x7fffffff;
 #pragma unroll
   for (int ph = 0; ph < NB / NBP; ++ph) {
   const int nbase = nt0 + ph * NBP;  // first row tile of this pass
@@ -342,12 +346,9 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       pk.y = pack_h16x2(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3]);
       *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, f, Mpad)) = pk;
     }
-  } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this workgroup's vocabulary slice
+  } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this pass's part of the workgroup's vocabulary slice
     const SampleCtl ctl = *a.ctl;
     const int step = *a.d_step;
-    Lse lse = lse_empty();
-    float by = -INFINITY, bz = 0.f;
-    int bi = 0x7fffffff;
 #pragma unroll
     for (int nb = 0; nb < NBP; ++nb) {
       if (nbase + nb >= a.n_tiles) continue;
@@ -361,27 +362,32 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       for (int r = 0; r < 4; ++r) {
         const float z = sum[nb][r] * sc;
         const float zt = ctl.greedy ? z : z * ctl.inv_temp;
-        lse_push(lse, zt);
+        lse_push(smp_lse, zt);
         const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
-        if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: the first maximum wins
+        if (y > smp_y) { smp_y = y; smp_i = v0 + r; smp_z = zt; }  // ascending index: the first maximum wins
       }
-    }
-#pragma unroll
-    for (int o = 16; o <= 32; o <<= 1) {
-      const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
-      const float oy = __shfl_xor(by, o, 64), oz = __shfl_xor(bz, o, 64);
-      const int oi = __shfl_xor(bi, o, 64);
-      lse = lse_merge(lse, ol);
-      if (oy > by || (oy == by && oi < bi)) { by = oy; bi = oi; bz = oz; }
-    }
-    if (lane < 16 && m < a.M) {
-      // row-major per token row, so that the merge reads a row's partials as one contiguous run
-      DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)m * n_groups + grp;
-      p->m = lse.m; p->s = lse.s; p->y = by; p->idx = bi; p->zt = bz;
     }
   }
   }  // token tiles of this wavefront
   }  // passes
+  if (EPI == DEPI_SAMPLE) {
+    if (wave < MB && mt0 + wave < a.m_tiles) {
+      const int col = lane & 15, m = (mt0 + wave) * 16 + col;
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const Lse ol = {__shfl_xor(smp_lse.m, o, 64), __shfl_xor(smp_lse.s, o, 64)};
+        const float oy = __shfl_xor(smp_y, o, 64), oz = __shfl_xor(smp_z, o, 64);
+        const int oi = __shfl_xor(smp_i, o, 64);
+        smp_lse = lse_merge(smp_lse, ol);
+        if (oy > smp_y || (oy == smp_y && oi < smp_i)) { smp_y = oy; smp_i = oi; smp_z = oz; }
+      }
+      if (lane < 16 && m < a.M) {
+        // row-major per token row, so that the merge reads a row's partials as one contiguous run
+        DecSamplePartial* p = reinterpret_cast<DecSamplePartial*>(a.out_f32) + (size_t)m * n_groups + grp;
+        p->m = smp_lse.m; p->s = smp_lse.s; p->y = smp_y; p->idx = smp_i; p->zt = smp_z;
+      }
+    }
+  }
 }
 
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int NBP = NB>
@@ -393,7 +399,9 @@ static void launch_dec_t(const DecGemmArgs& a0, int epi, hipStream_t st, int msp
   if constexpr (NBP != NB) {  // several passes over the exchange buffer: SwiGLU and split-K shapes only
     const dim3 grid(gx, epi == DEPI_PARTIAL ? a.ksplit : 1), block(WAVES * 64);
     if (epi == DEPI_PARTIAL) k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_PARTIAL, NBP><<<grid, block, 0, st>>>(a);
-    else k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
+    else if (epi == DEPI_SAMPLE) {
+      if constexpr (MB <= WAVES) k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SAMPLE, NBP><<<grid, block, 0, st>>>(a);
+    } else k_gemm_dec<NB, MB, WAVES, PFW, PFX, MINW, DEPI_SWIGLU, NBP><<<grid, block, 0, st>>>(a);
   } else {
     const dim3 grid(gx, epi == DEPI_PARTIAL ? a.ksplit : msplit);
     const dim3 block(WAVES * 64);
@@ -415,18 +423,22 @@ static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st, int
   if (a.k_tiles >= 48 && !(epi == DEPI_RESID && a.n_xchunks > 1)) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st, msplit);
   else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st, msplit);
 }
-// Wide shape: many row tiles (gate/up, LM head): NB tiles per workgroup, K split over 4 wavefronts.
+// Wide shape: many row tiles (gate/up, LM head) or a split K (down): NB tiles per workgroup, K split over its wavefronts.
+// What a CU pulls from L2 and HBM grows with the wavefronts it hosts, so the forms below put 8 to 12 on a CU where the
+// registers and LDS allow (LDS: the exchange buffer is walked in NB / NBP passes).
 template <int MB>
 static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
   if constexpr (MB > 4) {
-    // 128 rows: the activation operand is 8 KiB per k step against 1 KiB per weight row tile, and every
-    // workgroup reads all of it from L2, so four row tiles per workgroup halve the L2 traffic of two
-    launch_dec_t<4, 4, 4, 2, 2, 2>(a, epi, st, 1, true);
+    // 65..128 rows: the activation operand is 8 KiB per k step against 1 KiB per weight row tile and every workgroup
+    // reads its rows of it from L2: four row tiles x 64 rows per workgroup, the two workgroups of a tile set 8 apart in
+    // launch order (one XCD: the second read of the weights hits L2), three workgroups per CU
+    launch_dec_t<4, 4, 4, 2, 2, 3, 2>(a, epi, st, 1, true);
   } else {
     // every workgroup reads the whole activation operand, so a CU that hosts two workgroups takes about
     // twice as long as one that hosts one: one round of workgroups with 6 row tiles beats 1.x rounds with 4
     if (epi == DEPI_SWIGLU && a.n_tiles > 4 * 256 && a.n_tiles <= 6 * 256) launch_dec_t<6, MB, 8, 2, 2, 1, 2>(a, epi, st);
     else if (epi == DEPI_PARTIAL && a.partial_nb == 2) launch_dec_t<2, MB, 8, 2, 2, 1>(a, epi, st);
+    else if (epi == DEPI_SAMPLE) launch_dec_t<4, MB, 4, 2, 2, 3, 2>(a, epi, st);  // three workgroups per CU
     else launch_dec_t<4, MB, 4, 2, 2, 2>(a, epi, st);
   }
 }
