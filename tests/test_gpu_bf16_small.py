@@ -28,6 +28,8 @@ CASES = [
     ("small-ragged", SMALL, 0.05, 3, 37, 3, 21, 0.8),
     ("gqa6-b24", GQA6, 0.05, 3, 50, 8, 40, 1.0),
     ("gqa7-b64", GQA7, 0.05, 8, 20, 8, 20, 1.0),
+    ("gqa6-b40", GQA6, 0.05, 5, 21, 8, 12, 1.0),          # three row tiles: the second workgroup of a row split holds one
+    ("gqa4-b100", GQA4, 0.05, 25, 18, 4, 10, 1.0),        # seven row tiles of the 128-row form
     ("gqa6-b128", GQA6, 0.04, 16, 16, 8, 12, 1.0),
     ("gqa6-two-groups", GQA6, 0.04, 18, 9, 8, 6, 1.0),
     ("small-greedy", SMALL, 0.05, 2, 16, 1, 10, 0.0),
