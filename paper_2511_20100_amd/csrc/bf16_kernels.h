@@ -76,12 +76,22 @@ void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, cons
                   h16_t* x, float* ss_out, int M, hipStream_t st);
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);
 int dec_wide_nb(int m_tiles);
-void embed_dec(float* h, const int* ids, int B, const bf16_t* E, int d, int vocab, int* err_flag, const float* gain,
-               float eps, h16_t* x, int m_tiles, float* ss_out, hipStream_t st);
-// Merges the sampler partials of a step, writes the outputs of step *d_step and advances *d_step (d_step[1] is the
-// kernel's arrival counter: zero before the first launch, left at zero by every launch).
+// What the sampler merge prepares for the next decode step from the token it has just chosen for a row: the
+// residual h = E[token], x' = fp16(RMSNorm(h; gain)) in tiled layout (Mpad rows) and the per-tile sums of squares.
+struct EmbedNextArgs {
+  float* h;
+  const bf16_t* E;
+  int d;             // <= 4096
+  const float* gain;
+  float eps;
+  h16_t* x;
+  int Mpad;
+  float* ss_out;
+};
+// Merges the sampler partials of a step, writes the outputs of step *d_step, advances *d_step (d_step[1] is the
+// kernel's arrival counter: zero before the first launch, left at zero by every launch) and embeds the chosen tokens.
 void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,
-                  hipStream_t st);
+                  const EmbedNextArgs& emb, hipStream_t st);
 struct AttnDecArgs {
   const float* qkv;      // fp32 [B, (Hq + 2 Hkv) * 128], not yet rotated
   const float* cos;

@@ -517,60 +517,52 @@ void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, cons
 }
 
 // ---------------------------------------------------------------- embedding of the fed-back token
-// h = E[id]; exact row norm (the workgroup holds the whole row); x' = fp16(h g r); per-tile squares.
-__global__ __launch_bounds__(256) void k_embed_dec(float* h, const int* ids, const bf16_t* E, int d, int vocab,
-                                                   int* err_flag, const float* gain, float eps, h16_t* x,
-                                                   int Mpad, float* ss_out) {
-  __shared__ float red[16];
-  const int m = blockIdx.x;
-  int id = ids[m];
-  if (id < 0 || id >= vocab) {
-    if (threadIdx.x == 0) atomicOr(err_flag, 1);
-    id = id < 0 ? 0 : vocab - 1;
-  }
+// Row m of the residual for the next step: h = E[id]; exact row norm (the workgroup holds the whole row);
+// x' = fp16(h g r); per-tile sums of squares.  Runs at the end of the sampler merge, by all 256 threads of the
+// row's workgroup (16 elements each: d <= 4096).
+__device__ __forceinline__ void embed_row(const EmbedNextArgs& e, int m, int id, float* red) {
   float v[16];
   float ss = 0.f;
-  const int k = threadIdx.x * 16;
+  const int d = e.d, k = threadIdx.x * 16;
   const bool live = k < d;
   if (live) {
-    const v4u r0 = *reinterpret_cast<const v4u*>(E + (size_t)id * d + k);
-    const v4u r1 = *reinterpret_cast<const v4u*>(E + (size_t)id * d + k + 8);
+    const v4u r0 = *reinterpret_cast<const v4u*>(e.E + (size_t)id * d + k);
+    const v4u r1 = *reinterpret_cast<const v4u*>(e.E + (size_t)id * d + k + 8);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      v[2 * e] = __uint_as_float(r0[e] << 16);
-      v[2 * e + 1] = __uint_as_float(r0[e] & 0xffff0000u);
-      v[8 + 2 * e] = __uint_as_float(r1[e] << 16);
-      v[8 + 2 * e + 1] = __uint_as_float(r1[e] & 0xffff0000u);
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(r0[i] << 16);
+      v[2 * i + 1] = __uint_as_float(r0[i] & 0xffff0000u);
+      v[8 + 2 * i] = __uint_as_float(r1[i] << 16);
+      v[8 + 2 * i + 1] = __uint_as_float(r1[i] & 0xffff0000u);
     }
 #pragma unroll
-    for (int e = 0; e < 16; ++e) ss += v[e] * v[e];
+    for (int i = 0; i < 16; ++i) ss += v[i] * v[i];
 #pragma unroll
-    for (int e = 0; e < 16; e += 4)
-      *reinterpret_cast<v4f*>(h + (size_t)m * d + k + e) = v4f{v[e], v[e + 1], v[e + 2], v[e + 3]};
-    ss_out[(size_t)(k >> 4) * Mpad + m] = ss;
+    for (int i = 0; i < 16; i += 4)
+      *reinterpret_cast<v4f*>(e.h + (size_t)m * d + k + i) = v4f{v[i], v[i + 1], v[i + 2], v[i + 3]};
+    e.ss_out[(size_t)(k >> 4) * e.Mpad + m] = ss;
   }
   const float tot = block_sum(ss, red);
-  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+  const float r = 1.0f / sqrtf(tot / (float)d + e.eps);
   if (live) {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       v4u pk;
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        pk[e] = pack_h16x2(v[half * 8 + 2 * e] * gain[k + half * 8 + 2 * e] * r,
-                           v[half * 8 + 2 * e + 1] * gain[k + half * 8 + 2 * e + 1] * r);
-      *reinterpret_cast<v4u*>(x + act_off(m, k + half * 8, Mpad)) = pk;
+      for (int i = 0; i < 4; ++i)
+        pk[i] = pack_h16x2(v[half * 8 + 2 * i] * e.gain[k + half * 8 + 2 * i] * r,
+                           v[half * 8 + 2 * i + 1] * e.gain[k + half * 8 + 2 * i + 1] * r);
+      *reinterpret_cast<v4u*>(e.x + act_off(m, k + half * 8, e.Mpad)) = pk;
     }
   }
-}
-void embed_dec(float* h, const int* ids, int B, const bf16_t* E, int d, int vocab, int* err_flag, const float* gain,
-               float eps, h16_t* x, int m_tiles, float* ss_out, hipStream_t st) {
-  k_embed_dec<<<B, 256, 0, st>>>(h, ids, E, d, vocab, err_flag, gain, eps, x, m_tiles * 16, ss_out);
 }
 
 // ---------------------------------------------------------------- sampler merge (per row)
 __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* part, int n_groups, int M,
-                                                      const SampleCtl* ctlp, int* d_step, int* cur_ids) {
+                                                      const SampleCtl* ctlp, int* d_step, int* cur_ids,
+                                                      EmbedNextArgs emb) {
+  __shared__ float red[16];
+  __shared__ int s_tok;
   __shared__ Lse s_lse[4];
   __shared__ float s_y[4], s_z[4];
   __shared__ int s_i[4];
@@ -624,6 +616,7 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
       }
     }
     cur_ids[b] = tok;
+    s_tok = tok;
     ctl.out_ids[(size_t)b * ctl.max_new + step] = tok;
     ctl.out_logprobs[(size_t)b * ctl.max_new + step] = lp;
     // the last row to get here advances the step counter: by then every row has read it (d_step[1] counts
@@ -634,11 +627,13 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
       d_step[0] = step + 1;
     }
   }
+  __syncthreads();
+  embed_row(emb, b, s_tok, red);  // the row's operand of the next step's first GEMM
 }
 void sample_merge(const float* part, int n_groups, int M, const SampleCtl* ctl, int* d_step, int* cur_ids,
-                  hipStream_t st) {
+                  const EmbedNextArgs& emb, hipStream_t st) {
   k_sample_merge<<<M, 256, 0, st>>>(reinterpret_cast<const DecSamplePartial*>(part), n_groups, M, ctl, d_step,
-                                    cur_ids);
+                                    cur_ids, emb);
 }
 
 

@@ -345,8 +345,6 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
   h16_t* a = (h16_t*)p.a;
   float* ss[2] = {p.ssA, p.ssB};
   int cur = 0, old = 0;
-  bf16::embed_dec(h, p.cur_ids, B, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, w->layers[0].attn_norm, c.rms_eps,
-                  x, bt, ss[0], st);
   bf16::DecGemmArgs g{};
   g.m_tiles = bt; g.M = B; g.ss_tiles = D.nt_d; g.inv_d = 1.0f / (float)D.d; g.eps = c.rms_eps;
   for (int l = 0; l < c.n_layers; ++l) {
@@ -517,7 +515,10 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       lm.ctl = (const bf16::SampleCtl*)p.ctl; lm.d_step = p.d_step;
       bf16::gemm_dec(lm, bf16::DEC_SAMPLE, s);
       const int groups = (D.nt_V + bf16::dec_wide_nb(gp.bt) - 1) / bf16::dec_wide_nb(gp.bt);
-      bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, s);  // also ++*d_step
+      // also ++*d_step, and the embedding + first norm of the chosen tokens: the next step starts at its QKV projection
+      const bf16::EmbedNextArgs emb{p.hB, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xB,
+                                    gp.bt * 16, p.ssA};
+      bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, emb, s);
     };
     auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) {
       const float *ss_cur = nullptr, *ss_old = nullptr;
