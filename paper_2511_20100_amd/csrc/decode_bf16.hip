@@ -835,16 +835,36 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     cur = load_kv<DHD>(dec_page<DHD>(pool, a.layer, 0, i0, g), dec_page<DHD>(pool, a.layer, 0, i1, g),
                   dec_page<DHD>(pool, a.layer, 1, i0, g), dec_page<DHD>(pool, a.layer, 1, i1, g), lane);
   }
-  for (int pg = pg0; pg < p_hi; pg += 2 * AW) {
-    const int pn = pg + 2 * AW;
-    KvFrags<DHD> nxt = cur;
-    if (pn < p_hi) {
-      const int i0 = page_id(pn), i1 = page_id(pn + 1);
-      nxt = load_kv<DHD>(dec_page<DHD>(pool, a.layer, 0, i0, g), dec_page<DHD>(pool, a.layer, 0, i1, g),
-                    dec_page<DHD>(pool, a.layer, 1, i0, g), dec_page<DHD>(pool, a.layer, 1, i1, g), lane);
-    }
-    attn_step1<DHD>(cur, pg * kPageTokens, qf, qpos, scale, st, lane);
-    cur = nxt;
+  // Stage j of this wavefront = pages pg0 + 2 AW j, +1.  Two register sets alternate: while one is multiplied the
+  // loads of the next stage fill the other.  The loop body has no conditional load (a load behind a branch makes
+  // the compiler wait for every outstanding load at the join, i.e. for the prefetch it has just issued) and no
+  // copies between the sets; the last one or two stages are taken outside the loop.
+  const h16_t* kbase = dec_page<DHD>(pool, a.layer, 0, 0, g);
+  const h16_t* vbase = dec_page<DHD>(pool, a.layer, 1, 0, g);
+  const size_t pstride = (size_t)pool.n_kv_heads * (kPageTokens * DHD);
+  auto load_stage = [&](int j) {
+    const int pg = pg0 + 2 * AW * j;
+    const size_t o0 = (size_t)page_id(pg) * pstride, o1 = (size_t)page_id(pg + 1) * pstride;
+    return load_kv<DHD>(kbase + o0, kbase + o1, vbase + o0, vbase + o1, lane);
+  };
+  auto attend = [&](const KvFrags<DHD>& f, int j) {
+    attn_step1<DHD>(f, (pg0 + 2 * AW * j) * kPageTokens, qf, qpos, scale, st, lane);
+  };
+  const int n_st = pg0 < p_hi ? (p_hi - pg0 + 2 * AW - 1) / (2 * AW) : 0;
+  KvFrags<DHD> alt;
+  int j = 0;
+  for (; j + 2 < n_st; j += 2) {
+    alt = load_stage(j + 1);
+    attend(cur, j);
+    cur = load_stage(j + 2);
+    attend(alt, j + 1);
+  }
+  if (j + 1 < n_st) {
+    alt = load_stage(j + 1);
+    attend(cur, j);
+    attend(alt, j + 1);
+  } else if (j < n_st) {
+    attend(cur, j);
   }
   float l = st.l;
   l += __shfl_xor(l, 16, 64);
