@@ -682,9 +682,13 @@ __device__ __forceinline__ KvFrags<HD> load_kv(const h16_t* K0, const h16_t* K1,
 }
 
 // One step (two pages, 32 tokens from tok0) of a single block of query columns on loaded fragments.
-template <int HD>
+// The softmax state is kept in base-2 units: scale2 = log2(e) / sqrt(head_dim), st.m = running maximum of
+// scale2 * score, weights = 2^(scale2 * score - m) (one v_exp_f32 each).  MASK = false: every token of the step
+// is visible to the query (tok0 + 31 <= position), so nothing is compared; the unused columns (zero queries)
+// then carry finite garbage that nobody reads.
+template <int HD, bool MASK>
 __device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const v8bf (&qf)[HD / 32], int qpos,
-                                           float scale, AttnState<HD / 16>& st, int lane) {
+                                           float scale2, AttnState<HD / 16>& st, int lane) {
   const int lg = lane >> 4;
   v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
@@ -697,19 +701,19 @@ __device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int t0 = tok0 + 4 * lg + r, t1 = t0 + 16;
-    sv[r] = (t0 <= qpos) ? s0[r] * scale : -INFINITY;
-    sv[4 + r] = (t1 <= qpos) ? s1[r] * scale : -INFINITY;
+    sv[r] = (!MASK || t0 <= qpos) ? s0[r] * scale2 : -INFINITY;
+    sv[4 + r] = (!MASK || t1 <= qpos) ? s1[r] * scale2 : -INFINITY;
     tmax = fmaxf(tmax, fmaxf(sv[r], sv[4 + r]));
   }
   tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
   const float m_new = fmaxf(st.m, tmax);
-  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  const float corr = expf(st.m - m_safe);
+  const float m_safe = (MASK && m_new == -INFINITY) ? 0.f : m_new;
+  const float corr = __builtin_amdgcn_exp2f(st.m - m_safe);
   float p[8], psum = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    p[e] = expf(sv[e] - m_safe);
+    p[e] = __builtin_amdgcn_exp2f(sv[e] - m_safe);
     psum += p[e];
   }
   st.l = st.l * corr + psum;
@@ -720,9 +724,12 @@ __device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const
   pk[2] = pack_h16x2(p[4], p[5]);
   pk[3] = pack_h16x2(p[6], p[7]);
   const v8bf pf = __builtin_bit_cast(v8bf, pk);
+  if (__any(corr != 1.0f)) {  // the running maximum of some column moved: rescale what has been summed
 #pragma unroll
-  for (int cb = 0; cb < HD / 16; ++cb)
-    st.o[cb] = mfma16(__builtin_bit_cast(v8bf, f.v[cb]), pf, st.o[cb] * corr);
+    for (int cb = 0; cb < HD / 16; ++cb) st.o[cb] = st.o[cb] * corr;
+  }
+#pragma unroll
+  for (int cb = 0; cb < HD / 16; ++cb) st.o[cb] = mfma16(__builtin_bit_cast(v8bf, f.v[cb]), pf, st.o[cb]);
 }
 
 template <int DHD>
@@ -827,7 +834,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   const int qpos = (col < G) ? pos : -1;
   AttnState<DHD / 16> st;
   attn_init(st);
-  const float scale = DHD == 128 ? 0.08838834764831845f : 0.125f;  // 1 / sqrt(head_dim)
+  const float scale2 = (DHD == 128 ? 0.08838834764831845f : 0.125f) * 1.4426950408889634f;  // log2(e) / sqrt(head_dim)
   auto page_id = [&](int pg) { return s_table[min(pg, n_ctx_pages - 1) - p_lo]; };
   // the speculative load may have raced with the append above: redo it if it covers the current page
   if (owner_wg && (cur_page == pg0 || cur_page == pg0 + 1) && pg0 < p_hi) {
@@ -847,24 +854,28 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     const size_t o0 = (size_t)page_id(pg) * pstride, o1 = (size_t)page_id(pg + 1) * pstride;
     return load_kv<DHD>(kbase + o0, kbase + o1, vbase + o0, vbase + o1, lane);
   };
-  auto attend = [&](const KvFrags<DHD>& f, int j) {
-    attn_step1<DHD>(f, (pg0 + 2 * AW * j) * kPageTokens, qf, qpos, scale, st, lane);
+  // a stage that is followed by another stage of this wavefront lies wholly before the current position
+  auto attend_full = [&](const KvFrags<DHD>& f, int j) {
+    attn_step1<DHD, false>(f, (pg0 + 2 * AW * j) * kPageTokens, qf, qpos, scale2, st, lane);
+  };
+  auto attend_last = [&](const KvFrags<DHD>& f, int j) {
+    attn_step1<DHD, true>(f, (pg0 + 2 * AW * j) * kPageTokens, qf, qpos, scale2, st, lane);
   };
   const int n_st = pg0 < p_hi ? (p_hi - pg0 + 2 * AW - 1) / (2 * AW) : 0;
   KvFrags<DHD> alt;
   int j = 0;
   for (; j + 2 < n_st; j += 2) {
     alt = load_stage(j + 1);
-    attend(cur, j);
+    attend_full(cur, j);
     cur = load_stage(j + 2);
-    attend(alt, j + 1);
+    attend_full(alt, j + 1);
   }
   if (j + 1 < n_st) {
     alt = load_stage(j + 1);
-    attend(cur, j);
-    attend(alt, j + 1);
+    attend_full(cur, j);
+    attend_last(alt, j + 1);
   } else if (j < n_st) {
-    attend(cur, j);
+    attend_last(cur, j);
   }
   float l = st.l;
   l += __shfl_xor(l, 16, 64);
@@ -889,7 +900,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     for (int w = 0; w < AW; ++w) mm = fmaxf(mm, s_m[w][c]);
 #pragma unroll
     for (int w = 0; w < AW; ++w) {
-      const float f = expf(s_m[w][c] - mm);
+      const float f = __builtin_amdgcn_exp2f(s_m[w][c] - mm);
       ll += f * s_l[w][c];
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += f * s_o[w][c][d0 + e];
@@ -904,7 +915,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     *reinterpret_cast<v4u*>(a.o + chunk * a.o_chunk_stride + act_off(b, (g * G + c) * DHD + d0, Mpad)) = pk;
     if (a.n_chunks > 1 && d0 == 0) {
       float* ml = a.ml + (((size_t)b * Hq + g * G + c) * a.n_chunks + chunk) * 2;
-      ml[0] = mm;
+      ml[0] = mm * 0.6931471805599453f;  // the consumer works in natural units
       ml[1] = ll;
     }
   }
