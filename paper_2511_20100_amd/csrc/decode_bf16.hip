@@ -719,10 +719,10 @@ __device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const
   st.l = st.l * corr + psum;
   st.m = m_new;
   v4u pk;
-  pk[0] = pack_h16x2(p[0], p[1]);
-  pk[1] = pack_h16x2(p[2], p[3]);
-  pk[2] = pack_h16x2(p[4], p[5]);
-  pk[3] = pack_h16x2(p[6], p[7]);
+  pk[0] = pack_h16x2_inrange(p[0], p[1]);  // weights lie in [0, 1]
+  pk[1] = pack_h16x2_inrange(p[2], p[3]);
+  pk[2] = pack_h16x2_inrange(p[4], p[5]);
+  pk[3] = pack_h16x2_inrange(p[6], p[7]);
   const v8bf pf = __builtin_bit_cast(v8bf, pk);
   if (__any(corr != 1.0f)) {  // the running maximum of some column moved: rescale what has been summed
 #pragma unroll
