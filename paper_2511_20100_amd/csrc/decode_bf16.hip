@@ -64,7 +64,29 @@ struct DecStream {
 
   __device__ __forceinline__ void run(v4f (&acc)[NB][MB]) {
     if (k0 >= k1) return;
-    for (int ks = k0; ks < k1; ks += PFW) {
+    int ks = k0;
+    // Steady state: every slot that is multiplied is refilled, unconditionally.  (A refill behind a branch makes the
+    // compiler wait, at the join, for every outstanding load -- the other slots' refills included -- so the ring
+    // would never hold more than one slot in flight.)
+    for (; ks + 2 * PFW <= k1; ks += PFW) {
+#pragma unroll
+      for (int s = 0; s < PFW; ++s) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s % PFX][mb], acc[nb][mb]);
+        // the slot's refill goes out before the next slot is multiplied (the scheduler would otherwise sink every
+        // load to the end of the trip, behind all the products)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)(ks + s + PFW) * 512, 0);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) xr[s % PFX][mb] = load_frag(xp[mb] + (size_t)(ks + s + PFX) * xstep, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // the last PFW .. 2 PFW - 1 steps: refills only while the range lasts
+    for (; ks < k1; ks += PFW) {
 #pragma unroll
       for (int s = 0; s < PFW; ++s) {
         if (ks + s < k1) {
