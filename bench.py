@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 # HBM bytes one launch of the gate/up decode kernel moves at the 1.5B workload, from FETCH_SIZE / WRITE_SIZE
 # counter runs scaled by the library's copy kernel (profiles/decode_kernels_1p5b_hbm_counters.txt).
 # Belongs to k_gemm_dec<6, 4, 8, 2, 2, 1, SWIGLU, 2>: set to None when that kernel or its launch shape changes.
-GATE_UP_TRAFFIC_1P5B = 27932.0 * 1024 * 2.000 + 1120.0 * 1024 * 1.000
+GATE_UP_TRAFFIC_1P5B = 27939.5 * 1024 * 2.000 + 1120.0 * 1024 * 1.000
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
 
 WORKLOADS = {
