@@ -253,7 +253,8 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
           }
 #pragma unroll
         for (int c = 0; c < NCM; ++c) {
-          const h16_t* xp = a.Xt + (size_t)min(c, NC - 1) * a.x_chunk_stride + lane * 8;
+          if (c >= NC) break;  // NC is uniform: the chunks that do not exist are neither loaded nor multiplied
+          const h16_t* xp = a.Xt + (size_t)c * a.x_chunk_stride + lane * 8;
 #pragma unroll
           for (int t = 0; t < 4; ++t)
 #pragma unroll

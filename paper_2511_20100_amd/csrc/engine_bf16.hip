@@ -272,6 +272,8 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   // page ids of a chunk are staged in LDS; kMaxDecodeContext keeps the chunk count within max_chunks
   p.chunk_pages = std::min(p.chunk_pages, 512);
   p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
+  p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;  // equal chunks again after the clamp
+  p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
   const size_t Mpad = (size_t)p.bt * 16;
   const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;
   p.part = cv.take<float>(part);
