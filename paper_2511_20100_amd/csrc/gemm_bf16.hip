@@ -39,7 +39,26 @@ __device__ __forceinline__ void wave_gemm(const h16_t* __restrict__ Wt, int k_ti
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)kk * xstep, 0);
   }
-  for (int ks = k0; ks < k1; ks += PF) {
+  int ks = k0;
+  // Steady state: every slot that is multiplied is refilled, unconditionally, and before the next slot is
+  // multiplied.  (Behind a branch the refill makes the compiler wait at the join for every outstanding load, the
+  // other slot's included; unpinned, it sinks all loads of a trip behind all its products.)
+  for (; ks + 2 * PF <= k1; ks += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma16(wr[s][nb], xr[s][mb], acc[nb][mb]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) wr[s][nb] = load_frag(wp[nb] + (size_t)(ks + s + PF) * 512, 0);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) xr[s][mb] = load_frag(xp[mb] + (size_t)(ks + s + PF) * xstep, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  for (; ks < k1; ks += PF) {  // the last PF .. 2 PF - 1 steps: refills only while the range lasts
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
       if (ks + s < k1) {
