@@ -101,6 +101,7 @@ struct AttnDecArgs {
   const int* d_step;
   KvPool pool;
   int chunk_pages, n_chunks, m_tiles;
+  int split_at_prompt;   // n_chunks == 2: chunk 0 = the whole pages of the sequence's prompt (pos_base / row_pos), chunk 1 = the rest
   int share;             // consecutive sequences that share prompt pages (samples per prompt); B % share == 0
   h16_t* o;              // tiled fp16 [Hq * hd (k), m_tiles * 16], one per chunk, o_chunk_stride elements apart:
   size_t o_chunk_stride; //   the output over the chunk's keys alone, normalised by the chunk's own sum

@@ -189,7 +189,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   const int k0 = kbeg + wave * per_wave, k1 = min(kend, k0 + per_wave);
   // O projection behind a context-split attention: the operand comes in chunks that are combined below
   bool chunked = false;
-  if constexpr (EPI == DEPI_RESID && NB == 1 && WAVES == 8 && MB <= 4) chunked = a.n_xchunks > 1;  // workgroup-uniform
+  if constexpr (EPI == DEPI_RESID && NB == 1 && (WAVES == 8 || WAVES == 12) && MB <= 4) chunked = a.n_xchunks > 1;  // workgroup-uniform
   DecStream<NB, MB, PFW, PFX> stream;
   stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, k0, chunked ? k0 : k1, lane);
 #pragma unroll
@@ -226,13 +226,14 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = v4f{0.f, 0.f, 0.f, 0.f};
   stream.run(acc);
-  if constexpr (EPI == DEPI_RESID && NB == 1 && WAVES == 8 && MB <= 4) {
+  if constexpr (EPI == DEPI_RESID && NB == 1 && (WAVES == 8 || WAVES == 12) && MB <= 4) {
     if (chunked) {
       // out[n][row] = sum_head sum_chunk share(row, head, chunk) * (W[n, head] . o_chunk[head, row]), where o_chunk is
       // the attention output over the chunk's keys normalised by the chunk's own sum l, and
       // share = l exp(m - max_c m) / sum_c l exp(m - max_c m).  Wavefront w takes heads w, w + WAVES, ...; everything
       // a head needs (its weight tiles, the operand tiles of every chunk, the chunk statistics) is requested at once.
-      constexpr int NCM = MB >= 4 ? 2 : MB == 2 ? 4 : 8;  // chunks at most (the host keeps MB * chunks <= 8)
+      // chunks at most (the host keeps MB * chunks <= 8); the 12-wavefront form holds two, in half the registers
+      constexpr int NCM = WAVES == 12 ? 2 : MB >= 4 ? 2 : MB == 2 ? 4 : 8;
       const int HT = a.head_tiles, n_heads = a.k_tiles / HT, NC = a.n_xchunks;
       const int col = lane & 15;
       const h16_t* wp = a.Wt + (size_t)min(nt0, a.n_tiles - 1) * a.k_tiles * 512 + lane * 8;
@@ -441,9 +442,10 @@ static void launch_dec_t(const DecGemmArgs& a0, int epi, hipStream_t st, int msp
 // Narrow shape: one weight row tile per workgroup, K split over 8 or 16 wavefronts (QKV, O, down).
 template <int MB>
 static void launch_dec_narrow(const DecGemmArgs& a, int epi, hipStream_t st, int msplit = 1) {
-  // 16 wavefronts split long K ranges; the chunked O projection keeps 8, which leaves a wavefront the registers
-  // to hold a whole head's operands of every chunk at once
+  // 16 wavefronts split long K ranges; the chunked O projection, where a wavefront holds a whole head's operands of
+  // every chunk at once, takes 12 wavefronts for two chunks (12 heads: one round of loads) and 8 for more
   if (a.k_tiles >= 48 && !(epi == DEPI_RESID && a.n_xchunks > 1)) launch_dec_t<1, MB, 16, 3, 3, 1>(a, epi, st, msplit);
+  else if (epi == DEPI_RESID && MB <= 2 && a.n_xchunks == 2) launch_dec_t<1, MB, 12, 3, 3, 1>(a, DEPI_RESID, st, msplit);
   else launch_dec_t<1, MB, 8, 3, 3, 1>(a, epi, st, msplit);
 }
 // Wide shape: many row tiles (gate/up, LM head) or a split K (down): NB tiles per workgroup, K split over its wavefronts.
@@ -782,12 +784,20 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   const int col = lane & 15, lg = lane >> 4;
   const KvPool& pool = a.pool;
   const int* table = pool.page_table + (size_t)b * pool.max_pages;
-  const int p_lo = chunk * a.chunk_pages;
+  const int pos0 = a.row_pos ? a.row_pos[b] : a.pos_base;
+  // Pages [p_lo, p_end) of the sequence are this workgroup's.  Either equal chunks, or (two chunks, split_at_prompt)
+  // the whole pages of the prompt and the rest: a boundary that depends on the sequence alone, so that a sequence
+  // gets the same arithmetic whatever else is in the batch and however many tokens the call may generate.
+  int p_lo = chunk * a.chunk_pages, p_end = p_lo + a.chunk_pages;
+  if (a.split_at_prompt) {
+    const int nb = ((pos0 + 1) / kPageTokens) & ~1;  // even: the steps below take pages in pairs
+    p_lo = chunk ? nb : 0;
+    p_end = chunk ? pool.max_pages : nb;
+  }
   // ---- loads that do not depend on the position: step counter, this chunk's page ids, the raw
   // q/k/v row, and (speculatively) the first pair of pages of this wavefront
   const int step = *a.d_step;
-  const int pos0 = a.row_pos ? a.row_pos[b] : a.pos_base;
-  for (int i = tid; i < a.chunk_pages; i += AW * 64) s_table[i] = table[min(p_lo + i, pool.max_pages - 1)];
+  for (int i = tid; i < p_end - p_lo; i += AW * 64) s_table[i] = table[min(p_lo + i, pool.max_pages - 1)];
   const float* row = a.qkv + (size_t)b * (Hq + 2 * Hkv) * DHD;
   float qraw[2] = {0.f, 0.f};
   const int qj = tid >> 6, qi = tid & 63;  // wavefront j rotates head j (AW >= G)
@@ -805,7 +815,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   // ---- position-dependent part
   const int pos = pos0 + step;
   const int n_ctx_pages = pos / kPageTokens + 1;
-  const int p_hi = min(n_ctx_pages, p_lo + a.chunk_pages);
+  const int p_hi = min(n_ctx_pages, p_end);
   if (p_lo >= p_hi) {
     // this chunk lies beyond the context: it contributes nothing, which its consumer learns from a zero sum;
     // the operand slice is cleared so that stale bits (possibly NaN patterns) never meet a zero weight

@@ -70,6 +70,7 @@ struct RolloutPlan {
   float* ssB;
   float* rs_buf;      // 1/rms per row, handed from the split-K down projection to its reduction
   int chunk_pages, n_chunks;       // decode-attention context split
+  int split_at_prompt;             // two chunks: the prompt's whole pages | the rest (else equal chunks)
   int ks_qkv, ks_o, ks_down;       // split-K factors of the decode GEMMs
   int down_nb;                     // weight row tiles per workgroup of the down projection (2 or 4)
   int bt;                          // 16-row tiles covering B

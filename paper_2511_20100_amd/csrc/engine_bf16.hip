@@ -260,10 +260,10 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
     p.down_nb = 2;
     p.ks_down = std::max(1, std::min(256 / ((D.nt_d + 1) / 2), D.kt_F / 16));
   }
-  // context split of the decode attention for small batches, up to about 128 workgroups of 8 wavefronts (beyond
-  // that the attention kernel's fixed part dominates and the split only costs the O projection, which combines
-  // the chunks, a second operand: measured at batch 64 with 2 kv heads)
-  const int want = std::max(1, 128 / std::max(1, p.B * D.Hkv));
+  // context split of the decode attention: for small batches up to about 128 workgroups of 8 wavefronts, and two
+  // ways at 33..64 rows (256 workgroups: the O projection combines two chunks in its 12-wavefront form at little
+  // extra cost; with its 8-wavefront form the split lost what the attention gained)
+  const int want = std::max(p.bt >= 3 && p.bt <= 4 ? 2 : 1, 128 / std::max(1, p.B * D.Hkv));
   // the O projection that combines the chunks holds (row tiles per workgroup) * chunks <= 8 operand sets: its
   // workgroups take one row tile up to 32 rows and two beyond
   const int max_chunks = p.bt <= 2 ? 8 : 4;
@@ -274,6 +274,9 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
   p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;  // equal chunks again after the clamp
   p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
+  // the two-way split at 33..64 rows is made at the end of each sequence's prompt (its shared pages | its own):
+  // independent of max_new and of the other sequences, and about even when prompts and generations are of a size
+  p.split_at_prompt = (p.bt >= 3 && p.bt <= 4 && p.n_chunks == 2 && p.max_pages <= 512) ? 1 : 0;
   const size_t Mpad = (size_t)p.bt * 16;
   const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;
   p.part = cv.take<float>(part);
@@ -359,7 +362,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     mark(MTMC_KERNEL_QKV);
     bf16::AttnDecArgs at{};
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
-    at.pos_base = pos_base; at.row_pos = p.ragged ? p.row_pos : nullptr; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages;
+    at.pos_base = pos_base; at.row_pos = p.ragged ? p.row_pos : nullptr; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages; at.split_at_prompt = p.split_at_prompt;
     at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples;
     at.o = (h16_t*)p.o_chunks; at.o_chunk_stride = (size_t)D.nq * bt * 16; at.ml = p.attn_ml;
     mark(MTMC_KERNEL_ATTENTION);
