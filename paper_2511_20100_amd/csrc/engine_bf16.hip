@@ -261,9 +261,9 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
     p.ks_down = std::max(1, std::min(256 / ((D.nt_d + 1) / 2), D.kt_F / 16));
   }
   // context split of the decode attention: for small batches up to about 128 workgroups of 8 wavefronts, and two
-  // ways at 33..64 rows (256 workgroups: the O projection combines two chunks in its 12-wavefront form at little
+  // ways at 33..64 rows when that still leaves at most 256 workgroups (the O projection combines two chunks in its 12-wavefront form at little
   // extra cost; with its 8-wavefront form the split lost what the attention gained)
-  const int want = std::max(p.bt >= 3 && p.bt <= 4 ? 2 : 1, 128 / std::max(1, p.B * D.Hkv));
+  const int want = std::max(p.bt >= 3 && p.bt <= 4 && p.B * D.Hkv <= 128 ? 2 : 1, 128 / std::max(1, p.B * D.Hkv));
   // the O projection that combines the chunks holds (row tiles per workgroup) * chunks <= 8 operand sets: its
   // workgroups take one row tile up to 32 rows and two beyond
   const int max_chunks = p.bt <= 2 ? 8 : 4;
