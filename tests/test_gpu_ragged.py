@@ -61,6 +61,8 @@ CASES = [
     ("small-mixed", SMALL, 0.05, [37, 16, 1, 33], 3, 21, 0.8),
     ("gqa6-two-groups", GQA6, 0.04, [9, 3, 20, 16, 7, 32, 1, 12, 25, 31, 17, 2, 8, 30, 11, 5, 19, 14], 8, 6, 1.0),
     ("gqa6-long", GQA6, 0.05, [150, 64, 90], 4, 30, 1.0),
+    # 40 rows: the context of every sequence is split at the end of its own prompt (0, 0, 2, 4 and 6 whole page pairs)
+    ("small-b40-split", SMALL, 0.05, [5, 16, 33, 70, 120], 8, 14, 1.0),
     ("hd64-mixed", inputs.ModelConfig(2, 256, 4, 2, 64, 688, 4096, dtype="bf16"), 0.05, [37, 16, 1, 33, 70], 3, 21, 1.0),
 ]
 
