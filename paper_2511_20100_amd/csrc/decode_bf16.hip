@@ -192,6 +192,42 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   if constexpr (EPI == DEPI_RESID && NB == 1 && (WAVES == 8 || WAVES == 12) && MB <= 4) chunked = a.n_xchunks > 1;  // workgroup-uniform
   DecStream<NB, MB, PFW, PFX> stream;
   stream.start(a.Wt, a.k_tiles, a.n_tiles, nt0, a.Xt, a.m_tiles, mt0, k0, chunked ? k0 : k1, lane);
+  // Chunk-combining form: what one head needs (its weight tiles, the operand tiles of every chunk, the chunk
+  // statistics).  chunks at most: the host keeps MB * chunks <= 8; the 12-wavefront form, which only ever runs with
+  // two chunks, holds two in half the registers and requests its first head here, in the shadow of the row scales.
+  constexpr bool kCombines = (EPI == DEPI_RESID && NB == 1 && (WAVES == 8 || WAVES == 12) && MB <= 4);
+  constexpr int NCM = !kCombines ? 1 : WAVES == 12 ? 2 : MB >= 4 ? 2 : MB == 2 ? 4 : 8;
+  v8bf c_wf[4], c_xf[NCM][4][MB];
+  float c_m[NCM][MB], c_l[NCM][MB];
+  auto load_head = [&](int j) {
+    const int HT = a.head_tiles, n_heads = a.k_tiles / HT, NC = a.n_xchunks;
+    const int col = lane & 15;
+    const h16_t* wp = a.Wt + (size_t)min(nt0, a.n_tiles - 1) * a.k_tiles * 512 + lane * 8;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) c_wf[t] = load_frag(wp + (size_t)(j * HT + min(t, HT - 1)) * 512, 0);
+#pragma unroll
+    for (int c = 0; c < NCM; ++c)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int row = (mt0 + mb) * 16 + col;
+        const bool live = c < NC && row < a.M;
+        const float* ml = a.chunk_ml + (((size_t)row * n_heads + j) * NC + c) * 2;
+        c_m[c][mb] = live ? ml[0] : -INFINITY;
+        c_l[c][mb] = live ? ml[1] : 0.f;
+      }
+#pragma unroll
+    for (int c = 0; c < NCM; ++c) {
+      if (c >= NC) break;  // NC is uniform: the chunks that do not exist are neither loaded nor multiplied
+      const h16_t* xp = a.Xt + (size_t)c * a.x_chunk_stride + lane * 8;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          c_xf[c][t][mb] =
+              load_frag(xp + ((size_t)(j * HT + min(t, HT - 1)) * a.m_tiles + min(mt0 + mb, a.m_tiles - 1)) * 512, 0);
+    }
+  };
+  if constexpr (kCombines && WAVES == 12) load_head(min(wave, a.k_tiles / a.head_tiles - 1));
 #pragma unroll
   for (int u = 0; u < BT; ++u) {
     sa += va[u];
@@ -230,50 +266,21 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
     if (chunked) {
       // out[n][row] = sum_head sum_chunk share(row, head, chunk) * (W[n, head] . o_chunk[head, row]), where o_chunk is
       // the attention output over the chunk's keys normalised by the chunk's own sum l, and
-      // share = l exp(m - max_c m) / sum_c l exp(m - max_c m).  Wavefront w takes heads w, w + WAVES, ...; everything
-      // a head needs (its weight tiles, the operand tiles of every chunk, the chunk statistics) is requested at once.
-      // chunks at most (the host keeps MB * chunks <= 8); the 12-wavefront form holds two, in half the registers
-      constexpr int NCM = WAVES == 12 ? 2 : MB >= 4 ? 2 : MB == 2 ? 4 : 8;
+      // share = l exp(m - max_c m) / sum_c l exp(m - max_c m).  Wavefront w takes heads w, w + WAVES, ...
       const int HT = a.head_tiles, n_heads = a.k_tiles / HT, NC = a.n_xchunks;
-      const int col = lane & 15;
-      const h16_t* wp = a.Wt + (size_t)min(nt0, a.n_tiles - 1) * a.k_tiles * 512 + lane * 8;
       for (int j = wave; j < n_heads; j += WAVES) {
-        v8bf wf[4], xf[NCM][4][MB];
-        float cm[NCM][MB], cl[NCM][MB];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) wf[t] = load_frag(wp + (size_t)(j * HT + min(t, HT - 1)) * 512, 0);
-#pragma unroll
-        for (int c = 0; c < NCM; ++c)
-#pragma unroll
-          for (int mb = 0; mb < MB; ++mb) {
-            const int row = (mt0 + mb) * 16 + col;
-            const bool live = c < NC && row < a.M;
-            const float* ml = a.chunk_ml + (((size_t)row * n_heads + j) * NC + c) * 2;
-            cm[c][mb] = live ? ml[0] : -INFINITY;
-            cl[c][mb] = live ? ml[1] : 0.f;
-          }
-#pragma unroll
-        for (int c = 0; c < NCM; ++c) {
-          if (c >= NC) break;  // NC is uniform: the chunks that do not exist are neither loaded nor multiplied
-          const h16_t* xp = a.Xt + (size_t)c * a.x_chunk_stride + lane * 8;
-#pragma unroll
-          for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-              xf[c][t][mb] =
-                  load_frag(xp + ((size_t)(j * HT + min(t, HT - 1)) * a.m_tiles + min(mt0 + mb, a.m_tiles - 1)) * 512, 0);
-        }
+        if (WAVES != 12 || j != wave) load_head(j);
         float mx[MB], den[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-          mx[mb] = cm[0][mb];
+          mx[mb] = c_m[0][mb];
 #pragma unroll
-          for (int c = 1; c < NCM; ++c) mx[mb] = fmaxf(mx[mb], cm[c][mb]);
+          for (int c = 1; c < NCM; ++c) mx[mb] = fmaxf(mx[mb], c_m[c][mb]);
           den[mb] = 0.f;
 #pragma unroll
           for (int c = 0; c < NCM; ++c) {
-            cl[c][mb] = (cl[c][mb] > 0.f) ? cl[c][mb] * expf(cm[c][mb] - mx[mb]) : 0.f;  // un-normalised share
-            den[mb] += cl[c][mb];
+            c_l[c][mb] = (c_l[c][mb] > 0.f) ? c_l[c][mb] * expf(c_m[c][mb] - mx[mb]) : 0.f;  // un-normalised share
+            den[mb] += c_l[c][mb];
           }
         }
 #pragma unroll
@@ -284,8 +291,8 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
             v4f part = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-              if (t < HT) part = mfma16(wf[t], xf[c][t][mb], part);
-            const float share = (den[mb] > 0.f) ? cl[c][mb] / den[mb] : 0.f;
+              if (t < HT) part = mfma16(c_wf[t], c_xf[c][t][mb], part);
+            const float share = (den[mb] > 0.f) ? c_l[c][mb] / den[mb] : 0.f;
             acc[0][mb] = acc[0][mb] + part * share;
           }
         }
