@@ -794,7 +794,8 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   const int pos0 = a.row_pos ? a.row_pos[b] : a.pos_base;
   // Pages [p_lo, p_end) of the sequence are this workgroup's.  Either equal chunks, or (two chunks, split_at_prompt)
   // the whole pages of the prompt and the rest: a boundary that depends on the sequence alone, so that a sequence
-  // gets the same arithmetic whatever else is in the batch and however many tokens the call may generate.
+  // gets the same arithmetic whatever else is in the batch and however many tokens the call may generate (given
+  // that the call splits at all: contexts of more than 8 pages).
   int p_lo = chunk * a.chunk_pages, p_end = p_lo + a.chunk_pages;
   if (a.split_at_prompt) {
     const int nb = ((pos0 + 1) / kPageTokens) & ~1;  // even: the steps below take pages in pairs

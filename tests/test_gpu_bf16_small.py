@@ -155,6 +155,24 @@ def test_calls_overlapping_on_two_streams_match_calls_in_turn(lib):
         lib.mtmc_weights_destroy(handle)
 
 
+def test_at_64_rows_the_first_tokens_do_not_depend_on_max_new(lib):
+    """At 33..64 rows the decode attention splits a sequence's context at the end of its prompt, a boundary that
+    depends on the sequence alone: once contexts are long enough to be split at all (more than 8 pages), a longer
+    generation budget (more pages per sequence) leaves the arithmetic of the first steps unchanged, bit for bit."""
+    import torch
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
+    try:
+        prompts = torch.from_numpy(inputs.make_prompts(8, 150, cfg.vocab, seed=5)).cuda()  # > 8 pages: split in both calls
+        short = lib.mtmc_rollout(handle, prompts, 8, 8, 1.0, 3)
+        long_ = lib.mtmc_rollout(handle, prompts, 8, 90, 1.0, 3)
+        torch.cuda.synchronize()
+        assert torch.equal(short[0], long_[0][:, :8]) and torch.equal(short[1], long_[1][:, :8])
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
 def test_kernel_timer_does_not_change_results(lib):
     import torch
     cfg = GQA6
