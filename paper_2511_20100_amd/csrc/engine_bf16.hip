@@ -336,9 +336,10 @@ void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, fl
   }
 }
 
-// One decode step over the B sequences of a group: embeds cur_ids, runs the blocks (six launches
-// each) against the paged cache at position prompt_len - 1 + *d_step and leaves in xB the operand
-// of the LM head together with the row-norm bookkeeping (*ss_cur, *ss_old) its consumer needs.
+// One decode step over the B sequences of a group.  In: hB / xB / ssA hold the embedded and normalised tokens of
+// the step (the sampler merge of the previous step leaves them).  Runs the blocks (six launches each) against the
+// paged cache at position prompt_len - 1 + *d_step and leaves in xB the operand of the LM head together with the
+// row-norm bookkeeping (*ss_cur, *ss_old) its consumer needs.
 void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, KvPool pool, int pos_base,
                    const float** ss_cur_out, const float** ss_old_out, hipStream_t st, KernelTimer* tm = nullptr) {
   auto mark = [&](int k) { if (tm) tm->mark(k); };
