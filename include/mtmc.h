@@ -47,10 +47,16 @@ extern "C" {
 #define MTMC_EINVAL  (-1)  /* null pointer, bad shape, unsupported configuration        */
 #define MTMC_ENOMEM  (-2)  /* workspace too small, or device allocation failed           */
 #define MTMC_EHIP    (-3)  /* a HIP runtime call failed; message holds hipGetErrorString */
-#define MTMC_EDATA   (-4)  /* a token id outside [0, vocab) was seen on the device       */
+#define MTMC_EDATA   (-4)  /* the device saw bad data: see mtmc_poll_errors                */
 
 #define MTMC_F32  0        /* matrices fp32, all arithmetic fp32                          */
-#define MTMC_BF16 1        /* matrices and KV cache bf16, fp32 accumulation and residual  */
+/* MTMC_BF16: the caller's matrices are bf16.  The library converts them once, at load, to IEEE fp16 (exact for
+ * every bf16 value of magnitude in [2^-17, 65504]; larger or non-finite weights are rejected, smaller ones lose
+ * at most 3e-8) and runs the matrix cores on fp16 operands: the activations that enter a matrix product and
+ * the KV cache are fp16 (11 significant bits, range +-65504), everything else -- residual stream, norms,
+ * softmax statistics, log-sum-exp, all accumulators -- is fp32.  A producer that has to clamp a value into
+ * the fp16 range raises MTMC_DATA_FP16_RANGE (see mtmc_poll_errors).                              */
+#define MTMC_BF16 1
 
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -118,8 +124,10 @@ int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompt
  * (Inference Pipeline, "Macro Thinking": the policy's output ends with a terminal action or at the
  * step limit).  Prompt p is prompts[p, :prompt_lens[p]]; the rest of its row is padding and never
  * influences a result.  Sequence b = p * n_samples + s continues prompt p exactly as mtmc_rollout
- * would continue it alone (same counters of the random generator, same results for any batch
- * composition).  With stop_id >= 0 a sequence ends with the first sampled stop_id: that token and
+ * would continue it alone (same counters of the random generator, so the same noise whatever else is in the
+ * batch; calls of the same shape give bit-identical results, and across batch sizes, which select other kernel
+ * tilings and so another order of the fp32 sums, log-probabilities agree to about 1e-3 and a sampled id can
+ * differ only where two candidates are that close).  With stop_id >= 0 a sequence ends with the first sampled stop_id: that token and
  * its log-probability are reported, every later slot of the row holds stop_id with log-probability
  * 0, and out_lens[b] = number of tokens generated including the stop token (max_new if none).
  * Finished sequences keep their slot in the batch: the call costs the same as without a stop token.
@@ -212,18 +220,32 @@ int mtmc_ppo_clip_loss(const float* new_logprobs, const float* old_logprobs, con
                        size_t workspace_bytes, void* stream);
 
 /*
- * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll saw a token
- * id outside [0, vocab) or an action / prompt length outside its range (the flag is cleared), MTMC_EHIP
- * on a runtime error, else MTMC_OK.
+ * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll raised a bit of the
+ * device's sticky data flag (the flag is cleared; mtmc_last_error() names the causes), MTMC_EHIP on a
+ * runtime error, else MTMC_OK.  The bits:
+ *   MTMC_DATA_TOKEN_ID    a token id outside [0, vocab) (clamped into range)
+ *   MTMC_DATA_WEIGHT      a weight that is not finite or, MTMC_BF16, exceeds 65504 in magnitude
+ *                         (mtmc_weights_create fails with MTMC_EINVAL on it)
+ *   MTMC_DATA_LENGTH      an action or prompt length outside its range (clamped)
+ *   MTMC_DATA_FP16_RANGE  MTMC_BF16: an activation, a rotated query or key, a value or an attention output
+ *                         had to be clamped to +-65504 (a NaN becomes -65504) where it is stored as fp16, or
+ *                         every logit of a row was NaN (token 0 is then reported).  Outputs of the calls
+ *                         since the last poll are unreliable.
+ * mtmc_data_error_string returns the text for a set of bits (valid until the thread's next call of it).
  */
+#define MTMC_DATA_TOKEN_ID   1
+#define MTMC_DATA_WEIGHT     2
+#define MTMC_DATA_LENGTH     4
+#define MTMC_DATA_FP16_RANGE 8
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);
+const char* mtmc_data_error_string(int bits);
 
 /*
  * Tuning switches.
  *   MTMC_OPT_HIP_GRAPH (default 1): mtmc_rollout captures one decode step into a HIP graph and
  *   replays it for every token.  Results do not depend on it (same kernels in the same order).
- *   Instantiated graphs are cached inside `w`, keyed by workspace address and shape; replacing
- *   a cached graph synchronises `stream` once.  When `stream` is itself being captured the steps
+ *   Instantiated graphs are cached inside `w`, keyed by workspace address and the call's shape; replacing
+ *   a cached graph (more than 8 are never kept) synchronises the device once.  When `stream` is itself being captured the steps
  *   are launched directly.
  *   MTMC_OPT_GEMM_LDS_MIN_BLOCKS (default 192, value >= 1): prefill / scoring GEMMs (MTMC_BF16)
  *   whose output has at least this many 256 x 256 blocks run in the LDS-staged kernel, smaller

@@ -157,12 +157,27 @@ extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
   MTMC_HIP_CHECK(hipMemcpy(&flag, w->err_flag, sizeof(int), hipMemcpyDeviceToHost));
   if (flag) {
     MTMC_HIP_CHECK(hipMemset(w->err_flag, 0, sizeof(int)));
-    set_error(std::string(flag & 1 ? "a token id outside [0, vocab) was seen (and clamped) on the device" : "") +
-              ((flag & 1) && (flag & 4) ? "; " : "") +
-              (flag & 4 ? "an action or prompt length outside its range was seen (and clamped) on the device" : ""));
+    set_error(mtmc_data_error_string(flag));
     return MTMC_EDATA;
   }
   return MTMC_OK;
+}
+
+extern "C" const char* mtmc_data_error_string(int bits) {
+  static thread_local std::string text;
+  text.clear();
+  auto add = [&](int bit, const char* msg) {
+    if (!(bits & bit)) return;
+    if (!text.empty()) text += "; ";
+    text += msg;
+  };
+  add(MTMC_DATA_TOKEN_ID, "a token id outside [0, vocab) was seen (and clamped) on the device");
+  add(MTMC_DATA_WEIGHT, "a weight is not finite or exceeds 65504 in magnitude");
+  add(MTMC_DATA_LENGTH, "an action or prompt length outside its range was seen (and clamped) on the device");
+  add(MTMC_DATA_FP16_RANGE,
+      "an activation, key or value left the fp16 range (magnitude above 65504, or not finite) and was clamped: "
+      "the results of the calls since the last poll are unreliable");
+  return text.c_str();
 }
 
 // --------------------------------------------------------------------------------------
@@ -381,3 +396,4 @@ extern "C" int mtmc_ppo_clip_loss(const float* new_logprobs, const float* old_lo
   MTMC_HIP_CHECK(hipGetLastError());
   return MTMC_OK;
 }
+

@@ -50,7 +50,8 @@ constexpr int QB = 128;   // query columns per workgroup
 
 template <int PHD>
 __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
-                                                           int row_stride, int pos_base, KvPool pool, int layer) {
+                                                           int row_stride, int pos_base, KvPool pool, int layer,
+                                                           int* err_flag) {
   constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 or 2 KiB
   constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
   constexpr int kPageKiB = kPageBytes / 1024;
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
 
   // ---- this wavefront's column blocks (columns c0 + 32 b + col, b = wave and 7 - wave).
   // Q fragments (B operand: column col, dims 16 j + 8 hh + 0..7).
-  v8bf qf[NCB][PHD / 16];
+  v8h qf[NCB][PHD / 16];
   int qpos[NCB], qabs[NCB], qhd[NCB];  // index in the sequence / position among the keys (-1: padding), head
 #pragma unroll
   for (int i = 0; i < NCB; ++i) {
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
     for (int j = 0; j < PHD / 16; ++j) {
       v4u raw = {0u, 0u, 0u, 0u};
       if (qpos[i] >= 0) raw = *reinterpret_cast<const v4u*>(qrow + 16 * j);
-      qf[i][j] = __builtin_bit_cast(v8bf, raw);
+      qf[i][j] = __builtin_bit_cast(v8h, raw);
     }
   }
   // last key step that holds a key some column of this wavefront's block may see (-1: the block is all padding)
@@ -161,13 +162,13 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
       for (int e = 0; e < 16; ++e) sacc[i][e] = 0.f;
 #pragma unroll
     for (int j = 0; j < PHD / 16; ++j) {
-      const v8bf kf = *reinterpret_cast<const v8bf*>(sb + koff + j * 512);
+      const v8h kf = *reinterpret_cast<const v8h*>(sb + koff + j * 512);
 #pragma unroll
       for (int i = 0; i < NCB; ++i)
         sacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[i][j], sacc[i], 0, 0, 0);
     }
     // ---- online softmax down each column; P^T fragments for the two token groups
-    v8bf pf[NCB][2];
+    v8h pf[NCB][2];
     const bool diag = 32 * t + 31 > pos_base + min_pos;  // some column of the workgroup may not see all 32 tokens
 #pragma unroll
     for (int i = 0; i < NCB; ++i) {
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
         pk[1] = pack_h16x2_inrange(p[8 * jj + 2], p[8 * jj + 3]);
         pk[2] = pack_h16x2_inrange(p[8 * jj + 4], p[8 * jj + 5]);
         pk[3] = pack_h16x2_inrange(p[8 * jj + 6], p[8 * jj + 7]);
-        pf[i][jj] = __builtin_bit_cast(v8bf, pk);
+        pf[i][jj] = __builtin_bit_cast(v8h, pk);
       }
     }
     // ---- O^T += V^T P^T: V fragments read from LDS once, used by every active block
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int d = 0; d < PHD / 32; ++d) {
-        const v8bf vf = *reinterpret_cast<const v8bf*>(sb + voff + jj * kPageBytes + d * 1024);
+        const v8h vf = *reinterpret_cast<const v8h*>(sb + voff + jj * kPageBytes + d * 1024);
 #pragma unroll
         for (int i = 0; i < NCB; ++i)
           oacc[i][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[i][jj], oacc[i][d], 0, 0, 0);
@@ -246,8 +247,8 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
 #pragma unroll
       for (int qq = 0; qq < 4; ++qq) {
         uint2 pk;
-        pk.x = pack_h16x2(oacc[i][d][4 * qq] * inv, oacc[i][d][4 * qq + 1] * inv);
-        pk.y = pack_h16x2(oacc[i][d][4 * qq + 2] * inv, oacc[i][d][4 * qq + 3] * inv);
+        pk.x = pack_h16x2_flag(oacc[i][d][4 * qq] * inv, oacc[i][d][4 * qq + 1] * inv, err_flag);
+        pk.y = pack_h16x2_flag(oacc[i][d][4 * qq + 2] * inv, oacc[i][d][4 * qq + 3] * inv, err_flag);
         *reinterpret_cast<uint2*>(o + act_off(tok, qhd[i] * PHD + 32 * d + 8 * qq + 4 * hh, Mpad)) = pk;
       }
   }
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
 }  // namespace
 
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
-                       TokMap map, KvPool pool, int layer, hipStream_t st) {
+                       TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st) {
   static bool configured = false;
   constexpr int kLdsMax = 160 * 1024;
   if (!configured) {
@@ -273,10 +274,10 @@ void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles,
   const dim3 grid((n_cols + QB - 1) / QB, Hkv, n_seqs);
   if (hd == 64)
     k_attn_prefill32<64><<<grid, 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv, map.row_stride, map.pos_base, pool,
-                                                       layer);
+                                                       layer, err_flag);
   else
     k_attn_prefill32<128><<<grid, 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv, map.row_stride, map.pos_base,
-                                                        pool, layer);
+                                                        pool, layer, err_flag);
 }
 
 }  // namespace bf16

@@ -29,6 +29,7 @@ struct LargeArgs {
   float* out_f32;
   int ld_out;
   h16_t* out_bf16;
+  int* err_flag;         // SwiGLU epilogue: raised when a value does not fit fp16
 };
 
 struct ScoreHeadArgs {
@@ -70,10 +71,11 @@ struct DecGemmArgs {
   // set by the launcher: the rows are split over pairs of workgroups that follow each other by 8 in launch order
   // (same XCD, dispatched together, so the second read of a weight tile hits L2); 0 = rows split over grid.y, if at all
   int row_pairs;
+  int* err_flag;         // RESID / SWIGLU: raised when a value written as fp16 does not fit
 };
 enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3, DEC_PARTIAL = 4 };
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
-                  h16_t* x, float* ss_out, int M, hipStream_t st);
+                  h16_t* x, float* ss_out, int M, int* err_flag, hipStream_t st);
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);
 int dec_wide_nb(int m_tiles);
 // What the sampler merge prepares for the next decode step from the token it has just chosen for a row: the
@@ -87,6 +89,8 @@ struct EmbedNextArgs {
   h16_t* x;
   int Mpad;
   float* ss_out;
+  int vocab;         // a chosen id outside [0, vocab) (every logit NaN) is replaced by 0 and reported
+  int* err_flag;
 };
 // Merges the sampler partials of a step, writes the outputs of step *d_step, advances *d_step (d_step[1] is the
 // kernel's arrival counter: zero before the first launch, left at zero by every launch) and embeds the chosen tokens.
@@ -107,12 +111,15 @@ struct AttnDecArgs {
   size_t o_chunk_stride; //   the output over the chunk's keys alone, normalised by the chunk's own sum
   float* ml;             // [B, Hq, n_chunks, 2]: running maximum and sum of (sequence, head, chunk); the consumer
                          //   (O projection) combines the chunks.  Not written when n_chunks == 1.
+  int* err_flag;         // raised when q, k, v or the output does not fit fp16
 };
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st);
 
 // ---- weight re-tiling (once, at load) ------------------------------------------------------
 // dst (tiled fp16, n_tiles x k_tiles blocks) <- src row-major [N, K] bf16; rows/cols past N/K are
 // zero.  Sets bit 1 of *err_flag if a weight does not fit fp16 (magnitude above 65504, or not finite).
+// check_finite_bf16 does the same for a matrix that is kept as bf16 (the embedding table): not finite -> bit 1.
+void check_finite_bf16(const bf16_t* src, size_t n, int* err_flag, hipStream_t st);
 void retile_weight(h16_t* dst, const bf16_t* src, int N, int K, int n_tiles, int k_tiles, int* err_flag,
                    hipStream_t st);
 // Gate and up interleaved by 16-row tiles: tile 2j <- gate rows 16j.., tile 2j+1 <- up rows 16j..
@@ -123,7 +130,7 @@ void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
                     int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st);
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                       int M, int m_tiles, int lds_min_blocks, hipStream_t st);
+                       int M, int m_tiles, int lds_min_blocks, int* err_flag, hipStream_t st);
 // LDS-staged 256 x 256 kernel behind the two launchers above (epi: 0 store, 1 accumulate, 2 SwiGLU).
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st);
 int score_head_blocks(int n_tiles, int* groups_per_block);
@@ -149,17 +156,17 @@ void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, i
            hipStream_t st);
 // h[m, :] += sum_s P[s][m][:] (n_split may be 0); x = bf16(RMSNorm(h; gain)) in tiled layout.
 void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
-              h16_t* x, int M, int m_tiles, int d, hipStream_t st);
+              h16_t* x, int M, int m_tiles, int d, int* err_flag, hipStream_t st);
 // qkv fp32 [T, (Hq + 2 Hkv) hd] (row stride ld), T = n_seqs * S tokens at positions map.pos_base + t % S: rotates q
 // (-> fp16 row-major [T, Hq*hd]) and k, writes k and v into the pages.  map.d_step and map.row_pos must be NULL.
 void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int Hkv, const float* cos,
-                   const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st);
+                   const float* sin, TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st);
 
 // ---- attention -----------------------------------------------------------------------------
 // Floats of the per-chunk partial results of the decode attention kernel.
 // Prefill / scoring: causal attention of every token of T = n_seqs * S over its own sequence.
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
-                       TokMap map, KvPool pool, int layer, hipStream_t st);
+                       TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st);
 
 }  // namespace bf16
 }  // namespace mtmc

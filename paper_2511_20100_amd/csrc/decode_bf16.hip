@@ -35,7 +35,7 @@ struct DecStream {
   const h16_t* xp[MB];
   size_t xstep;
   int k0, k1;
-  v8bf wr[PFW][NB], xr[PFX][MB];
+  v8h wr[PFW][NB], xr[PFX][MB];
 
   __device__ __forceinline__ void start(const h16_t* __restrict__ Wt, int k_tiles, int n_tiles, int nt0,
                                         const h16_t* __restrict__ Xt, int m_tiles, int mt0, int k0_, int k1_,
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // two chunks, holds two in half the registers and requests its first head here, in the shadow of the row scales.
   constexpr bool kCombines = (EPI == DEPI_RESID && NB == 1 && (WAVES == 8 || WAVES == 12) && MB <= 4);
   constexpr int NCM = !kCombines ? 1 : WAVES == 12 ? 2 : MB >= 4 ? 2 : MB == 2 ? 4 : 8;
-  v8bf c_wf[4], c_xf[NCM][4][MB];
+  v8h c_wf[4], c_xf[NCM][4][MB];
   float c_m[NCM][MB], c_l[NCM][MB];
   auto load_head = [&](int j) {
     const int HT = a.head_tiles, n_heads = a.k_tiles / HT, NC = a.n_xchunks;
@@ -356,8 +356,8 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
         hv = *reinterpret_cast<const v4f*>(hp) + sum[nb];
         *reinterpret_cast<v4f*>(hp) = hv;
         uint2 pk;
-        pk.x = pack_h16x2(hv[0] * g[0] * sc, hv[1] * g[1] * sc);
-        pk.y = pack_h16x2(hv[2] * g[2] * sc, hv[3] * g[3] * sc);
+        pk.x = pack_h16x2_flag(hv[0] * g[0] * sc, hv[1] * g[1] * sc, a.err_flag);
+        pk.y = pack_h16x2_flag(hv[2] * g[2] * sc, hv[3] * g[3] * sc, a.err_flag);
         *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, n, Mpad)) = pk;
       }
       float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
@@ -373,8 +373,8 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
       const int f = ((nbase + nb) >> 1) * 16 + rq;
       const v4f g = sum[nb] * sc, u = sum[(nb + 1) % NBP] * sc;
       uint2 pk;
-      pk.x = pack_h16x2(silu_d(g[0]) * u[0], silu_d(g[1]) * u[1]);
-      pk.y = pack_h16x2(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3]);
+      pk.x = pack_h16x2_flag(silu_d(g[0]) * u[0], silu_d(g[1]) * u[1], a.err_flag);
+      pk.y = pack_h16x2_flag(silu_d(g[2]) * u[2], silu_d(g[3]) * u[3], a.err_flag);
       *reinterpret_cast<uint2*>(a.out_h16 + act_off(m, f, Mpad)) = pk;
     }
   } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this pass's part of the workgroup's vocabulary slice
@@ -510,7 +510,8 @@ void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
 // columns; a thread owns (row, 4 consecutive columns).  The partial sums are added in split order.
 __global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ P, int ksplit, int Mpad, int N,
                                                       float* h, const float* __restrict__ gain,
-                                                      const float* __restrict__ rs, h16_t* x, float* ss_out, int M) {
+                                                      const float* __restrict__ rs, h16_t* x, float* ss_out, int M,
+                                                      int* err_flag) {
   const int nt = blockIdx.x, cg = threadIdx.x & 3;
   const int n = nt * 16 + cg * 4;
   const v4f g = *reinterpret_cast<const v4f*>(gain + n);
@@ -533,8 +534,8 @@ __global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ 
       *reinterpret_cast<v4f*>(hp) = hv;
       const float sc = rs[m];
       uint2 pk;
-      pk.x = pack_h16x2(hv[0] * g[0] * sc, hv[1] * g[1] * sc);
-      pk.y = pack_h16x2(hv[2] * g[2] * sc, hv[3] * g[3] * sc);
+      pk.x = pack_h16x2_flag(hv[0] * g[0] * sc, hv[1] * g[1] * sc, err_flag);
+      pk.y = pack_h16x2_flag(hv[2] * g[2] * sc, hv[3] * g[3] * sc, err_flag);
       *reinterpret_cast<uint2*>(x + act_off(m, n, Mpad)) = pk;
     }
     float ss = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
@@ -544,8 +545,8 @@ __global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ 
   }
 }
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
-                  h16_t* x, float* ss_out, int M, hipStream_t st) {
-  k_resid_reduce<<<N / 16, 256, 0, st>>>(P, ksplit, m_tiles * 16, N, h, gain, rs, x, ss_out, M);
+                  h16_t* x, float* ss_out, int M, int* err_flag, hipStream_t st) {
+  k_resid_reduce<<<N / 16, 256, 0, st>>>(P, ksplit, m_tiles * 16, N, h, gain, rs, x, ss_out, M, err_flag);
 }
 
 // ---------------------------------------------------------------- embedding of the fed-back token
@@ -582,8 +583,8 @@ __device__ __forceinline__ void embed_row(const EmbedNextArgs& e, int m, int id,
       v4u pk;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        pk[i] = pack_h16x2(v[half * 8 + 2 * i] * e.gain[k + half * 8 + 2 * i] * r,
-                           v[half * 8 + 2 * i + 1] * e.gain[k + half * 8 + 2 * i + 1] * r);
+        pk[i] = pack_h16x2_flag(v[half * 8 + 2 * i] * e.gain[k + half * 8 + 2 * i] * r,
+                                v[half * 8 + 2 * i + 1] * e.gain[k + half * 8 + 2 * i + 1] * r, e.err_flag);
       *reinterpret_cast<v4u*>(e.x + act_off(m, k + half * 8, e.Mpad)) = pk;
     }
   }
@@ -638,6 +639,10 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
     const int step = *d_step;
     int tok = bi;
     float lp = bz - (lse.m + logf(lse.s));
+    if ((unsigned)tok >= (unsigned)emb.vocab) {  // no logit of the row compared greater than -inf: every one is NaN
+      tok = 0;
+      atomicOr(emb.err_flag, kErrFp16Range);
+    }
     if (ctl.done) {
       if (ctl.done[b]) {
         tok = ctl.stop_id;
@@ -691,7 +696,7 @@ constexpr int ATAB = 512;    // page-table entries of one chunk kept in LDS
 
 template <int HD>
 struct KvFrags {
-  v8bf k[2][HD / 32];
+  v8h k[2][HD / 32];
   v4u v[HD / 16];
 };
 template <int HD>
@@ -719,7 +724,7 @@ __device__ __forceinline__ KvFrags<HD> load_kv(const h16_t* K0, const h16_t* K1,
 // is visible to the query (tok0 + 31 <= position), so nothing is compared; the unused columns (zero queries)
 // then carry finite garbage that nobody reads.
 template <int HD, bool MASK>
-__device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const v8bf (&qf)[HD / 32], int qpos,
+__device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const v8h (&qf)[HD / 32], int qpos,
                                            float scale2, AttnState<HD / 16>& st, int lane) {
   const int lg = lane >> 4;
   v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = s0;
@@ -755,13 +760,13 @@ __device__ __forceinline__ void attn_step1(const KvFrags<HD>& f, int tok0, const
   pk[1] = pack_h16x2_inrange(p[2], p[3]);
   pk[2] = pack_h16x2_inrange(p[4], p[5]);
   pk[3] = pack_h16x2_inrange(p[6], p[7]);
-  const v8bf pf = __builtin_bit_cast(v8bf, pk);
+  const v8h pf = __builtin_bit_cast(v8h, pk);
   if (__any(corr != 1.0f)) {  // the running maximum of some column moved: rescale what has been summed
 #pragma unroll
     for (int cb = 0; cb < HD / 16; ++cb) st.o[cb] = st.o[cb] * corr;
   }
 #pragma unroll
-  for (int cb = 0; cb < HD / 16; ++cb) st.o[cb] = mfma16(__builtin_bit_cast(v8bf, f.v[cb]), pf, st.o[cb]);
+  for (int cb = 0; cb < HD / 16; ++cb) st.o[cb] = mfma16(__builtin_bit_cast(v8h, f.v[cb]), pf, st.o[cb]);
 }
 
 template <int DHD>
@@ -843,8 +848,8 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   const float* sn = a.sin + (size_t)pos * (DHD / 2);
   if (qj < G && qi < HALF) {
     const float c = cs[qi], s = sn[qi];
-    q_s[qj][qi] = f32_to_h16(qraw[0] * c - qraw[1] * s);
-    q_s[qj][qi + HALF] = f32_to_h16(qraw[1] * c + qraw[0] * s);
+    q_s[qj][qi] = f32_to_h16_flag(qraw[0] * c - qraw[1] * s, a.err_flag);
+    q_s[qj][qi + HALF] = f32_to_h16_flag(qraw[1] * c + qraw[0] * s, a.err_flag);
   }
   // the owner of the current position appends K and V to the cache (last wavefront: it is idle above when G < AW)
   const int cur_page = pos / kPageTokens;
@@ -858,19 +863,19 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     const float v0 = row[(size_t)(Hq + Hkv + g) * DHD + i], v1 = row[(size_t)(Hq + Hkv + g) * DHD + i + HALF];
     const float c = cs[i], s = sn[i];
     const int c0 = i, c1 = i + HALF;
-    kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16(x0 * c - x1 * s);
-    kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16(x1 * c + x0 * s);
-    vp[c0 * kPageTokens + slot] = f32_to_h16(v0);
-    vp[c1 * kPageTokens + slot] = f32_to_h16(v1);
+    kp[(c0 >> 3) * 128 + slot * 8 + (c0 & 7)] = f32_to_h16_flag(x0 * c - x1 * s, a.err_flag);
+    kp[(c1 >> 3) * 128 + slot * 8 + (c1 & 7)] = f32_to_h16_flag(x1 * c + x0 * s, a.err_flag);
+    vp[c0 * kPageTokens + slot] = f32_to_h16_flag(v0, a.err_flag);
+    vp[c1 * kPageTokens + slot] = f32_to_h16_flag(v1, a.err_flag);
   }
   __syncthreads();  // q_s, s_table complete; this workgroup's K/V stores are visible to its own loads
 
-  v8bf qf[DHD / 32];
+  v8h qf[DHD / 32];
 #pragma unroll
   for (int kb = 0; kb < DHD / 32; ++kb) {
     v4u raw = {0u, 0u, 0u, 0u};
     if (col < G) raw = *reinterpret_cast<const v4u*>(&q_s[col][kb * 32 + 8 * lg]);
-    qf[kb] = __builtin_bit_cast(v8bf, raw);
+    qf[kb] = __builtin_bit_cast(v8h, raw);
   }
   const int qpos = (col < G) ? pos : -1;
   AttnState<DHD / 16> st;
@@ -952,7 +957,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
     const float inv = 1.0f / ll;  // every page of an active chunk holds at least one visible key
     v4u pk;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) pk[e] = pack_h16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
+    for (int e = 0; e < 4; ++e) pk[e] = pack_h16x2_flag(acc[2 * e] * inv, acc[2 * e + 1] * inv, a.err_flag);
     *reinterpret_cast<v4u*>(a.o + chunk * a.o_chunk_stride + act_off(b, (g * G + c) * DHD + d0, Mpad)) = pk;
     if (a.n_chunks > 1 && d0 == 0) {
       float* ml = a.ml + (((size_t)b * Hq + g * G + c) * a.n_chunks + chunk) * 2;

@@ -50,6 +50,18 @@ void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int
   k_retile<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(dst, gate, up, F, K, 2 * f_tiles, k_tiles, 1, err_flag);
 }
 
+// The embedding table stays bf16 (it is gathered, not multiplied): only its finiteness is checked at load.
+__global__ void k_check_finite_bf16(const bf16_t* src, size_t n, int* err_flag) {
+  bool bad = false;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    bad |= (src[i] & 0x7f80u) == 0x7f80u;  // exponent all ones: infinity or NaN
+  if (bad) atomicOr(err_flag, 2);
+}
+void check_finite_bf16(const bf16_t* src, size_t n, int* err_flag, hipStream_t st) {
+  if (n == 0) return;
+  k_check_finite_bf16<<<1024, 256, 0, st>>>(src, n, err_flag);
+}
+
 // ---------------------------------------------------------------- control
 __global__ void k_set_ctl(SampleCtl* dst, SampleCtl v) { *dst = v; }
 void set_sample_ctl(SampleCtl* dst, const SampleCtl& v, hipStream_t st) { k_set_ctl<<<1, 1, 0, st>>>(dst, v); }
@@ -73,7 +85,8 @@ void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, i
 // operand).  Pass 1 folds the split-K partial sums into the fp32 residual and accumulates the
 // sum of squares; pass 2 writes bf16(h * rsqrt(mean + eps) * gain).
 __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p,
-                                                  const float* gain, float eps, h16_t* x, int Mpad, int d) {
+                                                  const float* gain, float eps, h16_t* x, int Mpad, int d,
+                                                  int* err_flag) {
   __shared__ float red[16];
   const int m = blockIdx.x;
   float* hr = h + (size_t)m * d;
@@ -99,10 +112,10 @@ __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int 
     const v4f a = *reinterpret_cast<const v4f*>(hr + k), b = *reinterpret_cast<const v4f*>(hr + k + 4);
     const v4f ga = *reinterpret_cast<const v4f*>(gain + k), gb = *reinterpret_cast<const v4f*>(gain + k + 4);
     v4u pk;
-    pk[0] = pack_h16x2(a[0] * r * ga[0], a[1] * r * ga[1]);
-    pk[1] = pack_h16x2(a[2] * r * ga[2], a[3] * r * ga[3]);
-    pk[2] = pack_h16x2(b[0] * r * gb[0], b[1] * r * gb[1]);
-    pk[3] = pack_h16x2(b[2] * r * gb[2], b[3] * r * gb[3]);
+    pk[0] = pack_h16x2_flag(a[0] * r * ga[0], a[1] * r * ga[1], err_flag);
+    pk[1] = pack_h16x2_flag(a[2] * r * ga[2], a[3] * r * ga[3], err_flag);
+    pk[2] = pack_h16x2_flag(b[0] * r * gb[0], b[1] * r * gb[1], err_flag);
+    pk[3] = pack_h16x2_flag(b[2] * r * gb[2], b[3] * r * gb[3], err_flag);
     *reinterpret_cast<v4u*>(x + act_off(m, k, Mpad)) = pk;
   }
 }
@@ -112,7 +125,8 @@ __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int 
 // of the fragment layout (the per-row kernel above writes 16 bytes of every 256: sixteen workgroups share
 // each cache line).
 __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h, const float* __restrict__ gain,
-                                                     float eps, h16_t* x, int M, int m_tiles, int d) {
+                                                     float eps, h16_t* x, int M, int m_tiles, int d,
+                                                     int* err_flag) {
   extern __shared__ __attribute__((aligned(16))) uint8_t xs[];  // 16 rows of 2 d + 16 bytes
   const int row_bytes = 2 * d + 16;
   const int mt = blockIdx.x, r = threadIdx.x >> 4, sub = threadIdx.x & 15;
@@ -145,10 +159,10 @@ __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h
   auto emit = [&](int k, const v4f& a, const v4f& b) {
     const v4f ga = *reinterpret_cast<const v4f*>(gain + k), gb = *reinterpret_cast<const v4f*>(gain + k + 4);
     v4u pk;
-    pk[0] = pack_h16x2(a[0] * rr * ga[0], a[1] * rr * ga[1]);
-    pk[1] = pack_h16x2(a[2] * rr * ga[2], a[3] * rr * ga[3]);
-    pk[2] = pack_h16x2(b[0] * rr * gb[0], b[1] * rr * gb[1]);
-    pk[3] = pack_h16x2(b[2] * rr * gb[2], b[3] * rr * gb[3]);
+    pk[0] = pack_h16x2_flag(a[0] * rr * ga[0], a[1] * rr * ga[1], err_flag);
+    pk[1] = pack_h16x2_flag(a[2] * rr * ga[2], a[3] * rr * ga[3], err_flag);
+    pk[2] = pack_h16x2_flag(b[0] * rr * gb[0], b[1] * rr * gb[1], err_flag);
+    pk[3] = pack_h16x2_flag(b[2] * rr * gb[2], b[3] * rr * gb[3], err_flag);
     *reinterpret_cast<v4u*>(xs + r * row_bytes + k * 2) = pk;
   };
 #pragma unroll
@@ -168,7 +182,7 @@ __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h
 }
 
 void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
-              h16_t* x, int M, int m_tiles, int d, hipStream_t st) {
+              h16_t* x, int M, int m_tiles, int d, int* err_flag, hipStream_t st) {
   if (M == 0) return;
   if (n_split == 0 && M >= 1024 && d % 32 == 0 && d * 32 + 256 <= 160 * 1024) {
     static bool configured = false;
@@ -177,10 +191,10 @@ void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const 
                                 160 * 1024);
       configured = true;
     }
-    k_norm_tile16<<<(M + 15) / 16, 256, 16 * (2 * d + 16), st>>>(h, gain, eps, x, M, m_tiles, d);
+    k_norm_tile16<<<(M + 15) / 16, 256, 16 * (2 * d + 16), st>>>(h, gain, eps, x, M, m_tiles, d, err_flag);
     return;
   }
-  k_add_norm<<<M, 256, 0, st>>>(h, P, n_split, ldp, Mpad_p, gain, eps, x, m_tiles * 16, d);
+  k_add_norm<<<M, 256, 0, st>>>(h, P, n_split, ldp, Mpad_p, gain, eps, x, m_tiles * 16, d, err_flag);
 }
 
 // ---------------------------------------------------------------- rotary embedding + KV write
@@ -195,7 +209,7 @@ void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const 
 template <int HD>
 __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv, int ld, int S, int Hq, int Hkv,
                                                       const float* cos, const float* sin, int row_stride, int pos_base,
-                                                      KvPool pool, int layer) {
+                                                      KvPool pool, int layer, int* err_flag) {
   constexpr int HALF = HD / 2, QUADS = HALF / 4;  // quads of rotation pairs per head
   constexpr int ROW = HD + 8;                     // LDS row stride in halfs: 16-byte reads down a column stay conflict-free
   __shared__ __attribute__((aligned(16))) h16_t k_s[kPageTokens][ROW];
@@ -221,8 +235,8 @@ __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv
       const v4f sn = *reinterpret_cast<const v4f*>(sin + (size_t)pos * HALF + i);
       const v4f ra = a * c - b * sn, rb = b * c + a * sn;
       uint2 lo, hi;
-      lo.x = pack_h16x2(ra[0], ra[1]); lo.y = pack_h16x2(ra[2], ra[3]);
-      hi.x = pack_h16x2(rb[0], rb[1]); hi.y = pack_h16x2(rb[2], rb[3]);
+      lo.x = pack_h16x2_flag(ra[0], ra[1], err_flag); lo.y = pack_h16x2_flag(ra[2], ra[3], err_flag);
+      hi.x = pack_h16x2_flag(rb[0], rb[1], err_flag); hi.y = pack_h16x2_flag(rb[2], rb[3], err_flag);
       if (head < Hq) {
         h16_t* qr = q + t * Hq * HD + (size_t)head * HD;
         *reinterpret_cast<uint2*>(qr + i) = lo;
@@ -242,7 +256,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv
       const size_t t = (size_t)seq * S + (pos - pos_base);
       const v4f v = *reinterpret_cast<const v4f*>(qkv + t * ld + (size_t)(Hq + Hkv + g) * HD + i);
       uint2 pk;
-      pk.x = pack_h16x2(v[0], v[1]); pk.y = pack_h16x2(v[2], v[3]);
+      pk.x = pack_h16x2_flag(v[0], v[1], err_flag); pk.y = pack_h16x2_flag(v[2], v[3], err_flag);
       *reinterpret_cast<uint2*>(&v_s[slot][i]) = pk;
     }
     __syncthreads();
@@ -273,16 +287,17 @@ __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv
   }
 }
 void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int Hkv, const float* cos,
-                   const float* sin, TokMap map, KvPool pool, int layer, hipStream_t st) {
+                   const float* sin, TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st) {
   if (T == 0) return;
   // pages that the positions pos_base .. pos_base + S - 1 of a sequence touch
   const int n_pg = (map.pos_base + S - 1) / kPageTokens - map.pos_base / kPageTokens + 1;
   const dim3 grid(n_pg, T / S);
   if (pool.head_dim == 64)
-    k_rope_kv_page<64><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool, layer);
+    k_rope_kv_page<64><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool, layer,
+                                             err_flag);
   else
     k_rope_kv_page<128><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool,
-                                              layer);
+                                              layer, err_flag);
 }
 
 }  // namespace bf16

@@ -15,8 +15,10 @@ namespace mtmc {
 // counter) lives in device memory that the kernels read.
 struct GraphCache {
   struct Entry {
+    // every pointer and split factor a captured launch holds follows from the workspace base and the shape of the
+    // WHOLE call (the plan), plus the rows of the group the step belongs to
     const void* workspace;
-    int B, prompt_len, n_samples, max_new, ragged;
+    int total_prompts, B, prompt_len, n_samples, max_new, ragged;
     hipGraphExec_t exec;
   };
   std::mutex mu;
@@ -199,6 +201,7 @@ int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob,
     }
   };
   copy(o.embed, lay.embed, (size_t)D.V * D.d * 2);
+  bf16::check_finite_bf16((const bf16_t*)(src + lay.embed), (size_t)D.V * D.d, w->err_flag, st);
   copy(o.fnorm, lay.final_norm, (size_t)D.d * 4);
   bf16::retile_weight(o.lm, (const bf16_t*)(src + lay.lm_head), D.V, D.d, D.nt_V, D.kt_d, w->err_flag, st);
   w->embed = o.embed;
@@ -325,14 +328,14 @@ void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, fl
     const LayerWeights& L = w->layers[l];
     const int kvl = l * layer_stride;
     bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, st);
-    bf16::rope_kv_write(qb, qkv, D.nqkv, T, S, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, st);
-    bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, st);
+    bf16::rope_kv_write(qb, qkv, D.nqkv, T, S, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, w->err_flag, st);
+    bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, w->err_flag, st);
     bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, st);
-    bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, st);
-    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, lmb, st);
+    bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st);
+    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, lmb, w->err_flag, st);
     bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, lmb, st);
     if (l + 1 < c.n_layers)
-      bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, st);
+      bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st);
   }
 }
 
@@ -352,7 +355,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
   float* ss[2] = {p.ssA, p.ssB};
   int cur = 0, old = 0;
   bf16::DecGemmArgs g{};
-  g.m_tiles = bt; g.M = B; g.ss_tiles = D.nt_d; g.inv_d = 1.0f / (float)D.d; g.eps = c.rms_eps;
+  g.m_tiles = bt; g.M = B; g.ss_tiles = D.nt_d; g.inv_d = 1.0f / (float)D.d; g.eps = c.rms_eps; g.err_flag = w->err_flag;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& L = w->layers[l];
     bf16::DecGemmArgs q = g;
@@ -365,7 +368,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
     at.pos_base = pos_base; at.row_pos = p.ragged ? p.row_pos : nullptr; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages; at.split_at_prompt = p.split_at_prompt;
     at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples;
-    at.o = (h16_t*)p.o_chunks; at.o_chunk_stride = (size_t)D.nq * bt * 16; at.ml = p.attn_ml;
+    at.o = (h16_t*)p.o_chunks; at.o_chunk_stride = (size_t)D.nq * bt * 16; at.ml = p.attn_ml; at.err_flag = w->err_flag;
     mark(MTMC_KERNEL_ATTENTION);
     bf16::attention_dec(at, B, st);
     mark(MTMC_KERNEL_ATTENTION);
@@ -391,7 +394,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     bf16::gemm_dec(r2, bf16::DEC_PARTIAL, st);
     mark(MTMC_KERNEL_DOWN);
     bf16::resid_reduce(p.part, p.ks_down, bt, D.d, h, (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm,
-                       p.rs_buf, x, ss[cur ^ 1], B, st);
+                       p.rs_buf, x, ss[cur ^ 1], B, w->err_flag, st);
     old = cur; cur ^= 1;
   }
   *ss_cur_out = ss[cur];
@@ -422,13 +425,14 @@ int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, S
     }
   }
   for (auto& e : gc.entries)
-    if (e.workspace == (const void*)gp.page_table && e.B == gp.B && e.prompt_len == gp.prompt_len &&
-        e.n_samples == gp.n_samples && e.max_new == gp.max_new && e.ragged == gp.ragged) {
+    if (e.workspace == (const void*)gp.page_table && e.total_prompts == gp.total_prompts && e.B == gp.B &&
+        e.prompt_len == gp.prompt_len && e.n_samples == gp.n_samples && e.max_new == gp.max_new &&
+        e.ragged == gp.ragged) {
       *out = e.exec;
       return MTMC_OK;
     }
-  if (gc.entries.size() >= 8) {  // evict the oldest; it may still be queued on the stream
-    MTMC_HIP_CHECK(hipStreamSynchronize(st));
+  if (gc.entries.size() >= 8) {  // evict the oldest; it may still be queued, on this stream or on another caller's
+    MTMC_HIP_CHECK(hipDeviceSynchronize());
     (void)hipGraphExecDestroy(gc.entries.front().exec);
     gc.entries.erase(gc.entries.begin());
   }
@@ -443,7 +447,8 @@ int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, S
     set_error(std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
     return MTMC_EHIP;
   }
-  gc.entries.push_back({(const void*)gp.page_table, gp.B, gp.prompt_len, gp.n_samples, gp.max_new, gp.ragged, exec});
+  gc.entries.push_back({(const void*)gp.page_table, gp.total_prompts, gp.B, gp.prompt_len, gp.n_samples, gp.max_new,
+                        gp.ragged, exec});
   *out = exec;
   return MTMC_OK;
 }
@@ -497,7 +502,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       chunk_pool.page_table = p.page_table + (size_t)p0 * p.n_samples * p.max_pages;
       TokMap map{p.prompt_len, p.n_samples, 0, nullptr};
       bf16::embed(p.h, gprompts + (size_t)p0 * p.prompt_len, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
-      bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+      bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
       prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, p.prompt_len,
                      map, chunk_pool, 1, st);
       if (ragged)
@@ -512,7 +517,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     else if (p.prompt_len % kPageTokens != 0)
       launch_fork_tail_pages(pool, c.n_layers, gp.B, p.n_samples, p.n_full, 2, st);
     // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i - 1
-    bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, st);
+    bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, w->err_flag, st);
     auto sample = [&](hipStream_t s, const float* ss_cur, const float* ss_old) {
       bf16::DecGemmArgs lm{};
       lm.Wt = (const h16_t*)w->lm_head; lm.Xt = (const h16_t*)p.xB; lm.n_tiles = D.nt_V; lm.k_tiles = D.kt_d;
@@ -523,7 +528,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       const int groups = (D.nt_V + bf16::dec_wide_nb(gp.bt) - 1) / bf16::dec_wide_nb(gp.bt);
       // also ++*d_step, and the embedding + first norm of the chosen tokens: the next step starts at its QKV projection
       const bf16::EmbedNextArgs emb{p.hB, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xB,
-                                    gp.bt * 16, p.ssA};
+                                    gp.bt * 16, p.ssA, D.V, w->err_flag};
       bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, emb, s);
     };
     auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) {
@@ -570,13 +575,13 @@ int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hi
     const int ns = std::min(p.chunk_seqs, a.n_seqs - s0);
     const int T = ns * S, mt = tiles16(T);
     bf16::embed(p.h, a.seqs + (size_t)s0 * S, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
-    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
     prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, S, map, pool, 0, st);
     const int R = ns * n_scored;
     if (R == 0) continue;
     const int rt = tiles16(R);
     launch_gather_rows(p.hs, p.h, R, D.d, n_scored, S, a.first, 1, st);
-    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
+    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, w->err_flag, st);
     bf16::score_targets(p.targets, a.seqs, R, S, a.first, n_scored, s0, 0, D.V, w->err_flag, st);
     bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
                        a.out_top1 != nullptr || a.out_margin != nullptr, w->opt_lds_min_blocks, st);
@@ -605,7 +610,7 @@ int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionA
       chunk_pool.page_table = p.page_table + (size_t)n0 * p.K * p.max_pages;
       TokMap map{p.Pp, p.K, 0, nullptr};
       bf16::embed(p.h, p.prefix + (size_t)n0 * p.Pp, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
-      bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+      bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
       prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, p.Pp, map,
                      chunk_pool, 1, st);
     }
@@ -621,12 +626,12 @@ int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionA
     KvPool chunk_pool = pool;
     chunk_pool.page_table = p.page_table + (size_t)r0 * p.max_pages;
     bf16::embed(p.h, p.vseq + (size_t)r0 * p.W, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
-    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, st);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
     prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, nr, p.W, map,
                    chunk_pool, 1, st);
     const int R = nr * p.A, rt = tiles16(R);
     launch_gather_rows(p.hs, p.h, R, D.d, p.A, p.W, 0, 1, st);
-    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, st);
+    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, w->err_flag, st);
     bf16::score_targets(p.targets, p.vseq, R, p.W, 0, p.A, r0, 0, D.V, w->err_flag, st);
     bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
                        false, w->opt_lds_min_blocks, st);

@@ -24,7 +24,7 @@ namespace mtmc {
 
 typedef uint16_t bf16_t;  // bf16 bit pattern (the caller's weights)
 typedef uint16_t h16_t;   // IEEE fp16 bit pattern (MFMA operands: re-tiled weights, activations, KV cache)
-typedef __attribute__((ext_vector_type(8))) _Float16 v8bf;  // one lane's share of a 16x32 MFMA operand
+typedef __attribute__((ext_vector_type(8))) _Float16 v8h;  // one lane's share of a 16x32 MFMA operand (fp16)
 typedef __attribute__((ext_vector_type(2))) _Float16 v2h;
 typedef __attribute__((ext_vector_type(4))) float v4f;
 typedef __attribute__((ext_vector_type(4))) uint32_t v4u;
@@ -40,6 +40,21 @@ __device__ __forceinline__ uint32_t pack_h16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// Bit of the library's device error flag that an activation producer raises when a value it stores as fp16 is
+// not finite or exceeds the fp16 range (the stored value is then the clamped one, -65504 for a NaN): the results
+// of the call are unreliable and the next poll of the flag reports it.
+constexpr int kErrFp16Range = 8;
+__device__ __forceinline__ bool fits_h16(float f) { return fabsf(f) <= 65504.f; }  // false for NaN
+// The converters every activation / KV-cache producer uses: same values as above, and the flag on a clamp.
+__device__ __forceinline__ h16_t f32_to_h16_flag(float f, int* err_flag) {
+  if (!fits_h16(f)) atomicOr(err_flag, kErrFp16Range);
+  return f32_to_h16(f);
+}
+__device__ __forceinline__ uint32_t pack_h16x2_flag(float lo, float hi, int* err_flag) {
+  if (!fits_h16(lo) || !fits_h16(hi)) atomicOr(err_flag, kErrFp16Range);
+  return pack_h16x2(lo, hi);
+}
+
 // For values known to lie inside the fp16 range (probabilities in [0, 1]): no clamp.
 __device__ __forceinline__ uint32_t pack_h16x2_inrange(float lo, float hi) {
   const v2h v = {(_Float16)lo, (_Float16)hi};
@@ -53,12 +68,12 @@ __host__ __device__ __forceinline__ size_t wgt_off(int n, int k, int Kpad) {
   return ((size_t)(n >> 4) * (Kpad >> 5) + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (n & 15)) * 8 + (k & 7);
 }
 
-__device__ __forceinline__ v8bf load_frag(const h16_t* tile_base, int lane) {
+__device__ __forceinline__ v8h load_frag(const h16_t* tile_base, int lane) {
   const v4u raw = *reinterpret_cast<const v4u*>(tile_base + lane * 8);
-  return __builtin_bit_cast(v8bf, raw);
+  return __builtin_bit_cast(v8h, raw);
 }
 
-__device__ __forceinline__ v4f mfma16(v8bf a, v8bf b, v4f c) {
+__device__ __forceinline__ v4f mfma16(v8h a, v8h b, v4f c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 

@@ -30,7 +30,7 @@ __device__ __forceinline__ void wave_gemm(const h16_t* __restrict__ Wt, int k_ti
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) xp[mb] = Xt + (size_t)min(mt0 + mb, m_tiles - 1) * 512 + lane * 8;
   const size_t xstep = (size_t)m_tiles * 512;
-  v8bf wr[PF][NB], xr[PF][MB];
+  v8h wr[PF][NB], xr[PF][MB];
 #pragma unroll
   for (int s = 0; s < PF; ++s) {
     const int kk = min(k0 + s, k1 - 1);
@@ -133,8 +133,8 @@ __global__ __launch_bounds__(256) void k_gemm_large(LargeArgs a) {
         const int f = ((nt0 + nb) >> 1) * 16 + rq;
         const v4f g = acc[nb][mb], u = acc[nb + 1][mb];
         uint2 pk;
-        pk.x = pack_h16x2(silu_f(g[0]) * u[0], silu_f(g[1]) * u[1]);
-        pk.y = pack_h16x2(silu_f(g[2]) * u[2], silu_f(g[3]) * u[3]);
+        pk.x = pack_h16x2_flag(silu_f(g[0]) * u[0], silu_f(g[1]) * u[1], a.err_flag);
+        pk.y = pack_h16x2_flag(silu_f(g[2]) * u[2], silu_f(g[3]) * u[3], a.err_flag);
         *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, f, Mpad)) = pk;
       } else {
         const int n = (nt0 + nb) * 16 + rq;
@@ -171,10 +171,10 @@ void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, 
   else launch_large(a, epi, st);
 }
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                       int M, int m_tiles, int lds_min_blocks, hipStream_t st) {
+                       int M, int m_tiles, int lds_min_blocks, int* err_flag, hipStream_t st) {
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
-  a.out_bf16 = act;
+  a.out_bf16 = act; a.err_flag = err_flag;
   if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, LEPI_SWIGLU, st);
   else launch_large(a, LEPI_SWIGLU, st);
 }

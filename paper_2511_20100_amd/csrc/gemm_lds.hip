@@ -51,7 +51,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // registers of a wavefront fill it exactly; left to itself the register allocator spreads them over both
 // halves and spills).  Consecutive uses of one accumulator are 16 MFMAs apart, far beyond the
 // dependent-issue distance of the instruction.
-__device__ __forceinline__ void mfma32_acc(v16f& acc, v8bf a, v8bf b) {
+__device__ __forceinline__ void mfma32_acc(v16f& acc, v8h a, v8h b) {
   asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b) : "memory");
 }
 
@@ -119,11 +119,11 @@ __device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t
   const int r32 = lane & 31;
   const int lane_off = (r32 >> 4) * 1024 + (((lane >> 5) << 4) + (r32 & 15)) * 16;
   // Fragments of one k-step: per 32-row block two operands (k groups 0,1 and 2,3).
-  struct Frags { v8bf w[4][2], x[4][2]; };
+  struct Frags { v8h w[4][2], x[4][2]; };
   auto read_frag = [&](Frags& f, const uint8_t* sb, int i) {  // i = 0..15
     const int blk = (i >> 1) & 3, p = i & 1;
-    if (i < 8) f.x[blk][p] = *reinterpret_cast<const v8bf*>(sb + (kBlkTiles + 8 * wm + 2 * blk) * 1024 + p * 512);
-    else f.w[blk][p] = *reinterpret_cast<const v8bf*>(sb + (8 * wn + 2 * blk) * 1024 + p * 512);
+    if (i < 8) f.x[blk][p] = *reinterpret_cast<const v8h*>(sb + (kBlkTiles + 8 * wm + 2 * blk) * 1024 + p * 512);
+    else f.w[blk][p] = *reinterpret_cast<const v8h*>(sb + (8 * wn + 2 * blk) * 1024 + p * 512);
   };
   auto issue_one = [&](const TileSrc& t, int kk, uint8_t* sb, int j) {  // j = 0..7; sb = this wavefront's part of a buffer
     if (j < 4) copy_block_to_lds(t.w[j] + (size_t)kk * 1024 + lane16, sb + j * 1024);
@@ -258,10 +258,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
         for (int q = 0; q < 2; ++q) {
           const int fo = (n0 >> 1) + 8 * q + rh;
           uint2 pk;
-          pk.x = pack_h16x2(silu_l(acc[nb][mb][4 * q + 0]) * acc[nb][mb][4 * q + 8],
-                            silu_l(acc[nb][mb][4 * q + 1]) * acc[nb][mb][4 * q + 9]);
-          pk.y = pack_h16x2(silu_l(acc[nb][mb][4 * q + 2]) * acc[nb][mb][4 * q + 10],
-                            silu_l(acc[nb][mb][4 * q + 3]) * acc[nb][mb][4 * q + 11]);
+          pk.x = pack_h16x2_flag(silu_l(acc[nb][mb][4 * q + 0]) * acc[nb][mb][4 * q + 8],
+                                 silu_l(acc[nb][mb][4 * q + 1]) * acc[nb][mb][4 * q + 9], a.err_flag);
+          pk.y = pack_h16x2_flag(silu_l(acc[nb][mb][4 * q + 2]) * acc[nb][mb][4 * q + 10],
+                                 silu_l(acc[nb][mb][4 * q + 3]) * acc[nb][mb][4 * q + 11], a.err_flag);
           *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, fo, Mpad)) = pk;
         }
       } else {

@@ -195,10 +195,12 @@ class Weights:
 
 
 def make_weights(cfg: ModelConfig, seed: int = 0, std: float = 0.02, threads: int | None = None,
-                 only_layers: int | None = None) -> Weights:
+                 only_layers: int | None = None, gain_std: float = 0.0) -> Weights:
     """Random weights: every matrix ~ N(0, std) (rounded to bf16 for dtype "bf16"), every
-    norm gain = 1.  ``only_layers`` keeps the first k layers (same values as in the full
-    model, since each tensor has its own random stream) and returns a k-layer model."""
+    norm gain = 1, or 1 + N(0, gain_std) per element when gain_std > 0 (a trained model's gains are
+    not all one; each gain vector has its own random stream like every other tensor).
+    ``only_layers`` keeps the first k layers (same values as in the full model, since each
+    tensor has its own random stream) and returns a k-layer model."""
     threads = threads or default_threads()
     full_specs = tensor_specs(cfg)
     index = {name: i for i, (name, _, _) in enumerate(full_specs)}
@@ -207,7 +209,10 @@ def make_weights(cfg: ModelConfig, seed: int = 0, std: float = 0.02, threads: in
     tensors: Dict[str, np.ndarray] = {}
     for name, shape, is_matrix in tensor_specs(cfg):
         if not is_matrix:
-            tensors[name] = np.ones(shape, dtype=np.float32)
+            g = np.ones(shape, dtype=np.float32)
+            if gain_std > 0.0:
+                g += _draw_normal(seed, index[name], int(np.prod(shape)), gain_std, 1).reshape(shape)
+            tensors[name] = g
             continue
         w = _draw_normal(seed, index[name], int(np.prod(shape)), std, threads).reshape(shape)
         tensors[name] = f32_to_bf16_bits(w) if cfg.dtype == "bf16" else w

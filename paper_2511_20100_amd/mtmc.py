@@ -19,6 +19,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtmc.so
 
 MTMC_OK, MTMC_EINVAL, MTMC_ENOMEM, MTMC_EHIP, MTMC_EDATA = 0, -1, -2, -3, -4
 MTMC_F32, MTMC_BF16 = 0, 1
+MTMC_DATA_TOKEN_ID, MTMC_DATA_WEIGHT, MTMC_DATA_LENGTH, MTMC_DATA_FP16_RANGE = 1, 2, 4, 8
 
 
 class MtmcError(RuntimeError):
@@ -81,6 +82,8 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_poll_errors.restype = ctypes.c_int
     lib.mtmc_last_error.argtypes = []
     lib.mtmc_last_error.restype = ctypes.c_char_p
+    lib.mtmc_data_error_string.argtypes = [ctypes.c_int]
+    lib.mtmc_data_error_string.restype = ctypes.c_char_p
     return lib
 
 
@@ -89,7 +92,7 @@ EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mt
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
            "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
-           "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss")
+           "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss", "mtmc_data_error_string")
 
 
 def mtmc_last_error() -> str:
@@ -304,3 +307,7 @@ def mtmc_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream: Optional[torch
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:
     _check(_lib.mtmc_poll_errors(handle, _stream_ptr(stream)))
+
+
+def mtmc_data_error_string(bits: int) -> str:
+    return (_lib.mtmc_data_error_string(int(bits)) or b"").decode()

@@ -39,6 +39,29 @@ def check_rollout_by_replay(handle, w, prompts, n_samples, max_new, temperature,
     return {"ids": ids, "logprobs": lp, "compared": gated, "steps": total, "max_logp_err": worst}
 
 
+def oracle_replay_window(model, prompt, new_ids, lo, hi, temperature, seed, seq_index):
+    """oracle.replay restricted to the steps lo .. hi - 1 of a long continuation: the oracle's blocks run over
+    prompt + new_ids[:hi - 1] (everything those steps can see), its LM head over the window's rows only, and
+    every sampling decision of the window is redone with the noise of (seed, seq_index, step).
+    Returns (tok, logp_of_given, margin), each [hi - lo]."""
+    P = len(prompt)
+    full = np.concatenate([prompt, new_ids[:hi - 1]]).astype(np.int64)
+    pos = np.arange(len(full))
+    h = model.embed(full)
+    for l in range(model.L):
+        h, _, _ = model.block(l, h, pos, None, None)
+    z = model.head(h[P - 1 + lo:P - 1 + hi]).astype(np.float32)
+    n = hi - lo
+    tok, lp, mar = np.zeros(n, np.int32), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for i in range(lo, hi):
+        g = oracle.gumbel_noise(seed, seq_index, i, model.V) if temperature != 0.0 else None
+        t, _, m = oracle.sample_token(z[i - lo], temperature, g)
+        tok[i - lo], mar[i - lo] = t, m
+        zt = z[i - lo] if temperature == 0.0 else z[i - lo] * np.float32(1.0 / temperature)
+        lp[i - lo] = oracle.log_softmax_at(zt[None, :], np.array([new_ids[i]]))[0]
+    return tok, lp, mar
+
+
 def check_score(handle, w, seqs, prompt_len, *, max_positions, rows=None, tol=LOGP_TOL_BF16, label=""):
     import torch
     from paper_2511_20100_amd import mtmc

@@ -69,6 +69,19 @@ def test_invalid_configurations_are_rejected():
     assert mtmc.mtmc_blob_bytes(c) == 0
 
 
+def test_data_flag_text_names_each_cause():
+    """What mtmc_poll_errors reports for each bit of the device's sticky data flag (host-only call)."""
+    from paper_2511_20100_amd import mtmc
+    assert mtmc.mtmc_data_error_string(0) == ""
+    assert "token id" in mtmc.mtmc_data_error_string(mtmc.MTMC_DATA_TOKEN_ID)
+    assert "length" in mtmc.mtmc_data_error_string(mtmc.MTMC_DATA_LENGTH)
+    assert "weight" in mtmc.mtmc_data_error_string(mtmc.MTMC_DATA_WEIGHT)
+    sat = mtmc.mtmc_data_error_string(mtmc.MTMC_DATA_FP16_RANGE)
+    assert "fp16 range" in sat and "65504" in sat and "clamped" in sat and "token id" not in sat
+    both = mtmc.mtmc_data_error_string(mtmc.MTMC_DATA_TOKEN_ID | mtmc.MTMC_DATA_FP16_RANGE)
+    assert "token id" in both and "fp16 range" in both and "; " in both
+
+
 def test_blob_roundtrip():
     w = inputs.make_weights(inputs.TINY.with_(n_layers=1), seed=3)
     blob = w.blob()

@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 import mtmc_oracle as oracle
 from helpers import oracle_model
-from parity import LOGP_TOL_BF16, MARGIN_GATE
+from parity import LOGP_TOL_BF16, MARGIN_GATE, oracle_replay_window
 from paper_2511_20100_amd import inputs
 
 CFG = inputs.POLICY_1P5B
@@ -94,6 +94,35 @@ def test_rows_against_the_oracle(run, row, steps):
     assert gate.mean() > 0.8
     assert err_r.max() <= LOGP_TOL_BF16
     assert err_s.max() <= LOGP_TOL_BF16
+
+
+def test_worst_decode_vs_score_tokens_against_the_oracle(run):
+    """The two GPU paths (decode step, scoring pass) round differently; where they disagree most, at least one of
+    them is furthest from the exact value.  Those tokens are the ones worth the oracle's time: the six rows that
+    hold the largest |decode - score| of the whole run, a 128-step window around each row's worst step, both
+    paths against the oracle within the tolerance and every sampling decision above the margin gate redone."""
+    model = oracle_model(run["w"], PROMPT_LEN + MAX_NEW)
+    d = np.abs(run["score"][:, PROMPT_LEN - 1:] - run["lp"])
+    rows = np.argsort(d.max(axis=1))[::-1][:6]
+    worst_r = worst_s = 0.0
+    for row in rows:
+        s_star = int(d[row].argmax())
+        lo = max(0, min(s_star - 64, MAX_NEW - 128))
+        hi = lo + 128
+        tok, ref_lp, mar = oracle_replay_window(model, run["prompts"][row // N_SAMPLES], run["ids"][row], lo, hi, 1.0, 1,
+                                                int(row))
+        gate = mar > MARGIN_GATE
+        given = run["ids"][row, lo:hi]
+        err_r = np.abs(ref_lp - run["lp"][row, lo:hi])
+        err_s = np.abs(ref_lp - run["score"][row, PROMPT_LEN - 1 + lo:PROMPT_LEN - 1 + hi])
+        print(f"row {row} steps {lo}..{hi - 1} (|decode - score| {d[row, s_star]:.2e} at step {s_star}): "
+              f"rollout err max {err_r.max():.2e} (at the worst step {err_r[s_star - lo]:.2e}), "
+              f"score err max {err_s.max():.2e} (at the worst step {err_s[s_star - lo]:.2e}), "
+              f"{int(gate.sum())}/128 decisions compared", flush=True)
+        assert np.array_equal(tok[gate], given[gate]), (row, np.nonzero(gate & (tok != given))[0][:8])
+        worst_r, worst_s = max(worst_r, float(err_r.max())), max(worst_s, float(err_s.max()))
+    print(f"worst over the six windows: rollout {worst_r:.2e}, score {worst_s:.2e}")
+    assert worst_r <= LOGP_TOL_BF16 and worst_s <= LOGP_TOL_BF16
 
 
 def test_score_top1_against_the_oracle(run):

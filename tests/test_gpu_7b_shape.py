@@ -38,7 +38,7 @@ def test_long_context_and_long_scoring_at_the_7b_shape():
     import torch
     from paper_2511_20100_amd import mtmc
     cfg = CFG.with_(n_layers=1)
-    w = inputs.make_weights(cfg, seed=0)
+    w = inputs.make_weights(cfg, seed=0, gain_std=0.1)
     handle = mtmc.mtmc_weights_create(mtmc.make_config(cfg, 3072), w.blob())
     try:
         prompts = inputs.make_prompts(4, 2048, cfg.vocab, seed=2)

@@ -38,7 +38,7 @@ def lib():
 
 @pytest.mark.parametrize("name,cfg,std,tol,n_states,P,K,A,min_len,normalize", CASES, ids=[c[0] for c in CASES])
 def test_actions_match_oracle(lib, name, cfg, std, tol, n_states, P, K, A, min_len, normalize):
-    w = inputs.make_weights(cfg, seed=0, std=std)
+    w = inputs.make_weights(cfg, seed=0, std=std, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, max(512, P + A)), w.blob())
     try:
         states = inputs.make_prompts(n_states, P, cfg.vocab, seed=21)
@@ -57,7 +57,7 @@ def test_actions_agree_with_the_scoring_pass_and_ignore_padding(lib):
     give identical bits."""
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         P, K, A = 41, 4, 9
@@ -85,7 +85,7 @@ def test_actions_agree_with_the_scoring_pass_and_ignore_padding(lib):
 def test_bad_action_lengths_and_shapes_are_reported(lib):
     import torch
     cfg = inputs.TINY
-    w = inputs.make_weights(cfg, seed=0)
+    w = inputs.make_weights(cfg, seed=0, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 64), w.blob())
     try:
         states = torch.from_numpy(inputs.make_prompts(2, 8, cfg.vocab, seed=1)).cuda()

@@ -45,7 +45,7 @@ def lib():
 
 @pytest.mark.parametrize("name,cfg,std,n_prompts,plen,n_samples,max_new,temp", CASES, ids=[c[0] for c in CASES])
 def test_rollout_and_score(lib, name, cfg, std, n_prompts, plen, n_samples, max_new, temp):
-    w = inputs.make_weights(cfg, seed=0, std=std)
+    w = inputs.make_weights(cfg, seed=0, std=std, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         prompts = inputs.make_prompts(n_prompts, plen, cfg.vocab, seed=2)
@@ -64,7 +64,7 @@ def test_rollout_and_score(lib, name, cfg, std, n_prompts, plen, n_samples, max_
 def test_determinism_and_offsets(lib):
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         prompts = torch.from_numpy(inputs.make_prompts(3, 20, cfg.vocab, seed=5)).cuda()
@@ -85,7 +85,7 @@ def test_determinism_and_offsets(lib):
 def test_score_long_sequences_and_chunks(lib):
     """Sequences longer than one attention block, several sequences per chunk and several chunks."""
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=3, std=0.05)
+    w = inputs.make_weights(cfg, seed=3, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 4096), w.blob())
     try:
         seqs = inputs.make_sequences(40, 333, cfg.vocab, seed=9)     # 40 x 333 tokens: 2 chunks of 24 + 16
@@ -103,7 +103,7 @@ def test_graph_replay_matches_direct_launches(lib):
     launches, on every replay, with other work and synchronisations in between."""
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         prompts = torch.from_numpy(inputs.make_prompts(4, 19, cfg.vocab, seed=5)).cuda()
@@ -128,7 +128,7 @@ def test_calls_overlapping_on_two_streams_match_calls_in_turn(lib):
     stream, give bit for bit what the same calls give one after the other."""
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         halves = [torch.from_numpy(inputs.make_prompts(3, 21, cfg.vocab, seed=5 + i)).cuda() for i in range(2)]
@@ -161,7 +161,7 @@ def test_at_64_rows_the_first_tokens_do_not_depend_on_max_new(lib):
     generation budget (more pages per sequence) leaves the arithmetic of the first steps unchanged, bit for bit."""
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         prompts = torch.from_numpy(inputs.make_prompts(8, 150, cfg.vocab, seed=5)).cuda()  # > 8 pages: split in both calls
@@ -176,7 +176,7 @@ def test_at_64_rows_the_first_tokens_do_not_depend_on_max_new(lib):
 def test_kernel_timer_does_not_change_results(lib):
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         prompts = torch.from_numpy(inputs.make_prompts(2, 17, cfg.vocab, seed=5)).cuda()
@@ -197,7 +197,7 @@ def test_lds_staged_gemm_on_ragged_shapes(lib, cfg, n_seqs, seq_len):
     feature counts (256 ... 2 x 688) that are not multiples of its block, against the oracle and
     against the direct kernel; then the same for the prompt pass of a rollout."""
     import torch
-    w = inputs.make_weights(cfg, seed=4, std=0.05)
+    w = inputs.make_weights(cfg, seed=4, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 512), w.blob())
     try:
         seqs = inputs.make_sequences(n_seqs, seq_len, cfg.vocab, seed=11)
@@ -219,7 +219,7 @@ def test_long_context_over_several_attention_chunks(lib):
     the context is then split over workgroups whose partial results the O projection combines.
     Prompt 8200 + 24 new tokens, small model, both samples replayed on the oracle."""
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=6, std=0.05)
+    w = inputs.make_weights(cfg, seed=6, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 8256), w.blob())
     try:
         prompts = inputs.make_prompts(1, 8200, cfg.vocab, seed=8)
@@ -235,7 +235,7 @@ def test_long_context_at_more_than_64_rows(lib):
     tokens, so that the O projection of that form has to combine two context chunks.  One prompt
     of 8200 tokens with 72 samples; three of them are replayed on the oracle."""
     cfg = GQA4
-    w = inputs.make_weights(cfg, seed=6, std=0.05)
+    w = inputs.make_weights(cfg, seed=6, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 8256), w.blob())
     try:
         prompts = inputs.make_prompts(1, 8200, cfg.vocab, seed=8)
@@ -250,7 +250,7 @@ def test_long_context_at_more_than_64_rows(lib):
 def test_context_limit_is_enforced(lib):
     import torch
     cfg = GQA4
-    w = inputs.make_weights(cfg, seed=6, std=0.05)
+    w = inputs.make_weights(cfg, seed=6, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 40000), w.blob())
     try:
         with pytest.raises(lib.MtmcError) as e:
@@ -266,7 +266,7 @@ def test_degenerate_sizes(lib):
     a call split over two processes' worth of prompts (seq_offset) that must reproduce the whole call."""
     import torch
     cfg = SMALL
-    w = inputs.make_weights(cfg, seed=1, std=0.05)
+    w = inputs.make_weights(cfg, seed=1, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
     try:
         seqs = torch.from_numpy(inputs.make_sequences(3, 20, cfg.vocab, seed=4)).cuda()
@@ -292,7 +292,7 @@ def test_bad_inputs_are_reported(lib):
     """A token id outside the vocabulary raises the sticky data flag; a weight beyond the fp16 range is refused."""
     import torch
     cfg = SMALL
-    w = inputs.make_weights(cfg, seed=1, std=0.05)
+    w = inputs.make_weights(cfg, seed=1, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
     try:
         prompts = torch.from_numpy(inputs.make_prompts(2, 8, cfg.vocab, seed=5)).cuda()
@@ -315,3 +315,93 @@ def test_bad_inputs_are_reported(lib):
     with pytest.raises(lib.MtmcError) as e:
         lib.mtmc_weights_create(lib.make_config(cfg, 128), blob)
     assert e.value.code == lib.MTMC_EINVAL
+
+
+def test_graph_of_a_tail_group_is_not_reused_by_a_call_of_its_shape(lib):
+    """A call of 20 prompts x 8 samples runs as groups of 128 + 32 rows; the 32-row group's captured step holds
+    pointers laid out by the 160-row plan.  A later call of 4 x 8 on the SAME workspace has its own plan: it must
+    not replay that graph.  Its results equal a fresh handle's (no cached graphs) bit for bit."""
+    import torch
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
+    plen, n_new = 18, 9
+    prompts = torch.from_numpy(inputs.make_prompts(20, plen, cfg.vocab, seed=5)).cuda()
+    tail = prompts[16:].contiguous()
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 64), w.blob())
+    try:
+        ws = torch.empty(lib.mtmc_rollout_workspace_bytes(handle, 20, plen, 8, n_new), dtype=torch.uint8, device="cuda")
+        assert ws.numel() >= lib.mtmc_rollout_workspace_bytes(handle, 4, plen, 8, n_new)
+        big = lib.mtmc_rollout(handle, prompts, 8, n_new, 1.0, 3, workspace=ws)
+        small = lib.mtmc_rollout(handle, tail, 8, n_new, 1.0, 3, seq_offset=128, workspace=ws)
+        again = lib.mtmc_rollout(handle, prompts, 8, n_new, 1.0, 3, workspace=ws)
+        lib.mtmc_poll_errors(handle)
+        big, small, again = [[t.cpu() for t in r] for r in (big, small, again)]
+    finally:
+        lib.mtmc_weights_destroy(handle)
+    fresh = lib.mtmc_weights_create(lib.make_config(cfg, 64), w.blob())
+    try:
+        ref = lib.mtmc_rollout(fresh, tail, 8, n_new, 1.0, 3, seq_offset=128)
+        lib.mtmc_poll_errors(fresh)
+        ref = [t.cpu() for t in ref]
+    finally:
+        lib.mtmc_weights_destroy(fresh)
+    assert torch.equal(small[0], ref[0]) and torch.equal(small[1], ref[1])
+    assert torch.equal(big[0], again[0]) and torch.equal(big[1], again[1])
+    # the same sequences inside the 160-row call: same noise, same ids (the 32-row group runs the same tiling)
+    assert torch.equal(big[0][128:], small[0])
+
+
+def test_values_beyond_the_fp16_range_are_reported(lib):
+    """The matrix products take fp16 operands.  A model whose value projection produces magnitudes beyond 65504
+    has them clamped in the KV cache: both the scoring pass and the rollout must raise the sticky data flag, and
+    the message must name the cause; the unscaled model raises nothing."""
+    import torch
+    cfg = SMALL
+    w = inputs.make_weights(cfg, seed=1, std=0.05, gain_std=0.1)
+    seqs = torch.from_numpy(inputs.make_sequences(2, 24, cfg.vocab, seed=4)).cuda()
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        lib.mtmc_score(handle, seqs, 8)
+        lib.mtmc_rollout(handle, seqs[:, :8].contiguous(), 2, 4, 1.0, 1)
+        lib.mtmc_poll_errors(handle)   # clean
+    finally:
+        lib.mtmc_weights_destroy(handle)
+    # one row of Wv of the second block scaled to 2e4 per entry (a legal fp16 weight): |v| ~ 2e4 * |x|_1 >> 65504
+    big = inputs.bf16_bits_to_f32(w.tensors["layers.1.wv"]).copy()
+    big[5, :] = 2.0e4
+    w.tensors["layers.1.wv"] = inputs.f32_to_bf16_bits(big)
+    w.drop_cache()
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        lib.mtmc_score(handle, seqs, 8)
+        with pytest.raises(lib.MtmcError) as e:
+            lib.mtmc_poll_errors(handle)
+        assert e.value.code == lib.MTMC_EDATA and "fp16 range" in str(e.value) and "token id" not in str(e.value)
+        lib.mtmc_poll_errors(handle)   # the flag was cleared by the poll
+        lib.mtmc_rollout(handle, seqs[:, :8].contiguous(), 2, 4, 1.0, 1)
+        with pytest.raises(lib.MtmcError) as e:
+            lib.mtmc_poll_errors(handle)
+        assert e.value.code == lib.MTMC_EDATA and "fp16 range" in str(e.value)
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_lds_gemm_at_its_shortest_reduction(lib):
+    """The LDS-staged GEMM streams k-steps through a ring of four buffers and needs at least four of them:
+    d_model = d_ffn = n_q_heads * head_dim = 128 gives every matrix product of the scoring pass (QKV, O,
+    gate/up, down, LM head) exactly four k-steps, the shortest pipeline there is, with several output blocks
+    per workgroup so that the stream crosses block boundaries with the ring never more than one block deep."""
+    cfg = inputs.ModelConfig(2, 128, 1, 1, 128, 128, 4096, dtype="bf16")
+    w = inputs.make_weights(cfg, seed=2, std=0.08, gain_std=0.1)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 512), w.blob())
+    try:
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_GEMM_LDS_MIN_BLOCKS, 1)
+        seqs = inputs.make_sequences(5, 300, cfg.vocab, seed=8)      # 1500 tokens: 6 row blocks, ragged tail
+        sc = check_score(handle, w, seqs, 200, max_positions=512, rows=[0, 4], label="k4-lds")
+        print("LDS GEMM with four k-steps: max log-prob err", sc["max_logp_err"], "top-1 compared", sc["compared"])
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_GEMM_LDS_MIN_BLOCKS, 1 << 20)   # the direct kernel on the same data
+        import torch
+        a = lib.mtmc_score(handle, torch.from_numpy(seqs).cuda(), 200)
+        assert (a.cpu().numpy() - sc["logprobs"]).__abs__().max() <= 1e-3
+    finally:
+        lib.mtmc_weights_destroy(handle)

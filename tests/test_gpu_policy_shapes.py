@@ -16,7 +16,7 @@ SHAPES = [("1p3b-mha", inputs.POLICY_1P3B_MHA.with_(n_layers=2)), ("1b-hd64", in
 @pytest.mark.parametrize("name,cfg", SHAPES, ids=[s[0] for s in SHAPES])
 def test_two_blocks_of_the_policy_shape(name, cfg):
     from paper_2511_20100_amd import mtmc
-    w = inputs.make_weights(cfg, seed=0)
+    w = inputs.make_weights(cfg, seed=0, gain_std=0.1)
     handle = mtmc.mtmc_weights_create(mtmc.make_config(cfg, 128), w.blob())
     try:
         prompts = inputs.make_prompts(8, 40, cfg.vocab, seed=2)

@@ -29,7 +29,7 @@ def junk_padding(prompts, lens, vocab):
 def test_fp32_ids_exact_with_and_without_stop(lib):
     import torch
     cfg = inputs.TINY
-    w = inputs.make_weights(cfg, seed=0)
+    w = inputs.make_weights(cfg, seed=0, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
     try:
         prompts = inputs.make_prompts(4, 40, cfg.vocab, seed=2)
@@ -70,7 +70,7 @@ CASES = [
 @pytest.mark.parametrize("name,cfg,std,lens,n_samples,max_new,temp", CASES, ids=[c[0] for c in CASES])
 def test_bf16_ragged_by_replay(lib, name, cfg, std, lens, n_samples, max_new, temp):
     import torch
-    w = inputs.make_weights(cfg, seed=0, std=std)
+    w = inputs.make_weights(cfg, seed=0, std=std, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         lens = np.array(lens, dtype=np.int32)
@@ -94,7 +94,7 @@ def test_bf16_ragged_by_replay(lib, name, cfg, std, lens, n_samples, max_new, te
 def test_equal_lengths_give_the_uniform_rollout_and_padding_never_matters(lib):
     import torch
     cfg = GQA6
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
     try:
         dev = lambda x: torch.from_numpy(x).cuda()
@@ -121,7 +121,7 @@ def test_equal_lengths_give_the_uniform_rollout_and_padding_never_matters(lib):
 def test_bad_lengths_and_stop_ids_are_reported(lib):
     import torch
     cfg = inputs.TINY
-    w = inputs.make_weights(cfg, seed=0)
+    w = inputs.make_weights(cfg, seed=0, gain_std=0.1)
     handle = lib.mtmc_weights_create(lib.make_config(cfg, 64), w.blob())
     try:
         prompts = torch.from_numpy(inputs.make_prompts(2, 8, cfg.vocab, seed=1)).cuda()

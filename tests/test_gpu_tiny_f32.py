@@ -130,7 +130,7 @@ def test_tied_lm_head():
     import torch
     from paper_2511_20100_amd import mtmc
     cfg = inputs.TINY.with_(tie_embeddings=True)
-    w = inputs.make_weights(cfg, seed=0, std=0.05)
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
     assert "lm_head" not in set(w.names())
     handle = mtmc.mtmc_weights_create(mtmc.make_config(cfg, 64), w.blob())
     try:

@@ -397,3 +397,17 @@ def test_tiny_workload_fp32_vs_fp64_and_margins():
     assert np.abs(s32 - s64).max() < 1e-5
     assert np.abs(s32[:, 31:] - lp).max() < 1e-5
     assert abs(float(lp.mean()) + math.log(4096)) < 0.2   # near-uniform policy at these weights
+
+
+def test_replay_window_equals_replay():
+    """The windowed replay used at the full-size workload (blocks over the prefix, LM head over the window's
+    rows only) is oracle.replay restricted to those steps."""
+    from parity import oracle_replay_window
+    cfg = small_cfg()
+    m = oracle_model(inputs.make_weights(cfg, seed=1, std=0.3, gain_std=0.1), max_positions=64)
+    prompt = inputs.make_prompts(1, 7, cfg.vocab, seed=2)[0]
+    ids, _, _ = oracle.rollout(m, prompt[None, :], 1, 20, 1.0, seed=5, first_seq=3)
+    tok, lp, mar = oracle.replay(m, prompt, ids[0], 1.0, 5, 3)
+    for lo, hi in [(0, 20), (4, 11), (19, 20)]:
+        t, l, r = oracle_replay_window(m, prompt, ids[0], lo, hi, 1.0, 5, 3)
+        assert np.array_equal(t, tok[lo:hi]) and np.allclose(l, lp[lo:hi], atol=1e-6) and np.allclose(r, mar[lo:hi], atol=1e-6)
