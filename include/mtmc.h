@@ -220,6 +220,21 @@ int mtmc_ppo_clip_loss(const float* new_logprobs, const float* old_logprobs, con
                        size_t workspace_bytes, void* stream);
 
 /*
+ * mtmc_ppo_clip_loss_static: mtmc_ppo_clip_loss for callers that cannot allocate device memory or pass a
+ * workspace -- code under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without the workspace), same kernels, same results bit for bit.  The per-workgroup partial sums
+ * live in a 32 KiB array that is part of the library's device code (one copy per GPU, held until the process
+ * ends); the call allocates and frees nothing.  Limits and rules:
+ *   - n <= MTMC_PPO_STATIC_MAX_SAMPLES, else MTMC_EINVAL (a larger job goes through mtmc_ppo_clip_loss);
+ *   - every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (different streams,
+ *     different threads) race on it and must be ordered by the caller; calls on one stream are ordered;
+ *   - the array keeps the previous call's partial sums; every call overwrites the entries it reads.
+ */
+#define MTMC_PPO_STATIC_MAX_SAMPLES 268435456
+int mtmc_ppo_clip_loss_static(const float* new_logprobs, const float* old_logprobs, const float* advantages,
+                              const int32_t* mask, int64_t n, float clip_eps, double* out, void* stream);
+
+/*
  * Synchronises `stream`, then returns MTMC_EDATA if any kernel since the last poll raised a bit of the
  * device's sticky data flag (the flag is cleared; mtmc_last_error() names the causes), MTMC_EHIP on a
  * runtime error, else MTMC_OK.  The bits:

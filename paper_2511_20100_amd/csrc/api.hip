@@ -397,3 +397,22 @@ extern "C" int mtmc_ppo_clip_loss(const float* new_logprobs, const float* old_lo
   return MTMC_OK;
 }
 
+extern "C" int mtmc_ppo_clip_loss_static(const float* new_logprobs, const float* old_logprobs,
+                                         const float* advantages, const int32_t* mask, int64_t n, float clip_eps,
+                                         double* out, void* stream) {
+  MTMC_REQUIRE(new_logprobs && old_logprobs && advantages && out, "NULL pointer argument");
+  MTMC_REQUIRE(n > 0, "n must be positive");
+  if (n > (int64_t)MTMC_PPO_STATIC_MAX_SAMPLES) {
+    set_error("invalid argument: mtmc_ppo_clip_loss_static takes at most MTMC_PPO_STATIC_MAX_SAMPLES (" +
+              std::to_string((long long)MTMC_PPO_STATIC_MAX_SAMPLES) + ") samples per call, got " +
+              std::to_string((long long)n) + "; use mtmc_ppo_clip_loss with a workspace, or split the samples");
+    return MTMC_EINVAL;
+  }
+  MTMC_REQUIRE(clip_eps >= 0.f && clip_eps < 1.f && std::isfinite(clip_eps), "clip_eps must lie in [0, 1)");
+  void* partials = nullptr;
+  if (int rc = ppo_static_scratch(&partials)) return rc;
+  launch_ppo_clip_loss(new_logprobs, old_logprobs, advantages, mask, (long long)n, (double)clip_eps, out, partials,
+                       (hipStream_t)stream);
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}

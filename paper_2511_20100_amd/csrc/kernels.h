@@ -51,6 +51,8 @@ void launch_action_reduce(float* token_lp, const int* action_len, int n_states, 
 // Clipped PPO surrogate over n samples (mask may be NULL); out = {loss, clip fraction, approx KL, count} as
 // doubles; workspace of ppo_workspace_bytes() bytes holds the per-workgroup partial sums.
 size_t ppo_workspace_bytes();
+// Device address of the current GPU's file-scope scratch array of ppo_workspace_bytes() bytes (MTMC_OK or an error).
+int ppo_static_scratch(void** out);
 void launch_ppo_clip_loss(const float* new_logp, const float* old_logp, const float* adv, const int* mask,
                           long long n, double eps, double* out, void* workspace, hipStream_t st);
 

@@ -1,6 +1,8 @@
 // Clipped surrogate of the PPO update over scored samples (value and two diagnostics, no gradient).
 // Two launches: per-workgroup partial sums in double, then one workgroup adds the partials; both
 // reductions run in a fixed order, so the result does not depend on scheduling.
+#include <mutex>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -63,9 +65,41 @@ __global__ __launch_bounds__(kPpoThreads) void k_ppo_final(const PpoSums* partia
   }
 }
 
+// Partial sums of the entry point that takes no workspace: one copy of this array per GPU, part of the loaded
+// code object, alive until the process ends.  Host code never uses the array's name as an address: it asks the
+// runtime for the device address once per device (ppo_static_scratch) and passes that to the kernels.
+static __device__ __align__(256) unsigned char scratch[kPpoBlocks * sizeof(PpoSums)];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
 }  // namespace
 
 size_t ppo_workspace_bytes() { return kPpoBlocks * sizeof(PpoSums); }
+
+// Device address of this GPU's copy of `scratch` (looked up on the first call on a device, with that device current).
+int ppo_static_scratch(void** out) {
+  int dev = -1;
+  MTMC_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("device index " + std::to_string(dev) + " is beyond the " + std::to_string(kMaxDevices) +
+              " devices the static scratch table covers");
+    return MTMC_EINVAL;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    MTMC_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) {
+      set_error("hipGetSymbolAddress returned no address for the static scratch array");
+      return MTMC_EHIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MTMC_OK;
+}
 
 void launch_ppo_clip_loss(const float* new_logp, const float* old_logp, const float* adv, const int* mask,
                           long long n, double eps, double* out, void* workspace, hipStream_t st) {

@@ -69,6 +69,8 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_ppo_workspace_bytes.restype = sz
     lib.mtmc_ppo_clip_loss.argtypes = [vp, vp, vp, vp, ctypes.c_int64, f32, vp, vp, sz, vp]
     lib.mtmc_ppo_clip_loss.restype = ctypes.c_int
+    lib.mtmc_ppo_clip_loss_static.argtypes = [vp, vp, vp, vp, ctypes.c_int64, f32, vp, vp]
+    lib.mtmc_ppo_clip_loss_static.restype = ctypes.c_int
     lib.mtmc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.mtmc_set_option.restype = ctypes.c_int
     lib.mtmc_kernel_timer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -92,7 +94,8 @@ EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mt
            "mtmc_rollout", "mtmc_score_workspace_bytes", "mtmc_score", "mtmc_poll_errors", "mtmc_last_error",
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
            "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
-           "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss", "mtmc_data_error_string")
+           "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss", "mtmc_data_error_string",
+           "mtmc_ppo_clip_loss_static")
 
 
 def mtmc_last_error() -> str:
@@ -269,6 +272,31 @@ def mtmc_ppo_clip_loss(new_logprobs: torch.Tensor, old_logprobs: torch.Tensor, a
     _check(_lib.mtmc_ppo_clip_loss(new_logprobs.data_ptr(), old_logprobs.data_ptr(), advantages.data_ptr(),
                                    mask.data_ptr() if mask is not None else None, new_logprobs.numel(), clip_eps,
                                    out.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return out
+
+
+MTMC_PPO_STATIC_MAX_SAMPLES = 268435456
+
+
+def mtmc_ppo_clip_loss_static(new_logprobs: torch.Tensor, old_logprobs: torch.Tensor, advantages: torch.Tensor,
+                              clip_eps: float, mask: Optional[torch.Tensor] = None, *,
+                              out: Optional[torch.Tensor] = None, n: Optional[int] = None,
+                              stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """mtmc_ppo_clip_loss without a workspace (the library's own static device array holds the partial sums).
+    With ``out`` given (CUDA double [4]) nothing is allocated on the way; ``n`` (default: all) takes the first n
+    samples of the tensors."""
+    for t in (new_logprobs, old_logprobs, advantages):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == new_logprobs.numel()
+    if mask is not None:
+        assert mask.is_cuda and mask.dtype == torch.int32 and mask.is_contiguous() and mask.numel() == new_logprobs.numel()
+    n = new_logprobs.numel() if n is None else int(n)
+    assert n <= new_logprobs.numel()
+    if out is None:
+        out = torch.empty(4, dtype=torch.float64, device=new_logprobs.device)
+    assert out.is_cuda and out.dtype == torch.float64 and out.numel() >= 4
+    _check(_lib.mtmc_ppo_clip_loss_static(new_logprobs.data_ptr(), old_logprobs.data_ptr(), advantages.data_ptr(),
+                                          mask.data_ptr() if mask is not None else None, n, clip_eps,
+                                          out.data_ptr(), _stream_ptr(stream)))
     return out
 
 
