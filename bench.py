@@ -25,11 +25,35 @@ sys.path.insert(0, ROOT)
 from paper_2511_20100_amd import inputs  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
-# HBM bytes one launch of the gate/up decode kernel moves at the 1.5B workload, from FETCH_SIZE / WRITE_SIZE
-# counter runs scaled by the library's copy kernel (profiles/decode_kernels_1p5b_hbm_counters.txt).
-# Belongs to k_gemm_dec<6, 4, 8, 2, 2, 1, SWIGLU, 2>: set to None when that kernel or its launch shape changes.
-GATE_UP_TRAFFIC_1P5B = 27939.5 * 1024 * 2.000 + 1120.0 * 1024 * 1.000
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
+# Counter summary that holds the HBM bytes one launch of the gate/up decode kernel moves at the 1.5B workload
+# (FETCH_SIZE / WRITE_SIZE runs scaled by the library's copy kernel), with the hash of the kernel sources the
+# counters were taken on: `traffic` is reported only while those sources are unchanged.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "decode_kernels_1p5b_hbm_counters.txt")
+DECODE_KERNEL_SOURCES = ("decode_bf16.hip", "frag.h", "bf16_kernels.h", "attention_core.h", "device_utils.h")
+
+
+def decode_sources_hash() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in DECODE_KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2511_20100_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def gate_up_traffic_from_profile():
+    """Bytes per launch from the committed counter summary, or None when the summary is missing, has no
+    machine-readable line, or was taken on other kernel sources than the ones in the tree."""
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None
+    m = re.search(r"^gate_up_traffic_bytes_per_launch:\s*([0-9.]+)\s+decode_sources_sha256_16:\s*([0-9a-f]{16})", text, re.M)
+    if not m or m.group(2) != decode_sources_hash():
+        return None
+    return float(m.group(1))
 
 WORKLOADS = {
     # name: (config, n_prompts, prompt_len, n_samples, max_new)
@@ -68,30 +92,68 @@ def forward_flops(cfg, n_seqs, seq_len, scored_per_seq):
     return gemm + attn + head
 
 
-def cpu_baseline(weights, cfg, prompts, max_positions):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+def cpu_baseline(weights, cfg, prompts, max_positions, score_only=False):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload: at the 1.5 B class
+    one whole prompt, at the 7 B class (14 GFLOP per token) one prompt truncated to 192 tokens.  The first use of
+    a bf16 tensor widens it to fp32 (an exact conversion, kept for the later tokens): that is part of the time."""
     sys.path.insert(0, os.path.join(ROOT, "oracle"))
     import mtmc_oracle as oracle
     model = oracle.Model(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads,
                          n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab,
                          rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, w=weights.f32, max_positions=max_positions)
-    if cfg.n_layers * cfg.d_model > 10000:
-        n_p, n_s, n_new = 1, 2, 128
+    big = cfg.n_layers * cfg.d_model > 60000          # 7 B class
+    if big:
+        n_p, n_s, n_new, plen = 1, 1, 8, 192
+    elif cfg.n_layers * cfg.d_model > 10000:
+        n_p, n_s, n_new, plen = 1, 2, 128, prompts.shape[1]
     else:
-        n_p, n_s, n_new = prompts.shape[0], 2, 32
+        n_p, n_s, n_new, plen = prompts.shape[0], 2, 32, prompts.shape[1]
+    sample_prompts = prompts[:n_p, :plen]
     t0 = time.perf_counter()
-    ids, _, _ = oracle.rollout(model, prompts[:n_p], n_s, n_new, 1.0, seed=1)
-    seqs = np.concatenate([np.repeat(prompts[:n_p], n_s, axis=0), ids], axis=1)[:1]
-    oracle.score(model, seqs, prompt_len=prompts.shape[1])
-    dt = time.perf_counter() - t0
+    if score_only:
+        seqs = np.concatenate([sample_prompts, prompts[:n_p, plen:plen + 64]], axis=1)
+        oracle.score(model, seqs, prompt_len=plen)
+        dt = time.perf_counter() - t0
+        n_tok, what = seqs.size, (f"scoring of {n_p} sequence of {seqs.shape[1]} tokens (the first {plen} as prompt: "
+                                  f"{seqs.shape[1] - plen} scored)")
+    else:
+        ids, _, _ = oracle.rollout(model, sample_prompts, n_s, n_new, 1.0, seed=1)
+        seqs = np.concatenate([np.repeat(sample_prompts, n_s, axis=0), ids], axis=1)[:1]
+        oracle.score(model, seqs, prompt_len=plen)
+        dt = time.perf_counter() - t0
+        n_tok, what = n_p * n_s * n_new, (f"{n_p} prompt(s) of {plen} tokens x {n_s} samples x {n_new} new tokens "
+                                          f"(cached decode), then scoring of 1 resulting sequence")
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    return {"value": n_p * n_s * n_new / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n_p} prompt(s) of {prompts.shape[1]} tokens x {n_s} samples x {n_new} new tokens "
-                      f"(cached decode), then scoring of 1 resulting sequence; {dt:.1f} s; subset, not extrapolated"}
+    return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{what}; {dt:.1f} s; subset, not extrapolated"}
+
+
+def attainable_rates(torch, mtmc, dev):
+    """What this GPU sustains, measured here: a plain streaming read of 2 GiB (GB/s) and a register-only loop of
+    fp16 32x32x16 matrix instructions on every SIMD (TFLOP/s)."""
+    stream = torch.cuda.current_stream()
+    buf = torch.ones(2 << 30, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    mtmc.mtmc_read_probe(buf, sink)
+    e[0].record(stream)
+    for _ in range(4):
+        mtmc.mtmc_read_probe(buf, sink)
+    e[1].record(stream)
+    e[1].synchronize()
+    read_gbs = 4 * buf.numel() / (e[0].elapsed_time(e[1]) * 1e-3) / 1e9
+    del buf
+    out = torch.empty(1024 * 256, dtype=torch.float32, device=dev)
+    mtmc.mtmc_mfma_probe(out, 1024, 2000)
+    e[0].record(stream)
+    flops = mtmc.mtmc_mfma_probe(out, 1024, 20000)
+    e[1].record(stream)
+    e[1].synchronize()
+    return read_gbs, flops / (e[0].elapsed_time(e[1]) * 1e-3) / 1e12
 
 
 def main() -> int:
@@ -214,17 +276,23 @@ def main() -> int:
     decode_ms = r_ms / max(1, max_new - 1)
     step_gbs = step_bytes / (decode_ms * 1e-3) / 1e9
     gate_up_bytes = 2 * cfg.d_ffn * cfg.d_model * 2   # gate and up matrices, 2 bytes per weight, read once
+    read_gbs, mfma_tflops = attainable_rates(torch, mtmc, dev)
+    hbm_attainable = {"value": read_gbs, "unit": "GB/s", "how": "plain streaming read of 2 GiB, measured in this run"}
+    mfma_attainable = {"value": mfma_tflops, "unit": "TFLOP/s",
+                       "how": "register-only loop of fp16 32x32x16 matrix instructions on all SIMDs, measured in this run"}
     if k_launches > 0:
         k_us = 1e3 * k_ms / k_launches
         roofline = {"bound": "hbm", "achieved": gate_up_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gate_up_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                    "traffic": GATE_UP_TRAFFIC_1P5B if args.workload == "1p5b" else None,
+                    "attainable": hbm_attainable,
+                    "traffic": gate_up_traffic_from_profile() if args.workload == "1p5b" else None,
                     "kernel": "k_gemm_dec<..., SWIGLU> (gate/up projection, one launch per layer per decode step)",
                     "bytes_per_launch": gate_up_bytes, "us_per_launch": k_us, "timed_launches": k_launches,
                     "empty_event_pair_us": 1e3 * k_empty_ms}
     else:
         roofline = {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": step_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "whole decode step"}
+                    "frac": step_gbs / HBM_PEAK_GBS, "attainable": hbm_attainable, "traffic": None,
+                    "kernel": "whole decode step"}
     result = {
         "metric": "rollout tokens/sec @1.5B-class bs64 bf16; decode HBM GB/s + scoring MFMA % peak",
         "value": (B * seq_len if args.no_rollout else new_tokens) / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -240,7 +308,8 @@ def main() -> int:
         "rollout_tokens_per_s": new_tokens / (r_ms * 1e-3), "rollout_ms": r_ms,
         "roofline": roofline,
         "decode_step": {"bound": "hbm", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": step_gbs / HBM_PEAK_GBS, "bytes_per_step": step_bytes, "ms_per_step": decode_ms,
+                        "frac": step_gbs / HBM_PEAK_GBS, "attainable": hbm_attainable,
+                        "bytes_per_step": step_bytes, "ms_per_step": decode_ms,
                         "note": "algorithmic bytes of an average decode step (weights once + KV with shared prompt pages) "
                                 "over rollout time / decode steps (prefill time included)"},
         "setup_s": setup_s,
@@ -250,7 +319,8 @@ def main() -> int:
         result["score_tokens_per_s"] = B * seq_len / (s_ms * 1e-3)
         result["score_ms"] = s_ms
         result["score_mfma"] = {"bound": "mfma", "achieved": flops / (s_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
-                                "unit": "TFLOP/s", "frac": flops / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+                                "unit": "TFLOP/s", "frac": flops / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                                "attainable": mfma_attainable}
     if args.no_rollout:  # nothing was decoded: the step is the scoring pass, bound by the matrix cores
         for key in ("rollout_tokens_per_s", "rollout_ms", "decode_step"):
             del result[key]
@@ -276,7 +346,8 @@ def main() -> int:
                                     "actions_per_s": n_prompts * K / (a_ms * 1e-3)}
         del ws_a
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(weights, cfg, prompts_np, seq_len)
+        progress("timing the oracle on the host cores")
+        result["cpu_baseline"] = cpu_baseline(weights, cfg, prompts_np, seq_len, score_only=args.no_rollout)
     mtmc.mtmc_weights_destroy(handle)
     print(json.dumps(result))
     return 0

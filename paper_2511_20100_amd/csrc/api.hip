@@ -150,6 +150,23 @@ extern "C" int mtmc_copy_probe(void* dst, const void* src, size_t bytes, void* s
   return MTMC_OK;
 }
 
+extern "C" int mtmc_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+  MTMC_REQUIRE(src != nullptr && sink != nullptr, "NULL pointer argument");
+  MTMC_REQUIRE(bytes >= (size_t)16384 && bytes % 16384 == 0 && ((uintptr_t)src & 15) == 0,
+               "bytes must be a positive multiple of 16384 and src 16-byte aligned");
+  launch_read_probe(src, bytes, sink, (hipStream_t)stream);
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}
+
+extern "C" int mtmc_mfma_probe(float* out, int32_t workgroups, int32_t iters, void* stream, double* flops) {
+  MTMC_REQUIRE(out != nullptr && flops != nullptr, "NULL pointer argument");
+  MTMC_REQUIRE(workgroups > 0 && workgroups <= 65536 && iters > 0 && iters <= (1 << 24), "workgroups or iters out of range");
+  *flops = launch_mfma_probe(out, workgroups, iters, (hipStream_t)stream);
+  MTMC_HIP_CHECK(hipGetLastError());
+  return MTMC_OK;
+}
+
 extern "C" int mtmc_poll_errors(const mtmc_weights* w, void* stream) {
   MTMC_REQUIRE(w != nullptr, "weights is NULL");
   MTMC_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));

@@ -50,6 +50,10 @@ void launch_action_reduce(float* token_lp, const int* action_len, int n_states, 
 
 // Clipped PPO surrogate over n samples (mask may be NULL); out = {loss, clip fraction, approx KL, count} as
 // doubles; workspace of ppo_workspace_bytes() bytes holds the per-workgroup partial sums.
+// probes.hip: a plain streaming read of `bytes` (a multiple of 16 KiB is read completely) and a register-only
+// loop of matrix instructions (returns the flops the launch performs; out holds workgroups * 256 floats)
+void launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
+double launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t st);
 size_t ppo_workspace_bytes();
 // Device address of the current GPU's file-scope scratch array of ppo_workspace_bytes() bytes (MTMC_OK or an error).
 int ppo_static_scratch(void** out);

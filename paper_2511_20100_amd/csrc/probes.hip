@@ -1,0 +1,71 @@
+// Measurement probes: what this GPU sustains for a plain streaming read and for back-to-back matrix
+// instructions on registers.  The benchmark reports both beside the published peaks.
+#include "common.h"
+#include "kernels.h"
+
+namespace mtmc {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t pv4u;
+typedef __attribute__((ext_vector_type(8))) _Float16 pv8h;
+typedef __attribute__((ext_vector_type(16))) float pv16f;
+
+// Every workgroup reads its contiguous share of the range, eight independent 16-byte loads per lane in flight.
+__global__ __launch_bounds__(512) void k_read_probe(const pv4u* __restrict__ src, size_t vec_per_wg, uint32_t* sink) {
+  const pv4u* p = src + (size_t)blockIdx.x * vec_per_wg;
+  pv4u acc = {0u, 0u, 0u, 0u};
+  size_t i = threadIdx.x;
+  for (; i + 7 * 512 < vec_per_wg; i += 8 * 512) {
+    pv4u v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[i + (size_t)u * 512];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  for (; i < vec_per_wg; i += 512) acc ^= p[i];
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) *sink = 1;  // keeps the loads alive
+}
+
+// One wavefront per SIMD, four independent 32 x 32 accumulators each: the issue pattern of the large-batch GEMM
+// without any memory traffic.
+__global__ __launch_bounds__(256, 1) void k_mfma_probe(float* out, int iters) {
+  pv16f acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  pv8h a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (_Float16)((threadIdx.x & 7) * 0.125f);
+    b[i] = (_Float16)(1.0f - i * 0.125f);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += acc[i][j];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace
+
+void launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st) {
+  const int wgs = 1024;
+  const size_t vec_per_wg = bytes / 16 / wgs;
+  if (vec_per_wg == 0) return;
+  k_read_probe<<<wgs, 512, 0, st>>>((const pv4u*)src, vec_per_wg, (uint32_t*)sink);
+}
+
+double launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t st) {
+  k_mfma_probe<<<workgroups, 256, 0, st>>>(out, iters);
+  // 4 wavefronts x 4 instructions per trip, 2 * 32 * 32 * 16 flops each
+  return (double)workgroups * 4.0 * 4.0 * (double)iters * 32768.0;
+}
+
+}  // namespace mtmc

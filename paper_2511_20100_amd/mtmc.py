@@ -80,6 +80,10 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_kernel_timer_read.restype = ctypes.c_int
     lib.mtmc_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.mtmc_copy_probe.restype = ctypes.c_int
+    lib.mtmc_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.mtmc_read_probe.restype = ctypes.c_int
+    lib.mtmc_mfma_probe.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.mtmc_mfma_probe.restype = ctypes.c_int
     lib.mtmc_poll_errors.argtypes = [vp, vp]
     lib.mtmc_poll_errors.restype = ctypes.c_int
     lib.mtmc_last_error.argtypes = []
@@ -95,7 +99,7 @@ EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mt
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
            "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
            "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss", "mtmc_data_error_string",
-           "mtmc_ppo_clip_loss_static")
+           "mtmc_ppo_clip_loss_static", "mtmc_read_probe", "mtmc_mfma_probe")
 
 
 def mtmc_last_error() -> str:
@@ -331,6 +335,20 @@ def mtmc_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream: Optional[torch
     if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
         raise ValueError("mtmc_copy_probe needs two device tensors of the same byte size")
     _check(_lib.mtmc_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)))
+
+
+def mtmc_read_probe(src: torch.Tensor, sink: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Streams the bytes of `src` (device tensor, a multiple of 16 KiB) through a plain read kernel once."""
+    assert src.is_cuda and sink.is_cuda and src.is_contiguous() and sink.numel() * sink.element_size() >= 4
+    _check(_lib.mtmc_read_probe(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream_ptr(stream)))
+
+
+def mtmc_mfma_probe(out: torch.Tensor, workgroups: int, iters: int, stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Launches the register-only matrix-instruction loop; returns the flops of the launch."""
+    assert out.is_cuda and out.dtype == torch.float32 and out.numel() >= workgroups * 256
+    flops = ctypes.c_double()
+    _check(_lib.mtmc_mfma_probe(out.data_ptr(), workgroups, iters, _stream_ptr(stream), ctypes.byref(flops)))
+    return flops.value
 
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:
