@@ -149,6 +149,28 @@ int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int
                         size_t workspace_bytes, void* stream);
 
 /*
+ * mtmc_rollout_ragged_cached: mtmc_rollout_ragged for a prompt that extends the previous call's (Inference
+ * Pipeline, "Macro Thinking": the state of optimisation step t + 1 is the state of step t plus the new code and
+ * history).  The workspace of a ragged call still holds the keys and values of its prompts; when the first
+ * reuse_len positions of EVERY prompt are unchanged since the previous mtmc_rollout_ragged[_cached] call on the
+ * same workspace, only the positions from reuse_len on are evaluated again.  Results are those of
+ * mtmc_rollout_ragged on the same arguments.
+ *   - reuse_len: a multiple of 16 (whole cache pages), below max_prompt_len; 0 = nothing is kept.
+ *   - the previous call on `workspace` must have had the same n_prompts, max_prompt_len, n_samples and max_new
+ *     (the cache layout follows from them), else MTMC_EINVAL; the caller must not have written to the
+ *     workspace in between, nor used it for another kind of call.
+ *   - checked on the device and reported by mtmc_poll_errors as MTMC_DATA_PREFIX (the results are then wrong):
+ *     every prompt's first reuse_len ids equal the previous call's, every previous prompt was at least
+ *     reuse_len long, every new prompt is longer than reuse_len.
+ *   - MTMC_BF16: the call must fit one group (n_prompts * n_samples <= 128).
+ */
+int mtmc_rollout_ragged_cached(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                               int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples, int32_t max_new,
+                               float temperature, uint64_t seed, uint32_t seq_offset, int32_t stop_id,
+                               int32_t reuse_len, int32_t* out_ids, float* out_logprobs, int32_t* out_lens,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * mtmc_score: teacher-forced pass over seqs [n_seqs, seq_len].  For i in [0, seq_len-1):
  *     out_logprobs[n, i] = z_i[seqs[n, i+1]] - logsumexp_v z_i[v]     if i + 1 >= prompt_len
  *                        = 0                                           otherwise
@@ -242,6 +264,7 @@ int mtmc_ppo_clip_loss_static(const float* new_logprobs, const float* old_logpro
  *   MTMC_DATA_WEIGHT      a weight that is not finite or, MTMC_BF16, exceeds 65504 in magnitude
  *                         (mtmc_weights_create fails with MTMC_EINVAL on it)
  *   MTMC_DATA_LENGTH      an action or prompt length outside its range (clamped)
+ *   MTMC_DATA_PREFIX      mtmc_rollout_ragged_cached: the cached prefix does not match the new prompts
  *   MTMC_DATA_FP16_RANGE  MTMC_BF16: an activation, a rotated query or key, a value or an attention output
  *                         had to be clamped to +-65504 (a NaN becomes -65504) where it is stored as fp16, or
  *                         every logit of a row was NaN (token 0 is then reported).  Outputs of the calls
@@ -252,6 +275,7 @@ int mtmc_ppo_clip_loss_static(const float* new_logprobs, const float* old_logpro
 #define MTMC_DATA_WEIGHT     2
 #define MTMC_DATA_LENGTH     4
 #define MTMC_DATA_FP16_RANGE 8
+#define MTMC_DATA_PREFIX     16
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);
 const char* mtmc_data_error_string(int bits);
 

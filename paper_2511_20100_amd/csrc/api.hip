@@ -91,6 +91,8 @@ extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, siz
   w->opt_hip_graph = 1;
   w->opt_lds_min_blocks = 192;
   w->graphs = nullptr;
+  w->ragged_mu = new (std::nothrow) std::mutex();
+  if (!w->ragged_mu) { delete w; set_error("out of host memory"); return MTMC_ENOMEM; }
   int rc = hipGetDevice(&w->device) == hipSuccess ? MTMC_OK : MTMC_EHIP;
   if (rc == MTMC_OK) rc = build_aux(w, st);
   if (rc == MTMC_OK)
@@ -113,6 +115,7 @@ extern "C" void mtmc_weights_destroy(mtmc_weights* w) {
   destroy_graph_cache(w);
   if (w->storage) (void)hipFree(w->storage);
   if (w->aux) (void)hipFree(w->aux);
+  delete w->ragged_mu;
   delete w;
 }
 
@@ -191,6 +194,9 @@ extern "C" const char* mtmc_data_error_string(int bits) {
   add(MTMC_DATA_TOKEN_ID, "a token id outside [0, vocab) was seen (and clamped) on the device");
   add(MTMC_DATA_WEIGHT, "a weight is not finite or exceeds 65504 in magnitude");
   add(MTMC_DATA_LENGTH, "an action or prompt length outside its range was seen (and clamped) on the device");
+  add(MTMC_DATA_PREFIX,
+      "a cached prompt prefix did not match: the ids of the first reuse_len positions differ from the previous "
+      "call's, or a prompt is not longer than reuse_len, or the previous prompt was shorter (results are wrong)");
   add(MTMC_DATA_FP16_RANGE,
       "an activation, key or value left the fp16 range (magnitude above 65504, or not finite) and was clamped: "
       "the results of the calls since the last poll are unreliable");
@@ -247,6 +253,7 @@ extern "C" int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32
   sa.prompt_lens = nullptr;
   sa.stop_id = -1;
   sa.out_lens = nullptr;
+  sa.reuse_len = 0;
   hipStream_t st = (hipStream_t)stream;
   int rc = w->cfg.dtype == MTMC_F32 ? f32_rollout(w, p, prompts, sa, st)
                                     : bf16_rollout(w, p, prompts, sa, st);
@@ -262,12 +269,14 @@ extern "C" size_t mtmc_rollout_ragged_workspace_bytes(const mtmc_weights* w, int
   return plan_rollout(w, n_prompts, max_prompt_len, n_samples, max_new, nullptr, true).total_bytes;
 }
 
-extern "C" int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
-                                   int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples,
-                                   int32_t max_new, float temperature, uint64_t seed, uint32_t seq_offset,
-                                   int32_t stop_id, int32_t* out_ids, float* out_logprobs, int32_t* out_lens,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
+static int rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                          int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples, int32_t max_new,
+                          float temperature, uint64_t seed, uint32_t seq_offset, int32_t stop_id, int32_t reuse_len,
+                          int32_t* out_ids, float* out_logprobs, int32_t* out_lens, void* workspace,
+                          size_t workspace_bytes, void* stream) {
   if (int rc = check_rollout_shape(w, n_prompts, max_prompt_len, n_samples, max_new)) return rc;
+  MTMC_REQUIRE(reuse_len >= 0 && reuse_len % kPageTokens == 0 && reuse_len < max_prompt_len,
+               "reuse_len must be a non-negative multiple of 16 below max_prompt_len");
   MTMC_REQUIRE(prompts && prompt_lens && out_ids && out_logprobs && out_lens && workspace, "NULL pointer argument");
   MTMC_REQUIRE(temperature >= 0.f && std::isfinite(temperature), "temperature must be finite and >= 0");
   MTMC_REQUIRE(stop_id < w->cfg.vocab, "stop_id must be a token id, or negative for none");
@@ -276,6 +285,25 @@ extern "C" int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts
   if (workspace_bytes < p.total_bytes) {
     set_error("workspace too small for mtmc_rollout_ragged: need " + std::to_string(p.total_bytes) + " bytes");
     return MTMC_ENOMEM;
+  }
+  {
+    // the cached prefix of a workspace: valid for the shape of the last call on it, gone with any other use
+    mtmc_weights* mw = const_cast<mtmc_weights*>(w);
+    std::lock_guard<std::mutex> lock(*mw->ragged_mu);
+    auto& calls = mw->ragged_calls;
+    auto it = calls.begin();
+    while (it != calls.end() && it->workspace != workspace) ++it;
+    if (reuse_len > 0) {
+      MTMC_REQUIRE(p.n_prompts == p.total_prompts,
+                   "a cached prefix needs the whole call in one group (at most 128 sequences with MTMC_BF16)");
+      MTMC_REQUIRE(it != calls.end() && it->n_prompts == n_prompts && it->max_prompt_len == max_prompt_len &&
+                       it->n_samples == n_samples && it->max_new == max_new,
+                   "reuse_len > 0 needs a previous mtmc_rollout_ragged call on this workspace with the same "
+                   "n_prompts, max_prompt_len, n_samples and max_new");
+    }
+    if (it != calls.end()) calls.erase(it);
+    if (calls.size() >= 16) calls.erase(calls.begin());
+    calls.push_back(RaggedCallRecord{workspace, n_prompts, max_prompt_len, n_samples, max_new});
   }
   SampleArgs sa;
   sa.greedy = temperature == 0.f ? 1 : 0;
@@ -288,12 +316,32 @@ extern "C" int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts
   sa.prompt_lens = prompt_lens;
   sa.stop_id = stop_id < 0 ? -1 : stop_id;
   sa.out_lens = out_lens;
+  sa.reuse_len = reuse_len;
   hipStream_t st = (hipStream_t)stream;
   int rc = w->cfg.dtype == MTMC_F32 ? f32_rollout(w, p, prompts, sa, st)
                                     : bf16_rollout(w, p, prompts, sa, st);
   if (rc != MTMC_OK) return rc;
   MTMC_HIP_CHECK(hipGetLastError());
   return MTMC_OK;
+}
+
+extern "C" int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                                   int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples,
+                                   int32_t max_new, float temperature, uint64_t seed, uint32_t seq_offset,
+                                   int32_t stop_id, int32_t* out_ids, float* out_logprobs, int32_t* out_lens,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  return rollout_ragged(w, prompts, prompt_lens, n_prompts, max_prompt_len, n_samples, max_new, temperature, seed,
+                        seq_offset, stop_id, 0, out_ids, out_logprobs, out_lens, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mtmc_rollout_ragged_cached(const mtmc_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                                          int32_t n_prompts, int32_t max_prompt_len, int32_t n_samples,
+                                          int32_t max_new, float temperature, uint64_t seed, uint32_t seq_offset,
+                                          int32_t stop_id, int32_t reuse_len, int32_t* out_ids, float* out_logprobs,
+                                          int32_t* out_lens, void* workspace, size_t workspace_bytes, void* stream) {
+  return rollout_ragged(w, prompts, prompt_lens, n_prompts, max_prompt_len, n_samples, max_new, temperature, seed,
+                        seq_offset, stop_id, reuse_len, out_ids, out_logprobs, out_lens, workspace, workspace_bytes,
+                        stream);
 }
 
 // --------------------------------------------------------------------------------------

@@ -5,6 +5,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -58,6 +59,13 @@ struct KvPool {
 
 struct GraphCache;  // engine_bf16.hip
 
+// What the library remembers (on the host) of the last mtmc_rollout_ragged* call on a workspace: a later call may
+// keep that call's cached prompt prefix only if it has the same shape, hence the same page layout.
+struct RaggedCallRecord {
+  const void* workspace;
+  int n_prompts, max_prompt_len, n_samples, max_new;
+};
+
 struct LayerWeights {
   const float* attn_norm;
   const float* ffn_norm;
@@ -86,4 +94,6 @@ struct mtmc_weights {
   int opt_hip_graph;    // replay decode steps as a captured HIP graph (default 1)
   int opt_lds_min_blocks;  // output blocks (256 x 256) from which large GEMMs use the LDS-staged kernel
   mtmc::GraphCache* graphs;  // instantiated decode-step graphs, keyed by workspace and shape
+  std::mutex* ragged_mu;     // guards ragged_calls
+  std::vector<mtmc::RaggedCallRecord> ragged_calls;  // at most 16, oldest dropped first
 };

@@ -48,6 +48,7 @@ struct RolloutPlan {
   int* row_pos;      // ragged: [B] position of a row's last prompt token
   int* done;         // ragged: [B] stop flags
   int* prompt_ids;   // ragged: [n_prompts, prompt_len] prompts with the padding cleared
+  int* suffix_ids;   // ragged: [n_prompts, prompt_len - reuse_len] the ids that are prefilled (all, without a cached prefix)
   void* kv;
   // activations (Tmax rows unless noted)
   float* h;
@@ -156,6 +157,7 @@ struct SampleArgs {
   const int* prompt_lens;
   int stop_id;
   int* out_lens;
+  int reuse_len;     // leading positions of every prompt whose keys / values the workspace still holds (0: none)
 };
 
 struct ScoreArgs {

@@ -74,6 +74,7 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
     p.row_pos = cv.take<int>(p.B);
     p.done = cv.take<int>(p.B);
     p.prompt_ids = cv.take<int>((size_t)n_prompts * prompt_len);
+    p.suffix_ids = cv.take<int>((size_t)n_prompts * prompt_len);
   }
   p.kv = cv.take<char>((size_t)c.n_layers * 2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim * act);
   p.h = cv.take<float>((size_t)p.Tmax * d);
@@ -249,11 +250,13 @@ int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
   F32Acts A{p.h, (float*)p.x, p.qkv, (float*)p.o, p.gu, (float*)p.a};
   KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};
   const bool ragged = sa.prompt_lens != nullptr;
+  const int R = ragged ? sa.reuse_len : 0;   // cached prefix: only positions R .. prompt_len - 1 are prefilled
+  const int S = p.prompt_len - R;
   if (ragged) {
-    launch_ragged_setup(p.page_table, p.row_pos, p.done, sa.out_lens, p.prompt_ids, prompts, sa.prompt_lens,
-                        p.n_prompts, p.n_samples, p.prompt_len, p.max_pages, p.nf_max, p.shared_total, p.max_new,
-                        w->err_flag, st);
-    prompts = p.prompt_ids;
+    launch_ragged_setup(p.page_table, p.row_pos, p.done, sa.out_lens, p.prompt_ids, p.suffix_ids, prompts,
+                        sa.prompt_lens, p.n_prompts, p.n_samples, p.prompt_len, p.max_pages, p.nf_max,
+                        p.shared_total, p.max_new, R, w->err_flag, st);
+    prompts = p.suffix_ids;
   } else {
     launch_build_page_table(p.page_table, p.B, p.max_pages, p.n_samples, p.n_full, p.shared_total, st);
   }
@@ -261,15 +264,15 @@ int f32_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts,
   // ---- prefill: whole prompts, chunk by chunk; the prompt's pages are those of its first sample
   for (int p0 = 0; p0 < p.n_prompts; p0 += p.chunk_prompts) {
     const int np = std::min(p.chunk_prompts, p.n_prompts - p0);
-    const int T = np * p.prompt_len;
+    const int T = np * S;
     KvPool chunk_pool = pool;
     chunk_pool.page_table = p.page_table + (size_t)p0 * p.n_samples * p.max_pages;
-    TokMap map{p.prompt_len, p.n_samples, 0, nullptr};
-    f32::embed(A.h, prompts + (size_t)p0 * p.prompt_len, T, (const float*)w->embed, d, V, w->err_flag, st);
+    TokMap map{S, p.n_samples, R, nullptr};
+    f32::embed(A.h, prompts + (size_t)p0 * S, T, (const float*)w->embed, d, V, w->err_flag, st);
     f32_layers(w, A, T, map, chunk_pool, 1, st);
     if (ragged)
       launch_gather_last_rows(p.hB + (size_t)p0 * p.n_samples * d, A.h, d, np, p.n_samples, p.prompt_len,
-                              sa.prompt_lens + p0, st);
+                              sa.prompt_lens + p0, R, st);
     else
       launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * d, A.h, np * p.n_samples, d, p.n_samples,
                          p.prompt_len, p.prompt_len - 1, 0, st);

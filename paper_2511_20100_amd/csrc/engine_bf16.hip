@@ -482,32 +482,35 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
                         sa.out_logprobs + out_off, sa.stop_id, (ragged && sa.stop_id >= 0) ? p.done : nullptr,
                         g_out_lens};
     bf16::set_sample_ctl((bf16::SampleCtl*)p.ctl, ctl, st);
+    const int R = ragged ? sa.reuse_len : 0;   // cached prefix: only positions R .. prompt_len - 1 are prefilled
+    const int S = p.prompt_len - R;
     if (ragged) {
-      launch_ragged_setup(p.page_table, p.row_pos, p.done, g_out_lens, p.prompt_ids, gprompts, glens, np_group,
-                          p.n_samples, p.prompt_len, p.max_pages, p.nf_max, gp.shared_total, p.max_new, w->err_flag,
-                          st);
-      gprompts = p.prompt_ids;
+      launch_ragged_setup(p.page_table, p.row_pos, p.done, g_out_lens, p.prompt_ids, p.suffix_ids, gprompts, glens,
+                          np_group, p.n_samples, p.prompt_len, p.max_pages, p.nf_max, gp.shared_total, p.max_new, R,
+                          w->err_flag, st);
+      gprompts = p.suffix_ids;
     } else {
       launch_build_page_table(p.page_table, gp.B, p.max_pages, p.n_samples, p.n_full, gp.shared_total, st);
     }
     launch_set_int(p.d_step, 0, st);
     launch_set_int(p.d_step + 1, 0, st);  // arrival counter of the sampler merge
-    // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0
-    launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
+    // stale or uninitialised cache slots must at least be finite: masked scores multiply them by 0 (with a cached
+    // prefix the pool holds the previous call's values: finite, and the prefix pages must stay)
+    if (R == 0) launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
     // ---- prefill, whole prompts per chunk; a prompt's pages are those of its first sample
     for (int p0 = 0; p0 < np_group; p0 += p.chunk_prompts) {
       const int np = std::min(p.chunk_prompts, np_group - p0);
-      const int T = np * p.prompt_len, mt = tiles16(T);
+      const int T = np * S, mt = tiles16(T);
       KvPool chunk_pool = pool;
       chunk_pool.page_table = p.page_table + (size_t)p0 * p.n_samples * p.max_pages;
-      TokMap map{p.prompt_len, p.n_samples, 0, nullptr};
-      bf16::embed(p.h, gprompts + (size_t)p0 * p.prompt_len, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+      TokMap map{S, p.n_samples, R, nullptr};
+      bf16::embed(p.h, gprompts + (size_t)p0 * S, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
       bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
-      prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, p.prompt_len,
-                     map, chunk_pool, 1, st);
+      prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, S, map, chunk_pool, 1,
+                     st);
       if (ragged)
         launch_gather_last_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, D.d, np, p.n_samples, p.prompt_len,
-                                glens + p0, st);
+                                glens + p0, R, st);
       else
         launch_gather_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, np * p.n_samples, D.d, p.n_samples,
                            p.prompt_len, p.prompt_len - 1, 0, st);

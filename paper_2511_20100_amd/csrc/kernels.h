@@ -26,16 +26,22 @@ void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, 
 // raises bit 4 of *err_flag).  Row b = p n_samples + s: table entry j is shared page p nf_max + j for
 // j < lens[p] / 16, else private page shared_total + b max_pages + j; row_pos[b] = lens[p] - 1;
 // done[b] = 0; out_lens[b] = max_new.  prompt_ids [n_prompts, Lmax] = prompts with the padding set to 0.
-void launch_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, const int* prompts,
-                         const int* lens, int n_prompts, int n_samples, int Lmax, int max_pages, int nf_max,
-                         int shared_total, int max_new, int* err_flag, hipStream_t st);
+// reuse_len > 0 (a multiple of 16): the first reuse_len positions of every prompt keep the cached keys and values
+// that the previous call left in the workspace.  That needs, per prompt: the same first reuse_len ids as the
+// previous call's (compared with prompt_ids before it is overwritten), a previous length of at least reuse_len
+// (row_pos before it is overwritten) and a new length above reuse_len; a violation raises bit 16 of *err_flag.
+// suffix_ids [n_prompts, Lmax - reuse_len] = the ids from position reuse_len on (what is left to prefill).
+void launch_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, int* suffix_ids,
+                         const int* prompts, const int* lens, int n_prompts, int n_samples, int Lmax, int max_pages,
+                         int nf_max, int shared_total, int max_new, int reuse_len, int* err_flag, hipStream_t st);
 // For every row b with b % n_samples != 0 whose prompt length is not a multiple of the page size: the page
 // that holds the prompt's last tokens := copy of that page of row b - b % n_samples, in every (layer, K/V).
 void launch_fork_tail_pages_ragged(KvPool pool, int n_layers, int rows, int n_samples, const int* lens, int Lmax,
                                    int elem_bytes, hipStream_t st);
-// dst[p n_samples + s, :] = src[p Lmax + lens[p] - 1, :] for p < n_prompts, s < n_samples.
+// dst[p n_samples + s, :] = src[p (Lmax - pos_base) + lens[p] - 1 - pos_base, :] for p < n_prompts, s < n_samples:
+// the hidden row of a prompt's last token when src holds the positions pos_base .. Lmax - 1 of every prompt.
 void launch_gather_last_rows(float* dst, const float* src, int d, int n_prompts, int n_samples, int Lmax,
-                             const int* lens, hipStream_t st);
+                             const int* lens, int pos_base, hipStream_t st);
 
 // Action-level scoring.  vseq [n_states K, A + 1]: row n K + k = last token of state n, then the
 // tokens of candidate k, then zeros; prefix [n_states, P - 1]: the states without their last token.
@@ -48,12 +54,12 @@ void launch_build_action_seqs(int* vseq, int* prefix, const int* states, const i
 void launch_action_reduce(float* token_lp, const int* action_len, int n_states, int K, int A, int normalize,
                           float* out_action, float* out_policy, hipStream_t st);
 
-// Clipped PPO surrogate over n samples (mask may be NULL); out = {loss, clip fraction, approx KL, count} as
-// doubles; workspace of ppo_workspace_bytes() bytes holds the per-workgroup partial sums.
 // probes.hip: a plain streaming read of `bytes` (a multiple of 16 KiB is read completely) and a register-only
 // loop of matrix instructions (returns the flops the launch performs; out holds workgroups * 256 floats)
 void launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 double launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t st);
+// Clipped PPO surrogate over n samples (mask may be NULL); out = {loss, clip fraction, approx KL, count} as
+// doubles; workspace of ppo_workspace_bytes() bytes holds the per-workgroup partial sums.
 size_t ppo_workspace_bytes();
 // Device address of the current GPU's file-scope scratch array of ppo_workspace_bytes() bytes (MTMC_OK or an error).
 int ppo_static_scratch(void** out);

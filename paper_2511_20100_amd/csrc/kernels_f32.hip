@@ -85,13 +85,16 @@ void launch_fork_tail_pages(KvPool pool, int n_layers, int rows, int n_samples, 
 // =====================================================================================
 __device__ __forceinline__ int clamp_len(int len, int Lmax) { return min(max(len, 1), Lmax); }
 
-__global__ void k_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids,
+__global__ void k_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, int* suffix_ids,
                                const int* prompts, const int* lens, int n_samples, int Lmax, int max_pages,
-                               int nf_max, int shared_total, int max_new, int* err_flag) {
+                               int nf_max, int shared_total, int max_new, int reuse_len, int* err_flag) {
   const int b = blockIdx.x, p = b / n_samples;
   const int raw = lens[p], len = clamp_len(raw, Lmax);
   if (threadIdx.x == 0) {
     if (raw != len) atomicOr(err_flag, 4);
+    // cached prefix: the previous call's prompt (row_pos still holds its last position) must cover it, and
+    // the new prompt must reach beyond it
+    if (reuse_len > 0 && (row_pos[b] + 1 < reuse_len || len <= reuse_len)) atomicOr(err_flag, 16);
     row_pos[b] = len - 1;
     done[b] = 0;
     out_lens[b] = max_new;
@@ -99,16 +102,23 @@ __global__ void k_ragged_setup(int* table, int* row_pos, int* done, int* out_len
   const int n_full = len / kPageTokens;
   for (int j = threadIdx.x; j < max_pages; j += blockDim.x)
     table[(size_t)b * max_pages + j] = (j < n_full) ? p * nf_max + j : shared_total + b * max_pages + j;
-  if (b % n_samples == 0)
-    for (int j = threadIdx.x; j < Lmax; j += blockDim.x)
-      prompt_ids[(size_t)p * Lmax + j] = (j < len) ? prompts[(size_t)p * Lmax + j] : 0;
+  if (b % n_samples == 0) {
+    bool changed = false;
+    for (int j = threadIdx.x; j < Lmax; j += blockDim.x) {
+      const int id = (j < len) ? prompts[(size_t)p * Lmax + j] : 0;
+      if (j < reuse_len) changed |= prompt_ids[(size_t)p * Lmax + j] != id;
+      else suffix_ids[(size_t)p * (Lmax - reuse_len) + (j - reuse_len)] = id;
+      prompt_ids[(size_t)p * Lmax + j] = id;
+    }
+    if (changed) atomicOr(err_flag, 16);
+  }
 }
-void launch_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, const int* prompts,
-                         const int* lens, int n_prompts, int n_samples, int Lmax, int max_pages, int nf_max,
-                         int shared_total, int max_new, int* err_flag, hipStream_t st) {
-  k_ragged_setup<<<n_prompts * n_samples, 256, 0, st>>>(table, row_pos, done, out_lens, prompt_ids, prompts, lens,
-                                                        n_samples, Lmax, max_pages, nf_max, shared_total, max_new,
-                                                        err_flag);
+void launch_ragged_setup(int* table, int* row_pos, int* done, int* out_lens, int* prompt_ids, int* suffix_ids,
+                         const int* prompts, const int* lens, int n_prompts, int n_samples, int Lmax, int max_pages,
+                         int nf_max, int shared_total, int max_new, int reuse_len, int* err_flag, hipStream_t st) {
+  k_ragged_setup<<<n_prompts * n_samples, 256, 0, st>>>(table, row_pos, done, out_lens, prompt_ids, suffix_ids,
+                                                        prompts, lens, n_samples, Lmax, max_pages, nf_max,
+                                                        shared_total, max_new, reuse_len, err_flag);
 }
 
 __global__ void k_fork_tail_pages_ragged(KvPool pool, int n_samples, const int* lens, int Lmax, int words_per_page) {
@@ -130,15 +140,16 @@ void launch_fork_tail_pages_ragged(KvPool pool, int n_layers, int rows, int n_sa
   k_fork_tail_pages_ragged<<<dim3(rows, n_layers * 2), 256, 0, st>>>(pool, n_samples, lens, Lmax, words);
 }
 
-__global__ void k_gather_last_rows(float* dst, const float* src, int d, int n_samples, int Lmax, const int* lens) {
+__global__ void k_gather_last_rows(float* dst, const float* src, int d, int n_samples, int Lmax, const int* lens,
+                                   int pos_base) {
   const int r = blockIdx.x, p = r / n_samples;
-  const size_t s = (size_t)p * Lmax + clamp_len(lens[p], Lmax) - 1;
+  const size_t s = (size_t)p * (Lmax - pos_base) + max(clamp_len(lens[p], Lmax) - 1 - pos_base, 0);
   for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(size_t)r * d + c] = src[s * d + c];
 }
 void launch_gather_last_rows(float* dst, const float* src, int d, int n_prompts, int n_samples, int Lmax,
-                             const int* lens, hipStream_t st) {
+                             const int* lens, int pos_base, hipStream_t st) {
   if (n_prompts == 0) return;
-  k_gather_last_rows<<<n_prompts * n_samples, 256, 0, st>>>(dst, src, d, n_samples, Lmax, lens);
+  k_gather_last_rows<<<n_prompts * n_samples, 256, 0, st>>>(dst, src, d, n_samples, Lmax, lens, pos_base);
 }
 
 // =====================================================================================

@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtmc.so
 
 MTMC_OK, MTMC_EINVAL, MTMC_ENOMEM, MTMC_EHIP, MTMC_EDATA = 0, -1, -2, -3, -4
 MTMC_F32, MTMC_BF16 = 0, 1
-MTMC_DATA_TOKEN_ID, MTMC_DATA_WEIGHT, MTMC_DATA_LENGTH, MTMC_DATA_FP16_RANGE = 1, 2, 4, 8
+MTMC_DATA_TOKEN_ID, MTMC_DATA_WEIGHT, MTMC_DATA_LENGTH, MTMC_DATA_FP16_RANGE, MTMC_DATA_PREFIX = 1, 2, 4, 8, 16
 
 
 class MtmcError(RuntimeError):
@@ -57,6 +57,9 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_rollout_ragged_workspace_bytes.restype = sz
     lib.mtmc_rollout_ragged.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, u64, u32, i32, vp, vp, vp, vp, sz, vp]
     lib.mtmc_rollout_ragged.restype = ctypes.c_int
+    lib.mtmc_rollout_ragged_cached.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, u64, u32, i32, i32, vp, vp, vp, vp,
+                                               sz, vp]
+    lib.mtmc_rollout_ragged_cached.restype = ctypes.c_int
     lib.mtmc_score_workspace_bytes.argtypes = [vp, i32, i32]
     lib.mtmc_score_workspace_bytes.restype = sz
     lib.mtmc_score.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -99,7 +102,7 @@ EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mt
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
            "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
            "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss", "mtmc_data_error_string",
-           "mtmc_ppo_clip_loss_static", "mtmc_read_probe", "mtmc_mfma_probe")
+           "mtmc_ppo_clip_loss_static", "mtmc_read_probe", "mtmc_mfma_probe", "mtmc_rollout_ragged_cached")
 
 
 def mtmc_last_error() -> str:
@@ -181,9 +184,11 @@ def mtmc_rollout_ragged_workspace_bytes(handle: int, n_prompts: int, max_prompt_
 
 def mtmc_rollout_ragged(handle: int, prompts: torch.Tensor, prompt_lens: torch.Tensor, n_samples: int, max_new: int,
                         temperature: float, seed: int, *, stop_id: int = -1, seq_offset: int = 0,
-                        workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+                        workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                        reuse_len: Optional[int] = None):
     """prompts int32 CUDA [n_prompts, max_prompt_len] (right-padded), prompt_lens int32 CUDA [n_prompts].
-    Returns (ids [B, max_new] int32, logprobs [B, max_new] float32, lens [B] int32), B = n_prompts * n_samples."""
+    Returns (ids [B, max_new] int32, logprobs [B, max_new] float32, lens [B] int32), B = n_prompts * n_samples.
+    With reuse_len (not None) the call is mtmc_rollout_ragged_cached on the given workspace."""
     for t in (prompts, prompt_lens):
         assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
     n_prompts, Lmax = prompts.shape
@@ -195,10 +200,25 @@ def mtmc_rollout_ragged(handle: int, prompts: torch.Tensor, prompt_lens: torch.T
     ids = torch.empty((B, max_new), dtype=torch.int32, device=prompts.device)
     lp = torch.empty((B, max_new), dtype=torch.float32, device=prompts.device)
     lens = torch.empty((B,), dtype=torch.int32, device=prompts.device)
-    _check(_lib.mtmc_rollout_ragged(handle, prompts.data_ptr(), prompt_lens.data_ptr(), n_prompts, Lmax, n_samples,
-                                    max_new, temperature, seed, seq_offset, stop_id, ids.data_ptr(), lp.data_ptr(),
-                                    lens.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    if reuse_len is None:
+        _check(_lib.mtmc_rollout_ragged(handle, prompts.data_ptr(), prompt_lens.data_ptr(), n_prompts, Lmax, n_samples,
+                                        max_new, temperature, seed, seq_offset, stop_id, ids.data_ptr(), lp.data_ptr(),
+                                        lens.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    else:
+        _check(_lib.mtmc_rollout_ragged_cached(handle, prompts.data_ptr(), prompt_lens.data_ptr(), n_prompts, Lmax,
+                                               n_samples, max_new, temperature, seed, seq_offset, stop_id,
+                                               int(reuse_len), ids.data_ptr(), lp.data_ptr(), lens.data_ptr(),
+                                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return ids, lp, lens
+
+
+def mtmc_rollout_ragged_cached(handle: int, prompts: torch.Tensor, prompt_lens: torch.Tensor, n_samples: int,
+                               max_new: int, temperature: float, seed: int, reuse_len: int, workspace: torch.Tensor,
+                               *, stop_id: int = -1, seq_offset: int = 0,
+                               stream: Optional[torch.cuda.Stream] = None):
+    """mtmc_rollout_ragged that keeps the first reuse_len cached positions of every prompt in `workspace`."""
+    return mtmc_rollout_ragged(handle, prompts, prompt_lens, n_samples, max_new, temperature, seed, stop_id=stop_id,
+                               seq_offset=seq_offset, workspace=workspace, stream=stream, reuse_len=reuse_len)
 
 
 def mtmc_score_workspace_bytes(handle: int, n_seqs: int, seq_len: int) -> int:

@@ -138,3 +138,113 @@ def test_bad_lengths_and_stop_ids_are_reported(lib):
             lib.mtmc_rollout_ragged_workspace_bytes(handle, 2, 8, 2, 60)
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+# ---------------------------------------------------------------- cached prompt prefix across calls
+def grown_prompts(prompts, lens, extra, Lmax, vocab, seed):
+    """State of the next optimisation step: every prompt keeps its tokens and gains extra[p] new ones."""
+    new = np.zeros((prompts.shape[0], Lmax), dtype=np.int32)
+    more = inputs.make_token_ids((prompts.shape[0], Lmax), vocab, seed)
+    new_lens = (lens + extra).astype(np.int32)
+    for p in range(prompts.shape[0]):
+        new[p, :lens[p]] = prompts[p, :lens[p]]
+        new[p, lens[p]:new_lens[p]] = more[p, lens[p]:new_lens[p]]
+    return new, new_lens
+
+
+def test_fp32_cached_prefix_equals_the_oracle_on_the_whole_prompt(lib):
+    """Two optimisation steps: the second call's prompts extend the first call's; it keeps the cached keys and
+    values of the first 32 positions and must give exactly what the oracle gives on the whole new prompts."""
+    import torch
+    cfg = inputs.TINY
+    w = inputs.make_weights(cfg, seed=0, gain_std=0.1)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        Lmax, n_new = 64, 10
+        lens = np.array([40, 33, 47, 36], dtype=np.int32)
+        prompts = np.zeros((4, Lmax), dtype=np.int32)
+        prompts[:, :48] = inputs.make_prompts(4, 48, cfg.vocab, seed=2)
+        dev = lambda x: torch.from_numpy(x).cuda()
+        ws = torch.empty(lib.mtmc_rollout_ragged_workspace_bytes(handle, 4, Lmax, 2, n_new), dtype=torch.uint8, device="cuda")
+        model = oracle_model(w, 128)
+        ids, lp, n = lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), 2, n_new, 1.0, 1, workspace=ws)
+        ref = oracle.rollout_ragged(model, prompts, lens, 2, n_new, 1.0, seed=1)
+        assert np.array_equal(ids.cpu().numpy(), ref[0])
+        new, new_lens = grown_prompts(prompts, lens, np.array([9, 20, 1, 28]), Lmax, cfg.vocab, seed=7)
+        ids2, lp2, n2 = lib.mtmc_rollout_ragged_cached(handle, dev(new), dev(new_lens), 2, n_new, 1.0, 5, 32, ws)
+        lib.mtmc_poll_errors(handle)
+        ref2 = oracle.rollout_ragged(model, new, new_lens, 2, n_new, 1.0, seed=5)
+        print("min sampling margin of the oracle:", ref2[3].min())
+        assert np.array_equal(ids2.cpu().numpy(), ref2[0]) and np.abs(lp2.cpu().numpy() - ref2[1]).max() <= 1e-4
+        # a third step on top of the second, keeping 48 positions now
+        new3, lens3 = grown_prompts(new, new_lens, np.array([5, 3, 10, 0]), Lmax, cfg.vocab, seed=8)
+        ids3, lp3, _ = lib.mtmc_rollout_ragged_cached(handle, dev(new3), dev(lens3), 2, n_new, 1.0, 6, 48, ws)
+        lib.mtmc_poll_errors(handle)
+        ref3 = oracle.rollout_ragged(model, new3, lens3, 2, n_new, 1.0, seed=6)
+        assert np.array_equal(ids3.cpu().numpy(), ref3[0]) and np.abs(lp3.cpu().numpy() - ref3[1]).max() <= 1e-4
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_bf16_cached_prefix_equals_a_fresh_call(lib):
+    """MFMA path, 5 prompts x 8 samples: the call that keeps 3 cached pages gives what a fresh call on the same
+    prompts gives (bit for bit: every token's arithmetic is the same, only the cached positions are skipped),
+    with a stop token, and one row is replayed on the oracle."""
+    import torch
+    cfg = GQA6
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 256), w.blob())
+    try:
+        Lmax, n_new, ns = 120, 12, 8
+        lens = np.array([50, 64, 97, 49, 80], dtype=np.int32)
+        prompts = np.zeros((5, Lmax), dtype=np.int32)
+        prompts[:, :100] = inputs.make_prompts(5, 100, cfg.vocab, seed=2)
+        dev = lambda x: torch.from_numpy(x).cuda()
+        nbytes = lib.mtmc_rollout_ragged_workspace_bytes(handle, 5, Lmax, ns, n_new)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        first = lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), ns, n_new, 1.0, 1, workspace=ws)
+        new, new_lens = grown_prompts(prompts, lens, np.array([30, 11, 23, 1, 40]), Lmax, cfg.vocab, seed=7)
+        stop = 5
+        cached = lib.mtmc_rollout_ragged_cached(handle, dev(new), dev(new_lens), ns, n_new, 1.0, 9, 48, ws, stop_id=stop)
+        lib.mtmc_poll_errors(handle)
+        fresh = lib.mtmc_rollout_ragged(handle, dev(new), dev(new_lens), ns, n_new, 1.0, 9, stop_id=stop,
+                                        workspace=torch.empty(nbytes, dtype=torch.uint8, device="cuda"))
+        lib.mtmc_poll_errors(handle)
+        for a, b in zip(cached, fresh):
+            assert torch.equal(a, b)
+        rep = check_ragged_by_replay(handle, w, new, new_lens, ns, n_new, 1.0, 9, stop_id=stop, max_positions=256,
+                                     label="cached-prefix")
+        assert np.array_equal(rep["ids"], cached[0].cpu().numpy())
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_cached_prefix_misuse_is_reported(lib):
+    import torch
+    cfg = inputs.TINY
+    w = inputs.make_weights(cfg, seed=0)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        dev = lambda x: torch.from_numpy(x).cuda()
+        prompts = inputs.make_prompts(2, 48, cfg.vocab, seed=2)
+        lens = np.array([40, 48], dtype=np.int32)
+        ws = torch.empty(lib.mtmc_rollout_ragged_workspace_bytes(handle, 2, 48, 2, 4), dtype=torch.uint8, device="cuda")
+        with pytest.raises(lib.MtmcError, match="previous mtmc_rollout_ragged"):      # nothing cached yet
+            lib.mtmc_rollout_ragged_cached(handle, dev(prompts), dev(lens), 2, 4, 1.0, 1, 16, ws)
+        lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), 2, 4, 1.0, 1, workspace=ws)
+        with pytest.raises(lib.MtmcError, match="multiple of 16"):
+            lib.mtmc_rollout_ragged_cached(handle, dev(prompts), dev(lens), 2, 4, 1.0, 1, 20, ws)
+        with pytest.raises(lib.MtmcError, match="previous mtmc_rollout_ragged"):      # another shape
+            lib.mtmc_rollout_ragged_cached(handle, dev(prompts), dev(lens), 2, 5, 1.0, 1, 16, ws)
+        lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), 2, 4, 1.0, 1, workspace=ws)
+        changed = prompts.copy(); changed[1, 7] = (changed[1, 7] + 1) % cfg.vocab      # inside the kept prefix
+        lib.mtmc_rollout_ragged_cached(handle, dev(changed), dev(lens), 2, 4, 1.0, 1, 16, ws)
+        with pytest.raises(lib.MtmcError, match="cached prompt prefix") as e:
+            lib.mtmc_poll_errors(handle)
+        assert e.value.code == lib.MTMC_EDATA
+        lib.mtmc_rollout_ragged(handle, dev(prompts), dev(np.array([20, 48], dtype=np.int32)), 2, 4, 1.0, 1, workspace=ws)
+        lib.mtmc_rollout_ragged_cached(handle, dev(prompts), dev(lens), 2, 4, 1.0, 1, 32, ws)   # prompt 0 was 20 long
+        with pytest.raises(lib.MtmcError, match="cached prompt prefix"):
+            lib.mtmc_poll_errors(handle)
+    finally:
+        lib.mtmc_weights_destroy(handle)
