@@ -156,6 +156,88 @@ def attainable_rates(torch, mtmc, dev):
     return read_gbs, flops / (e[0].elapsed_time(e[1]) * 1e-3) / 1e12
 
 
+def inference_legs(torch, mtmc, dev, handle, weights, cfg, prompts, n_samples, max_new, progress):
+    """Beside the step, not part of `value`: what the policy's use at inference time costs (prompts that end at a
+    terminal token, and a state that extends the previous step's).
+    stop token: the same batch with one token made likely (its LM-head row scaled by 8: with the synthetic,
+    nearly uniform policy no token would ever come up), so that rows end after tens of steps; the call that looks
+    at the stop flags (rows give up their places, the call ends with the last row) against the one that does not.
+    cached prefix: 32 new tokens on the same prompts, evaluating them whole against keeping all but their last
+    64 positions from the previous call."""
+    stream = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    n_prompts, prompt_len = prompts.shape
+    lens = torch.full((n_prompts,), prompt_len, dtype=torch.int32, device=dev)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ev[0].record(stream)
+        out = fn()
+        ev[1].record(stream)
+        ev[1].synchronize()
+        return out, ev[0].elapsed_time(ev[1])
+
+    out = {}
+    # a long state (as much as the handle's positions allow) and a short action
+    short_new = 32
+    long_len = (prompt_len + max_new - short_new) // 32 * 32
+    keep = long_len - 64
+    if keep > 0:
+        long_prompts = torch.from_numpy(inputs.make_prompts(n_prompts, long_len, cfg.vocab, seed=6)).to(dev)
+        long_lens = torch.full((n_prompts,), long_len, dtype=torch.int32, device=dev)
+        ws = torch.empty(mtmc.mtmc_rollout_ragged_workspace_bytes(handle, n_prompts, long_len, n_samples, short_new),
+                         dtype=torch.uint8, device=dev)
+        whole, ms_whole = timed(lambda: mtmc.mtmc_rollout_ragged(handle, long_prompts, long_lens, n_samples, short_new,
+                                                                 1.0, 1, workspace=ws))
+        kept, ms_kept = timed(lambda: mtmc.mtmc_rollout_ragged_cached(handle, long_prompts, long_lens, n_samples,
+                                                                      short_new, 1.0, 1, keep, ws))
+        mtmc.mtmc_poll_errors(handle)
+        same_ids = (whole[0] == kept[0]).all(dim=1)
+        out["cached_prefix"] = {"workload": f"{n_prompts} prompts of {long_len} tokens x {n_samples} samples, {short_new} "
+                                            f"new tokens; {keep} positions of every prompt kept from the previous call",
+                                "ms_whole_prompts": ms_whole, "ms_cached_prefix": ms_kept,
+                                "rows_with_the_same_ids": int(same_ids.sum().item()), "rows": int(same_ids.numel()),
+                                "max_logprob_difference_on_those_rows":
+                                    float((whole[1][same_ids] - kept[1][same_ids]).abs().max().item()) if same_ids.any() else None,
+                                "note": "512 tokens and 11 776 tokens run different matrix kernels (same sums, another "
+                                        "rounding order): the two calls agree to that rounding, not bit for bit"}
+        progress(f"cached prefix: {ms_kept:.1f} ms against {ms_whole:.1f} ms")
+        del ws, long_prompts
+    stop = 7
+    saved = weights.tensors["lm_head"]
+    scaled = saved.copy()
+    scaled[stop] = inputs.f32_to_bf16_bits(8.0 * inputs.bf16_bits_to_f32(saved[stop]))
+    weights.tensors["lm_head"] = scaled
+    try:
+        blob = torch.from_numpy(weights.blob())
+    finally:
+        weights.tensors["lm_head"] = saved
+    h2 = mtmc.mtmc_weights_create(mtmc.make_config(cfg, prompt_len + max_new), blob)
+    del blob, scaled
+    try:
+        ws = torch.empty(mtmc.mtmc_rollout_ragged_workspace_bytes(h2, n_prompts, prompt_len, n_samples, max_new),
+                         dtype=torch.uint8, device=dev)
+        run = lambda: mtmc.mtmc_rollout_ragged(h2, prompts, lens, n_samples, max_new, 1.0, 1, stop_id=stop, workspace=ws)
+        (ids, lp, n), ms_poll = timed(run)
+        mtmc.mtmc_set_option(h2, mtmc.MTMC_OPT_STOP_POLL_STEPS, 0)
+        (ids0, lp0, n0), ms_static = timed(run)
+        mtmc.mtmc_poll_errors(h2)
+        toks = int(n.sum().item())
+        out["stop_token"] = {"workload": f"{n_prompts} x {n_samples} rows, prompt {prompt_len}, up to {max_new} new tokens, "
+                                         f"stop token with its LM-head row scaled by 8",
+                             "tokens_generated": toks, "longest_row": int(n.max().item()),
+                             "median_row": float(n.float().median().item()),
+                             "ms_rows_give_up_places": ms_poll, "ms_rows_keep_places": ms_static,
+                             "tokens_per_s_rows_give_up_places": toks / (ms_poll * 1e-3),
+                             "tokens_per_s_rows_keep_places": int(n0.sum().item()) / (ms_static * 1e-3)}
+        progress(f"stop token: {toks} tokens, {ms_poll:.1f} ms against {ms_static:.1f} ms")
+        del ws
+    finally:
+        mtmc.mtmc_weights_destroy(h2)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +250,8 @@ def main() -> int:
     ap.add_argument("--no-rollout", action="store_true",
                     help="time the scoring pass alone, on sequences whose new tokens are random ids (for counter runs)")
     ap.add_argument("--no-actions", action="store_true", help="skip the action-scoring leg (reported beside the step)")
+    ap.add_argument("--no-inference-legs", action="store_true",
+                    help="skip the stop-token and cached-prefix legs (reported beside the step, 1p5b workload only)")
     ap.add_argument("--no-graph", action="store_true", help="launch decode steps directly (for counter runs)")
     ap.add_argument("--progress", action="store_true", help="print a line to stderr as each stage ends")
     ap.add_argument("--no-kernel-timer", action="store_true", help="do not bracket the gate/up launches with events")
@@ -345,6 +429,8 @@ def main() -> int:
                                                 f"1..{A} tokens per action", "ms": a_ms,
                                     "actions_per_s": n_prompts * K / (a_ms * 1e-3)}
         del ws_a
+    if args.workload == "1p5b" and not args.no_inference_legs and not args.no_rollout:
+        result["inference"] = inference_legs(torch, mtmc, dev, handle, weights, cfg, prompts, n_samples, max_new, progress)
     if not args.no_cpu_baseline:
         progress("timing the oracle on the host cores")
         result["cpu_baseline"] = cpu_baseline(weights, cfg, prompts_np, seq_len, score_only=args.no_rollout)

@@ -130,7 +130,8 @@ int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompt
  * differ only where two candidates are that close).  With stop_id >= 0 a sequence ends with the first sampled stop_id: that token and
  * its log-probability are reported, every later slot of the row holds stop_id with log-probability
  * 0, and out_lens[b] = number of tokens generated including the stop token (max_new if none).
- * Finished sequences keep their slot in the batch: the call costs the same as without a stop token.
+ * MTMC_BF16: finished sequences give up their place in the batch and the call ends when all have
+ * finished (MTMC_OPT_STOP_POLL_STEPS); MTMC_F32: they keep their place.
  *
  * prompts      device int32 [n_prompts, max_prompt_len], right-padded
  * prompt_lens  device int32 [n_prompts], values in [1, max_prompt_len]; a value outside is clamped
@@ -154,7 +155,9 @@ int mtmc_rollout_ragged(const mtmc_weights* w, const int32_t* prompts, const int
  * history).  The workspace of a ragged call still holds the keys and values of its prompts; when the first
  * reuse_len positions of EVERY prompt are unchanged since the previous mtmc_rollout_ragged[_cached] call on the
  * same workspace, only the positions from reuse_len on are evaluated again.  Results are those of
- * mtmc_rollout_ragged on the same arguments.
+ * mtmc_rollout_ragged on the same arguments: bit for bit when both calls run the same matrix kernels, and
+ * to the rounding order of the fp32 sums (about 1e-3 in a log-probability) when the number of tokens left
+ * to evaluate falls under the size from which the large-batch kernel is used (MTMC_OPT_GEMM_LDS_MIN_BLOCKS).
  *   - reuse_len: a multiple of 16 (whole cache pages), below max_prompt_len; 0 = nothing is kept.
  *   - the previous call on `workspace` must have had the same n_prompts, max_prompt_len, n_samples and max_new
  *     (the cache layout follows from them), else MTMC_EINVAL; the caller must not have written to the
@@ -290,9 +293,21 @@ const char* mtmc_data_error_string(int bits);
  *   whose output has at least this many 256 x 256 blocks run in the LDS-staged kernel, smaller
  *   ones in the direct 128 x 128 kernel.  Both sum over K in the same order; results agree to
  *   the fp32 rounding inside the matrix instruction.
+ *   MTMC_OPT_STOP_POLL_STEPS (default 32, 0 = off): MTMC_BF16 rollouts with a stop token look at the rows'
+ *   stop flags every this many decode steps.  The look itself is queued on the stream; the host reads it one
+ *   period later (so the GPU never waits for the host), ends the call once every row has stopped and packs
+ *   the rows still running into fewer 16-row tiles when that frees a tile, so that a batch costs less as
+ *   its rows finish.  With it the call blocks the calling thread on the stream (it returns when at most
+ *   two periods of work are still queued) and calls with a stop token on one weights handle take turns;
+ *   with 0, or when `stream` is being captured, the call only enqueues, as mtmc_rollout does, every row keeps
+ *   its place, and the call costs what it costs without a stop token.  Packing changes the tiling, hence
+ *   the order of the fp32 sums, of the steps after it: log-probabilities then agree with the unpacked call's
+ *   to about 1e-3 (an id can differ where two candidates are that close), and with the definition as
+ *   closely as before.
  */
 #define MTMC_OPT_HIP_GRAPH 1
 #define MTMC_OPT_GEMM_LDS_MIN_BLOCKS 2
+#define MTMC_OPT_STOP_POLL_STEPS 3
 int mtmc_set_option(mtmc_weights* w, int option, int value);
 
 /*

@@ -20,6 +20,10 @@ struct SampleCtl {
   int stop_id;
   int* done;
   int* out_lens;
+  // Rows packed into fewer slots (a batch whose finished rows gave up their places): slot m of the decode
+  // kernels holds row slot_row[m] of the call, or nobody (-1).  NULL: slot m is row m.  Outputs, stop flags, the
+  // fed-back ids (cur_ids) and the random-number counters go by row.
+  const int* slot_row;
 };
 
 struct LargeArgs {
@@ -114,6 +118,18 @@ struct AttnDecArgs {
   int* err_flag;         // raised when q, k, v or the output does not fit fp16
 };
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st);
+
+// ---- packing the live rows of a batch with a stop token into the leading slots ------------------
+// live[0] = number of rows whose stop flag is clear.
+void count_live(const int* done, int B, int* live, hipStream_t st);
+// slot_row[0 .. slots) = the rows with a clear stop flag in ascending order, then -1; the page-table rows and
+// position bases of those rows gathered by slot (an empty slot gets page 0 everywhere and position base -1,
+// which the attention kernel takes as "nobody here").
+void compact_rows(const int* done, int B, int slots, int* slot_row, const int* page_table, const int* row_pos,
+                  int max_pages, int* page_table_c, int* row_pos_c, hipStream_t st);
+// The residual, its normalised fp16 operand and the sums of squares of every slot's current token
+// (cur_ids by row; token 0 for an empty slot), in the layout of `slots` rows.
+void embed_slots(const int* slot_row, const int* cur_ids, int slots, const EmbedNextArgs& emb, hipStream_t st);
 
 // ---- weight re-tiling (once, at load) ------------------------------------------------------
 // dst (tiled fp16, n_tiles x k_tiles blocks) <- src row-major [N, K] bf16; rows/cols past N/K are

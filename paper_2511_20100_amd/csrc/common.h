@@ -93,6 +93,7 @@ struct mtmc_weights {
   int d_ffn_pad;        // F rounded up to the K-tile of the bf16 kernels (== F for fp32)
   int opt_hip_graph;    // replay decode steps as a captured HIP graph (default 1)
   int opt_lds_min_blocks;  // output blocks (256 x 256) from which large GEMMs use the LDS-staged kernel
+  int opt_stop_poll;       // decode steps between two looks at the stop flags of a rollout with a stop token (0: never)
   mtmc::GraphCache* graphs;  // instantiated decode-step graphs, keyed by workspace and shape
   std::mutex* ragged_mu;     // guards ragged_calls
   std::vector<mtmc::RaggedCallRecord> ragged_calls;  // at most 16, oldest dropped first

@@ -380,13 +380,15 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this pass's part of the workgroup's vocabulary slice
     const SampleCtl ctl = *a.ctl;
     const int step = *a.d_step;
+    // the random numbers of a row follow the row, whatever slot it sits in (an empty slot draws row 0's: unused)
+    const int smp_row = (ctl.slot_row && m < a.M) ? max(ctl.slot_row[m], 0) : m;
 #pragma unroll
     for (int nb = 0; nb < NBP; ++nb) {
       if (nbase + nb >= a.n_tiles) continue;
       const int v0 = (nbase + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
       uint4 rb = make_uint4(0, 0, 0, 0);
       if (!ctl.greedy)
-        rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + m, 0u), ctl.key0,
+        rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + smp_row, 0u), ctl.key0,
                            ctl.key1);
       const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
 #pragma unroll
@@ -637,25 +639,30 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
     }
     const SampleCtl ctl = *ctlp;
     const int step = *d_step;
+    const int row = ctl.slot_row ? ctl.slot_row[b] : b;   // b is the slot
     int tok = bi;
     float lp = bz - (lse.m + logf(lse.s));
-    if ((unsigned)tok >= (unsigned)emb.vocab) {  // no logit of the row compared greater than -inf: every one is NaN
-      tok = 0;
-      atomicOr(emb.err_flag, kErrFp16Range);
-    }
-    if (ctl.done) {
-      if (ctl.done[b]) {
-        tok = ctl.stop_id;
-        lp = 0.f;
-      } else if (tok == ctl.stop_id) {
-        ctl.done[b] = 1;
-        ctl.out_lens[b] = step + 1;
+    if (row < 0) {
+      tok = 0;  // nobody in this slot: nothing is reported, the slot keeps computing on token 0
+    } else {
+      if ((unsigned)tok >= (unsigned)emb.vocab) {  // no logit of the row compared greater than -inf: every one is NaN
+        tok = 0;
+        atomicOr(emb.err_flag, kErrFp16Range);
       }
+      if (ctl.done) {
+        if (ctl.done[row]) {
+          tok = ctl.stop_id;
+          lp = 0.f;
+        } else if (tok == ctl.stop_id) {
+          ctl.done[row] = 1;
+          ctl.out_lens[row] = step + 1;
+        }
+      }
+      cur_ids[row] = tok;
+      ctl.out_ids[(size_t)row * ctl.max_new + step] = tok;
+      ctl.out_logprobs[(size_t)row * ctl.max_new + step] = lp;
     }
-    cur_ids[b] = tok;
     s_tok = tok;
-    ctl.out_ids[(size_t)b * ctl.max_new + step] = tok;
-    ctl.out_logprobs[(size_t)b * ctl.max_new + step] = lp;
     // the last row to get here advances the step counter: by then every row has read it (d_step[1] counts
     // arrivals and is left at zero for the next launch)
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
@@ -828,7 +835,8 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   // ---- position-dependent part
   const int pos = pos0 + step;
   const int n_ctx_pages = pos / kPageTokens + 1;
-  const int p_hi = min(n_ctx_pages, p_end);
+  // a negative position base marks a slot that holds no sequence (rows packed into fewer slots): nothing to attend
+  const int p_hi = pos0 < 0 ? p_lo : min(n_ctx_pages, p_end);
   if (p_lo >= p_hi) {
     // this chunk lies beyond the context: it contributes nothing, which its consumer learns from a zero sum;
     // the operand slice is cleared so that stale bits (possibly NaN patterns) never meet a zero weight
@@ -965,6 +973,54 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
       ml[1] = ll;
     }
   }
+}
+
+// ---------------------------------------------------------------- packing live rows into the leading slots
+__global__ void k_count_live(const int* done, int B, int* live) {
+  __shared__ float red[16];
+  float n = 0.f;
+  for (int b = threadIdx.x; b < B; b += blockDim.x) n += done[b] ? 0.f : 1.f;
+  const float tot = block_sum(n, red);
+  if (threadIdx.x == 0) live[0] = (int)tot;
+}
+void count_live(const int* done, int B, int* live, hipStream_t st) { k_count_live<<<1, 256, 0, st>>>(done, B, live); }
+
+// One workgroup; B is small (the rows of one group).  Thread 0 walks the flags in row order (a stable packing),
+// then all threads gather the page-table rows.
+__global__ __launch_bounds__(256) void k_compact_rows(const int* done, int B, int slots, int* slot_row,
+                                                      const int* page_table, const int* row_pos, int max_pages,
+                                                      int* page_table_c, int* row_pos_c) {
+  __shared__ int s_row[256];
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int b = 0; b < B && n < slots; ++b)
+      if (!done[b]) s_row[n++] = b;
+    for (; n < slots; ++n) s_row[n] = -1;
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < slots; s += blockDim.x) {
+    slot_row[s] = s_row[s];
+    row_pos_c[s] = s_row[s] >= 0 ? row_pos[s_row[s]] : -1;
+  }
+  for (int i = threadIdx.x; i < slots * max_pages; i += blockDim.x) {
+    const int s = i / max_pages, j = i - s * max_pages;
+    page_table_c[i] = s_row[s] >= 0 ? page_table[(size_t)s_row[s] * max_pages + j] : 0;
+  }
+}
+void compact_rows(const int* done, int B, int slots, int* slot_row, const int* page_table, const int* row_pos,
+                  int max_pages, int* page_table_c, int* row_pos_c, hipStream_t st) {
+  k_compact_rows<<<1, 256, 0, st>>>(done, B, slots, slot_row, page_table, row_pos, max_pages, page_table_c, row_pos_c);
+}
+
+__global__ __launch_bounds__(256) void k_embed_slots(const int* slot_row, const int* cur_ids, EmbedNextArgs emb) {
+  __shared__ float red[16];
+  const int s = blockIdx.x, row = slot_row[s];
+  int tok = row >= 0 ? cur_ids[row] : 0;
+  tok = min(max(tok, 0), emb.vocab - 1);
+  embed_row(emb, s, tok, red);
+}
+void embed_slots(const int* slot_row, const int* cur_ids, int slots, const EmbedNextArgs& emb, hipStream_t st) {
+  k_embed_slots<<<slots, 256, 0, st>>>(slot_row, cur_ids, emb);
 }
 
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {

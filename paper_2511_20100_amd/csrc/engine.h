@@ -48,6 +48,10 @@ struct RolloutPlan {
   int* row_pos;      // ragged: [B] position of a row's last prompt token
   int* done;         // ragged: [B] stop flags
   int* prompt_ids;   // ragged: [n_prompts, prompt_len] prompts with the padding cleared
+  int* slot_row;     // ragged, bf16: [bt * 16] row held by each slot once live rows are packed (-1: nobody)
+  int* page_table_c; // ragged, bf16: [B, max_pages] page-table rows by slot
+  int* row_pos_c;    // ragged, bf16: [bt * 16] position base by slot (-1: nobody)
+  int* live;         // ragged, bf16: [16] live[0] = rows that have not stopped
   int* suffix_ids;   // ragged: [n_prompts, prompt_len - reuse_len] the ids that are prefilled (all, without a cached prefix)
   void* kv;
   // activations (Tmax rows unless noted)

@@ -30,6 +30,10 @@ struct GraphCache {
   size_t events_used = 0;
   std::vector<hipEvent_t> empty_events;  // pairs recorded back to back (what a pair costs by itself)
   size_t empty_used = 0;
+  // rollouts with a stop token: where the host reads the number of live rows (pinned, two slots used in turn)
+  std::mutex poll_mu;                    // one such rollout at a time per weights handle
+  int* host_live = nullptr;
+  hipEvent_t poll_events[2] = {nullptr, nullptr};
 };
 
 // Brackets launches of one kernel class with HIP events while a decode step is launched directly.
@@ -66,6 +70,9 @@ void destroy_graph_cache(mtmc_weights* w) {
   if (w->graphs->capture_stream) (void)hipStreamDestroy(w->graphs->capture_stream);
   for (hipEvent_t e : w->graphs->events) (void)hipEventDestroy(e);
   for (hipEvent_t e : w->graphs->empty_events) (void)hipEventDestroy(e);
+  for (hipEvent_t e : w->graphs->poll_events)
+    if (e) (void)hipEventDestroy(e);
+  if (w->graphs->host_live) (void)hipHostFree(w->graphs->host_live);
   delete w->graphs;
   w->graphs = nullptr;
 }
@@ -250,47 +257,79 @@ int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob,
 // ======================================================================================
 // workspace extras
 // ======================================================================================
-void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) {
-  const Dims D = dims_of(w);
-  p.ks_qkv = choose_ksplit(D.nt_qkv, D.kt_d, p.bt);
-  p.ks_o = choose_ksplit(D.nt_d, D.kt_nq, p.bt);
-  p.ks_down = choose_ksplit(D.nt_d, D.kt_F, p.bt);
+namespace {
+// Launch shape of the decode kernels for B rows in bt 16-row tiles.
+struct DecodeTune {
+  int ks_qkv, ks_o, ks_down, down_nb, n_chunks, chunk_pages, split_at_prompt;
+};
+DecodeTune tune_decode(const Dims& D, int B, int bt, int max_pages) {
+  DecodeTune t;
+  t.ks_qkv = choose_ksplit(D.nt_qkv, D.kt_d, bt);
+  t.ks_o = choose_ksplit(D.nt_d, D.kt_nq, bt);
+  t.ks_down = choose_ksplit(D.nt_d, D.kt_F, bt);
   // A small down projection (each workgroup's share of the weights under 256 KB) is bound by fixed costs and by
   // what few wavefronts pull per CU: two row tiles and 8 wavefronts per workgroup, half the K splits (1.3-1.7 %
   // of the step at d 1536 / F 8960; at d 3584 / F 18944 the doubled activation reads cost 1.3 % instead).
-  p.down_nb = 4;
-  if (p.bt <= 4 && 4 * (D.kt_F / p.ks_down) < 256) {
-    p.down_nb = 2;
-    p.ks_down = std::max(1, std::min(256 / ((D.nt_d + 1) / 2), D.kt_F / 16));
+  t.down_nb = 4;
+  if (bt <= 4 && 4 * (D.kt_F / t.ks_down) < 256) {
+    t.down_nb = 2;
+    t.ks_down = std::max(1, std::min(256 / ((D.nt_d + 1) / 2), D.kt_F / 16));
   }
   // context split of the decode attention: for small batches up to about 128 workgroups of 8 wavefronts, and two
   // ways at 33..64 rows when that still leaves at most 256 workgroups (the O projection combines two chunks in its 12-wavefront form at little
   // extra cost; with its 8-wavefront form the split lost what the attention gained)
-  const int want = std::max(p.bt >= 3 && p.bt <= 4 && p.B * D.Hkv <= 128 ? 2 : 1, 128 / std::max(1, p.B * D.Hkv));
+  const int want = std::max(bt >= 3 && bt <= 4 && B * D.Hkv <= 128 ? 2 : 1, 128 / std::max(1, B * D.Hkv));
   // the O projection that combines the chunks holds (row tiles per workgroup) * chunks <= 8 operand sets: its
   // workgroups take one row tile up to 32 rows and two beyond
-  const int max_chunks = p.bt <= 2 ? 8 : 4;
-  p.n_chunks = std::max(1, std::min({want, (p.max_pages + 7) / 8, max_chunks}));
-  p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;
+  const int max_chunks = bt <= 2 ? 8 : 4;
+  t.n_chunks = std::max(1, std::min({want, (max_pages + 7) / 8, max_chunks}));
+  t.chunk_pages = ((max_pages + t.n_chunks - 1) / t.n_chunks + 1) / 2 * 2;
   // page ids of a chunk are staged in LDS; kMaxDecodeContext keeps the chunk count within max_chunks
-  p.chunk_pages = std::min(p.chunk_pages, 512);
-  p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
-  p.chunk_pages = ((p.max_pages + p.n_chunks - 1) / p.n_chunks + 1) / 2 * 2;  // equal chunks again after the clamp
-  p.n_chunks = (p.max_pages + p.chunk_pages - 1) / p.chunk_pages;
+  t.chunk_pages = std::min(t.chunk_pages, 512);
+  t.n_chunks = (max_pages + t.chunk_pages - 1) / t.chunk_pages;
+  t.chunk_pages = ((max_pages + t.n_chunks - 1) / t.n_chunks + 1) / 2 * 2;  // equal chunks again after the clamp
+  t.n_chunks = (max_pages + t.chunk_pages - 1) / t.chunk_pages;
   // the two-way split at 33..64 rows is made at the end of each sequence's prompt (its shared pages | its own):
   // independent of max_new and of the other sequences, and about even when prompts and generations are of a size
-  p.split_at_prompt = (p.bt >= 3 && p.bt <= 4 && p.n_chunks == 2 && p.max_pages <= 512) ? 1 : 0;
+  t.split_at_prompt = (bt >= 3 && bt <= 4 && t.n_chunks == 2 && max_pages <= 512) ? 1 : 0;
+  return t;
+}
+void apply_tune(RolloutPlan& p, const DecodeTune& t) {
+  p.ks_qkv = t.ks_qkv; p.ks_o = t.ks_o; p.ks_down = t.ks_down; p.down_nb = t.down_nb;
+  p.n_chunks = t.n_chunks; p.chunk_pages = t.chunk_pages; p.split_at_prompt = t.split_at_prompt;
+}
+}  // namespace
+
+void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) {
+  const Dims D = dims_of(w);
+  apply_tune(p, tune_decode(D, p.B, p.bt, p.max_pages));
+  // Buffers whose size follows from the launch shape are sized for every number of row tiles up to bt: a rollout
+  // with a stop token packs its live rows into fewer tiles as rows finish, and each tile count has its own shape.
+  size_t part = 0, o_chunks = 0, attn_ml = 0;
+  for (int bt = 1; bt <= p.bt; ++bt) {
+    const int B = bt == p.bt ? p.B : bt * 16;
+    const DecodeTune t = tune_decode(D, B, bt, p.max_pages);
+    const size_t Mpad = (size_t)bt * 16;
+    part = std::max(part, std::max({(size_t)t.ks_qkv * D.nqkv, (size_t)t.ks_o * D.d, (size_t)t.ks_down * D.d}) * Mpad);
+    o_chunks = std::max(o_chunks, (size_t)t.n_chunks * D.nq * Mpad);
+    attn_ml = std::max(attn_ml, Mpad * D.Hq * t.n_chunks * 2);
+  }
   const size_t Mpad = (size_t)p.bt * 16;
-  const size_t part = std::max({(size_t)p.ks_qkv * D.nqkv, (size_t)p.ks_o * D.d, (size_t)p.ks_down * D.d}) * Mpad;
   p.part = cv.take<float>(part);
-  p.o_chunks = cv.take<h16_t>((size_t)p.n_chunks * D.nq * Mpad);
-  p.attn_ml = cv.take<float>((size_t)p.B * D.Hq * p.n_chunks * 2);
-  p.lm_part = cv.take<float>((size_t)((D.nt_V + 1) / 2) * p.B * 8);
+  p.o_chunks = cv.take<h16_t>(o_chunks);
+  p.attn_ml = cv.take<float>(attn_ml);
+  p.lm_part = cv.take<float>((size_t)((D.nt_V + 1) / 2) * Mpad * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
   p.ctl = cv.take<bf16::SampleCtl>(1);
   p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
   p.ssB = cv.take<float>((size_t)D.nt_d * Mpad);
   p.rs_buf = cv.take<float>(Mpad);
+  if (p.ragged) {
+    p.slot_row = cv.take<int>(Mpad);
+    p.page_table_c = cv.take<int>(Mpad * p.max_pages);
+    p.row_pos_c = cv.take<int>(Mpad);
+    p.live = cv.take<int>(16);
+  }
 }
 
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
@@ -480,8 +519,13 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
     bf16::SampleCtl ctl{sa.greedy, sa.inv_temp, (uint32_t)(sa.seed & 0xffffffffu), (uint32_t)(sa.seed >> 32),
                         sa.seq_offset + (uint32_t)(g0 * p.n_samples), sa.max_new, sa.out_ids + out_off,
                         sa.out_logprobs + out_off, sa.stop_id, (ragged && sa.stop_id >= 0) ? p.done : nullptr,
-                        g_out_lens};
+                        g_out_lens, nullptr};
     bf16::set_sample_ctl((bf16::SampleCtl*)p.ctl, ctl, st);
+    if (ragged && sa.stop_id >= 0) {
+      // what a row reports after its end; rows that have given up their slot never write again
+      launch_fill_u32((uint32_t*)(sa.out_ids + out_off), (uint32_t)sa.stop_id, (size_t)gp.B * p.max_new, st);
+      launch_fill_u32((uint32_t*)(sa.out_logprobs + out_off), 0u, (size_t)gp.B * p.max_new, st);
+    }
     const int R = ragged ? sa.reuse_len : 0;   // cached prefix: only positions R .. prompt_len - 1 are prefilled
     const int S = p.prompt_len - R;
     if (ragged) {
@@ -521,30 +565,94 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       launch_fork_tail_pages(pool, c.n_layers, gp.B, p.n_samples, p.n_full, 2, st);
     // ---- step 0 samples from the prompt's last position; step i > 0 first feeds token i - 1
     bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, gp.B, gp.bt, D.d, w->err_flag, st);
-    auto sample = [&](hipStream_t s, const float* ss_cur, const float* ss_old) {
+    // q: the shape the step runs in (the group's rows, or the slots its live rows were packed into)
+    auto embed_args = [&](const RolloutPlan& q) {
+      return bf16::EmbedNextArgs{p.hB, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xB,
+                                 q.bt * 16, p.ssA, D.V, w->err_flag};
+    };
+    auto sample = [&](hipStream_t s, const float* ss_cur, const float* ss_old, const RolloutPlan& q) {
       bf16::DecGemmArgs lm{};
       lm.Wt = (const h16_t*)w->lm_head; lm.Xt = (const h16_t*)p.xB; lm.n_tiles = D.nt_V; lm.k_tiles = D.kt_d;
-      lm.m_tiles = gp.bt; lm.M = gp.B; lm.ss_cur = ss_cur; lm.ss_old = ss_old; lm.ss_tiles = D.nt_d;
+      lm.m_tiles = q.bt; lm.M = q.B; lm.ss_cur = ss_cur; lm.ss_old = ss_old; lm.ss_tiles = D.nt_d;
       lm.inv_d = 1.0f / (float)D.d; lm.eps = c.rms_eps; lm.out_f32 = p.lm_part;
       lm.ctl = (const bf16::SampleCtl*)p.ctl; lm.d_step = p.d_step;
       bf16::gemm_dec(lm, bf16::DEC_SAMPLE, s);
-      const int groups = (D.nt_V + bf16::dec_wide_nb(gp.bt) - 1) / bf16::dec_wide_nb(gp.bt);
+      const int groups = (D.nt_V + bf16::dec_wide_nb(q.bt) - 1) / bf16::dec_wide_nb(q.bt);
       // also ++*d_step, and the embedding + first norm of the chosen tokens: the next step starts at its QKV projection
-      const bf16::EmbedNextArgs emb{p.hB, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xB,
-                                    gp.bt * 16, p.ssA, D.V, w->err_flag};
-      bf16::sample_merge(p.lm_part, groups, gp.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, emb, s);
+      bf16::sample_merge(p.lm_part, groups, q.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, embed_args(q), s);
     };
-    auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) {
+    auto decode_step_in = [&](hipStream_t s, KernelTimer* tm, const RolloutPlan& q, const KvPool& qpool) {
       const float *ss_cur = nullptr, *ss_old = nullptr;
       if (tm) tm->mark_empty_pair();
-      decode_layers(w, D, gp, pool, p.prompt_len - 1, &ss_cur, &ss_old, s, tm);
+      decode_layers(w, D, q, qpool, p.prompt_len - 1, &ss_cur, &ss_old, s, tm);
       if (tm) tm->mark(MTMC_KERNEL_LM_HEAD);
-      sample(s, ss_cur, ss_old);
+      sample(s, ss_cur, ss_old, q);
       if (tm) tm->mark(MTMC_KERNEL_LM_HEAD);
     };
+    auto decode_step_timed = [&](hipStream_t s, KernelTimer* tm) { decode_step_in(s, tm, gp, pool); };
     auto decode_step = [&](hipStream_t s) { decode_step_timed(s, nullptr); };
-    sample(st, nullptr, nullptr);  // xB holds the exactly normalised last prompt position
-    if (p.max_new > 1) {
+    sample(st, nullptr, nullptr, gp);  // xB holds the exactly normalised last prompt position
+    // A stop token: every `poll` steps the number of rows still running goes to the host, which reads it one
+    // period later, ends the group when it is zero and packs the live rows into fewer 16-row tiles when it
+    // frees a tile.  Not while the caller is capturing the stream (the host must not wait then).
+    int poll = (ragged && sa.stop_id >= 0) ? w->opt_stop_poll : 0;
+    if (poll > 0) {
+      hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        poll = 0;
+      }
+    }
+    if (p.max_new > 1 && poll > 0) {
+      mtmc_weights* mw = const_cast<mtmc_weights*>(w);
+      if (!mw->graphs) mw->graphs = new GraphCache();
+      GraphCache& gc = *mw->graphs;
+      std::lock_guard<std::mutex> poll_lock(gc.poll_mu);
+      if (!gc.host_live) {
+        MTMC_HIP_CHECK(hipHostMalloc((void**)&gc.host_live, 64 * sizeof(int), hipHostMallocDefault));
+        for (hipEvent_t& e : gc.poll_events) MTMC_HIP_CHECK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      }
+      RolloutPlan cur = gp;
+      KvPool cur_pool = pool;
+      auto step_cur = [&](hipStream_t s) { decode_step_in(s, nullptr, cur, cur_pool); };
+      hipGraphExec_t exec = nullptr;
+      if (int rc = decode_graph(w, cur, st, step_cur, &exec)) return rc;
+      int i = 1, slot = 0;
+      bool have_prev = false;
+      while (i < p.max_new) {
+        const int n = std::min(poll, p.max_new - i);
+        for (int j = 0; j < n; ++j) {
+          if (exec) MTMC_HIP_CHECK(hipGraphLaunch(exec, st));
+          else step_cur(st);
+        }
+        i += n;
+        if (i >= p.max_new) break;
+        bf16::count_live(p.done, gp.B, p.live, st);
+        MTMC_HIP_CHECK(hipMemcpyAsync(gc.host_live + 16 * slot, p.live, sizeof(int), hipMemcpyDeviceToHost, st));
+        MTMC_HIP_CHECK(hipEventRecord(gc.poll_events[slot], st));
+        if (have_prev) {
+          MTMC_HIP_CHECK(hipEventSynchronize(gc.poll_events[slot ^ 1]));
+          const int n_live = gc.host_live[16 * (slot ^ 1)];  // one period old: rows only ever finish, so an upper bound
+          if (n_live <= 0) break;  // every later slot of the outputs already holds stop_id / 0
+          const int slots = tiles16(n_live) * 16;
+          if (slots < cur.bt * 16) {
+            bf16::compact_rows(p.done, gp.B, slots, p.slot_row, p.page_table, p.row_pos, p.max_pages, p.page_table_c,
+                               p.row_pos_c, st);
+            cur = gp;
+            cur.B = slots; cur.bt = slots / 16; cur.n_samples = 1; cur.ragged = 2;
+            cur.row_pos = p.row_pos_c;
+            apply_tune(cur, tune_decode(D, cur.B, cur.bt, p.max_pages));
+            cur_pool.page_table = p.page_table_c;
+            ctl.slot_row = p.slot_row;
+            bf16::set_sample_ctl((bf16::SampleCtl*)p.ctl, ctl, st);
+            bf16::embed_slots(p.slot_row, p.cur_ids, slots, embed_args(cur), st);
+            if (int rc = decode_graph(w, cur, st, step_cur, &exec)) return rc;
+          }
+        }
+        have_prev = true;
+        slot ^= 1;
+      }
+    } else if (p.max_new > 1) {
       hipGraphExec_t exec = nullptr;
       if (int rc = decode_graph(w, gp, st, decode_step, &exec)) return rc;
       GraphCache* gc = w->graphs;

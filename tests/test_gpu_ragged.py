@@ -248,3 +248,50 @@ def test_cached_prefix_misuse_is_reported(lib):
             lib.mtmc_poll_errors(handle)
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+# ---------------------------------------------------------------- finished rows give up their place
+STOPPY = inputs.ModelConfig(2, 384, 6, 1, 128, 1024, 64, dtype="bf16")    # 64 tokens: a stop token comes up every ~64 steps
+STOPPY16 = inputs.ModelConfig(2, 256, 4, 2, 128, 688, 16, dtype="bf16")   # 16 tokens: every ~16 steps
+
+
+@pytest.mark.parametrize("name,cfg,lens,n_samples,max_new,poll", [
+    ("b40-poll4", STOPPY, [37, 16, 1, 33, 70], 8, 96, 4),      # 48 slots -> 32 -> 16 as rows finish
+    ("b64-poll8", STOPPY, [21, 40, 9, 64, 33, 17, 50, 5], 8, 80, 8),
+    ("b128-poll4", STOPPY, list(range(3, 35, 2)), 8, 128, 4),   # the 128-row kernels first, then the 64-row ones
+    ("b16-all-stop", STOPPY16, [30, 7], 8, 200, 4),            # every row stops long before the budget: the call ends early
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_rows_that_stop_give_up_their_place(lib, name, cfg, lens, n_samples, max_new, poll):
+    """With a stop token the library looks at the stop flags every few steps, packs the rows still running into
+    fewer 16-row tiles and ends when none is left.  Every row is replayed on the oracle (decisions above the
+    margin gate, log-probs, lengths, stop_id / 0 after the end); up to the first look the packed call equals the
+    call that never looks."""
+    import torch
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 512), w.blob())
+    try:
+        lens = np.array(lens, dtype=np.int32)
+        prompts = inputs.make_prompts(len(lens), int(lens.max()), cfg.vocab, seed=2)
+        stop = 3
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_STOP_POLL_STEPS, poll)
+        rep = check_ragged_by_replay(handle, w, prompts, lens, n_samples, max_new, 1.0, 1, stop_id=stop,
+                                     max_positions=512, label=name)
+        n = rep["lens"]
+        print(name, "lengths: min", n.min(), "median", int(np.median(n)), "max", n.max(), "stopped", int((n < max_new).sum()),
+              "of", n.size, "; compared", rep["compared"], "of", rep["steps"], "max log-prob err", rep["max_logp_err"])
+        assert (n < max_new).sum() >= n.size // 3
+        again = lib.mtmc_rollout_ragged(handle, torch.from_numpy(prompts).cuda(), torch.from_numpy(lens).cuda(), n_samples,
+                                        max_new, 1.0, 1, stop_id=stop)
+        assert np.array_equal(again[0].cpu().numpy(), rep["ids"]) and np.array_equal(again[1].cpu().numpy(), rep["logprobs"])
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_STOP_POLL_STEPS, 0)
+        static = lib.mtmc_rollout_ragged(handle, torch.from_numpy(prompts).cuda(), torch.from_numpy(lens).cuda(), n_samples,
+                                         max_new, 1.0, 1, stop_id=stop)
+        lib.mtmc_poll_errors(handle)
+        s_ids, s_lp = static[0].cpu().numpy(), static[1].cpu().numpy()
+        first = 2 * poll   # the first look is read one period late: no row moves before step 2 * poll
+        assert np.array_equal(s_ids[:, :first], rep["ids"][:, :first]) and np.array_equal(s_lp[:, :first], rep["logprobs"][:, :first])
+        same = (s_ids == rep["ids"]).all(axis=1)
+        print(name, "rows identical to the unpacked call:", int(same.sum()), "of", same.size)
+        assert np.abs(s_lp[same] - rep["logprobs"][same]).max() <= 5e-3
+    finally:
+        lib.mtmc_weights_destroy(handle)
