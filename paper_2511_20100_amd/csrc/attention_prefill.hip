@@ -51,7 +51,7 @@ constexpr int QB = 128;   // query columns per workgroup
 template <int PHD>
 __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t* q, int S, int Mpad, int Hq, int Hkv,
                                                            int row_stride, int pos_base, KvPool pool, int layer,
-                                                           int* err_flag) {
+                                                           int* err_flag, const int* seq_start) {
   constexpr int kPageBytes = kPageTokens * PHD * 2;  // 4 or 2 KiB
   constexpr int kAStageBytes = 4 * kPageBytes;       // K page 0, K page 1, V page 0, V page 1
   constexpr int kPageKiB = kPageBytes / 1024;
@@ -59,7 +59,15 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int qblk = gridDim.x - 1 - blockIdx.x;  // longest columns first
   const int c0 = qblk * QB, g = blockIdx.y, seq = blockIdx.z;
+  // sequences of different lengths packed back to back: this one holds the tokens tok0 .. tok0 + S - 1 (the grid
+  // is sized for the longest; a workgroup whose columns lie beyond this sequence's has nothing to do)
+  int tok0 = seq * S;
+  if (seq_start) {
+    tok0 = seq_start[seq];
+    S = seq_start[seq + 1] - tok0;
+  }
   const int G = Hq / Hkv, n_cols = G * S;
+  if (c0 >= n_cols) return;  // whole workgroup, before any barrier
   // positions covered by the workgroup's columns: exact when they belong to one query head, else all
   const int c_last = min(c0 + QB, n_cols) - 1;
   const bool one_head = c0 / S == c_last / S;
@@ -119,7 +127,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
     qpos[i] = live ? pos : -1;
     qabs[i] = live ? pos_base + pos : -1;
     qhd[i] = g * G + jh;
-    const h16_t* qrow = q + ((size_t)seq * S + max(qpos[i], 0)) * Hq * PHD + (size_t)qhd[i] * PHD + 8 * hh;
+    const h16_t* qrow = q + ((size_t)tok0 + max(qpos[i], 0)) * Hq * PHD + (size_t)qhd[i] * PHD + 8 * hh;
 #pragma unroll
     for (int j = 0; j < PHD / 16; ++j) {
       v4u raw = {0u, 0u, 0u, 0u};
@@ -241,7 +249,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
     l += __shfl_xor(l, 32, 64);
     if (qpos[i] < 0) continue;
     const float inv = 1.0f / l;
-    const int tok = seq * S + qpos[i];
+    const int tok = tok0 + qpos[i];
 #pragma unroll
     for (int d = 0; d < PHD / 32; ++d)
 #pragma unroll
@@ -257,7 +265,7 @@ __global__ __launch_bounds__(256, 3) void k_attn_prefill32(h16_t* o, const h16_t
 }  // namespace
 
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
-                       TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st) {
+                       TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st, const int* seq_start) {
   static bool configured = false;
   constexpr int kLdsMax = 160 * 1024;
   if (!configured) {
@@ -274,10 +282,10 @@ void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles,
   const dim3 grid((n_cols + QB - 1) / QB, Hkv, n_seqs);
   if (hd == 64)
     k_attn_prefill32<64><<<grid, 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv, map.row_stride, map.pos_base, pool,
-                                                       layer, err_flag);
+                                                       layer, err_flag, seq_start);
   else
     k_attn_prefill32<128><<<grid, 256, lds_bytes, st>>>(o, q, S, m_tiles * 16, Hq, Hkv, map.row_stride, map.pos_base,
-                                                        pool, layer, err_flag);
+                                                        pool, layer, err_flag, seq_start);
 }
 
 }  // namespace bf16

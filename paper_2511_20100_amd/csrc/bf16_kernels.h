@@ -34,6 +34,7 @@ struct LargeArgs {
   int ld_out;
   h16_t* out_bf16;
   int* err_flag;         // SwiGLU epilogue: raised when a value does not fit fp16
+  const int* d_rows;     // optional (device): only the first *d_rows rows hold tokens; blocks of rows beyond are skipped
 };
 
 struct ScoreHeadArgs {
@@ -44,6 +45,7 @@ struct ScoreHeadArgs {
   float* part;
   int n_groups, groups_per_block;
   int want_top;   // 0: the two largest logits are not tracked (the caller asked for log-probs only)
+  const int* d_rows;  // optional (device): only the first *d_rows rows hold tokens
 };
 
 // ---- decode step (six launches per block; see decode_bf16.hip) ------------------------------
@@ -143,15 +145,19 @@ void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int
                     int k_tiles, int* err_flag, hipStream_t st);
 
 // ---- GEMMs ---------------------------------------------------------------------------------
+// d_rows (device, may be NULL): the number of rows that hold tokens when it is known on the device only (rows
+// packed by a kernel); M and m_tiles then give the capacity the launch is sized for.
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
-                    int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st);
+                    int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, const int* d_rows,
+                    hipStream_t st);
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                       int M, int m_tiles, int lds_min_blocks, int* err_flag, hipStream_t st);
+                       int M, int m_tiles, int lds_min_blocks, int* err_flag, const int* d_rows, hipStream_t st);
 // LDS-staged 256 x 256 kernel behind the two launchers above (epi: 0 store, 1 accumulate, 2 SwiGLU).
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st);
 int score_head_blocks(int n_tiles, int* groups_per_block);
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
-                  int m_tiles, const int* targets, bool want_top, int lds_min_blocks, hipStream_t st);
+                  int m_tiles, const int* targets, bool want_top, int lds_min_blocks, const int* d_rows,
+                  hipStream_t st);
 // One partial result of the scoring LM head: a row's state over one vocabulary slice.
 struct ScorePartial {
   float m, s, v1;   // log-sum-exp state, largest logit
@@ -165,24 +171,43 @@ void score_targets(int* targets, const int* seqs, int R, int S, int first, int n
                    int row0, int vocab, int* err_flag, hipStream_t st);
 void score_reduce(const float* part, int n_parts, int R, int S, int first, int n_scored, int seq0,
                   int row0, float* out_logprobs, int* out_top1, float* out_margin, hipStream_t st);
+// Rows packed by build_packed_actions: row r < *d_rows goes to out_logprobs[out_index[r]].
+void score_reduce_scatter(const float* part, int n_parts, int R, const int* d_rows, const int* out_index,
+                          float* out_logprobs, hipStream_t st);
+// Candidate actions of different lengths packed without padding (action-level scoring).  Rows b = r0 .. r0 + nr - 1
+// of the call (candidate b has len_b = action_len[b] clamped to [0, A] tokens a_1 .. a_len) become the packed
+// token list of a chunk: candidate b contributes the len_b inputs [last token of its state, a_1 .. a_{len-1}]
+// (none when empty), whose outputs predict a_1 .. a_len.
+//   seq_start [nr + 1]  first packed token of every candidate (exclusive prefix sums); d_rows[0] = their total
+//   ids, targets [cap]  input token and the token it must predict, per packed token
+//   out_index [cap]     b * A + i: where the term of (candidate b, action token i) goes
+// One workgroup of 1024 threads; nr * A <= cap.  An action_len outside [0, A] raises bit 4 of *err_flag.
+void build_packed_actions(int* seq_start, int* d_rows, int* ids, int* targets, int* out_index, const int* states,
+                          const int* actions, const int* action_len, int P, int K, int A, int r0, int nr, int vocab,
+                          int* err_flag, hipStream_t st);
 
 // ---- elementwise / row kernels -------------------------------------------------------------
 void set_sample_ctl(SampleCtl* dst, const SampleCtl& v, hipStream_t st);
 void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, int* err_flag,
-           hipStream_t st);
+           hipStream_t st, const int* d_rows = nullptr);
 // h[m, :] += sum_s P[s][m][:] (n_split may be 0); x = bf16(RMSNorm(h; gain)) in tiled layout.
 void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
-              h16_t* x, int M, int m_tiles, int d, int* err_flag, hipStream_t st);
+              h16_t* x, int M, int m_tiles, int d, int* err_flag, hipStream_t st, const int* d_rows = nullptr);
 // qkv fp32 [T, (Hq + 2 Hkv) hd] (row stride ld), T = n_seqs * S tokens at positions map.pos_base + t % S: rotates q
 // (-> fp16 row-major [T, Hq*hd]) and k, writes k and v into the pages.  map.d_step and map.row_pos must be NULL.
+// seq_start (device, may be NULL): sequences of different lengths packed back to back: sequence s holds the
+// tokens seq_start[s] .. seq_start[s + 1] - 1 at positions map.pos_base + 0, 1, ...; S is then the longest
+// length a sequence can have and n_seqs the number of sequences (T is ignored).
 void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int Hkv, const float* cos,
-                   const float* sin, TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st);
+                   const float* sin, TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st,
+                   const int* seq_start = nullptr, int n_seqs = 0);
 
 // ---- attention -----------------------------------------------------------------------------
 // Floats of the per-chunk partial results of the decode attention kernel.
 // Prefill / scoring: causal attention of every token of T = n_seqs * S over its own sequence.
 void attention_prefill(h16_t* o, const h16_t* q, int n_seqs, int S, int m_tiles, int Hq, int Hkv,
-                       TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st);
+                       TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st,
+                       const int* seq_start = nullptr);
 
 }  // namespace bf16
 }  // namespace mtmc

@@ -67,8 +67,16 @@ __global__ void k_set_ctl(SampleCtl* dst, SampleCtl v) { *dst = v; }
 void set_sample_ctl(SampleCtl* dst, const SampleCtl& v, hipStream_t st) { k_set_ctl<<<1, 1, 0, st>>>(dst, v); }
 
 // ---------------------------------------------------------------- embedding
-__global__ void k_embed(float* h, const int* ids, const bf16_t* E, int d, int vocab, int* err_flag) {
+__global__ void k_embed(float* h, const int* ids, const bf16_t* E, int d, int vocab, int* err_flag,
+                        const int* d_rows) {
   const int t = blockIdx.x;
+  if (d_rows && t >= *d_rows) {
+    // rows packed on the device: no token here.  The rows that share a 256-row block with tokens still go through
+    // the matrix kernels: they are cleared, so that what is computed from them is zero (and finite)
+    if (t < ((*d_rows + 255) & ~255))
+      for (int c = threadIdx.x; c < d; c += blockDim.x) h[(size_t)t * d + c] = 0.f;
+    return;
+  }
   int id = ids[t];
   if (id < 0 || id >= vocab) {
     if (threadIdx.x == 0) atomicOr(err_flag, 1);
@@ -76,8 +84,10 @@ __global__ void k_embed(float* h, const int* ids, const bf16_t* E, int d, int vo
   }
   for (int c = threadIdx.x; c < d; c += blockDim.x) h[(size_t)t * d + c] = bf16_to_f32(E[(size_t)id * d + c]);
 }
-void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, int* err_flag, hipStream_t st) {
-  k_embed<<<T, 256, 0, st>>>(h, ids, E, d, vocab, err_flag);
+void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, int* err_flag, hipStream_t st,
+           const int* d_rows) {
+  if (T == 0) return;
+  k_embed<<<T, 256, 0, st>>>(h, ids, E, d, vocab, err_flag, d_rows);
 }
 
 // ---------------------------------------------------------------- residual add + RMSNorm
@@ -86,9 +96,10 @@ void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, i
 // sum of squares; pass 2 writes bf16(h * rsqrt(mean + eps) * gain).
 __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p,
                                                   const float* gain, float eps, h16_t* x, int Mpad, int d,
-                                                  int* err_flag) {
+                                                  int* err_flag, const int* d_rows) {
   __shared__ float red[16];
   const int m = blockIdx.x;
+  if (d_rows && m >= ((*d_rows + 255) & ~255)) return;  // rows packed on the device: no token in this 256-row block
   float* hr = h + (size_t)m * d;
   float ss = 0.f;
   for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
@@ -126,10 +137,11 @@ __global__ __launch_bounds__(256) void k_add_norm(float* h, const float* P, int 
 // each cache line).
 __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h, const float* __restrict__ gain,
                                                      float eps, h16_t* x, int M, int m_tiles, int d,
-                                                     int* err_flag) {
+                                                     int* err_flag, const int* d_rows) {
   extern __shared__ __attribute__((aligned(16))) uint8_t xs[];  // 16 rows of 2 d + 16 bytes
   const int row_bytes = 2 * d + 16;
   const int mt = blockIdx.x, r = threadIdx.x >> 4, sub = threadIdx.x & 15;
+  if (d_rows && mt * 16 >= ((*d_rows + 255) & ~255)) return;  // rows packed on the device: no token in this 256-row block
   const int m = mt * 16 + r;
   const bool valid = m < M;
   const float* hr = h + (size_t)min(m, M - 1) * d;
@@ -182,7 +194,7 @@ __global__ __launch_bounds__(256) void k_norm_tile16(const float* __restrict__ h
 }
 
 void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const float* gain, float eps,
-              h16_t* x, int M, int m_tiles, int d, int* err_flag, hipStream_t st) {
+              h16_t* x, int M, int m_tiles, int d, int* err_flag, hipStream_t st, const int* d_rows) {
   if (M == 0) return;
   if (n_split == 0 && M >= 1024 && d % 32 == 0 && d * 32 + 256 <= 160 * 1024) {
     static bool configured = false;
@@ -191,10 +203,10 @@ void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const 
                                 160 * 1024);
       configured = true;
     }
-    k_norm_tile16<<<(M + 15) / 16, 256, 16 * (2 * d + 16), st>>>(h, gain, eps, x, M, m_tiles, d, err_flag);
+    k_norm_tile16<<<(M + 15) / 16, 256, 16 * (2 * d + 16), st>>>(h, gain, eps, x, M, m_tiles, d, err_flag, d_rows);
     return;
   }
-  k_add_norm<<<M, 256, 0, st>>>(h, P, n_split, ldp, Mpad_p, gain, eps, x, m_tiles * 16, d, err_flag);
+  k_add_norm<<<M, 256, 0, st>>>(h, P, n_split, ldp, Mpad_p, gain, eps, x, m_tiles * 16, d, err_flag, d_rows);
 }
 
 // ---------------------------------------------------------------- rotary embedding + KV write
@@ -209,14 +221,21 @@ void add_norm(float* h, const float* P, int n_split, int ldp, int Mpad_p, const 
 template <int HD>
 __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv, int ld, int S, int Hq, int Hkv,
                                                       const float* cos, const float* sin, int row_stride, int pos_base,
-                                                      KvPool pool, int layer, int* err_flag) {
+                                                      KvPool pool, int layer, int* err_flag, const int* seq_start) {
   constexpr int HALF = HD / 2, QUADS = HALF / 4;  // quads of rotation pairs per head
   constexpr int ROW = HD + 8;                     // LDS row stride in halfs: 16-byte reads down a column stay conflict-free
   __shared__ __attribute__((aligned(16))) h16_t k_s[kPageTokens][ROW];
   __shared__ __attribute__((aligned(16))) h16_t v_s[kPageTokens][ROW];
   const int seq = blockIdx.y;
+  // sequences of different lengths packed back to back: this one holds the tokens tok0 .. tok0 + S - 1
+  size_t tok0 = (size_t)seq * S;
+  if (seq_start) {
+    tok0 = (size_t)seq_start[seq];
+    S = seq_start[seq + 1] - seq_start[seq];
+  }
   const int pg = pos_base / kPageTokens + blockIdx.x;          // page index of the sequence
   const int p_lo = max(pg * kPageTokens, pos_base), p_hi = min((pg + 1) * kPageTokens, pos_base + S);
+  if (p_lo >= p_hi) return;  // whole workgroup: the sequence has no token in this page
   const bool whole = p_hi - p_lo == kPageTokens;
   const int page = pool.page_table[(size_t)seq * row_stride * pool.max_pages + pg];
   h16_t* kv = (h16_t*)pool.base;
@@ -228,7 +247,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv
       const int slot = u / QUADS, i = (u % QUADS) * 4;
       const int pos = pg * kPageTokens + slot;
       if (pos < p_lo || pos >= p_hi) continue;
-      const size_t t = (size_t)seq * S + (pos - pos_base);
+      const size_t t = tok0 + (pos - pos_base);
       const float* pr = qkv + t * ld + (size_t)head * HD;
       const v4f a = *reinterpret_cast<const v4f*>(pr + i), b = *reinterpret_cast<const v4f*>(pr + i + HALF);
       const v4f c = *reinterpret_cast<const v4f*>(cos + (size_t)pos * HALF + i);
@@ -253,7 +272,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv
       const int slot = u / (HD / 4), i = (u % (HD / 4)) * 4;
       const int pos = pg * kPageTokens + slot;
       if (pos < p_lo || pos >= p_hi) continue;
-      const size_t t = (size_t)seq * S + (pos - pos_base);
+      const size_t t = tok0 + (pos - pos_base);
       const v4f v = *reinterpret_cast<const v4f*>(qkv + t * ld + (size_t)(Hq + Hkv + g) * HD + i);
       uint2 pk;
       pk.x = pack_h16x2_flag(v[0], v[1], err_flag); pk.y = pack_h16x2_flag(v[2], v[3], err_flag);
@@ -287,17 +306,18 @@ __global__ __launch_bounds__(256) void k_rope_kv_page(h16_t* q, const float* qkv
   }
 }
 void rope_kv_write(h16_t* q, const float* qkv, int ld, int T, int S, int Hq, int Hkv, const float* cos,
-                   const float* sin, TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st) {
-  if (T == 0) return;
+                   const float* sin, TokMap map, KvPool pool, int layer, int* err_flag, hipStream_t st,
+                   const int* seq_start, int n_seqs) {
+  if (seq_start ? (n_seqs == 0 || S == 0) : T == 0) return;
   // pages that the positions pos_base .. pos_base + S - 1 of a sequence touch
   const int n_pg = (map.pos_base + S - 1) / kPageTokens - map.pos_base / kPageTokens + 1;
-  const dim3 grid(n_pg, T / S);
+  const dim3 grid(n_pg, seq_start ? n_seqs : T / S);
   if (pool.head_dim == 64)
     k_rope_kv_page<64><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool, layer,
-                                             err_flag);
+                                             err_flag, seq_start);
   else
     k_rope_kv_page<128><<<grid, 256, 0, st>>>(q, qkv, ld, S, Hq, Hkv, cos, sin, map.row_stride, map.pos_base, pool,
-                                              layer, err_flag);
+                                              layer, err_flag, seq_start);
 }
 
 }  // namespace bf16

@@ -136,6 +136,11 @@ struct ActionPlan {
   float* lm_part;
   void* qb;
   int* targets;
+  // bf16 path: the candidates of a chunk packed without padding (built on the device, see build_packed_actions)
+  int* seq_start;    // [chunk_rows + 1]
+  int* d_rows;       // [16] d_rows[0] = packed tokens of the chunk
+  int* pids;         // [chunk_rows * A] input token of every packed token
+  int* out_index;    // [chunk_rows * A] where its term goes in out_token
   size_t total_bytes;
 };
 

@@ -348,6 +348,10 @@ void bf16_plan_actions_extra(const mtmc_weights* w, ActionPlan& p, Carver& cv) {
   p.lm_part = cv.take<float>((size_t)blocks * 2 * p.rows_max * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
   p.targets = cv.take<int>(p.rows_max);
+  p.seq_start = cv.take<int>((size_t)p.chunk_rows + 1);
+  p.d_rows = cv.take<int>(16);
+  p.pids = cv.take<int>(p.rows_max);
+  p.out_index = cv.take<int>(p.rows_max);
 }
 
 // ======================================================================================
@@ -358,23 +362,27 @@ namespace {
 // All residual blocks over T >= 1 tokens in the large-batch (prefill / scoring) form.
 // In: h (fp32 [T, d]) and x = bf16 RMSNorm(h; attn_norm of layer 0) in tiled layout.
 // Out: h after the last block (x is not refreshed after the last block).
+// seq_start / d_rows (device, may be NULL): the sequences have different lengths and are packed back to back
+// (sequence s = tokens seq_start[s] .. seq_start[s + 1] - 1, *d_rows tokens in all); S is then the longest
+// length possible and n_seqs * S the capacity the launches are sized for.
 void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, float* qkv, h16_t* qb,
                     h16_t* o, h16_t* a, int n_seqs, int S, TokMap map, KvPool pool, int layer_stride,
-                    hipStream_t st) {
+                    hipStream_t st, const int* seq_start = nullptr, const int* d_rows = nullptr) {
   const mtmc_config& c = w->cfg;
   const int T = n_seqs * S, mt = tiles16(T), lmb = w->opt_lds_min_blocks;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& L = w->layers[l];
     const int kvl = l * layer_stride;
-    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, st);
-    bf16::rope_kv_write(qb, qkv, D.nqkv, T, S, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, w->err_flag, st);
-    bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, w->err_flag, st);
-    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, st);
-    bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st);
-    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, lmb, w->err_flag, st);
-    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, lmb, st);
+    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, d_rows, st);
+    bf16::rope_kv_write(qb, qkv, D.nqkv, T, S, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, w->err_flag, st,
+                        seq_start, n_seqs);
+    bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, w->err_flag, st, seq_start);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, d_rows, st);
+    bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st, d_rows);
+    bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, lmb, w->err_flag, d_rows, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, lmb, d_rows, st);
     if (l + 1 < c.n_layers)
-      bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st);
+      bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st, d_rows);
   }
 }
 
@@ -695,7 +703,7 @@ int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hi
     bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, w->err_flag, st);
     bf16::score_targets(p.targets, a.seqs, R, S, a.first, n_scored, s0, 0, D.V, w->err_flag, st);
     bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
-                       a.out_top1 != nullptr || a.out_margin != nullptr, w->opt_lds_min_blocks, st);
+                       a.out_top1 != nullptr || a.out_margin != nullptr, w->opt_lds_min_blocks, nullptr, st);
     bf16::score_reduce(p.lm_part, n_parts, R, S, a.first, n_scored, s0, 0, a.out_logprobs, a.out_top1, a.out_margin, st);
   }
   return MTMC_OK;
@@ -727,26 +735,32 @@ int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionA
     }
     if (p.Pp % kPageTokens != 0) launch_fork_tail_pages(pool, c.n_layers, p.B, p.K, p.n_full, 2, st);
   }
-  // ---- the candidates: W tokens per row on top of the shared pages, every position scored
-  TokMap map{p.W, 1, p.Pp, nullptr};
+  // ---- the candidates, packed without padding: candidate b is the len_b tokens [last state token, a_1 ..
+  // a_{len - 1}] at positions P - 1 .. on top of its state's pages, and every one of them is scored (it predicts
+  // a_1 .. a_len).  The number of packed tokens is known on the device only: the launches are sized for nr * A
+  // rows and the kernels skip the blocks of rows beyond *d_rows.
+  TokMap map{p.A, 1, p.Pp, nullptr};
   int gpb = 0;
   const int n_parts = bf16::score_head_blocks(D.nt_V, &gpb) * 2;
   for (int r0 = 0; r0 < p.B; r0 += p.chunk_rows) {
     const int nr = std::min(p.chunk_rows, p.B - r0);
-    const int T = nr * p.W, mt = tiles16(T);
+    const int T = nr * p.A, mt = tiles16(T);
     KvPool chunk_pool = pool;
     chunk_pool.page_table = p.page_table + (size_t)r0 * p.max_pages;
-    bf16::embed(p.h, p.vseq + (size_t)r0 * p.W, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
-    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
-    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, nr, p.W, map,
-                   chunk_pool, 1, st);
-    const int R = nr * p.A, rt = tiles16(R);
-    launch_gather_rows(p.hs, p.h, R, D.d, p.A, p.W, 0, 1, st);
-    bf16::add_norm(p.hs, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, R, rt, D.d, w->err_flag, st);
-    bf16::score_targets(p.targets, p.vseq, R, p.W, 0, p.A, r0, 0, D.V, w->err_flag, st);
-    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, R, rt, p.targets,
-                       false, w->opt_lds_min_blocks, st);
-    bf16::score_reduce(p.lm_part, n_parts, R, p.W, 0, p.A, r0, 0, a.out_token, nullptr, nullptr, st);
+    bf16::build_packed_actions(p.seq_start, p.d_rows, p.pids, p.targets, p.out_index, a.states, a.actions,
+                               a.action_len, p.P, p.K, p.A, r0, nr, D.V, w->err_flag, st);
+    // rows without a token that share a 256-row block with tokens run through the matrix kernels: cleared inputs
+    // (embedding, attention output) keep everything computed from them at zero
+    launch_fill_u32((uint32_t*)p.o, 0u, (size_t)mt * 16 * D.nq / 2, st);
+    bf16::embed(p.h, p.pids, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st, p.d_rows);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st,
+                   p.d_rows);
+    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, nr, p.A, map,
+                   chunk_pool, 1, st, p.seq_start, p.d_rows);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, T, mt, D.d, w->err_flag, st, p.d_rows);
+    bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, T, mt, p.targets,
+                       false, w->opt_lds_min_blocks, p.d_rows, st);
+    bf16::score_reduce_scatter(p.lm_part, n_parts, T, p.d_rows, p.out_index, a.out_token, st);
   }
   launch_action_reduce(a.out_token, a.action_len, p.n_states, p.K, p.A, a.normalize, a.out_action, a.out_policy,
                        st);

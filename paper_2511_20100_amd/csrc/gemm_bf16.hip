@@ -113,6 +113,7 @@ __global__ __launch_bounds__(256) void k_gemm_large(LargeArgs a) {
   const int nt0 = blk.nb * 8 + (wave & 1) * 4;
   const int mt0 = blk.mb * 8 + (wave >> 1) * 4;
   if (nt0 >= a.n_tiles || mt0 >= a.m_tiles) return;
+  if (a.d_rows && mt0 * 16 >= *a.d_rows) return;  // rows packed on the device: no token in these rows
   v4f acc[4][4];
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb)
@@ -162,19 +163,20 @@ static bool use_lds_kernel(int n_tiles, int k_tiles, int m_tiles, int lds_min_bl
   return k_tiles >= 4 && k_tiles % 2 == 0 && ((n_tiles + 15) / 16) * ((m_tiles + 15) / 16) >= lds_min_blocks;
 }
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
-                    int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, hipStream_t st) {
+                    int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, const int* d_rows,
+                    hipStream_t st) {
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M; a.N = N;
-  a.out_f32 = C; a.ld_out = ldc;
+  a.out_f32 = C; a.ld_out = ldc; a.d_rows = d_rows;
   const int epi = accumulate ? LEPI_ADD : LEPI_STORE;
   if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, epi, st);
   else launch_large(a, epi, st);
 }
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
-                       int M, int m_tiles, int lds_min_blocks, int* err_flag, hipStream_t st) {
+                       int M, int m_tiles, int lds_min_blocks, int* err_flag, const int* d_rows, hipStream_t st) {
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
-  a.out_bf16 = act; a.err_flag = err_flag;
+  a.out_bf16 = act; a.err_flag = err_flag; a.d_rows = d_rows;
   if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, LEPI_SWIGLU, st);
   else launch_large(a, LEPI_SWIGLU, st);
 }
@@ -188,6 +190,7 @@ __global__ __launch_bounds__(256) void k_lmhead_score(ScoreHeadArgs a) {
   const int wn = wave & 1;
   const int mt0 = blockIdx.y * 8 + (wave >> 1) * 4;
   if (mt0 >= a.m_tiles) return;
+  if (a.d_rows && mt0 * 16 >= *a.d_rows) return;  // rows packed on the device: no token in these rows
   const int col = lane & 15, rq = (lane >> 4) * 4;
   Lse lse[4];
   Top2 top[4];
@@ -254,9 +257,11 @@ int score_head_blocks(int n_tiles, int* groups_per_block) {
 }
 
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
-                  int m_tiles, const int* targets, bool want_top, int lds_min_blocks, hipStream_t st) {
+                  int m_tiles, const int* targets, bool want_top, int lds_min_blocks, const int* d_rows,
+                  hipStream_t st) {
   ScoreHeadArgs a{};
   a.want_top = want_top ? 1 : 0;
+  a.d_rows = d_rows;
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M;
   a.targets = targets; a.part = part;
   a.n_groups = (n_tiles + 7) / 8;
@@ -321,6 +326,92 @@ void score_reduce(const float* part, int n_parts, int R, int S, int first, int n
                   int row0, float* out_logprobs, int* out_top1, float* out_margin, hipStream_t st) {
   k_score_reduce<<<R, 64, 0, st>>>(reinterpret_cast<const ScorePartial*>(part), n_parts, R, S, first,
                                    n_scored, seq0, row0, out_logprobs, out_top1, out_margin);
+}
+
+__global__ __launch_bounds__(64) void k_score_reduce_scatter(const ScorePartial* part, int n_parts, int R,
+                                                             const int* d_rows, const int* out_index,
+                                                             float* out_logprobs) {
+  const int r = blockIdx.x;
+  if (r >= *d_rows) return;
+  const int lane = threadIdx.x;
+  Lse lse = lse_empty();
+  float zt = -INFINITY;
+  for (int g = lane; g < n_parts; g += 64) {
+    const ScorePartial p = part[(size_t)g * R + r];
+    lse = lse_merge(lse, Lse{p.m, p.s});
+    zt = fmaxf(zt, p.zt);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const Lse ol = {__shfl_xor(lse.m, o, 64), __shfl_xor(lse.s, o, 64)};
+    lse = lse_merge(lse, ol);
+    zt = fmaxf(zt, __shfl_xor(zt, o, 64));
+  }
+  if (lane == 0) out_logprobs[out_index[r]] = zt - (lse.m + logf(lse.s));
+}
+void score_reduce_scatter(const float* part, int n_parts, int R, const int* d_rows, const int* out_index,
+                          float* out_logprobs, hipStream_t st) {
+  if (R == 0) return;
+  k_score_reduce_scatter<<<R, 64, 0, st>>>(reinterpret_cast<const ScorePartial*>(part), n_parts, R, d_rows, out_index,
+                                           out_logprobs);
+}
+
+// One workgroup of 1024 threads: thread t owns the candidates t, t + 1024, ... in blocks of consecutive
+// candidates, sums their lengths, the 1024 sums are scanned in LDS, then every thread writes its candidates.
+__global__ __launch_bounds__(1024) void k_build_packed_actions(int* seq_start, int* d_rows, int* ids, int* targets,
+                                                               int* out_index, const int* states, const int* actions,
+                                                               const int* action_len, int P, int K, int A, int r0,
+                                                               int nr, int vocab, int* err_flag) {
+  __shared__ int s_sum[1024];
+  const int tid = threadIdx.x;
+  const int per = (nr + 1023) / 1024;            // consecutive candidates per thread
+  const int c0 = min(tid * per, nr), c1 = min(c0 + per, nr);
+  auto len_of = [&](int c) {
+    const int raw = action_len[r0 + c];
+    if (raw < 0 || raw > A) atomicOr(err_flag, 4);
+    return min(max(raw, 0), A);
+  };
+  int mine = 0;
+  for (int c = c0; c < c1; ++c) mine += len_of(c);
+  s_sum[tid] = mine;
+  __syncthreads();
+  // inclusive scan (Hillis-Steele, 10 rounds)
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int v = tid >= off ? s_sum[tid - off] : 0;
+    __syncthreads();
+    s_sum[tid] += v;
+    __syncthreads();
+  }
+  int at = s_sum[tid] - mine;                      // first packed token of this thread's candidates
+  if (tid == 1023) d_rows[0] = s_sum[1023];
+  for (int c = c0; c < c1; ++c) {
+    const int b = r0 + c, len = min(max(action_len[b], 0), A);
+    seq_start[c] = at;
+    const int* act = actions + (size_t)b * A;
+    for (int i = 0; i < len; ++i) {
+      int in = i == 0 ? states[(size_t)(b / K) * P + P - 1] : act[i - 1];
+      int tg = act[i];
+      if (tg < 0 || tg >= vocab) {
+        atomicOr(err_flag, 1);
+        tg = tg < 0 ? 0 : vocab - 1;
+      }
+      if (in < 0 || in >= vocab) {
+        atomicOr(err_flag, 1);
+        in = in < 0 ? 0 : vocab - 1;
+      }
+      ids[at + i] = in;
+      targets[at + i] = tg;
+      out_index[at + i] = b * A + i;
+    }
+    at += len;
+  }
+  if (tid == 1023) seq_start[nr] = s_sum[1023];
+}
+void build_packed_actions(int* seq_start, int* d_rows, int* ids, int* targets, int* out_index, const int* states,
+                          const int* actions, const int* action_len, int P, int K, int A, int r0, int nr, int vocab,
+                          int* err_flag, hipStream_t st) {
+  k_build_packed_actions<<<1, 1024, 0, st>>>(seq_start, d_rows, ids, targets, out_index, states, actions, action_len,
+                                             P, K, A, r0, nr, vocab, err_flag);
 }
 
 }  // namespace bf16

@@ -204,7 +204,11 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave & 1, wm = wave >> 1;
-  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles;
+  int nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  // rows packed on the device: only the row blocks that hold tokens are walked (the operand layout keeps the
+  // stride of the full capacity)
+  if (a.d_rows) nb_m = min(nb_m, (*a.d_rows + kBlkTiles * 16 - 1) / (kBlkTiles * 16));
   // persistent workgroup: launch indices blockIdx.x, + gridDim.x, ... (gridDim.x is a multiple of 8, so all
   // of them map to the same XCD); indices that name no block are skipped
   const int total = 8 * ((((nb_m + 7) / 8) + kBand - 1) / kBand) * kBand * nb_n;
@@ -302,6 +306,7 @@ __global__ __launch_bounds__(256, 1) void k_lmhead_lds(ScoreHeadArgs a, int slic
   const Block blk = block_of(blockIdx.x, slices, nb_m);
   if (!blk.valid) return;  // whole workgroup
   const int mt_base = blk.mb * kBlkTiles;
+  if (a.d_rows && mt_base * 16 >= *a.d_rows) return;  // rows packed on the device: this block holds no token
   const int col = lane & 31, rh = (lane >> 5) * 4;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   // The per-row running results live in LDS behind the ring (28 words per thread, word-interleaved over the

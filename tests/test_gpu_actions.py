@@ -27,6 +27,8 @@ CASES = [
     ("bf16-hd64-tied", inputs.ModelConfig(2, 512, 8, 2, 64, 1024, 2048, dtype="bf16", tie_embeddings=True), 0.05,
      LOGP_TOL_BF16, 2, 45, 6, 9, 1, False),
     ("bf16-long-state", GQA6, 0.04, LOGP_TOL_BF16, 1, 300, 3, 5, 1, False),         # several 256-key blocks of context
+    ("bf16-chunked", SMALL, 0.05, LOGP_TOL_BF16, 5, 20, 200, 170, 0, False),        # 1000 candidates: packed in 2 chunks
+    ("bf16-one-token-actions", GQA6, 0.05, LOGP_TOL_BF16, 3, 30, 40, 1, 0, False),  # A = 1: a candidate is one token or empty
 ]
 
 
@@ -78,6 +80,24 @@ def test_actions_agree_with_the_scoring_pass_and_ignore_padding(lib):
         live = np.arange(A)[None, None, :] < lens[:, :, None]
         assert np.abs(np.where(live, s - tok.cpu().numpy(), 0.0)).max() <= 2 * LOGP_TOL_BF16
         lib.mtmc_poll_errors(handle)
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+def test_all_candidates_empty(lib):
+    """No candidate has a token: nothing is evaluated in the second pass; every score is 0 and the policy uniform."""
+    import torch
+    cfg = SMALL
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        states = torch.from_numpy(inputs.make_prompts(2, 19, cfg.vocab, seed=1)).cuda()
+        actions, lens = inputs.make_actions(2, 4, 6, cfg.vocab, seed=2)
+        tok, act, pol = lib.mtmc_score_actions(handle, states, torch.from_numpy(actions).cuda(),
+                                               torch.zeros((2, 4), dtype=torch.int32, device="cuda"))
+        lib.mtmc_poll_errors(handle)
+        assert torch.all(tok == 0) and torch.all(act == 0)
+        assert torch.allclose(pol, torch.full_like(pol, float(-np.log(4.0))), atol=1e-6)
     finally:
         lib.mtmc_weights_destroy(handle)
 
