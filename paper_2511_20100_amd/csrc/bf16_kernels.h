@@ -80,6 +80,19 @@ struct DecGemmArgs {
   int* err_flag;         // RESID / SWIGLU: raised when a value written as fp16 does not fit
 };
 enum { DEC_STORE = 0, DEC_RESID = 1, DEC_SWIGLU = 2, DEC_SAMPLE = 3, DEC_PARTIAL = 4 };
+// One partial result of the sampling LM head: the state of a row over one workgroup's vocabulary slice.
+struct DecSamplePartial {
+  float m, s, y;   // log-sum-exp state (maximum, sum), largest perturbed logit
+  int idx;         // its vocabulary index
+  float zt;        // its unperturbed logit / T
+  float pad[3];
+};
+// 65..128 rows (decode_rows128.hip): every wavefront of a workgroup owns its own weight row tiles and all the rows,
+// the wavefronts walk K together and share the activation operand through LDS.  Returns false when the launch is
+// one it does not take (the caller then uses the general form).  The wide launches (gate/up, down, LM head) give a
+// workgroup kRows128WideTiles weight row tiles.
+constexpr int kRows128WideTiles = 8;
+bool gemm_dec_rows128(const DecGemmArgs& a, int epi, hipStream_t st);
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
                   h16_t* x, float* ss_out, int M, int* err_flag, hipStream_t st);
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);

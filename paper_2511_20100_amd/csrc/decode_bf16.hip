@@ -111,14 +111,8 @@ struct DecStream {
 
 __device__ __forceinline__ float silu_d(float g) { return g / (1.0f + expf(-g)); }
 
-enum { DEPI_STORE = 0, DEPI_RESID = 1, DEPI_SWIGLU = 2, DEPI_SAMPLE = 3, DEPI_PARTIAL = 4 };
-
-struct DecSamplePartial {
-  float m, s, y;
-  int idx;
-  float zt;
-  float pad[3];
-};
+enum { DEPI_STORE = DEC_STORE, DEPI_RESID = DEC_RESID, DEPI_SWIGLU = DEC_SWIGLU, DEPI_SAMPLE = DEC_SAMPLE,
+       DEPI_PARTIAL = DEC_PARTIAL };
 
 template <int NB, int MB, int WAVES, int PFW, int PFX, int MINW, int EPI, int NBP = NB>
 __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
@@ -477,11 +471,14 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
   }
 }
 
-int dec_wide_nb(int) { return 4; }
+// Weight row tiles per workgroup of the wide launches (what the sampler's partial results are counted in).
+int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? kRows128WideTiles : 4; }
 
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
   const bool wide = (epi == DEPI_SWIGLU || epi == DEPI_SAMPLE || epi == DEPI_PARTIAL);
   const int mb = a.m_tiles <= 1 ? 1 : a.m_tiles <= 2 ? 2 : a.m_tiles <= 4 ? 4 : 8;
+  // 65..128 rows: the form whose wavefronts share the activation operand through LDS (rows128)
+  if (mb == 8 && gemm_dec_rows128(a, epi, st)) return;
   if (wide) {
     switch (mb) {
       case 1: launch_dec_wide<1>(a, epi, st); break;
