@@ -26,11 +26,12 @@ from paper_2511_20100_amd import inputs  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
-# Counter summary that holds the HBM bytes one launch of the gate/up decode kernel moves at the 1.5B workload
+# Counter summary of a workload: holds the HBM bytes one launch of its gate/up decode kernel moves
 # (FETCH_SIZE / WRITE_SIZE runs scaled by the library's copy kernel), with the hash of the kernel sources the
 # counters were taken on: `traffic` is reported only while those sources are unchanged.
-TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "decode_kernels_1p5b_hbm_counters.txt")
-DECODE_KERNEL_SOURCES = ("decode_bf16.hip", "frag.h", "bf16_kernels.h", "attention_core.h", "device_utils.h")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "decode_kernels_{workload}_hbm_counters.txt")
+DECODE_KERNEL_SOURCES = ("decode_bf16.hip", "decode_rows128.hip", "frag.h", "bf16_kernels.h", "attention_core.h",
+                         "device_utils.h")
 
 
 def decode_sources_hash() -> str:
@@ -42,12 +43,12 @@ def decode_sources_hash() -> str:
     return h.hexdigest()[:16]
 
 
-def gate_up_traffic_from_profile():
-    """Bytes per launch from the committed counter summary, or None when the summary is missing, has no
-    machine-readable line, or was taken on other kernel sources than the ones in the tree."""
+def gate_up_traffic_from_profile(workload):
+    """Bytes per launch from the workload's committed counter summary, or None when the summary is missing, has
+    no machine-readable line, or was taken on other kernel sources than the ones in the tree."""
     import re
     try:
-        text = open(TRAFFIC_PROFILE).read()
+        text = open(TRAFFIC_PROFILE.format(workload=workload)).read()
     except OSError:
         return None
     m = re.search(r"^gate_up_traffic_bytes_per_launch:\s*([0-9.]+)\s+decode_sources_sha256_16:\s*([0-9a-f]{16})", text, re.M)
@@ -369,8 +370,9 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": gate_up_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gate_up_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                     "attainable": hbm_attainable,
-                    "traffic": gate_up_traffic_from_profile() if args.workload == "1p5b" else None,
-                    "kernel": "k_gemm_dec<..., SWIGLU> (gate/up projection, one launch per layer per decode step)",
+                    "traffic": gate_up_traffic_from_profile(args.workload),
+                    "kernel": "gate/up projection of a decode step, one launch per layer (k_gemm_dec<..., SWIGLU> up to "
+                              "64 rows, k_gemm_rows128<..., SWIGLU> at 65..128)",
                     "bytes_per_launch": gate_up_bytes, "us_per_launch": k_us, "timed_launches": k_launches,
                     "empty_event_pair_us": 1e3 * k_empty_ms}
     else:
