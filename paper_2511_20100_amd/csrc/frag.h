@@ -55,6 +55,13 @@ __device__ __forceinline__ uint32_t pack_h16x2_flag(float lo, float hi, int* err
   return pack_h16x2(lo, hi);
 }
 
+// The same for an epilogue that converts many values: the out-of-range test is collected in a per-lane flag that the
+// caller raises once at its end (one atomic per kernel part instead of a branch per pair).
+__device__ __forceinline__ uint32_t pack_h16x2_track(float lo, float hi, bool& out_of_range) {
+  out_of_range |= !fits_h16(lo) | !fits_h16(hi);
+  return pack_h16x2(lo, hi);
+}
+
 // For values known to lie inside the fp16 range (probabilities in [0, 1]): no clamp.
 __device__ __forceinline__ uint32_t pack_h16x2_inrange(float lo, float hi) {
   const v2h v = {(_Float16)lo, (_Float16)hi};

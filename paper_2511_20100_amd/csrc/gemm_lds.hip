@@ -245,6 +245,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
       }
   };
   if (EPI == LEPI_ADD) fetch_old(0, old[0]);
+  bool out_of_range = false;  // SwiGLU form: a product that does not fit fp16 (reported once per block, below)
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb) {
     if (EPI == LEPI_ADD && nb + 1 < 4) fetch_old(nb + 1, old[(nb + 1) & 1]);
@@ -262,10 +263,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
         for (int q = 0; q < 2; ++q) {
           const int fo = (n0 >> 1) + 8 * q + rh;
           uint2 pk;
-          pk.x = pack_h16x2_flag(silu_l(acc[nb][mb][4 * q + 0]) * acc[nb][mb][4 * q + 8],
-                                 silu_l(acc[nb][mb][4 * q + 1]) * acc[nb][mb][4 * q + 9], a.err_flag);
-          pk.y = pack_h16x2_flag(silu_l(acc[nb][mb][4 * q + 2]) * acc[nb][mb][4 * q + 10],
-                                 silu_l(acc[nb][mb][4 * q + 3]) * acc[nb][mb][4 * q + 11], a.err_flag);
+          pk.x = pack_h16x2_track(silu_l(acc[nb][mb][4 * q + 0]) * acc[nb][mb][4 * q + 8],
+                                  silu_l(acc[nb][mb][4 * q + 1]) * acc[nb][mb][4 * q + 9], out_of_range);
+          pk.y = pack_h16x2_track(silu_l(acc[nb][mb][4 * q + 2]) * acc[nb][mb][4 * q + 10],
+                                  silu_l(acc[nb][mb][4 * q + 3]) * acc[nb][mb][4 * q + 11], out_of_range);
           *reinterpret_cast<uint2*>(a.out_bf16 + act_off(m, fo, Mpad)) = pk;
         }
       } else {
@@ -290,6 +291,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
       }
     }
   }
+  if (EPI == LEPI_SWIGLU && out_of_range) atomicOr(a.err_flag, kErrFp16Range);
 };
   lds_gemm_stream(reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles, a.m_tiles,
                   a.k_tiles, lds, lane, __builtin_amdgcn_readfirstlane(wave), wn, wm, tile_at, epilogue);

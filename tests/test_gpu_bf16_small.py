@@ -384,6 +384,25 @@ def test_values_beyond_the_fp16_range_are_reported(lib):
         assert e.value.code == lib.MTMC_EDATA and "fp16 range" in str(e.value)
     finally:
         lib.mtmc_weights_destroy(handle)
+    # the same for a SwiGLU product: one row of W_up and of W_gate at 2e4 per entry, so that silu(g) u of that feature
+    # leaves the range for every token whose x has a positive sum (and some do); the scoring pass is run on each of
+    # its two GEMM kernels (the LDS-staged one collects the test per output block and raises the flag once)
+    w = inputs.make_weights(cfg, seed=1, std=0.05, gain_std=0.1)
+    for name in ("layers.0.wup", "layers.0.wgate"):
+        big = inputs.bf16_bits_to_f32(w.tensors[name]).copy()
+        big[7, :] = 2.0e4
+        w.tensors[name] = inputs.f32_to_bf16_bits(big)
+    w.drop_cache()
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        for min_blocks in (1, 1 << 20):
+            lib.mtmc_set_option(handle, lib.MTMC_OPT_GEMM_LDS_MIN_BLOCKS, min_blocks)
+            lib.mtmc_score(handle, seqs, 8)
+            with pytest.raises(lib.MtmcError) as e:
+                lib.mtmc_poll_errors(handle)
+            assert e.value.code == lib.MTMC_EDATA and "fp16 range" in str(e.value), min_blocks
+    finally:
+        lib.mtmc_weights_destroy(handle)
 
 
 def test_lds_gemm_at_its_shortest_reduction(lib):
