@@ -89,8 +89,9 @@ struct DecSamplePartial {
 };
 // 65..128 rows (decode_rows128.hip): every wavefront of a workgroup owns its own weight row tiles and all the rows,
 // the wavefronts walk K together and share the activation operand through LDS.  Returns false when the launch is
-// one it does not take (the caller then uses the general form).  The wide launches (gate/up, down, LM head) give a
-// workgroup kRows128WideTiles weight row tiles.
+// one it does not take (the caller then uses the general form).  The down projection and the LM head give a
+// workgroup kRows128WideTiles weight row tiles (the host sizes the split-K factor and the sampler's partial results
+// by that); the gate/up launch picks its own shape, 8 to 16 tiles, so that the launch is one round on the CUs.
 constexpr int kRows128WideTiles = 8;
 bool gemm_dec_rows128(const DecGemmArgs& a, int epi, hipStream_t st);
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,

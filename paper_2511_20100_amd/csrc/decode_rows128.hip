@@ -41,13 +41,14 @@ __device__ __forceinline__ void wait_vm() {
 __device__ __forceinline__ float silu_r(float g) { return g / (1.0f + expf(-g)); }
 
 // NBW weight row tiles per wavefront, WAVES wavefronts per workgroup.
-template <int NBW, int WAVES, int EPI>
-__global__ __launch_bounds__(WAVES * 64, 2) void k_gemm_rows128(DecGemmArgs a) {
+template <int NBW, int WAVES, int EPI, int MINB>
+__global__ __launch_bounds__(WAVES * 64, MINB) void k_gemm_rows128(DecGemmArgs a) {
   static_assert(EPI == DEC_SWIGLU || EPI == DEC_PARTIAL || EPI == DEC_SAMPLE, "the wide launches only");
-  static_assert((kKT * kMB) % WAVES == 0, "the copies of a stage are split evenly over the wavefronts");
   static_assert(EPI != DEC_SWIGLU || NBW % 2 == 0, "gate and up tiles come in pairs");
   constexpr int NT = WAVES * 64;
-  constexpr int XC = kKT * kMB / WAVES;             // 1 KiB copies per wavefront and step
+  // 1 KiB copies per wavefront and step: every wavefront issues the same number (the waits count operations), so
+  // when WAVES does not divide the stage's 16 blocks the last wavefronts copy the last block more than once
+  constexpr int XC = (kKT * kMB + WAVES - 1) / WAVES;
   constexpr int OPS = XC + kKT * NBW;               // vector-memory operations a wavefront issues per step
   static_assert((kD - 1) * OPS < 64, "the wait counts the operations of kD - 1 steps");
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_gemm_rows128(DecGemmArgs a) {
       uint8_t* stage = lds + (step % kNSX) * kXStageBytes;
 #pragma unroll
       for (int i = 0; i < XC; ++i) {
-        const int c = wave * XC + i, t = c / kMB, mt = c % kMB;
+        const int c = min(wave * XC + i, kKT * kMB - 1), t = c / kMB, mt = c % kMB;
         const int kk = min(kbeg + step * kKT + t, klast);
         __builtin_amdgcn_global_load_lds((glb_ptr_t)(xsrc + ((size_t)kk * a.m_tiles + min(mt, a.m_tiles - 1)) * 512),
                                          (lds_ptr_t)(stage + c * 1024), 16, 0, 0);
@@ -289,17 +290,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_gemm_rows128(DecGemmArgs a) {
   }
 }
 
-template <int NBW, int WAVES, int EPI>
+template <int NBW, int WAVES, int EPI, int MINB = 2>
 void launch_rows128(const DecGemmArgs& a, hipStream_t st) {
   static bool configured = false;  // per process; the attribute is a property of the function
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows128<NBW, WAVES, EPI>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows128<NBW, WAVES, EPI, MINB>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kXRingBytes);
     configured = true;
   }
   const int per_wg = NBW * WAVES;
   const dim3 grid((a.n_tiles + per_wg - 1) / per_wg, EPI == DEC_PARTIAL ? a.ksplit : 1);
-  k_gemm_rows128<NBW, WAVES, EPI><<<grid, WAVES * 64, kXRingBytes, st>>>(a);
+  k_gemm_rows128<NBW, WAVES, EPI, MINB><<<grid, WAVES * 64, kXRingBytes, st>>>(a);
 }
 
 }  // namespace
@@ -311,7 +312,17 @@ bool gemm_dec_rows128(const DecGemmArgs& a, int epi, hipStream_t st) {
   // 7 B shape), and fewer tiles per workgroup bring back the activation reads this form exists to avoid.
   if (epi == DEC_STORE || epi == DEC_RESID) return false;
   switch (epi) {
-    case DEC_SWIGLU: launch_rows128<kRows128WideTiles / 4, 4, DEC_SWIGLU>(a, st); return true;
+    case DEC_SWIGLU: {
+      // One round on the 256 CUs with as many workgroups as that allows: a CU that hosts two workgroups pulls two
+      // activation copies and takes nearly twice as long, and workgroups of more tiles leave CUs idle (7 B shape,
+      // 2368 tiles: 8 tiles x 296 workgroups 89 us, 10 x 237 67 us, 12 x 198 69 us, 16 x 148 76 us).
+      const auto groups = [&](int waves) { return (a.n_tiles + 2 * waves - 1) / (2 * waves); };
+      if (groups(4) <= 256) launch_rows128<2, 4, DEC_SWIGLU>(a, st);
+      else if (groups(5) <= 256) launch_rows128<2, 5, DEC_SWIGLU, 1>(a, st);
+      else if (groups(6) <= 256) launch_rows128<2, 6, DEC_SWIGLU, 1>(a, st);
+      else launch_rows128<2, 8, DEC_SWIGLU, 1>(a, st);
+      return true;
+    }
     case DEC_PARTIAL: launch_rows128<kRows128WideTiles / 4, 4, DEC_PARTIAL>(a, st); return true;
     case DEC_SAMPLE: launch_rows128<kRows128WideTiles / 4, 4, DEC_SAMPLE>(a, st); return true;
     default: return false;

@@ -15,6 +15,8 @@ GQA7 = inputs.ModelConfig(1, 512, 7, 1, 128, 1536, 2064, dtype="bf16")      # G 
 MHA = inputs.ModelConfig(2, 256, 2, 2, 128, 512, 2048, dtype="bf16")        # G = 1: every query head has its own kv head
 GQA4 = inputs.ModelConfig(1, 512, 4, 1, 128, 1024, 2048, dtype="bf16")
 GQA8 = inputs.ModelConfig(1, 1024, 8, 1, 128, 1024, 2048, dtype="bf16")     # the widest group the kernels take
+FFN_W6 = inputs.ModelConfig(1, 256, 2, 1, 128, 22016, 2048, dtype="bf16")   # 2752 gate/up row tiles: 12 per workgroup at 65..128 rows
+FFN_W8 = inputs.ModelConfig(1, 256, 2, 1, 128, 25600, 2048, dtype="bf16")   # 3200 gate/up row tiles: 16 per workgroup
 HD64 = inputs.ModelConfig(2, 256, 4, 2, 64, 688, 4096, dtype="bf16")        # head_dim 64
 HD64_TIED = inputs.ModelConfig(2, 512, 8, 2, 64, 1024, 2048, dtype="bf16", tie_embeddings=True)  # G = 4, tied LM head
 CASES = [
@@ -31,6 +33,8 @@ CASES = [
     ("gqa6-b40", GQA6, 0.05, 5, 21, 8, 12, 1.0),          # three row tiles: the second workgroup of a row split holds one
     ("gqa4-b100", GQA4, 0.05, 25, 18, 4, 10, 1.0),        # seven row tiles of the 128-row form
     ("gqa6-b128", GQA6, 0.04, 16, 16, 8, 12, 1.0),
+    ("ffn-w6-b100", FFN_W6, 0.02, 25, 12, 4, 6, 1.0),     # gate/up workgroups of 6 wavefronts (5 at the 7 B width: test_gpu_7b_shape)
+    ("ffn-w8-b128", FFN_W8, 0.02, 16, 12, 8, 6, 1.0),     # ... of 8 wavefronts
     ("gqa6-two-groups", GQA6, 0.04, 18, 9, 8, 6, 1.0),
     ("small-greedy", SMALL, 0.05, 2, 16, 1, 10, 0.0),
     ("small-one-token", SMALL, 0.05, 1, 1, 2, 4, 1.0),
