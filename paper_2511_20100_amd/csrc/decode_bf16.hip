@@ -498,7 +498,16 @@ void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
       // workgroups of 64 rows per pair of tiles; behind a context-split attention the form that combines chunks
       default:
         if (epi == DEPI_RESID && a.n_xchunks > 1) launch_dec_narrow<2>(a, epi, st, (a.m_tiles + 1) / 2);
-        else launch_dec_t<2, 4, 8, 2, 2, 1>(a, epi, st, 2);
+        // ... in one round on the 256 CUs: a CU that hosts two of these workgroups takes twice as long, so a launch of
+        // more than 128 pairs of tiles takes three tiles per workgroup
+        else if ((a.n_tiles + 1) / 2 * 2 <= 256) launch_dec_t<2, 4, 8, 2, 2, 1>(a, epi, st, 2);
+        else {
+          DecGemmArgs a3 = a;
+          a3.row_pairs = 0;
+          const dim3 grid((a.n_tiles + 2) / 3, 2), block(8 * 64);
+          if (epi == DEPI_STORE) k_gemm_dec<3, 4, 8, 2, 2, 1, DEPI_STORE><<<grid, block, 0, st>>>(a3);
+          else k_gemm_dec<3, 4, 8, 2, 2, 1, DEPI_RESID><<<grid, block, 0, st>>>(a3);
+        }
         break;
     }
   }
