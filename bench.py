@@ -431,6 +431,28 @@ def main() -> int:
                                                 f"1..{A} tokens per action", "ms": a_ms,
                                     "actions_per_s": n_prompts * K / (a_ms * 1e-3)}
         del ws_a
+        if not args.no_rollout and not args.no_score:
+            # beside the step as well: the scoring of the step's own sequences through mtmc_score_actions, with the
+            # prompts as states and each prompt's samples as its candidates, so that a prompt is evaluated once instead
+            # of once per sample (the same log-probs, bit for bit, wherever both routes run the same matrix kernels)
+            cont = out_ids.reshape(n_prompts, n_samples, max_new)
+            full = torch.full((n_prompts, n_samples), max_new, dtype=torch.int32, device=dev)
+            ws_a = torch.empty(mtmc.mtmc_score_actions_workspace_bytes(handle, n_prompts, prompt_len, n_samples, max_new),
+                               dtype=torch.uint8, device=dev)
+            tok = mtmc.mtmc_score_actions(handle, prompts, cont, full, workspace=ws_a)[0]
+            ev[0].record(stream)
+            for _ in range(2):
+                tok = mtmc.mtmc_score_actions(handle, prompts, cont, full, workspace=ws_a)[0]
+            ev[1].record(stream)
+            ev[1].synchronize()
+            mtmc.mtmc_poll_errors(handle)
+            ref = score_lp[:, prompt_len - 1:]
+            result["scoring_with_shared_prompts"] = {
+                "call": "mtmc_score_actions(states = the prompts, candidates = each prompt's samples)",
+                "ms": ev[0].elapsed_time(ev[1]) / 2, "ms_mtmc_score": s_ms,
+                "same_bits_as_mtmc_score": bool(torch.equal(tok.reshape(B, max_new), ref)),
+                "max_difference": float((tok.reshape(B, max_new) - ref).abs().max())}
+            del ws_a
     if args.workload == "1p5b" and not args.no_inference_legs and not args.no_rollout:
         result["inference"] = inference_legs(torch, mtmc, dev, handle, weights, cfg, prompts, n_samples, max_new, progress)
     if not args.no_cpu_baseline:

@@ -204,6 +204,9 @@ int mtmc_score(const mtmc_weights* w, const int32_t* seqs, int32_t n_seqs, int32
  *     out_policy_logprobs[n, k]   = out_action_logprobs[n, k] - logsumexp_j out_action_logprobs[n, j]
  * An empty action (N = 0) has log-probability 0.  The state is evaluated once per state, not once
  * per candidate: the K candidates of a state read the same cached keys and values of its tokens.
+ * Scoring what mtmc_rollout returned is the case states = the prompts, candidates = the samples of each
+ * prompt, every action_len = max_new: out_token_logprobs is then what mtmc_score returns from position
+ * prompt_len - 1 on, with each prompt evaluated once instead of once per sample.
  *
  * states       device int32 [n_states, state_len], state_len >= 1
  * actions      device int32 [n_states, n_actions, max_action_len]; padding entries are ignored
