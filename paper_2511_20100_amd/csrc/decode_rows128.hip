@@ -251,13 +251,17 @@ __global__ __launch_bounds__(WAVES * 64, MINB) void k_gemm_rows128(DecGemmArgs a
         if (!ctl.greedy)
           rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + row, 0u), ctl.key0, ctl.key1);
         const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
+        float zt[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float z = acc[nb][mb][r] * sc;
-          const float zt = ctl.greedy ? z : z * ctl.inv_temp;
-          lse_push(lse, zt);
-          const float y = ctl.greedy ? zt : zt + gumbel_from_bits(rr[r]);
-          if (y > by) { by = y; bi = v0 + r; bz = zt; }  // ascending index: the first maximum wins
+          zt[r] = ctl.greedy ? z : z * ctl.inv_temp;
+        }
+        lse_push4(lse, zt[0], zt[1], zt[2], zt[3]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float y = ctl.greedy ? zt[r] : zt[r] + gumbel_from_bits(rr[r]);
+          if (y > by) { by = y; bi = v0 + r; bz = zt[r]; }  // ascending index: the first maximum wins
         }
       }
 #pragma unroll

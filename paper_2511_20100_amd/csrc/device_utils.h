@@ -48,9 +48,9 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1
   constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
-    const uint32_t hi0 = __umulhi(M0, c.x), lo0 = M0 * c.x;
-    const uint32_t hi1 = __umulhi(M1, c.z), lo1 = M1 * c.z;
-    c = make_uint4(hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0);
+    // one 32 x 32 -> 64 bit product per multiplier (a single multiply instruction gives both halves)
+    const uint64_t p0 = (uint64_t)M0 * c.x, p1 = (uint64_t)M1 * c.z;
+    c = make_uint4((uint32_t)(p1 >> 32) ^ c.y ^ k0, (uint32_t)p1, (uint32_t)(p0 >> 32) ^ c.w ^ k1, (uint32_t)p0);
     k0 += W0;
     k1 += W1;
   }
@@ -58,9 +58,13 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1
 }
 
 // u = ((r >> 9) + 1/2) 2^-23 lies strictly inside (0, 1) and is exact in fp32; g = -ln(-ln u).
+// Both logarithms are the hardware's base-2 logarithm (1 ulp) times ln 2: u and -ln u (6e-8 .. 16.7) are normal
+// numbers, so none of the library routine's range fix-ups is needed; g is within about 2e-6 of the exact value.
 __device__ __forceinline__ float gumbel_from_bits(uint32_t r) {
+  constexpr float kLn2 = 0.6931471805599453f;
   const float u = ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f;
-  return -logf(-logf(u));
+  const float l = -kLn2 * __builtin_amdgcn_logf(u);
+  return -kLn2 * __builtin_amdgcn_logf(l);
 }
 
 // Online log-sum-exp state (m = running max, s = sum of exp(x - m)).
@@ -75,6 +79,22 @@ __device__ __forceinline__ void lse_push(Lse& a, float x) {
   } else {
     a.s += expf(x - a.m);
   }
+}
+// The same for four values at once, without branches: the new maximum first, then the old sum and the four terms
+// rescaled to it with the hardware's 2^x (relative error about 1e-7 per term; every argument is <= 0).  An empty
+// state (m = -inf, s = 0) and values of -inf contribute exp2(-inf) = 0; the four values must not all be -inf while
+// the state is empty.
+__device__ __forceinline__ void lse_push4(Lse& a, float x0, float x1, float x2, float x3) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  const float m = fmaxf(fmaxf(a.m, fmaxf(x0, x1)), fmaxf(x2, x3));
+  const float mk = m * kLog2e;
+  float s = a.s * __builtin_amdgcn_exp2f(fmaf(a.m, kLog2e, -mk));
+  s += __builtin_amdgcn_exp2f(fmaf(x0, kLog2e, -mk));
+  s += __builtin_amdgcn_exp2f(fmaf(x1, kLog2e, -mk));
+  s += __builtin_amdgcn_exp2f(fmaf(x2, kLog2e, -mk));
+  s += __builtin_amdgcn_exp2f(fmaf(x3, kLog2e, -mk));
+  a.m = m;
+  a.s = s;
 }
 __device__ __forceinline__ Lse lse_merge(Lse a, Lse b) {
   if (b.s == 0.f) return a;
