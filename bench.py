@@ -30,7 +30,7 @@ MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense 16-bit MFMA rate
 # (FETCH_SIZE / WRITE_SIZE runs scaled by the library's copy kernel), with the hash of the kernel sources the
 # counters were taken on: `traffic` is reported only while those sources are unchanged.
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "decode_kernels_{workload}_hbm_counters.txt")
-DECODE_KERNEL_SOURCES = ("decode_bf16.hip", "decode_rows128.hip", "frag.h", "bf16_kernels.h", "attention_core.h",
+DECODE_KERNEL_SOURCES = ("decode_bf16.hip", "decode_rows128.hip", "decode_lmhead.hip", "frag.h", "bf16_kernels.h", "attention_core.h",
                          "device_utils.h")
 
 

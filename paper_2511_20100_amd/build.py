@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmtmc.so")
 SOURCES = ["api.hip", "engine.hip", "engine_bf16.hip", "kernels_f32.hip", "ppo.hip", "probes.hip", "gemm_bf16.hip", "gemm_lds.hip",
-           "attention_prefill.hip", "elementwise_bf16.hip", "decode_bf16.hip", "decode_rows128.hip"]
+           "attention_prefill.hip", "elementwise_bf16.hip", "decode_bf16.hip", "decode_rows128.hip", "decode_lmhead.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -98,6 +98,12 @@ void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, cons
                   h16_t* x, float* ss_out, int M, int* err_flag, hipStream_t st);
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st);
 int dec_wide_nb(int m_tiles);
+// Sampling LM head (decode_lmhead.hip): the persistent form for up to 64 rows and the model widths it is built for.
+// lmhead_sample_persistent_groups = partial results per row that launch leaves (0: the launch is not taken);
+// dec_sample_groups = the same for whichever form gemm_dec(.., DEC_SAMPLE) runs (what sample_merge must be told).
+int lmhead_sample_persistent_groups(int n_tiles, int k_tiles, int m_tiles);
+bool lmhead_sample_persistent(const DecGemmArgs& a, hipStream_t st);
+int dec_sample_groups(int n_tiles, int k_tiles, int m_tiles);
 // What the sampler merge prepares for the next decode step from the token it has just chosen for a row: the
 // residual h = E[token], x' = fp16(RMSNorm(h; gain)) in tiled layout (Mpad rows) and the per-tile sums of squares.
 struct EmbedNextArgs {

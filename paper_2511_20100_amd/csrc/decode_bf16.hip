@@ -477,12 +477,19 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
 
 // Weight row tiles per workgroup of the wide launches (what the sampler's partial results are counted in).
 int dec_wide_nb(int m_tiles) { return m_tiles > 4 ? kRows128WideTiles : 4; }
+int dec_sample_groups(int n_tiles, int k_tiles, int m_tiles) {
+  const int persistent = lmhead_sample_persistent_groups(n_tiles, k_tiles, m_tiles);
+  if (persistent > 0) return persistent;
+  return (n_tiles + dec_wide_nb(m_tiles) - 1) / dec_wide_nb(m_tiles);
+}
 
 void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
   const bool wide = (epi == DEPI_SWIGLU || epi == DEPI_SAMPLE || epi == DEPI_PARTIAL);
   const int mb = a.m_tiles <= 1 ? 1 : a.m_tiles <= 2 ? 2 : a.m_tiles <= 4 ? 4 : 8;
   // 65..128 rows: the form whose wavefronts share the activation operand through LDS (rows128)
   if (mb == 8 && gemm_dec_rows128(a, epi, st)) return;
+  // sampling LM head up to 64 rows: the persistent form where the model width allows it
+  if (epi == DEPI_SAMPLE && mb <= 4 && lmhead_sample_persistent(a, st)) return;
   if (wide) {
     switch (mb) {
       case 1: launch_dec_wide<1>(a, epi, st); break;

@@ -585,7 +585,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       lm.inv_d = 1.0f / (float)D.d; lm.eps = c.rms_eps; lm.out_f32 = p.lm_part;
       lm.ctl = (const bf16::SampleCtl*)p.ctl; lm.d_step = p.d_step;
       bf16::gemm_dec(lm, bf16::DEC_SAMPLE, s);
-      const int groups = (D.nt_V + bf16::dec_wide_nb(q.bt) - 1) / bf16::dec_wide_nb(q.bt);
+      const int groups = bf16::dec_sample_groups(D.nt_V, D.kt_d, q.bt);
       // also ++*d_step, and the embedding + first norm of the chosen tokens: the next step starts at its QKV projection
       bf16::sample_merge(p.lm_part, groups, q.B, (const bf16::SampleCtl*)p.ctl, p.d_step, p.cur_ids, embed_args(q), s);
     };
