@@ -66,7 +66,9 @@ struct DecGemmArgs {
   const int* d_step;
   int ksplit;            // PARTIAL: K splits (grid.y); out_f32 = partial sums [ksplit][m_tiles*16][ld_out]
   float* rs_out;         // PARTIAL: 1/rms of every row of the state described by ss_cur
-  int partial_nb;        // PARTIAL, up to 64 rows: 2 = two weight row tiles and 8 wavefronts per workgroup, else four and 4
+  int partial_nb;        // PARTIAL, up to 64 rows: 2 = two weight row tiles and 8 wavefronts per workgroup, 3 = three
+                         // and 5 with ksplit = 8 aligned to the XCDs, else four and 4
+  int xcd_split;         // set by the launcher of the XCD-aligned form
   // RESID with n_xchunks > 1 (O projection behind a context-split attention): Xt holds n_xchunks operands
   // x_chunk_stride elements apart, each the attention output over one chunk of the context, normalised by itself;
   // chunk_ml [M][k_tiles / head_tiles][n_xchunks][2] = (running maximum, sum) of row, head, chunk.  The product is

@@ -126,6 +126,16 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // weight row tiles nt0 .. nt0 + NB - 1 (group grp of n_groups), token tiles mt0 .. mt0 + MB - 1: the launch may
   // split the rows over gridDim.y (split-K uses that index itself) or over pairs of workgroups along x
   int grp = blockIdx.x, n_groups = gridDim.x, mpart = (EPI == DEPI_PARTIAL) ? 0 : blockIdx.y;
+  // split-K: this workgroup's K split and their number.  XCD-aligned form (8 splits, one-dimensional grid): workgroups
+  // go to the 8 XCDs round-robin in launch order, so split s = launch index % 8 runs on XCD s alone and every XCD's
+  // L2 fetches one eighth of the activation operand instead of all of it
+  int ksp = blockIdx.y, nsp = gridDim.y;
+  if (EPI == DEPI_PARTIAL && a.xcd_split) {
+    ksp = blockIdx.x & 7;
+    nsp = 8;
+    grp = blockIdx.x >> 3;
+    n_groups = gridDim.x >> 3;
+  }
   if (a.row_pairs) {
     grp = (blockIdx.x >> 4) * 8 + (blockIdx.x & 7);
     mpart = (blockIdx.x >> 3) & 1;
@@ -140,7 +150,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // A split-K launch only needs them in the kernel that finishes the sum: its first workgroup
   // computes them on the side and leaves them in rs_out.
   constexpr bool kProducer = (EPI == DEPI_RESID || EPI == DEPI_PARTIAL);
-  const bool do_rs = EPI != DEPI_PARTIAL || (blockIdx.x == 0 && blockIdx.y == 0);  // workgroup-uniform (x 0: group 0, rows 0..)
+  const bool do_rs = EPI != DEPI_PARTIAL || (grp == 0 && ksp == 0);  // workgroup-uniform (x 0: group 0, rows 0..)
   constexpr int NT = WAVES * 64;
   constexpr int BT = (WAVES >= 8) ? 8 : 24;  // loads per batch (all tiles of d = 1536 in one batch)
   const int P = NT / Mpad;  // Mpad <= 128 <= NT
@@ -175,8 +185,8 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   // ---- operand streams: issued behind the row-scale loads, in flight while the scales are worked out
   int kbeg = 0, kend = a.k_tiles;
   if (EPI == DEPI_PARTIAL) {
-    const int per_split = (a.k_tiles + gridDim.y - 1) / gridDim.y;
-    kbeg = blockIdx.y * per_split;
+    const int per_split = (a.k_tiles + nsp - 1) / nsp;
+    kbeg = ksp * per_split;
     kend = min(a.k_tiles, kbeg + per_split);
   }
   const int per_wave = (max(kend - kbeg, 0) + WAVES - 1) / WAVES;
@@ -325,7 +335,7 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
   const float sc = (EPI == DEPI_PARTIAL) ? 1.f : s_scale[m];
 
   if (EPI == DEPI_PARTIAL) {
-    float* P = a.out_f32 + (size_t)blockIdx.y * Mpad * a.ld_out;
+    float* P = a.out_f32 + (size_t)ksp * Mpad * a.ld_out;
 #pragma unroll
     for (int nb = 0; nb < NBP; ++nb) {
       if (nbase + nb >= a.n_tiles) continue;
@@ -469,7 +479,14 @@ static void launch_dec_wide(const DecGemmArgs& a, int epi, hipStream_t st) {
     // every workgroup reads the whole activation operand, so a CU that hosts two workgroups takes about
     // twice as long as one that hosts one: one round of workgroups with 6 row tiles beats 1.x rounds with 4
     if (epi == DEPI_SWIGLU && a.n_tiles > 4 * 256 && a.n_tiles <= 6 * 256) launch_dec_t<6, MB, 8, 2, 2, 1, 2>(a, epi, st);
-    else if (epi == DEPI_PARTIAL && a.partial_nb == 2) launch_dec_t<2, MB, 8, 2, 2, 1>(a, epi, st);
+    else if (epi == DEPI_PARTIAL && a.partial_nb == 3) {
+      // 8 K splits, one per XCD; three row tiles and 5 wavefronts per workgroup, rings three deep (1.5 B shape: down
+      // projection 11.3 -> 10.6 us, HBM fetch of the launch 36.8 -> 29 MB; 7 wavefronts or rings two deep: 0.2 % slower)
+      DecGemmArgs x = a;
+      x.xcd_split = 1;
+      x.row_pairs = 0;
+      k_gemm_dec<3, MB, 5, 3, 3, 1, DEPI_PARTIAL, 3><<<dim3(8 * ((a.n_tiles + 2) / 3)), 5 * 64, 0, st>>>(x);
+    } else if (epi == DEPI_PARTIAL && a.partial_nb == 2) launch_dec_t<2, MB, 8, 2, 2, 1>(a, epi, st);
     else if (epi == DEPI_SAMPLE) launch_dec_t<4, MB, 4, 2, 2, 3, 2>(a, epi, st);  // three workgroups per CU
     else launch_dec_t<4, MB, 4, 2, 2, 2>(a, epi, st);
   }

@@ -274,6 +274,12 @@ DecodeTune tune_decode(const Dims& D, int B, int bt, int max_pages) {
   if (bt <= 4 && 4 * (D.kt_F / t.ks_down) < 256) {
     t.down_nb = 2;
     t.ks_down = std::max(1, std::min(256 / ((D.nt_d + 1) / 2), D.kt_F / 16));
+    // ... and where 8 splits of three-tile workgroups still are one round, the split is aligned to the 8 XCDs: each
+    // XCD then fetches its eighth of the activation operand (64 x F fp16) instead of all of it
+    if ((D.nt_d + 2) / 3 * 8 <= 256 && D.kt_F >= 8 * 10) {
+      t.down_nb = 3;
+      t.ks_down = 8;
+    }
   }
   // context split of the decode attention: for small batches up to about 128 workgroups of 8 wavefronts, and two
   // ways at 33..64 rows when that still leaves at most 256 workgroups (the O projection combines two chunks in its 12-wavefront form at little
