@@ -135,7 +135,8 @@ def cpu_baseline(weights, cfg, prompts, max_positions, score_only=False):
 
 def attainable_rates(torch, mtmc, dev):
     """What this GPU sustains, measured here: a plain streaming read of 2 GiB (GB/s) and a register-only loop of
-    fp16 32x32x16 matrix instructions on every SIMD (TFLOP/s)."""
+    fp16 32x32x16 matrix instructions on every SIMD, with the register tile of the scoring GEMM and pseudo-random
+    operands (TFLOP/s)."""
     stream = torch.cuda.current_stream()
     buf = torch.ones(2 << 30, dtype=torch.uint8, device=dev)
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -149,9 +150,9 @@ def attainable_rates(torch, mtmc, dev):
     read_gbs = 4 * buf.numel() / (e[0].elapsed_time(e[1]) * 1e-3) / 1e9
     del buf
     out = torch.empty(1024 * 256, dtype=torch.float32, device=dev)
-    mtmc.mtmc_mfma_probe(out, 1024, 2000)
+    mtmc.mtmc_mfma_probe(out, 1024, 500)
     e[0].record(stream)
-    flops = mtmc.mtmc_mfma_probe(out, 1024, 20000)
+    flops = mtmc.mtmc_mfma_probe(out, 1024, 5000)
     e[1].record(stream)
     e[1].synchronize()
     return read_gbs, flops / (e[0].elapsed_time(e[1]) * 1e-3) / 1e12
@@ -364,7 +365,8 @@ def main() -> int:
     read_gbs, mfma_tflops = attainable_rates(torch, mtmc, dev)
     hbm_attainable = {"value": read_gbs, "unit": "GB/s", "how": "plain streaming read of 2 GiB, measured in this run"}
     mfma_attainable = {"value": mfma_tflops, "unit": "TFLOP/s",
-                       "how": "register-only loop of fp16 32x32x16 matrix instructions on all SIMDs, measured in this run"}
+                       "how": "register-only loop of fp16 32x32x16 matrix instructions on all SIMDs (4 x 4 accumulator blocks per "
+                              "wavefront, pseudo-random operands), measured in this run"}
     if k_launches > 0:
         k_us = 1e3 * k_ms / k_launches
         roofline = {"bound": "hbm", "achieved": gate_up_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -344,9 +344,10 @@ int mtmc_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
  * Diagnostics for measurement: what the device sustains, to be reported beside its published peaks.
  * mtmc_read_probe reads `bytes` (a positive multiple of 16384; src device, 16-byte aligned) once with a plain
  * streaming kernel and discards them (sink: 4 writable device bytes).  mtmc_mfma_probe runs `iters` rounds of
- * four independent fp16 32x32x16 matrix instructions in every wavefront of `workgroups` workgroups of four
- * wavefronts, on registers only (out: device floats [workgroups * 256], overwritten), and returns in *flops
- * the floating-point operations of the launch.  Both are stream-ordered and do not synchronise: the caller
+ * sixteen fp16 32x32x16 matrix instructions (four A fragments times four B fragments of pseudo-random values, on
+ * sixteen accumulator blocks) in every wavefront of `workgroups` workgroups of four wavefronts, on registers
+ * only (out: device floats [workgroups * 256], overwritten), and returns in *flops the floating-point
+ * operations of the launch.  Both are stream-ordered and do not synchronise: the caller
  * brackets them with events.
  */
 int mtmc_read_probe(const void* src, size_t bytes, void* sink, void* stream);

@@ -27,29 +27,42 @@ __global__ __launch_bounds__(512) void k_read_probe(const pv4u* __restrict__ src
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) *sink = 1;  // keeps the loads alive
 }
 
-// One wavefront per SIMD, four independent 32 x 32 accumulators each: the issue pattern of the large-batch GEMM
-// without any memory traffic.
+// One wavefront per SIMD with the register tile of the large-batch GEMM and nothing else: 4 x 4 accumulator blocks
+// of 32 x 32, every trip multiplies four A fragments with four B fragments (16 instructions).  The fragments hold
+// pseudo-random values of both signs spread over the fp16 exponents that real operands have: what the matrix pipes
+// sustain depends on the data (the chip is power-limited there), and constant operands read about 40 % higher.
 __global__ __launch_bounds__(256, 1) void k_mfma_probe(float* out, int iters) {
-  pv16f acc[4];
+  pv16f acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-  pv8h a, b;
+    for (int k = 0; k < 4; ++k)
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (_Float16)((threadIdx.x & 7) * 0.125f);
-    b[i] = (_Float16)(1.0f - i * 0.125f);
-  }
+      for (int j = 0; j < 16; ++j) acc[i][k][j] = 0.f;
+  pv8h a[4], b[4];
+  uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      h ^= h << 13; h ^= h >> 17; h ^= h << 5;   // xorshift32
+      a[f][i] = (_Float16)(((int)(h & 0xffff) - 32768) * (1.0f / 32768.0f) * (1.0f + (float)((h >> 16) & 3)));
+      h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+      b[f][i] = (_Float16)(((int)(h & 0xffff) - 32768) * (0.05f / 32768.0f) * (1.0f + (float)((h >> 16) & 3)));
+    }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[i][k] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[k], acc[i][k], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) s += acc[i][j];
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s += acc[i][k][j];
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
@@ -64,8 +77,8 @@ void launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st
 
 double launch_mfma_probe(float* out, int workgroups, int iters, hipStream_t st) {
   k_mfma_probe<<<workgroups, 256, 0, st>>>(out, iters);
-  // 4 wavefronts x 4 instructions per trip, 2 * 32 * 32 * 16 flops each
-  return (double)workgroups * 4.0 * 4.0 * (double)iters * 32768.0;
+  // 4 wavefronts x 16 instructions per trip, 2 * 32 * 32 * 16 flops each
+  return (double)workgroups * 4.0 * 16.0 * (double)iters * 32768.0;
 }
 
 }  // namespace mtmc

@@ -41,3 +41,19 @@ def test_ppo_edge_cases():
     assert np.abs(wide[:3] - np.array(ref[:3])).max() <= TOL
     with pytest.raises(mtmc.MtmcError, match="clip_eps"):
         mtmc.mtmc_ppo_clip_loss(dev(new), dev(old), dev(adv), 1.5)
+
+
+def test_measurement_probes_run_and_report_their_work():
+    """The two probes behind the `attainable` figures of the benchmark: the streaming read touches nothing but its
+    sink, the matrix-instruction loop returns the flops of its launch and overwrites its output with finite sums."""
+    import torch
+    from paper_2511_20100_amd import mtmc
+    src = torch.ones(64 << 20, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    mtmc.mtmc_read_probe(src, sink)
+    out = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    flops = mtmc.mtmc_mfma_probe(out, 8, 100)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0 and bool((src == 1).all())
+    assert flops == 8 * 4 * 16 * 100 * 2 * 32 * 32 * 16
+    assert bool(torch.isfinite(out).all()) and float(out.abs().max()) > 0.0
