@@ -235,6 +235,32 @@ def inference_legs(torch, mtmc, dev, handle, weights, cfg, prompts, n_samples, m
                              "tokens_per_s_rows_keep_places": int(n0.sum().item()) / (ms_static * 1e-3)}
         progress(f"stop token: {toks} tokens, {ms_poll:.1f} ms against {ms_static:.1f} ms")
         del ws
+        # eight batches of 128 sequences in one call: the slots of finished sequences go to the next prompt of the
+        # call, against batch after batch (each ending with its last row, rows giving up their places as above)
+        mtmc.mtmc_set_option(h2, mtmc.MTMC_OPT_STOP_POLL_STEPS, 32)
+        many = 8 * (128 // n_samples)
+        m_prompts = torch.from_numpy(inputs.make_prompts(many, prompt_len, cfg.vocab, seed=8)).to(dev)
+        m_lens = torch.full((many,), prompt_len, dtype=torch.int32, device=dev)
+        ws = torch.empty(mtmc.mtmc_rollout_ragged_workspace_bytes(h2, many, prompt_len, n_samples, max_new),
+                         dtype=torch.uint8, device=dev)
+        run = lambda: mtmc.mtmc_rollout_ragged(h2, m_prompts, m_lens, n_samples, max_new, 1.0, 1, stop_id=stop, workspace=ws)
+        (ids, lp, n), ms_admit = timed(run)
+        mtmc.mtmc_set_option(h2, mtmc.MTMC_OPT_ADMIT_PROMPTS, 0)
+        (ids0, lp0, n0), ms_batches = timed(run)
+        mtmc.mtmc_poll_errors(h2)
+        toks, toks0 = int(n.sum().item()), int(n0.sum().item())
+        same = (ids == ids0).all(dim=1)
+        out["prompts_join_a_running_batch"] = {
+            "workload": f"{many} x {n_samples} rows through the 128 slots of one batch, prompt {prompt_len}, up to "
+                        f"{max_new} new tokens, the same stop token",
+            "tokens_generated": toks, "longest_row": int(n.max().item()), "median_row": float(n.float().median().item()),
+            "ms_prompts_join": ms_admit, "ms_batch_after_batch": ms_batches,
+            "tokens_per_s_prompts_join": toks / (ms_admit * 1e-3),
+            "tokens_per_s_batch_after_batch": toks0 / (ms_batches * 1e-3),
+            "rows_with_the_same_ids": int(same.sum().item()), "rows": int(same.numel()),
+            "max_logprob_difference_on_those_rows": float((lp[same] - lp0[same]).abs().max().item()) if same.any() else None}
+        progress(f"prompts join a running batch: {toks} tokens, {ms_admit:.1f} ms against {ms_batches:.1f} ms")
+        del ws
     finally:
         mtmc.mtmc_weights_destroy(h2)
     return out

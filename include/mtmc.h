@@ -311,6 +311,7 @@ const char* mtmc_data_error_string(int bits);
 #define MTMC_OPT_HIP_GRAPH 1
 #define MTMC_OPT_GEMM_LDS_MIN_BLOCKS 2
 #define MTMC_OPT_STOP_POLL_STEPS 3
+#define MTMC_OPT_ADMIT_PROMPTS 4
 int mtmc_set_option(mtmc_weights* w, int option, int value);
 
 /*

@@ -91,6 +91,7 @@ extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, siz
   w->opt_hip_graph = 1;
   w->opt_lds_min_blocks = 192;
   w->opt_stop_poll = 32;
+  w->opt_admit = 1;
   w->graphs = nullptr;
   w->ragged_mu = new (std::nothrow) std::mutex();
   if (!w->ragged_mu) { delete w; set_error("out of host memory"); return MTMC_ENOMEM; }
@@ -123,13 +124,15 @@ extern "C" void mtmc_weights_destroy(mtmc_weights* w) {
 extern "C" int mtmc_set_option(mtmc_weights* w, int option, int value) {
   MTMC_REQUIRE(w != nullptr, "weights is NULL");
   MTMC_REQUIRE(option == MTMC_OPT_HIP_GRAPH || option == MTMC_OPT_GEMM_LDS_MIN_BLOCKS ||
-                   option == MTMC_OPT_STOP_POLL_STEPS,
+                   option == MTMC_OPT_STOP_POLL_STEPS || option == MTMC_OPT_ADMIT_PROMPTS,
                "unknown option");
   if (option == MTMC_OPT_HIP_GRAPH) {
     w->opt_hip_graph = value ? 1 : 0;
   } else if (option == MTMC_OPT_STOP_POLL_STEPS) {
     MTMC_REQUIRE(value >= 0 && value <= (1 << 20), "MTMC_OPT_STOP_POLL_STEPS needs a value in [0, 2^20]");
     w->opt_stop_poll = value;
+  } else if (option == MTMC_OPT_ADMIT_PROMPTS) {
+    w->opt_admit = value ? 1 : 0;
   } else {
     MTMC_REQUIRE(value >= 1, "MTMC_OPT_GEMM_LDS_MIN_BLOCKS needs a value >= 1");
     w->opt_lds_min_blocks = value;

@@ -24,6 +24,11 @@ struct SampleCtl {
   // kernels holds row slot_row[m] of the call, or nobody (-1).  NULL: slot m is row m.  Outputs, stop flags, the
   // fed-back ids (cur_ids) and the random-number counters go by row.
   const int* slot_row;
+  // Rows that joined the batch while it was running (a new prompt took the places of a finished one): the
+  // sequence in slot m is at its own step *d_step - row_step0[m].  It reports under that step, draws that
+  // step's random numbers, raises its stop flag when that step is max_new - 1 and reports nothing after that
+  // or once the flag is up.  NULL: every row is at step *d_step.
+  const int* row_step0;
 };
 
 struct LargeArgs {
@@ -131,6 +136,11 @@ struct AttnDecArgs {
   int Hq, Hkv, layer, pos_base;
   const int* row_pos;    // per-sequence position base (sequences of different lengths), or NULL: pos_base
   const int* d_step;
+  // sequences that joined the batch while it was running: the sequence in slot b is at step
+  // min(*d_step - row_step0[b], max_step) (a slot whose sequence has ended keeps rewriting its last position
+  // until the host gives the slot to another sequence).  NULL: every sequence is at step *d_step.
+  const int* row_step0;
+  int max_step;
   KvPool pool;
   int chunk_pages, n_chunks, m_tiles;
   int split_at_prompt;   // n_chunks == 2: chunk 0 = the whole pages of the sequence's prompt (pos_base / row_pos), chunk 1 = the rest
@@ -210,6 +220,33 @@ void build_packed_actions(int* seq_start, int* d_rows, int* ids, int* targets, i
 
 // ---- elementwise / row kernels -------------------------------------------------------------
 void set_sample_ctl(SampleCtl* dst, const SampleCtl& v, hipStream_t st);
+// A batch that takes in new prompts as it runs.  Every slot has pages of its own for a whole sequence; the whole
+// pages of a prompt lie in one of the call's regions of nf_max pages, shared by the prompt's sequences.
+// admit_init: slot s holds row s (nobody from B on), every row at step *d_step.
+// admit_prompt: the sequences of prompt `prompt_index` of the call (rows prompt_index * n_samples + j) take the
+// slots slots[j]; they are at their step *d_step - step0; their page-table rows are rebuilt over `region`; the
+// prompt, its padding cleared, is left in ids_out [Lmax].  fork_tail_slots: after the prefill through slots[0].
+// slot_live: which slots hold a sequence that still runs.  compact_slots: those sequences packed into the leading
+// slots of a second set of tables.
+struct AdmitArgs {
+  int* page_table;     // [slots, max_pages]
+  int* row_pos;        // [slots]
+  int* slot_row;       // [slots]
+  int* row_step0;      // [slots]
+  int* ids_out;
+  const int* prompt;   // device [Lmax]
+  const int* len;      // device, the prompt's length (clamped to [1, Lmax] and reported when outside)
+  int region, prompt_index, n_samples, Lmax, max_pages, nf_max, shared_total, step0;
+  int* err_flag;
+  int slots[128];
+};
+void admit_init(int* slot_row, int* row_step0, int B, int Mpad, hipStream_t st);
+void admit_prompt(const AdmitArgs& a, hipStream_t st);
+void fork_tail_slots(const AdmitArgs& a, KvPool pool, int n_layers, hipStream_t st);
+void slot_live(const int* done, const int* slot_row, int n_slots, int* live, hipStream_t st);
+void compact_slots(const int* done, int B, int slots, const int* slot_row, const int* page_table, const int* row_pos,
+                   const int* row_step0, int max_pages, int* slot_row_c, int* page_table_c, int* row_pos_c,
+                   int* row_step0_c, hipStream_t st);
 void embed(float* h, const int* ids, int T, const bf16_t* E, int d, int vocab, int* err_flag,
            hipStream_t st, const int* d_rows = nullptr);
 // h[m, :] += sum_s P[s][m][:] (n_split may be 0); x = bf16(RMSNorm(h; gain)) in tiled layout.

@@ -383,9 +383,10 @@ __global__ __launch_bounds__(WAVES * 64, MINW) void k_gemm_dec(DecGemmArgs a) {
     }
   } else {  // DEPI_SAMPLE: log-sum-exp and Gumbel arg-max over this pass's part of the workgroup's vocabulary slice
     const SampleCtl ctl = *a.ctl;
-    const int step = *a.d_step;
-    // the random numbers of a row follow the row, whatever slot it sits in (an empty slot draws row 0's: unused)
+    // the random numbers of a row follow the row and its own step, whatever slot it sits in and whenever it joined
+    // (an empty slot draws row 0's: unused)
     const int smp_row = (ctl.slot_row && m < a.M) ? max(ctl.slot_row[m], 0) : m;
+    const int step = *a.d_step - ((ctl.row_step0 && m < a.M) ? ctl.row_step0[m] : 0);
 #pragma unroll
     for (int nb = 0; nb < NBP; ++nb) {
       if (nbase + nb >= a.n_tiles) continue;
@@ -683,18 +684,37 @@ __global__ __launch_bounds__(256) void k_sample_merge(const DecSamplePartial* pa
         tok = 0;
         atomicOr(emb.err_flag, kErrFp16Range);
       }
-      if (ctl.done) {
-        if (ctl.done[row]) {
+      if (ctl.row_step0) {
+        // a batch that takes in new prompts as it runs (its caller passes stop flags and has filled the outputs
+        // with what a finished row reports): this row is at its own step, and the batch may run on after its end
+        const int own = step - ctl.row_step0[b];
+        if (ctl.done[row] || own >= ctl.max_new) {
           tok = ctl.stop_id;
-          lp = 0.f;
-        } else if (tok == ctl.stop_id) {
-          ctl.done[row] = 1;
-          ctl.out_lens[row] = step + 1;
+        } else {
+          if (tok == ctl.stop_id) {
+            ctl.done[row] = 1;
+            ctl.out_lens[row] = own + 1;
+          } else if (own == ctl.max_new - 1) {
+            ctl.done[row] = 1;
+          }
+          ctl.out_ids[(size_t)row * ctl.max_new + own] = tok;
+          ctl.out_logprobs[(size_t)row * ctl.max_new + own] = lp;
         }
+        cur_ids[row] = tok;
+      } else {
+        if (ctl.done) {
+          if (ctl.done[row]) {
+            tok = ctl.stop_id;
+            lp = 0.f;
+          } else if (tok == ctl.stop_id) {
+            ctl.done[row] = 1;
+            ctl.out_lens[row] = step + 1;
+          }
+        }
+        cur_ids[row] = tok;
+        ctl.out_ids[(size_t)row * ctl.max_new + step] = tok;
+        ctl.out_logprobs[(size_t)row * ctl.max_new + step] = lp;
       }
-      cur_ids[row] = tok;
-      ctl.out_ids[(size_t)row * ctl.max_new + step] = tok;
-      ctl.out_logprobs[(size_t)row * ctl.max_new + step] = lp;
     }
     s_tok = tok;
     // the last row to get here advances the step counter: by then every row has read it (d_step[1] counts
@@ -838,6 +858,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
   const KvPool& pool = a.pool;
   const int* table = pool.page_table + (size_t)b * pool.max_pages;
   const int pos0 = a.row_pos ? a.row_pos[b] : a.pos_base;
+  const int step0 = a.row_step0 ? a.row_step0[b] : 0;
   // Pages [p_lo, p_end) of the sequence are this workgroup's.  Either equal chunks, or (two chunks, split_at_prompt)
   // the whole pages of the prompt and the rest: a boundary that depends on the sequence alone, so that a sequence
   // gets the same arithmetic whatever else is in the batch and however many tokens the call may generate (given
@@ -867,7 +888,7 @@ __global__ __launch_bounds__(AW * 64) void k_attn_dec(AttnDecArgs a) {
                   dec_page<DHD>(pool, a.layer, 1, i0, g), dec_page<DHD>(pool, a.layer, 1, i1, g), lane);
   }
   // ---- position-dependent part
-  const int pos = pos0 + step;
+  const int pos = pos0 + (a.row_step0 ? min(step - step0, a.max_step) : step);
   const int n_ctx_pages = pos / kPageTokens + 1;
   // a negative position base marks a slot that holds no sequence (rows packed into fewer slots): nothing to attend
   const int p_hi = pos0 < 0 ? p_lo : min(n_ctx_pages, p_end);
@@ -1055,6 +1076,101 @@ __global__ __launch_bounds__(256) void k_embed_slots(const int* slot_row, const 
 }
 void embed_slots(const int* slot_row, const int* cur_ids, int slots, const EmbedNextArgs& emb, hipStream_t st) {
   k_embed_slots<<<slots, 256, 0, st>>>(slot_row, cur_ids, emb);
+}
+
+// ---------------------------------------------------------------- a batch that takes in new prompts as it runs
+__global__ void k_admit_init(int* slot_row, int* row_step0, int B, int Mpad) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < Mpad) {
+    slot_row[s] = s < B ? s : -1;
+    row_step0[s] = 0;
+  }
+}
+void admit_init(int* slot_row, int* row_step0, int B, int Mpad, hipStream_t st) {
+  k_admit_init<<<(Mpad + 255) / 256, 256, 0, st>>>(slot_row, row_step0, B, Mpad);
+}
+
+__global__ __launch_bounds__(256) void k_admit_prompt(AdmitArgs a) {
+  const int j = blockIdx.x, slot = a.slots[j];
+  const int raw = *a.len, len = min(max(raw, 1), a.Lmax);
+  if (threadIdx.x == 0) {
+    if (raw != len && j == 0) atomicOr(a.err_flag, 4);
+    a.row_pos[slot] = len - 1;
+    a.slot_row[slot] = a.prompt_index * a.n_samples + j;
+    a.row_step0[slot] = a.step0;
+  }
+  // whole prompt pages: the region's, shared by the prompt's sequences; the rest: the slot's own
+  const int n_full = len / kPageTokens;
+  for (int i = threadIdx.x; i < a.max_pages; i += blockDim.x)
+    a.page_table[(size_t)slot * a.max_pages + i] =
+        (i < n_full) ? a.region * a.nf_max + i : a.shared_total + slot * a.max_pages + i;
+  if (j == 0)
+    for (int i = threadIdx.x; i < a.Lmax; i += blockDim.x) a.ids_out[i] = (i < len) ? a.prompt[i] : 0;
+}
+void admit_prompt(const AdmitArgs& a, hipStream_t st) { k_admit_prompt<<<a.n_samples, 256, 0, st>>>(a); }
+
+// the prompt's last, partly filled page (written into the first slot's own page by the prefill) goes to the other slots
+__global__ void k_fork_tail_slots(AdmitArgs a, KvPool pool, int words_per_page) {
+  const int j = blockIdx.x + 1;
+  const int len = min(max(*a.len, 1), a.Lmax);
+  if (len % kPageTokens == 0) return;
+  const int page_idx = len / kPageTokens;
+  const int lw = blockIdx.y;  // layer * 2 + which
+  const int src = a.shared_total + a.slots[0] * a.max_pages + page_idx;
+  const int dst = a.shared_total + a.slots[j] * a.max_pages + page_idx;
+  const uint32_t* s = (const uint32_t*)pool.base + ((size_t)lw * pool.n_pages + src) * words_per_page;
+  uint32_t* d = (uint32_t*)pool.base + ((size_t)lw * pool.n_pages + dst) * words_per_page;
+  for (int i = threadIdx.x; i < words_per_page; i += blockDim.x) d[i] = s[i];
+}
+void fork_tail_slots(const AdmitArgs& a, KvPool pool, int n_layers, hipStream_t st) {
+  if (a.n_samples < 2) return;
+  const int words = pool.n_kv_heads * kPageTokens * pool.head_dim * 2 / 4;
+  k_fork_tail_slots<<<dim3(a.n_samples - 1, n_layers * 2), 256, 0, st>>>(a, pool, words);
+}
+
+// live[s] = 1 when the sequence in slot s still runs (s < n_slots <= 256)
+__global__ __launch_bounds__(256) void k_slot_live(const int* done, const int* slot_row, int n_slots, int* live) {
+  const int s = threadIdx.x;
+  if (s >= n_slots) return;
+  const int row = slot_row[s];
+  live[s] = (row >= 0 && !done[row]) ? 1 : 0;
+}
+void slot_live(const int* done, const int* slot_row, int n_slots, int* live, hipStream_t st) {
+  k_slot_live<<<1, 256, 0, st>>>(done, slot_row, n_slots, live);
+}
+
+// The sequences that still run, in slot order, move to the leading `slots` slots of a second set of tables
+// (one workgroup; B <= 256).
+__global__ __launch_bounds__(256) void k_compact_slots(const int* done, int B, int slots, const int* slot_row,
+                                                       const int* page_table, const int* row_pos, const int* row_step0,
+                                                       int max_pages, int* slot_row_c, int* page_table_c, int* row_pos_c,
+                                                       int* row_step0_c) {
+  __shared__ int s_src[256];
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int s = 0; s < B && n < slots; ++s) {
+      const int row = slot_row[s];
+      if (row >= 0 && !done[row]) s_src[n++] = s;
+    }
+    for (; n < slots; ++n) s_src[n] = -1;
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < slots; s += blockDim.x) {
+    const int src = s_src[s];
+    slot_row_c[s] = src >= 0 ? slot_row[src] : -1;
+    row_pos_c[s] = src >= 0 ? row_pos[src] : -1;
+    row_step0_c[s] = src >= 0 ? row_step0[src] : 0;
+  }
+  for (int i = threadIdx.x; i < slots * max_pages; i += blockDim.x) {
+    const int s = i / max_pages, j = i - s * max_pages;
+    page_table_c[i] = s_src[s] >= 0 ? page_table[(size_t)s_src[s] * max_pages + j] : 0;
+  }
+}
+void compact_slots(const int* done, int B, int slots, const int* slot_row, const int* page_table, const int* row_pos,
+                   const int* row_step0, int max_pages, int* slot_row_c, int* page_table_c, int* row_pos_c,
+                   int* row_step0_c, hipStream_t st) {
+  k_compact_slots<<<1, 256, 0, st>>>(done, B, slots, slot_row, page_table, row_pos, row_step0, max_pages, slot_row_c,
+                                     page_table_c, row_pos_c, row_step0_c);
 }
 
 void attention_dec(const AttnDecArgs& a, int B, hipStream_t st) {

@@ -113,10 +113,11 @@ __global__ __launch_bounds__(kLW * 64, 1) void k_lmhead_sample(DecGemmArgs a) {
   const bool has_blocks = q0 < BLK;
   const int m = my_mb * 16 + col;   // this lane's row, the same in every step
   const SampleCtl ctl = *a.ctl;
-  const int step_no = *a.d_step;
   const float sc = (has_blocks && m < Mpad) ? s_scale[m] : 1.f;
-  // the random numbers of a row follow the row, whatever slot it sits in (an empty slot draws row 0's: unused)
+  // the random numbers of a row follow the row and its own step, whatever slot it sits in and whenever it joined
+  // (an empty slot draws row 0's: unused)
   const int smp_row = (ctl.slot_row && m < a.M) ? max(ctl.slot_row[m], 0) : m;
+  const int step_no = *a.d_step - ((ctl.row_step0 && m < a.M) ? ctl.row_step0[m] : 0);
   Lse lse = lse_empty();
   float by = -INFINITY, bz = 0.f;
   int bi = 0x7fffffff;

@@ -240,6 +240,7 @@ __global__ __launch_bounds__(WAVES * 64, MINB) void k_gemm_rows128(DecGemmArgs a
       const int m = mb * 16 + col;
       const float sc = m < Mpad ? s_scale[m] : 1.f;
       const int row = (ctl.slot_row && m < a.M) ? max(ctl.slot_row[m], 0) : m;
+      const int row_step = step - ((ctl.row_step0 && m < a.M) ? ctl.row_step0[m] : 0);  // a row that joined later
       Lse lse = lse_empty();
       float by = -INFINITY, bz = 0.f;
       int bi = 0x7fffffff;
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(WAVES * 64, MINB) void k_gemm_rows128(DecGemmArgs a
         const int v0 = (nt0 + nb) * 16 + rq;  // multiple of 4: one generator block per 4 entries
         uint4 rb = make_uint4(0, 0, 0, 0);
         if (!ctl.greedy)
-          rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)step, ctl.seq_offset + row, 0u), ctl.key0, ctl.key1);
+          rb = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), (uint32_t)row_step, ctl.seq_offset + row, 0u), ctl.key0, ctl.key1);
         const uint32_t rr[4] = {rb.x, rb.y, rb.z, rb.w};
         float zt[4];
 #pragma unroll

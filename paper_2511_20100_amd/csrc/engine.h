@@ -38,20 +38,28 @@ struct RolloutPlan {
   int nf_max;        // ragged: shared pages reserved per prompt (prompt_len / 16)
   int n_full;        // pages per prompt that are completely filled by the prompt (shared)
   int max_pages;     // page-table row length
-  int shared_total;  // n_prompts * n_full
+  int shared_total;  // pages shared by the sequences of a prompt: n_prompts * n_full; ragged: n_regions * nf_max
+  int n_regions;     // ragged: regions of nf_max shared pages (n_prompts; bf16 calls of several groups: more, so that
+                     // a new prompt finds one free while the last sequences of earlier prompts still run)
   int n_pages;       // pages in the pool
   int chunk_prompts, Tmax;
   // control
   int* page_table;
   int* d_step;
-  int* cur_ids;
+  int* cur_ids;      // [B]; ragged, bf16: [total_prompts * n_samples], by row of the call
   int* row_pos;      // ragged: [B] position of a row's last prompt token
-  int* done;         // ragged: [B] stop flags
+  int* done;         // ragged: [B] stop flags; bf16: [total_prompts * n_samples], by row of the call
   int* prompt_ids;   // ragged: [n_prompts, prompt_len] prompts with the padding cleared
   int* slot_row;     // ragged, bf16: [bt * 16] row held by each slot once live rows are packed (-1: nobody)
   int* page_table_c; // ragged, bf16: [B, max_pages] page-table rows by slot
   int* row_pos_c;    // ragged, bf16: [bt * 16] position base by slot (-1: nobody)
-  int* live;         // ragged, bf16: [16] live[0] = rows that have not stopped
+  int* live;         // ragged, bf16: [16 + 256] live[0] = rows that have not stopped; from 16 on, by place
+  int* row_step0;    // ragged, bf16: [bt * 16] step of the call at which the sequence in a slot was at its step 0
+  int* slot_row_c;   // ragged, bf16: [bt * 16] slot_row / row_step0 of the packed batch (page_table_c, row_pos_c)
+  int* row_step0_c;
+  float* hT;         // ragged, bf16: [n_samples, d] last prompt position of a prompt that joins a running batch
+  void* xT;          // ragged, bf16: its normalised operand, tiled
+  float* ssT;        // ragged, bf16: sums of squares that go with xT
   int* suffix_ids;   // ragged: [n_prompts, prompt_len - reuse_len] the ids that are prefilled (all, without a cached prefix)
   void* kv;
   // activations (Tmax rows unless noted)

@@ -58,7 +58,9 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
   p.nf_max = prompt_len / kPageTokens;
   p.n_full = ragged ? 0 : p.nf_max;
   p.max_pages = (prompt_len + max_new + kPageTokens - 1) / kPageTokens;
-  p.shared_total = n_prompts * p.nf_max;
+  p.n_regions = n_prompts;
+  if (bf && ragged && p.total_prompts > n_prompts) p.n_regions = std::min({p.total_prompts, 4 * n_prompts, 128});
+  p.shared_total = p.n_regions * p.nf_max;
   p.n_pages = p.shared_total + p.B * (p.max_pages - p.n_full);
   p.chunk_prompts = std::max(1, std::min(n_prompts, kChunkTokens / prompt_len));
   p.Tmax = (std::max(p.chunk_prompts * prompt_len, p.B) + 127) / 128 * 128;
@@ -69,10 +71,12 @@ RolloutPlan plan_rollout(const mtmc_weights* w, int n_prompts, int prompt_len, i
   Carver cv(base);
   p.page_table = cv.take<int>((size_t)p.B * p.max_pages);
   p.d_step = cv.take<int>(64);
-  p.cur_ids = cv.take<int>(p.B);
+  // bf16, ragged: a call of several groups may run as one batch whose places pass from prompt to prompt
+  const size_t n_flag_rows = (bf && ragged) ? (size_t)p.total_prompts * n_samples : (size_t)p.B;
+  p.cur_ids = cv.take<int>(n_flag_rows);
   if (ragged) {
     p.row_pos = cv.take<int>(p.B);
-    p.done = cv.take<int>(p.B);
+    p.done = cv.take<int>(n_flag_rows);
     p.prompt_ids = cv.take<int>((size_t)n_prompts * prompt_len);
     p.suffix_ids = cv.take<int>((size_t)n_prompts * prompt_len);
   }

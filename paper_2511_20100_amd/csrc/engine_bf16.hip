@@ -34,6 +34,7 @@ struct GraphCache {
   std::mutex poll_mu;                    // one such rollout at a time per weights handle
   int* host_live = nullptr;
   hipEvent_t poll_events[2] = {nullptr, nullptr};
+  int* host_places = nullptr;            // pinned: sequences still running, by place (a batch that takes in prompts)
 };
 
 // Brackets launches of one kernel class with HIP events while a decode step is launched directly.
@@ -73,6 +74,7 @@ void destroy_graph_cache(mtmc_weights* w) {
   for (hipEvent_t e : w->graphs->poll_events)
     if (e) (void)hipEventDestroy(e);
   if (w->graphs->host_live) (void)hipHostFree(w->graphs->host_live);
+  if (w->graphs->host_places) (void)hipHostFree(w->graphs->host_places);
   delete w->graphs;
   w->graphs = nullptr;
 }
@@ -326,7 +328,7 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.attn_ml = cv.take<float>(attn_ml);
   p.lm_part = cv.take<float>((size_t)((D.nt_V + 1) / 2) * Mpad * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
-  p.ctl = cv.take<bf16::SampleCtl>(1);
+  p.ctl = cv.take<bf16::SampleCtl>(2);
   p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
   p.ssB = cv.take<float>((size_t)D.nt_d * Mpad);
   p.rs_buf = cv.take<float>(Mpad);
@@ -334,7 +336,14 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
     p.slot_row = cv.take<int>(Mpad);
     p.page_table_c = cv.take<int>(Mpad * p.max_pages);
     p.row_pos_c = cv.take<int>(Mpad);
-    p.live = cv.take<int>(16);
+    p.live = cv.take<int>(16 + 256);
+    p.row_step0 = cv.take<int>(Mpad);
+    p.slot_row_c = cv.take<int>(Mpad);
+    p.row_step0_c = cv.take<int>(Mpad);
+    const size_t MpadT = (size_t)tiles16(std::min(p.n_samples, 128)) * 16;  // a call takes at most 128 samples per prompt
+    p.hT = cv.take<float>(MpadT * D.d);
+    p.xT = cv.take<h16_t>(MpadT * D.d);
+    p.ssT = cv.take<float>((size_t)D.nt_d * MpadT);
   }
 }
 
@@ -421,6 +430,7 @@ void decode_layers(const mtmc_weights* w, const Dims& D, const RolloutPlan& p, K
     at.qkv = p.qkv; at.cos = w->rope_cos; at.sin = w->rope_sin; at.Hq = D.Hq; at.Hkv = D.Hkv; at.layer = l;
     at.pos_base = pos_base; at.row_pos = p.ragged ? p.row_pos : nullptr; at.d_step = p.d_step; at.pool = pool; at.chunk_pages = p.chunk_pages; at.split_at_prompt = p.split_at_prompt;
     at.n_chunks = p.n_chunks; at.m_tiles = bt; at.share = p.n_samples;
+    at.row_step0 = p.ragged == 3 ? p.row_step0 : nullptr; at.max_step = p.max_new - 1;
     at.o = (h16_t*)p.o_chunks; at.o_chunk_stride = (size_t)D.nq * bt * 16; at.ml = p.attn_ml; at.err_flag = w->err_flag;
     mark(MTMC_KERNEL_ATTENTION);
     bf16::attention_dec(at, B, st);
@@ -506,6 +516,196 @@ int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, S
   return MTMC_OK;
 }
 
+
+// A rollout with a stop token and more sequences than one batch holds, run as ONE batch that takes in the call's
+// prompts as it runs.  Every slot of the batch has pages of its own for a whole sequence; the whole pages of a prompt
+// lie in one of n_regions regions shared by the prompt's sequences.  The first n_prompts prompts start together as
+// in bf16_rollout.  Every few steps the host waits for the stream and reads which slots still hold a running
+// sequence.  While prompts are left, the next one is taken in as soon as n_samples slots are free (any slots) and
+// a region is free (one whose prompt's sequences have all ended): the slots' page-table rows are rebuilt, the
+// prompt is prefilled through the first of them, its step 0 is sampled from a batch of its own (a second control
+// block and step counter), and its sequences join the batch at their own step (row_step0).  A slot whose sequence
+// has ended keeps computing on its own pages until it is given away.  When no prompt is left, the sequences still
+// running are packed into fewer 16-row tiles as in bf16_rollout, and the call ends with the last of them.  While
+// prompts are left the batch keeps its shape, so a sequence's arithmetic does not depend on when it joined.
+int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* prompts, const SampleArgs& sa,
+                       hipStream_t st) {
+  const mtmc_config& c = w->cfg;
+  const Dims D = dims_of(w);
+  const int S = p.prompt_len, ns = p.n_samples, B = p.B;
+  const size_t total_rows = (size_t)p.total_prompts * ns;
+  KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};
+  const size_t kv_words = (size_t)c.n_layers * 2 * p.n_pages * c.n_kv_heads * kPageTokens * c.head_dim / 2;
+  RolloutPlan gp = p;
+  gp.ragged = 3;  // the step graph of this form is its own (its launches carry row_step0)
+  bf16::SampleCtl* d_ctl = (bf16::SampleCtl*)p.ctl;
+  const uint32_t key0 = (uint32_t)(sa.seed & 0xffffffffu), key1 = (uint32_t)(sa.seed >> 32);
+  bf16::SampleCtl ctl{sa.greedy, sa.inv_temp, key0, key1, sa.seq_offset, sa.max_new, sa.out_ids, sa.out_logprobs,
+                      sa.stop_id, p.done, sa.out_lens, p.slot_row, p.row_step0};
+  bf16::set_sample_ctl(d_ctl, ctl, st);
+  // what a row reports after its end
+  launch_fill_u32((uint32_t*)sa.out_ids, (uint32_t)sa.stop_id, total_rows * p.max_new, st);
+  launch_fill_u32((uint32_t*)sa.out_logprobs, 0u, total_rows * p.max_new, st);
+  launch_fill_u32((uint32_t*)p.done, 0u, total_rows, st);
+  launch_fill_u32((uint32_t*)sa.out_lens, (uint32_t)p.max_new, total_rows, st);
+  launch_ragged_setup(p.page_table, p.row_pos, p.done, sa.out_lens, p.prompt_ids, p.suffix_ids, prompts, sa.prompt_lens,
+                      p.n_prompts, ns, S, p.max_pages, p.nf_max, p.shared_total, p.max_new, 0, w->err_flag, st);
+  bf16::admit_init(p.slot_row, p.row_step0, B, p.bt * 16, st);
+  launch_set_int(p.d_step, 0, st);
+  launch_set_int(p.d_step + 1, 0, st);
+  launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
+  // prefill of `np` prompts (ids [np, S], padding cleared) through the page-table rows from `table` on (one row
+  // per sequence, n_samples rows per prompt, the prompt's pages being those of its first row)
+  auto prefill = [&](const int* ids, int np, const int* table) {
+    const int T = np * S, mt = tiles16(T);
+    KvPool ppool = pool;
+    ppool.page_table = table;
+    TokMap map{S, ns, 0, nullptr};
+    bf16::embed(p.h, ids, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
+    bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
+    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, S, map, ppool, 1, st);
+  };
+  for (int p0 = 0; p0 < p.n_prompts; p0 += p.chunk_prompts) {
+    const int np = std::min(p.chunk_prompts, p.n_prompts - p0);
+    const int* table = p.page_table + (size_t)p0 * ns * p.max_pages;
+    prefill(p.suffix_ids + (size_t)p0 * S, np, table);
+    launch_gather_last_rows(p.hB + (size_t)p0 * ns * D.d, p.h, D.d, np, ns, S, sa.prompt_lens + p0, 0, st);
+    KvPool fpool = pool;
+    fpool.page_table = table;
+    launch_fork_tail_pages_ragged(fpool, c.n_layers, np * ns, ns, sa.prompt_lens + p0, S, 2, st);
+  }
+  bf16::add_norm(p.hB, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xB, B, gp.bt, D.d, w->err_flag, st);
+  auto embed_args = [&](const RolloutPlan& q) {
+    return bf16::EmbedNextArgs{p.hB, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xB,
+                               q.bt * 16, p.ssA, D.V, w->err_flag};
+  };
+  // LM head + sampler over `rows` rows of the operand x; `dc` / `ds`: control block and step counter
+  auto sample = [&](hipStream_t s, const h16_t* x, int rows, const float* ss_cur, const float* ss_old,
+                    const bf16::SampleCtl* dc, int* ds, int* cur_ids, const bf16::EmbedNextArgs& e) {
+    bf16::DecGemmArgs lm{};
+    lm.Wt = (const h16_t*)w->lm_head; lm.Xt = x; lm.n_tiles = D.nt_V; lm.k_tiles = D.kt_d;
+    lm.m_tiles = tiles16(rows); lm.M = rows; lm.ss_cur = ss_cur; lm.ss_old = ss_old; lm.ss_tiles = D.nt_d;
+    lm.inv_d = 1.0f / (float)D.d; lm.eps = c.rms_eps; lm.out_f32 = p.lm_part;
+    lm.ctl = dc; lm.d_step = ds;
+    bf16::gemm_dec(lm, bf16::DEC_SAMPLE, s);
+    bf16::sample_merge(p.lm_part, bf16::dec_sample_groups(D.nt_V, D.kt_d, lm.m_tiles), rows, dc, ds, cur_ids, e, s);
+  };
+  // cur: the shape the step runs in (the batch, or the slots its last sequences were packed into)
+  RolloutPlan cur = gp;
+  KvPool cur_pool = pool;
+  auto decode_step = [&](hipStream_t s) {
+    const float *ss_cur = nullptr, *ss_old = nullptr;
+    decode_layers(w, D, cur, cur_pool, 0, &ss_cur, &ss_old, s);
+    sample(s, (const h16_t*)p.xB, cur.B, ss_cur, ss_old, d_ctl, p.d_step, p.cur_ids, embed_args(cur));
+  };
+  sample(st, (const h16_t*)p.xB, B, nullptr, nullptr, d_ctl, p.d_step, p.cur_ids, embed_args(gp));  // step 0 of the first prompts
+
+  mtmc_weights* mw = const_cast<mtmc_weights*>(w);
+  if (!mw->graphs) mw->graphs = new GraphCache();
+  GraphCache& gc = *mw->graphs;
+  std::lock_guard<std::mutex> poll_lock(gc.poll_mu);
+  if (!gc.host_places) MTMC_HIP_CHECK(hipHostMalloc((void**)&gc.host_places, 256 * sizeof(int), hipHostMallocDefault));
+  const int* live = gc.host_places;
+  hipGraphExec_t exec = nullptr;
+  if (int rc = decode_graph(w, cur, st, decode_step, &exec)) return rc;
+
+  std::vector<int> slot_region(B), region_users(p.n_regions, 0);  // region a slot's sequence reads; -1: none
+  for (int s = 0; s < B; ++s) slot_region[s] = s / ns;
+  int next_prompt = p.n_prompts, steps = 1;  // steps: value of *d_step once the queued work has run
+  int* d_live = p.live + 16;
+  const int period = std::max(1, std::min(w->opt_stop_poll, 8));
+  const int MpadT = tiles16(ns) * 16;
+  const bf16::EmbedNextArgs embT{p.hT, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xT,
+                                 MpadT, p.ssT, D.V, w->err_flag};
+  // every sequence ends within max_new steps of its start and a prompt is taken in whenever all the sequences of
+  // an earlier one have ended, at the latest
+  const long long step_limit = ((long long)p.total_prompts + 2) * ((long long)p.max_new + 2LL * period);
+  std::vector<int> free_slots;
+  for (;;) {
+    for (int j = 0; j < period; ++j) {
+      if (exec) MTMC_HIP_CHECK(hipGraphLaunch(exec, st));
+      else decode_step(st);
+    }
+    steps += period;
+    if (steps > step_limit) {
+      set_error("internal error: a rollout that takes in prompts as it runs did not end");
+      return MTMC_EHIP;
+    }
+    // the tables by slot of the whole batch stay as they are once no prompt is left: the packed batch is always made from them
+    bf16::slot_live(p.done, p.slot_row, B, d_live, st);
+    MTMC_HIP_CHECK(hipMemcpyAsync(gc.host_places, d_live, B * sizeof(int), hipMemcpyDeviceToHost, st));
+    MTMC_HIP_CHECK(hipStreamSynchronize(st));
+    int n_live = 0;
+    for (int s = 0; s < B; ++s) n_live += live[s];
+    if (next_prompt < p.total_prompts) {
+      std::fill(region_users.begin(), region_users.end(), 0);
+      free_slots.clear();
+      for (int s = 0; s < B; ++s) {
+        if (live[s]) ++region_users[slot_region[s]];
+        else free_slots.push_back(s);
+      }
+      size_t taken = 0;
+      int region = 0;
+      bool admitted = false;
+      while (next_prompt < p.total_prompts && free_slots.size() - taken >= (size_t)ns) {
+        while (region < p.n_regions && region_users[region] > 0) ++region;
+        if (region == p.n_regions) break;  // the last sequences of too many prompts still run: wait
+        const int q = next_prompt++;
+        bf16::AdmitArgs aa{p.page_table, p.row_pos, p.slot_row, p.row_step0, p.suffix_ids, prompts + (size_t)q * S,
+                           sa.prompt_lens + q, region, q, ns, S, p.max_pages, p.nf_max, p.shared_total, steps - 1,
+                           w->err_flag, {}};
+        for (int j = 0; j < ns; ++j) {
+          aa.slots[j] = free_slots[taken + j];
+          slot_region[aa.slots[j]] = region;
+        }
+        taken += ns;
+        region_users[region] = ns;
+        bf16::admit_prompt(aa, st);
+        prefill(p.suffix_ids, 1, p.page_table + (size_t)aa.slots[0] * p.max_pages);
+        launch_gather_last_rows(p.hT, p.h, D.d, 1, ns, S, aa.len, 0, st);
+        bf16::fork_tail_slots(aa, pool, c.n_layers, st);
+        bf16::add_norm(p.hT, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xT, ns, tiles16(ns), D.d, w->err_flag, st);
+        // its step 0, as a batch of its own: rows q * ns .. of the call, a step counter of its own
+        bf16::SampleCtl ct = ctl;
+        ct.seq_offset = sa.seq_offset + (uint32_t)(q * ns);
+        ct.out_ids = sa.out_ids + (size_t)q * ns * p.max_new;
+        ct.out_logprobs = sa.out_logprobs + (size_t)q * ns * p.max_new;
+        ct.done = p.done + (size_t)q * ns;
+        ct.out_lens = sa.out_lens + (size_t)q * ns;
+        ct.slot_row = nullptr;
+        ct.row_step0 = nullptr;
+        bf16::set_sample_ctl(d_ctl + 1, ct, st);
+        launch_set_int(p.d_step + 8, 0, st);
+        launch_set_int(p.d_step + 9, 0, st);
+        sample(st, (const h16_t*)p.xT, ns, nullptr, nullptr, d_ctl + 1, p.d_step + 8, p.cur_ids + (size_t)q * ns, embT);
+        admitted = true;
+      }
+      // the first tokens of the new sequences become operands of the next step (the other slots get again what
+      // they hold).  B, not the padded count: h has B rows
+      if (admitted) bf16::embed_slots(p.slot_row, p.cur_ids, B, embed_args(gp), st);
+      continue;
+    }
+    if (n_live == 0) break;
+    const int slots = tiles16(n_live) * 16;
+    if (slots < cur.bt * 16) {
+      bf16::compact_slots(p.done, B, slots, p.slot_row, p.page_table, p.row_pos, p.row_step0, p.max_pages, p.slot_row_c,
+                          p.page_table_c, p.row_pos_c, p.row_step0_c, st);
+      cur = gp;
+      cur.B = slots; cur.bt = slots / 16; cur.n_samples = 1;
+      cur.row_pos = p.row_pos_c; cur.row_step0 = p.row_step0_c;
+      apply_tune(cur, tune_decode(D, cur.B, cur.bt, p.max_pages));
+      cur_pool.page_table = p.page_table_c;
+      bf16::SampleCtl cc = ctl;
+      cc.slot_row = p.slot_row_c;
+      cc.row_step0 = p.row_step0_c;
+      bf16::set_sample_ctl(d_ctl, cc, st);
+      bf16::embed_slots(p.slot_row_c, p.cur_ids, slots, embed_args(cur), st);
+      if (int rc = decode_graph(w, cur, st, decode_step, &exec)) return rc;
+    }
+  }
+  return MTMC_OK;
+}
+
 }  // namespace
 
 int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts, const SampleArgs& sa,
@@ -514,6 +714,14 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
   if (p.n_samples > 128) {
     set_error("invalid argument: MTMC_BF16 rollout takes at most 128 samples per prompt");
     return MTMC_EINVAL;
+  }
+  if (sa.prompt_lens && sa.stop_id >= 0 && sa.reuse_len == 0 && p.total_prompts > p.n_prompts && p.max_new > 1 &&
+      w->opt_admit && w->opt_stop_poll > 0) {
+    // not while the caller is capturing the stream: the host must not wait then
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs == hipStreamCaptureStatusNone)
+      return bf16_rollout_admit(w, p, prompts, sa, st);
+    (void)hipGetLastError();
   }
   const Dims D = dims_of(w);
   KvPool pool{p.kv, p.n_pages, c.n_kv_heads, c.head_dim, p.page_table, p.max_pages};

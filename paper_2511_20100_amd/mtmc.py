@@ -328,6 +328,7 @@ MTMC_MAX_DECODE_CONTEXT = 32768   # prompt_len + max_new of a MTMC_BF16 rollout
 MTMC_OPT_HIP_GRAPH = 1
 MTMC_OPT_GEMM_LDS_MIN_BLOCKS = 2
 MTMC_OPT_STOP_POLL_STEPS = 3
+MTMC_OPT_ADMIT_PROMPTS = 4
 
 
 def mtmc_set_option(handle: int, option: int, value: int) -> None:
