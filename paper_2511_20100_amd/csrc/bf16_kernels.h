@@ -234,6 +234,8 @@ struct AdmitArgs {
   int* slot_row;       // [slots]
   int* row_step0;      // [slots]
   int* ids_out;
+  int* prefill_row;    // [max_pages] a copy of the page-table row of slots[0] (the prefill of several new prompts
+                       // at once goes through a table of these rows)
   const int* prompt;   // device [Lmax]
   const int* len;      // device, the prompt's length (clamped to [1, Lmax] and reported when outside)
   int region, prompt_index, n_samples, Lmax, max_pages, nf_max, shared_total, step0;

@@ -1101,9 +1101,11 @@ __global__ __launch_bounds__(256) void k_admit_prompt(AdmitArgs a) {
   }
   // whole prompt pages: the region's, shared by the prompt's sequences; the rest: the slot's own
   const int n_full = len / kPageTokens;
-  for (int i = threadIdx.x; i < a.max_pages; i += blockDim.x)
-    a.page_table[(size_t)slot * a.max_pages + i] =
-        (i < n_full) ? a.region * a.nf_max + i : a.shared_total + slot * a.max_pages + i;
+  for (int i = threadIdx.x; i < a.max_pages; i += blockDim.x) {
+    const int page = (i < n_full) ? a.region * a.nf_max + i : a.shared_total + slot * a.max_pages + i;
+    a.page_table[(size_t)slot * a.max_pages + i] = page;
+    if (j == 0) a.prefill_row[i] = page;
+  }
   if (j == 0)
     for (int i = threadIdx.x; i < a.Lmax; i += blockDim.x) a.ids_out[i] = (i < len) ? a.prompt[i] : 0;
 }

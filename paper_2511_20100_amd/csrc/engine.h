@@ -55,6 +55,7 @@ struct RolloutPlan {
   int* row_pos_c;    // ragged, bf16: [bt * 16] position base by slot (-1: nobody)
   int* live;         // ragged, bf16: [16 + 256] live[0] = rows that have not stopped; from 16 on, by place
   int* row_step0;    // ragged, bf16: [bt * 16] step of the call at which the sequence in a slot was at its step 0
+  int* prefill_table; // ragged, bf16: [bt * 16, max_pages] page-table rows through which new prompts are prefilled
   int* slot_row_c;   // ragged, bf16: [bt * 16] slot_row / row_step0 of the packed batch (page_table_c, row_pos_c)
   int* row_step0_c;
   float* hT;         // ragged, bf16: [n_samples, d] last prompt position of a prompt that joins a running batch

@@ -338,9 +338,10 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
     p.row_pos_c = cv.take<int>(Mpad);
     p.live = cv.take<int>(16 + 256);
     p.row_step0 = cv.take<int>(Mpad);
+    p.prefill_table = cv.take<int>(Mpad * p.max_pages);
     p.slot_row_c = cv.take<int>(Mpad);
     p.row_step0_c = cv.take<int>(Mpad);
-    const size_t MpadT = (size_t)tiles16(std::min(p.n_samples, 128)) * 16;  // a call takes at most 128 samples per prompt
+    const size_t MpadT = Mpad;  // the sequences of the prompts that join at one look: no more than the batch holds
     p.hT = cv.take<float>(MpadT * D.d);
     p.xT = cv.take<h16_t>(MpadT * D.d);
     p.ssT = cv.take<float>((size_t)D.nt_d * MpadT);
@@ -556,11 +557,11 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
   launch_fill_u32((uint32_t*)p.kv, 0u, kv_words, st);
   // prefill of `np` prompts (ids [np, S], padding cleared) through the page-table rows from `table` on (one row
   // per sequence, n_samples rows per prompt, the prompt's pages being those of its first row)
-  auto prefill = [&](const int* ids, int np, const int* table) {
+  auto prefill = [&](const int* ids, int np, const int* table, int rows_per_prompt) {
     const int T = np * S, mt = tiles16(T);
     KvPool ppool = pool;
     ppool.page_table = table;
-    TokMap map{S, ns, 0, nullptr};
+    TokMap map{S, rows_per_prompt, 0, nullptr};
     bf16::embed(p.h, ids, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
     bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
     prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, S, map, ppool, 1, st);
@@ -568,7 +569,7 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
   for (int p0 = 0; p0 < p.n_prompts; p0 += p.chunk_prompts) {
     const int np = std::min(p.chunk_prompts, p.n_prompts - p0);
     const int* table = p.page_table + (size_t)p0 * ns * p.max_pages;
-    prefill(p.suffix_ids + (size_t)p0 * S, np, table);
+    prefill(p.suffix_ids + (size_t)p0 * S, np, table, ns);
     launch_gather_last_rows(p.hB + (size_t)p0 * ns * D.d, p.h, D.d, np, ns, S, sa.prompt_lens + p0, 0, st);
     KvPool fpool = pool;
     fpool.page_table = table;
@@ -614,9 +615,6 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
   int next_prompt = p.n_prompts, steps = 1;  // steps: value of *d_step once the queued work has run
   int* d_live = p.live + 16;
   const int period = std::max(1, std::min(w->opt_stop_poll, 8));
-  const int MpadT = tiles16(ns) * 16;
-  const bf16::EmbedNextArgs embT{p.hT, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xT,
-                                 MpadT, p.ssT, D.V, w->err_flag};
   // every sequence ends within max_new steps of its start and a prompt is taken in whenever all the sequences of
   // an earlier one have ended, at the latest
   const long long step_limit = ((long long)p.total_prompts + 2) * ((long long)p.max_new + 2LL * period);
@@ -644,41 +642,51 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
         if (live[s]) ++region_users[slot_region[s]];
         else free_slots.push_back(s);
       }
-      size_t taken = 0;
-      int region = 0;
-      bool admitted = false;
-      while (next_prompt < p.total_prompts && free_slots.size() - taken >= (size_t)ns) {
-        while (region < p.n_regions && region_users[region] > 0) ++region;
-        if (region == p.n_regions) break;  // the last sequences of too many prompts still run: wait
-        const int q = next_prompt++;
-        bf16::AdmitArgs aa{p.page_table, p.row_pos, p.slot_row, p.row_step0, p.suffix_ids, prompts + (size_t)q * S,
-                           sa.prompt_lens + q, region, q, ns, S, p.max_pages, p.nf_max, p.shared_total, steps - 1,
-                           w->err_flag, {}};
-        for (int j = 0; j < ns; ++j) {
-          aa.slots[j] = free_slots[taken + j];
-          slot_region[aa.slots[j]] = region;
+      // the prompts that can join now: n_samples free slots and a free region each, no more than one prefill takes
+      std::vector<int> regions;
+      for (int r = 0; r < p.n_regions; ++r)
+        if (region_users[r] == 0) regions.push_back(r);
+      const int left = p.total_prompts - next_prompt;
+      const int k = std::min({(int)(free_slots.size() / ns), (int)regions.size(), left, p.chunk_prompts});
+      // a prefill costs about the same for one prompt as for a few: wait for a quarter of the batch, unless every
+      // slot is free or fewer prompts are left
+      const int k_min = std::min(left, std::max(1, p.n_prompts / 4));
+      const bool admitted = k >= k_min || (k > 0 && n_live == 0);
+      if (admitted) {
+        const int q0 = next_prompt;
+        next_prompt += k;
+        std::vector<bf16::AdmitArgs> adm(k);
+        for (int i = 0; i < k; ++i) {
+          const int q = q0 + i;
+          adm[i] = bf16::AdmitArgs{p.page_table, p.row_pos, p.slot_row, p.row_step0, p.suffix_ids + (size_t)i * S,
+                                   p.prefill_table + (size_t)i * p.max_pages, prompts + (size_t)q * S, sa.prompt_lens + q,
+                                   regions[i], q, ns, S, p.max_pages, p.nf_max, p.shared_total, steps - 1, w->err_flag, {}};
+          for (int j = 0; j < ns; ++j) {
+            adm[i].slots[j] = free_slots[(size_t)i * ns + j];
+            slot_region[adm[i].slots[j]] = regions[i];
+          }
+          bf16::admit_prompt(adm[i], st);
         }
-        taken += ns;
-        region_users[region] = ns;
-        bf16::admit_prompt(aa, st);
-        prefill(p.suffix_ids, 1, p.page_table + (size_t)aa.slots[0] * p.max_pages);
-        launch_gather_last_rows(p.hT, p.h, D.d, 1, ns, S, aa.len, 0, st);
-        bf16::fork_tail_slots(aa, pool, c.n_layers, st);
-        bf16::add_norm(p.hT, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xT, ns, tiles16(ns), D.d, w->err_flag, st);
-        // its step 0, as a batch of its own: rows q * ns .. of the call, a step counter of its own
+        prefill(p.suffix_ids, k, p.prefill_table, 1);
+        launch_gather_last_rows(p.hT, p.h, D.d, k, ns, S, sa.prompt_lens + q0, 0, st);
+        for (int i = 0; i < k; ++i) bf16::fork_tail_slots(adm[i], pool, c.n_layers, st);
+        const int rows = k * ns;
+        bf16::add_norm(p.hT, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xT, rows, tiles16(rows), D.d, w->err_flag, st);
+        // their step 0, as a batch of its own: rows q0 * ns .. of the call, a step counter of its own
         bf16::SampleCtl ct = ctl;
-        ct.seq_offset = sa.seq_offset + (uint32_t)(q * ns);
-        ct.out_ids = sa.out_ids + (size_t)q * ns * p.max_new;
-        ct.out_logprobs = sa.out_logprobs + (size_t)q * ns * p.max_new;
-        ct.done = p.done + (size_t)q * ns;
-        ct.out_lens = sa.out_lens + (size_t)q * ns;
+        ct.seq_offset = sa.seq_offset + (uint32_t)(q0 * ns);
+        ct.out_ids = sa.out_ids + (size_t)q0 * ns * p.max_new;
+        ct.out_logprobs = sa.out_logprobs + (size_t)q0 * ns * p.max_new;
+        ct.done = p.done + (size_t)q0 * ns;
+        ct.out_lens = sa.out_lens + (size_t)q0 * ns;
         ct.slot_row = nullptr;
         ct.row_step0 = nullptr;
         bf16::set_sample_ctl(d_ctl + 1, ct, st);
         launch_set_int(p.d_step + 8, 0, st);
         launch_set_int(p.d_step + 9, 0, st);
-        sample(st, (const h16_t*)p.xT, ns, nullptr, nullptr, d_ctl + 1, p.d_step + 8, p.cur_ids + (size_t)q * ns, embT);
-        admitted = true;
+        const bf16::EmbedNextArgs embT{p.hT, (const bf16_t*)w->embed, D.d, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.xT,
+                                       tiles16(rows) * 16, p.ssT, D.V, w->err_flag};
+        sample(st, (const h16_t*)p.xT, rows, nullptr, nullptr, d_ctl + 1, p.d_step + 8, p.cur_ids + (size_t)q0 * ns, embT);
       }
       // the first tokens of the new sequences become operands of the next step (the other slots get again what
       // they hold).  B, not the padded count: h has B rows
