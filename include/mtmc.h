@@ -292,7 +292,7 @@ const char* mtmc_data_error_string(int bits);
  *   Instantiated graphs are cached inside `w`, keyed by workspace address and the call's shape; replacing
  *   a cached graph (more than 8 are never kept) synchronises the device once.  When `stream` is itself being captured the steps
  *   are launched directly.
- *   MTMC_OPT_GEMM_LDS_MIN_BLOCKS (default 192, value >= 1): prefill / scoring GEMMs (MTMC_BF16)
+ *   MTMC_OPT_GEMM_LDS_MIN_BLOCKS (default 32, value >= 1): prefill / scoring GEMMs (MTMC_BF16)
  *   whose output has at least this many 256 x 256 blocks run in the LDS-staged kernel, smaller
  *   ones in the direct 128 x 128 kernel.  Both sum over K in the same order; results agree to
  *   the fp32 rounding inside the matrix instruction.

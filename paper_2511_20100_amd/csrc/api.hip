@@ -89,7 +89,7 @@ extern "C" int mtmc_weights_create(const mtmc_config* cfg, const void* blob, siz
   w->storage = nullptr;
   w->aux = nullptr;
   w->opt_hip_graph = 1;
-  w->opt_lds_min_blocks = 192;
+  w->opt_lds_min_blocks = 32;
   w->opt_stop_poll = 32;
   w->opt_admit = 1;
   w->graphs = nullptr;

@@ -91,18 +91,24 @@ enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
 // walks them in bands of LGM token blocks x all feature blocks, feature index slowest, so that the
 // ~32-64 workgroups resident on an XCD at one time share LGM activation panels and a few weight
 // panels through that L2.
+// With fewer token blocks than XCDs (a prompt or two) the XCDs share out the feature blocks instead, or most of them
+// would have nothing to do.
 constexpr int LGM = 4;
 struct LargeBlock { int nb, mb; bool valid; };
 __device__ __forceinline__ LargeBlock large_block(int L, int nb_n, int nb_m) {
+  const bool by_feature = nb_m < 8 && nb_n > nb_m;
+  const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
   const int xcd = L & 7, j = L >> 3;
-  const int band = j / (LGM * nb_n), r = j - band * (LGM * nb_n);
-  const int nb = r / LGM, mi = band * LGM + (r - nb * LGM);
-  const int mb = xcd + 8 * mi;
-  return LargeBlock{nb, mb, mb < nb_m};
+  const int band = j / (LGM * n_walk), r = j - band * (LGM * n_walk);
+  const int wb = r / LGM, oi = band * LGM + (r - wb * LGM);
+  const int ob = xcd + 8 * oi;
+  return by_feature ? LargeBlock{ob, wb, ob < n_own} : LargeBlock{wb, ob, ob < n_own};
 }
 static int large_grid(int nb_n, int nb_m) {
-  const int per_xcd = (nb_m + 7) / 8, bands = (per_xcd + LGM - 1) / LGM;
-  return 8 * bands * LGM * nb_n;
+  const bool by_feature = nb_m < 8 && nb_n > nb_m;
+  const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
+  const int per_xcd = (n_own + 7) / 8, bands = (per_xcd + LGM - 1) / LGM;
+  return 8 * bands * LGM * n_walk;
 }
 
 template <int EPI>

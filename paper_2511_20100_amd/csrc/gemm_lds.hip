@@ -63,19 +63,41 @@ __device__ __forceinline__ float silu_l(float g) {
 
 // Launch index -> output block: XCD (L % 8) owns token blocks xcd + 8 i and walks them in bands of
 // kBand token blocks x all feature blocks, so workgroups resident together on an XCD share panels
-// in its L2.
+// in its L2.  With fewer token blocks than XCDs (a prompt or two) the XCDs share out the feature blocks
+// instead, or most of them would have nothing to do.
 constexpr int kBand = 4;
 struct Block { int nb, mb; bool valid; };
 __device__ __forceinline__ Block block_of(int L, int nb_n, int nb_m) {
+  const bool by_feature = nb_m < 8 && nb_n > nb_m;
+  const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
   const int xcd = L & 7, j = L >> 3;
-  const int band = j / (kBand * nb_n), r = j - band * (kBand * nb_n);
-  const int nb = r / kBand, mi = band * kBand + (r - nb * kBand);
-  const int mb = xcd + 8 * mi;
-  return Block{nb, mb, mb < nb_m};
+  const int band = j / (kBand * n_walk), r = j - band * (kBand * n_walk);
+  const int wb = r / kBand, oi = band * kBand + (r - wb * kBand);
+  const int ob = xcd + 8 * oi;
+  return by_feature ? Block{ob, wb, ob < n_own} : Block{wb, ob, ob < n_own};
+}
+// The same order without the gaps: the t-th block of those an XCD owns (t < blocks_of_xcd), band by band; the
+// last band of an XCD is as high as the blocks it has left.  What a persistent workgroup walks: striding over
+// launch indices instead would give the indices that name no block to always the same workgroups.
+__device__ __forceinline__ int blocks_of_xcd(int xcd, int nb_n, int nb_m) {
+  const bool by_feature = nb_m < 8 && nb_n > nb_m;
+  const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
+  return xcd < n_own ? (n_own - xcd + 7) / 8 * n_walk : 0;
+}
+__device__ __forceinline__ Block block_of_xcd(int xcd, int t, int nb_n, int nb_m) {
+  const bool by_feature = nb_m < 8 && nb_n > nb_m;
+  const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
+  const int count = (n_own - xcd + 7) / 8;
+  const int band = t / (kBand * n_walk), r = t - band * (kBand * n_walk);
+  const int height = min(kBand, count - band * kBand);
+  const int wb = r / height, ob = xcd + 8 * (band * kBand + (r - wb * height));
+  return by_feature ? Block{ob, wb, true} : Block{wb, ob, true};
 }
 int grid_of(int nb_n, int nb_m) {
-  const int per_xcd = (nb_m + 7) / 8, bands = (per_xcd + kBand - 1) / kBand;
-  return 8 * bands * kBand * nb_n;
+  const bool by_feature = nb_m < 8 && nb_n > nb_m;
+  const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
+  const int per_xcd = (n_own + 7) / 8, bands = (per_xcd + kBand - 1) / kBand;
+  return 8 * bands * kBand * n_walk;
 }
 
 enum { LEPI_STORE = 0, LEPI_ADD = 1, LEPI_SWIGLU = 2 };
@@ -209,20 +231,18 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
   // rows packed on the device: only the row blocks that hold tokens are walked (the operand layout keeps the
   // stride of the full capacity)
   if (a.d_rows) nb_m = min(nb_m, (*a.d_rows + kBlkTiles * 16 - 1) / (kBlkTiles * 16));
-  // persistent workgroup: launch indices blockIdx.x, + gridDim.x, ... (gridDim.x is a multiple of 8, so all
-  // of them map to the same XCD); indices that name no block are skipped
-  const int total = 8 * ((((nb_m + 7) / 8) + kBand - 1) / kBand) * kBand * nb_n;
-  int L = (int)blockIdx.x - (int)gridDim.x;
+  // persistent workgroup: gridDim.x is a multiple of 8, so this workgroup and the gridDim.x / 8 - 1 others of its
+  // XCD share out the blocks the XCD owns, in the order block_of_xcd gives them
+  const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+  const int total = blocks_of_xcd(xcd, nb_n, nb_m);
+  int t = (int)(blockIdx.x >> 3) - stride;
   auto tile_at = [&](int, int& nt_base, int& mt_base) {
-    for (L += gridDim.x; L < total; L += gridDim.x) {
-      const Block blk = block_of(L, nb_n, nb_m);
-      if (blk.valid) {
-        nt_base = blk.nb * kBlkTiles;
-        mt_base = blk.mb * kBlkTiles;
-        return true;
-      }
-    }
-    return false;
+    t += stride;
+    if (t >= total) return false;
+    const Block blk = block_of_xcd(xcd, t, nb_n, nb_m);
+    nt_base = blk.nb * kBlkTiles;
+    mt_base = blk.mb * kBlkTiles;
+    return true;
   };
   auto epilogue = [&](v16f (&acc)[4][4], int nt_base, int mt_base) {
   // ---- epilogue: in a 32 x 32 block, lane holds token lane % 32 and features 8 q + 4 (lane / 32) + 0..3
