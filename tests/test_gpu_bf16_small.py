@@ -428,3 +428,29 @@ def test_lds_gemm_at_its_shortest_reduction(lib):
         assert (a.cpu().numpy() - sc["logprobs"]).__abs__().max() <= 1e-3
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+@pytest.mark.parametrize("n_seqs,S", [(2, 448), (3, 300), (7, 256), (8, 256), (9, 250), (17, 256), (33, 264)],
+                         ids=lambda v: str(v))
+def test_prefill_gemms_cover_every_block_at_any_number_of_token_blocks(lib, n_seqs, S):
+    """The prefill / scoring GEMMs hand their output blocks to the 8 XCDs by token block, or by feature block when
+    there are fewer than 8 token blocks, and the LDS-staged kernel's workgroups walk the blocks of their XCD band by
+    band (the last band is lower).  Token-block counts on both sides of 8, with full and partial bands, in both
+    kernels: one sequence against the oracle, and the two kernels against each other on every position (a block that
+    nobody computes leaves stale values)."""
+    import torch
+    cfg = inputs.ModelConfig(2, 256, 2, 1, 128, 1024, 4096, dtype="bf16")   # 8 gate/up blocks of 256, 2 QKV, 1 O / down
+    w = inputs.make_weights(cfg, seed=3, std=0.06, gain_std=0.1)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 512), w.blob())
+    try:
+        seqs = inputs.make_sequences(n_seqs, S, cfg.vocab, seed=9)
+        first = S - 40
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_GEMM_LDS_MIN_BLOCKS, 1)
+        sc = check_score(handle, w, seqs, first, max_positions=512, rows=[n_seqs - 1], label=f"lds-{n_seqs}x{S}")
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_GEMM_LDS_MIN_BLOCKS, 1 << 20)
+        direct = check_score(handle, w, seqs, first, max_positions=512, rows=[0], label=f"direct-{n_seqs}x{S}")
+        d = np.abs(direct["logprobs"] - sc["logprobs"]).max()
+        print(f"{n_seqs} x {S}: LDS err {sc['max_logp_err']:.2e}, direct err {direct['max_logp_err']:.2e}, LDS vs direct {d:.2e}")
+        assert d <= 3e-3   # two matrix instructions, two rounding orders; a missing block would be off by units
+    finally:
+        lib.mtmc_weights_destroy(handle)
