@@ -164,6 +164,8 @@ def inference_legs(torch, mtmc, dev, handle, weights, cfg, prompts, n_samples, m
     stop token: the same batch with one token made likely (its LM-head row scaled by 8: with the synthetic,
     nearly uniform policy no token would ever come up), so that rows end after tens of steps; the call that looks
     at the stop flags (rows give up their places, the call ends with the last row) against the one that does not.
+    prompts join a running batch: 1024 sequences with the same stop token in one call, which takes its prompts in as
+    sequences finish, against the same call run batch after batch.
     cached prefix: 32 new tokens on the same prompts, evaluating them whole against keeping all but their last
     64 positions from the previous call."""
     stream = torch.cuda.current_stream()
@@ -202,8 +204,9 @@ def inference_legs(torch, mtmc, dev, handle, weights, cfg, prompts, n_samples, m
                                 "rows_with_the_same_ids": int(same_ids.sum().item()), "rows": int(same_ids.numel()),
                                 "max_logprob_difference_on_those_rows":
                                     float((whole[1][same_ids] - kept[1][same_ids]).abs().max().item()) if same_ids.any() else None,
-                                "note": "512 tokens and 11 776 tokens run different matrix kernels (same sums, another "
-                                        "rounding order): the two calls agree to that rounding, not bit for bit"}
+                                "note": "512 tokens and 12 032 tokens run different matrix kernels for the O and down "
+                                        "projections (same sums, another rounding order): the two calls agree to that "
+                                        "rounding, not bit for bit"}
         progress(f"cached prefix: {ms_kept:.1f} ms against {ms_whole:.1f} ms")
         del ws, long_prompts
     stop = 7

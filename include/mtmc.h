@@ -131,7 +131,9 @@ int mtmc_rollout(const mtmc_weights* w, const int32_t* prompts, int32_t n_prompt
  * its log-probability are reported, every later slot of the row holds stop_id with log-probability
  * 0, and out_lens[b] = number of tokens generated including the stop token (max_new if none).
  * MTMC_BF16: finished sequences give up their place in the batch and the call ends when all have
- * finished (MTMC_OPT_STOP_POLL_STEPS); MTMC_F32: they keep their place.
+ * finished (MTMC_OPT_STOP_POLL_STEPS); a call with more sequences than one batch holds (128) runs as one
+ * batch that takes the call's next prompts in as sequences finish (MTMC_OPT_ADMIT_PROMPTS).  MTMC_F32: they
+ * keep their place.
  *
  * prompts      device int32 [n_prompts, max_prompt_len], right-padded
  * prompt_lens  device int32 [n_prompts], values in [1, max_prompt_len]; a value outside is clamped
@@ -307,6 +309,15 @@ const char* mtmc_data_error_string(int bits);
  *   the order of the fp32 sums, of the steps after it: log-probabilities then agree with the unpacked call's
  *   to about 1e-3 (an id can differ where two candidates are that close), and with the definition as
  *   closely as before.
+ *   MTMC_OPT_ADMIT_PROMPTS (default 1): a MTMC_BF16 mtmc_rollout_ragged call with a stop token, more than 128
+ *   sequences and MTMC_OPT_STOP_POLL_STEPS > 0 runs as one batch of 128 slots; every min(8, poll steps) steps the
+ *   calling thread waits for the stream, and prompts of the call that find n_samples free slots (left by
+ *   sequences that have ended) are prefilled and join the batch, each sequence at its own step; when no prompt is
+ *   left the sequences still running are packed as described above.  A sequence's random numbers go by its row and
+ *   its own step, so results are those of the call that runs batch after batch (value 0) up to the rounding order
+ *   of the fp32 sums (step 0 of a prompt that joins is sampled in a smaller batch, the packed batch runs other
+ *   tilings): about 1e-3 in a log-probability, an id can differ where two candidates are that close.  Not used
+ *   when `stream` is being captured, without a stop token, or with a cached prefix.
  */
 #define MTMC_OPT_HIP_GRAPH 1
 #define MTMC_OPT_GEMM_LDS_MIN_BLOCKS 2
