@@ -284,6 +284,22 @@ int mtmc_ppo_clip_loss_static(const float* new_logprobs, const float* old_logpro
 #define MTMC_DATA_LENGTH     4
 #define MTMC_DATA_FP16_RANGE 8
 #define MTMC_DATA_PREFIX     16
+/*
+ * Host logic of the rollout that takes in prompts as it runs (MTMC_OPT_ADMIT_PROMPTS), exposed so that it can be
+ * checked without a GPU; makes no GPU call.  Which of the call's remaining prompts join the batch at one look:
+ *   live [n_slots]         1 when the slot holds a sequence that still runs, else 0
+ *   slot_region [n_slots]  region of shared prompt pages that the slot's sequence reads (< n_regions)
+ * A prompt needs n_samples free slots and a region that no running sequence reads.  Returns
+ * k = min(free slots / n_samples, free regions, prompts_left, max_at_once), or 0 while k < min(prompts_left,
+ * wait_for) and some sequence still runs (a prefill costs about the same for one prompt as for a few);
+ * out_slots [k * n_samples] = the lowest free slots, n_samples per prompt, out_regions [k] = the lowest free
+ * regions (both host arrays with room for the largest k).  MTMC_EINVAL (negative) for a NULL pointer or a
+ * count below 1 (prompts_left may be 0).
+ */
+int mtmc_admission_plan(const int32_t* live, const int32_t* slot_region, int32_t n_slots, int32_t n_regions,
+                        int32_t n_samples, int32_t prompts_left, int32_t max_at_once, int32_t wait_for,
+                        int32_t* out_slots, int32_t* out_regions);
+
 int mtmc_poll_errors(const mtmc_weights* w, void* stream);
 const char* mtmc_data_error_string(int bits);
 

@@ -121,6 +121,18 @@ extern "C" void mtmc_weights_destroy(mtmc_weights* w) {
   delete w;
 }
 
+extern "C" int mtmc_admission_plan(const int32_t* live, const int32_t* slot_region, int32_t n_slots, int32_t n_regions,
+                                   int32_t n_samples, int32_t prompts_left, int32_t max_at_once, int32_t wait_for,
+                                   int32_t* out_slots, int32_t* out_regions) {
+  if (!live || !slot_region || !out_slots || !out_regions || n_slots < 1 || n_regions < 1 || n_samples < 1 ||
+      prompts_left < 0 || max_at_once < 1 || wait_for < 1) {
+    set_error("invalid argument: mtmc_admission_plan needs its arrays and counts of at least 1");
+    return MTMC_EINVAL;
+  }
+  return admission_plan(live, slot_region, n_slots, n_regions, n_samples, prompts_left, max_at_once, wait_for,
+                        out_slots, out_regions);
+}
+
 extern "C" int mtmc_set_option(mtmc_weights* w, int option, int value) {
   MTMC_REQUIRE(w != nullptr, "weights is NULL");
   MTMC_REQUIRE(option == MTMC_OPT_HIP_GRAPH || option == MTMC_OPT_GEMM_LDS_MIN_BLOCKS ||

@@ -518,6 +518,34 @@ int decode_graph(const mtmc_weights* w, const RolloutPlan& gp, hipStream_t st, S
 }
 
 
+}  // namespace
+
+int admission_plan(const int* live, const int* slot_region, int n_slots, int n_regions, int n_samples, int prompts_left,
+                   int max_at_once, int wait_for, int* out_slots, int* out_regions) {
+  std::vector<int> users(n_regions, 0);
+  int n_free = 0, n_live = 0;
+  for (int s = 0; s < n_slots; ++s) {
+    if (live[s]) {
+      ++n_live;
+      if (slot_region[s] >= 0 && slot_region[s] < n_regions) ++users[slot_region[s]];
+    } else {
+      ++n_free;
+    }
+  }
+  int free_regions = 0;
+  for (int r = 0; r < n_regions; ++r) free_regions += users[r] == 0;
+  const int k = std::min({n_free / n_samples, free_regions, prompts_left, max_at_once});
+  if (k <= 0 || (k < std::min(prompts_left, wait_for) && n_live > 0)) return 0;
+  int ns = 0, nr = 0;
+  for (int s = 0; s < n_slots && ns < k * n_samples; ++s)
+    if (!live[s]) out_slots[ns++] = s;
+  for (int r = 0; r < n_regions && nr < k; ++r)
+    if (users[r] == 0) out_regions[nr++] = r;
+  return k;
+}
+
+namespace {
+
 // A rollout with a stop token and more sequences than one batch holds, run as ONE batch that takes in the call's
 // prompts as it runs.  Every slot of the batch has pages of its own for a whole sequence; the whole pages of a prompt
 // lie in one of n_regions regions shared by the prompt's sequences.  The first n_prompts prompts start together as
@@ -610,7 +638,7 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
   hipGraphExec_t exec = nullptr;
   if (int rc = decode_graph(w, cur, st, decode_step, &exec)) return rc;
 
-  std::vector<int> slot_region(B), region_users(p.n_regions, 0);  // region a slot's sequence reads; -1: none
+  std::vector<int> slot_region(B), regions(p.n_regions);  // slot_region: the region a slot's sequence reads
   for (int s = 0; s < B; ++s) slot_region[s] = s / ns;
   int next_prompt = p.n_prompts, steps = 1;  // steps: value of *d_step once the queued work has run
   int* d_live = p.live + 16;
@@ -618,7 +646,7 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
   // every sequence ends within max_new steps of its start and a prompt is taken in whenever all the sequences of
   // an earlier one have ended, at the latest
   const long long step_limit = ((long long)p.total_prompts + 2) * ((long long)p.max_new + 2LL * period);
-  std::vector<int> free_slots;
+  std::vector<int> free_slots(B);
   for (;;) {
     for (int j = 0; j < period; ++j) {
       if (exec) MTMC_HIP_CHECK(hipGraphLaunch(exec, st));
@@ -636,22 +664,12 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
     int n_live = 0;
     for (int s = 0; s < B; ++s) n_live += live[s];
     if (next_prompt < p.total_prompts) {
-      std::fill(region_users.begin(), region_users.end(), 0);
-      free_slots.clear();
-      for (int s = 0; s < B; ++s) {
-        if (live[s]) ++region_users[slot_region[s]];
-        else free_slots.push_back(s);
-      }
-      // the prompts that can join now: n_samples free slots and a free region each, no more than one prefill takes
-      std::vector<int> regions;
-      for (int r = 0; r < p.n_regions; ++r)
-        if (region_users[r] == 0) regions.push_back(r);
-      const int left = p.total_prompts - next_prompt;
-      const int k = std::min({(int)(free_slots.size() / ns), (int)regions.size(), left, p.chunk_prompts});
       // a prefill costs about the same for one prompt as for a few: wait for a quarter of the batch, unless every
       // slot is free or fewer prompts are left
-      const int k_min = std::min(left, std::max(1, p.n_prompts / 4));
-      const bool admitted = k >= k_min || (k > 0 && n_live == 0);
+      const int left = p.total_prompts - next_prompt;
+      const int k = admission_plan(live, slot_region.data(), B, p.n_regions, ns, left, p.chunk_prompts,
+                                   std::max(1, p.n_prompts / 4), free_slots.data(), regions.data());
+      const bool admitted = k > 0;
       if (admitted) {
         const int q0 = next_prompt;
         next_prompt += k;

@@ -93,6 +93,8 @@ def _load() -> ctypes.CDLL:
     lib.mtmc_last_error.restype = ctypes.c_char_p
     lib.mtmc_data_error_string.argtypes = [ctypes.c_int]
     lib.mtmc_data_error_string.restype = ctypes.c_char_p
+    lib.mtmc_admission_plan.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.mtmc_admission_plan.restype = ctypes.c_int
     return lib
 
 
@@ -102,7 +104,8 @@ EXPORTS = ("mtmc_weights_create", "mtmc_weights_destroy", "mtmc_blob_bytes", "mt
            "mtmc_set_option", "mtmc_kernel_timer", "mtmc_kernel_timer_read", "mtmc_copy_probe",
            "mtmc_score_actions_workspace_bytes", "mtmc_score_actions", "mtmc_rollout_ragged_workspace_bytes",
            "mtmc_rollout_ragged", "mtmc_ppo_workspace_bytes", "mtmc_ppo_clip_loss", "mtmc_data_error_string",
-           "mtmc_ppo_clip_loss_static", "mtmc_read_probe", "mtmc_mfma_probe", "mtmc_rollout_ragged_cached")
+           "mtmc_ppo_clip_loss_static", "mtmc_read_probe", "mtmc_mfma_probe", "mtmc_rollout_ragged_cached",
+           "mtmc_admission_plan")
 
 
 def mtmc_last_error() -> str:
@@ -375,6 +378,22 @@ def mtmc_mfma_probe(out: torch.Tensor, workgroups: int, iters: int, stream: Opti
 
 def mtmc_poll_errors(handle: int, stream: Optional[torch.cuda.Stream] = None) -> None:
     _check(_lib.mtmc_poll_errors(handle, _stream_ptr(stream)))
+
+
+def mtmc_admission_plan(live, slot_region, n_regions: int, n_samples: int, prompts_left: int, max_at_once: int,
+                        wait_for: int):
+    """Host arrays in (numpy int32 [n_slots]); returns (slots [k, n_samples], regions [k]) as numpy arrays."""
+    import numpy as np
+    live = np.ascontiguousarray(live, dtype=np.int32)
+    slot_region = np.ascontiguousarray(slot_region, dtype=np.int32)
+    assert live.ndim == 1 and live.shape == slot_region.shape
+    slots = np.zeros(max(live.size, 1), dtype=np.int32)
+    regions = np.zeros(max(n_regions, 1), dtype=np.int32)
+    k = _lib.mtmc_admission_plan(live.ctypes.data, slot_region.ctypes.data, live.size, n_regions, n_samples, prompts_left,
+                                 max_at_once, wait_for, slots.ctypes.data, regions.ctypes.data)
+    if k < 0:
+        raise MtmcError(k, mtmc_last_error())
+    return slots[:k * n_samples].reshape(k, n_samples).copy(), regions[:k].copy()
 
 
 def mtmc_data_error_string(bits: int) -> str:
