@@ -291,7 +291,7 @@ int mtmc_ppo_clip_loss_static(const float* new_logprobs, const float* old_logpro
  *   slot_region [n_slots]  region of shared prompt pages that the slot's sequence reads (< n_regions)
  * A prompt needs n_samples free slots and a region that no running sequence reads.  Returns
  * k = min(free slots / n_samples, free regions, prompts_left, max_at_once), or 0 while k < min(prompts_left,
- * wait_for) and some sequence still runs (a prefill costs about the same for one prompt as for a few);
+ * wait_for, max_at_once) and some sequence still runs (a prefill costs about the same for one prompt as for a few);
  * out_slots [k * n_samples] = the lowest free slots, n_samples per prompt, out_regions [k] = the lowest free
  * regions (both host arrays with room for the largest k).  MTMC_EINVAL (negative) for a NULL pointer or a
  * count below 1 (prompts_left may be 0).

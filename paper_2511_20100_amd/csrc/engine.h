@@ -205,7 +205,7 @@ int bf16_store_weights(mtmc_weights* w, const BlobLayout& lay, const void* blob,
 // Which prompts join a running batch at one look (host only).  live [n_slots]: the slot holds a sequence that still
 // runs; slot_region [n_slots]: the region of shared prompt pages that sequence reads.  A prompt needs n_samples free
 // slots and a region that no running sequence reads.  Returns k = min(free slots / n_samples, free regions,
-// prompts_left, max_at_once), or 0 while k < min(prompts_left, wait_for) and some sequence still runs; out_slots
+// prompts_left, max_at_once), or 0 while k < min(prompts_left, wait_for, max_at_once) and some sequence still runs; out_slots
 // [k * n_samples] = the lowest free slots, prompt by prompt, out_regions [k] = the lowest free regions.
 int admission_plan(const int* live, const int* slot_region, int n_slots, int n_regions, int n_samples, int prompts_left,
                    int max_at_once, int wait_for, int* out_slots, int* out_regions);

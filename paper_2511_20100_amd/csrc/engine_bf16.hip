@@ -535,7 +535,7 @@ int admission_plan(const int* live, const int* slot_region, int n_slots, int n_r
   int free_regions = 0;
   for (int r = 0; r < n_regions; ++r) free_regions += users[r] == 0;
   const int k = std::min({n_free / n_samples, free_regions, prompts_left, max_at_once});
-  if (k <= 0 || (k < std::min(prompts_left, wait_for) && n_live > 0)) return 0;
+  if (k <= 0 || (k < std::min({prompts_left, wait_for, max_at_once}) && n_live > 0)) return 0;
   int ns = 0, nr = 0;
   for (int s = 0; s < n_slots && ns < k * n_samples; ++s)
     if (!live[s]) out_slots[ns++] = s;

@@ -14,7 +14,7 @@ def brute(live, slot_region, n_regions, ns, left, max_at_once, wait_for):
     used = {int(slot_region[s]) for s in range(len(live)) if live[s]}
     free_regions = [r for r in range(n_regions) if r not in used]
     k = min(len(free) // ns, len(free_regions), left, max_at_once)
-    if k <= 0 or (k < min(left, wait_for) and any(live)):
+    if k <= 0 or (k < min(left, wait_for, max_at_once) and any(live)):
         k = 0
     return k, free[:k * ns], free_regions[:k]
 
@@ -75,3 +75,12 @@ def test_bad_arguments_are_rejected():
         mtmc.mtmc_admission_plan(one, one, 0, 1, 1, 1, 1)
     with pytest.raises(mtmc.MtmcError):
         mtmc.mtmc_admission_plan(one, one, 2, 0, 1, 1, 1)
+
+
+def test_never_waits_for_more_than_one_prefill_takes():
+    ns = 8
+    slot_region = (np.arange(128) // ns).astype(np.int32)
+    live = np.ones(128, dtype=np.int32)
+    live[:16] = 0                                       # two prompts' slots are free, a prefill takes two (long prompts)
+    s, r = mtmc.mtmc_admission_plan(live, slot_region, 64, ns, 10, 2, 4)
+    assert s.shape[0] == 2

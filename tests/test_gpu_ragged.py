@@ -6,7 +6,7 @@ pytestmark = pytest.mark.gpu
 
 import mtmc_oracle as oracle
 from helpers import oracle_model
-from parity import LOGP_TOL_BF16, check_ragged_by_replay
+from parity import LOGP_TOL_BF16, MARGIN_GATE, check_ragged_by_replay
 from paper_2511_20100_amd import inputs
 
 SMALL = inputs.ModelConfig(2, 256, 4, 2, 128, 688, 4096, dtype="bf16")
@@ -359,5 +359,68 @@ def test_new_prompts_take_the_places_of_finished_ones(lib, name, cfg, n_prompts,
         lib.mtmc_rollout_ragged(handle, dev(prompts), dev(bad), n_samples, max_new, 1.0, 1, stop_id=stop)
         with pytest.raises(lib.MtmcError, match="length"):
             lib.mtmc_poll_errors(handle)
+    finally:
+        lib.mtmc_weights_destroy(handle)
+
+
+EDGE = [
+    # name, cfg, prompt lengths (cycled over n_prompts), n_prompts, n_samples, max_new, temperature, graph
+    ("one-sample-per-prompt", STOPPY, [5, 16, 33], 150, 1, 40, 1.0, 1),          # 128 places of one slot
+    ("128-samples-one-place", STOPPY16, [20, 7, 48], 3, 128, 60, 1.0, 1),        # a prompt fills the batch: joins only when all have ended
+    ("two-steps", STOPPY16, [9, 32], 40, 8, 2, 1.0, 1),                           # every row ends at its step 0 or 1
+    ("greedy", STOPPY16, [12, 30, 16], 40, 8, 50, 0.0, 1),                        # the 8 samples of a prompt are the same sequence
+    ("whole-pages-no-graph", STOPPY, [16, 32, 48], 36, 8, 48, 1.0, 0),            # no partly filled page to fork; steps launched directly
+    ("long-prompts-two-per-prefill", STOPPY16, [4000, 3990], 22, 8, 24, 1.0, 1),  # a prefill takes two of these prompts at most
+]
+
+
+@pytest.mark.parametrize("name,cfg,lens,n_prompts,n_samples,max_new,temp,graph", EDGE, ids=[e[0] for e in EDGE])
+def test_joining_prompts_edge_cases(lib, name, cfg, lens, n_prompts, n_samples, max_new, temp, graph):
+    import torch
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
+    max_len = max(lens)
+    positions = (max_len + max_new + 63) // 64 * 64
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, positions), w.blob())
+    try:
+        lens = np.array([lens[i % len(lens)] for i in range(n_prompts)], dtype=np.int32)
+        prompts = inputs.make_prompts(n_prompts, max_len, cfg.vocab, seed=2)
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_HIP_GRAPH, graph)
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_STOP_POLL_STEPS, 4)
+        dev = lambda x: torch.from_numpy(x).cuda()
+        ids, lp, n = lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), n_samples, max_new, temp, 3, stop_id=3)
+        lib.mtmc_poll_errors(handle)
+        ids, lp, n = ids.cpu().numpy(), lp.cpu().numpy(), n.cpu().numpy()
+        print(name, "lengths: min", n.min(), "median", int(np.median(n)), "max", n.max(), "of", n.size, "rows")
+        # every row: ends at its first stop token, stop_id / 0 behind it
+        for b in range(ids.shape[0]):
+            hits = np.nonzero(ids[b] == 3)[0]
+            end = int(hits[0]) + 1 if hits.size else max_new
+            assert n[b] == end and np.all(ids[b, end:] == 3) and np.all(lp[b, end:] == 0.0), (name, b)
+            assert np.all(lp[b, :end] < 0.0) and np.all(np.isfinite(lp[b, :end]))
+        if temp == 0.0:
+            g = ids.reshape(n_prompts, n_samples, max_new)
+            assert np.all(g == g[:, :1])
+        # rows spread over the call (first batch, joined early, joined last) against the oracle
+        model = oracle_model(w, positions)
+        rows = sorted({0, n_samples - 1, ids.shape[0] // 2, ids.shape[0] - n_samples, ids.shape[0] - 1})
+        worst = 0.0
+        for b in rows:
+            p, e = b // n_samples, int(n[b])
+            tok, ref_lp, margin = oracle.replay(model, prompts[p, :lens[p]], ids[b, :e], temp, 3, b)
+            gate = margin > MARGIN_GATE
+            assert np.array_equal(tok[gate], ids[b, :e][gate]), (name, b)
+            worst = max(worst, float(np.abs(ref_lp - lp[b, :e]).max()))
+        print(name, "rows", rows, "max log-prob err", worst)
+        assert worst <= LOGP_TOL_BF16
+        # the same call again, and batch after batch
+        again = lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), n_samples, max_new, temp, 3, stop_id=3)
+        assert np.array_equal(again[0].cpu().numpy(), ids) and np.array_equal(again[1].cpu().numpy(), lp)
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_ADMIT_PROMPTS, 0)
+        other = lib.mtmc_rollout_ragged(handle, dev(prompts), dev(lens), n_samples, max_new, temp, 3, stop_id=3)
+        lib.mtmc_poll_errors(handle)
+        same = (other[0].cpu().numpy() == ids).all(axis=1)
+        print(name, "rows identical to the batch-after-batch call:", int(same.sum()), "of", same.size)
+        assert same.mean() >= 0.6
+        assert np.abs(other[1].cpu().numpy()[same] - lp[same]).max() <= 5e-3
     finally:
         lib.mtmc_weights_destroy(handle)
