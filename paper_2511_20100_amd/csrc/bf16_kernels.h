@@ -40,6 +40,8 @@ struct LargeArgs {
   h16_t* out_bf16;
   int* err_flag;         // SwiGLU epilogue: raised when a value does not fit fp16
   const int* d_rows;     // optional (device): only the first *d_rows rows hold tokens; blocks of rows beyond are skipped
+  int k_split;           // split-K form: ranges of k-steps, and the partial sums [k_split][M][N] (set by its launcher)
+  float* part;
 };
 
 struct ScoreHeadArgs {
@@ -179,13 +181,18 @@ void retile_gate_up(h16_t* dst, const bf16_t* gate, const bf16_t* up, int F, int
 // ---- GEMMs ---------------------------------------------------------------------------------
 // d_rows (device, may be NULL): the number of rows that hold tokens when it is known on the device only (rows
 // packed by a kernel); M and m_tiles then give the capacity the launch is sized for.
+// part (device, may be NULL) / part_floats: room for partial sums; with it, an output of few 256 x 256 blocks is
+// computed over several ranges of K at once (gemm_lds_split) and summed in a fixed order.
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
                     int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, const int* d_rows,
-                    hipStream_t st);
+                    hipStream_t st, float* part = nullptr, size_t part_floats = 0);
 void gemm_large_swiglu(h16_t* act, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt,
                        int M, int m_tiles, int lds_min_blocks, int* err_flag, const int* d_rows, hipStream_t st);
 // LDS-staged 256 x 256 kernel behind the two launchers above (epi: 0 store, 1 accumulate, 2 SwiGLU).
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st);
+// Split-K form of the store / accumulate GEMM for outputs of at most 128 blocks: false when it does not apply
+// (no range count from 2 to 8 divides K into even ranges of at least 8 k-steps that fit `part`), and nothing was launched.
+bool gemm_lds_split(const LargeArgs& a, bool accumulate, float* part, size_t part_floats, hipStream_t st);
 int score_head_blocks(int n_tiles, int* groups_per_block);
 void lmhead_score(float* part, const h16_t* Wt, int n_tiles, int k_tiles, const h16_t* Xt, int M,
                   int m_tiles, const int* targets, bool want_top, int lds_min_blocks, const int* d_rows,

@@ -28,6 +28,8 @@ struct Carver {
   }
 };
 
+constexpr size_t kGemmPartFloats = (size_t)16 << 20;  // 64 MiB: up to 8 ranges of K for the outputs that are split
+
 struct RolloutPlan {
   // A call is run as consecutive groups of `n_prompts` prompts (B = n_prompts * n_samples
   // sequences each); all sizes below are per group.
@@ -78,6 +80,7 @@ struct RolloutPlan {
   void* o_chunks;     // decode-attention output per context chunk: n_chunks tiled fp16 operands [Hq*hd, bt*16]
   float* attn_ml;     // (max, sum) per (sequence, head, chunk) for the O projection to combine the chunks
   float* lm_part;     // LM-head per-tile partial reductions
+  float* gemm_part;   // partial sums of the prefill GEMMs' split-K form (kGemmPartFloats)
   void* qb;           // rotated queries, bf16 row-major [Tmax, Hq*hd]
   void* ctl;          // per-call sampling parameters (device copy)
   float* ssA;         // per-tile sums of squares of the residual rows (two generations)

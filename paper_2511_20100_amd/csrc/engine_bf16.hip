@@ -328,6 +328,7 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   p.attn_ml = cv.take<float>(attn_ml);
   p.lm_part = cv.take<float>((size_t)((D.nt_V + 1) / 2) * Mpad * 8);
   p.qb = cv.take<h16_t>((size_t)p.Tmax * D.nq);
+  p.gemm_part = cv.take<float>(kGemmPartFloats);
   p.ctl = cv.take<bf16::SampleCtl>(2);
   p.ssA = cv.take<float>((size_t)D.nt_d * Mpad);
   p.ssB = cv.take<float>((size_t)D.nt_d * Mpad);
@@ -383,20 +384,21 @@ namespace {
 // length possible and n_seqs * S the capacity the launches are sized for.
 void prefill_layers(const mtmc_weights* w, const Dims& D, float* h, h16_t* x, float* qkv, h16_t* qb,
                     h16_t* o, h16_t* a, int n_seqs, int S, TokMap map, KvPool pool, int layer_stride,
-                    hipStream_t st, const int* seq_start = nullptr, const int* d_rows = nullptr) {
+                    hipStream_t st, const int* seq_start = nullptr, const int* d_rows = nullptr, float* part = nullptr) {
   const mtmc_config& c = w->cfg;
   const int T = n_seqs * S, mt = tiles16(T), lmb = w->opt_lds_min_blocks;
+  const size_t pf = part ? kGemmPartFloats : 0;  // partial sums of the split-K GEMMs (a prompt or a few)
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& L = w->layers[l];
     const int kvl = l * layer_stride;
-    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, d_rows, st);
+    bf16::gemm_large_f32(qkv, D.nqkv, D.nqkv, false, (const h16_t*)L.wqkv, D.nt_qkv, D.kt_d, x, T, mt, lmb, d_rows, st, part, pf);
     bf16::rope_kv_write(qb, qkv, D.nqkv, T, S, D.Hq, D.Hkv, w->rope_cos, w->rope_sin, map, pool, kvl, w->err_flag, st,
                         seq_start, n_seqs);
     bf16::attention_prefill(o, qb, n_seqs, S, mt, D.Hq, D.Hkv, map, pool, kvl, w->err_flag, st, seq_start);
-    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, d_rows, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wo, D.nt_d, D.kt_nq, o, T, mt, lmb, d_rows, st, part, pf);
     bf16::add_norm(h, nullptr, 0, 0, 0, L.ffn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st, d_rows);
     bf16::gemm_large_swiglu(a, (const h16_t*)L.wgu, D.nt_gu, D.kt_d, x, T, mt, lmb, w->err_flag, d_rows, st);
-    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, lmb, d_rows, st);
+    bf16::gemm_large_f32(h, D.d, D.d, true, (const h16_t*)L.wdown, D.nt_d, D.kt_F, a, T, mt, lmb, d_rows, st, part, pf);
     if (l + 1 < c.n_layers)
       bf16::add_norm(h, nullptr, 0, 0, 0, w->layers[l + 1].attn_norm, c.rms_eps, x, T, mt, D.d, w->err_flag, st, d_rows);
   }
@@ -592,7 +594,8 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
     TokMap map{S, rows_per_prompt, 0, nullptr};
     bf16::embed(p.h, ids, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
     bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
-    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, S, map, ppool, 1, st);
+    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, S, map, ppool, 1, st, nullptr,
+                   nullptr, p.gemm_part);
   };
   for (int p0 = 0; p0 < p.n_prompts; p0 += p.chunk_prompts) {
     const int np = std::min(p.chunk_prompts, p.n_prompts - p0);
@@ -799,7 +802,7 @@ int bf16_rollout(const mtmc_weights* w, const RolloutPlan& p, const int* prompts
       bf16::embed(p.h, gprompts + (size_t)p0 * S, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
       bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
       prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, np, S, map, chunk_pool, 1,
-                     st);
+                     st, nullptr, nullptr, p.gemm_part);
       if (ragged)
         launch_gather_last_rows(p.hB + (size_t)p0 * p.n_samples * D.d, p.h, D.d, np, p.n_samples, p.prompt_len,
                                 glens + p0, R, st);

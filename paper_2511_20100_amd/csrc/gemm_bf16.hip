@@ -170,11 +170,12 @@ static bool use_lds_kernel(int n_tiles, int k_tiles, int m_tiles, int lds_min_bl
 }
 void gemm_large_f32(float* C, int ldc, int N, bool accumulate, const h16_t* Wt, int n_tiles,
                     int k_tiles, const h16_t* Xt, int M, int m_tiles, int lds_min_blocks, const int* d_rows,
-                    hipStream_t st) {
+                    hipStream_t st, float* part, size_t part_floats) {
   LargeArgs a{};
   a.Wt = Wt; a.Xt = Xt; a.n_tiles = n_tiles; a.k_tiles = k_tiles; a.m_tiles = m_tiles; a.M = M; a.N = N;
   a.out_f32 = C; a.ld_out = ldc; a.d_rows = d_rows;
   const int epi = accumulate ? LEPI_ADD : LEPI_STORE;
+  if (part && gemm_lds_split(a, accumulate, part, part_floats, st)) return;
   if (use_lds_kernel(n_tiles, k_tiles, m_tiles, lds_min_blocks)) gemm_lds(a, epi, st);
   else launch_large(a, epi, st);
 }

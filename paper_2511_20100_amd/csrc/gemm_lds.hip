@@ -79,7 +79,7 @@ __device__ __forceinline__ Block block_of(int L, int nb_n, int nb_m) {
 // The same order without the gaps: the t-th block of those an XCD owns (t < blocks_of_xcd), band by band; the
 // last band of an XCD is as high as the blocks it has left.  What a persistent workgroup walks: striding over
 // launch indices instead would give the indices that name no block to always the same workgroups.
-__device__ __forceinline__ int blocks_of_xcd(int xcd, int nb_n, int nb_m) {
+__host__ __device__ __forceinline__ int blocks_of_xcd(int xcd, int nb_n, int nb_m) {
   const bool by_feature = nb_m < 8 && nb_n > nb_m;
   const int n_walk = by_feature ? nb_m : nb_n, n_own = by_feature ? nb_n : nb_m;
   return xcd < n_own ? (n_own - xcd + 7) / 8 * n_walk : 0;
@@ -110,12 +110,12 @@ struct TileSrc {
   const uint8_t* x[4];
 };
 __device__ __forceinline__ TileSrc tile_src(const uint8_t* Wt, const uint8_t* Xt, int n_tiles, int m_tiles, int K,
-                                            int nt_base, int mt_base, int uwave) {
+                                            int nt_base, int mt_base, int uwave, int k0 = 0) {
   TileSrc t;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    t.w[j] = Wt + ((size_t)min(nt_base + 4 * uwave + j, n_tiles - 1) * K) * 1024;
-    t.x[j] = Xt + (size_t)min(mt_base + 4 * uwave + j, m_tiles - 1) * 1024;
+    t.w[j] = Wt + ((size_t)min(nt_base + 4 * uwave + j, n_tiles - 1) * K + k0) * 1024;
+    t.x[j] = Xt + ((size_t)k0 * m_tiles + min(mt_base + 4 * uwave + j, m_tiles - 1)) * 1024;
   }
   return t;
 }
@@ -127,12 +127,18 @@ __device__ __forceinline__ TileSrc tile_src(const uint8_t* Wt, const uint8_t* Xt
 // kStages LDS buffers: while the last steps of a block are multiplied the first steps of the next one are
 // already being fetched, and its first fragments are read, so that a new block starts without refilling
 // the pipeline and its copies run under the epilogue of the previous one.  K >= kStages and even.
-template <typename TileAt, typename Epilogue>
+// SPLIT: a work item is an output block over k-steps k0 .. k0 + Ks - 1 only (tile_at also names k0, the epilogue
+// gets it); the rows of W are still K k-steps long.  Ks >= kStages and even.
+template <bool SPLIT = false, typename TileAt, typename Epilogue>
 __device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t* Xt, int n_tiles, int m_tiles, int K,
                                                 uint8_t* lds, int lane, int uwave, int wn, int wm, TileAt tile_at,
-                                                Epilogue epilogue) {
-  int nt_base = 0, mt_base = 0;
-  if (!tile_at(0, nt_base, mt_base)) return;  // whole workgroup
+                                                Epilogue epilogue, int Ks = 0) {
+  int nt_base = 0, mt_base = 0, k0 = 0;
+  const int KL = SPLIT ? Ks : K;  // k-steps of a work item
+  bool any;
+  if constexpr (SPLIT) any = tile_at(0, nt_base, mt_base, k0);
+  else any = tile_at(0, nt_base, mt_base);
+  if (!any) return;  // whole workgroup
   const size_t xstep = (size_t)m_tiles * 1024;
   const uint32_t lane16 = lane * 16;
   // A 32-row operand of the 32x32x16 MFMA (lane l: row l % 32, 8 consecutive k of half l / 32) is
@@ -152,7 +158,7 @@ __device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t
     else copy_block_to_lds(t.x[j - 4] + (size_t)kk * xstep + lane16, sb + (kBlkTiles + j - 4) * 1024);
   };
 
-  TileSrc cur = tile_src(Wt, Xt, n_tiles, m_tiles, K, nt_base, mt_base, uwave);
+  TileSrc cur = tile_src(Wt, Xt, n_tiles, m_tiles, K, nt_base, mt_base, uwave, k0);
   // ---- fill the ring with the first kStages steps of the first block, read its first fragments
 #pragma unroll
   for (int s = 0; s < kStages; ++s)
@@ -166,9 +172,11 @@ __device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t
 
   int g0 = 0;  // stream index of step 0 of the current block (step g lives in buffer g % kStages)
   for (int ti = 0;; ++ti) {
-    int nt_next = 0, mt_next = 0;
-    const bool has_next = tile_at(ti + 1, nt_next, mt_next);
-    const TileSrc nxt = has_next ? tile_src(Wt, Xt, n_tiles, m_tiles, K, nt_next, mt_next, uwave) : cur;
+    int nt_next = 0, mt_next = 0, k0_next = 0;
+    bool has_next;
+    if constexpr (SPLIT) has_next = tile_at(ti + 1, nt_next, mt_next, k0_next);
+    else has_next = tile_at(ti + 1, nt_next, mt_next);
+    const TileSrc nxt = has_next ? tile_src(Wt, Xt, n_tiles, m_tiles, K, nt_next, mt_next, uwave, k0_next) : cur;
     v16f acc[4][4];
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb)
@@ -190,9 +198,9 @@ __device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t
       uint8_t* fbuf = lds + (g % kStages) * kStageBytes + uwave * 4096;
       // step g + kStages: of this block, else of the next one, else (nothing follows) a clamped copy nobody reads
       const int ka = kt + kStages;
-      const bool own = ka < K;
+      const bool own = ka < KL;
       const TileSrc& src = own ? cur : nxt;
-      const int kk = own ? ka : (has_next ? ka - K : K - 1);
+      const int kk = own ? ka : (has_next ? ka - KL : KL - 1);
 #pragma unroll
       for (int i = 0; i < 32; ++i) {
         const int pp = i >> 4, nb = (i >> 2) & 3, mb = i & 3;
@@ -201,21 +209,23 @@ __device__ __forceinline__ void lds_gemm_stream(const uint8_t* Wt, const uint8_t
         if ((i & 3) == 1) issue_one(src, kk, fbuf, i >> 2);
       }
     };
-    for (int kt = 0; kt < K; kt += 2) {
+    for (int kt = 0; kt < KL; kt += 2) {
       step(fa, fb, kt);
       step(fb, fa, kt + 1);
     }
-    g0 += K;
+    g0 += KL;
     // the last MFMAs were issued from inline assembly: give them time to retire before their accumulators
     // are read (16 passes of 4 cycles cover the longest one)
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-    epilogue(acc, nt_base, mt_base);
+    if constexpr (SPLIT) epilogue(acc, nt_base, mt_base, k0);
+    else epilogue(acc, nt_base, mt_base);
     if (!has_next) break;
     // the epilogue's stores (and loads) share the counter with the copies: drain it so that the waits of the
     // next block count copies only (they have been flying under the epilogue)
     wait_vmcnt<0>();
     nt_base = nt_next;
     mt_base = mt_next;
+    k0 = k0_next;
     cur = nxt;
   }
   wait_vmcnt<0>();  // the clamped copies past the last step still target this workgroup's LDS
@@ -315,6 +325,79 @@ __global__ __launch_bounds__(256, 1) void k_gemm_lds(LargeArgs a) {
 };
   lds_gemm_stream(reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles, a.m_tiles,
                   a.k_tiles, lds, lane, __builtin_amdgcn_readfirstlane(wave), wn, wm, tile_at, epilogue);
+}
+
+// Split-K form for outputs of few blocks and a long reduction (the O and down projections, and the QKV projection,
+// of a prompt or a few: 12-128 blocks for 256 CUs): a work item is one output block over one of a.k_split equal
+// ranges of k-steps, the items of a block are neighbours in an XCD's walk, and every item stores its sum as fp32
+// into its own slice of a.part ([k_split][M][N]); k_splitk_reduce then adds the slices in order, so the result does
+// not depend on which workgroup ran when.
+__global__ __launch_bounds__(256, 1) void k_gemm_lds_split(LargeArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int nb_n = (a.n_tiles + kBlkTiles - 1) / kBlkTiles;
+  int nb_m = (a.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  if (a.d_rows) nb_m = min(nb_m, (*a.d_rows + kBlkTiles * 16 - 1) / (kBlkTiles * 16));
+  const int S = a.k_split, Ks = a.k_tiles / S;
+  const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+  const int total = blocks_of_xcd(xcd, nb_n, nb_m) * S;
+  int t = (int)(blockIdx.x >> 3) - stride;
+  auto tile_at = [&](int, int& nt_base, int& mt_base, int& k0) {
+    t += stride;
+    if (t >= total) return false;
+    const Block blk = block_of_xcd(xcd, t / S, nb_n, nb_m);
+    nt_base = blk.nb * kBlkTiles;
+    mt_base = blk.mb * kBlkTiles;
+    k0 = (t % S) * Ks;
+    return true;
+  };
+  auto epilogue = [&](v16f (&acc)[4][4], int nt_base, int mt_base, int k0) {
+    // as the store form of k_gemm_lds: every 32 x 32 block is turned round in a wavefront-private LDS tile so that
+    // a store instruction covers 8 rows of 128 contiguous bytes
+    float* out = a.part + (size_t)(k0 / Ks) * a.M * a.N;
+    const int col = lane & 31, rh = (lane >> 5) * 4;
+    const int f = (lane & 7) * 4, trow = lane >> 3;
+    float* tb = reinterpret_cast<float*>(lds + kStages * kStageBytes) + wave * (32 * kTrRow);
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        asm volatile("" : "+a"(acc[nb][mb])::"memory");
+        const int n0 = (nt_base + 8 * wn + 2 * nb) * 16;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<v4f*>(tb + col * kTrRow + 8 * q + rh) =
+              v4f{acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
+        __builtin_amdgcn_wave_barrier();
+        const int m0 = (mt_base + 8 * wm + 2 * mb) * 16, n = n0 + f;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+          const int row = pass * 8 + trow, mm = m0 + row;
+          const v4f v = *reinterpret_cast<const v4f*>(tb + row * kTrRow + f);
+          if (mm < a.M && n < a.N) *reinterpret_cast<v4f*>(out + (size_t)mm * a.N + n) = v;
+        }
+        __builtin_amdgcn_wave_barrier();  // the tile is reused by the next accumulator block
+      }
+    }
+  };
+  lds_gemm_stream<true>(reinterpret_cast<const uint8_t*>(a.Wt), reinterpret_cast<const uint8_t*>(a.Xt), a.n_tiles,
+                        a.m_tiles, a.k_tiles, lds, lane, __builtin_amdgcn_readfirstlane(wave), wn, wm, tile_at, epilogue,
+                        Ks);
+}
+
+// out (+)= part[0] + part[1] + ... in that order; four features per thread
+__global__ __launch_bounds__(256) void k_splitk_reduce(float* out, int ld_out, const float* part, int S, int M, int N,
+                                                       int accumulate, const int* d_rows) {
+  const int n4 = N >> 2;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)M * n4) return;
+  const int m = (int)(i / n4), n = (int)(i - (size_t)m * n4) * 4;
+  if (d_rows && m >= *d_rows) return;
+  float* o = out + (size_t)m * ld_out + n;
+  v4f acc = accumulate ? *reinterpret_cast<const v4f*>(o) : v4f{0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < S; ++s) acc = acc + *reinterpret_cast<const v4f*>(part + ((size_t)s * M + m) * N + n);
+  *reinterpret_cast<v4f*>(o) = acc;
 }
 
 // Scoring LM head on the same engine: a workgroup owns 256 rows and one vocabulary slice (8 blocks of
@@ -464,6 +547,35 @@ void lmhead_score_lds(const ScoreHeadArgs& a, int slices, hipStream_t st) {
     configured = true;
   }
   k_lmhead_lds<<<grid_of(slices, (a.m_tiles + kBlkTiles - 1) / kBlkTiles), 256, lds_bytes, st>>>(a, slices);
+}
+
+bool gemm_lds_split(const LargeArgs& a0, bool accumulate, float* part, size_t part_floats, hipStream_t st) {
+  const int nb_n = (a0.n_tiles + kBlkTiles - 1) / kBlkTiles, nb_m = (a0.m_tiles + kBlkTiles - 1) / kBlkTiles;
+  const int blocks = nb_n * nb_m;
+  if (!part || blocks > kPersistentGrid / 2 || a0.N % 4 != 0) return false;
+  // the most splits, up to 8 and to one round of workgroups, that leave every range even and at least 8 k-steps long
+  int S = 0;
+  for (int s = std::min(8, kPersistentGrid / blocks); s >= 2 && !S; --s)
+    if (a0.k_tiles % s == 0 && (a0.k_tiles / s) % 2 == 0 && a0.k_tiles / s >= 8 &&
+        (size_t)s * a0.M * a0.N <= part_floats)
+      S = s;
+  if (!S) return false;
+  static bool configured = false;
+  const int lds_bytes = kStages * kStageBytes + kTrBytes;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_lds_split), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              lds_bytes);
+    configured = true;
+  }
+  LargeArgs a = a0;
+  a.k_split = S;
+  a.part = part;
+  const int grid = std::min(kPersistentGrid, 8 * blocks_of_xcd(0, nb_n, nb_m) * S);
+  k_gemm_lds_split<<<grid, 256, lds_bytes, st>>>(a);
+  const size_t quads = (size_t)a.M * (a.N / 4);
+  k_splitk_reduce<<<(unsigned)((quads + 255) / 256), 256, 0, st>>>(a.out_f32, a.ld_out, part, S, a.M, a.N,
+                                                                  accumulate ? 1 : 0, a.d_rows);
+  return true;
 }
 
 void gemm_lds(const LargeArgs& a, int epi, hipStream_t st) {

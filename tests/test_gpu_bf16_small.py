@@ -454,3 +454,28 @@ def test_prefill_gemms_cover_every_block_at_any_number_of_token_blocks(lib, n_se
         assert d <= 3e-3   # two matrix instructions, two rounding orders; a missing block would be off by units
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+@pytest.mark.parametrize("n_prompts", [1, 4])
+def test_prefill_of_a_few_prompts_at_the_1p5b_widths(lib, n_prompts):
+    """One and four prompts of 512 tokens at the layer widths of the 1.5 B-class policy (2 of its 28 blocks): the
+    sizes at which the QKV, O and down projections of the prefill are 12-64 output blocks and run over several ranges
+    of K at once, the partial sums added in a fixed order.  Rollout by replay on the oracle, the same call twice (the
+    order of the sums does not depend on the schedule), and the scoring pass on the same sequences."""
+    import torch
+    from parity import check_rollout_by_replay
+    cfg = inputs.POLICY_1P5B.with_(n_layers=2)
+    w = inputs.make_weights(cfg, seed=0)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 640), w.blob())
+    try:
+        prompts = inputs.make_prompts(n_prompts, 512, cfg.vocab, seed=4)
+        rows = sorted({0, n_prompts * 8 - 1})
+        rep = check_rollout_by_replay(handle, w, prompts, 8, 6, 1.0, 1, max_positions=640, rows=rows, label=f"1p5b-{n_prompts}x512")
+        print(f"{n_prompts} x 512: compared", rep["compared"], "of", rep["steps"], "max log-prob err", rep["max_logp_err"])
+        again = lib.mtmc_rollout(handle, torch.from_numpy(prompts).cuda(), 8, 6, 1.0, 1)
+        assert np.array_equal(again[0].cpu().numpy(), rep["ids"]) and np.array_equal(again[1].cpu().numpy(), rep["logprobs"])
+        seqs = np.concatenate([np.repeat(prompts, 8, axis=0), rep["ids"]], axis=1)
+        sc = check_score(handle, w, seqs, 512, max_positions=640, rows=rows[:1], label=f"1p5b-{n_prompts}x512-score")
+        assert np.abs(sc["logprobs"][:, 511:] - rep["logprobs"]).max() <= 2 * LOGP_TOL_BF16
+    finally:
+        lib.mtmc_weights_destroy(handle)
