@@ -111,6 +111,7 @@ struct ScorePlan {
   float* logits;
   float* part;
   float* lm_part;
+  float* gemm_part;   // partial sums of the split-K GEMMs (kGemmPartFloats), or NULL when the pass is too large to use them
   void* qb;
   int* targets;
   size_t total_bytes;
@@ -146,6 +147,7 @@ struct ActionPlan {
   void* xs;
   float* logits;
   float* lm_part;
+  float* gemm_part;   // partial sums of the split-K GEMMs (kGemmPartFloats), or NULL when the pass is too large to use them
   void* qb;
   int* targets;
   // bf16 path: the candidates of a chunk packed without padding (built on the device, see build_packed_actions)

@@ -349,6 +349,9 @@ void bf16_plan_rollout_extra(const mtmc_weights* w, RolloutPlan& p, Carver& cv) 
   }
 }
 
+// whether a pass over up to T tokens can have a d-wide output of at most 128 blocks of 256 x 256 (what gemm_lds_split takes)
+static bool split_k_may_apply(int T, int d) { return (size_t)((T + 255) / 256) * ((d + 255) / 256) <= 128; }
+
 void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
   const Dims D = dims_of(w);
   int gpb = 0;
@@ -356,6 +359,7 @@ void bf16_plan_score_extra(const mtmc_weights* w, ScorePlan& p, Carver& cv) {
   p.lm_part = cv.take<float>((size_t)blocks * 2 * p.rows_max * 8);
   p.qb = cv.take<h16_t>((size_t)p.T * D.nq);
   p.targets = cv.take<int>(p.rows_max);
+  p.gemm_part = split_k_may_apply(p.T, D.d) ? cv.take<float>(kGemmPartFloats) : nullptr;
 }
 
 void bf16_plan_actions_extra(const mtmc_weights* w, ActionPlan& p, Carver& cv) {
@@ -369,6 +373,9 @@ void bf16_plan_actions_extra(const mtmc_weights* w, ActionPlan& p, Carver& cv) {
   p.d_rows = cv.take<int>(16);
   p.pids = cv.take<int>(p.rows_max);
   p.out_index = cv.take<int>(p.rows_max);
+  // no split-K scratch: the prefix pass keeps the sums of the scoring pass at 98 k tokens, so that scoring rollout
+  // samples through this entry point gives what mtmc_score gives, bit for bit, at the sizes both are used at
+  p.gemm_part = nullptr;
 }
 
 // ======================================================================================
@@ -938,7 +945,8 @@ int bf16_score(const mtmc_weights* w, const ScorePlan& p, const ScoreArgs& a, hi
     const int T = ns * S, mt = tiles16(T);
     bf16::embed(p.h, a.seqs + (size_t)s0 * S, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
     bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
-    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, S, map, pool, 0, st);
+    prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, S, map, pool, 0, st, nullptr,
+                   nullptr, p.gemm_part);
     const int R = ns * n_scored;
     if (R == 0) continue;
     const int rt = tiles16(R);
@@ -974,7 +982,7 @@ int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionA
       bf16::embed(p.h, p.prefix + (size_t)n0 * p.Pp, T, (const bf16_t*)w->embed, D.d, D.V, w->err_flag, st);
       bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st);
       prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, ns, p.Pp, map,
-                     chunk_pool, 1, st);
+                     chunk_pool, 1, st, nullptr, nullptr, p.gemm_part);
     }
     if (p.Pp % kPageTokens != 0) launch_fork_tail_pages(pool, c.n_layers, p.B, p.K, p.n_full, 2, st);
   }
@@ -999,7 +1007,7 @@ int bf16_score_actions(const mtmc_weights* w, const ActionPlan& p, const ActionA
     bf16::add_norm(p.h, nullptr, 0, 0, 0, w->layers[0].attn_norm, c.rms_eps, (h16_t*)p.x, T, mt, D.d, w->err_flag, st,
                    p.d_rows);
     prefill_layers(w, D, p.h, (h16_t*)p.x, p.qkv, (h16_t*)p.qb, (h16_t*)p.o, (h16_t*)p.a, nr, p.A, map,
-                   chunk_pool, 1, st, p.seq_start, p.d_rows);
+                   chunk_pool, 1, st, p.seq_start, p.d_rows, p.gemm_part);
     bf16::add_norm(p.h, nullptr, 0, 0, 0, w->final_norm, c.rms_eps, (h16_t*)p.xs, T, mt, D.d, w->err_flag, st, p.d_rows);
     bf16::lmhead_score(p.lm_part, (const h16_t*)w->lm_head, D.nt_V, D.kt_d, (const h16_t*)p.xs, T, mt, p.targets,
                        false, w->opt_lds_min_blocks, p.d_rows, st);
