@@ -545,7 +545,7 @@ void gemm_dec(const DecGemmArgs& a, int epi, hipStream_t st) {
 // ---------------------------------------------------------------- split-K sum + residual epilogue
 // h += sum_s P[s]; x' = fp16(h g r_old); per-tile sums of squares.  One workgroup per 16 output
 // columns and 64 rows; a thread owns (row, 4 consecutive columns).  The partial sums are added in split order.
-__global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ P, int ksplit, int Mpad, int N,
+__global__ __launch_bounds__(128) void k_resid_reduce(const float* __restrict__ P, int ksplit, int Mpad, int N,
                                                       float* h, const float* __restrict__ gain,
                                                       const float* __restrict__ rs, h16_t* x, float* ss_out, int M,
                                                       int* err_flag) {
@@ -553,7 +553,7 @@ __global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ 
   const int n = nt * 16 + cg * 4;
   const v4f g = *reinterpret_cast<const v4f*>(gain + n);
   {
-    const int m = (threadIdx.x >> 2) + 64 * blockIdx.y;
+    const int m = (threadIdx.x >> 2) + 32 * blockIdx.y;
     const bool live = m < M;
     v4f hv = v4f{0.f, 0.f, 0.f, 0.f};
     if (live) {
@@ -584,7 +584,7 @@ __global__ __launch_bounds__(256) void k_resid_reduce(const float* __restrict__ 
 }
 void resid_reduce(const float* P, int ksplit, int m_tiles, int N, float* h, const float* gain, const float* rs,
                   h16_t* x, float* ss_out, int M, int* err_flag, hipStream_t st) {
-  k_resid_reduce<<<dim3(N / 16, (m_tiles + 3) / 4), 256, 0, st>>>(P, ksplit, m_tiles * 16, N, h, gain, rs, x, ss_out, M, err_flag);
+  k_resid_reduce<<<dim3(N / 16, (m_tiles + 1) / 2), 128, 0, st>>>(P, ksplit, m_tiles * 16, N, h, gain, rs, x, ss_out, M, err_flag);
 }
 
 // ---------------------------------------------------------------- embedding of the fed-back token
