@@ -95,7 +95,7 @@ struct mtmc_weights {
   int opt_lds_min_blocks;  // output blocks (256 x 256) from which large GEMMs use the LDS-staged kernel
   int opt_stop_poll;       // decode steps between two looks at the stop flags of a rollout with a stop token (0: never)
   int opt_admit;           // a rollout with a stop token and more sequences than one batch holds runs as one batch
-                           // whose places pass to the next prompt as their sequences finish (0: batch after batch)
+                           // that takes in the next prompts as sequences finish and leave slots (0: batch after batch)
   mtmc::GraphCache* graphs;  // instantiated decode-step graphs, keyed by workspace and shape
   std::mutex* ragged_mu;     // guards ragged_calls
   std::vector<mtmc::RaggedCallRecord> ragged_calls;  // at most 16, oldest dropped first

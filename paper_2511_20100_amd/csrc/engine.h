@@ -55,7 +55,7 @@ struct RolloutPlan {
   int* slot_row;     // ragged, bf16: [bt * 16] row held by each slot once live rows are packed (-1: nobody)
   int* page_table_c; // ragged, bf16: [B, max_pages] page-table rows by slot
   int* row_pos_c;    // ragged, bf16: [bt * 16] position base by slot (-1: nobody)
-  int* live;         // ragged, bf16: [16 + 256] live[0] = rows that have not stopped; from 16 on, by place
+  int* live;         // ragged, bf16: [16 + 256] live[0] = rows that have not stopped; from 16 on: per slot, does it hold a sequence that still runs
   int* row_step0;    // ragged, bf16: [bt * 16] step of the call at which the sequence in a slot was at its step 0
   int* prefill_table; // ragged, bf16: [bt * 16, max_pages] page-table rows through which new prompts are prefilled
   int* slot_row_c;   // ragged, bf16: [bt * 16] slot_row / row_step0 of the packed batch (page_table_c, row_pos_c)

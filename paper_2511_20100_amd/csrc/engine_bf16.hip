@@ -34,7 +34,7 @@ struct GraphCache {
   std::mutex poll_mu;                    // one such rollout at a time per weights handle
   int* host_live = nullptr;
   hipEvent_t poll_events[2] = {nullptr, nullptr};
-  int* host_places = nullptr;            // pinned: sequences still running, by place (a batch that takes in prompts)
+  int* host_slots = nullptr;            // pinned: which slots hold a sequence that still runs (a batch that takes in prompts)
 };
 
 // Brackets launches of one kernel class with HIP events while a decode step is launched directly.
@@ -74,7 +74,7 @@ void destroy_graph_cache(mtmc_weights* w) {
   for (hipEvent_t e : w->graphs->poll_events)
     if (e) (void)hipEventDestroy(e);
   if (w->graphs->host_live) (void)hipHostFree(w->graphs->host_live);
-  if (w->graphs->host_places) (void)hipHostFree(w->graphs->host_places);
+  if (w->graphs->host_slots) (void)hipHostFree(w->graphs->host_slots);
   delete w->graphs;
   w->graphs = nullptr;
 }
@@ -643,8 +643,8 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
   if (!mw->graphs) mw->graphs = new GraphCache();
   GraphCache& gc = *mw->graphs;
   std::lock_guard<std::mutex> poll_lock(gc.poll_mu);
-  if (!gc.host_places) MTMC_HIP_CHECK(hipHostMalloc((void**)&gc.host_places, 256 * sizeof(int), hipHostMallocDefault));
-  const int* live = gc.host_places;
+  if (!gc.host_slots) MTMC_HIP_CHECK(hipHostMalloc((void**)&gc.host_slots, 256 * sizeof(int), hipHostMallocDefault));
+  const int* live = gc.host_slots;
   hipGraphExec_t exec = nullptr;
   if (int rc = decode_graph(w, cur, st, decode_step, &exec)) return rc;
 
@@ -669,7 +669,7 @@ int bf16_rollout_admit(const mtmc_weights* w, const RolloutPlan& p, const int* p
     }
     // the tables by slot of the whole batch stay as they are once no prompt is left: the packed batch is always made from them
     bf16::slot_live(p.done, p.slot_row, B, d_live, st);
-    MTMC_HIP_CHECK(hipMemcpyAsync(gc.host_places, d_live, B * sizeof(int), hipMemcpyDeviceToHost, st));
+    MTMC_HIP_CHECK(hipMemcpyAsync(gc.host_slots, d_live, B * sizeof(int), hipMemcpyDeviceToHost, st));
     MTMC_HIP_CHECK(hipStreamSynchronize(st));
     int n_live = 0;
     for (int s = 0; s < B; ++s) n_live += live[s];
