@@ -24,7 +24,7 @@ struct SampleCtl {
   // kernels holds row slot_row[m] of the call, or nobody (-1).  NULL: slot m is row m.  Outputs, stop flags, the
   // fed-back ids (cur_ids) and the random-number counters go by row.
   const int* slot_row;
-  // Rows that joined the batch while it was running (the sequences of a new prompt took slots that finished sequences left): the
+  // Rows that joined the batch while it was running (a new prompt took the places of a finished one): the
   // sequence in slot m is at its own step *d_step - row_step0[m].  It reports under that step, draws that
   // step's random numbers, raises its stop flag when that step is max_new - 1 and reports nothing after that
   // or once the flag is up.  NULL: every row is at step *d_step.
