@@ -424,3 +424,43 @@ def test_joining_prompts_edge_cases(lib, name, cfg, lens, n_prompts, n_samples, 
         assert np.abs(other[1].cpu().numpy()[same] - lp[same]).max() <= 5e-3
     finally:
         lib.mtmc_weights_destroy(handle)
+
+
+def test_joining_calls_of_different_sizes_share_a_workspace(lib):
+    """The step graphs a call replays hold pointers into its workspace that follow from the whole call's shape.  Three
+    calls on ONE workspace buffer - 40 prompts (prompts join the running batch), 24 prompts (the same, another page
+    layout), 16 prompts (one batch, rows give up their places) - must each give what a fresh handle gives on a buffer
+    of its own, bit for bit."""
+    import torch
+    cfg = STOPPY
+    w = inputs.make_weights(cfg, seed=0, std=0.05, gain_std=0.1)
+    dev = lambda x: torch.from_numpy(x).cuda()
+    ns, max_new, max_len, stop = 8, 40, 33, 3
+    shapes = (40, 24, 16)
+    prompts = {n: inputs.make_prompts(n, max_len, cfg.vocab, seed=10 + n) for n in shapes}
+    lens = {n: (1 + (np.arange(n) * 5) % max_len).astype(np.int32) for n in shapes}
+
+    def run(handle, n, ws):
+        out = lib.mtmc_rollout_ragged(handle, dev(prompts[n]), dev(lens[n]), ns, max_new, 1.0, 2, stop_id=stop, workspace=ws)
+        lib.mtmc_poll_errors(handle)
+        return [x.cpu().numpy() for x in out]
+
+    fresh = {}
+    for n in shapes:
+        handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+        try:
+            lib.mtmc_set_option(handle, lib.MTMC_OPT_STOP_POLL_STEPS, 4)
+            fresh[n] = run(handle, n, None)
+        finally:
+            lib.mtmc_weights_destroy(handle)
+    handle = lib.mtmc_weights_create(lib.make_config(cfg, 128), w.blob())
+    try:
+        lib.mtmc_set_option(handle, lib.MTMC_OPT_STOP_POLL_STEPS, 4)
+        nbytes = max(lib.mtmc_rollout_ragged_workspace_bytes(handle, n, max_len, ns, max_new) for n in shapes)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for n in shapes + shapes[::-1]:
+            got = run(handle, n, ws)
+            for a, b in zip(got, fresh[n]):
+                assert np.array_equal(a, b), n
+    finally:
+        lib.mtmc_weights_destroy(handle)
